@@ -1,0 +1,298 @@
+"""CPU oracle for the V-ABFT verified-GEMM path.  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this module.  It shares no code with the HIP path and never calls it.
+
+Everything is written out from the paper's definitions, in float64 numpy, with
+no blocking, fusion or reordering beyond what the definitions state:
+
+  * GEMM, checksum encode, expected checksum, row sums, detection test:
+    section 2.2 "ABFT for Matrix Multiplication" (Eq. for r1, the encoded
+    matrices, Eq. abft-encoded, the row-sum equation, Eq. abft-check, and the
+    verification difference E_i).
+  * Row statistics and the extrema-variance bound: section 3.5 (Theorem
+    "Extrema-Variance Bound") and Algorithm 1 steps for mu_A, sigma_A^2,
+    mu_Bk, sigma_Bk^2.
+  * Threshold: the boxed T_bound of section 3.4 / Algorithm 1 (T_det, T_var23,
+    T_var4), with c_sigma = 2.5 (section 3.4) and e_max from the
+    "Recommended e_max across platforms" table (GPU rows) as default.
+  * Fault model: single bit flips in a stored floating-point word (section 5.1
+    "Error injection"), replayed on the row sum.
+
+Inputs are the already-rounded storage arrays (see workloads.py); bf16 arrives
+as uint16 bit patterns.  All products of bf16/f16 values are exact in float64.
+
+Pins (tests/test_oracle_*.py, -m "not gpu"): brute-force integer identities,
+the theorem's equality cases, closed forms for constant / two-point matrices,
+the V-ABFT threshold columns of the paper's three tightness tables, the 7-20x
+tightness band, zero false positives, scaling laws, IEEE bit-flip identities
+and the published splitmix64 test vector.
+
+Parity unpinned (stated here as required): detection rates by bit position
+have no comparable value in the paper (different e_max, shape and injection
+site); the fault-free values of E themselves are implementation rounding noise
+and are only bounded (|E| <= T, |E_gpu - E_oracle| <= tol * scale).
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+C_SIGMA_DEFAULT = 2.5  # section 3.4, text below the boxed formula
+
+
+# --------------------------------------------------------------------------
+# storage decode
+# --------------------------------------------------------------------------
+def decode(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Storage array -> float64 (exact)."""
+    if dtype == "bf16":
+        assert x.dtype == np.uint16
+        return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    if dtype == "f16":
+        assert x.dtype == np.float16
+        return x.astype(np.float64)
+    if dtype == "f32":
+        assert x.dtype == np.float32
+        return x.astype(np.float64)
+    if dtype == "f64":
+        assert x.dtype == np.float64
+        return x
+    raise ValueError(dtype)
+
+
+def acc_dtype(dtype: str):
+    """Accumulator type: FP32 for BF16/FP16/FP32 inputs, FP64 for FP64
+    (section 3.6, "Theoretical analysis": low-precision inputs accumulate in FP32)."""
+    return np.float64 if dtype == "f64" else np.float32
+
+
+def logical_B(B: np.ndarray, dtype: str, transB: int) -> np.ndarray:
+    """The K x N matrix of the problem statement, as float64."""
+    Bd = decode(B, dtype)
+    return Bd.T if transB else Bd
+
+
+# --------------------------------------------------------------------------
+# section 2.2: product, checksums, detection
+# --------------------------------------------------------------------------
+def gemm(A: np.ndarray, B: np.ndarray) -> np.ndarray:
+    """C = A x B in float64 (A: MxK, B: KxN, both float64)."""
+    return A @ B
+
+
+def encode_checksum(B: np.ndarray) -> np.ndarray:
+    """B r1 with r1 the all-ones vector: Be[k] = sum_n B[k, n]."""
+    return B.sum(axis=1)
+
+
+def expected_checksum(A: np.ndarray, Be: np.ndarray) -> np.ndarray:
+    """C^{r1} = A (B r1)."""
+    return A @ Be
+
+
+def row_sums(C: np.ndarray) -> np.ndarray:
+    """C^{r1'} = C r1."""
+    return C.sum(axis=1)
+
+
+def verification_difference(expected: np.ndarray, rowsum: np.ndarray) -> np.ndarray:
+    """E_i = C^{r1}[i] - C^{r1'}[i]."""
+    return expected - rowsum
+
+
+def fault_flags(E: np.ndarray, T: np.ndarray) -> np.ndarray:
+    """Eq. abft-check: a row is faulty if |E_i| > T_i.  Written as
+    not(|E_i| <= T_i) so that a NaN/Inf row sum (exponent-MSB flip) is flagged;
+    identical to '>' for finite values."""
+    with np.errstate(invalid="ignore"):
+        return (~(np.abs(E) <= T)).astype(np.int32)
+
+
+# --------------------------------------------------------------------------
+# section 3.5 / Algorithm 1: statistics and threshold
+# --------------------------------------------------------------------------
+def row_stats(X: np.ndarray):
+    """(max, min, mean) of every row."""
+    return X.max(axis=1), X.min(axis=1), X.mean(axis=1)
+
+
+def extrema_variance(mx: np.ndarray, mn: np.ndarray, mu: np.ndarray) -> np.ndarray:
+    """sigma^2 <= (max - mu)(mu - min); clamped at 0 against rounding."""
+    return np.maximum(0.0, (mx - mu) * (mu - mn))
+
+
+def b_aggregates(B: np.ndarray):
+    """S1 = sum_k |mu_Bk|, S2 = sum_k sigma_Bk^2, S3 = sum_k mu_Bk^2: the only
+    way B enters Algorithm 1's three terms."""
+    mx, mn, mu = row_stats(B)
+    var = extrema_variance(mx, mn, mu)
+    return float(np.abs(mu).sum()), float(var.sum()), float((mu * mu).sum())
+
+
+def threshold_terms(A: np.ndarray, B: np.ndarray, c_sigma: float = C_SIGMA_DEFAULT):
+    """(T_det, T_var23, T_var4) per row of A, before the e_max factor."""
+    N = B.shape[1]
+    mxa, mna, mua = row_stats(A)
+    vara = extrema_variance(mxa, mna, mua)
+    S1, S2, S3 = b_aggregates(B)
+    t_det = N * np.abs(mua) * S1
+    t_var23 = c_sigma * np.sqrt(N * mua * mua * S2 + float(N) * N * vara * S3)
+    t_var4 = c_sigma * math.sqrt(N) * np.sqrt(vara) * math.sqrt(S2)
+    return t_det, t_var23, t_var4
+
+
+def threshold(A: np.ndarray, B: np.ndarray, e_max: float, c_sigma: float = C_SIGMA_DEFAULT) -> np.ndarray:
+    """Algorithm 1 for every row m of A: T_m = e_max (T_det + T_var23 + T_var4)."""
+    t_det, t_var23, t_var4 = threshold_terms(A, B, c_sigma)
+    return e_max * (t_det + t_var23 + t_var4)
+
+
+def default_emax(dtype: str, K: int, N: int) -> float:
+    """Recommended e_max, GPU rows of the "Recommended e_max across platforms"
+    table, for verification before output quantisation: the FP32 law for every
+    FP32-accumulated type (the fused check of section 3.6 sees FP32 values),
+    the FP64 law for FP64.  The table's size variable is the square dimension;
+    for rectangular problems the larger accumulation depth max(K, N) is used."""
+    n = float(max(K, N))
+    if dtype == "f64":
+        return 1.0e-17 * math.sqrt(n) + 2.5e-16
+    return 5.0e-9 * math.sqrt(n) + 1.2e-7
+
+
+# --------------------------------------------------------------------------
+# whole fault-free path
+# --------------------------------------------------------------------------
+def verify(A_st, B_st, dtype: str, transB: int = 0, e_max: float | None = None,
+           c_sigma: float = C_SIGMA_DEFAULT, full_gemm: bool = True, rows=None):
+    """All oracle quantities of one verified GEMM.
+
+    rows: optional index array; C and rowsum are then computed for those rows
+    only (the O(MK+KN) quantities are always complete)."""
+    A = decode(A_st, dtype)
+    B = logical_B(B_st, dtype, transB)
+    K, N = B.shape
+    if e_max is None:
+        e_max = default_emax(dtype, K, N)
+    out = {"e_max": e_max}
+    out["Be"] = encode_checksum(B)
+    mxb, mnb, mub = row_stats(B)
+    out["bstat"] = np.stack([mxb, mnb, mub], axis=1)
+    out["S"] = np.array(b_aggregates(B))
+    mxa, mna, mua = row_stats(A)
+    out["astat"] = np.stack([mxa, mna, mua], axis=1)
+    out["expected"] = expected_checksum(A, out["Be"])
+    out["T"] = threshold(A, B, e_max, c_sigma)
+    # magnitude scales for the K-scaled comparison tolerances
+    absB_rowsum = np.abs(B).sum(axis=1)
+    out["scale_Be"] = absB_rowsum
+    out["scale_expected"] = np.abs(A) @ np.abs(out["Be"])
+    out["scale_rowsum"] = np.abs(A) @ absB_rowsum
+    if full_gemm:
+        sel = slice(None) if rows is None else np.asarray(rows)
+        C = gemm(A[sel], B)
+        out["C"] = C
+        out["rows"] = None if rows is None else np.asarray(rows)
+        out["rowsum"] = row_sums(C)
+        out["E"] = verification_difference(out["expected"][sel], out["rowsum"])
+        out["flags"] = fault_flags(out["E"], out["T"][sel])
+    return out
+
+
+# --------------------------------------------------------------------------
+# accumulator-precision CPU path (the CPU's own "actual difference")
+# --------------------------------------------------------------------------
+def accumulator_path(A_st, B_st, dtype: str, transB: int = 0):
+    """The two computation paths of section 3.2 carried out on the CPU in the
+    accumulator precision; returns (expected, rowsum, E) with E evaluated in
+    float64 from the two rounded results."""
+    acc = acc_dtype(dtype)
+    A = decode(A_st, dtype).astype(acc)
+    B = np.ascontiguousarray(logical_B(B_st, dtype, transB).astype(acc))
+    C = A @ B
+    rowsum = C.sum(axis=1, dtype=acc)
+    Be = B.sum(axis=1, dtype=acc)
+    expected = A @ Be
+    E = expected.astype(np.float64) - rowsum.astype(np.float64)
+    return expected, rowsum, E
+
+
+def tightness(T: np.ndarray, E: np.ndarray):
+    """Threshold divided by actual verification difference (section 5.1,
+    "Metrics"): (mean T / mean |E|, max T / max |E|)."""
+    aE = np.abs(E)
+    return float(T.mean() / aE.mean()), float(T.max() / aE.max())
+
+
+# --------------------------------------------------------------------------
+# fault model
+# --------------------------------------------------------------------------
+def bitflip(value: float, bit: int, acc) -> float:
+    """Flip one bit of the IEEE word holding `value` in the accumulator type."""
+    if acc == np.float32:
+        w = np.array([value], dtype=np.float32).view(np.uint32)
+        w ^= np.uint32(1 << bit)
+        return float(w.view(np.float32)[0])
+    w = np.array([value], dtype=np.float64).view(np.uint64)
+    w ^= np.uint64(1 << bit)
+    return float(w.view(np.float64)[0])
+
+
+_MASK64 = (1 << 64) - 1
+_GAMMA = 0x9E3779B97F4A7C15
+
+
+def splitmix64_at(seed: int, index: int) -> int:
+    """The index-th output (index >= 0) of the splitmix64 stream seeded with
+    `seed`: a stateless, counter-based draw."""
+    z = (seed + (index + 1) * _GAMMA) & _MASK64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _MASK64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _MASK64
+    return z ^ (z >> 31)
+
+
+def _splitmix64_vec(seed: int, index: np.ndarray) -> np.ndarray:
+    with np.errstate(over="ignore"):
+        z = np.uint64(seed & _MASK64) + (index.astype(np.uint64) + np.uint64(1)) * np.uint64(_GAMMA)
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        return z ^ (z >> np.uint64(31))
+
+
+def bernoulli_hit_limit(rate: float) -> int:
+    """An element is hit iff the top 53 bits of its draw are below this."""
+    return int(math.floor(rate * float(1 << 53)))
+
+
+def bernoulli_faults(seed: int, rate: float, bit_lo: int, bit_hi: int, M: int, N: int):
+    """The set {(i, j, bit)} of the seeded Bernoulli injector: element (i, j)
+    draws z = splitmix64_at(seed, i*N + j); it is hit iff (z >> 11) < floor(rate*2^53);
+    the flipped bit is bit_lo + (z & 0x7FF) mod (bit_hi - bit_lo + 1)."""
+    limit = np.uint64(bernoulli_hit_limit(rate))
+    span = np.uint64(bit_hi - bit_lo + 1)
+    out = []
+    chunk = 1 << 22
+    total = M * N
+    for start in range(0, total, chunk):
+        idx = np.arange(start, min(total, start + chunk), dtype=np.uint64)
+        z = _splitmix64_vec(seed, idx)
+        hit = np.nonzero((z >> np.uint64(11)) < limit)[0]
+        for h in hit:
+            e = int(idx[h])
+            bit = bit_lo + int((z[h] & np.uint64(0x7FF)) % span)
+            out.append((e // N, e % N, bit))
+    return out
+
+
+def replay_faults(rowsum: np.ndarray, records, row_index=None) -> np.ndarray:
+    """Row sums after the logged faults: rowsum[i] += (after - before).
+    records: iterable of (row, col, bit, before, after).  row_index maps a
+    matrix row to a position in `rowsum` when only some rows are held."""
+    out = np.array(rowsum, dtype=np.float64, copy=True)
+    for (i, _j, _bit, before, after) in records:
+        p = i if row_index is None else row_index.get(i)
+        if p is None:
+            continue
+        out[p] = out[p] + (after - before)
+    return out

@@ -1,0 +1,329 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests touches the HIP path.  Each is chosen so that a plausible
+mistake in the oracle (dropped term, wrong sign/index, transposed operand,
+wrong constant) fails at least one of them.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import vabft_oracle as orc
+
+
+# --------------------------------------------------------------------------
+# storage decode / bit flips: IEEE identities
+# --------------------------------------------------------------------------
+def test_bf16_decode_known_patterns():
+    bits = np.array([0x3F80, 0xC000, 0x4049, 0x0000, 0x3F00, 0x7F80], dtype=np.uint16)
+    got = orc.decode(bits, "bf16")
+    assert got.tolist() == [1.0, -2.0, 3.140625, 0.0, 0.5, math.inf]
+
+
+def test_bf16_rounding_is_nearest_even():
+    # 1 + 2^-8 is a tie between 1.0 (even) and 1+2^-7 (odd) -> 1.0;
+    # 1 + 3*2^-8 is a tie between 1+2^-7 (odd) and 1+2^-6 (even) -> 1+2^-6
+    x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20], dtype=np.float32)
+    got = orc.decode(wl.f32_to_bf16_bits(x), "bf16")
+    assert got.tolist() == [1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7]
+
+
+def test_bitflip_identities_fp32():
+    f32 = np.float32
+    assert orc.bitflip(1.0, 31, f32) == -1.0            # sign
+    assert orc.bitflip(1.0, 23, f32) == 0.5             # exponent LSB 127 -> 126
+    assert orc.bitflip(1.0, 30, f32) == math.inf        # exponent MSB: 0x7f800000
+    assert orc.bitflip(2.0, 30, f32) == 0.0             # 0x40000000 -> 0
+    assert orc.bitflip(1.0, 22, f32) == 1.5             # top mantissa bit
+    assert orc.bitflip(1.0, 0, f32) == 1.0 + 2.0 ** -23
+    # involution
+    for bit in range(32):
+        v = 0.7431
+        w = orc.bitflip(orc.bitflip(v, bit, f32), bit, f32)
+        assert w == float(np.float32(v))
+
+
+def test_bitflip_identities_fp64():
+    f64 = np.float64
+    assert orc.bitflip(1.0, 63, f64) == -1.0
+    assert orc.bitflip(1.0, 52, f64) == 0.5
+    assert orc.bitflip(1.0, 62, f64) == math.inf
+    assert orc.bitflip(1.0, 51, f64) == 1.5
+    assert orc.bitflip(1.0, 0, f64) == 1.0 + 2.0 ** -52
+
+
+# --------------------------------------------------------------------------
+# counter-based generator: published vector
+# --------------------------------------------------------------------------
+def test_splitmix64_published_vector(golden_dir):
+    lines = [l.strip() for l in open(os.path.join(golden_dir, "splitmix64_vector.txt")) if not l.startswith("#")]
+    seed = int(lines[0].split()[1])
+    want = [int(v) for v in lines[1:] if v]
+    got = [orc.splitmix64_at(seed, i) for i in range(len(want))]
+    assert got == want
+    vec = orc._splitmix64_vec(seed, np.arange(len(want)))
+    assert [int(v) for v in vec] == want
+
+
+def test_bernoulli_faults_statistics_and_brute_force():
+    M, N, rate = 64, 96, 0.01
+    got = orc.bernoulli_faults(7, rate, 16, 30, M, N)
+    # brute force through the scalar generator
+    lim = orc.bernoulli_hit_limit(rate)
+    want = []
+    for e in range(M * N):
+        z = orc.splitmix64_at(7, e)
+        if (z >> 11) < lim:
+            want.append((e // N, e % N, 16 + (z & 0x7FF) % 15))
+    assert got == want
+    # hit count is Binomial(M*N, rate): within 5 sigma
+    n = M * N
+    assert abs(len(got) - n * rate) < 5 * math.sqrt(n * rate)
+    assert all(16 <= b <= 30 for (_, _, b) in got)
+
+
+# --------------------------------------------------------------------------
+# section 2.2: brute-force integer identities on tiny matrices
+# --------------------------------------------------------------------------
+def _brute_gemm(A, B):
+    M, K = len(A), len(A[0])
+    N = len(B[0])
+    return [[sum(A[i][k] * B[k][j] for k in range(K)) for j in range(N)] for i in range(M)]
+
+
+def test_gemm_and_checksum_identity_brute_force():
+    g = wl.rng(3)
+    for (M, K, N) in [(1, 1, 1), (2, 3, 4), (5, 7, 3), (8, 8, 8), (3, 1, 6)]:
+        A = g.integers(-9, 10, size=(M, K))
+        B = g.integers(-9, 10, size=(K, N))
+        Cb = _brute_gemm(A.tolist(), B.tolist())
+        C = orc.gemm(A.astype(np.float64), B.astype(np.float64))
+        assert C.tolist() == [[float(v) for v in r] for r in Cb]
+        # non-square shapes catch a transposed operand or a checksum over the wrong axis
+        Be = orc.encode_checksum(B.astype(np.float64))
+        assert Be.tolist() == [float(sum(r)) for r in B.tolist()]
+        exp = orc.expected_checksum(A.astype(np.float64), Be)
+        rs = orc.row_sums(C)
+        assert rs.tolist() == [float(sum(r)) for r in Cb]
+        # C e == A (B e) exactly in integer arithmetic
+        assert exp.tolist() == rs.tolist()
+        E = orc.verification_difference(exp, rs)
+        assert not E.any()
+
+
+def test_sign_of_verification_difference_and_flag_rule():
+    exp = np.array([10.0, 10.0, 10.0, 10.0, 10.0])
+    rs = np.array([9.0, 11.0, 10.5, np.nan, np.inf])
+    E = orc.verification_difference(exp, rs)
+    assert E[0] == 1.0 and E[1] == -1.0            # E = checksum - rowsum
+    T = np.full(5, 0.75)
+    f = orc.fault_flags(E, T)
+    assert f.tolist() == [1, 1, 0, 1, 1]           # NaN / Inf rows are flagged
+    # boundary: |E| == T is not a fault (strict '>')
+    assert orc.fault_flags(np.array([0.75, -0.75]), np.array([0.75, 0.75])).tolist() == [0, 0]
+
+
+def test_transB_layout():
+    g = wl.rng(5)
+    B = g.normal(size=(6, 9)).astype(np.float32)
+    assert np.array_equal(orc.logical_B(B, "f32", 0), B.astype(np.float64))
+    assert np.array_equal(orc.logical_B(np.ascontiguousarray(B.T), "f32", 1), B.astype(np.float64))
+
+
+# --------------------------------------------------------------------------
+# section 3.5: extrema-variance theorem
+# --------------------------------------------------------------------------
+def test_extrema_variance_theorem_holds_and_is_tight():
+    g = wl.rng(11)
+    for dist in ("n_1_1", "u_-1_1", "trunc_n_0_1", "n_1e-6_1"):
+        X = wl.paper_distribution(g, dist, (64, 257))
+        mx, mn, mu = orc.row_stats(X)
+        bound = orc.extrema_variance(mx, mn, mu)
+        true_var = X.var(axis=1)  # population variance, as in the theorem
+        assert np.all(true_var <= bound * (1 + 1e-12))
+    # equality: half the entries at l, half at m
+    row = np.array([[-3.0] * 8 + [5.0] * 8])
+    mx, mn, mu = orc.row_stats(row)
+    assert orc.extrema_variance(mx, mn, mu)[0] == 16.0 == row.var()
+    # constant row -> 0 ; asymmetric two-point row: p(1-p)(m-l)^2
+    row = np.array([[2.5] * 10])
+    assert orc.extrema_variance(*orc.row_stats(row))[0] == 0.0
+    row = np.array([[0.0] * 3 + [4.0] * 1])
+    assert orc.extrema_variance(*orc.row_stats(row))[0] == pytest.approx(0.25 * 0.75 * 16.0)
+    # a mean rounded outside [min, max] must not give a negative variance
+    assert orc.extrema_variance(np.array([1.0]), np.array([1.0]), np.array([1.0 + 1e-16]))[0] == 0.0
+
+
+# --------------------------------------------------------------------------
+# section 3.4 / Algorithm 1: closed forms of the threshold
+# --------------------------------------------------------------------------
+def test_threshold_closed_form_constant_matrices():
+    # sigma_A = sigma_B = 0: only the deterministic term survives
+    M, K, N = 3, 5, 7
+    A = np.full((M, K), -2.0)
+    B = np.full((K, N), 0.5)
+    T = orc.threshold(A, B, e_max=1e-3, c_sigma=2.5)
+    assert np.allclose(T, 1e-3 * N * 2.0 * K * 0.5, rtol=1e-15)
+
+
+def test_threshold_closed_form_two_point_zero_mean():
+    # rows of A and B half -a / +a, half -b / +b: mu = 0, sigma^2 = a^2, b^2
+    # -> only the interaction term: c_sigma sqrt(N) a sqrt(K b^2)
+    M, K, N = 2, 8, 6
+    a, b = 3.0, 0.5
+    A = np.tile(np.array([a, -a] * (K // 2)), (M, 1))
+    B = np.tile(np.array([b, -b] * (N // 2)), (K, 1))
+    T = orc.threshold(A, B, e_max=2.0, c_sigma=2.5)
+    assert np.allclose(T, 2.0 * 2.5 * math.sqrt(N) * a * math.sqrt(K * b * b), rtol=1e-15)
+
+
+def test_threshold_closed_form_mixed_terms():
+    # A row two-point {0, 2} (mu=1, var=1); B rows two-point {1, 3} (mu=2, var=1)
+    K, N = 4, 10
+    A = np.array([[0.0, 2.0, 0.0, 2.0]])
+    B = np.tile(np.array([1.0, 3.0] * (N // 2)), (K, 1))
+    S1, S2, S3 = orc.b_aggregates(B)
+    assert (S1, S2, S3) == (8.0, 4.0, 16.0)
+    t_det, t23, t4 = orc.threshold_terms(A, B, c_sigma=2.0)
+    assert t_det[0] == N * 1.0 * 8.0
+    assert t23[0] == pytest.approx(2.0 * math.sqrt(N * 1.0 * 4.0 + N * N * 1.0 * 16.0))
+    assert t4[0] == pytest.approx(2.0 * math.sqrt(N) * 1.0 * 2.0)
+    # the three terms are weighted equally by e_max and c_sigma enters terms 2-4 only
+    T1 = orc.threshold(A, B, 1.0, 2.0)[0]
+    T2 = orc.threshold(A, B, 1.0, 4.0)[0]
+    assert T2 - T1 == pytest.approx(t23[0] + t4[0])
+
+
+def test_threshold_rectangular_uses_N_of_B_and_K_sums():
+    # distinguishes N from K and rows-of-B statistics from columns-of-B statistics
+    K, N = 3, 5
+    A = np.array([[1.0, 1.0, 1.0]])
+    B = np.arange(K * N, dtype=np.float64).reshape(K, N)  # row k: 5k..5k+4, mean 5k+2
+    T = orc.threshold(A, B, 1.0, 2.5)[0]
+    assert T == pytest.approx(N * 1.0 * (2 + 7 + 12) + 2.5 * math.sqrt(N * 1.0 * 3 * 4.0))
+
+
+def _read_table(golden_dir, which):
+    rows = []
+    for line in open(os.path.join(golden_dir, "paper_tightness_tables.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        t, n, act, thr, tight = line.split()
+        if t == which:
+            rows.append((int(n), float(act), float(thr), float(tight)))
+    return rows
+
+
+def test_threshold_bf16_table_closed_form(golden_dir):
+    # U(0,1) with ideal statistics (mu=1/2, max=1, min=0) has a closed form:
+    # T = e_max (n^2/4 + 2.5 sqrt(n^2/16 + n^3/16) + 2.5 n/4)
+    for n, _act, thr, _tight in _read_table(golden_dir, "bf16"):
+        closed = 8e-3 * (n * n / 4 + 2.5 * math.sqrt(n * n / 16 + n ** 3 / 16) + 0.625 * n)
+        assert closed == pytest.approx(thr, rel=0.01)
+
+
+@pytest.mark.parametrize("table,dist,stype,trials", [("bf16", "u_0_1", "bf16", 4), ("fp32", "u_-1_1", "f32", 6),
+                                                    ("fp64", "u_-1_1", "f64", 6)])
+def test_threshold_reproduces_paper_tables(golden_dir, table, dist, stype, trials):
+    """Row-mean V-ABFT threshold of the oracle on fresh matrices vs the value the
+    paper prints, for all five sizes of each tightness table."""
+    for n, _act, thr, _tight in _read_table(golden_dir, table):
+        vals = []
+        for t in range(trials):
+            g = wl.rng(1000 + t, n)
+            A = wl.to_storage(wl.paper_distribution(g, dist, (n, n)), stype)
+            B = wl.to_storage(wl.paper_distribution(g, dist, (n, n)), stype)
+            if table == "bf16":
+                e_max = 8e-3
+            else:
+                e_max = orc.default_emax(stype, n, n)
+            T = orc.threshold(orc.decode(A, stype), orc.decode(B, stype), e_max)
+            vals.append(T.mean())
+        got = float(np.mean(vals))
+        tol = 0.05 if n == 128 else 0.03
+        assert got == pytest.approx(thr, rel=tol), (table, n, got, thr)
+
+
+def test_default_emax_table_values():
+    assert orc.default_emax("f32", 1024, 1024) == pytest.approx(5.0e-9 * 32 + 1.2e-7)
+    assert orc.default_emax("bf16", 4096, 4096) == pytest.approx(4.4e-7)
+    assert orc.default_emax("f16", 8192, 8192) == orc.default_emax("f32", 8192, 8192)
+    assert orc.default_emax("f64", 2048, 2048) == pytest.approx(1.0e-17 * math.sqrt(2048) + 2.5e-16)
+    # rectangular: the larger accumulation depth
+    assert orc.default_emax("bf16", 4096, 11008) == orc.default_emax("bf16", 11008, 11008)
+
+
+# --------------------------------------------------------------------------
+# scaling laws that follow from the boxed formula
+# --------------------------------------------------------------------------
+def test_threshold_scaling_and_invariances():
+    g = wl.rng(21)
+    A = g.normal(0.3, 1.0, size=(9, 33))
+    B = g.normal(-0.2, 2.0, size=(33, 17))
+    T = orc.threshold(A, B, 1e-6)
+    assert np.allclose(orc.threshold(A, B, 3e-6), 3 * T, rtol=1e-14)
+    assert np.allclose(orc.threshold(-4.0 * A, B, 1e-6), 4 * T, rtol=1e-12)
+    assert np.allclose(orc.threshold(A, 0.5 * B, 1e-6), 0.5 * T, rtol=1e-12)
+    pn = g.permutation(17)
+    assert np.allclose(orc.threshold(A, B[:, pn], 1e-6), T, rtol=1e-12)
+    pk = g.permutation(33)
+    assert np.allclose(orc.threshold(A[:, pk], B[pk, :], 1e-6), T, rtol=1e-12)
+    # T_m depends on row m of A only
+    A2 = A.copy()
+    A2[0] *= 7
+    T2 = orc.threshold(A2, B, 1e-6)
+    assert np.allclose(T2[1:], T[1:], rtol=1e-14) and T2[0] == pytest.approx(7 * T[0])
+
+
+# --------------------------------------------------------------------------
+# the verification difference on a real CPU path: tightness band and zero FPR
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("stype,lo,hi", [("f32", 5.0, 25.0), ("f64", 5.0, 25.0)])
+def test_tightness_band_cpu(stype, lo, hi):
+    """mean T / mean |E| of the CPU accumulator-precision path on U(-1,1) lands in
+    the band of the paper's FP32/FP64 tightness tables (7-20x printed; CPU BLAS
+    accumulation orders differ, so the accepted band is 5-25x)."""
+    for n in (128, 256, 512, 1024):
+        ratios = []
+        for t in range(3):
+            g = wl.rng(50 + t, n)
+            A = wl.to_storage(wl.uniform(g, (n, n)), stype)
+            B = wl.to_storage(wl.uniform(g, (n, n)), stype)
+            T = orc.threshold(orc.decode(A, stype), orc.decode(B, stype), orc.default_emax(stype, n, n))
+            _, _, E = orc.accumulator_path(A, B, stype)
+            assert np.all(np.abs(E) <= T)
+            ratios.append(orc.tightness(T, E)[0])
+        r = float(np.mean(ratios))
+        assert lo <= r <= hi, (stype, n, r)
+
+
+@pytest.mark.parametrize("stype", ["bf16", "f16", "f32", "f64"])
+@pytest.mark.parametrize("dist", wl.PAPER_DISTRIBUTIONS)
+def test_zero_false_positives_cpu(stype, dist):
+    for t, (M, K, N) in enumerate([(96, 128, 160), (128, 1024, 256), (256, 256, 256)]):
+        g = wl.rng(77 + t, wl.PAPER_DISTRIBUTIONS.index(dist))
+        A = wl.to_storage(wl.paper_distribution(g, dist, (M, K)), stype)
+        B = wl.to_storage(wl.paper_distribution(g, dist, (K, N)), stype)
+        o = orc.verify(A, B, stype, 0)
+        assert not o["flags"].any()                      # exact-path E is far below T
+        _, _, E = orc.accumulator_path(A, B, stype)
+        assert not orc.fault_flags(E, o["T"]).any()      # accumulator-precision path too
+
+
+def test_replay_faults_flags_large_deltas_only():
+    g = wl.rng(5)
+    A = wl.to_storage(g.normal(size=(32, 64)), "f32")
+    B = wl.to_storage(g.normal(size=(64, 48)), "f32")
+    o = orc.verify(A, B, "f32")
+    i, j = 7, 11
+    before = float(np.float32(o["C"][i, j]))
+    for bit, must_flag in [(30, True), (28, True), (2, False)]:
+        after = orc.bitflip(before, bit, np.float32)
+        rs = orc.replay_faults(o["rowsum"], [(i, j, bit, before, after)])
+        f = orc.fault_flags(orc.verification_difference(o["expected"], rs), o["T"])
+        assert f.sum() == (1 if must_flag else 0)
+        if must_flag:
+            assert f[i] == 1

@@ -1,0 +1,168 @@
+"""Seeded synthetic input generators for the V-ABFT verified-GEMM workloads.
+
+This module holds NO arithmetic of the method (no checksums, statistics,
+thresholds, hashes or bit flips).  It only draws matrices from documented
+distributions and rounds them to the storage type of a configuration.  It is
+the one module that both the CPU oracle's tests and the HIP path's tests /
+benchmark import; the oracle and the HIP path share nothing else.
+
+Storage conventions returned by every generator
+  "f64"  -> numpy float64 array
+  "f32"  -> numpy float32 array
+  "f16"  -> numpy float16 array (IEEE binary16, round-to-nearest-even)
+  "bf16" -> numpy uint16 array holding bfloat16 bit patterns
+            (round-to-nearest-even from float32)
+
+Distributions follow the paper's evaluation set-up (section "Experimental
+Setup", "Distributions tested") and the five benchmark configurations:
+N(mu, sigma), U(lo, hi), |N(1,1)| (the calibration protocol's positive
+matrices), truncated normals (true truncation by rejection, not clipping) and
+"outlier channel" activations (a seeded 1 % of the K columns scaled by 20).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+DTYPES = ("f64", "f32", "f16", "bf16")
+
+
+def rng(seed: int, stream: int = 0) -> np.random.Generator:
+    """Counter-based generator; (seed, stream) name an independent stream."""
+    return np.random.Generator(np.random.Philox(key=[int(seed) & (2**64 - 1), int(stream)]))
+
+
+# --------------------------------------------------------------------------
+# storage rounding
+# --------------------------------------------------------------------------
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """float32 -> bfloat16 bit patterns, round-to-nearest-even (finite inputs)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = u + np.uint32(0x7FFF) + lsb
+    return (r >> np.uint32(16)).astype(np.uint16)
+
+
+def to_storage(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Round a float64 sample to the storage type of a configuration."""
+    if dtype == "f64":
+        return np.ascontiguousarray(x, dtype=np.float64)
+    if dtype == "f32":
+        return np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == "f16":
+        return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16)
+    if dtype == "bf16":
+        return f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+    raise ValueError(f"unknown dtype {dtype!r}")
+
+
+# --------------------------------------------------------------------------
+# distributions (all return float64 samples of the requested shape)
+# --------------------------------------------------------------------------
+def normal(g: np.random.Generator, shape, mean=0.0, std=1.0) -> np.ndarray:
+    return g.normal(mean, std, size=shape)
+
+
+def uniform(g: np.random.Generator, shape, lo=-1.0, hi=1.0) -> np.ndarray:
+    return g.uniform(lo, hi, size=shape)
+
+
+def abs_normal(g: np.random.Generator, shape, mean=1.0, std=1.0) -> np.ndarray:
+    """|N(mean, std)|: the positive matrices of the calibration protocol."""
+    return np.abs(g.normal(mean, std, size=shape))
+
+
+def truncated_normal(g: np.random.Generator, shape, mean=0.0, std=1.0, bound_sigmas=1.0) -> np.ndarray:
+    """N(mean, std) conditioned on |x - mean| <= bound_sigmas * std (rejection)."""
+    n = int(np.prod(shape))
+    out = np.empty(n, dtype=np.float64)
+    filled = 0
+    while filled < n:
+        need = n - filled
+        z = g.normal(0.0, 1.0, size=int(need * 1.6) + 16)
+        z = z[np.abs(z) <= bound_sigmas][:need]
+        out[filled:filled + z.size] = z
+        filled += z.size
+    return (mean + std * out).reshape(shape)
+
+
+def outlier_activations(g: np.random.Generator, shape, frac=0.01, scale=20.0):
+    """N(0,1) activations with round(frac*K) seeded columns multiplied by scale.
+
+    Returns (sample, outlier_column_indices)."""
+    m, k = shape
+    x = g.normal(0.0, 1.0, size=shape)
+    n_out = int(round(frac * k))
+    cols = np.sort(g.choice(k, size=n_out, replace=False))
+    x[:, cols] *= scale
+    return x, cols
+
+
+# --------------------------------------------------------------------------
+# the benchmark configurations
+# --------------------------------------------------------------------------
+CONFIGS = {
+    # name: dtype, M, N, K, transB
+    "c1_f32_256": dict(dtype="f32", M=256, N=256, K=256, transB=0),
+    "c2_bf16_4096": dict(dtype="bf16", M=4096, N=4096, K=4096, transB=0),
+    "c3_bf16_ffn": dict(dtype="bf16", M=4096, N=11008, K=4096, transB=1),
+    "c4_f16_8192": dict(dtype="f16", M=8192, N=8192, K=8192, transB=0),
+    "c5_f64_2048": dict(dtype="f64", M=2048, N=2048, K=2048, transB=0),
+}
+
+
+def make_config(name: str, seed: int = 0, variant: int = 0, shape=None):
+    """Inputs of one trial of a benchmark configuration.
+
+    Returns dict(dtype, M, N, K, transB, A, B) with A of shape (M, K) and B of
+    shape (K, N) when transB == 0, or (N, K) when transB == 1 (the "weight"
+    layout), both already rounded to storage.  `shape=(M, N, K)` overrides
+    the size (used by tests to run a configuration's distributions at a size
+    the oracle finishes quickly).  `variant` selects the second B of c5.
+    """
+    cfg = dict(CONFIGS[name])
+    if shape is not None:
+        cfg["M"], cfg["N"], cfg["K"] = (int(v) for v in shape)
+    M, N, K, dt = cfg["M"], cfg["N"], cfg["K"], cfg["dtype"]
+    ga, gb = rng(seed, 1), rng(seed, 2)
+    if name == "c1_f32_256" or name == "c2_bf16_4096":
+        A = normal(ga, (M, K))
+        B = normal(gb, (K, N))
+    elif name == "c3_bf16_ffn":
+        A, cols = outlier_activations(ga, (M, K))
+        cfg["outlier_cols"] = cols
+        # weights drawn directly in the (N, K) layout a linear layer stores
+        B = truncated_normal(gb, (N, K), 0.0, 0.02, 2.0)
+    elif name == "c4_f16_8192":
+        A = uniform(ga, (M, K))
+        B = uniform(gb, (K, N))
+    elif name == "c5_f64_2048":
+        A = normal(ga, (M, K))
+        if variant == 0:
+            B = truncated_normal(gb, (K, N), 0.0, 1.0, 3.0)
+        else:
+            B = uniform(gb, (K, N), 0.0, 1.0)
+    else:
+        raise KeyError(name)
+    cfg["A"] = to_storage(A, dt)
+    cfg["B"] = to_storage(B, dt)
+    return cfg
+
+
+def paper_distribution(g: np.random.Generator, which: str, shape) -> np.ndarray:
+    """The four fault-free test distributions of the paper's evaluation."""
+    if which == "n_1e-6_1":
+        return normal(g, shape, 1e-6, 1.0)
+    if which == "n_1_1":
+        return normal(g, shape, 1.0, 1.0)
+    if which == "u_-1_1":
+        return uniform(g, shape, -1.0, 1.0)
+    if which == "trunc_n_0_1":
+        return truncated_normal(g, shape, 0.0, 1.0, 1.0)
+    if which == "u_0_1":
+        return uniform(g, shape, 0.0, 1.0)
+    if which == "abs_n_1_1":
+        return abs_normal(g, shape)
+    raise KeyError(which)
+
+
+PAPER_DISTRIBUTIONS = ("n_1e-6_1", "n_1_1", "u_-1_1", "trunc_n_0_1")
