@@ -1,0 +1,141 @@
+/*
+ * vabft.h - C ABI of the V-ABFT verified-GEMM hot path for AMD MI355X (gfx950).
+ *
+ * The library computes C = A x B on the matrix cores with the fused row-checksum
+ * verification of ABFT (paper section 2.2, "ABFT for Matrix Multiplication") and
+ * the variance-based adaptive threshold of V-ABFT (section 3.4 boxed T_bound,
+ * Algorithm 1, section 3.5 extrema-variance bound).
+ *
+ * Conventions common to every entry point
+ *   - Pointers whose name starts with d_ / dA / dB / dC are DEVICE pointers owned by
+ *     the caller; everything else is a host pointer read before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every
+ *     call only enqueues work on that stream: it never synchronises, allocates or
+ *     frees device memory.
+ *   - Matrices are row-major with leading dimensions in ELEMENTS.
+ *       A: M x K (lda >= K);  C: M x N (ldc >= N)
+ *       B: transB == 0 -> K x N (ldb >= N);  transB == 1 -> stored N x K (ldb >= K),
+ *          the layout in which a linear layer keeps its weight.
+ *   - Element type `dtype` applies to A, B and C.  The accumulator type ("acc") is
+ *     double for VABFT_F64 and float otherwise (section 3.6: low-precision inputs are
+ *     accumulated in FP32 and verified before output quantisation).  Vectors
+ *     described as "acc" have that element type.
+ *   - bf16 is the upper half of an IEEE binary32 word; conversions from the
+ *     accumulator round to nearest even.
+ *   - Return value: a vabft_status.  Argument errors are detected on the host before
+ *     anything is launched (null pointer, non-positive size, leading dimension
+ *     smaller than the row length, unknown dtype, workspace too small).
+ *   - Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef VABFT_H
+#define VABFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    VABFT_OK = 0,
+    VABFT_EINVAL = 1,       /* bad argument */
+    VABFT_EUNSUPPORTED = 2, /* valid but not implemented for this dtype/layout */
+    VABFT_EWORKSPACE = 3,   /* workspace missing or smaller than vabft_workspace_bytes */
+    VABFT_EDEVICE = 4       /* the HIP runtime reported an error at launch */
+} vabft_status;
+
+typedef enum { VABFT_F64 = 0, VABFT_F32 = 1, VABFT_F16 = 2, VABFT_BF16 = 3 } vabft_dtype;
+
+typedef struct {
+    int32_t M, N, K;
+    int32_t dtype;  /* vabft_dtype of A, B and C */
+    int32_t transB; /* 0: B is K x N row-major; 1: B is stored N x K row-major */
+    int32_t reserved;
+    int64_t lda, ldb, ldc; /* leading dimensions in elements */
+} vabft_problem;
+
+/* Fault injector (section 5.1 "Error injection": single bit flips).  The flip is applied
+ * to the accumulator word of C[i][j] after the K loop, before the row sum and before
+ * output quantisation; the corrupted value is also what is stored to C.
+ *   mode 0: off.
+ *   mode 1: explicit list: d_list holds n_list int32 triples (row, col, bit).
+ *   mode 2: Bernoulli: element e = i*N + j draws z = splitmix64(seed + (e+1)*0x9E3779B97F4A7C15)
+ *           (the e-th output of the splitmix64 stream seeded with `seed`); it is hit iff
+ *           (z >> 11) < floor(rate * 2^53); the flipped bit is
+ *           bit_lo + (z & 0x7FF) % (bit_hi - bit_lo + 1).
+ * Bits are numbered from the least significant bit of the accumulator word (0..31 for
+ * float, 0..63 for double). */
+typedef struct {
+    int32_t mode;
+    int32_t bit_lo, bit_hi; /* mode 2 */
+    int32_t n_list;         /* mode 1 */
+    uint64_t seed;          /* mode 2 */
+    double rate;            /* mode 2: probability per element, 0 <= rate <= 1 */
+    const int32_t* d_list;  /* mode 1: device pointer, 3 * n_list int32 */
+    int32_t log_capacity;   /* records d_injlog can hold */
+    int32_t reserved;
+} vabft_inject;
+
+typedef struct {
+    int32_t row, col, bit, pad;
+    double before, after; /* accumulator value before / after the flip */
+} vabft_inject_rec;
+
+const char* vabft_status_string(int status);
+
+/* Bytes of device scratch that vabft_encode and vabft_gemm_verified need for this
+ * problem (0 is never returned for a valid problem; returns 0 for an invalid one). */
+size_t vabft_workspace_bytes(const vabft_problem* p);
+
+/* Recommended e_max for a check made on accumulator values (section 3.6; table
+ * "Recommended e_max across platforms", GPU rows): 5.0e-9*sqrt(n)+1.2e-7 for a float
+ * accumulator, 1.0e-17*sqrt(n)+2.5e-16 for double, with n = max(K, N). */
+double vabft_default_emax(int32_t dtype, int32_t K, int32_t N);
+
+/* Checksum encode and B-side statistics (section 2.2 Eq. for r1 and the encoded matrix
+ * B^r; Algorithm 1, loop over k).  One streaming pass over B.
+ *   d_Be    [K] acc : Be[k] = sum_n B[k][n]                (the column B r1)
+ *   d_bstat [3K] acc: (max, min, mean) of row k of the logical K x N matrix, k-major
+ *   d_S     [3] double: S1 = sum_k |mu_Bk|, S2 = sum_k sigma_Bk^2, S3 = sum_k mu_Bk^2 with
+ *           sigma_Bk^2 = max(0, (max - mu)(mu - min))      (section 3.5 theorem)
+ * Results are bit-reproducible from run to run (no floating-point atomics). */
+int vabft_encode(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S,
+                 void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* A-side statistics, expected checksum and threshold (Algorithm 1 for every row m;
+ * section 2.2 C^{r1} = A (B r1)).  One streaming pass over A.
+ *   d_astat    [3M] acc: (max, min, mean) of row m of A
+ *   d_expected [M] acc : sum_k A[m][k] * Be[k], accumulated in acc
+ *   d_T        [M] acc : e_max * (T_det + T_var23 + T_var4), evaluated in double
+ * e_max > 0 and c_sigma >= 0 are the "precision parameters" of Algorithm 1
+ * (c_sigma = 2.5 in the paper). */
+int vabft_threshold(const vabft_problem* p, const void* dA, const void* d_Be, const double* d_S,
+                    double e_max, double c_sigma, void* d_astat, void* d_expected, void* d_T,
+                    void* stream);
+
+/* GEMM on the matrix cores with the fused check (section 2.2 Eq. abft-check and the
+ * verification difference E_i; section 3.6 "Online (Fused Kernel) ABFT").
+ *   verify == 0: plain C = A x B from the same kernel with the check compiled out;
+ *                d_expected, d_T, d_rowsum, d_E, d_flags, d_nflag and inj may be NULL.
+ *   verify == 1: additionally
+ *     d_rowsum [M] acc : sum_j acc[i][j] taken on the accumulator tile before quantisation,
+ *                        partial sums combined in a fixed order
+ *     d_E      [M] acc : expected[i] - rowsum[i]
+ *     d_flags  [M] int32: !( |E_i| <= T_i )   (equals |E_i| > T_i for finite values and
+ *                        also flags NaN / Inf row sums)
+ *     d_nflag  [1] int32: number of flagged rows
+ *   inj (host pointer, may be NULL = off): fault injector; d_injlog / d_ninj receive up to
+ *   inj->log_capacity records and the number of flips applied (which may exceed the
+ *   capacity; records beyond it are dropped).  Record order is unspecified.
+ * dC [M x N] receives the product rounded to `dtype`. */
+int vabft_gemm_verified(const vabft_problem* p, const void* dA, const void* dB, void* dC,
+                        const void* d_expected, const void* d_T, int32_t verify,
+                        const vabft_inject* inj, void* d_rowsum, void* d_E, int32_t* d_flags,
+                        int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
+                        void* d_workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VABFT_H */

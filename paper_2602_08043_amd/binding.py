@@ -1,0 +1,123 @@
+"""ctypes binding of libvabft.so: the same entry points as include/vabft.h.
+
+Argument marshalling only.  Every step of the path runs in the HIP kernels of the
+library; there is no CPU or PyTorch fallback: if the library is missing, loading
+fails with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, Structure, byref, c_char_p, c_double, c_int32, c_int64, c_size_t, c_uint64, c_void_p
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libvabft.so")
+
+VABFT_OK, VABFT_EINVAL, VABFT_EUNSUPPORTED, VABFT_EWORKSPACE, VABFT_EDEVICE = range(5)
+VABFT_F64, VABFT_F32, VABFT_F16, VABFT_BF16 = range(4)
+DTYPE_CODE = {"f64": VABFT_F64, "f32": VABFT_F32, "f16": VABFT_F16, "bf16": VABFT_BF16}
+
+EXPORTS = ("vabft_status_string", "vabft_workspace_bytes", "vabft_default_emax", "vabft_encode",
+           "vabft_threshold", "vabft_gemm_verified")
+
+
+class Problem(Structure):
+    _fields_ = [("M", c_int32), ("N", c_int32), ("K", c_int32), ("dtype", c_int32), ("transB", c_int32),
+                ("reserved", c_int32), ("lda", c_int64), ("ldb", c_int64), ("ldc", c_int64)]
+
+
+class Inject(Structure):
+    _fields_ = [("mode", c_int32), ("bit_lo", c_int32), ("bit_hi", c_int32), ("n_list", c_int32),
+                ("seed", c_uint64), ("rate", c_double), ("d_list", c_void_p), ("log_capacity", c_int32),
+                ("reserved", c_int32)]
+
+
+class InjectRec(Structure):
+    _fields_ = [("row", c_int32), ("col", c_int32), ("bit", c_int32), ("pad", c_int32),
+                ("before", c_double), ("after", c_double)]
+
+
+class VabftError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def load(path: str | None = None):
+    """Load libvabft.so (built in-tree by paper_2602_08043_amd/build.py)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        raise ImportError(
+            f"{p} not found: the HIP library has not been built. Run "
+            "`python -c 'import __graft_entry__ as g; g.build()'` (needs hipcc); there is no fallback path.")
+    lib = ctypes.CDLL(p)
+    lib.vabft_status_string.restype = c_char_p
+    lib.vabft_status_string.argtypes = [ctypes.c_int]
+    lib.vabft_workspace_bytes.restype = c_size_t
+    lib.vabft_workspace_bytes.argtypes = [POINTER(Problem)]
+    lib.vabft_default_emax.restype = c_double
+    lib.vabft_default_emax.argtypes = [c_int32, c_int32, c_int32]
+    lib.vabft_encode.restype = ctypes.c_int
+    lib.vabft_encode.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
+                                 c_void_p]
+    lib.vabft_threshold.restype = ctypes.c_int
+    lib.vabft_threshold.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_double, c_double, c_void_p,
+                                    c_void_p, c_void_p, c_void_p]
+    lib.vabft_gemm_verified.restype = ctypes.c_int
+    lib.vabft_gemm_verified.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int32,
+                                        POINTER(Inject), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                        c_void_p, c_size_t, c_void_p]
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def make_problem(M, N, K, dtype, transB=0, lda=None, ldb=None, ldc=None) -> Problem:
+    code = DTYPE_CODE[dtype] if isinstance(dtype, str) else int(dtype)
+    return Problem(M, N, K, code, int(transB), 0, K if lda is None else lda,
+                   (K if transB else N) if ldb is None else ldb, N if ldc is None else ldc)
+
+
+def status_string(status: int) -> str:
+    return load().vabft_status_string(int(status)).decode()
+
+
+def vabft_workspace_bytes(p: Problem) -> int:
+    return int(load().vabft_workspace_bytes(byref(p)))
+
+
+def vabft_default_emax(dtype, K: int, N: int) -> float:
+    code = DTYPE_CODE[dtype] if isinstance(dtype, str) else int(dtype)
+    return float(load().vabft_default_emax(code, K, N))
+
+
+def _check(rc: int, where: str, check: bool):
+    if check and rc != VABFT_OK:
+        raise VabftError(rc, where)
+    return rc
+
+
+def vabft_encode(p: Problem, dB, d_Be, d_bstat, d_S, d_workspace, workspace_bytes, stream=None, check=True) -> int:
+    rc = load().vabft_encode(byref(p), dB, d_Be, d_bstat, d_S, d_workspace, workspace_bytes, stream)
+    return _check(rc, "vabft_encode", check)
+
+
+def vabft_threshold(p: Problem, dA, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T, stream=None,
+                    check=True) -> int:
+    rc = load().vabft_threshold(byref(p), dA, d_Be, d_S, float(e_max), float(c_sigma), d_astat, d_expected, d_T,
+                                stream)
+    return _check(rc, "vabft_threshold", check)
+
+
+def vabft_gemm_verified(p: Problem, dA, dB, dC, d_expected, d_T, verify, inj, d_rowsum, d_E, d_flags, d_nflag,
+                        d_injlog, d_ninj, d_workspace, workspace_bytes, stream=None, check=True) -> int:
+    rc = load().vabft_gemm_verified(byref(p), dA, dB, dC, d_expected, d_T, int(verify),
+                                    byref(inj) if inj is not None else None, d_rowsum, d_E, d_flags, d_nflag,
+                                    d_injlog, d_ninj, d_workspace, workspace_bytes, stream)
+    return _check(rc, "vabft_gemm_verified", check)

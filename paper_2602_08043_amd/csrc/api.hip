@@ -1,0 +1,220 @@
+// C ABI of libvabft: argument validation, workspace layout, dispatch, and the compare-and-flag
+// step (paper section 2.2 Eq. abft-check, E_i = C^{r1}[i] - C^{r1'}[i]).
+#include <math.h>
+
+#include "vabft_device.h"
+#include "vabft_host.h"
+
+namespace vabft {
+
+// rowsum[i] = sum_t rowpart[t][i] in tile order; E = expected - rowsum; flag = !(|E| <= T)
+template <typename acc_t>
+__global__ __launch_bounds__(256) void finalize_kernel(const acc_t* __restrict__ rowpart, int tiles_n, int M,
+                                                       const acc_t* __restrict__ expected,
+                                                       const acc_t* __restrict__ T, acc_t* __restrict__ rowsum,
+                                                       acc_t* __restrict__ E, int32_t* __restrict__ flags,
+                                                       int32_t* __restrict__ nflag) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    int f = 0;
+    if (i < M) {
+        acc_t s = 0;
+        for (int t = 0; t < tiles_n; ++t) s += rowpart[(int64_t)t * M + i];
+        const acc_t e = expected[i] - s;
+        f = !(fabs(e) <= T[i]);
+        rowsum[i] = s;
+        E[i] = e;
+        flags[i] = f;
+    }
+    const int cnt = __syncthreads_count(f);
+    if (threadIdx.x == 0 && cnt) atomicAdd(nflag, cnt);
+}
+
+__global__ void zero_int_kernel(int32_t* p) { *p = 0; }
+
+static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static bool problem_ok(const vabft_problem* p) {
+    if (!p) return false;
+    if (p->M <= 0 || p->N <= 0 || p->K <= 0) return false;
+    if (p->dtype < VABFT_F64 || p->dtype > VABFT_BF16) return false;
+    if (p->transB != 0 && p->transB != 1) return false;
+    if (p->lda < p->K || p->ldc < p->N) return false;
+    if (p->ldb < (p->transB ? p->K : p->N)) return false;
+    return true;
+}
+
+static inline size_t elem_bytes(int dtype) { return dtype == VABFT_F64 ? 8 : dtype == VABFT_F32 ? 4 : 2; }
+static inline size_t acc_bytes(int dtype) { return dtype == VABFT_F64 ? 8 : 4; }
+static inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+static void tile_shape(int dtype, int* bm, int* bn) {
+    if (dtype == VABFT_F16 || dtype == VABFT_BF16) {
+        *bm = 256;
+        *bn = 256;
+    } else {
+        *bm = 128;
+        *bn = 128;
+    }
+}
+
+size_t gemm_workspace_bytes(const vabft_problem* p) {
+    int bm, bn;
+    tile_shape(p->dtype, &bm, &bn);
+    const size_t tiles_n = ((size_t)p->N + bn - 1) / bn;
+    return tiles_n * (size_t)p->M * acc_bytes(p->dtype);
+}
+
+int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* dC, const void* d_expected,
+                  const void* d_T, int verify, const vabft_inject* inj, void* d_rowsum, void* d_E, int32_t* d_flags,
+                  int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj, void* ws, hipStream_t st) {
+    GemmArgs a;
+    a.A = dA;
+    a.B = dB;
+    a.C = dC;
+    a.M = p->M;
+    a.N = p->N;
+    a.K = p->K;
+    a.lda = p->lda;
+    a.ldb = p->ldb;
+    a.ldc = p->ldc;
+    int bm, bn;
+    tile_shape(p->dtype, &bm, &bn);
+    a.tiles_m = (p->M + bm - 1) / bm;
+    a.tiles_n = (p->N + bn - 1) / bn;
+    const size_t eb = elem_bytes(p->dtype);
+    a.a_vec_ok = aligned_to(dA, 16) && (p->lda * eb) % 16 == 0;
+    a.b_vec_ok = aligned_to(dB, 16) && (p->ldb * eb) % 16 == 0;
+    a.c_vec_ok = aligned_to(dC, 8) && (p->ldc * eb) % 8 == 0;
+    a.rowpart = ws;
+    a.d_nflag = d_nflag;
+    a.inj.mode = 0;
+    a.inj.bit_lo = 0;
+    a.inj.bit_span = 1;
+    a.inj.n_list = 0;
+    a.inj.seed = 0;
+    a.inj.hit_limit = 0;
+    a.inj.d_list = nullptr;
+    a.inj.log_capacity = 0;
+    a.inj.d_log = d_injlog;
+    a.inj.d_ninj = d_ninj;
+    if (inj && inj->mode != 0) {
+        a.inj.mode = inj->mode;
+        a.inj.bit_lo = inj->bit_lo;
+        a.inj.bit_span = inj->bit_hi - inj->bit_lo + 1;
+        a.inj.n_list = inj->n_list;
+        a.inj.seed = inj->seed;
+        a.inj.hit_limit = (uint64_t)floor(inj->rate * 9007199254740992.0);
+        a.inj.d_list = inj->d_list;
+        a.inj.log_capacity = inj->log_capacity;
+        zero_int_kernel<<<1, 1, 0, st>>>(d_ninj);
+    }
+    // the unguarded kernels need whole tiles and 16-byte aligned rows
+    const int bk = (p->dtype == VABFT_F16 || p->dtype == VABFT_BF16) ? 64 : 16;
+    const bool edge = (p->M % bm) || (p->N % bn) || (p->K % bk) || !a.a_vec_ok || !a.b_vec_ok || !a.c_vec_ok;
+    int rc;
+    const int mode = !verify ? 0 : (a.inj.mode != 0 ? 2 : 1);
+    switch (p->dtype) {
+        case VABFT_BF16: rc = gemm16_launch_bf16(a, p->transB, mode, edge, st); break;
+        case VABFT_F16: rc = gemm16_launch_f16(a, p->transB, mode, edge, st); break;
+        case VABFT_F32: rc = gemmw_launch_f32(a, p->transB, mode, edge, st); break;
+        case VABFT_F64: rc = gemmw_launch_f64(a, p->transB, mode, edge, st); break;
+        default: return VABFT_EINVAL;
+    }
+    if (rc != VABFT_OK || !verify) return rc;
+    const dim3 grid((p->M + 255) / 256), block(256);
+    if (p->dtype == VABFT_F64)
+        finalize_kernel<double><<<grid, block, 0, st>>>((const double*)ws, a.tiles_n, p->M, (const double*)d_expected,
+                                                        (const double*)d_T, (double*)d_rowsum, (double*)d_E, d_flags,
+                                                        d_nflag);
+    else
+        finalize_kernel<float><<<grid, block, 0, st>>>((const float*)ws, a.tiles_n, p->M, (const float*)d_expected,
+                                                       (const float*)d_T, (float*)d_rowsum, (float*)d_E, d_flags,
+                                                       d_nflag);
+    return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
+}
+
+}  // namespace vabft
+
+using namespace vabft;
+
+extern "C" {
+
+const char* vabft_status_string(int status) {
+    switch (status) {
+        case VABFT_OK: return "ok";
+        case VABFT_EINVAL: return "invalid argument";
+        case VABFT_EUNSUPPORTED: return "unsupported dtype or layout";
+        case VABFT_EWORKSPACE: return "workspace missing or too small";
+        case VABFT_EDEVICE: return "HIP runtime error at launch";
+    }
+    return "unknown status";
+}
+
+size_t vabft_workspace_bytes(const vabft_problem* p) {
+    if (!problem_ok(p)) return 0;
+    const size_t a = encode_workspace_bytes(p), b = gemm_workspace_bytes(p);
+    return round_up((a > b ? a : b) + 256, 256);
+}
+
+double vabft_default_emax(int32_t dtype, int32_t K, int32_t N) {
+    const double n = (double)(K > N ? K : N);
+    if (dtype == VABFT_F64) return 1.0e-17 * sqrt(n) + 2.5e-16;
+    return 5.0e-9 * sqrt(n) + 1.2e-7;
+}
+
+int vabft_encode(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S, void* d_workspace,
+                 size_t workspace_bytes, void* stream) {
+    if (!problem_ok(p) || !dB || !d_Be || !d_bstat || !d_S) return VABFT_EINVAL;
+    if (!aligned_to(dB, elem_bytes(p->dtype)) || !aligned_to(d_Be, acc_bytes(p->dtype)) ||
+        !aligned_to(d_bstat, acc_bytes(p->dtype)) || !aligned_to(d_S, 8))
+        return VABFT_EINVAL;
+    const size_t need = encode_workspace_bytes(p);
+    if (need && (!d_workspace || workspace_bytes < need || !aligned_to(d_workspace, 16))) return VABFT_EWORKSPACE;
+    return encode_dispatch(p, dB, d_Be, d_bstat, d_S, d_workspace, (hipStream_t)stream);
+}
+
+int vabft_threshold(const vabft_problem* p, const void* dA, const void* d_Be, const double* d_S, double e_max,
+                    double c_sigma, void* d_astat, void* d_expected, void* d_T, void* stream) {
+    if (!problem_ok(p) || !dA || !d_Be || !d_S || !d_astat || !d_expected || !d_T) return VABFT_EINVAL;
+    if (!(e_max > 0.0) || !(c_sigma >= 0.0) || !isfinite(e_max) || !isfinite(c_sigma)) return VABFT_EINVAL;
+    const size_t ab = acc_bytes(p->dtype);
+    if (!aligned_to(dA, elem_bytes(p->dtype)) || !aligned_to(d_Be, ab) || !aligned_to(d_S, 8) ||
+        !aligned_to(d_astat, ab) || !aligned_to(d_expected, ab) || !aligned_to(d_T, ab))
+        return VABFT_EINVAL;
+    return threshold_dispatch(p, dA, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T, (hipStream_t)stream);
+}
+
+int vabft_gemm_verified(const vabft_problem* p, const void* dA, const void* dB, void* dC, const void* d_expected,
+                        const void* d_T, int32_t verify, const vabft_inject* inj, void* d_rowsum, void* d_E,
+                        int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
+                        void* d_workspace, size_t workspace_bytes, void* stream) {
+    if (!problem_ok(p) || !dA || !dB || !dC) return VABFT_EINVAL;
+    if (verify != 0 && verify != 1) return VABFT_EINVAL;
+    const size_t eb = elem_bytes(p->dtype), ab = acc_bytes(p->dtype);
+    if (!aligned_to(dA, eb) || !aligned_to(dB, eb) || !aligned_to(dC, eb)) return VABFT_EINVAL;
+    const bool inj_on = inj && inj->mode != 0;
+    if (verify) {
+        if (!d_expected || !d_T || !d_rowsum || !d_E || !d_flags || !d_nflag) return VABFT_EINVAL;
+        if (!aligned_to(d_expected, ab) || !aligned_to(d_T, ab) || !aligned_to(d_rowsum, ab) || !aligned_to(d_E, ab) ||
+            !aligned_to(d_flags, 4) || !aligned_to(d_nflag, 4))
+            return VABFT_EINVAL;
+        const size_t need = gemm_workspace_bytes(p);
+        if (!d_workspace || workspace_bytes < need || !aligned_to(d_workspace, 16)) return VABFT_EWORKSPACE;
+    } else if (inj_on) {
+        return VABFT_EINVAL;  // the injector lives in the verified kernel
+    }
+    if (inj_on) {
+        const int bits = (int)ab * 8;
+        if (inj->mode != 1 && inj->mode != 2) return VABFT_EINVAL;
+        if (!d_ninj || inj->log_capacity < 0 || (inj->log_capacity > 0 && !d_injlog)) return VABFT_EINVAL;
+        if (inj->mode == 1 && (inj->n_list < 0 || (inj->n_list > 0 && !inj->d_list))) return VABFT_EINVAL;
+        if (inj->mode == 2) {
+            if (!(inj->rate >= 0.0 && inj->rate <= 1.0)) return VABFT_EINVAL;
+            if (inj->bit_lo < 0 || inj->bit_hi < inj->bit_lo || inj->bit_hi >= bits) return VABFT_EINVAL;
+        }
+    }
+    return gemm_dispatch(p, dA, dB, dC, d_expected, d_T, verify, inj, d_rowsum, d_E, d_flags, d_nflag, d_injlog,
+                         d_ninj, d_workspace, (hipStream_t)stream);
+}
+
+}  // extern "C"

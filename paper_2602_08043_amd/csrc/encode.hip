@@ -1,0 +1,440 @@
+// Checksum encode B*r1 with per-row (max, min, mean) statistics and the three B aggregates
+// of Algorithm 1 (paper section 2.2 Eq. r1 / encoded matrices; section 3.5; Algorithm 1 k-loop),
+// and the A-side pass: row statistics, expected checksum A*(B r1) and the threshold T_m
+// (section 3.4 boxed formula).  Both are single streaming passes bound by HBM bandwidth.
+#include "vabft_device.h"
+#include "vabft_host.h"
+
+namespace vabft {
+
+// ---------------------------------------------------------------------------
+// chunk unpacking: 16 raw bytes -> vec accumulator-typed values
+// ---------------------------------------------------------------------------
+template <typename T> struct Unpack;
+template <> struct Unpack<bf16_t> {
+    static __device__ __forceinline__ void run(const raw16& r, float (&v)[8]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(r.w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(r.w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ float one(const void* base, int64_t idx) {
+        return Elem<bf16_t>::to_acc(reinterpret_cast<const uint16_t*>(base)[idx]);
+    }
+};
+template <> struct Unpack<f16_t> {
+    static __device__ __forceinline__ void run(const raw16& r, float (&v)[8]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = Elem<f16_t>::to_acc((uint16_t)(r.w[i] & 0xffffu));
+            v[2 * i + 1] = Elem<f16_t>::to_acc((uint16_t)(r.w[i] >> 16));
+        }
+    }
+    static __device__ __forceinline__ float one(const void* base, int64_t idx) {
+        return Elem<f16_t>::to_acc(reinterpret_cast<const uint16_t*>(base)[idx]);
+    }
+};
+template <> struct Unpack<float> {
+    static __device__ __forceinline__ void run(const raw16& r, float (&v)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = __uint_as_float(r.w[i]);
+    }
+    static __device__ __forceinline__ float one(const void* base, int64_t idx) {
+        return reinterpret_cast<const float*>(base)[idx];
+    }
+};
+template <> struct Unpack<double> {
+    static __device__ __forceinline__ void run(const raw16& r, double (&v)[2]) {
+        v[0] = __hiloint2double((int)r.w[1], (int)r.w[0]);
+        v[1] = __hiloint2double((int)r.w[3], (int)r.w[2]);
+    }
+    static __device__ __forceinline__ double one(const void* base, int64_t idx) {
+        return reinterpret_cast<const double*>(base)[idx];
+    }
+};
+
+// ---------------------------------------------------------------------------
+// B stored K x N: one wavefront reduces one row k
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void encode_rows_kernel(const void* __restrict__ B, int K, int N, int64_t ldb,
+                                                          typename Elem<T>::acc_t* __restrict__ Be,
+                                                          typename Elem<T>::acc_t* __restrict__ bstat, int vec_ok) {
+    using acc_t = typename Elem<T>::acc_t;
+    constexpr int V = Elem<T>::vec;
+    const int lane = threadIdx.x & 63;
+    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (k >= K) return;
+    const char* row = reinterpret_cast<const char*>(B) + (int64_t)k * ldb * Elem<T>::bytes;
+    acc_t sum = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
+    int done = 0;
+    if (vec_ok) {
+        const int nchunks = N / V;
+        int c = lane;
+        for (; c + 192 < nchunks; c += 256) {
+            raw16 r0 = ld16(row + (int64_t)c * 16);
+            raw16 r1 = ld16(row + (int64_t)(c + 64) * 16);
+            raw16 r2 = ld16(row + (int64_t)(c + 128) * 16);
+            raw16 r3 = ld16(row + (int64_t)(c + 192) * 16);
+            acc_t v[4][V];
+            Unpack<T>::run(r0, v[0]);
+            Unpack<T>::run(r1, v[1]);
+            Unpack<T>::run(r2, v[2]);
+            Unpack<T>::run(r3, v[3]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    sum += v[u][e];
+                    mx = v[u][e] > mx ? v[u][e] : mx;
+                    mn = v[u][e] < mn ? v[u][e] : mn;
+                }
+        }
+        for (; c < nchunks; c += 64) {
+            raw16 r0 = ld16(row + (int64_t)c * 16);
+            acc_t v[V];
+            Unpack<T>::run(r0, v);
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                sum += v[e];
+                mx = v[e] > mx ? v[e] : mx;
+                mn = v[e] < mn ? v[e] : mn;
+            }
+        }
+        done = nchunks * V;
+    }
+    for (int n = done + lane; n < N; n += 64) {
+        acc_t x = Unpack<T>::one(row, n);
+        sum += x;
+        mx = x > mx ? x : mx;
+        mn = x < mn ? x : mn;
+    }
+    sum = wave_sum(sum);
+    mx = wave_max(mx);
+    mn = wave_min(mn);
+    if (lane == 0) {
+        Be[k] = sum;
+        bstat[3 * (int64_t)k + 0] = mx;
+        bstat[3 * (int64_t)k + 1] = mn;
+        bstat[3 * (int64_t)k + 2] = (acc_t)((double)sum / (double)N);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// B stored N x K (weight layout): column reduction in two steps.
+// Step 1: block (kx, ny) reduces rows [ny*rows_per_block, ...) of 64*V columns.
+// part layout: [nsplit][3][K] (sum, max, min).
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict__ Bt, int K, int N, int64_t ldb,
+                                                          int rows_per_block,
+                                                          typename Elem<T>::acc_t* __restrict__ part, int vec_ok) {
+    using acc_t = typename Elem<T>::acc_t;
+    constexpr int V = Elem<T>::vec;
+    __shared__ acc_t red[3][3][64 * V];  // waves 1..3 park their partials here
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int k0 = (blockIdx.x * 64 + lane) * V;
+    const int n_begin = blockIdx.y * rows_per_block;
+    const int n_end = min(N, n_begin + rows_per_block);
+    acc_t sum[V], mx[V], mn[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+        sum[e] = 0;
+        mx[e] = -type_max<acc_t>();
+        mn[e] = type_max<acc_t>();
+    }
+    const bool full = vec_ok && (k0 + V <= K);
+    if (full) {
+        int n = n_begin + wave;
+        for (; n + 12 < n_end; n += 16) {
+            raw16 r[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                r[u] = ld16(reinterpret_cast<const char*>(Bt) + ((int64_t)(n + 4 * u) * ldb + k0) * Elem<T>::bytes);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                acc_t v[V];
+                Unpack<T>::run(r[u], v);
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    sum[e] += v[e];
+                    mx[e] = v[e] > mx[e] ? v[e] : mx[e];
+                    mn[e] = v[e] < mn[e] ? v[e] : mn[e];
+                }
+            }
+        }
+        for (; n < n_end; n += 4) {
+            raw16 r0 = ld16(reinterpret_cast<const char*>(Bt) + ((int64_t)n * ldb + k0) * Elem<T>::bytes);
+            acc_t v[V];
+            Unpack<T>::run(r0, v);
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                sum[e] += v[e];
+                mx[e] = v[e] > mx[e] ? v[e] : mx[e];
+                mn[e] = v[e] < mn[e] ? v[e] : mn[e];
+            }
+        }
+    } else {
+        for (int n = n_begin + wave; n < n_end; n += 4) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                if (k0 + e < K) {
+                    acc_t x = Unpack<T>::one(Bt, (int64_t)n * ldb + k0 + e);
+                    sum[e] += x;
+                    mx[e] = x > mx[e] ? x : mx[e];
+                    mn[e] = x < mn[e] ? x : mn[e];
+                }
+            }
+        }
+    }
+    if (wave > 0) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            red[wave - 1][0][lane * V + e] = sum[e];
+            red[wave - 1][1][lane * V + e] = mx[e];
+            red[wave - 1][2][lane * V + e] = mn[e];
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int w = 0; w < 3; ++w)
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                sum[e] += red[w][0][lane * V + e];
+                acc_t a = red[w][1][lane * V + e], b = red[w][2][lane * V + e];
+                mx[e] = a > mx[e] ? a : mx[e];
+                mn[e] = b < mn[e] ? b : mn[e];
+            }
+        acc_t* p = part + (int64_t)blockIdx.y * 3 * K;
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            if (k0 + e < K) {
+                p[k0 + e] = sum[e];
+                p[(int64_t)K + k0 + e] = mx[e];
+                p[2 * (int64_t)K + k0 + e] = mn[e];
+            }
+        }
+    }
+}
+
+// Step 2: combine the nsplit partials of column k in a fixed order.
+template <typename acc_t>
+__global__ __launch_bounds__(256) void encode_cols_combine_kernel(const acc_t* __restrict__ part, int nsplit, int K,
+                                                                  int N, acc_t* __restrict__ Be,
+                                                                  acc_t* __restrict__ bstat) {
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= K) return;
+    acc_t sum = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
+    for (int s = 0; s < nsplit; ++s) {
+        const acc_t* p = part + (int64_t)s * 3 * K;
+        sum += p[k];
+        acc_t a = p[(int64_t)K + k], b = p[2 * (int64_t)K + k];
+        mx = a > mx ? a : mx;
+        mn = b < mn ? b : mn;
+    }
+    Be[k] = sum;
+    bstat[3 * (int64_t)k + 0] = mx;
+    bstat[3 * (int64_t)k + 1] = mn;
+    bstat[3 * (int64_t)k + 2] = (acc_t)((double)sum / (double)N);
+}
+
+// ---------------------------------------------------------------------------
+// S1, S2, S3 from (Be, max, min): one block, fixed-order tree, double arithmetic
+// ---------------------------------------------------------------------------
+template <typename acc_t>
+__global__ __launch_bounds__(1024) void encode_aggregate_kernel(const acc_t* __restrict__ Be,
+                                                                const acc_t* __restrict__ bstat, int K, int N,
+                                                                double* __restrict__ S) {
+    __shared__ double red[3][1024];
+    const int t = threadIdx.x;
+    double s1 = 0, s2 = 0, s3 = 0;
+    for (int k = t; k < K; k += 1024) {
+        const double mu = (double)Be[k] / (double)N;
+        const double mx = (double)bstat[3 * (int64_t)k], mn = (double)bstat[3 * (int64_t)k + 1];
+        double var = (mx - mu) * (mu - mn);
+        var = var > 0 ? var : 0;
+        s1 += fabs(mu);
+        s2 += var;
+        s3 += mu * mu;
+    }
+    red[0][t] = s1;
+    red[1][t] = s2;
+    red[2][t] = s3;
+    __syncthreads();
+    for (int off = 512; off >= 1; off >>= 1) {
+        if (t < off) {
+            red[0][t] += red[0][t + off];
+            red[1][t] += red[1][t + off];
+            red[2][t] += red[2][t + off];
+        }
+        __syncthreads();
+    }
+    if (t < 3) S[t] = red[t][0];
+}
+
+// ---------------------------------------------------------------------------
+// A side: one wavefront per row m: (max, min, mean), dot with Be, threshold
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restrict__ A, int M, int K, int N,
+                                                             int64_t lda,
+                                                             const typename Elem<T>::acc_t* __restrict__ Be,
+                                                             const double* __restrict__ S, double e_max,
+                                                             double c_sigma,
+                                                             typename Elem<T>::acc_t* __restrict__ astat,
+                                                             typename Elem<T>::acc_t* __restrict__ expected,
+                                                             typename Elem<T>::acc_t* __restrict__ Tout, int vec_ok) {
+    using acc_t = typename Elem<T>::acc_t;
+    constexpr int V = Elem<T>::vec;
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= M) return;
+    const char* row = reinterpret_cast<const char*>(A) + (int64_t)m * lda * Elem<T>::bytes;
+    acc_t sum = 0, dot = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
+    int done = 0;
+    if (vec_ok) {
+        const int nchunks = K / V;
+        int c = lane;
+        for (; c + 64 < nchunks; c += 128) {
+            raw16 r0 = ld16(row + (int64_t)c * 16);
+            raw16 r1 = ld16(row + (int64_t)(c + 64) * 16);
+            acc_t v0[V], v1[V], b0[V], b1[V];
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                b0[e] = Be[(int64_t)c * V + e];
+                b1[e] = Be[(int64_t)(c + 64) * V + e];
+            }
+            Unpack<T>::run(r0, v0);
+            Unpack<T>::run(r1, v1);
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                sum += v0[e];
+                dot = fma(v0[e], b0[e], dot);
+                mx = v0[e] > mx ? v0[e] : mx;
+                mn = v0[e] < mn ? v0[e] : mn;
+            }
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                sum += v1[e];
+                dot = fma(v1[e], b1[e], dot);
+                mx = v1[e] > mx ? v1[e] : mx;
+                mn = v1[e] < mn ? v1[e] : mn;
+            }
+        }
+        for (; c < nchunks; c += 64) {
+            raw16 r0 = ld16(row + (int64_t)c * 16);
+            acc_t v0[V];
+            Unpack<T>::run(r0, v0);
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const acc_t b = Be[(int64_t)c * V + e];
+                sum += v0[e];
+                dot = fma(v0[e], b, dot);
+                mx = v0[e] > mx ? v0[e] : mx;
+                mn = v0[e] < mn ? v0[e] : mn;
+            }
+        }
+        done = nchunks * V;
+    }
+    for (int k = done + lane; k < K; k += 64) {
+        acc_t x = Unpack<T>::one(row, k);
+        sum += x;
+        dot = fma(x, Be[k], dot);
+        mx = x > mx ? x : mx;
+        mn = x < mn ? x : mn;
+    }
+    sum = wave_sum(sum);
+    dot = wave_sum(dot);
+    mx = wave_max(mx);
+    mn = wave_min(mn);
+    if (lane == 0) {
+        const double mu = (double)sum / (double)K;
+        double var = ((double)mx - mu) * (mu - (double)mn);
+        var = var > 0 ? var : 0;
+        const double S1 = S[0], S2 = S[1], S3 = S[2];
+        const double dN = (double)N;
+        const double t_det = dN * fabs(mu) * S1;
+        const double t_var23 = c_sigma * sqrt(dN * mu * mu * S2 + dN * dN * var * S3);
+        const double t_var4 = c_sigma * sqrt(dN) * sqrt(var) * sqrt(S2);
+        astat[3 * (int64_t)m + 0] = mx;
+        astat[3 * (int64_t)m + 1] = mn;
+        astat[3 * (int64_t)m + 2] = (acc_t)mu;
+        expected[m] = dot;
+        Tout[m] = (acc_t)(e_max * (t_det + t_var23 + t_var4));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host launchers
+// ---------------------------------------------------------------------------
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+constexpr int ENC_ROWS_PER_BLOCK = 128;  // n-rows per block in the transposed layout
+
+size_t encode_workspace_bytes(const vabft_problem* p) {
+    if (!p->transB) return 0;
+    const size_t acc_bytes = p->dtype == VABFT_F64 ? 8 : 4;
+    const size_t nsplit = ((size_t)p->N + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
+    return nsplit * 3 * (size_t)p->K * acc_bytes;
+}
+
+template <typename T>
+static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S, void* ws,
+                         hipStream_t st) {
+    using acc_t = typename Elem<T>::acc_t;
+    const int vec_ok = aligned16(dB) && ((p->ldb * Elem<T>::bytes) % 16 == 0);
+    if (!p->transB) {
+        encode_rows_kernel<T><<<dim3((p->K + 3) / 4), dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, (acc_t*)d_Be,
+                                                                          (acc_t*)d_bstat, vec_ok);
+    } else {
+        constexpr int V = Elem<T>::vec;
+        const int nsplit = (p->N + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
+        dim3 grid((p->K + 64 * V - 1) / (64 * V), nsplit);
+        encode_cols_kernel<T><<<grid, dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, ENC_ROWS_PER_BLOCK, (acc_t*)ws,
+                                                          vec_ok);
+        encode_cols_combine_kernel<acc_t><<<dim3((p->K + 255) / 256), dim3(256), 0, st>>>(
+            (const acc_t*)ws, nsplit, p->K, p->N, (acc_t*)d_Be, (acc_t*)d_bstat);
+    }
+    encode_aggregate_kernel<acc_t><<<dim3(1), dim3(1024), 0, st>>>((const acc_t*)d_Be, (const acc_t*)d_bstat, p->K,
+                                                                   p->N, d_S);
+    return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
+}
+
+int encode_dispatch(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S, void* ws,
+                    hipStream_t st) {
+    switch (p->dtype) {
+        case VABFT_F64: return encode_launch<double>(p, dB, d_Be, d_bstat, d_S, ws, st);
+        case VABFT_F32: return encode_launch<float>(p, dB, d_Be, d_bstat, d_S, ws, st);
+        case VABFT_F16: return encode_launch<f16_t>(p, dB, d_Be, d_bstat, d_S, ws, st);
+        case VABFT_BF16: return encode_launch<bf16_t>(p, dB, d_Be, d_bstat, d_S, ws, st);
+    }
+    return VABFT_EINVAL;
+}
+
+template <typename T>
+static int threshold_launch(const vabft_problem* p, const void* dA, const void* d_Be, const double* d_S, double e_max,
+                            double c_sigma, void* d_astat, void* d_expected, void* d_T, hipStream_t st) {
+    using acc_t = typename Elem<T>::acc_t;
+    const int vec_ok = aligned16(dA) && ((p->lda * Elem<T>::bytes) % 16 == 0);
+    threshold_rows_kernel<T><<<dim3((p->M + 3) / 4), dim3(256), 0, st>>>(dA, p->M, p->K, p->N, p->lda,
+                                                                         (const acc_t*)d_Be, d_S, e_max, c_sigma,
+                                                                         (acc_t*)d_astat, (acc_t*)d_expected,
+                                                                         (acc_t*)d_T, vec_ok);
+    return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
+}
+
+int threshold_dispatch(const vabft_problem* p, const void* dA, const void* d_Be, const double* d_S, double e_max,
+                       double c_sigma, void* d_astat, void* d_expected, void* d_T, hipStream_t st) {
+    switch (p->dtype) {
+        case VABFT_F64: return threshold_launch<double>(p, dA, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T, st);
+        case VABFT_F32: return threshold_launch<float>(p, dA, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T, st);
+        case VABFT_F16: return threshold_launch<f16_t>(p, dA, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T, st);
+        case VABFT_BF16:
+            return threshold_launch<bf16_t>(p, dA, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T, st);
+    }
+    return VABFT_EINVAL;
+}
+
+}  // namespace vabft

@@ -1,0 +1,304 @@
+// BF16 / FP16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16) with the fused V-ABFT
+// epilogue: row sums of the FP32 accumulator tile before output quantisation (paper section
+// 3.6 "Online (Fused Kernel) ABFT"; section 2.2 C^{r1'} = C r1), and the accumulator bit-flip
+// injector (section 5.1).
+//
+// Tile 256 x 256 x 64 per workgroup of 4 wavefronts (2 x 2), 128 x 128 per wavefront as
+// 4 x 4 MFMA tiles.  Operands are staged in LDS as [row][64 k] with the eight 16-byte chunks
+// of a row XOR-swizzled so that both the staging stores and the ds_read_b128 fragment loads
+// are bank-conflict free.  The MFMA is issued with the roles of A and B swapped
+// (D' = B^T A^T), which puts one C row in one lane: lane l of a tile owns row (l % 32) and the
+// 16 registers run along 16 of the tile's 32 columns, the other 16 sit in lane l ^ 32.  A row
+// sum is therefore 16 in-register adds per tile plus one cross-lane add.
+#pragma once
+#include "gemm_common.h"
+
+namespace vabft {
+
+template <typename T> struct Mfma16;
+template <> struct Mfma16<bf16_t> {
+    static __device__ __forceinline__ f32x16_t run(const raw16& a, const raw16& b, f32x16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
+                                                       c, 0, 0, 0);
+    }
+};
+template <> struct Mfma16<f16_t> {
+    static __device__ __forceinline__ f32x16_t run(const raw16& a, const raw16& b, f32x16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c,
+                                                      0, 0, 0);
+    }
+};
+
+namespace g16 {
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+constexpr int STAGE = A_BYTES + B_BYTES;
+constexpr int LDS_BYTES = 2 * STAGE;  // double buffered: 128 KiB
+
+__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
+__device__ __forceinline__ int lds_pos(int row, int chunk) { return row * 128 + ((chunk ^ swz(row)) << 4); }
+}  // namespace g16
+
+// MODE 0: plain GEMM; 1: fused row-sum check; 2: check plus the fault injector.
+template <typename T, int TRANSB, int MODE, bool EDGE>
+__global__ __launch_bounds__(256) void gemm16_kernel(const GemmArgs g) {
+    using namespace g16;
+    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+    int bm, bn;
+    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
+    if (VERIFY && blockIdx.x == 0 && tid == 0) *g.d_nflag = 0;
+    const int row0 = bm * BM, col0 = bn * BN;
+    const uint16_t* __restrict__ A = reinterpret_cast<const uint16_t*>(g.A);
+    const uint16_t* __restrict__ B = reinterpret_cast<const uint16_t*>(g.B);
+
+    f32x16_t acc[4][4];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+    raw16 ra[8], rb[8];
+
+    // ---- global -> registers ------------------------------------------------
+    auto load_tiles = [&](int kt) {
+        const int kbase = kt * BK;
+        {
+            const int c = tid & 7, r = tid >> 3;
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int gr = row0 + r + 32 * p, gk = kbase + c * 8;
+                if (!EDGE)
+                    ra[p] = ld16(A + (int64_t)gr * g.lda + gk);
+                else
+                    ra[p] = guarded_chunk2(A, gr, g.M, gk, g.K, g.lda, g.a_vec_ok);
+            }
+        }
+        if (TRANSB) {
+            const int c = tid & 7, r = tid >> 3;
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int gn = col0 + r + 32 * p, gk = kbase + c * 8;
+                if (!EDGE)
+                    rb[p] = ld16(B + (int64_t)gn * g.ldb + gk);
+                else
+                    rb[p] = guarded_chunk2(B, gn, g.N, gk, g.K, g.ldb, g.b_vec_ok);
+            }
+        } else {
+            const int nc = tid & 31, kb = tid >> 5;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int gk = kbase + kb * 8 + e, gn = col0 + nc * 8;
+                if (!EDGE)
+                    rb[e] = ld16(B + (int64_t)gk * g.ldb + gn);
+                else
+                    rb[e] = guarded_chunk2(B, gk, g.K, gn, g.N, g.ldb, g.b_vec_ok);
+            }
+        }
+    };
+
+    // ---- registers -> LDS ---------------------------------------------------
+    auto store_tiles = [&](int s) {
+        unsigned char* As = smem + s * STAGE;
+        unsigned char* Bs = As + A_BYTES;
+        {
+            const int c = tid & 7, r = tid >> 3;
+#pragma unroll
+            for (int p = 0; p < 8; ++p) *reinterpret_cast<raw16*>(As + lds_pos(r + 32 * p, c)) = ra[p];
+        }
+        if (TRANSB) {
+            const int c = tid & 7, r = tid >> 3;
+#pragma unroll
+            for (int p = 0; p < 8; ++p) *reinterpret_cast<raw16*>(Bs + lds_pos(r + 32 * p, c)) = rb[p];
+        } else {
+            // 8 x 8 transpose of 16-bit elements: rb[e] holds k = kb*8+e, n = nc*8 .. +7
+            const int nc = tid & 31, kb = tid >> 5;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                raw16 o;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const uint32_t lo = rb[2 * w].w[q >> 1], hi = rb[2 * w + 1].w[q >> 1];
+                    o.w[w] = (q & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+                }
+                *reinterpret_cast<raw16*>(Bs + lds_pos(nc * 8 + q, kb)) = o;
+            }
+        }
+    };
+
+    // ---- LDS -> MFMA ----------------------------------------------------------
+    auto compute = [&](int s) {
+        const unsigned char* As = smem + s * STAGE;
+        const unsigned char* Bs = As + A_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            raw16 af[4], bf[4];
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+                af[mi] = *reinterpret_cast<const raw16*>(As + lds_pos(wm * 128 + mi * 32 + l32, ks * 2 + lh));
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+                bf[ni] = *reinterpret_cast<const raw16*>(Bs + lds_pos(wn * 128 + ni * 32 + l32, ks * 2 + lh));
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = Mfma16<T>::run(bf[ni], af[mi], acc[mi][ni]);
+        }
+    };
+
+    const int nk = (g.K + BK - 1) / BK;
+    load_tiles(0);
+    store_tiles(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const bool more = kt + 1 < nk;
+        if (more) load_tiles(kt + 1);
+        compute(kt & 1);
+        if (more) store_tiles((kt + 1) & 1);
+        __syncthreads();
+    }
+
+    // accumulator element (mi, ni, r) is C[row0 + rl(mi)][col0 + cl(ni, r)]
+    const int rl_base = wm * 128 + l32;
+    const int cl_base = wn * 128 + 4 * lh;
+
+    // ---- fault injector -----------------------------------------------------
+    if (INJECT) {
+        const InjectArgs& inj = g.inj;
+        if (inj.mode == 1) {
+            for (int e = 0; e < inj.n_list; ++e) {
+                const int fr = inj.d_list[3 * e], fc = inj.d_list[3 * e + 1], fb = inj.d_list[3 * e + 2];
+                if (fr < row0 || fr >= row0 + BM || fc < col0 || fc >= col0 + BN) continue;
+                if (fr >= g.M || fc >= g.N || fb < 0 || fb > 31) continue;
+                const int rl = fr - row0, cl = fc - col0;
+                const bool own = (rl >> 7) == wm && (cl >> 7) == wn && (rl & 31) == l32 && ((cl >> 2) & 1) == lh;
+                if (own) {
+                    const int idx = ((rl >> 5) & 3) * 64 + ((cl >> 5) & 3) * 16 + ((cl & 31) >> 3) * 4 + (cl & 3);
+                    float before = 0.f, after = 0.f;
+                    static_for<0, 4>([&](auto mi_c) {
+                        static_for<0, 4>([&](auto ni_c) {
+                            static_for<0, 16>([&](auto r_c) {
+                                constexpr int mi = decltype(mi_c)::value, ni = decltype(ni_c)::value,
+                                              r = decltype(r_c)::value;
+                                if (idx == mi * 64 + ni * 16 + r) {
+                                    before = acc[mi][ni][r];
+                                    after = flip_bit(before, fb);
+                                    acc[mi][ni][r] = after;
+                                }
+                            });
+                        });
+                    });
+                    log_fault(inj, fr, fc, fb, (double)before, (double)after);
+                }
+            }
+        } else if (inj.mode == 2) {
+            static_for<0, 4>([&](auto mi_c) {
+                static_for<0, 4>([&](auto ni_c) {
+                    static_for<0, 16>([&](auto r_c) {
+                        constexpr int mi = decltype(mi_c)::value, ni = decltype(ni_c)::value, r = decltype(r_c)::value;
+                        const int gi = row0 + rl_base + mi * 32;
+                        const int gj = col0 + cl_base + ni * 32 + 8 * (r >> 2) + (r & 3);
+                        if (gi < g.M && gj < g.N) {
+                            const int bit = bernoulli_bit(inj, gi, gj, g.N);
+                            if (bit >= 0) acc[mi][ni][r] = flip_and_log<float>(inj, acc[mi][ni][r], gi, gj, bit);
+                        }
+                    });
+                });
+            });
+        }
+    }
+
+    // ---- row sums of the accumulator tile (before quantisation) -----------------
+    if (VERIFY) {
+        float* red = reinterpret_cast<float*>(smem);  // [2][256]
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+            float s = 0.f;
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s += acc[mi][ni][r];
+            s += __shfl_xor(s, 32, WAVE);
+            if (lh == 0) red[wn * BM + wm * 128 + mi * 32 + l32] = s;
+        }
+        __syncthreads();
+        {
+            const int gi = row0 + tid;
+            if (gi < g.M)
+                reinterpret_cast<float*>(g.rowpart)[(int64_t)bn * g.M + gi] = red[tid] + red[BM + tid];
+        }
+    }
+
+    // ---- quantise and store C -------------------------------------------------
+    uint16_t* __restrict__ C = reinterpret_cast<uint16_t*>(g.C);
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+        const int gi = row0 + rl_base + mi * 32;
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int gj = col0 + cl_base + ni * 32 + 8 * q;
+                uint16_t h[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) h[e] = Elem<T>::from_acc(acc[mi][ni][4 * q + e]);
+                if (!EDGE) {
+                    uint2 v;
+                    v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                    v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+                    *reinterpret_cast<uint2*>(C + (int64_t)gi * g.ldc + gj) = v;
+                } else if (gi < g.M) {
+                    if (g.c_vec_ok && gj + 4 <= g.N) {
+                        uint2 v;
+                        v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                        v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+                        *reinterpret_cast<uint2*>(C + (int64_t)gi * g.ldc + gj) = v;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (gj + e < g.N) C[(int64_t)gi * g.ldc + gj + e] = h[e];
+                    }
+                }
+            }
+    }
+}
+
+template <typename T>
+static int gemm16_launch(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st) {
+    const dim3 grid(a.tiles_m * a.tiles_n), block(256);
+    const size_t lds = g16::LDS_BYTES;
+#define VABFT_G16_CASE(TB, VF, ED)                                                                         \
+    if (transB == TB && mode == VF && edge == ED) {                                               \
+        auto kern = gemm16_kernel<T, TB, VF, ED>;                                                          \
+        static bool attr_set = false;                                                                      \
+        if (!attr_set) {                                                                                   \
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)   \
+                return VABFT_EDEVICE;                                                                      \
+            attr_set = true;                                                                               \
+        }                                                                                                  \
+        kern<<<grid, block, lds, st>>>(a);                                                                 \
+        return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;                                 \
+    }
+    VABFT_G16_CASE(0, 0, false)
+    VABFT_G16_CASE(0, 0, true)
+    VABFT_G16_CASE(0, 1, false)
+    VABFT_G16_CASE(0, 1, true)
+    VABFT_G16_CASE(0, 2, false)
+    VABFT_G16_CASE(0, 2, true)
+    VABFT_G16_CASE(1, 0, false)
+    VABFT_G16_CASE(1, 0, true)
+    VABFT_G16_CASE(1, 1, false)
+    VABFT_G16_CASE(1, 1, true)
+    VABFT_G16_CASE(1, 2, false)
+    VABFT_G16_CASE(1, 2, true)
+#undef VABFT_G16_CASE
+    return VABFT_EINVAL;
+}
+
+}  // namespace vabft

@@ -1,0 +1,116 @@
+"""Device-buffer plumbing around the C ABI: PyTorch supplies HBM allocations and the
+stream handle, nothing else.  All arithmetic happens inside libvabft.so."""
+from __future__ import annotations
+
+import ctypes
+
+import numpy as np
+import torch
+
+from . import binding as vb
+
+_TORCH_DTYPE = {"f64": torch.float64, "f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+_REC_DTYPE = np.dtype([("row", "<i4"), ("col", "<i4"), ("bit", "<i4"), ("pad", "<i4"), ("before", "<f8"),
+                       ("after", "<f8")])
+
+
+def to_device(x: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
+    """Storage array (see workloads.py) -> device tensor of the matching torch dtype."""
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(x)).to(device)
+
+
+def to_host(t: torch.Tensor, dtype: str) -> np.ndarray:
+    if dtype == "bf16":
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+class VerifiedGemm:
+    """Buffers of one problem and thin wrappers over the three entry points."""
+
+    def __init__(self, M, N, K, dtype: str, transB=0, device="cuda:0", log_capacity=4096):
+        vb.load()
+        self.M, self.N, self.K, self.dtype, self.transB = M, N, K, dtype, int(transB)
+        self.device = torch.device(device)
+        self.problem = vb.make_problem(M, N, K, dtype, transB)
+        acc = torch.float64 if dtype == "f64" else torch.float32
+        self.acc = acc
+        dev = self.device
+        self.C = torch.empty((M, N), dtype=_TORCH_DTYPE[dtype], device=dev)
+        self.Be = torch.empty(K, dtype=acc, device=dev)
+        self.bstat = torch.empty((K, 3), dtype=acc, device=dev)
+        self.S = torch.empty(3, dtype=torch.float64, device=dev)
+        self.astat = torch.empty((M, 3), dtype=acc, device=dev)
+        self.expected = torch.empty(M, dtype=acc, device=dev)
+        self.T = torch.empty(M, dtype=acc, device=dev)
+        self.rowsum = torch.empty(M, dtype=acc, device=dev)
+        self.E = torch.empty(M, dtype=acc, device=dev)
+        self.flags = torch.empty(M, dtype=torch.int32, device=dev)
+        self.nflag = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.ninj = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.log_capacity = int(log_capacity)
+        self.injlog = torch.zeros(max(1, self.log_capacity) * _REC_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+        self.ws_bytes = vb.vabft_workspace_bytes(self.problem)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
+        self._list = None
+
+    @staticmethod
+    def _stream():
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def encode(self, B: torch.Tensor):
+        return vb.vabft_encode(self.problem, B.data_ptr(), self.Be.data_ptr(), self.bstat.data_ptr(),
+                               self.S.data_ptr(), self.ws.data_ptr(), self.ws_bytes, self._stream())
+
+    def threshold(self, A: torch.Tensor, e_max=None, c_sigma=2.5):
+        if e_max is None:
+            e_max = vb.vabft_default_emax(self.dtype, self.K, self.N)
+        self.e_max = e_max
+        return vb.vabft_threshold(self.problem, A.data_ptr(), self.Be.data_ptr(), self.S.data_ptr(), e_max, c_sigma,
+                                  self.astat.data_ptr(), self.expected.data_ptr(), self.T.data_ptr(), self._stream())
+
+    def make_inject(self, mode=0, faults=None, seed=0, rate=0.0, bit_lo=0, bit_hi=0) -> vb.Inject:
+        """mode 1: faults = [(row, col, bit), ...]; mode 2: Bernoulli(seed, rate, bit_lo..bit_hi)."""
+        inj = vb.Inject()
+        inj.mode = mode
+        inj.bit_lo, inj.bit_hi = bit_lo, bit_hi
+        inj.seed, inj.rate = seed, rate
+        inj.log_capacity = self.log_capacity
+        if mode == 1:
+            arr = np.asarray(faults, dtype=np.int32).reshape(-1, 3)
+            self._list = torch.from_numpy(arr.copy()).to(self.device)
+            inj.n_list = arr.shape[0]
+            inj.d_list = self._list.data_ptr()
+        return inj
+
+    def gemm(self, A: torch.Tensor, B: torch.Tensor, verify=1, inj: vb.Inject | None = None):
+        return vb.vabft_gemm_verified(self.problem, A.data_ptr(), B.data_ptr(), self.C.data_ptr(),
+                                      self.expected.data_ptr(), self.T.data_ptr(), verify, inj,
+                                      self.rowsum.data_ptr(), self.E.data_ptr(), self.flags.data_ptr(),
+                                      self.nflag.data_ptr(), self.injlog.data_ptr(), self.ninj.data_ptr(),
+                                      self.ws.data_ptr(), self.ws_bytes, self._stream())
+
+    def run(self, A, B, e_max=None, c_sigma=2.5, inj=None):
+        """One pass of the whole path: encode, threshold, verified GEMM."""
+        self.encode(B)
+        self.threshold(A, e_max, c_sigma)
+        self.gemm(A, B, 1, inj)
+
+    def inject_records(self):
+        """Downloaded injection log as a list of (row, col, bit, before, after), sorted."""
+        n = int(self.ninj.item())
+        m = min(n, self.log_capacity)
+        raw = self.injlog.cpu().numpy()[: m * _REC_DTYPE.itemsize].view(_REC_DTYPE)
+        recs = sorted((int(r["row"]), int(r["col"]), int(r["bit"]), float(r["before"]), float(r["after"]))
+                      for r in raw)
+        return n, recs
+
+    def results(self):
+        torch.cuda.synchronize(self.device)
+        out = {k: getattr(self, k).cpu().numpy() for k in
+               ("Be", "bstat", "S", "astat", "expected", "T", "rowsum", "E", "flags")}
+        out["nflag"] = int(self.nflag.item())
+        out["C"] = to_host(self.C, self.dtype)
+        return out

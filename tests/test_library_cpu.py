@@ -1,0 +1,68 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol
+include/vabft.h declares, and rejects bad arguments before launching anything."""
+import os
+import re
+
+import pytest
+
+from paper_2602_08043_amd import binding as vb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(vb.LIB_PATH):
+        import __graft_entry__ as ge
+        ge.build()
+    return vb.load()
+
+
+def test_exports_match_header(lib):
+    header = open(os.path.join(ROOT, "include", "vabft.h")).read()
+    declared = set(re.findall(r"\b(vabft_[a-z_]+)\s*\(", header))
+    assert declared == set(vb.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layouts_match_header():
+    import ctypes
+    assert ctypes.sizeof(vb.Problem) == 48
+    assert ctypes.sizeof(vb.Inject) == 48
+    assert ctypes.sizeof(vb.InjectRec) == 32
+    assert vb.Problem.lda.offset == 24 and vb.Inject.seed.offset == 16 and vb.Inject.d_list.offset == 32
+
+
+def test_status_strings_and_default_emax(lib):
+    assert vb.status_string(0) == "ok"
+    assert "workspace" in vb.status_string(vb.VABFT_EWORKSPACE)
+    assert vb.vabft_default_emax("bf16", 4096, 4096) == pytest.approx(5.0e-9 * 64 + 1.2e-7)
+    assert vb.vabft_default_emax("f64", 2048, 2048) == pytest.approx(1.0e-17 * 2048 ** 0.5 + 2.5e-16)
+    assert vb.vabft_default_emax("f16", 4096, 11008) == vb.vabft_default_emax("f32", 11008, 4096)
+
+
+def test_workspace_bytes(lib):
+    p = vb.make_problem(4096, 4096, 4096, "bf16")
+    assert vb.vabft_workspace_bytes(p) >= 16 * 4096 * 4
+    assert vb.vabft_workspace_bytes(vb.make_problem(0, 4, 4, "f32")) == 0
+    assert vb.vabft_workspace_bytes(vb.make_problem(4, 4, 4, 9)) == 0
+    pt = vb.make_problem(4096, 11008, 4096, "bf16", transB=1)
+    assert vb.vabft_workspace_bytes(pt) >= 86 * 3 * 4096 * 4
+
+
+def test_rejects_bad_arguments_without_a_gpu(lib):
+    p = vb.make_problem(8, 8, 8, "f32")
+    # null pointers
+    assert vb.vabft_encode(p, None, None, None, None, None, 0, None, check=False) == vb.VABFT_EINVAL
+    assert vb.vabft_threshold(p, None, None, None, 1e-6, 2.5, None, None, None, None, check=False) == vb.VABFT_EINVAL
+    assert vb.vabft_gemm_verified(p, None, None, None, None, None, 1, None, None, None, None, None, None, None, None, 0,
+                                  None, check=False) == vb.VABFT_EINVAL
+    # leading dimension smaller than the row, unknown dtype, bad transB
+    for bad in (vb.make_problem(8, 8, 8, "f32", lda=4), vb.make_problem(8, 8, 8, 7), vb.make_problem(8, 8, 8, "f32", transB=2),
+                vb.make_problem(8, 8, 8, "f32", transB=1, ldb=7), vb.make_problem(-1, 8, 8, "f32")):
+        assert vb.vabft_encode(bad, 16, 16, 16, 16, 16, 1 << 20, None, check=False) == vb.VABFT_EINVAL
+    # misaligned element pointer
+    assert vb.vabft_encode(p, 18, 16, 16, 16, None, 0, None, check=False) == vb.VABFT_EINVAL
+    with pytest.raises(vb.VabftError):
+        vb.vabft_encode(p, None, None, None, None, None, 0, None)
