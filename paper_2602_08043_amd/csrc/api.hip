@@ -84,7 +84,7 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     const size_t eb = elem_bytes(p->dtype);
     a.a_vec_ok = aligned_to(dA, 16) && (p->lda * eb) % 16 == 0;
     a.b_vec_ok = aligned_to(dB, 16) && (p->ldb * eb) % 16 == 0;
-    a.c_vec_ok = aligned_to(dC, 8) && (p->ldc * eb) % 8 == 0;
+    a.c_vec_ok = aligned_to(dC, 16) && (p->ldc * eb) % 16 == 0;
     a.rowpart = ws;
     a.d_nflag = d_nflag;
     a.inj.mode = 0;

@@ -39,6 +39,155 @@ __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 __device__ __forceinline__ int lds_pos(int row, int chunk) { return row * 128 + ((chunk ^ swz(row)) << 4); }
 }  // namespace g16
 
+// Epilogue shared by the 16-bit GEMM kernels: optional fault injection on the accumulator
+// registers, row sums of the accumulator tile before quantisation, quantised store of C.
+// Accumulator element (mi, ni, r) of a wavefront is
+//   C[row0 + wm*128 + mi*32 + lane%32][col0 + wn*128 + ni*32 + 8*(r/4) + 4*(lane/32) + r%4].
+// `smem` must be free for reuse (all wavefronts past their last LDS read).
+template <typename T, int MODE, bool EDGE>
+__device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x16_t (&acc)[4][4], unsigned char* smem,
+                                                int row0, int col0, int bn, int tid, int lane, int wm, int wn,
+                                                int l32, int lh) {
+    using namespace g16;
+    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2;
+    (void)lane;
+    // accumulator element (mi, ni, r) is C[row0 + rl(mi)][col0 + cl(ni, r)]
+    const int rl_base = wm * 128 + l32;
+    const int cl_base = wn * 128 + 4 * lh;
+
+    // ---- fault injector -----------------------------------------------------
+    if (INJECT) {
+        const InjectArgs& inj = g.inj;
+        if (inj.mode == 1) {
+            for (int e = 0; e < inj.n_list; ++e) {
+                const int fr = inj.d_list[3 * e], fc = inj.d_list[3 * e + 1], fb = inj.d_list[3 * e + 2];
+                if (fr < row0 || fr >= row0 + BM || fc < col0 || fc >= col0 + BN) continue;
+                if (fr >= g.M || fc >= g.N || fb < 0 || fb > 31) continue;
+                const int rl = fr - row0, cl = fc - col0;
+                const bool own = (rl >> 7) == wm && (cl >> 7) == wn && (rl & 31) == l32 && ((cl >> 2) & 1) == lh;
+                if (own) {
+                    const int idx = ((rl >> 5) & 3) * 64 + ((cl >> 5) & 3) * 16 + ((cl & 31) >> 3) * 4 + (cl & 3);
+                    float before = 0.f, after = 0.f;
+                    static_for<0, 4>([&](auto mi_c) {
+                        static_for<0, 4>([&](auto ni_c) {
+                            static_for<0, 16>([&](auto r_c) {
+                                constexpr int mi = decltype(mi_c)::value, ni = decltype(ni_c)::value,
+                                              r = decltype(r_c)::value;
+                                if (idx == mi * 64 + ni * 16 + r) {
+                                    before = acc[mi][ni][r];
+                                    after = flip_bit(before, fb);
+                                    acc[mi][ni][r] = after;
+                                }
+                            });
+                        });
+                    });
+                    log_fault(inj, fr, fc, fb, (double)before, (double)after);
+                }
+            }
+        } else if (inj.mode == 2) {
+            static_for<0, 4>([&](auto mi_c) {
+                static_for<0, 4>([&](auto ni_c) {
+                    static_for<0, 16>([&](auto r_c) {
+                        constexpr int mi = decltype(mi_c)::value, ni = decltype(ni_c)::value, r = decltype(r_c)::value;
+                        const int gi = row0 + rl_base + mi * 32;
+                        const int gj = col0 + cl_base + ni * 32 + 8 * (r >> 2) + (r & 3);
+                        if (gi < g.M && gj < g.N) {
+                            const int bit = bernoulli_bit(inj, gi, gj, g.N);
+                            if (bit >= 0) acc[mi][ni][r] = flip_and_log<float>(inj, acc[mi][ni][r], gi, gj, bit);
+                        }
+                    });
+                });
+            });
+        }
+    }
+
+    // ---- row sums of the accumulator tile (before quantisation) -----------------
+    if (VERIFY) {
+        float* red = reinterpret_cast<float*>(smem);  // [2][256]
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+            float s = 0.f;
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s += acc[mi][ni][r];
+            s += __shfl_xor(s, 32, WAVE);
+            if (lh == 0) red[wn * BM + wm * 128 + mi * 32 + l32] = s;
+        }
+        __syncthreads();
+        {
+            const int gi = row0 + tid;
+            if (gi < g.M)
+                reinterpret_cast<float*>(g.rowpart)[(int64_t)bn * g.M + gi] = red[tid] + red[BM + tid];
+        }
+    }
+
+    // ---- quantise and store C -------------------------------------------------
+    uint16_t* __restrict__ C = reinterpret_cast<uint16_t*>(g.C);
+    if (!EDGE) {
+        // Whole tiles: pass each 32 x 128 slab of the wavefront's tile through a private LDS
+        // buffer so that global stores are 16 bytes per lane and 256 contiguous bytes per row
+        // (a lane owns 4 consecutive columns of one row, which alone would give 8-byte pieces
+        // scattered over 32 rows).  Row pitch 264 B keeps the ds_write_b64 conflict free.
+        constexpr int PITCH = 264;
+        unsigned char* stage = smem + 4096 + (wm * 2 + wn) * (32 * PITCH);
+        const int srow = lane >> 4, schunk = lane & 15;
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint16_t h[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) h[e] = Elem<T>::from_acc(acc[mi][ni][4 * q + e]);
+                    uint2 v;
+                    v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                    v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+                    *reinterpret_cast<uint2*>(stage + l32 * PITCH + ni * 64 + q * 16 + lh * 8) = v;
+                }
+            // LDS operations of one wavefront complete in order; only the compiler must not
+            // move the reads above the writes (or the next slab's writes above these reads)
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int r = srow + 4 * t;
+                const raw16 v = *reinterpret_cast<const raw16*>(stage + r * PITCH + schunk * 16);
+                const int gi = row0 + wm * 128 + mi * 32 + r;
+                const int gj = col0 + wn * 128 + schunk * 8;
+                *reinterpret_cast<raw16*>(C + (int64_t)gi * g.ldc + gj) = v;
+            }
+            asm volatile("" ::: "memory");
+        }
+    } else {
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+            const int gi = row0 + rl_base + mi * 32;
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int gj = col0 + cl_base + ni * 32 + 8 * q;
+                    uint16_t h[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) h[e] = Elem<T>::from_acc(acc[mi][ni][4 * q + e]);
+                    if (gi < g.M) {
+                        if (g.c_vec_ok && gj + 4 <= g.N) {
+                            uint2 v;
+                            v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                            v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+                            *reinterpret_cast<uint2*>(C + (int64_t)gi * g.ldc + gj) = v;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (gj + e < g.N) C[(int64_t)gi * g.ldc + gj + e] = h[e];
+                        }
+                    }
+                }
+        }
+    }
+}
+
 // MODE 0: plain GEMM; 1: fused row-sum check; 2: check plus the fault injector.
 template <typename T, int TRANSB, int MODE, bool EDGE>
 __global__ __launch_bounds__(256) void gemm16_kernel(const GemmArgs g) {
@@ -163,118 +312,17 @@ __global__ __launch_bounds__(256) void gemm16_kernel(const GemmArgs g) {
         __syncthreads();
     }
 
-    // accumulator element (mi, ni, r) is C[row0 + rl(mi)][col0 + cl(ni, r)]
-    const int rl_base = wm * 128 + l32;
-    const int cl_base = wn * 128 + 4 * lh;
-
-    // ---- fault injector -----------------------------------------------------
-    if (INJECT) {
-        const InjectArgs& inj = g.inj;
-        if (inj.mode == 1) {
-            for (int e = 0; e < inj.n_list; ++e) {
-                const int fr = inj.d_list[3 * e], fc = inj.d_list[3 * e + 1], fb = inj.d_list[3 * e + 2];
-                if (fr < row0 || fr >= row0 + BM || fc < col0 || fc >= col0 + BN) continue;
-                if (fr >= g.M || fc >= g.N || fb < 0 || fb > 31) continue;
-                const int rl = fr - row0, cl = fc - col0;
-                const bool own = (rl >> 7) == wm && (cl >> 7) == wn && (rl & 31) == l32 && ((cl >> 2) & 1) == lh;
-                if (own) {
-                    const int idx = ((rl >> 5) & 3) * 64 + ((cl >> 5) & 3) * 16 + ((cl & 31) >> 3) * 4 + (cl & 3);
-                    float before = 0.f, after = 0.f;
-                    static_for<0, 4>([&](auto mi_c) {
-                        static_for<0, 4>([&](auto ni_c) {
-                            static_for<0, 16>([&](auto r_c) {
-                                constexpr int mi = decltype(mi_c)::value, ni = decltype(ni_c)::value,
-                                              r = decltype(r_c)::value;
-                                if (idx == mi * 64 + ni * 16 + r) {
-                                    before = acc[mi][ni][r];
-                                    after = flip_bit(before, fb);
-                                    acc[mi][ni][r] = after;
-                                }
-                            });
-                        });
-                    });
-                    log_fault(inj, fr, fc, fb, (double)before, (double)after);
-                }
-            }
-        } else if (inj.mode == 2) {
-            static_for<0, 4>([&](auto mi_c) {
-                static_for<0, 4>([&](auto ni_c) {
-                    static_for<0, 16>([&](auto r_c) {
-                        constexpr int mi = decltype(mi_c)::value, ni = decltype(ni_c)::value, r = decltype(r_c)::value;
-                        const int gi = row0 + rl_base + mi * 32;
-                        const int gj = col0 + cl_base + ni * 32 + 8 * (r >> 2) + (r & 3);
-                        if (gi < g.M && gj < g.N) {
-                            const int bit = bernoulli_bit(inj, gi, gj, g.N);
-                            if (bit >= 0) acc[mi][ni][r] = flip_and_log<float>(inj, acc[mi][ni][r], gi, gj, bit);
-                        }
-                    });
-                });
-            });
-        }
-    }
-
-    // ---- row sums of the accumulator tile (before quantisation) -----------------
-    if (VERIFY) {
-        float* red = reinterpret_cast<float*>(smem);  // [2][256]
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi) {
-            float s = 0.f;
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s += acc[mi][ni][r];
-            s += __shfl_xor(s, 32, WAVE);
-            if (lh == 0) red[wn * BM + wm * 128 + mi * 32 + l32] = s;
-        }
-        __syncthreads();
-        {
-            const int gi = row0 + tid;
-            if (gi < g.M)
-                reinterpret_cast<float*>(g.rowpart)[(int64_t)bn * g.M + gi] = red[tid] + red[BM + tid];
-        }
-    }
-
-    // ---- quantise and store C -------------------------------------------------
-    uint16_t* __restrict__ C = reinterpret_cast<uint16_t*>(g.C);
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
-        const int gi = row0 + rl_base + mi * 32;
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int gj = col0 + cl_base + ni * 32 + 8 * q;
-                uint16_t h[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) h[e] = Elem<T>::from_acc(acc[mi][ni][4 * q + e]);
-                if (!EDGE) {
-                    uint2 v;
-                    v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
-                    v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
-                    *reinterpret_cast<uint2*>(C + (int64_t)gi * g.ldc + gj) = v;
-                } else if (gi < g.M) {
-                    if (g.c_vec_ok && gj + 4 <= g.N) {
-                        uint2 v;
-                        v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
-                        v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
-                        *reinterpret_cast<uint2*>(C + (int64_t)gi * g.ldc + gj) = v;
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (gj + e < g.N) C[(int64_t)gi * g.ldc + gj + e] = h[e];
-                    }
-                }
-            }
-    }
+    gemm16_epilogue<T, MODE, EDGE>(g, acc, smem, row0, col0, bn, tid, lane, wm, wn, l32, lh);
 }
 
+// Launcher of the guarded (ragged-size) kernel.
 template <typename T>
-static int gemm16_launch(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st) {
+static int gemm16_edge_launch(const GemmArgs& a, int transB, int mode, hipStream_t st) {
     const dim3 grid(a.tiles_m * a.tiles_n), block(256);
     const size_t lds = g16::LDS_BYTES;
-#define VABFT_G16_CASE(TB, VF, ED)                                                                         \
-    if (transB == TB && mode == VF && edge == ED) {                                               \
-        auto kern = gemm16_kernel<T, TB, VF, ED>;                                                          \
+#define VABFT_G16_CASE(TB, VF)                                                                             \
+    if (transB == TB && mode == VF) {                                                                      \
+        auto kern = gemm16_kernel<T, TB, VF, true>;                                                        \
         static bool attr_set = false;                                                                      \
         if (!attr_set) {                                                                                   \
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
@@ -285,18 +333,12 @@ static int gemm16_launch(const GemmArgs& a, int transB, int mode, bool edge, hip
         kern<<<grid, block, lds, st>>>(a);                                                                 \
         return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;                                 \
     }
-    VABFT_G16_CASE(0, 0, false)
-    VABFT_G16_CASE(0, 0, true)
-    VABFT_G16_CASE(0, 1, false)
-    VABFT_G16_CASE(0, 1, true)
-    VABFT_G16_CASE(0, 2, false)
-    VABFT_G16_CASE(0, 2, true)
-    VABFT_G16_CASE(1, 0, false)
-    VABFT_G16_CASE(1, 0, true)
-    VABFT_G16_CASE(1, 1, false)
-    VABFT_G16_CASE(1, 1, true)
-    VABFT_G16_CASE(1, 2, false)
-    VABFT_G16_CASE(1, 2, true)
+    VABFT_G16_CASE(0, 0)
+    VABFT_G16_CASE(0, 1)
+    VABFT_G16_CASE(0, 2)
+    VABFT_G16_CASE(1, 0)
+    VABFT_G16_CASE(1, 1)
+    VABFT_G16_CASE(1, 2)
 #undef VABFT_G16_CASE
     return VABFT_EINVAL;
 }

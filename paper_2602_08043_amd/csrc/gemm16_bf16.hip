@@ -1,7 +1,9 @@
-// BF16 instantiation of the 16-bit verified GEMM.
-#include "gemm16.h"
+// BF16 instantiation of the 16-bit verified GEMM: whole-tile problems take the
+// direct-to-LDS pipelined kernel, everything else the guarded kernel.
+#include "gemm16_fast.h"
 namespace vabft {
 int gemm16_launch_bf16(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st) {
-    return gemm16_launch<bf16_t>(a, transB, mode, edge, st);
+    if (!edge) return gemm16_fast_launch<bf16_t>(a, transB, mode, st);
+    return gemm16_edge_launch<bf16_t>(a, transB, mode, st);
 }
 }  // namespace vabft

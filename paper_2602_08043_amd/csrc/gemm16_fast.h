@@ -1,0 +1,259 @@
+// BF16 / FP16 GEMM main loop for whole-tile problems (M % 256 == 0, N % 256 == 0,
+// K % 64 == 0, 16-byte aligned rows): global memory -> LDS without passing through
+// registers (global_load_lds_dwordx4), fragments software-pipelined one k-step ahead of the
+// MFMAs, one workgroup barrier per 64-wide k-tile, and the loads of the tile after next
+// spread between the MFMAs so that the texture path never backs up into the MFMA issue.
+//
+// LDS has 64 banks on gfx950 and serves 16 lanes of a ds_read_b128 per cycle, so 16
+// consecutive rows must land on 16 distinct 16-byte slots of a 256-byte window.
+// Layouts (per stage, 64 KiB, two stages):
+//   A tile, and B tile when B is stored N x K:  [256 rows][8 chunks of 16 B], chunk c of row r
+//       at position c ^ ((r >> 1) & 7); fragments by ds_read_b128.
+//   B tile when B is stored K x N:  [64 k][32 chunks of 16 B] (n contiguous), chunk c of row k
+//       at position c ^ (4 * (k & 3)); fragments by ds_read_b64_tr_b16, which hands lane i of a
+//       16-lane block the 4 k-consecutive values of column i of a 4(k) x 16(n) sub-tile.
+// The epilogue (injector, accumulator row sums, quantised store) is shared with gemm16.h.
+#pragma once
+#include "gemm16.h"
+
+namespace vabft {
+
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+
+namespace g16f {
+using namespace g16;
+typedef __attribute__((address_space(3))) unsigned char lds_u8;
+typedef const __attribute__((address_space(1))) unsigned char glb_u8;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+__device__ __forceinline__ raw16 lds_read16(const lds_u8* p) {
+    const u32x4_t v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4_t*>(p);
+    return __builtin_bit_cast(raw16, v);
+}
+
+// s_waitcnt lgkmcnt(0) only (vmcnt and expcnt fields left at their maxima)
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
+// Transposing 8-byte LDS read, issued as inline assembly: the compiler treats the intrinsic
+// form as possibly aliasing the asynchronous global -> LDS loads and would wait for ALL of
+// them (vmcnt(0)) in front of every such read.  The caller must wait for lgkmcnt before it
+// uses the result (LDS operations of a wavefront complete in order).
+template <int OFFSET> __device__ __forceinline__ uint64_t lds_read_tr16_b64(const lds_u8* p) {
+    static_assert(OFFSET >= 0 && OFFSET < 65536, "ds offset field is 16 bits");
+    uint64_t v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
+                 : "=v"(v)
+                 : "v"((uint32_t) reinterpret_cast<uintptr_t>(p)), "n"(OFFSET));
+    return v;
+}
+
+// 16 bytes per lane, global -> LDS at (wave-uniform) lds_base + lane * 16
+__device__ __forceinline__ void g2l16(const void* gptr, lds_u8* lds_base) {
+    __builtin_amdgcn_global_load_lds((glb_u8*)gptr, (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+}
+
+}  // namespace g16f
+
+template <typename T, int TRANSB, int MODE>
+__global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
+    using namespace g16f;
+    constexpr bool VERIFY = MODE >= 1;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    lds_u8* const lds = (lds_u8*)smem;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+    int bm, bn;
+    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
+    if (VERIFY && blockIdx.x == 0 && tid == 0) *g.d_nflag = 0;
+    const int row0 = bm * BM, col0 = bn * BN;
+    const unsigned char* __restrict__ A = reinterpret_cast<const unsigned char*>(g.A);
+    const unsigned char* __restrict__ B = reinterpret_cast<const unsigned char*>(g.B);
+
+    f32x16_t acc[4][4];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+    // ---- global -> LDS: each wavefront issues 8 + 8 loads of 1 KiB per k-tile -----------
+    // Addresses are a wave-uniform 64-bit base (scalar registers) plus a 32-bit lane offset.
+    // A (and N x K B): load i of a wavefront covers rows wave*64 + i*8 .. +7; lane l sits at row
+    // l/8, chunk position l%8, and fetches chunk (l%8) ^ ((row>>1)&7) with
+    // (row>>1)&7 = 4*(i&1) + l/16.  Two lane offsets (even / odd i) cover all loads.
+    const uint32_t rk_e = ((lane & 7) ^ (lane >> 4)) << 4, rk_o = ((lane & 7) ^ (lane >> 4) ^ 4) << 4;
+    const unsigned char* const a_base = A + (int64_t)(row0 + wave * 64) * g.lda * 2;
+    const uint32_t a_lane_e = (uint32_t)(lane >> 3) * (uint32_t)g.lda * 2 + rk_e;
+    const uint32_t a_lane_o = (uint32_t)(lane >> 3) * (uint32_t)g.lda * 2 + rk_o;
+    const int64_t a_step = 8 * g.lda * 2;
+    const unsigned char* b_base;
+    uint32_t b_lane_e, b_lane_o;
+    int64_t b_step;
+    if (TRANSB) {
+        b_base = B + (int64_t)(col0 + wave * 64) * g.ldb * 2;
+        b_lane_e = (uint32_t)(lane >> 3) * (uint32_t)g.ldb * 2 + rk_e;
+        b_lane_o = (uint32_t)(lane >> 3) * (uint32_t)g.ldb * 2 + rk_o;
+        b_step = 8 * g.ldb * 2;
+    } else {
+        // K x N B: load i covers k rows wave*16 + 2*i, +1; lane l sits at row l/32, chunk position
+        // l%32 and fetches chunk (l%32) ^ (4*(k&3)), k & 3 = (2*i + l/32) & 3.
+        b_base = B + ((int64_t)(wave * 16) * g.ldb + col0) * 2;
+        b_lane_e = (uint32_t)lh * (uint32_t)g.ldb * 2 + ((l32 ^ (4 * lh)) << 4);
+        b_lane_o = (uint32_t)lh * (uint32_t)g.ldb * 2 + ((l32 ^ (4 * (2 + lh))) << 4);
+        b_step = 2 * g.ldb * 2;
+    }
+    const int64_t b_ktile = TRANSB ? (int64_t)(BK * 2) : (int64_t)BK * g.ldb * 2;
+    lds_u8* const a_dst = lds + wave * (64 * 128);
+    lds_u8* const b_dst = lds + A_BYTES + (TRANSB ? wave * (64 * 128) : wave * (16 * 512));
+
+    // load `l` (0..7: A, 8..15: B) of the tile whose uniform bases are (ap, bp), into stage LS
+    auto issue_load = [&](auto ls_c, auto l_c, const unsigned char* ap, const unsigned char* bp) {
+        constexpr int LS = decltype(ls_c)::value, l = decltype(l_c)::value;
+        if constexpr (l < 8)
+            g2l16(ap + l * a_step + ((l & 1) ? a_lane_o : a_lane_e), a_dst + LS * STAGE + l * 1024);
+        else
+            g2l16(bp + (l - 8) * b_step + ((l & 1) ? b_lane_o : b_lane_e), b_dst + LS * STAGE + (l - 8) * 1024);
+    };
+
+    // ---- LDS -> fragments: loop-invariant lane addresses, everything else is an immediate ----
+    const int f_swz = (l32 >> 1) & 7;  // ((row >> 1) & 7) for row = 32*x + l32
+    lds_u8* a_rd[2][4];                // [stage][k-step]
+    lds_u8* b_rd[2][4];                // N x K B: [stage][k-step];  K x N B: [stage][ni]
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            a_rd[st][q] = lds + st * STAGE + (wm * 128 + l32) * 128 + (((q * 2 + lh) ^ f_swz) << 4);
+            if (TRANSB) {
+                b_rd[st][q] = lds + st * STAGE + A_BYTES + (wn * 128 + l32) * 128 + (((q * 2 + lh) ^ f_swz) << 4);
+            } else {
+                // 16-lane block b = lane/16 reads the 4(k) x 16(n) sub-tile at
+                //   k = 8*(b/2) + s/4 (+4 for the second half), n = 16*(b%2) + 4*(s%4), s = lane%16
+                const int t_s = lane & 15, t_b = lane >> 4;
+                const int t_k = 8 * (t_b >> 1) + (t_s >> 2);
+                const int t_n = wn * 128 + 16 * (t_b & 1) + 4 * (t_s & 3) + q * 32;
+                b_rd[st][q] = lds + st * STAGE + A_BYTES + t_k * 512 + (((t_n >> 3) ^ (4 * (t_k & 3))) << 4) +
+                              (t_n & 4) * 2;
+            }
+        }
+
+    // One fragment read operation `op` of k-step KS from stage S into (af, bf).  A k-step needs
+    // NRD operations: 4 ds_read_b128 for A, then 4 ds_read_b128 (N x K B) or 8 transposing
+    // 8-byte reads (K x N B: low halves first, then high halves).
+    constexpr int NRD = TRANSB ? 8 : 12;
+    auto frag_op = [&](auto s_c, auto ks_c, auto op_c, raw16 (&af)[4], raw16 (&bf)[4]) {
+        constexpr int S = decltype(s_c)::value, KS = decltype(ks_c)::value, op = decltype(op_c)::value;
+        if constexpr (op < 4) {
+            af[op] = lds_read16(a_rd[S][KS] + op * 4096);
+        } else if constexpr (TRANSB != 0) {
+            bf[op - 4] = lds_read16(b_rd[S][KS] + (op - 4) * 4096);
+        } else {
+            constexpr int ni = (op - 4) & 3, hi = (op - 4) >> 2;
+            const uint64_t v = lds_read_tr16_b64<(KS * 16 + 4 * hi) * 512>(b_rd[S][ni]);
+            bf[ni].w[2 * hi] = (uint32_t)v;
+            bf[ni].w[2 * hi + 1] = (uint32_t)(v >> 32);
+        }
+    };
+
+    // One k-step = 16 slots of one MFMA.  Slot i also issues fragment read i of the NEXT k-step
+    // (stage S, k-step KS, into the other register set) and, on odd slots when LBASE >= 0,
+    // global -> LDS load LBASE + i/2 of the next tile into stage S^1.  Everything a slot issues
+    // besides its MFMA must fit under that MFMA's 32 cycles; a scheduling barrier closes every
+    // slot so the compiler keeps the interleaving.
+    auto kstep = [&](auto s_c, auto ks_c, auto lbase_c, const raw16 (&af)[4], const raw16 (&bf)[4],
+                     raw16 (&naf)[4], raw16 (&nbf)[4], const unsigned char* ap, const unsigned char* bp) {
+        constexpr int S = decltype(s_c)::value, LBASE = decltype(lbase_c)::value;
+        if (!TRANSB) wait_lgkmcnt0();  // the assembly reads of (af, bf) issued during the previous k-step
+        static_for<0, 16>([&](auto slot_c) {
+            constexpr int slot = decltype(slot_c)::value;
+            constexpr int mi = slot >> 2, ni = slot & 3;
+            acc[mi][ni] = Mfma16<T>::run(bf[ni], af[mi], acc[mi][ni]);
+            __builtin_amdgcn_sched_barrier(0);  // MFMA first, the rest of the slot in its shadow
+            if constexpr (slot < NRD) frag_op(s_c, ks_c, slot_c, naf, nbf);
+            if constexpr (LBASE >= 0 && (slot & 1))
+                issue_load(std::integral_constant<int, S ^ 1>{}, std::integral_constant<int, LBASE + slot / 2>{}, ap,
+                           bp);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+    using I8 = std::integral_constant<int, 8>;
+    using IN = std::integral_constant<int, -1>;
+
+    const int nk = g.K / BK;
+    raw16 af0[4], bf0[4], af1[4], bf1[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) af1[i] = bf1[i] = raw16{{0u, 0u, 0u, 0u}};
+    static_for<0, 16>([&](auto l_c) { issue_load(I0{}, l_c, a_base, b_base); });
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    // One body per k-tile, running from barrier to barrier.  Global k-step j = 4*kt + ks
+    // multiplies register set j%2 and fetches the fragments of step j+1 into the other set.
+    // The barrier that publishes tile kt sits BEFORE the last k-step of tile kt-1, so that
+    // step's MFMAs cover the latency of the first fragment reads of tile kt (the very first
+    // pass multiplies zeros).  The 16 loads of tile kt+1 (clamped at the last tile; the reload
+    // is harmless) ride in the first two k-steps after the barrier; the stage they fill held
+    // tile kt-1, whose last reads completed before that barrier.  The body is instantiated for
+    // both stage parities so that every LDS offset is an instruction immediate.
+    auto tile_body = [&](auto s_c, int kt) {
+        const int ktn = kt + 1 < nk ? kt + 1 : nk - 1;
+        const unsigned char* ap = a_base + (int64_t)ktn * (BK * 2);
+        const unsigned char* bp = b_base + ktn * b_ktile;
+        kstep(s_c, I0{}, I0{}, af1, bf1, af0, bf0, ap, bp);  // step (kt-1, 3)
+        kstep(s_c, I1{}, I8{}, af0, bf0, af1, bf1, ap, bp);  // step (kt, 0)
+        kstep(s_c, I2{}, IN{}, af1, bf1, af0, bf0, ap, bp);  // step (kt, 1)
+        kstep(s_c, I3{}, IN{}, af0, bf0, af1, bf1, ap, bp);  // step (kt, 2)
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+    };
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        tile_body(I0{}, kt);
+        tile_body(I1{}, kt + 1);
+    }
+    if (kt < nk) tile_body(I0{}, kt);
+    // step (nk-1, 3)
+    if (!TRANSB) wait_lgkmcnt0();
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = Mfma16<T>::run(bf1[ni], af1[mi], acc[mi][ni]);
+
+    gemm16_epilogue<T, MODE, false>(g, acc, smem, row0, col0, bn, tid, lane, wm, wn, l32, lh);
+}
+
+template <typename T>
+static int gemm16_fast_launch(const GemmArgs& a, int transB, int mode, hipStream_t st) {
+    const dim3 grid(a.tiles_m * a.tiles_n), block(256);
+    const size_t lds = g16::LDS_BYTES;
+#define VABFT_G16F_CASE(TB, VF)                                                                            \
+    if (transB == TB && mode == VF) {                                                                      \
+        auto kern = gemm16_fast_kernel<T, TB, VF>;                                                         \
+        static bool attr_set = false;                                                                      \
+        if (!attr_set) {                                                                                   \
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)   \
+                return VABFT_EDEVICE;                                                                      \
+            attr_set = true;                                                                               \
+        }                                                                                                  \
+        kern<<<grid, block, lds, st>>>(a);                                                                 \
+        return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;                                 \
+    }
+    VABFT_G16F_CASE(0, 0)
+    VABFT_G16F_CASE(0, 1)
+    VABFT_G16F_CASE(0, 2)
+    VABFT_G16F_CASE(1, 0)
+    VABFT_G16F_CASE(1, 1)
+    VABFT_G16F_CASE(1, 2)
+#undef VABFT_G16F_CASE
+    return VABFT_EINVAL;
+}
+
+}  // namespace vabft

@@ -52,7 +52,4 @@ int gemm16_launch_f16(const GemmArgs& a, int transB, int mode, bool edge, hipStr
 int gemmw_launch_f32(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st);
 int gemmw_launch_f64(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st);
 
-void gemm16_tile(int* bm, int* bn);
-void gemmw_tile(int* bm, int* bn);
-
 }  // namespace vabft
