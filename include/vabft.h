@@ -25,7 +25,10 @@
  *   - Return value: a vabft_status.  Argument errors are detected on the host before
  *     anything is launched (null pointer, non-positive size, leading dimension
  *     smaller than the row length, unknown dtype, workspace too small).
- *   - Calls that share a workspace must be ordered on one stream.
+ *   - Calls that share a workspace must be ordered on one stream.  The first bytes of the
+ *     workspace hold arrival counters that must be zero when a call starts: zero-fill the
+ *     workspace once after allocating it (vabft_workspace_init, or any fill); every call
+ *     leaves the counters zero again.
  */
 #ifndef VABFT_H
 #define VABFT_H
@@ -88,6 +91,10 @@ const char* vabft_status_string(int status);
  * problem (0 is never returned for a valid problem; returns 0 for an invalid one). */
 size_t vabft_workspace_bytes(const vabft_problem* p);
 
+/* Zero-fill a freshly allocated workspace (a small fill kernel on `stream`; safe to capture
+ * in a HIP graph).  Needed once per allocation, before the first vabft_gemm_verified*. */
+int vabft_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream);
+
 /* Recommended e_max for a check made on accumulator values (section 3.6; table
  * "Recommended e_max across platforms", GPU rows): 5.0e-9*sqrt(n)+1.2e-7 for a float
  * accumulator, 1.0e-17*sqrt(n)+2.5e-16 for double, with n = max(K, N). */
@@ -134,6 +141,24 @@ int vabft_gemm_verified(const vabft_problem* p, const void* dA, const void* dB, 
                         const vabft_inject* inj, void* d_rowsum, void* d_E, int32_t* d_flags,
                         int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
                         void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* The same check with the A-side pass of Algorithm 1 folded into the GEMM launch: one call
+ * computes what vabft_threshold followed by vabft_gemm_verified(verify = 1) computes
+ * (Algorithm 1 for every row of A; section 2.2 C^{r1} = A (B r1); Eq. abft-check), reading A
+ * once.  Inputs d_Be / d_S come from vabft_encode; e_max, c_sigma as in vabft_threshold.
+ * Outputs: d_astat [3M], d_expected [M], d_T [M] (as vabft_threshold) and d_rowsum, d_E,
+ * d_flags, d_nflag, dC, injection log (as vabft_gemm_verified).  For BF16 / FP16 problems made
+ * of whole 256 x 256 x 128 tiles with 16-byte aligned rows the statistics ride on the operand
+ * fragments inside the GEMM kernel and the compare-and-flag step runs in the last workgroup of
+ * each row block (a single launch); other problems run the two passes back to back.  The
+ * summation order of the A-side sums differs between the two routes (both are fixed and
+ * bit-reproducible). */
+int vabft_gemm_verified_fused(const vabft_problem* p, const void* dA, const void* dB, void* dC,
+                              const void* d_Be, const double* d_S, double e_max, double c_sigma,
+                              void* d_astat, void* d_expected, void* d_T, const vabft_inject* inj,
+                              void* d_rowsum, void* d_E, int32_t* d_flags, int32_t* d_nflag,
+                              vabft_inject_rec* d_injlog, int32_t* d_ninj, void* d_workspace,
+                              size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -17,8 +17,8 @@ VABFT_OK, VABFT_EINVAL, VABFT_EUNSUPPORTED, VABFT_EWORKSPACE, VABFT_EDEVICE = ra
 VABFT_F64, VABFT_F32, VABFT_F16, VABFT_BF16 = range(4)
 DTYPE_CODE = {"f64": VABFT_F64, "f32": VABFT_F32, "f16": VABFT_F16, "bf16": VABFT_BF16}
 
-EXPORTS = ("vabft_status_string", "vabft_workspace_bytes", "vabft_default_emax", "vabft_encode",
-           "vabft_threshold", "vabft_gemm_verified")
+EXPORTS = ("vabft_status_string", "vabft_workspace_bytes", "vabft_workspace_init", "vabft_default_emax",
+           "vabft_encode", "vabft_threshold", "vabft_gemm_verified", "vabft_gemm_verified_fused")
 
 
 class Problem(Structure):
@@ -73,6 +73,13 @@ def load(path: str | None = None):
     lib.vabft_gemm_verified.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int32,
                                         POINTER(Inject), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                         c_void_p, c_size_t, c_void_p]
+    lib.vabft_workspace_init.restype = ctypes.c_int
+    lib.vabft_workspace_init.argtypes = [c_void_p, c_size_t, c_void_p]
+    lib.vabft_gemm_verified_fused.restype = ctypes.c_int
+    lib.vabft_gemm_verified_fused.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                              c_double, c_double, c_void_p, c_void_p, c_void_p, POINTER(Inject),
+                                              c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                              c_size_t, c_void_p]
     if path is None:
         _lib = lib
     return lib
@@ -121,3 +128,17 @@ def vabft_gemm_verified(p: Problem, dA, dB, dC, d_expected, d_T, verify, inj, d_
                                     byref(inj) if inj is not None else None, d_rowsum, d_E, d_flags, d_nflag,
                                     d_injlog, d_ninj, d_workspace, workspace_bytes, stream)
     return _check(rc, "vabft_gemm_verified", check)
+
+
+def vabft_workspace_init(d_workspace, workspace_bytes, stream=None, check=True) -> int:
+    rc = load().vabft_workspace_init(d_workspace, workspace_bytes, stream)
+    return _check(rc, "vabft_workspace_init", check)
+
+
+def vabft_gemm_verified_fused(p: Problem, dA, dB, dC, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T, inj,
+                              d_rowsum, d_E, d_flags, d_nflag, d_injlog, d_ninj, d_workspace, workspace_bytes,
+                              stream=None, check=True) -> int:
+    rc = load().vabft_gemm_verified_fused(byref(p), dA, dB, dC, d_Be, d_S, float(e_max), float(c_sigma), d_astat,
+                                          d_expected, d_T, byref(inj) if inj is not None else None, d_rowsum, d_E,
+                                          d_flags, d_nflag, d_injlog, d_ninj, d_workspace, workspace_bytes, stream)
+    return _check(rc, "vabft_gemm_verified_fused", check)

@@ -12,7 +12,8 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libvabft.so")
 
-SOURCES = ["api.hip", "encode.hip", "gemm16_bf16.hip", "gemm16_f16.hip", "gemm_f32.hip", "gemm_f64.hip"]
+SOURCES = ["gemm16_bf16_nn.hip", "gemm16_bf16_nt.hip", "gemm16_f16_nn.hip", "gemm16_f16_nt.hip", "api.hip",
+           "encode.hip", "gemm_f32.hip", "gemm_f64.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
@@ -29,7 +30,7 @@ def _run(cmd):
     return out
 
 
-def build_library(verbose: bool = True, jobs: int = 6) -> str:
+def build_library(verbose: bool = True, jobs: int = 8) -> str:
     os.makedirs(OBJ, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES]

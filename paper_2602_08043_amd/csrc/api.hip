@@ -57,16 +57,40 @@ static void tile_shape(int dtype, int* bm, int* bn) {
     }
 }
 
+// Workspace layout: [tickets: 2*tiles_m + 1 int32, rounded to 256 B][scratch].
+// The scratch area holds, for the GEMM, rowpart[tiles_n][M] acc followed (16-bit types) by
+// apart[tiles_n][4][M] acc, and for the encode of an N x K B its column partials; the two
+// calls are ordered on one stream, so they share it.  The tickets must be zero between
+// launches: the kernels leave them zero, vabft_workspace_init zeroes them the first time.
+static size_t tickets_bytes(const vabft_problem* p) {
+    int bm, bn;
+    tile_shape(p->dtype, &bm, &bn);
+    const size_t tiles_m = ((size_t)p->M + bm - 1) / bm;
+    return round_up((2 * tiles_m + 1) * sizeof(int32_t), 256);
+}
+
 size_t gemm_workspace_bytes(const vabft_problem* p) {
     int bm, bn;
     tile_shape(p->dtype, &bm, &bn);
     const size_t tiles_n = ((size_t)p->N + bn - 1) / bn;
-    return tiles_n * (size_t)p->M * acc_bytes(p->dtype);
+    const bool is16 = p->dtype == VABFT_F16 || p->dtype == VABFT_BF16;
+    return tiles_n * (size_t)p->M * acc_bytes(p->dtype) * (is16 ? 5 : 1);
 }
 
-int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* dC, const void* d_expected,
-                  const void* d_T, int verify, const vabft_inject* inj, void* d_rowsum, void* d_E, int32_t* d_flags,
-                  int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj, void* ws, hipStream_t st) {
+__global__ void fill_zero_kernel(uint32_t* p, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+void workspace_init_launch(void* ws, size_t bytes, hipStream_t st) {
+    const size_t n = bytes / 4;
+    const int blocks = (int)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+    fill_zero_kernel<<<blocks > 0 ? blocks : 1, 256, 0, st>>>(reinterpret_cast<uint32_t*>(ws), n);
+}
+
+int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* dC, void* d_expected, void* d_T,
+                  int verify, const FusedArgs* fused, const vabft_inject* inj, void* d_rowsum, void* d_E,
+                  int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj, void* ws,
+                  hipStream_t st) {
     GemmArgs a;
     a.A = dA;
     a.B = dB;
@@ -81,12 +105,27 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     tile_shape(p->dtype, &bm, &bn);
     a.tiles_m = (p->M + bm - 1) / bm;
     a.tiles_n = (p->N + bn - 1) / bn;
-    const size_t eb = elem_bytes(p->dtype);
+    const size_t eb = elem_bytes(p->dtype), ab = acc_bytes(p->dtype);
+    const bool is16 = p->dtype == VABFT_F16 || p->dtype == VABFT_BF16;
     a.a_vec_ok = aligned_to(dA, 16) && (p->lda * eb) % 16 == 0;
     a.b_vec_ok = aligned_to(dB, 16) && (p->ldb * eb) % 16 == 0;
     a.c_vec_ok = aligned_to(dC, 16) && (p->ldc * eb) % 16 == 0;
-    a.rowpart = ws;
+    unsigned char* wsb = reinterpret_cast<unsigned char*>(ws);
+    a.tickets = reinterpret_cast<int32_t*>(wsb);
+    a.rowpart = ws ? wsb + tickets_bytes(p) : nullptr;
+    a.apart = ws ? wsb + tickets_bytes(p) + (size_t)a.tiles_n * p->M * ab : nullptr;
     a.d_nflag = d_nflag;
+    a.expected = d_expected;
+    a.T = d_T;
+    a.rowsum = d_rowsum;
+    a.E = d_E;
+    a.flags = d_flags;
+    a.fused_stats = 0;
+    a.Be = nullptr;
+    a.S = nullptr;
+    a.e_max = 0;
+    a.c_sigma = 0;
+    a.astat = nullptr;
     a.inj.mode = 0;
     a.inj.bit_lo = 0;
     a.inj.bit_span = 1;
@@ -109,27 +148,47 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
         zero_int_kernel<<<1, 1, 0, st>>>(d_ninj);
     }
     // the unguarded kernels need whole tiles and 16-byte aligned rows
-    const int bk = (p->dtype == VABFT_F16 || p->dtype == VABFT_BF16) ? 64 : 16;
+    const int bk = is16 ? 64 : 16;
     const bool edge = (p->M % bm) || (p->N % bn) || (p->K % bk) || !a.a_vec_ok || !a.b_vec_ok || !a.c_vec_ok;
+    // whole-tile 16-bit kernels do the compare-and-flag step (and, if asked, the A-side pass) in-kernel
+    const bool in_kernel_finalize = is16 && !edge;
+    if (fused) {
+        if (in_kernel_finalize && a.tiles_n >= 2 && p->K % 128 == 0 && aligned_to(fused->d_Be, 16)) {
+            a.fused_stats = 1;
+            a.Be = fused->d_Be;
+            a.S = fused->d_S;
+            a.e_max = fused->e_max;
+            a.c_sigma = fused->c_sigma;
+            a.astat = fused->d_astat;
+        } else {
+            const int rc = threshold_dispatch(p, dA, fused->d_Be, fused->d_S, fused->e_max, fused->c_sigma,
+                                              fused->d_astat, d_expected, d_T, st);
+            if (rc != VABFT_OK) return rc;
+        }
+    }
     int rc;
     const int mode = !verify ? 0 : (a.inj.mode != 0 ? 2 : 1);
     switch (p->dtype) {
-        case VABFT_BF16: rc = gemm16_launch_bf16(a, p->transB, mode, edge, st); break;
-        case VABFT_F16: rc = gemm16_launch_f16(a, p->transB, mode, edge, st); break;
+        case VABFT_BF16:
+            rc = p->transB ? gemm16_launch_bf16_nt(a, mode, edge, st) : gemm16_launch_bf16_nn(a, mode, edge, st);
+            break;
+        case VABFT_F16:
+            rc = p->transB ? gemm16_launch_f16_nt(a, mode, edge, st) : gemm16_launch_f16_nn(a, mode, edge, st);
+            break;
         case VABFT_F32: rc = gemmw_launch_f32(a, p->transB, mode, edge, st); break;
         case VABFT_F64: rc = gemmw_launch_f64(a, p->transB, mode, edge, st); break;
         default: return VABFT_EINVAL;
     }
-    if (rc != VABFT_OK || !verify) return rc;
+    if (rc != VABFT_OK || !verify || in_kernel_finalize) return rc;
     const dim3 grid((p->M + 255) / 256), block(256);
     if (p->dtype == VABFT_F64)
-        finalize_kernel<double><<<grid, block, 0, st>>>((const double*)ws, a.tiles_n, p->M, (const double*)d_expected,
-                                                        (const double*)d_T, (double*)d_rowsum, (double*)d_E, d_flags,
-                                                        d_nflag);
+        finalize_kernel<double><<<grid, block, 0, st>>>((const double*)a.rowpart, a.tiles_n, p->M,
+                                                        (const double*)d_expected, (const double*)d_T,
+                                                        (double*)d_rowsum, (double*)d_E, d_flags, d_nflag);
     else
-        finalize_kernel<float><<<grid, block, 0, st>>>((const float*)ws, a.tiles_n, p->M, (const float*)d_expected,
-                                                       (const float*)d_T, (float*)d_rowsum, (float*)d_E, d_flags,
-                                                       d_nflag);
+        finalize_kernel<float><<<grid, block, 0, st>>>((const float*)a.rowpart, a.tiles_n, p->M,
+                                                       (const float*)d_expected, (const float*)d_T, (float*)d_rowsum,
+                                                       (float*)d_E, d_flags, d_nflag);
     return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
 }
 
@@ -153,7 +212,13 @@ const char* vabft_status_string(int status) {
 size_t vabft_workspace_bytes(const vabft_problem* p) {
     if (!problem_ok(p)) return 0;
     const size_t a = encode_workspace_bytes(p), b = gemm_workspace_bytes(p);
-    return round_up((a > b ? a : b) + 256, 256);
+    return tickets_bytes(p) + round_up((a > b ? a : b) + 256, 256);
+}
+
+int vabft_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream) {
+    if (!d_workspace || workspace_bytes < 4 || !aligned_to(d_workspace, 16)) return VABFT_EWORKSPACE;
+    workspace_init_launch(d_workspace, workspace_bytes, (hipStream_t)stream);
+    return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
 }
 
 double vabft_default_emax(int32_t dtype, int32_t K, int32_t N) {
@@ -169,8 +234,10 @@ int vabft_encode(const vabft_problem* p, const void* dB, void* d_Be, void* d_bst
         !aligned_to(d_bstat, acc_bytes(p->dtype)) || !aligned_to(d_S, 8))
         return VABFT_EINVAL;
     const size_t need = encode_workspace_bytes(p);
-    if (need && (!d_workspace || workspace_bytes < need || !aligned_to(d_workspace, 16))) return VABFT_EWORKSPACE;
-    return encode_dispatch(p, dB, d_Be, d_bstat, d_S, d_workspace, (hipStream_t)stream);
+    if (need && (!d_workspace || workspace_bytes < tickets_bytes(p) + need || !aligned_to(d_workspace, 16)))
+        return VABFT_EWORKSPACE;
+    void* scratch = d_workspace ? reinterpret_cast<unsigned char*>(d_workspace) + tickets_bytes(p) : nullptr;
+    return encode_dispatch(p, dB, d_Be, d_bstat, d_S, scratch, (hipStream_t)stream);
 }
 
 int vabft_threshold(const vabft_problem* p, const void* dA, const void* d_Be, const double* d_S, double e_max,
@@ -184,10 +251,10 @@ int vabft_threshold(const vabft_problem* p, const void* dA, const void* d_Be, co
     return threshold_dispatch(p, dA, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T, (hipStream_t)stream);
 }
 
-int vabft_gemm_verified(const vabft_problem* p, const void* dA, const void* dB, void* dC, const void* d_expected,
-                        const void* d_T, int32_t verify, const vabft_inject* inj, void* d_rowsum, void* d_E,
-                        int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
-                        void* d_workspace, size_t workspace_bytes, void* stream) {
+static int check_gemm_args(const vabft_problem* p, const void* dA, const void* dB, void* dC, int verify,
+                           const vabft_inject* inj, const void* d_expected, const void* d_T, void* d_rowsum,
+                           void* d_E, int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
+                           void* d_workspace, size_t workspace_bytes) {
     if (!problem_ok(p) || !dA || !dB || !dC) return VABFT_EINVAL;
     if (verify != 0 && verify != 1) return VABFT_EINVAL;
     const size_t eb = elem_bytes(p->dtype), ab = acc_bytes(p->dtype);
@@ -198,7 +265,7 @@ int vabft_gemm_verified(const vabft_problem* p, const void* dA, const void* dB, 
         if (!aligned_to(d_expected, ab) || !aligned_to(d_T, ab) || !aligned_to(d_rowsum, ab) || !aligned_to(d_E, ab) ||
             !aligned_to(d_flags, 4) || !aligned_to(d_nflag, 4))
             return VABFT_EINVAL;
-        const size_t need = gemm_workspace_bytes(p);
+        const size_t need = tickets_bytes(p) + gemm_workspace_bytes(p);
         if (!d_workspace || workspace_bytes < need || !aligned_to(d_workspace, 16)) return VABFT_EWORKSPACE;
     } else if (inj_on) {
         return VABFT_EINVAL;  // the injector lives in the verified kernel
@@ -213,8 +280,40 @@ int vabft_gemm_verified(const vabft_problem* p, const void* dA, const void* dB, 
             if (inj->bit_lo < 0 || inj->bit_hi < inj->bit_lo || inj->bit_hi >= bits) return VABFT_EINVAL;
         }
     }
-    return gemm_dispatch(p, dA, dB, dC, d_expected, d_T, verify, inj, d_rowsum, d_E, d_flags, d_nflag, d_injlog,
-                         d_ninj, d_workspace, (hipStream_t)stream);
+    return VABFT_OK;
+}
+
+int vabft_gemm_verified(const vabft_problem* p, const void* dA, const void* dB, void* dC, const void* d_expected,
+                        const void* d_T, int32_t verify, const vabft_inject* inj, void* d_rowsum, void* d_E,
+                        int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
+                        void* d_workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_gemm_args(p, dA, dB, dC, verify, inj, d_expected, d_T, d_rowsum, d_E, d_flags, d_nflag,
+                                   d_injlog, d_ninj, d_workspace, workspace_bytes);
+    if (rc != VABFT_OK) return rc;
+    return gemm_dispatch(p, dA, dB, dC, const_cast<void*>(d_expected), const_cast<void*>(d_T), verify, nullptr, inj,
+                         d_rowsum, d_E, d_flags, d_nflag, d_injlog, d_ninj, d_workspace, (hipStream_t)stream);
+}
+
+int vabft_gemm_verified_fused(const vabft_problem* p, const void* dA, const void* dB, void* dC, const void* d_Be,
+                              const double* d_S, double e_max, double c_sigma, void* d_astat, void* d_expected,
+                              void* d_T, const vabft_inject* inj, void* d_rowsum, void* d_E, int32_t* d_flags,
+                              int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj, void* d_workspace,
+                              size_t workspace_bytes, void* stream) {
+    const int rc = check_gemm_args(p, dA, dB, dC, 1, inj, d_expected, d_T, d_rowsum, d_E, d_flags, d_nflag, d_injlog,
+                                   d_ninj, d_workspace, workspace_bytes);
+    if (rc != VABFT_OK) return rc;
+    if (!d_Be || !d_S || !d_astat) return VABFT_EINVAL;
+    if (!(e_max > 0.0) || !(c_sigma >= 0.0) || !isfinite(e_max) || !isfinite(c_sigma)) return VABFT_EINVAL;
+    const size_t ab = acc_bytes(p->dtype);
+    if (!aligned_to(d_Be, ab) || !aligned_to(d_S, 8) || !aligned_to(d_astat, ab)) return VABFT_EINVAL;
+    FusedArgs f;
+    f.d_Be = d_Be;
+    f.d_S = d_S;
+    f.e_max = e_max;
+    f.c_sigma = c_sigma;
+    f.d_astat = d_astat;
+    return gemm_dispatch(p, dA, dB, dC, d_expected, d_T, 1, &f, inj, d_rowsum, d_E, d_flags, d_nflag, d_injlog, d_ninj,
+                         d_workspace, (hipStream_t)stream);
 }
 
 }  // extern "C"

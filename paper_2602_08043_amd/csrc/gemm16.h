@@ -39,23 +39,17 @@ __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 __device__ __forceinline__ int lds_pos(int row, int chunk) { return row * 128 + ((chunk ^ swz(row)) << 4); }
 }  // namespace g16
 
-// Epilogue shared by the 16-bit GEMM kernels: optional fault injection on the accumulator
-// registers, row sums of the accumulator tile before quantisation, quantised store of C.
-// Accumulator element (mi, ni, r) of a wavefront is
+// Pieces of the epilogue of the 16-bit GEMM kernels.  Accumulator element (mi, ni, r) of a
+// wavefront is
 //   C[row0 + wm*128 + mi*32 + lane%32][col0 + wn*128 + ni*32 + 8*(r/4) + 4*(lane/32) + r%4].
-// `smem` must be free for reuse (all wavefronts past their last LDS read).
-template <typename T, int MODE, bool EDGE>
-__device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x16_t (&acc)[4][4], unsigned char* smem,
-                                                int row0, int col0, int bn, int tid, int lane, int wm, int wn,
-                                                int l32, int lh) {
+
+// Fault injector on the accumulator registers (paper section 5.1 "Error injection").
+template <bool INJECT>
+__device__ __forceinline__ void gemm16_inject(const GemmArgs& g, f32x16_t (&acc)[4][4], int row0, int col0, int wm,
+                                              int wn, int l32, int lh) {
     using namespace g16;
-    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2;
-    (void)lane;
-    // accumulator element (mi, ni, r) is C[row0 + rl(mi)][col0 + cl(ni, r)]
     const int rl_base = wm * 128 + l32;
     const int cl_base = wn * 128 + 4 * lh;
-
-    // ---- fault injector -----------------------------------------------------
     if (INJECT) {
         const InjectArgs& inj = g.inj;
         if (inj.mode == 1) {
@@ -101,28 +95,34 @@ __device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x16_t (&ac
         }
     }
 
-    // ---- row sums of the accumulator tile (before quantisation) -----------------
-    if (VERIFY) {
-        float* red = reinterpret_cast<float*>(smem);  // [2][256]
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi) {
-            float s = 0.f;
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s += acc[mi][ni][r];
-            s += __shfl_xor(s, 32, WAVE);
-            if (lh == 0) red[wn * BM + wm * 128 + mi * 32 + l32] = s;
-        }
-        __syncthreads();
-        {
-            const int gi = row0 + tid;
-            if (gi < g.M)
-                reinterpret_cast<float*>(g.rowpart)[(int64_t)bn * g.M + gi] = red[tid] + red[BM + tid];
-        }
-    }
+}
 
-    // ---- quantise and store C -------------------------------------------------
+// Row sums of the wavefront's accumulator tile, taken before quantisation (section 2.2
+// C^{r1'} = C r1 on the tile; section 3.6 fused check): 64 in-register adds per row plus one
+// cross-lane add.  Lanes 0..31 leave the sum of row (wm*128 + mi*32 + lane) over the
+// wavefront's 128 columns in red[wn][row].
+__device__ __forceinline__ void gemm16_rowsum_to_lds(const f32x16_t (&acc)[4][4], float* red, int wm, int wn, int l32,
+                                                     int lh) {
+    using namespace g16;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+        float s = 0.f;
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s += acc[mi][ni][r];
+        s += __shfl_xor(s, 32, WAVE);
+        if (lh == 0) red[wn * BM + wm * 128 + mi * 32 + l32] = s;
+    }
+}
+
+// Quantise and store the wavefront's tile of C.
+template <typename T, bool EDGE>
+__device__ __forceinline__ void gemm16_store_c(const GemmArgs& g, const f32x16_t (&acc)[4][4], unsigned char* smem,
+                                               int row0, int col0, int lane, int wm, int wn, int l32, int lh) {
+    using namespace g16;
+    const int rl_base = wm * 128 + l32;
+    const int cl_base = wn * 128 + 4 * lh;
     uint16_t* __restrict__ C = reinterpret_cast<uint16_t*>(g.C);
     if (!EDGE) {
         // Whole tiles: pass each 32 x 128 slab of the wavefront's tile through a private LDS
@@ -186,6 +186,25 @@ __device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x16_t (&ac
                 }
         }
     }
+}
+
+// Epilogue of the guarded kernel: injector, row sums -> rowpart[bn][row], store.
+// `smem` must be free for reuse (all wavefronts past their last LDS read).
+template <typename T, int MODE, bool EDGE>
+__device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x16_t (&acc)[4][4], unsigned char* smem,
+                                                int row0, int col0, int bn, int tid, int lane, int wm, int wn,
+                                                int l32, int lh) {
+    using namespace g16;
+    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2;
+    gemm16_inject<INJECT>(g, acc, row0, col0, wm, wn, l32, lh);
+    if (VERIFY) {
+        float* red = reinterpret_cast<float*>(smem);  // [2][256]
+        gemm16_rowsum_to_lds(acc, red, wm, wn, l32, lh);
+        __syncthreads();
+        const int gi = row0 + tid;
+        if (gi < g.M) reinterpret_cast<float*>(g.rowpart)[(int64_t)bn * g.M + gi] = red[tid] + red[BM + tid];
+    }
+    gemm16_store_c<T, EDGE>(g, acc, smem, row0, col0, lane, wm, wn, l32, lh);
 }
 
 // MODE 0: plain GEMM; 1: fused row-sum check; 2: check plus the fault injector.
@@ -316,13 +335,13 @@ __global__ __launch_bounds__(256) void gemm16_kernel(const GemmArgs g) {
 }
 
 // Launcher of the guarded (ragged-size) kernel.
-template <typename T>
-static int gemm16_edge_launch(const GemmArgs& a, int transB, int mode, hipStream_t st) {
+template <typename T, int TRANSB>
+static int gemm16_edge_launch_tb(const GemmArgs& a, int mode, hipStream_t st) {
     const dim3 grid(a.tiles_m * a.tiles_n), block(256);
     const size_t lds = g16::LDS_BYTES;
-#define VABFT_G16_CASE(TB, VF)                                                                             \
-    if (transB == TB && mode == VF) {                                                                      \
-        auto kern = gemm16_kernel<T, TB, VF, true>;                                                        \
+#define VABFT_G16_CASE(VF)                                                                                 \
+    if (mode == VF) {                                                                                      \
+        auto kern = gemm16_kernel<T, TRANSB, VF, true>;                                                    \
         static bool attr_set = false;                                                                      \
         if (!attr_set) {                                                                                   \
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
@@ -333,12 +352,9 @@ static int gemm16_edge_launch(const GemmArgs& a, int transB, int mode, hipStream
         kern<<<grid, block, lds, st>>>(a);                                                                 \
         return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;                                 \
     }
-    VABFT_G16_CASE(0, 0)
-    VABFT_G16_CASE(0, 1)
-    VABFT_G16_CASE(0, 2)
-    VABFT_G16_CASE(1, 0)
-    VABFT_G16_CASE(1, 1)
-    VABFT_G16_CASE(1, 2)
+    VABFT_G16_CASE(0)
+    VABFT_G16_CASE(1)
+    VABFT_G16_CASE(2)
 #undef VABFT_G16_CASE
     return VABFT_EINVAL;
 }

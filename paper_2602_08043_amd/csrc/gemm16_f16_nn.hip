@@ -1,0 +1,9 @@
+// F16 verified GEMM, B stored K x N: whole-tile problems take the direct-to-LDS
+// pipelined kernel, everything else the guarded kernel.
+#include "gemm16_fast.h"
+namespace vabft {
+int gemm16_launch_f16_nn(const GemmArgs& a, int mode, bool edge, hipStream_t st) {
+    if (!edge) return gemm16_fast_launch_tb<f16_t, 0>(a, mode, st);
+    return gemm16_edge_launch_tb<f16_t, 0>(a, mode, st);
+}
+}  // namespace vabft

@@ -12,7 +12,14 @@
 //   B tile when B is stored K x N:  [64 k][32 chunks of 16 B] (n contiguous), chunk c of row k
 //       at position c ^ (4 * (k & 3)); fragments by ds_read_b64_tr_b16, which hands lane i of a
 //       16-lane block the 4 k-consecutive values of column i of a 4(k) x 16(n) sub-tile.
-// The epilogue (injector, accumulator row sums, quantised store) is shared with gemm16.h.
+// Check-side work fused into this kernel (MODE >= 1):
+//   * row sums of the accumulator tile before quantisation (section 3.6 fused check);
+//   * optionally (FUSED) the A-side of Algorithm 1: every A fragment passes through registers
+//     on its way to the MFMA, so tile-column bn accumulates sum / max / min / dot-with-Be of
+//     the k-steps whose body index is congruent to bn modulo the number of tile-columns;
+//   * the compare-and-flag step: the last workgroup to finish a tile-row (an arrival ticket per
+//     tile-row) combines that row block's partials in a fixed order, evaluates the threshold
+//     in double precision, and writes rowsum, E, flags; the last row block writes nflag.
 #pragma once
 #include "gemm16.h"
 
@@ -52,12 +59,30 @@ __device__ __forceinline__ void g2l16(const void* gptr, lds_u8* lds_base) {
     __builtin_amdgcn_global_load_lds((glb_u8*)gptr, (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
 }
 
+__device__ __forceinline__ float ld_agent(const float* p) {
+    return __builtin_bit_cast(float, __hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT));
+}
+
+// element e (0..3) of the two selected dwords of a 16-byte fragment, as float
+template <typename T> __device__ __forceinline__ float frag_elem(uint32_t d0, uint32_t d1, int e);
+template <> __device__ __forceinline__ float frag_elem<bf16_t>(uint32_t d0, uint32_t d1, int e) {
+    const uint32_t d = e < 2 ? d0 : d1;
+    return __uint_as_float((e & 1) ? (d & 0xffff0000u) : (d << 16));
+}
+template <> __device__ __forceinline__ float frag_elem<f16_t>(uint32_t d0, uint32_t d1, int e) {
+    const uint32_t d = e < 2 ? d0 : d1;
+    return Elem<f16_t>::to_acc((uint16_t)((e & 1) ? (d >> 16) : (d & 0xffffu)));
+}
+
+constexpr int SRED_OFFSET = 40960;  // LDS offset of the A-statistics staging area in the epilogue
 }  // namespace g16f
 
-template <typename T, int TRANSB, int MODE>
+template <typename T, int TRANSB, int MODE, bool FUSED>
 __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     using namespace g16f;
-    constexpr bool VERIFY = MODE >= 1;
+    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2;
+    static_assert(!FUSED || VERIFY, "fused statistics belong to the verified kernel");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     lds_u8* const lds = (lds_u8*)smem;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -66,7 +91,6 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     const int l32 = lane & 31, lh = lane >> 5;
     int bm, bn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
-    if (VERIFY && blockIdx.x == 0 && tid == 0) *g.d_nflag = 0;
     const int row0 = bm * BM, col0 = bn * BN;
     const unsigned char* __restrict__ A = reinterpret_cast<const unsigned char*>(g.A);
     const unsigned char* __restrict__ B = reinterpret_cast<const unsigned char*>(g.B);
@@ -158,14 +182,69 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         }
     };
 
+    // ---- fused A-side statistics (FUSED) ------------------------------------------------
+    // Both wavefronts of a wm pair hold the same A fragments; wavefront wn takes elements
+    // 4*wn .. 4*wn+3 of each 8-element fragment, so a lane accumulates, per mi, over
+    // k = kbase + 8*(lane/32) + 4*wn + 0..3 of row wm*128 + mi*32 + lane%32.
+    // st[mi] = (sum, dot with Be, max, min); bev[q] = the four Be values of k-step q of the body.
+    float st[4][4];
+    f32x4_t bev[2][4];  // [tile of the unit][k-step of the body]
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+        st[mi][0] = 0.f;
+        st[mi][1] = 0.f;
+        st[mi][2] = -3.402823466e+38f;
+        st[mi][3] = 3.402823466e+38f;
+    }
+    const float* const Be = reinterpret_cast<const float*>(g.Be);
+    // Be values of the two bodies of unit u (tiles 2u, 2u+1): k-step 0 of body kb multiplies
+    // step (kb-1, 3), k-steps 1..3 multiply steps (kb, 0..2)
+    auto prefetch_be = [&](int u) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int kb = 2 * u + t;
+                int k = (q == 0 ? kb * BK - 16 : kb * BK + (q - 1) * 16) + 8 * lh + 4 * wn;
+                k = k < 0 ? 0 : (k > g.K - 4 ? g.K - 4 : k);  // clamped values are never used
+                bev[t][q] = *reinterpret_cast<const f32x4_t*>(Be + k);
+            }
+    };
+    uint32_t sd0 = 0, sd1 = 0;  // the two dwords of the current fragment that this wavefront folds
+    // `skip` (wave-uniform) keeps the all-zero fragments of the very first pass out of max / min
+    auto stats_elem = [&](const raw16 (&af)[4], auto t_c, auto q_c, auto slot_c, bool skip) {
+        constexpr int t = decltype(t_c)::value, q = decltype(q_c)::value, slot = decltype(slot_c)::value;
+        constexpr int mi = slot >> 2, e = slot & 3;
+        if constexpr (e == 0) {
+            // select by value (a conditional between the two array elements themselves would
+            // become a pointer select and push the fragment arrays out of registers)
+            const uint32_t lo0 = af[mi].w[0], lo1 = af[mi].w[1], hi0 = af[mi].w[2], hi1 = af[mi].w[3];
+            sd0 = wn ? hi0 : lo0;
+            sd1 = wn ? hi1 : lo1;
+        }
+        const float x = frag_elem<T>(sd0, sd1, e);
+        st[mi][0] += x;
+        st[mi][1] = fmaf(x, bev[t][q][e], st[mi][1]);
+        if constexpr (q == 0 && t == 0) {
+            st[mi][2] = fmaxf(st[mi][2], skip ? -3.402823466e+38f : x);
+            st[mi][3] = fminf(st[mi][3], skip ? 3.402823466e+38f : x);
+        } else {
+            st[mi][2] = fmaxf(st[mi][2], x);
+            st[mi][3] = fminf(st[mi][3], x);
+        }
+    };
+
     // One k-step = 16 slots of one MFMA.  Slot i also issues fragment read i of the NEXT k-step
     // (stage S, k-step KS, into the other register set) and, on odd slots when LBASE >= 0,
-    // global -> LDS load LBASE + i/2 of the next tile into stage S^1.  Everything a slot issues
-    // besides its MFMA must fit under that MFMA's 32 cycles; a scheduling barrier closes every
-    // slot so the compiler keeps the interleaving.
-    auto kstep = [&](auto s_c, auto ks_c, auto lbase_c, const raw16 (&af)[4], const raw16 (&bf)[4],
-                     raw16 (&naf)[4], raw16 (&nbf)[4], const unsigned char* ap, const unsigned char* bp) {
+    // global -> LDS load LBASE + i/2 of the next tile into stage S^1; with STATS it also folds one
+    // element per mi-slot of the fragments being multiplied into the A statistics.  Everything a
+    // slot issues besides its MFMA should fit under that MFMA's 32 cycles; a scheduling barrier
+    // closes every slot so the compiler keeps the interleaving.
+    auto kstep = [&](auto s_c, auto ks_c, auto lbase_c, auto stats_c, auto q_c, const raw16 (&af)[4],
+                     const raw16 (&bf)[4], raw16 (&naf)[4], raw16 (&nbf)[4], const unsigned char* ap,
+                     const unsigned char* bp, bool skip) {
         constexpr int S = decltype(s_c)::value, LBASE = decltype(lbase_c)::value;
+        constexpr bool STATS = decltype(stats_c)::value != 0;
         if (!TRANSB) wait_lgkmcnt0();  // the assembly reads of (af, bf) issued during the previous k-step
         static_for<0, 16>([&](auto slot_c) {
             constexpr int slot = decltype(slot_c)::value;
@@ -176,6 +255,7 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
             if constexpr (LBASE >= 0 && (slot & 1))
                 issue_load(std::integral_constant<int, S ^ 1>{}, std::integral_constant<int, LBASE + slot / 2>{}, ap,
                            bp);
+            if constexpr (FUSED && STATS) stats_elem(af, s_c, q_c, slot_c, skip);
             __builtin_amdgcn_sched_barrier(0);
         });
     };
@@ -201,41 +281,170 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     // pass multiplies zeros).  The 16 loads of tile kt+1 (clamped at the last tile; the reload
     // is harmless) ride in the first two k-steps after the barrier; the stage they fill held
     // tile kt-1, whose last reads completed before that barrier.  The body is instantiated for
-    // both stage parities so that every LDS offset is an instruction immediate.
-    auto tile_body = [&](auto s_c, int kt) {
+    // both stage parities so that every LDS offset is an instruction immediate, with and
+    // without the statistics.  (The stage parity of tile kt is kt & 1 = its position in a unit.)
+    auto tile_body = [&](auto s_c, auto st_c, int kt, bool skip) {
         const int ktn = kt + 1 < nk ? kt + 1 : nk - 1;
         const unsigned char* ap = a_base + (int64_t)ktn * (BK * 2);
         const unsigned char* bp = b_base + ktn * b_ktile;
-        kstep(s_c, I0{}, I0{}, af1, bf1, af0, bf0, ap, bp);  // step (kt-1, 3)
-        kstep(s_c, I1{}, I8{}, af0, bf0, af1, bf1, ap, bp);  // step (kt, 0)
-        kstep(s_c, I2{}, IN{}, af1, bf1, af0, bf0, ap, bp);  // step (kt, 1)
-        kstep(s_c, I3{}, IN{}, af0, bf0, af1, bf1, ap, bp);  // step (kt, 2)
+        kstep(s_c, I0{}, I0{}, st_c, I0{}, af1, bf1, af0, bf0, ap, bp, skip);  // step (kt-1, 3)
+        kstep(s_c, I1{}, I8{}, st_c, I1{}, af0, bf0, af1, bf1, ap, bp, false);  // step (kt, 0)
+        kstep(s_c, I2{}, IN{}, st_c, I2{}, af1, bf1, af0, bf0, ap, bp, false);  // step (kt, 1)
+        kstep(s_c, I3{}, IN{}, st_c, I3{}, af0, bf0, af1, bf1, ap, bp, false);  // step (kt, 2)
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     };
-    int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
-        tile_body(I0{}, kt);
-        tile_body(I1{}, kt + 1);
+    if (FUSED) {
+        // Tiles are walked in units of two (so the stage parity stays a compile-time constant).
+        // Tile-column bn folds the units u with u % tiles_n == bn into the statistics: plain
+        // units run in a branch-free inner loop, the folded unit in straight-line code between
+        // two such loops.  K is a multiple of 128 here (the host checks), so there is no odd tile.
+        const int nunits = nk >> 1;
+        int hu = bn;
+        prefetch_be(hu);
+        int u = 0;
+        for (;;) {
+            const int stop = hu < nunits ? hu : nunits;
+            for (; u < stop; ++u) {
+                tile_body(I0{}, I0{}, 2 * u, false);
+                tile_body(I1{}, I0{}, 2 * u + 1, false);
+            }
+            if (u >= nunits) break;
+            tile_body(I0{}, I1{}, 2 * u, u == 0);
+            tile_body(I1{}, I1{}, 2 * u + 1, false);
+            ++u;
+            hu += g.tiles_n;
+            prefetch_be(hu);
+        }
+        // step (nk-1, 3) is the first k-step of the unit that would follow the last one
+        if (!TRANSB) wait_lgkmcnt0();
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = Mfma16<T>::run(bf1[ni], af1[mi], acc[mi][ni]);
+        if (hu == nunits) static_for<0, 16>([&](auto slot_c) { stats_elem(af1, I0{}, I0{}, slot_c, false); });
+    } else {
+        int kt = 0;
+        for (; kt + 1 < nk; kt += 2) {
+            tile_body(I0{}, I0{}, kt, false);
+            tile_body(I1{}, I0{}, kt + 1, false);
+        }
+        if (kt < nk) tile_body(I0{}, I0{}, kt, false);
+        if (!TRANSB) wait_lgkmcnt0();
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = Mfma16<T>::run(bf1[ni], af1[mi], acc[mi][ni]);
     }
-    if (kt < nk) tile_body(I0{}, kt);
-    // step (nk-1, 3)
-    if (!TRANSB) wait_lgkmcnt0();
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = Mfma16<T>::run(bf1[ni], af1[mi], acc[mi][ni]);
 
-    gemm16_epilogue<T, MODE, false>(g, acc, smem, row0, col0, bn, tid, lane, wm, wn, l32, lh);
+    // ---- epilogue -------------------------------------------------------------------------
+    gemm16_inject<INJECT>(g, acc, row0, col0, wm, wn, l32, lh);
+    if (VERIFY) {
+        float* red = reinterpret_cast<float*>(smem);                 // [2 wn][256 rows]
+        float* sred = reinterpret_cast<float*>(smem + SRED_OFFSET);  // [2 wn][4][256 rows]
+        int* s_last = reinterpret_cast<int*>(smem + 2048);
+        gemm16_rowsum_to_lds(acc, red, wm, wn, l32, lh);
+        if (FUSED) {
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) {
+                const float s0 = st[mi][0] + __shfl_xor(st[mi][0], 32, WAVE);
+                const float s1 = st[mi][1] + __shfl_xor(st[mi][1], 32, WAVE);
+                const float s2 = fmaxf(st[mi][2], __shfl_xor(st[mi][2], 32, WAVE));
+                const float s3 = fminf(st[mi][3], __shfl_xor(st[mi][3], 32, WAVE));
+                if (lh == 0) {
+                    const int r = wm * 128 + mi * 32 + l32;
+                    sred[(wn * 4 + 0) * BM + r] = s0;
+                    sred[(wn * 4 + 1) * BM + r] = s1;
+                    sred[(wn * 4 + 2) * BM + r] = s2;
+                    sred[(wn * 4 + 3) * BM + r] = s3;
+                }
+            }
+        }
+        __syncthreads();
+        const int gi = row0 + tid;
+        float* rowpart = reinterpret_cast<float*>(g.rowpart);
+        float* apart = reinterpret_cast<float*>(g.apart);
+        rowpart[(int64_t)bn * g.M + gi] = red[tid] + red[BM + tid];
+        if (FUSED) {
+            float* ap = apart + (int64_t)bn * 4 * g.M + gi;
+            ap[0] = sred[0 * BM + tid] + sred[4 * BM + tid];
+            ap[(int64_t)g.M] = sred[1 * BM + tid] + sred[5 * BM + tid];
+            ap[2 * (int64_t)g.M] = fmaxf(sred[2 * BM + tid], sred[6 * BM + tid]);
+            ap[3 * (int64_t)g.M] = fminf(sred[3 * BM + tid], sred[7 * BM + tid]);
+        }
+        // publish the partials, then take this tile-row's arrival ticket
+        __threadfence();
+        __syncthreads();
+        if (tid == 0) *s_last = (atomicAdd(&g.tickets[bm], 1) == g.tiles_n - 1);
+        __syncthreads();
+        if (*s_last) {
+            __threadfence();
+            float rs = 0.f;
+            for (int t = 0; t < g.tiles_n; ++t) rs += ld_agent(rowpart + (int64_t)t * g.M + gi);
+            float expv, thr;
+            if (FUSED) {
+                float sum = 0.f, dot = 0.f, mx = -3.402823466e+38f, mn = 3.402823466e+38f;
+                for (int t = 0; t < g.tiles_n; ++t) {
+                    const float* ap = apart + (int64_t)t * 4 * g.M + gi;
+                    sum += ld_agent(ap);
+                    dot += ld_agent(ap + (int64_t)g.M);
+                    mx = fmaxf(mx, ld_agent(ap + 2 * (int64_t)g.M));
+                    mn = fminf(mn, ld_agent(ap + 3 * (int64_t)g.M));
+                }
+                const double mu = (double)sum / (double)g.K;
+                double var = ((double)mx - mu) * (mu - (double)mn);
+                var = var > 0 ? var : 0;
+                const double S1 = g.S[0], S2 = g.S[1], S3 = g.S[2], dN = (double)g.N;
+                const double t_det = dN * fabs(mu) * S1;
+                const double t_var23 = g.c_sigma * sqrt(dN * mu * mu * S2 + dN * dN * var * S3);
+                const double t_var4 = g.c_sigma * sqrt(dN) * sqrt(var) * sqrt(S2);
+                expv = dot;
+                thr = (float)(g.e_max * (t_det + t_var23 + t_var4));
+                float* astat = reinterpret_cast<float*>(g.astat);
+                astat[3 * (int64_t)gi + 0] = mx;
+                astat[3 * (int64_t)gi + 1] = mn;
+                astat[3 * (int64_t)gi + 2] = (float)mu;
+                reinterpret_cast<float*>(const_cast<void*>(g.expected))[gi] = expv;
+                reinterpret_cast<float*>(const_cast<void*>(g.T))[gi] = thr;
+            } else {
+                expv = reinterpret_cast<const float*>(g.expected)[gi];
+                thr = reinterpret_cast<const float*>(g.T)[gi];
+            }
+            const float e = expv - rs;
+            const int f = !(fabsf(e) <= thr);
+            reinterpret_cast<float*>(g.rowsum)[gi] = rs;
+            reinterpret_cast<float*>(g.E)[gi] = e;
+            g.flags[gi] = f;
+            const int cnt = __syncthreads_count(f);
+            if (tid == 0) {
+                int* rowcnt = g.tickets + g.tiles_m;
+                int* done = g.tickets + 2 * g.tiles_m;
+                __hip_atomic_store(&rowcnt[bm], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&g.tickets[bm], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __threadfence();
+                if (atomicAdd(done, 1) == g.tiles_m - 1) {
+                    __threadfence();
+                    int tot = 0;
+                    for (int i = 0; i < g.tiles_m; ++i)
+                        tot += __hip_atomic_load(&rowcnt[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    *g.d_nflag = tot;
+                    __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+        __syncthreads();  // the store below reuses the LDS the reductions read
+    }
+    gemm16_store_c<T, false>(g, acc, smem, row0, col0, lane, wm, wn, l32, lh);
 }
 
-template <typename T>
-static int gemm16_fast_launch(const GemmArgs& a, int transB, int mode, hipStream_t st) {
+template <typename T, int TRANSB>
+static int gemm16_fast_launch_tb(const GemmArgs& a, int mode, hipStream_t st) {
     const dim3 grid(a.tiles_m * a.tiles_n), block(256);
     const size_t lds = g16::LDS_BYTES;
-#define VABFT_G16F_CASE(TB, VF)                                                                            \
-    if (transB == TB && mode == VF) {                                                                      \
-        auto kern = gemm16_fast_kernel<T, TB, VF>;                                                         \
+    const int fused = a.fused_stats ? 1 : 0;
+#define VABFT_G16F_CASE(VF, FU)                                                                            \
+    if (mode == VF && fused == FU) {                                                                       \
+        auto kern = gemm16_fast_kernel<T, TRANSB, VF, FU != 0>;                                            \
         static bool attr_set = false;                                                                      \
         if (!attr_set) {                                                                                   \
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
@@ -247,11 +456,10 @@ static int gemm16_fast_launch(const GemmArgs& a, int transB, int mode, hipStream
         return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;                                 \
     }
     VABFT_G16F_CASE(0, 0)
-    VABFT_G16F_CASE(0, 1)
-    VABFT_G16F_CASE(0, 2)
     VABFT_G16F_CASE(1, 0)
+    VABFT_G16F_CASE(2, 0)
     VABFT_G16F_CASE(1, 1)
-    VABFT_G16F_CASE(1, 2)
+    VABFT_G16F_CASE(2, 1)
 #undef VABFT_G16F_CASE
     return VABFT_EINVAL;
 }

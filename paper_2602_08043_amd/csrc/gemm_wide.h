@@ -77,24 +77,33 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     static_assert(NCH_A == NCH_B, "tile shape");
     T ra[NCH_A][V], rb[NCH_B][V];
 
+    // one 16-byte chunk; whole-tile problems need no guards
+    auto load_chunk = [&](const T* base, int r, int nr, int c, int nc, int64_t ld, int vec_ok, T (&out)[V]) {
+        if (!EDGE) {
+            const raw16 v = ld16(base + (int64_t)r * ld + c);
+            __builtin_memcpy(out, &v, 16);
+        } else {
+            guarded_chunk_wide<T, V>(base, r, nr, c, nc, ld, vec_ok, out);
+        }
+    };
     auto load_tiles = [&](int kt) {
         const int kbase = kt * BK;
 #pragma unroll
         for (int p = 0; p < NCH_A; ++p) {
             const int id = tid + 256 * p, r = id / CPR, c = id % CPR;
-            guarded_chunk_wide<T, V>(A, row0 + r, g.M, kbase + c * V, g.K, g.lda, EDGE ? g.a_vec_ok : 1, ra[p]);
+            load_chunk(A, row0 + r, g.M, kbase + c * V, g.K, g.lda, g.a_vec_ok, ra[p]);
         }
         if (TRANSB) {
 #pragma unroll
             for (int p = 0; p < NCH_B; ++p) {
                 const int id = tid + 256 * p, r = id / CPR, c = id % CPR;
-                guarded_chunk_wide<T, V>(B, col0 + r, g.N, kbase + c * V, g.K, g.ldb, EDGE ? g.b_vec_ok : 1, rb[p]);
+                load_chunk(B, col0 + r, g.N, kbase + c * V, g.K, g.ldb, g.b_vec_ok, rb[p]);
             }
         } else {
 #pragma unroll
             for (int p = 0; p < NCH_B; ++p) {
                 const int id = tid + 256 * p, kr = id / CPK, c = id % CPK;
-                guarded_chunk_wide<T, V>(B, kbase + kr, g.K, col0 + c * V, g.N, g.ldb, EDGE ? g.b_vec_ok : 1, rb[p]);
+                load_chunk(B, kbase + kr, g.K, col0 + c * V, g.N, g.ldb, g.b_vec_ok, rb[p]);
             }
         }
     };

@@ -36,19 +36,47 @@ struct GemmArgs {
     int64_t lda, ldb, ldc;
     int32_t tiles_m, tiles_n;
     int32_t a_vec_ok, b_vec_ok, c_vec_ok;
-    void* rowpart;    // [tiles_n][M] acc
-    int32_t* d_nflag; // zeroed by the GEMM kernel, accumulated by the finalize kernel
+    void* rowpart;    // [tiles_n][M] acc: per-tile-column partial row sums
+    int32_t* d_nflag; // number of flagged rows
     InjectArgs inj;
+    // in-kernel compare-and-flag (whole-tile 16-bit kernels): the last workgroup to finish a
+    // tile-row combines the partials of that row block
+    const void* expected;  // [M] acc: input, or output when fused_stats
+    const void* T;         // [M] acc: input, or output when fused_stats
+    void* rowsum;          // [M] acc
+    void* E;               // [M] acc
+    int32_t* flags;        // [M]
+    int32_t* tickets;      // [tiles_m] arrival counters, [tiles_m] flag counts, [1] finished row blocks;
+                           // all zero between launches
+    // fused A-side statistics (Algorithm 1 for the rows of A, inside the GEMM)
+    int32_t fused_stats;
+    const void* Be;   // [K] acc
+    const double* S;  // [3]
+    double e_max, c_sigma;
+    void* astat;      // [M][3] acc, output
+    void* apart;      // [tiles_n][4][M] acc: per-K-slice (sum, dot, max, min) of the rows of A
 };
 
 size_t gemm_workspace_bytes(const vabft_problem* p);
-int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* dC, const void* d_expected,
-                  const void* d_T, int verify, const vabft_inject* inj, void* d_rowsum, void* d_E, int32_t* d_flags,
-                  int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj, void* ws, hipStream_t st);
+struct FusedArgs {  // non-null d_Be selects the fused A-side path
+    const void* d_Be;
+    const double* d_S;
+    double e_max, c_sigma;
+    void* d_astat;
+};
+int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* dC, void* d_expected, void* d_T,
+                  int verify, const FusedArgs* fused, const vabft_inject* inj, void* d_rowsum, void* d_E,
+                  int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj, void* ws,
+                  hipStream_t st);
+void workspace_init_launch(void* ws, size_t bytes, hipStream_t st);
 
 // per-dtype launchers (one translation unit each, to compile in parallel)
-int gemm16_launch_bf16(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st);
-int gemm16_launch_f16(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st);
+// mode: 0 plain, 1 check, 2 check + injector.  With edge == false the 16-bit kernels do the
+// compare-and-flag step themselves; otherwise the caller launches the finalize kernel.
+int gemm16_launch_bf16_nn(const GemmArgs& a, int mode, bool edge, hipStream_t st);
+int gemm16_launch_bf16_nt(const GemmArgs& a, int mode, bool edge, hipStream_t st);
+int gemm16_launch_f16_nn(const GemmArgs& a, int mode, bool edge, hipStream_t st);
+int gemm16_launch_f16_nt(const GemmArgs& a, int mode, bool edge, hipStream_t st);
 int gemmw_launch_f32(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st);
 int gemmw_launch_f64(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st);
 

@@ -54,6 +54,7 @@ class VerifiedGemm:
         self.injlog = torch.zeros(max(1, self.log_capacity) * _REC_DTYPE.itemsize, dtype=torch.uint8, device=dev)
         self.ws_bytes = vb.vabft_workspace_bytes(self.problem)
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
+        vb.vabft_workspace_init(self.ws.data_ptr(), self.ws_bytes, self._stream())
         self._list = None
 
     @staticmethod
@@ -92,11 +93,28 @@ class VerifiedGemm:
                                       self.nflag.data_ptr(), self.injlog.data_ptr(), self.ninj.data_ptr(),
                                       self.ws.data_ptr(), self.ws_bytes, self._stream())
 
+    def gemm_fused(self, A: torch.Tensor, B: torch.Tensor, e_max=None, c_sigma=2.5, inj: vb.Inject | None = None):
+        """A-side pass, GEMM and check in one call (needs encode(B) first)."""
+        if e_max is None:
+            e_max = vb.vabft_default_emax(self.dtype, self.K, self.N)
+        self.e_max = e_max
+        return vb.vabft_gemm_verified_fused(self.problem, A.data_ptr(), B.data_ptr(), self.C.data_ptr(),
+                                            self.Be.data_ptr(), self.S.data_ptr(), e_max, c_sigma,
+                                            self.astat.data_ptr(), self.expected.data_ptr(), self.T.data_ptr(), inj,
+                                            self.rowsum.data_ptr(), self.E.data_ptr(), self.flags.data_ptr(),
+                                            self.nflag.data_ptr(), self.injlog.data_ptr(), self.ninj.data_ptr(),
+                                            self.ws.data_ptr(), self.ws_bytes, self._stream())
+
     def run(self, A, B, e_max=None, c_sigma=2.5, inj=None):
-        """One pass of the whole path: encode, threshold, verified GEMM."""
+        """One pass of the whole path: encode, threshold, verified GEMM (three calls)."""
         self.encode(B)
         self.threshold(A, e_max, c_sigma)
         self.gemm(A, B, 1, inj)
+
+    def run_fused(self, A, B, e_max=None, c_sigma=2.5, inj=None):
+        """One pass of the whole path in two calls: encode, fused threshold + verified GEMM."""
+        self.encode(B)
+        self.gemm_fused(A, B, e_max, c_sigma, inj)
 
     def inject_records(self):
         """Downloaded injection log as a list of (row, col, bit, before, after), sorted."""

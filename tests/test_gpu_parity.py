@@ -130,6 +130,59 @@ def test_plain_gemm_matches_verified(dtype, M, N, K, transB):
     assert np.all(r["rowsum"] == 123.0)
 
 
+FUSED = [
+    # whole-tile 16-bit problems: statistics and compare/flag inside the GEMM kernel
+    ("bf16", 512, 512, 256, 0), ("bf16", 512, 768, 384, 1), ("f16", 256, 1024, 512, 0), ("f16", 768, 512, 128, 1),
+    ("bf16", 256, 512, 1152, 0),
+    # everything else: the two passes back to back behind the same entry point
+    ("bf16", 512, 256, 256, 0), ("bf16", 512, 512, 192, 0), ("bf16", 300, 520, 200, 1), ("f16", 100, 99, 50, 0),
+    ("f32", 256, 256, 256, 0), ("f64", 200, 260, 70, 1),
+]
+
+
+@pytest.mark.parametrize("dtype,M,N,K,transB", FUSED)
+def test_fused_entry_point_parity(dtype, M, N, K, transB):
+    """vabft_gemm_verified_fused against the oracle, twice in a row on the same workspace
+    (arrival counters must come back to zero), then against the three-call route."""
+    for seed, dist in ((11, "n_1e-6_1"), (12, "n_1_1"), (13, "u_-1_1")):
+        A, B = _gen(dtype, M, N, K, transB, seed, dist)
+        print(f"fused case {dtype} {M}x{N}x{K} transB={transB} seed={seed} {dist}", flush=True)
+        dA, dB = _dev(A, dtype), _dev(B, dtype)
+        vg = _session(M, N, K, dtype, transB)
+        o = orc.verify(A, B, dtype, transB)
+        for rep in range(2):
+            vg.rowsum.fill_(7.0)
+            vg.T.fill_(-1.0)
+            vg.run_fused(dA, dB)
+            r = vg.results()
+            check_light(r, o, dtype, M, N, K)
+            check_rows(r, o, dtype)
+            check_C(r, o, A, B, dtype, transB)
+            assert np.array_equal(r["astat"][:, 0].astype(np.float64), o["astat"][:, 0])
+            assert np.array_equal(r["astat"][:, 1].astype(np.float64), o["astat"][:, 1])
+            assert np.all(np.abs(r["astat"][:, 2] - o["astat"][:, 2]) <= _tol(dtype) * np.abs(orc.decode(A, dtype)).mean(axis=1) + 1e-300)
+            assert not r["flags"].any() and r["nflag"] == 0
+        # same C bit for bit, same flags, as the three-call route
+        C_fused = r["C"].copy()
+        vg.run(dA, dB)
+        r3 = vg.results()
+        assert np.array_equal(r3["C"], C_fused)
+        assert np.array_equal(r3["rowsum"], r["rowsum"])
+        assert np.allclose(r3["T"], r["T"], rtol=2e-6 if dtype != "f64" else 1e-12, atol=0)
+    # one exponent flip through the fused call
+    i, j = M // 2, N // 3
+    bit = 61 if dtype == "f64" else 29
+    inj = vg.make_inject(mode=1, faults=[(i, j, bit)])
+    vg.run_fused(dA, dB, inj=inj)
+    r = vg.results()
+    n, recs = vg.inject_records()
+    assert n == 1 and recs[0][:3] == (i, j, bit)
+    assert r["flags"][i] == 1 and r["nflag"] == 1 and r["flags"].sum() == 1
+    # and the counters are clean again afterwards
+    vg.run_fused(dA, dB)
+    assert vg.results()["nflag"] == 0
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f16", "f32", "f64"])
 @pytest.mark.parametrize("transB", [0, 1])
 def test_exact_arithmetic_gives_zero_difference(dtype, transB):
@@ -302,7 +355,7 @@ def test_full_size_sampled(name, variant):
     print(f"full {name} variant {variant}: {M}x{N}x{K} {dt} transB={tb}", flush=True)
     dA, dB = _dev(cfg["A"], dt), _dev(cfg["B"], dt)
     vg = _session(M, N, K, dt, tb)
-    vg.run(dA, dB)
+    vg.run_fused(dA, dB)  # the launch configuration bench.py times
     r = vg.results()
     rows = np.sort(wl.rng(3, 77).choice(M, size=64, replace=False))
     # tile-boundary rows too
@@ -314,6 +367,12 @@ def test_full_size_sampled(name, variant):
     assert not r["flags"].any() and r["nflag"] == 0
     assert not o["flags"].any()
     assert np.all(np.abs(r["E"]) <= r["T"])
+    # the three-call route at full size agrees too
+    vg.run(dA, dB)
+    r3 = vg.results()
+    check_light(r3, o, dt, M, N, K)
+    check_rows(r3, o, dt, rows)
+    assert np.array_equal(r3["C"], r["C"]) and r3["nflag"] == 0
     # one exponent-bit flip at full size, replayed by the oracle on a sampled row
     i = int(rows[5])
     j = N - 3
