@@ -59,9 +59,16 @@ __device__ __forceinline__ void g2l16(const void* gptr, lds_u8* lds_base) {
     __builtin_amdgcn_global_load_lds((glb_u8*)gptr, (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
 }
 
+// Partials exchanged between workgroups (which may sit on different XCDs with private L2s) go
+// through device-scope relaxed atomic stores and loads: they are performed at the device's
+// coherence point, so no cache write-back / invalidate fence is needed around the ticket.
 __device__ __forceinline__ float ld_agent(const float* p) {
     return __builtin_bit_cast(float, __hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED,
                                                         __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ void st_agent(float* p, float v) {
+    __hip_atomic_store(reinterpret_cast<uint32_t*>(p), __builtin_bit_cast(uint32_t, v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // element e (0..3) of the two selected dwords of a 16-byte fragment, as float
@@ -75,6 +82,10 @@ template <> __device__ __forceinline__ float frag_elem<f16_t>(uint32_t d0, uint3
     return Elem<f16_t>::to_acc((uint16_t)((e & 1) ? (d >> 16) : (d & 0xffffu)));
 }
 
+#ifndef VABFT_G16_READS_PER_SLOT
+#define VABFT_G16_READS_PER_SLOT 1
+#endif
+constexpr int RPS = VABFT_G16_READS_PER_SLOT;  // fragment reads issued per MFMA slot, front-loaded
 constexpr int SRED_OFFSET = 40960;  // LDS offset of the A-statistics staging area in the epilogue
 }  // namespace g16f
 
@@ -251,7 +262,11 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
             constexpr int mi = slot >> 2, ni = slot & 3;
             acc[mi][ni] = Mfma16<T>::run(bf[ni], af[mi], acc[mi][ni]);
             __builtin_amdgcn_sched_barrier(0);  // MFMA first, the rest of the slot in its shadow
-            if constexpr (slot < NRD) frag_op(s_c, ks_c, slot_c, naf, nbf);
+            {
+                constexpr int r_lo = slot * RPS < NRD ? slot * RPS : NRD;
+                constexpr int r_hi = (slot + 1) * RPS < NRD ? (slot + 1) * RPS : NRD;
+                static_for<r_lo, r_hi>([&](auto op_c) { frag_op(s_c, ks_c, op_c, naf, nbf); });
+            }
             if constexpr (LBASE >= 0 && (slot & 1))
                 issue_load(std::integral_constant<int, S ^ 1>{}, std::integral_constant<int, LBASE + slot / 2>{}, ap,
                            bp);
@@ -364,33 +379,52 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         const int gi = row0 + tid;
         float* rowpart = reinterpret_cast<float*>(g.rowpart);
         float* apart = reinterpret_cast<float*>(g.apart);
-        rowpart[(int64_t)bn * g.M + gi] = red[tid] + red[BM + tid];
+        st_agent(rowpart + (int64_t)bn * g.M + gi, red[tid] + red[BM + tid]);
         if (FUSED) {
             float* ap = apart + (int64_t)bn * 4 * g.M + gi;
-            ap[0] = sred[0 * BM + tid] + sred[4 * BM + tid];
-            ap[(int64_t)g.M] = sred[1 * BM + tid] + sred[5 * BM + tid];
-            ap[2 * (int64_t)g.M] = fmaxf(sred[2 * BM + tid], sred[6 * BM + tid]);
-            ap[3 * (int64_t)g.M] = fminf(sred[3 * BM + tid], sred[7 * BM + tid]);
+            st_agent(ap, sred[0 * BM + tid] + sred[4 * BM + tid]);
+            st_agent(ap + (int64_t)g.M, sred[1 * BM + tid] + sred[5 * BM + tid]);
+            st_agent(ap + 2 * (int64_t)g.M, fmaxf(sred[2 * BM + tid], sred[6 * BM + tid]));
+            st_agent(ap + 3 * (int64_t)g.M, fminf(sred[3 * BM + tid], sred[7 * BM + tid]));
         }
-        // publish the partials, then take this tile-row's arrival ticket
-        __threadfence();
+        // every thread's partials are performed (vmcnt(0)) before the workgroup takes this
+        // tile-row's arrival ticket
+        __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         if (tid == 0) *s_last = (atomicAdd(&g.tickets[bm], 1) == g.tiles_n - 1);
         __syncthreads();
         if (*s_last) {
-            __threadfence();
-            float rs = 0.f;
-            for (int t = 0; t < g.tiles_n; ++t) rs += ld_agent(rowpart + (int64_t)t * g.M + gi);
+            // Combine the tile-column partials in tile order.  The device-scope loads are issued
+            // in batches of 8 tile-columns before anything is folded, so their latencies overlap.
+            float rs = 0.f, sum = 0.f, dot = 0.f, mx = -3.402823466e+38f, mn = 3.402823466e+38f;
+            for (int t0 = 0; t0 < g.tiles_n; t0 += 8) {
+                float v[8][5];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int t = t0 + j < g.tiles_n ? t0 + j : g.tiles_n - 1;  // clamped duplicates are not folded
+                    v[j][0] = ld_agent(rowpart + (int64_t)t * g.M + gi);
+                    if (FUSED) {
+                        const float* ap = apart + (int64_t)t * 4 * g.M + gi;
+                        v[j][1] = ld_agent(ap);
+                        v[j][2] = ld_agent(ap + (int64_t)g.M);
+                        v[j][3] = ld_agent(ap + 2 * (int64_t)g.M);
+                        v[j][4] = ld_agent(ap + 3 * (int64_t)g.M);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (t0 + j < g.tiles_n) {
+                        rs += v[j][0];
+                        if (FUSED) {
+                            sum += v[j][1];
+                            dot += v[j][2];
+                            mx = fmaxf(mx, v[j][3]);
+                            mn = fminf(mn, v[j][4]);
+                        }
+                    }
+            }
             float expv, thr;
             if (FUSED) {
-                float sum = 0.f, dot = 0.f, mx = -3.402823466e+38f, mn = 3.402823466e+38f;
-                for (int t = 0; t < g.tiles_n; ++t) {
-                    const float* ap = apart + (int64_t)t * 4 * g.M + gi;
-                    sum += ld_agent(ap);
-                    dot += ld_agent(ap + (int64_t)g.M);
-                    mx = fmaxf(mx, ld_agent(ap + 2 * (int64_t)g.M));
-                    mn = fminf(mn, ld_agent(ap + 3 * (int64_t)g.M));
-                }
                 const double mu = (double)sum / (double)g.K;
                 double var = ((double)mx - mu) * (mu - (double)mn);
                 var = var > 0 ? var : 0;
@@ -421,9 +455,8 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
                 int* done = g.tickets + 2 * g.tiles_m;
                 __hip_atomic_store(&rowcnt[bm], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(&g.tickets[bm], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __threadfence();
+                __builtin_amdgcn_s_waitcnt(0);
                 if (atomicAdd(done, 1) == g.tiles_m - 1) {
-                    __threadfence();
                     int tot = 0;
                     for (int i = 0; i < g.tiles_m; ++i)
                         tot += __hip_atomic_load(&rowcnt[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
