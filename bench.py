@@ -40,8 +40,8 @@ WORKLOAD_TEXT = {
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="c2_bf16_4096", choices=sorted(WORKLOAD_TEXT))
     ap.add_argument("--quality-trials", type=int, default=40, help="fault-free trials for FPR / tightness")
     ap.add_argument("--flips-per-bit", type=int, default=16, help="single-bit-flip trials per bit position")
@@ -87,7 +87,16 @@ def main():
         torch.cuda.synchronize()
         return t0.elapsed_time(t1) / steps  # ms per step
 
-    # ---- the timed region: exactly K whole-path steps between two synchronisations
+    # ---- bring the GPU to its sustained clocks first (untimed, ~0.3 s of the same steps): the
+    #      first milliseconds after idle run at different clocks than a long job does
+    t_spin = time.time()
+    while time.time() - t_spin < 0.3:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
+
+    # ---- the timed region: W untimed warm-up steps, then exactly K whole-path steps between
+    #      two synchronisations
     ms_step = timed(step, args.steps, args.warmup)
     nflag_timed = int(vg.nflag.item())
 

@@ -219,59 +219,96 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
     }
 }
 
-// Step 2: combine the nsplit partials of column k in a fixed order.
+// Step 2: combine the nsplit partials of column k in a fixed order: 16 columns per block,
+// 16 groups of threads per column; group g folds splits g, g+16, ... in increasing order and
+// the 16 group results are folded in group order.
 template <typename acc_t>
 __global__ __launch_bounds__(256) void encode_cols_combine_kernel(const acc_t* __restrict__ part, int nsplit, int K,
                                                                   int N, acc_t* __restrict__ Be,
                                                                   acc_t* __restrict__ bstat) {
-    const int k = blockIdx.x * 256 + threadIdx.x;
-    if (k >= K) return;
+    __shared__ acc_t red[3][16][16];
+    const int kl = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int k = blockIdx.x * 16 + kl;
     acc_t sum = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
-    for (int s = 0; s < nsplit; ++s) {
-        const acc_t* p = part + (int64_t)s * 3 * K;
-        sum += p[k];
-        acc_t a = p[(int64_t)K + k], b = p[2 * (int64_t)K + k];
-        mx = a > mx ? a : mx;
-        mn = b < mn ? b : mn;
+    if (k < K) {
+        for (int s = grp; s < nsplit; s += 16) {
+            const acc_t* p = part + (int64_t)s * 3 * K;
+            sum += p[k];
+            const acc_t a = p[(int64_t)K + k], b = p[2 * (int64_t)K + k];
+            mx = a > mx ? a : mx;
+            mn = b < mn ? b : mn;
+        }
     }
-    Be[k] = sum;
-    bstat[3 * (int64_t)k + 0] = mx;
-    bstat[3 * (int64_t)k + 1] = mn;
-    bstat[3 * (int64_t)k + 2] = (acc_t)((double)sum / (double)N);
+    red[0][grp][kl] = sum;
+    red[1][grp][kl] = mx;
+    red[2][grp][kl] = mn;
+    __syncthreads();
+    if (grp == 0 && k < K) {
+        sum = red[0][0][kl];
+        mx = red[1][0][kl];
+        mn = red[2][0][kl];
+#pragma unroll
+        for (int g = 1; g < 16; ++g) {
+            sum += red[0][g][kl];
+            const acc_t a = red[1][g][kl], b = red[2][g][kl];
+            mx = a > mx ? a : mx;
+            mn = b < mn ? b : mn;
+        }
+        Be[k] = sum;
+        bstat[3 * (int64_t)k + 0] = mx;
+        bstat[3 * (int64_t)k + 1] = mn;
+        bstat[3 * (int64_t)k + 2] = (acc_t)((double)sum / (double)N);
+    }
 }
 
 // ---------------------------------------------------------------------------
-// S1, S2, S3 from (Be, max, min): one block, fixed-order tree, double arithmetic
+// S1, S2, S3 from (Be, max, min): one block; each thread folds rows t, t+1024, ... in
+// increasing order, then a fixed-order reduction (butterfly inside each wavefront, then the 16
+// wavefront results in order), all in double arithmetic.
 // ---------------------------------------------------------------------------
 template <typename acc_t>
 __global__ __launch_bounds__(1024) void encode_aggregate_kernel(const acc_t* __restrict__ Be,
                                                                 const acc_t* __restrict__ bstat, int K, int N,
                                                                 double* __restrict__ S) {
-    __shared__ double red[3][1024];
+    __shared__ double red[3][16];
     const int t = threadIdx.x;
     double s1 = 0, s2 = 0, s3 = 0;
-    for (int k = t; k < K; k += 1024) {
-        const double mu = (double)Be[k] / (double)N;
-        const double mx = (double)bstat[3 * (int64_t)k], mn = (double)bstat[3 * (int64_t)k + 1];
-        double var = (mx - mu) * (mu - mn);
-        var = var > 0 ? var : 0;
-        s1 += fabs(mu);
-        s2 += var;
-        s3 += mu * mu;
-    }
-    red[0][t] = s1;
-    red[1][t] = s2;
-    red[2][t] = s3;
-    __syncthreads();
-    for (int off = 512; off >= 1; off >>= 1) {
-        if (t < off) {
-            red[0][t] += red[0][t + off];
-            red[1][t] += red[1][t + off];
-            red[2][t] += red[2][t + off];
+    for (int k0 = 0; k0 < K; k0 += 4096) {
+        acc_t be[4], mxv[4], mnv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int k = k0 + t + 1024 * u;
+            const int kc = k < K ? k : K - 1;
+            be[u] = Be[kc];
+            mxv[u] = bstat[3 * (int64_t)kc];
+            mnv[u] = bstat[3 * (int64_t)kc + 1];
         }
-        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (k0 + t + 1024 * u < K) {
+                const double mu = (double)be[u] / (double)N;
+                double var = ((double)mxv[u] - mu) * (mu - (double)mnv[u]);
+                var = var > 0 ? var : 0;
+                s1 += fabs(mu);
+                s2 += var;
+                s3 += mu * mu;
+            }
+        }
     }
-    if (t < 3) S[t] = red[t][0];
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    s3 = wave_sum(s3);
+    if ((t & 63) == 0) {
+        red[0][t >> 6] = s1;
+        red[1][t >> 6] = s2;
+        red[2][t >> 6] = s3;
+    }
+    __syncthreads();
+    if (t < 3) {
+        double v = 0;
+        for (int w = 0; w < 16; ++w) v += red[t][w];
+        S[t] = v;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -394,7 +431,7 @@ static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, voi
         dim3 grid((p->K + 64 * V - 1) / (64 * V), nsplit);
         encode_cols_kernel<T><<<grid, dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, ENC_ROWS_PER_BLOCK, (acc_t*)ws,
                                                           vec_ok);
-        encode_cols_combine_kernel<acc_t><<<dim3((p->K + 255) / 256), dim3(256), 0, st>>>(
+        encode_cols_combine_kernel<acc_t><<<dim3((p->K + 15) / 16), dim3(256), 0, st>>>(
             (const acc_t*)ws, nsplit, p->K, p->N, (acc_t*)d_Be, (acc_t*)d_bstat);
     }
     encode_aggregate_kernel<acc_t><<<dim3(1), dim3(1024), 0, st>>>((const acc_t*)d_Be, (const acc_t*)d_bstat, p->K,
