@@ -57,7 +57,7 @@ static void tile_shape(int dtype, int* bm, int* bn) {
     }
 }
 
-// Workspace layout: [tickets: 2*tiles_m + 1 int32, rounded to 256 B][scratch].
+// Workspace layout: [tickets: tiles_m int32 + one 64-bit counter, rounded to 256 B][scratch].
 // The scratch area holds, for the GEMM, rowpart[tiles_n][M] acc followed (16-bit types) by
 // apart[tiles_n][4][M] acc, and for the encode of an N x K B its column partials; the two
 // calls are ordered on one stream, so they share it.  The tickets must be zero between
@@ -66,7 +66,7 @@ static size_t tickets_bytes(const vabft_problem* p) {
     int bm, bn;
     tile_shape(p->dtype, &bm, &bn);
     const size_t tiles_m = ((size_t)p->M + bm - 1) / bm;
-    return round_up((2 * tiles_m + 1) * sizeof(int32_t), 256);
+    return round_up((tiles_m + 4) * sizeof(int32_t), 256);
 }
 
 size_t gemm_workspace_bytes(const vabft_problem* p) {
@@ -153,7 +153,8 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     // whole-tile 16-bit kernels do the compare-and-flag step (and, if asked, the A-side pass) in-kernel
     const bool in_kernel_finalize = is16 && !edge;
     if (fused) {
-        if (in_kernel_finalize && a.tiles_n >= 2 && p->K % 128 == 0 && aligned_to(fused->d_Be, 16)) {
+        // the fused kernel caches the Be slices of the k-units a tile-column folds: at most 16
+        if (in_kernel_finalize && a.tiles_n >= 2 && p->K % 128 == 0 && (p->K / 128) / a.tiles_n + 2 <= 16) {
             a.fused_stats = 1;
             a.Be = fused->d_Be;
             a.S = fused->d_S;

@@ -86,7 +86,12 @@ template <> __device__ __forceinline__ float frag_elem<f16_t>(uint32_t d0, uint3
 #define VABFT_G16_READS_PER_SLOT 1
 #endif
 constexpr int RPS = VABFT_G16_READS_PER_SLOT;  // fragment reads issued per MFMA slot, front-loaded
-constexpr int SRED_OFFSET = 40960;  // LDS offset of the A-statistics staging area in the epilogue
+constexpr int SRED_OFFSET = 40960;
+// Be values the workgroup will need, cached in LDS behind the two operand stages: one slot of
+// 128 floats per folded unit u (k = 128*u - 16 .. 128*u + 111).
+constexpr int BE_CACHE_OFFSET = LDS_BYTES;
+constexpr int BE_CACHE_SLOTS = 16;
+constexpr int LDS_BYTES_FUSED = LDS_BYTES + BE_CACHE_SLOTS * 128 * 4;  // LDS offset of the A-statistics staging area in the epilogue
 }  // namespace g16f
 
 template <typename T, int TRANSB, int MODE, bool FUSED>
@@ -208,18 +213,15 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         st[mi][3] = 3.402823466e+38f;
     }
     const float* const Be = reinterpret_cast<const float*>(g.Be);
-    // Be values of the two bodies of unit u (tiles 2u, 2u+1): k-step 0 of body kb multiplies
-    // step (kb-1, 3), k-steps 1..3 multiply steps (kb, 0..2)
-    auto prefetch_be = [&](int u) {
+    // Be values of folded unit number j of this workgroup (unit u = bn + j*tiles_n, tiles 2u and
+    // 2u+1), from the LDS cache filled in the prologue.  k-step q of body kb = 2u + t multiplies
+    // step (kb-1, 3) for q = 0 and (kb, q-1) otherwise, i.e. k = 128u - 16 + 64t + 16q + ...
+    auto load_bev = [&](int j) {
+        const float* slot = reinterpret_cast<const float*>(smem + BE_CACHE_OFFSET) + j * 128 + 8 * lh + 4 * wn;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int kb = 2 * u + t;
-                int k = (q == 0 ? kb * BK - 16 : kb * BK + (q - 1) * 16) + 8 * lh + 4 * wn;
-                k = k < 0 ? 0 : (k > g.K - 4 ? g.K - 4 : k);  // clamped values are never used
-                bev[t][q] = *reinterpret_cast<const f32x4_t*>(Be + k);
-            }
+            for (int q = 0; q < 4; ++q) bev[t][q] = *reinterpret_cast<const f32x4_t*>(slot + 64 * t + 16 * q);
     };
     uint32_t sd0 = 0, sd1 = 0;  // the two dwords of the current fragment that this wavefront folds
     // `skip` (wave-uniform) keeps the all-zero fragments of the very first pass out of max / min
@@ -270,7 +272,9 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
             if constexpr (LBASE >= 0 && (slot & 1))
                 issue_load(std::integral_constant<int, S ^ 1>{}, std::integral_constant<int, LBASE + slot / 2>{}, ap,
                            bp);
+#ifndef VABFT_LAB_NOSTATS
             if constexpr (FUSED && STATS) stats_elem(af, s_c, q_c, slot_c, skip);
+#endif
             __builtin_amdgcn_sched_barrier(0);
         });
     };
@@ -286,6 +290,21 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) af1[i] = bf1[i] = raw16{{0u, 0u, 0u, 0u}};
     static_for<0, 16>([&](auto l_c) { issue_load(I0{}, l_c, a_base, b_base); });
+#ifdef VABFT_LAB_NOCACHE
+    if (false) {
+#else
+    if (FUSED) {
+#endif
+        // cache the Be slices of every unit this tile-column folds (the host guarantees they fit)
+        float* cache = reinterpret_cast<float*>(smem + BE_CACHE_OFFSET);
+        const int nunits = nk >> 1;
+        for (int j = 0, u = bn; u <= nunits && j < BE_CACHE_SLOTS; ++j, u += g.tiles_n) {
+            if (tid < 128) {
+                const int k = 128 * u - 16 + tid;
+                cache[j * 128 + tid] = (k >= 0 && k < g.K) ? Be[k] : 0.f;
+            }
+        }
+    }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -315,8 +334,7 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         // units run in a branch-free inner loop, the folded unit in straight-line code between
         // two such loops.  K is a multiple of 128 here (the host checks), so there is no odd tile.
         const int nunits = nk >> 1;
-        int hu = bn;
-        prefetch_be(hu);
+        int hu = bn, hj = 0;
         int u = 0;
         for (;;) {
             const int stop = hu < nunits ? hu : nunits;
@@ -325,11 +343,12 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
                 tile_body(I1{}, I0{}, 2 * u + 1, false);
             }
             if (u >= nunits) break;
+            load_bev(hj);
             tile_body(I0{}, I1{}, 2 * u, u == 0);
             tile_body(I1{}, I1{}, 2 * u + 1, false);
             ++u;
             hu += g.tiles_n;
-            prefetch_be(hu);
+            ++hj;
         }
         // step (nk-1, 3) is the first k-step of the unit that would follow the last one
         if (!TRANSB) wait_lgkmcnt0();
@@ -337,7 +356,10 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
             for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = Mfma16<T>::run(bf1[ni], af1[mi], acc[mi][ni]);
-        if (hu == nunits) static_for<0, 16>([&](auto slot_c) { stats_elem(af1, I0{}, I0{}, slot_c, false); });
+        if (hu == nunits) {
+            load_bev(hj);
+            static_for<0, 16>([&](auto slot_c) { stats_elem(af1, I0{}, I0{}, slot_c, false); });
+        }
     } else {
         int kt = 0;
         for (; kt + 1 < nk; kt += 2) {
@@ -393,14 +415,18 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         __syncthreads();
         if (tid == 0) *s_last = (atomicAdd(&g.tickets[bm], 1) == g.tiles_n - 1);
         __syncthreads();
+#ifdef VABFT_LAB_NOFINAL
+        if (false) {
+#else
         if (*s_last) {
+#endif
             // Combine the tile-column partials in tile order.  The device-scope loads are issued
-            // in batches of 8 tile-columns before anything is folded, so their latencies overlap.
+            // in batches of 16 tile-columns before anything is folded, so their latencies overlap.
             float rs = 0.f, sum = 0.f, dot = 0.f, mx = -3.402823466e+38f, mn = 3.402823466e+38f;
-            for (int t0 = 0; t0 < g.tiles_n; t0 += 8) {
-                float v[8][5];
+            for (int t0 = 0; t0 < g.tiles_n; t0 += 16) {
+                float v[16][5];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
+                for (int j = 0; j < 16; ++j) {
                     const int t = t0 + j < g.tiles_n ? t0 + j : g.tiles_n - 1;  // clamped duplicates are not folded
                     v[j][0] = ld_agent(rowpart + (int64_t)t * g.M + gi);
                     if (FUSED) {
@@ -412,7 +438,7 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
                     }
                 }
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
+                for (int j = 0; j < 16; ++j)
                     if (t0 + j < g.tiles_n) {
                         rs += v[j][0];
                         if (FUSED) {
@@ -451,17 +477,15 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
             g.flags[gi] = f;
             const int cnt = __syncthreads_count(f);
             if (tid == 0) {
-                int* rowcnt = g.tickets + g.tiles_m;
-                int* done = g.tickets + 2 * g.tiles_m;
-                __hip_atomic_store(&rowcnt[bm], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // this tile-row is done: reset its ticket, then one 64-bit atomic both counts the
+                // finished row blocks (high word) and accumulates the flagged rows (low word);
+                // whoever completes the count publishes nflag and leaves the counter zero
                 __hip_atomic_store(&g.tickets[bm], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __builtin_amdgcn_s_waitcnt(0);
-                if (atomicAdd(done, 1) == g.tiles_m - 1) {
-                    int tot = 0;
-                    for (int i = 0; i < g.tiles_m; ++i)
-                        tot += __hip_atomic_load(&rowcnt[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    *g.d_nflag = tot;
-                    __hip_atomic_store(done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                unsigned long long* done = reinterpret_cast<unsigned long long*>(g.tickets + ((g.tiles_m + 1) & ~1));
+                const unsigned long long old = atomicAdd(done, (1ull << 32) | (unsigned long long)(unsigned)cnt);
+                if ((int)(old >> 32) == g.tiles_m - 1) {
+                    *g.d_nflag = (int)(unsigned)(old & 0xffffffffull) + cnt;
+                    __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
         }
@@ -473,8 +497,8 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
 template <typename T, int TRANSB>
 static int gemm16_fast_launch_tb(const GemmArgs& a, int mode, hipStream_t st) {
     const dim3 grid(a.tiles_m * a.tiles_n), block(256);
-    const size_t lds = g16::LDS_BYTES;
     const int fused = a.fused_stats ? 1 : 0;
+    const size_t lds = fused ? g16f::LDS_BYTES_FUSED : g16::LDS_BYTES;
 #define VABFT_G16F_CASE(VF, FU)                                                                            \
     if (mode == VF && fused == FU) {                                                                       \
         auto kern = gemm16_fast_kernel<T, TRANSB, VF, FU != 0>;                                            \

@@ -46,8 +46,8 @@ struct GemmArgs {
     void* rowsum;          // [M] acc
     void* E;               // [M] acc
     int32_t* flags;        // [M]
-    int32_t* tickets;      // [tiles_m] arrival counters, [tiles_m] flag counts, [1] finished row blocks;
-                           // all zero between launches
+    int32_t* tickets;      // [tiles_m] arrival counters, then (8-byte aligned) one 64-bit word:
+                           // finished row blocks << 32 | flagged rows; all zero between launches
     // fused A-side statistics (Algorithm 1 for the rows of A, inside the GEMM)
     int32_t fused_stats;
     const void* Be;   // [K] acc
