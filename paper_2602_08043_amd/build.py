@@ -22,6 +22,15 @@ FLAGS = [
 ]
 
 
+# The FP32 / FP64 kernels need at most 128 accumulator registers: keep them in the ordinary
+# vector register file (VGPR-form MFMA).  Left to its heuristic the compiler puts them in the
+# accumulation file and copies all of them in and out around the MFMAs of every loop iteration.
+EXTRA_FLAGS = {
+    "gemm_f32.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "gemm_f64.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+}
+
+
 def _run(cmd):
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
@@ -37,7 +46,7 @@ def build_library(verbose: bool = True, jobs: int = 8) -> str:
 
     def compile_one(pair):
         src, obj = pair
-        out = _run([hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+        out = _run([hipcc, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj])
         if verbose and out.strip():
             print(out, file=sys.stderr)
         return obj

@@ -7,7 +7,7 @@
 
 namespace vabft {
 
-// rowsum[i] = sum_t rowpart[t][i] in tile order; E = expected - rowsum; flag = !(|E| <= T)
+// rowsum[i] = sum_t rowpart[t][i] in a fixed order; E = expected - rowsum; flag = !(|E| <= T)
 template <typename acc_t>
 __global__ __launch_bounds__(256) void finalize_kernel(const acc_t* __restrict__ rowpart, int tiles_n, int M,
                                                        const acc_t* __restrict__ expected,
@@ -17,8 +17,13 @@ __global__ __launch_bounds__(256) void finalize_kernel(const acc_t* __restrict__
     const int i = blockIdx.x * 256 + threadIdx.x;
     int f = 0;
     if (i < M) {
+        // partials folded four at a time, pairwise inside each group of four
         acc_t s = 0;
-        for (int t = 0; t < tiles_n; ++t) s += rowpart[(int64_t)t * M + i];
+        int t = 0;
+        for (; t + 3 < tiles_n; t += 4)
+            s += (rowpart[(int64_t)t * M + i] + rowpart[(int64_t)(t + 1) * M + i]) +
+                 (rowpart[(int64_t)(t + 2) * M + i] + rowpart[(int64_t)(t + 3) * M + i]);
+        for (; t < tiles_n; ++t) s += rowpart[(int64_t)t * M + i];
         const acc_t e = expected[i] - s;
         f = !(fabs(e) <= T[i]);
         rowsum[i] = s;
@@ -74,7 +79,9 @@ size_t gemm_workspace_bytes(const vabft_problem* p) {
     tile_shape(p->dtype, &bm, &bn);
     const size_t tiles_n = ((size_t)p->N + bn - 1) / bn;
     const bool is16 = p->dtype == VABFT_F16 || p->dtype == VABFT_BF16;
-    return tiles_n * (size_t)p->M * acc_bytes(p->dtype) * (is16 ? 5 : 1);
+    // 16-bit: rowpart + 4 A-statistics partials per tile-column; wide types: two row-sum partials
+    // per tile-column (one per wavefront column)
+    return tiles_n * (size_t)p->M * acc_bytes(p->dtype) * (is16 ? 5 : 2);
 }
 
 __global__ void fill_zero_kernel(uint32_t* p, size_t n) {
@@ -182,12 +189,13 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     }
     if (rc != VABFT_OK || !verify || in_kernel_finalize) return rc;
     const dim3 grid((p->M + 255) / 256), block(256);
+    const int nparts = is16 ? a.tiles_n : 2 * a.tiles_n;
     if (p->dtype == VABFT_F64)
-        finalize_kernel<double><<<grid, block, 0, st>>>((const double*)a.rowpart, a.tiles_n, p->M,
+        finalize_kernel<double><<<grid, block, 0, st>>>((const double*)a.rowpart, nparts, p->M,
                                                         (const double*)d_expected, (const double*)d_T,
                                                         (double*)d_rowsum, (double*)d_E, d_flags, d_nflag);
     else
-        finalize_kernel<float><<<grid, block, 0, st>>>((const float*)a.rowpart, a.tiles_n, p->M,
+        finalize_kernel<float><<<grid, block, 0, st>>>((const float*)a.rowpart, nparts, p->M,
                                                        (const float*)d_expected, (const float*)d_T, (float*)d_rowsum,
                                                        (float*)d_E, d_flags, d_nflag);
     return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
@@ -223,9 +231,20 @@ int vabft_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream
 }
 
 double vabft_default_emax(int32_t dtype, int32_t K, int32_t N) {
+    // The larger of (a) the paper's recommended GPU law (table "Recommended e_max across
+    // platforms", H100 rows) and (b) the law measured on MI355X with these kernels by the paper's
+    // calibration protocol (|N(1,1)| matrices, max |E| / |checksum| over trials, +20 %): the
+    // accumulation order of these kernels gives 3.3 - 7.4 u, slightly above (a) at small n.
     const double n = (double)(K > N ? K : N);
-    if (dtype == VABFT_F64) return 1.0e-17 * sqrt(n) + 2.5e-16;
-    return 5.0e-9 * sqrt(n) + 1.2e-7;
+    double paper, measured;
+    if (dtype == VABFT_F64) {
+        paper = 1.0e-17 * sqrt(n) + 2.5e-16;
+        measured = 5.0e-18 * sqrt(n) + 4.5e-16;
+    } else {
+        paper = 5.0e-9 * sqrt(n) + 1.2e-7;
+        measured = 3.0e-9 * sqrt(n) + 3.0e-7;
+    }
+    return paper > measured ? paper : measured;
 }
 
 int vabft_encode(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S, void* d_workspace,

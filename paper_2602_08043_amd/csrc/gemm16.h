@@ -98,19 +98,26 @@ __device__ __forceinline__ void gemm16_inject(const GemmArgs& g, f32x16_t (&acc)
 }
 
 // Row sums of the wavefront's accumulator tile, taken before quantisation (section 2.2
-// C^{r1'} = C r1 on the tile; section 3.6 fused check): 64 in-register adds per row plus one
-// cross-lane add.  Lanes 0..31 leave the sum of row (wm*128 + mi*32 + lane) over the
+// C^{r1'} = C r1 on the tile; section 3.6 fused check): 63 in-register adds per row, arranged
+// pairwise, plus one cross-lane add.  Lanes 0..31 leave the sum of row (wm*128 + mi*32 + lane) over the
 // wavefront's 128 columns in red[wn][row].
 __device__ __forceinline__ void gemm16_rowsum_to_lds(const f32x16_t (&acc)[4][4], float* red, int wm, int wn, int l32,
                                                      int lh) {
     using namespace g16;
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
-        float s = 0.f;
+        // pairwise over the 16 registers of a tile, then pairwise over the 4 tiles: a short
+        // rounding-error chain (depth 7 with the cross-lane add) instead of 64 sequential adds
+        float t[4];
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni)
+        for (int ni = 0; ni < 4; ++ni) {
+            float q[4];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s += acc[mi][ni][r];
+            for (int k = 0; k < 4; ++k)
+                q[k] = (acc[mi][ni][4 * k] + acc[mi][ni][4 * k + 1]) + (acc[mi][ni][4 * k + 2] + acc[mi][ni][4 * k + 3]);
+            t[ni] = (q[0] + q[1]) + (q[2] + q[3]);
+        }
+        float s = (t[0] + t[1]) + (t[2] + t[3]);
         s += __shfl_xor(s, 32, WAVE);
         if (lh == 0) red[wn * BM + wm * 128 + mi * 32 + l32] = s;
     }

@@ -437,17 +437,27 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
                         v[j][4] = ld_agent(ap + 3 * (int64_t)g.M);
                     }
                 }
+                // fold four at a time, pairwise inside each group (absent tile-columns count as
+                // the neutral element)
 #pragma unroll
                 for (int j = 0; j < 16; ++j)
-                    if (t0 + j < g.tiles_n) {
-                        rs += v[j][0];
-                        if (FUSED) {
-                            sum += v[j][1];
-                            dot += v[j][2];
-                            mx = fmaxf(mx, v[j][3]);
-                            mn = fminf(mn, v[j][4]);
-                        }
+                    if (!(t0 + j < g.tiles_n)) {
+                        v[j][0] = 0.f;
+                        v[j][1] = 0.f;
+                        v[j][2] = 0.f;
+                        v[j][3] = -3.402823466e+38f;
+                        v[j][4] = 3.402823466e+38f;
                     }
+#pragma unroll
+                for (int j = 0; j < 16; j += 4) {
+                    rs += (v[j][0] + v[j + 1][0]) + (v[j + 2][0] + v[j + 3][0]);
+                    if (FUSED) {
+                        sum += (v[j][1] + v[j + 1][1]) + (v[j + 2][1] + v[j + 3][1]);
+                        dot += (v[j][2] + v[j + 1][2]) + (v[j + 2][2] + v[j + 3][2]);
+                        mx = fmaxf(mx, fmaxf(fmaxf(v[j][3], v[j + 1][3]), fmaxf(v[j + 2][3], v[j + 3][3])));
+                        mn = fminf(mn, fminf(fminf(v[j][4], v[j + 1][4]), fminf(v[j + 2][4], v[j + 3][4])));
+                    }
+                }
             }
             float expv, thr;
             if (FUSED) {

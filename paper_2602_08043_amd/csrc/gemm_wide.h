@@ -7,7 +7,9 @@
 // Result layout per MFMA tile (probed on the device): lane l owns column (l % MT);
 //   32x32 (FP32): register r is row 8*(r/4) + 4*(l/32) + r%4
 //   16x16 (FP64): register r is row (l/16) + 4*r
-// so a row sum needs a butterfly over the MT lanes that share the row.
+// The epilogue goes through LDS: each wavefront parks its tile there, one lane per row adds
+// the row in column order (two partial row sums per tile-column, one per wavefront), and C
+// leaves in 16-byte pieces contiguous along rows.
 #pragma once
 #include "gemm_common.h"
 
@@ -38,7 +40,9 @@ template <typename T> constexpr int ldn() { return BN + 16 / (int)sizeof(T); }  
 template <typename T> constexpr int a_elems() { return BM * LDK; }
 template <typename T> constexpr int b_elems() { return (BN * LDK) > (BK * ldn<T>()) ? (BN * LDK) : (BK * ldn<T>()); }
 template <typename T> constexpr int stage_elems() { return a_elems<T>() + b_elems<T>(); }
-template <typename T> constexpr int lds_bytes() { return 2 * stage_elems<T>() * (int)sizeof(T); }
+template <typename T> constexpr int loop_bytes() { return 2 * stage_elems<T>() * (int)sizeof(T); }
+template <typename T> constexpr int epi_bytes() { return 4 * 64 * (64 + 16 / (int)sizeof(T)) * (int)sizeof(T); }
+template <typename T> constexpr int lds_bytes() { return loop_bytes<T>() > epi_bytes<T>() ? loop_bytes<T>() : epi_bytes<T>(); }
 }  // namespace gw
 
 // MODE 0: plain GEMM; 1: fused row-sum check; 2: check plus the fault injector.
@@ -165,83 +169,104 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
         __syncthreads();
     }
 
-    // accumulator element (mi, ni, r): row = row0 + wm*64 + mi*MT + row_of(r, lane), col = col0 + wn*64 + ni*MT + lm
-    if (INJECT) {
-        const InjectArgs& inj = g.inj;
-        if (inj.mode == 1) {
-            for (int e = 0; e < inj.n_list; ++e) {
-                const int fr = inj.d_list[3 * e], fc = inj.d_list[3 * e + 1], fb = inj.d_list[3 * e + 2];
-                if (fr < row0 || fr >= row0 + BM || fc < col0 || fc >= col0 + BN) continue;
-                if (fr >= g.M || fc >= g.N || fb < 0 || fb >= acc_bits<T>()) continue;
-                const int rl = fr - row0, cl = fc - col0;
-                if ((rl >> 6) != wm || (cl >> 6) != wn || (cl % MT) != lm) continue;
-                const int fmi = (rl & 63) / MT, fni = (cl & 63) / MT, rin = rl % MT;
-                T before = 0, after = 0;
-                bool mine = false;
-                static_for<0, TM>([&](auto mi_c) {
-                    static_for<0, TM>([&](auto ni_c) {
-                        static_for<0, NR>([&](auto r_c) {
-                            constexpr int mi = decltype(mi_c)::value, ni = decltype(ni_c)::value,
-                                          r = decltype(r_c)::value;
-                            if (mi == fmi && ni == fni && Cfg::row_of(r, lane) == rin) {
-                                before = acc[mi][ni][r];
-                                after = flip_bit(before, fb);
-                                acc[mi][ni][r] = after;
-                                mine = true;
-                            }
-                        });
-                    });
-                });
-                if (mine) log_fault(inj, fr, fc, fb, (double)before, (double)after);
-            }
-        } else if (inj.mode == 2) {
-            static_for<0, TM>([&](auto mi_c) {
-                static_for<0, TM>([&](auto ni_c) {
-                    static_for<0, NR>([&](auto r_c) {
-                        constexpr int mi = decltype(mi_c)::value, ni = decltype(ni_c)::value, r = decltype(r_c)::value;
-                        const int gi = row0 + wm * 64 + mi * MT + Cfg::row_of(r, lane);
-                        const int gj = col0 + wn * 64 + ni * MT + lm;
-                        if (gi < g.M && gj < g.N) {
-                            const int bit = bernoulli_bit(inj, gi, gj, g.N);
-                            if (bit >= 0) acc[mi][ni][r] = flip_and_log<T>(inj, acc[mi][ni][r], gi, gj, bit);
-                        }
-                    });
-                });
-            });
-        }
-    }
-
-    if (VERIFY) {
-        T* red = smem;  // [2][128]
-#pragma unroll
-        for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-            for (int r = 0; r < NR; ++r) {
-                T s = 0;
-#pragma unroll
-                for (int ni = 0; ni < TM; ++ni) s += acc[mi][ni][r];
-#pragma unroll
-                for (int off = MT / 2; off >= 1; off >>= 1) s += __shfl_xor(s, off, WAVE);
-                if (lm == 0) red[wn * BM + wm * 64 + mi * MT + Cfg::row_of(r, lane)] = s;
-            }
-        __syncthreads();
-        if (tid < BM) {
-            const int gi = row0 + tid;
-            if (gi < g.M) reinterpret_cast<T*>(g.rowpart)[(int64_t)bn * g.M + gi] = red[tid] + red[BM + tid];
-        }
-    }
-
-    T* __restrict__ C = reinterpret_cast<T*>(g.C);
+    // ---- epilogue through LDS ------------------------------------------------------------
+    // Each wavefront parks its 64 x 64 accumulator tile in a private, padded LDS buffer (the
+    // accumulators are only stored, never used as vector operands, so they stay in the
+    // accumulation registers through the main loop).  Element (mi, ni, r) is tile row
+    // mi*MT + row_of(r, lane), tile column ni*MT + lane%MT.  From there: the injector edits
+    // elements in place, lane l sums row l in column order, and rows are copied to C in
+    // 16-byte pieces that are contiguous along a row.
+    constexpr int PITCH = 64 + 16 / (int)sizeof(T);  // elements; 4 banks of skew per row
+    T* tile = smem + wave * (64 * PITCH);
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
         for (int ni = 0; ni < TM; ++ni)
 #pragma unroll
-            for (int r = 0; r < NR; ++r) {
-                const int gi = row0 + wm * 64 + mi * MT + Cfg::row_of(r, lane);
-                const int gj = col0 + wn * 64 + ni * MT + lm;
-                if (!EDGE || (gi < g.M && gj < g.N)) C[(int64_t)gi * g.ldc + gj] = acc[mi][ni][r];
+            for (int r = 0; r < NR; ++r)
+                tile[(mi * MT + Cfg::row_of(r, lane)) * PITCH + ni * MT + lm] = acc[mi][ni][r];
+    // LDS operations of one wavefront complete in order; the compiler must keep that order too
+    asm volatile("" ::: "memory");
+    const int trow0 = row0 + wm * 64, tcol0 = col0 + wn * 64;
+
+    if (INJECT) {
+        const InjectArgs& inj = g.inj;
+        if (inj.mode == 1) {
+            for (int e = 0; e < inj.n_list; ++e) {
+                const int fr = inj.d_list[3 * e], fc = inj.d_list[3 * e + 1], fb = inj.d_list[3 * e + 2];
+                if (fr < trow0 || fr >= trow0 + 64 || fc < tcol0 || fc >= tcol0 + 64) continue;
+                if (fr >= g.M || fc >= g.N || fb < 0 || fb >= acc_bits<T>()) continue;
+                if (lane == 0) {
+                    T* p = tile + (fr - trow0) * PITCH + (fc - tcol0);
+                    const T before = *p, after = flip_bit(before, fb);
+                    *p = after;
+                    log_fault(inj, fr, fc, fb, (double)before, (double)after);
+                }
             }
+        } else if (inj.mode == 2) {
+            const int gi = trow0 + lane;  // lane l walks row l of the tile
+            if (gi < g.M) {
+                for (int c = 0; c < 64; ++c) {
+                    const int gj = tcol0 + c;
+                    if (gj >= g.N) break;
+                    const int bit = bernoulli_bit(inj, gi, gj, g.N);
+                    if (bit >= 0) {
+                        T* p = tile + lane * PITCH + c;
+                        const T before = *p, after = flip_bit(before, bit);
+                        *p = after;
+                        log_fault(inj, gi, gj, bit, (double)before, (double)after);
+                    }
+                }
+            }
+        }
+        asm volatile("" ::: "memory");
+    }
+
+    if (VERIFY) {
+        // row sum of the accumulator tile (section 2.2 C^{r1'} = C r1, before any rounding of C):
+        // lane l adds the 64 columns of row l; partial index 2*bn + wn
+        // (pairwise inside each 16-byte chunk, chunk sums into four rotating accumulators that
+        // are folded pairwise at the end: a short error chain instead of 64 sequential adds)
+        const T* rowp = tile + lane * PITCH;
+        T part[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int c = 0; c < 64; c += V) {
+            T v[V];
+            const raw16 q = *reinterpret_cast<const raw16*>(rowp + c);
+            __builtin_memcpy(v, &q, 16);
+            T cs;
+            if constexpr (V == 2)
+                cs = v[0] + v[1];
+            else
+                cs = (v[0] + v[1]) + (v[2] + v[3]);
+            part[(c / V) & 3] += cs;
+        }
+        const T s = (part[0] + part[1]) + (part[2] + part[3]);
+        const int gi = trow0 + lane;
+        if (gi < g.M) reinterpret_cast<T*>(g.rowpart)[(int64_t)(2 * bn + wn) * g.M + gi] = s;
+    }
+
+    T* __restrict__ C = reinterpret_cast<T*>(g.C);
+    constexpr int CPRW = 64 / V;  // 16-byte chunks per tile row
+#pragma unroll 4
+    for (int it = 0; it < 64 * CPRW / 64; ++it) {
+        const int idx = lane + 64 * it, r = idx / CPRW, c = (idx % CPRW) * V;
+        const raw16 q = *reinterpret_cast<const raw16*>(tile + r * PITCH + c);
+        const int gi = trow0 + r, gj = tcol0 + c;
+        if (!EDGE) {
+            *reinterpret_cast<raw16*>(C + (int64_t)gi * g.ldc + gj) = q;
+        } else if (gi < g.M) {
+            if (g.c_vec_ok && gj + V <= g.N) {
+                *reinterpret_cast<raw16*>(C + (int64_t)gi * g.ldc + gj) = q;
+            } else {
+                T v[V];
+                __builtin_memcpy(v, &q, 16);
+#pragma unroll
+                for (int e = 0; e < V; ++e)
+                    if (gj + e < g.N) C[(int64_t)gi * g.ldc + gj + e] = v[e];
+            }
+        }
+    }
 }
 
 template <typename T>

@@ -22,6 +22,12 @@ OUT_TINY = {"bf16": 2.0 ** -133, "f16": 2.0 ** -24, "f32": 2.0 ** -149, "f64": 5
 OUT_MAX = {"bf16": 3.38e38, "f16": 65504.0, "f32": 3.4e38, "f64": 1.79e308}
 
 
+def _emax(dtype, K, N):
+    """The library's default e_max (a parameter of Algorithm 1; the oracle is given the same value)."""
+    from paper_2602_08043_amd import binding as vb
+    return vb.vabft_default_emax(dtype, K, N)
+
+
 def _tol(dtype):
     return 1e-12 if dtype == "f64" else 1e-5
 
@@ -104,13 +110,30 @@ def test_fault_free_parity_small(dtype, M, N, K, transB):
         vg = _session(M, N, K, dtype, transB)
         vg.run(_dev(A, dtype), _dev(B, dtype))
         r = vg.results()
-        o = orc.verify(A, B, dtype, transB)
+        o = orc.verify(A, B, dtype, transB, e_max=_emax(dtype, K, N))
         check_light(r, o, dtype, M, N, K)
         check_rows(r, o, dtype)
         check_C(r, o, A, B, dtype, transB)
         assert not o["flags"].any()
         assert not r["flags"].any() and r["nflag"] == 0
         assert np.all(np.abs(r["E"]) <= r["T"])
+
+
+@pytest.mark.parametrize("dtype,M,N,K,transB", [("bf16", 512, 512, 512, 0), ("f16", 512, 256, 384, 1),
+                                                 ("f32", 256, 128, 512, 0), ("f64", 256, 128, 64, 1),
+                                                 ("f64", 384, 384, 384, 0)])
+def test_no_false_positive_on_positive_matrices(dtype, M, N, K, transB):
+    """|N(1,1)| inputs (the calibration protocol's matrices, section 3.6): no cancellation, so the
+    relative verification difference is at its largest; the default e_max must still clear it."""
+    for seed in range(6):
+        A, B = _gen(dtype, M, N, K, transB, 40 + seed, "abs_n_1_1")
+        vg = _session(M, N, K, dtype, transB)
+        vg.run_fused(_dev(A, dtype), _dev(B, dtype))
+        r = vg.results()
+        assert r["nflag"] == 0 and not r["flags"].any(), (seed, float((np.abs(r["E"]) / r["T"]).max()))
+        o = orc.verify(A, B, dtype, transB, e_max=_emax(dtype, K, N))
+        check_light(r, o, dtype, M, N, K)
+        check_rows(r, o, dtype)
 
 
 @pytest.mark.parametrize("dtype,M,N,K,transB", [("bf16", 512, 768, 256, 0), ("f16", 300, 520, 200, 1),
@@ -149,7 +172,7 @@ def test_fused_entry_point_parity(dtype, M, N, K, transB):
         print(f"fused case {dtype} {M}x{N}x{K} transB={transB} seed={seed} {dist}", flush=True)
         dA, dB = _dev(A, dtype), _dev(B, dtype)
         vg = _session(M, N, K, dtype, transB)
-        o = orc.verify(A, B, dtype, transB)
+        o = orc.verify(A, B, dtype, transB, e_max=_emax(dtype, K, N))
         for rep in range(2):
             vg.rowsum.fill_(7.0)
             vg.T.fill_(-1.0)
@@ -196,7 +219,7 @@ def test_exact_arithmetic_gives_zero_difference(dtype, transB):
     vg = _session(M, N, K, dtype, transB)
     vg.run(_dev(A, dtype), _dev(B, dtype))
     r = vg.results()
-    o = orc.verify(A, B, dtype, transB)
+    o = orc.verify(A, B, dtype, transB, e_max=_emax(dtype, K, N))
     assert np.array_equal(r["Be"].astype(np.float64), o["Be"])
     assert np.array_equal(r["expected"].astype(np.float64), o["expected"])
     assert np.array_equal(r["rowsum"].astype(np.float64), o["rowsum"])
@@ -218,7 +241,7 @@ def test_explicit_bit_flips(dtype, M, N, K, transB):
     dA, dB = _dev(A, dtype), _dev(B, dtype)
     vg = _session(M, N, K, dtype, transB)
     vg.run(dA, dB)
-    o = orc.verify(A, B, dtype, transB)
+    o = orc.verify(A, B, dtype, transB, e_max=_emax(dtype, K, N))
     acc = _acc_np(dtype)
     nbits = 64 if dtype == "f64" else 32
     hi_bits = list(range(52, 63)) if dtype == "f64" else list(range(20, 31))
@@ -263,7 +286,7 @@ def test_bernoulli_injector_matches_oracle_generator(dtype, M, N, K, transB, rat
     dA, dB = _dev(A, dtype), _dev(B, dtype)
     vg = _session(M, N, K, dtype, transB)
     vg.run(dA, dB)
-    o = orc.verify(A, B, dtype, transB)
+    o = orc.verify(A, B, dtype, transB, e_max=_emax(dtype, K, N))
     acc = _acc_np(dtype)
     lo, hi = (40, 63) if dtype == "f64" else (16, 31)
     seed = 0xC0FFEE
@@ -360,7 +383,7 @@ def test_full_size_sampled(name, variant):
     rows = np.sort(wl.rng(3, 77).choice(M, size=64, replace=False))
     # tile-boundary rows too
     rows = np.unique(np.concatenate([rows, [0, 255, 256, M - 1]]))
-    o = orc.verify(cfg["A"], cfg["B"], dt, tb, rows=rows)
+    o = orc.verify(cfg["A"], cfg["B"], dt, tb, e_max=_emax(dt, K, N), rows=rows)
     check_light(r, o, dt, M, N, K)
     check_rows(r, o, dt, rows)
     check_C(r, o, cfg["A"], cfg["B"], dt, tb, rows)

@@ -37,8 +37,12 @@ def test_struct_layouts_match_header():
 def test_status_strings_and_default_emax(lib):
     assert vb.status_string(0) == "ok"
     assert "workspace" in vb.status_string(vb.VABFT_EWORKSPACE)
-    assert vb.vabft_default_emax("bf16", 4096, 4096) == pytest.approx(5.0e-9 * 64 + 1.2e-7)
-    assert vb.vabft_default_emax("f64", 2048, 2048) == pytest.approx(1.0e-17 * 2048 ** 0.5 + 2.5e-16)
+    # larger of the paper's GPU law and the MI355X-calibrated law, n = max(K, N)
+    for n in (128, 512, 4096, 8192, 65536):
+        paper, meas = 5.0e-9 * n ** 0.5 + 1.2e-7, 3.0e-9 * n ** 0.5 + 3.0e-7
+        assert vb.vabft_default_emax("bf16", n, n) == pytest.approx(max(paper, meas))
+        paper, meas = 1.0e-17 * n ** 0.5 + 2.5e-16, 5.0e-18 * n ** 0.5 + 4.5e-16
+        assert vb.vabft_default_emax("f64", n, n) == pytest.approx(max(paper, meas))
     assert vb.vabft_default_emax("f16", 4096, 11008) == vb.vabft_default_emax("f32", 11008, 4096)
 
 
