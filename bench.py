@@ -25,6 +25,10 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6, "f32": 157.3, "f64": 78.6}  # MI355X dense matrix peaks
 HBM_PEAK_GBPS = 8000.0
 ELEM_BYTES = {"bf16": 2, "f16": 2, "f32": 4, "f64": 8}
+# HBM-side bytes per launch of the verified GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# scaled by the same counters on 1 GiB device copies (profiles/gemm16_fast_bf16_c2_4096_hbm_traffic.md).
+# A counter figure cannot be taken live inside this script; workloads without a profile report null.
+PROFILED_TRAFFIC_BYTES = {"c2_bf16_4096": (2.0 * 99912 + 1.0 * 34953) * 1024}
 
 WORKLOAD_TEXT = {
     "c1_f32_256": "FP32 GEMM M=N=K=256, A,B ~ N(0,1), row-checksum V-ABFT check",
@@ -47,6 +51,9 @@ def main():
     ap.add_argument("--flips-per-bit", type=int, default=16, help="single-bit-flip trials per bit position")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-quality", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain device copies of known size (reference for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path is built and measured on ONE GPU; run with --gpus 1 "
@@ -86,6 +93,16 @@ def main():
         t1.record()
         torch.cuda.synchronize()
         return t0.elapsed_time(t1) / steps  # ms per step
+
+    if args.copy_calibration:
+        # 5 copies of 1 GiB (read 1 GiB + write 1 GiB each): the counters of these dispatches
+        # (the runtime's device-to-device copy kernel) give the KiB-per-count factor
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- bring the GPU to its sustained clocks first (untimed, ~0.3 s of the same steps): the
     #      first milliseconds after idle run at different clocks than a long job does
@@ -170,7 +187,7 @@ def main():
     peak = PEAK_TFLOPS[dt]
     achieved = flops / (gemm_ms * 1e-3) / 1e12
     out["roofline"] = {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                       "traffic": None, "kernel": "vabft_gemm_verified_fused launch (verified GEMM kernel)",
+                       "traffic": PROFILED_TRAFFIC_BYTES.get(args.config), "kernel": "vabft_gemm_verified_fused launch (verified GEMM kernel)",
                        "avg_launch_ms": gemm_ms}
     out["frac_of_peak_whole_path"] = out["value"] / peak
     out["plain_gemm_tflops"] = flops / (ms_plain * 1e-3) / 1e12
