@@ -82,10 +82,6 @@ template <> __device__ __forceinline__ float frag_elem<f16_t>(uint32_t d0, uint3
     return Elem<f16_t>::to_acc((uint16_t)((e & 1) ? (d >> 16) : (d & 0xffffu)));
 }
 
-#ifndef VABFT_G16_READS_PER_SLOT
-#define VABFT_G16_READS_PER_SLOT 1
-#endif
-constexpr int RPS = VABFT_G16_READS_PER_SLOT;  // fragment reads issued per MFMA slot, front-loaded
 constexpr int SRED_OFFSET = 40960;
 // Be values the workgroup will need, cached in LDS behind the two operand stages: one slot of
 // 128 floats per folded unit u (k = 128*u - 16 .. 128*u + 111).
@@ -264,17 +260,11 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
             constexpr int mi = slot >> 2, ni = slot & 3;
             acc[mi][ni] = Mfma16<T>::run(bf[ni], af[mi], acc[mi][ni]);
             __builtin_amdgcn_sched_barrier(0);  // MFMA first, the rest of the slot in its shadow
-            {
-                constexpr int r_lo = slot * RPS < NRD ? slot * RPS : NRD;
-                constexpr int r_hi = (slot + 1) * RPS < NRD ? (slot + 1) * RPS : NRD;
-                static_for<r_lo, r_hi>([&](auto op_c) { frag_op(s_c, ks_c, op_c, naf, nbf); });
-            }
+            if constexpr (slot < NRD) frag_op(s_c, ks_c, slot_c, naf, nbf);  // one read per slot, front-loaded
             if constexpr (LBASE >= 0 && (slot & 1))
                 issue_load(std::integral_constant<int, S ^ 1>{}, std::integral_constant<int, LBASE + slot / 2>{}, ap,
                            bp);
-#ifndef VABFT_LAB_NOSTATS
             if constexpr (FUSED && STATS) stats_elem(af, s_c, q_c, slot_c, skip);
-#endif
             __builtin_amdgcn_sched_barrier(0);
         });
     };
@@ -290,11 +280,7 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) af1[i] = bf1[i] = raw16{{0u, 0u, 0u, 0u}};
     static_for<0, 16>([&](auto l_c) { issue_load(I0{}, l_c, a_base, b_base); });
-#ifdef VABFT_LAB_NOCACHE
-    if (false) {
-#else
     if (FUSED) {
-#endif
         // cache the Be slices of every unit this tile-column folds (the host guarantees they fit)
         float* cache = reinterpret_cast<float*>(smem + BE_CACHE_OFFSET);
         const int nunits = nk >> 1;
@@ -410,16 +396,15 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
             st_agent(ap + 3 * (int64_t)g.M, fminf(sred[3 * BM + tid], sred[7 * BM + tid]));
         }
         // every thread's partials are performed (vmcnt(0)) before the workgroup takes this
-        // tile-row's arrival ticket
+        // tile-row's arrival ticket.  These round trips are short because no workgroup has issued
+        // its C stores yet (all tiles finish together); behind the store burst they would each
+        // cost several microseconds, which is why the check runs before the store and not in its
+        // shadow.
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         if (tid == 0) *s_last = (atomicAdd(&g.tickets[bm], 1) == g.tiles_n - 1);
         __syncthreads();
-#ifdef VABFT_LAB_NOFINAL
-        if (false) {
-#else
         if (*s_last) {
-#endif
             // Combine the tile-column partials in tile order.  The device-scope loads are issued
             // in batches of 16 tile-columns before anything is folded, so their latencies overlap.
             float rs = 0.f, sum = 0.f, dot = 0.f, mx = -3.402823466e+38f, mn = 3.402823466e+38f;
