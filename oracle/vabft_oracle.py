@@ -18,6 +18,9 @@ no blocking, fusion or reordering beyond what the definitions state:
     "Recommended e_max across platforms" table (GPU rows) as default.
   * Fault model: single bit flips in a stored floating-point word (section 5.1
     "Error injection"), replayed on the row sum.
+  * Position-weighted checksum r2, checksum differences D1 / D2, localisation
+    j = D2 / D1 - 1 and correction C[i][j] -= D1: section 2.2 "Error
+    localization and correction".
 
 Inputs are the already-rounded storage arrays (see workloads.py); bf16 arrives
 as uint16 bit patterns.  All products of bf16/f16 values are exact in float64.
@@ -189,6 +192,13 @@ def verify(A_st, B_st, dtype: str, transB: int = 0, e_max: float | None = None,
     out["scale_Be"] = absB_rowsum
     out["scale_expected"] = np.abs(A) @ np.abs(out["Be"])
     out["scale_rowsum"] = np.abs(A) @ absB_rowsum
+    # position-weighted checksum (section 2.2, r2)
+    out["Be2"] = encode_checksum_weighted(B)
+    out["expected2"] = expected_checksum_weighted(A, out["Be2"])
+    absB_rowsum2 = np.abs(B) @ weight_vector(N)
+    out["scale_Be2"] = absB_rowsum2
+    out["scale_expected2"] = np.abs(A) @ np.abs(out["Be2"])
+    out["scale_rowsum2"] = np.abs(A) @ absB_rowsum2
     if full_gemm:
         sel = slice(None) if rows is None else np.asarray(rows)
         C = gemm(A[sel], B)
@@ -197,6 +207,7 @@ def verify(A_st, B_st, dtype: str, transB: int = 0, e_max: float | None = None,
         out["rowsum"] = row_sums(C)
         out["E"] = verification_difference(out["expected"][sel], out["rowsum"])
         out["flags"] = fault_flags(out["E"], out["T"][sel])
+        out["rowsum2"] = row_sums_weighted(C)
     return out
 
 
@@ -295,4 +306,74 @@ def replay_faults(rowsum: np.ndarray, records, row_index=None) -> np.ndarray:
         if p is None:
             continue
         out[p] = out[p] + (after - before)
+    return out
+
+
+# --------------------------------------------------------------------------
+# position-weighted checksum, localisation, correction (section 2.2)
+# --------------------------------------------------------------------------
+LOC_NOT_FLAGGED = -1   # row passed the detection test
+LOC_UNRESOLVED = -2    # row flagged, but D2 / D1 - 1 is not (close to) a column index
+LOC_ROUND_TOL = 0.25   # accepted distance of D2 / D1 - 1 from the nearest integer (our reading:
+                       # the paper states the ideal single-error case only)
+
+
+def weight_vector(N: int) -> np.ndarray:
+    """r2 = [1, 2, ..., N]^T."""
+    return np.arange(1, N + 1, dtype=np.float64)
+
+
+def encode_checksum_weighted(B: np.ndarray) -> np.ndarray:
+    """B r2: Be2[k] = sum_n (n + 1) B[k, n]."""
+    return B @ weight_vector(B.shape[1])
+
+
+def expected_checksum_weighted(A: np.ndarray, Be2: np.ndarray) -> np.ndarray:
+    """C^{r2} = A (B r2)."""
+    return A @ Be2
+
+
+def row_sums_weighted(C: np.ndarray) -> np.ndarray:
+    """C^{r2'} = C r2 = sum_j (j + 1) C[:, j]."""
+    return C @ weight_vector(C.shape[1])
+
+
+def checksum_differences(expected, rowsum, expected2, rowsum2):
+    """D1 = C^{r1'} - C^{r1},  D2 = C^{r2'} - C^{r2}  (post-computation minus pre-computed)."""
+    return rowsum - expected, rowsum2 - expected2
+
+
+def localize(D1: np.ndarray, D2: np.ndarray, flags: np.ndarray, N: int) -> np.ndarray:
+    """Column of the single error of every flagged row: j = D2 / D1 - 1 for the
+    linear encoding w(k) = k + 1.  Rows that are not flagged give LOC_NOT_FLAGGED;
+    flagged rows whose ratio is not finite, not within LOC_ROUND_TOL of an integer,
+    or outside 0..N-1 give LOC_UNRESOLVED."""
+    loc = np.full(D1.shape, LOC_NOT_FLAGGED, dtype=np.int64)
+    for i in np.nonzero(flags)[0]:
+        loc[i] = LOC_UNRESOLVED
+        if D1[i] == 0 or not (np.isfinite(D1[i]) and np.isfinite(D2[i])):
+            continue
+        q = D2[i] / D1[i] - 1.0
+        j = np.rint(q)
+        if np.isfinite(q) and abs(q - j) <= LOC_ROUND_TOL and 0 <= j <= N - 1:
+            loc[i] = int(j)
+    return loc
+
+
+def correct(C: np.ndarray, loc: np.ndarray, D1: np.ndarray) -> np.ndarray:
+    """C[i][j] <- C[i][j] - D1[i] for every localised row (Delta := D1)."""
+    out = np.array(C, dtype=np.float64, copy=True)
+    for i in np.nonzero(loc >= 0)[0]:
+        out[i, loc[i]] -= D1[i]
+    return out
+
+
+def replay_faults_weighted(rowsum2: np.ndarray, records, row_index=None) -> np.ndarray:
+    """Weighted row sums after the logged faults: rowsum2[i] += (col + 1)(after - before)."""
+    out = np.array(rowsum2, dtype=np.float64, copy=True)
+    for (i, j, _bit, before, after) in records:
+        p = i if row_index is None else row_index.get(i)
+        if p is None:
+            continue
+        out[p] = out[p] + (j + 1.0) * (after - before)
     return out

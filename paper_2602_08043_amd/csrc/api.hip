@@ -234,15 +234,16 @@ double vabft_default_emax(int32_t dtype, int32_t K, int32_t N) {
     // The larger of (a) the paper's recommended GPU law (table "Recommended e_max across
     // platforms", H100 rows) and (b) the law measured on MI355X with these kernels by the paper's
     // calibration protocol (|N(1,1)| matrices, max |E| / |checksum| over trials, +20 %): the
-    // accumulation order of these kernels gives 3.3 - 7.4 u, slightly above (a) at small n.
+    // relative difference of these kernels is 3.6 - 9 u over n = 128 .. 8192 (about 100 000 trials per
+    // size), nearly flat in n, which is above (a) at small n.  (b) is the envelope of the +20 % values.
     const double n = (double)(K > N ? K : N);
     double paper, measured;
     if (dtype == VABFT_F64) {
         paper = 1.0e-17 * sqrt(n) + 2.5e-16;
-        measured = 5.0e-18 * sqrt(n) + 4.5e-16;
+        measured = 8.0e-18 * sqrt(n) + 4.6e-16;
     } else {
         paper = 5.0e-9 * sqrt(n) + 1.2e-7;
-        measured = 3.0e-9 * sqrt(n) + 3.0e-7;
+        measured = 3.0e-9 * sqrt(n) + 3.8e-7;
     }
     return paper > measured ? paper : measured;
 }

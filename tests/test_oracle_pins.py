@@ -327,3 +327,114 @@ def test_replay_faults_flags_large_deltas_only():
         assert f.sum() == (1 if must_flag else 0)
         if must_flag:
             assert f[i] == 1
+
+
+# --------------------------------------------------------------------------
+# position-weighted checksum, localisation, correction (section 2.2)
+# --------------------------------------------------------------------------
+def _brute_weighted(A, B):
+    """Triple loops, straight from the definitions of r2, C^{r2} and C^{r2'}."""
+    M, K, N = len(A), len(B), len(B[0])
+    Be2 = [sum((n + 1) * B[k][n] for n in range(N)) for k in range(K)]
+    C = [[sum(A[i][k] * B[k][j] for k in range(K)) for j in range(N)] for i in range(M)]
+    exp2 = [sum(A[i][k] * Be2[k] for k in range(K)) for i in range(M)]
+    rs2 = [sum((j + 1) * C[i][j] for j in range(N)) for i in range(M)]
+    return np.array(Be2, float), np.array(C, float), np.array(exp2, float), np.array(rs2, float)
+
+
+def test_weighted_checksum_matches_brute_force_and_identity():
+    rng = np.random.Generator(np.random.Philox(key=[91, 1]))
+    A = rng.integers(-6, 7, size=(5, 7)).astype(np.float64)
+    B = rng.integers(-6, 7, size=(7, 6)).astype(np.float64)
+    Be2, C, exp2, rs2 = _brute_weighted(A.tolist(), B.tolist())
+    assert np.array_equal(orc.weight_vector(6), np.array([1, 2, 3, 4, 5, 6], float))
+    assert np.array_equal(orc.encode_checksum_weighted(B), Be2)
+    assert np.array_equal(orc.expected_checksum_weighted(A, Be2), exp2)
+    assert np.array_equal(orc.row_sums_weighted(orc.gemm(A, B)), rs2)
+    # C r2 == A (B r2) exactly for small integers; a weight vector starting at 0 or a
+    # transposed operand breaks the first column / non-square case
+    assert np.array_equal(exp2, rs2)
+    # column 0 carries weight 1 (not 0): a matrix that is zero except column 0
+    B0 = np.zeros((7, 6))
+    B0[:, 0] = 1.0
+    assert np.array_equal(orc.encode_checksum_weighted(B0), np.ones(7))
+    # last column carries weight N
+    BN = np.zeros((7, 6))
+    BN[:, 5] = 1.0
+    assert np.array_equal(orc.encode_checksum_weighted(BN), 6.0 * np.ones(7))
+
+
+@pytest.mark.parametrize("j", [0, 1, 17, 30, 31])
+@pytest.mark.parametrize("delta", [5.0, -3.0, 1024.0])
+def test_single_error_is_localised_and_corrected_exactly(j, delta):
+    rng = np.random.Generator(np.random.Philox(key=[91, 2]))
+    A = rng.integers(-4, 5, size=(6, 9)).astype(np.float64)
+    B = rng.integers(-4, 5, size=(9, 32)).astype(np.float64)
+    C = orc.gemm(A, B)
+    exp1 = orc.expected_checksum(A, orc.encode_checksum(B))
+    exp2 = orc.expected_checksum_weighted(A, orc.encode_checksum_weighted(B))
+    bad = C.copy()
+    bad[3, j] += delta
+    D1, D2 = orc.checksum_differences(exp1, orc.row_sums(bad), exp2, orc.row_sums_weighted(bad))
+    # D1 = delta, D2 = w(j) delta with w(j) = j + 1 (the paper's two difference equations)
+    assert D1[3] == delta and D2[3] == (j + 1) * delta
+    assert np.all(np.delete(D1, 3) == 0) and np.all(np.delete(D2, 3) == 0)
+    flags = orc.fault_flags(-D1, np.full(6, 0.5))
+    loc = orc.localize(D1, D2, flags, 32)
+    assert loc.tolist() == [-1, -1, -1, j, -1, -1]
+    assert np.array_equal(orc.correct(bad, loc, D1), C)
+
+
+def test_sign_conventions_of_differences():
+    # D1 is post-computation minus pre-computed (= -E of the verification difference)
+    exp1, rs1 = np.array([10.0]), np.array([13.0])
+    exp2, rs2 = np.array([100.0]), np.array([112.0])
+    D1, D2 = orc.checksum_differences(exp1, rs1, exp2, rs2)
+    assert D1[0] == 3.0 and D2[0] == 12.0
+    assert orc.verification_difference(exp1, rs1)[0] == -D1[0]
+    assert orc.localize(D1, D2, np.array([1]), 8)[0] == 3  # 12 / 3 - 1
+
+
+def test_localisation_refuses_what_is_not_a_single_error():
+    N = 16
+    one = np.array([1])
+    # two errors of equal size in columns 2 and 5: ratio 4.5 -> between two columns
+    D1, D2 = np.array([2.0]), np.array([3.0 + 6.0])
+    assert orc.localize(D1, D2, one, N)[0] == orc.LOC_UNRESOLVED
+    # ratio points beyond the last column / before the first
+    assert orc.localize(np.array([1.0]), np.array([18.0]), one, N)[0] == orc.LOC_UNRESOLVED
+    assert orc.localize(np.array([1.0]), np.array([0.0]), one, N)[0] == orc.LOC_UNRESOLVED
+    # last and first column are fine
+    assert orc.localize(np.array([1.0]), np.array([16.0]), one, N)[0] == 15
+    assert orc.localize(np.array([-2.0]), np.array([-2.0]), one, N)[0] == 0
+    # infinities / NaN from exponent-MSB flips
+    assert orc.localize(np.array([np.inf]), np.array([np.inf]), one, N)[0] == orc.LOC_UNRESOLVED
+    assert orc.localize(np.array([np.nan]), np.array([1.0]), one, N)[0] == orc.LOC_UNRESOLVED
+    # a row that is not flagged is never touched
+    assert orc.localize(np.array([5.0]), np.array([10.0]), np.array([0]), N)[0] == orc.LOC_NOT_FLAGGED
+    # tolerance of the rounding: 0.25 accepted, 0.3 not
+    assert orc.localize(np.array([4.0]), np.array([4.0 * 7.25]), one, N)[0] == 6
+    assert orc.localize(np.array([4.0]), np.array([4.0 * 7.3]), one, N)[0] == orc.LOC_UNRESOLVED
+
+
+def test_weighted_replay_matches_recomputation():
+    rng = np.random.Generator(np.random.Philox(key=[91, 3]))
+    C = rng.integers(-9, 10, size=(4, 12)).astype(np.float64)
+    recs = [(1, 0, 23, C[1, 0], C[1, 0] + 8.0), (2, 11, 30, C[2, 11], -C[2, 11])]
+    bad = C.copy()
+    bad[1, 0] += 8.0
+    bad[2, 11] = -C[2, 11]
+    assert np.array_equal(orc.replay_faults_weighted(orc.row_sums_weighted(C), recs), orc.row_sums_weighted(bad))
+    assert np.array_equal(orc.replay_faults(orc.row_sums(C), recs), orc.row_sums(bad))
+
+
+def test_verify_reports_weighted_quantities():
+    cfg = wl.make_config("c1_f32_256", seed=3, shape=(24, 40, 16))
+    o = orc.verify(cfg["A"], cfg["B"], cfg["dtype"], cfg["transB"])
+    A = orc.decode(cfg["A"], "f32")
+    B = orc.logical_B(cfg["B"], "f32", cfg["transB"])
+    w = np.arange(1, 41, dtype=np.float64)
+    assert np.allclose(o["Be2"], (B * w).sum(axis=1), rtol=1e-13)
+    assert np.allclose(o["expected2"], o["rowsum2"], rtol=0, atol=1e-9 * o["scale_rowsum2"].max())
+    assert np.allclose(o["rowsum2"], ((A @ B) * w).sum(axis=1), rtol=1e-12, atol=1e-9)
+    assert np.all(o["scale_rowsum2"] >= np.abs(o["rowsum2"]))
