@@ -162,6 +162,50 @@ int vabft_gemm_verified_fused(const vabft_problem* p, const void* dA, const void
                               vabft_inject_rec* d_injlog, int32_t* d_ninj, void* d_workspace,
                               size_t workspace_bytes, void* stream);
 
+/* ---- Position-weighted checksum, localisation and correction (section 2.2: r2 = [1..N]^T,
+ * C^{r2} = A (B r2), C^{r2'} = C r2, "Error localization and correction") -------------------
+ * The three calls below are the weighted forms of vabft_encode, vabft_threshold and
+ * vabft_gemm_verified(verify = 1): same arguments, same results, plus one more vector each,
+ * produced in the same pass over the data.  All weighted vectors are in the accumulator type. */
+
+/*   d_Be2 [K] acc : Be2[k] = sum_n (n + 1) * B[k][n]       (the column B r2) */
+int vabft_encode_weighted(const vabft_problem* p, const void* dB, void* d_Be, void* d_Be2,
+                          void* d_bstat, double* d_S, void* d_workspace, size_t workspace_bytes,
+                          void* stream);
+
+/*   d_expected2 [M] acc : sum_k A[m][k] * Be2[k]            (C^{r2}) */
+int vabft_threshold_weighted(const vabft_problem* p, const void* dA, const void* d_Be,
+                             const void* d_Be2, const double* d_S, double e_max, double c_sigma,
+                             void* d_astat, void* d_expected, void* d_expected2, void* d_T,
+                             void* stream);
+
+/*   d_rowsum2 [M] acc : sum_j (j + 1) * acc[i][j] on the accumulator tile before quantisation
+ *                       (C^{r2'}), after the injector if one is given */
+int vabft_gemm_verified_weighted(const vabft_problem* p, const void* dA, const void* dB, void* dC,
+                                 const void* d_expected, const void* d_T, const vabft_inject* inj,
+                                 void* d_rowsum, void* d_rowsum2, void* d_E, int32_t* d_flags,
+                                 int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
+                                 void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* Localise and (correct == 1) correct the error of every flagged row under the paper's
+ * single-error-per-row model: D1 = rowsum - expected, D2 = rowsum2 - expected2,
+ * column j = D2 / D1 - 1 (linear weights w(k) = k + 1), correction C[i][j] <- C[i][j] - D1.
+ *   d_loc   [M] int32: -1 row not flagged; -2 flagged, but D2 / D1 - 1 is not finite, is further
+ *                      than 0.25 from an integer, or lies outside 0..N-1 (more than one error in
+ *                      the row, or an error too close to the rounding noise of the weighted
+ *                      sums): such a row has to be recomputed; otherwise the column j.
+ *   d_delta [M] acc  : D1 for flagged rows, 0 otherwise.
+ *   d_ncorrected [1] : number of elements rewritten (0 when correct == 0).
+ * The correction acts on the stored C: the element is read, converted to the accumulator type,
+ * D1 is subtracted and the result is rounded back to `dtype`.  For a 16-bit C the corrupted
+ * value was already rounded to 8 (BF16) or 11 (FP16) significant bits, so the corrected
+ * element is only as accurate as one unit in the last place of the CORRUPTED value.  Run after
+ * vabft_gemm_verified_weighted on the same stream. */
+int vabft_locate_correct(const vabft_problem* p, void* dC, const void* d_expected,
+                         const void* d_expected2, const void* d_rowsum, const void* d_rowsum2,
+                         const int32_t* d_flags, int32_t correct, int32_t* d_loc, void* d_delta,
+                         int32_t* d_ncorrected, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,7 +18,9 @@ VABFT_F64, VABFT_F32, VABFT_F16, VABFT_BF16 = range(4)
 DTYPE_CODE = {"f64": VABFT_F64, "f32": VABFT_F32, "f16": VABFT_F16, "bf16": VABFT_BF16}
 
 EXPORTS = ("vabft_status_string", "vabft_workspace_bytes", "vabft_workspace_init", "vabft_default_emax",
-           "vabft_encode", "vabft_threshold", "vabft_gemm_verified", "vabft_gemm_verified_fused")
+           "vabft_encode", "vabft_threshold", "vabft_gemm_verified", "vabft_gemm_verified_fused",
+           "vabft_encode_weighted", "vabft_threshold_weighted", "vabft_gemm_verified_weighted",
+           "vabft_locate_correct")
 
 
 class Problem(Structure):
@@ -80,6 +82,19 @@ def load(path: str | None = None):
                                               c_double, c_double, c_void_p, c_void_p, c_void_p, POINTER(Inject),
                                               c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                               c_size_t, c_void_p]
+    lib.vabft_encode_weighted.restype = ctypes.c_int
+    lib.vabft_encode_weighted.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                          c_size_t, c_void_p]
+    lib.vabft_threshold_weighted.restype = ctypes.c_int
+    lib.vabft_threshold_weighted.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_double,
+                                             c_double, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.vabft_gemm_verified_weighted.restype = ctypes.c_int
+    lib.vabft_gemm_verified_weighted.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                                 POINTER(Inject), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                                 c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.vabft_locate_correct.restype = ctypes.c_int
+    lib.vabft_locate_correct.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                         c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
     if path is None:
         _lib = lib
     return lib
@@ -142,3 +157,32 @@ def vabft_gemm_verified_fused(p: Problem, dA, dB, dC, d_Be, d_S, e_max, c_sigma,
                                           d_expected, d_T, byref(inj) if inj is not None else None, d_rowsum, d_E,
                                           d_flags, d_nflag, d_injlog, d_ninj, d_workspace, workspace_bytes, stream)
     return _check(rc, "vabft_gemm_verified_fused", check)
+
+
+def vabft_encode_weighted(p: Problem, dB, d_Be, d_Be2, d_bstat, d_S, d_workspace, workspace_bytes, stream=None,
+                          check=True) -> int:
+    rc = load().vabft_encode_weighted(byref(p), dB, d_Be, d_Be2, d_bstat, d_S, d_workspace, workspace_bytes, stream)
+    return _check(rc, "vabft_encode_weighted", check)
+
+
+def vabft_threshold_weighted(p: Problem, dA, d_Be, d_Be2, d_S, e_max, c_sigma, d_astat, d_expected, d_expected2, d_T,
+                             stream=None, check=True) -> int:
+    rc = load().vabft_threshold_weighted(byref(p), dA, d_Be, d_Be2, d_S, float(e_max), float(c_sigma), d_astat,
+                                         d_expected, d_expected2, d_T, stream)
+    return _check(rc, "vabft_threshold_weighted", check)
+
+
+def vabft_gemm_verified_weighted(p: Problem, dA, dB, dC, d_expected, d_T, inj, d_rowsum, d_rowsum2, d_E, d_flags,
+                                 d_nflag, d_injlog, d_ninj, d_workspace, workspace_bytes, stream=None,
+                                 check=True) -> int:
+    rc = load().vabft_gemm_verified_weighted(byref(p), dA, dB, dC, d_expected, d_T,
+                                             byref(inj) if inj is not None else None, d_rowsum, d_rowsum2, d_E,
+                                             d_flags, d_nflag, d_injlog, d_ninj, d_workspace, workspace_bytes, stream)
+    return _check(rc, "vabft_gemm_verified_weighted", check)
+
+
+def vabft_locate_correct(p: Problem, dC, d_expected, d_expected2, d_rowsum, d_rowsum2, d_flags, correct, d_loc,
+                         d_delta, d_ncorrected, stream=None, check=True) -> int:
+    rc = load().vabft_locate_correct(byref(p), dC, d_expected, d_expected2, d_rowsum, d_rowsum2, d_flags,
+                                     int(correct), d_loc, d_delta, d_ncorrected, stream)
+    return _check(rc, "vabft_locate_correct", check)

@@ -13,10 +13,22 @@ __global__ __launch_bounds__(256) void finalize_kernel(const acc_t* __restrict__
                                                        const acc_t* __restrict__ expected,
                                                        const acc_t* __restrict__ T, acc_t* __restrict__ rowsum,
                                                        acc_t* __restrict__ E, int32_t* __restrict__ flags,
-                                                       int32_t* __restrict__ nflag) {
+                                                       int32_t* __restrict__ nflag,
+                                                       const acc_t* __restrict__ rowpart2,
+                                                       acc_t* __restrict__ rowsum2) {
     const int i = blockIdx.x * 256 + threadIdx.x;
     int f = 0;
     if (i < M) {
+        if (rowsum2) {
+            // position-weighted row sums C r2, same fold
+            acc_t s2 = 0;
+            int t = 0;
+            for (; t + 3 < tiles_n; t += 4)
+                s2 += (rowpart2[(int64_t)t * M + i] + rowpart2[(int64_t)(t + 1) * M + i]) +
+                      (rowpart2[(int64_t)(t + 2) * M + i] + rowpart2[(int64_t)(t + 3) * M + i]);
+            for (; t < tiles_n; ++t) s2 += rowpart2[(int64_t)t * M + i];
+            rowsum2[i] = s2;
+        }
         // partials folded four at a time, pairwise inside each group of four
         acc_t s = 0;
         int t = 0;
@@ -35,6 +47,77 @@ __global__ __launch_bounds__(256) void finalize_kernel(const acc_t* __restrict__
 }
 
 __global__ void zero_int_kernel(int32_t* p) { *p = 0; }
+
+// one stored element of C, read and written in the accumulator type
+template <typename T> struct CElem;
+template <> struct CElem<bf16_t> {
+    using store_t = uint16_t;
+    static __device__ __forceinline__ float get(const store_t* p) { return Elem<bf16_t>::to_acc(*p); }
+    static __device__ __forceinline__ void put(store_t* p, float v) { *p = Elem<bf16_t>::from_acc(v); }
+};
+template <> struct CElem<f16_t> {
+    using store_t = uint16_t;
+    static __device__ __forceinline__ float get(const store_t* p) { return Elem<f16_t>::to_acc(*p); }
+    static __device__ __forceinline__ void put(store_t* p, float v) { *p = Elem<f16_t>::from_acc(v); }
+};
+template <> struct CElem<float> {
+    using store_t = float;
+    static __device__ __forceinline__ float get(const store_t* p) { return *p; }
+    static __device__ __forceinline__ void put(store_t* p, float v) { *p = v; }
+};
+template <> struct CElem<double> {
+    using store_t = double;
+    static __device__ __forceinline__ double get(const store_t* p) { return *p; }
+    static __device__ __forceinline__ void put(store_t* p, double v) { *p = v; }
+};
+
+// Localisation and correction under the single-error-per-row model (paper section 2.2 "Error
+// localization and correction"): D1 = C^{r1'} - C^{r1}, D2 = C^{r2'} - C^{r2}, column
+// j = D2 / D1 - 1 for the linear weights w(k) = k + 1, correction C[i][j] -= D1.
+// loc[i]: -1 row not flagged; -2 flagged but the ratio is not finite, further than 0.25 from an
+// integer or outside 0..N-1 (more than one error, or an error too close to the rounding noise of
+// the weighted sums); else the column.  delta[i] = D1 for flagged rows, 0 otherwise.
+template <typename T>
+__global__ __launch_bounds__(256) void locate_correct_kernel(void* __restrict__ Cv, int M, int N, int64_t ldc,
+                                                             const typename Elem<T>::acc_t* __restrict__ expected,
+                                                             const typename Elem<T>::acc_t* __restrict__ expected2,
+                                                             const typename Elem<T>::acc_t* __restrict__ rowsum,
+                                                             const typename Elem<T>::acc_t* __restrict__ rowsum2,
+                                                             const int32_t* __restrict__ flags, int correct,
+                                                             int32_t* __restrict__ loc,
+                                                             typename Elem<T>::acc_t* __restrict__ delta,
+                                                             int32_t* __restrict__ ncorrected) {
+    using acc_t = typename Elem<T>::acc_t;
+    using store_t = typename CElem<T>::store_t;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    int done = 0;
+    if (i < M) {
+        int l = -1;
+        acc_t d = 0;
+        if (flags[i]) {
+            l = -2;
+            const double d1 = (double)rowsum[i] - (double)expected[i];
+            const double d2 = (double)rowsum2[i] - (double)expected2[i];
+            d = (acc_t)d1;
+            if (d1 != 0.0 && isfinite(d1) && isfinite(d2)) {
+                const double q = d2 / d1 - 1.0;
+                const double j = rint(q);
+                if (isfinite(q) && fabs(q - j) <= 0.25 && j >= 0.0 && j <= (double)(N - 1)) {
+                    l = (int)j;
+                    if (correct) {
+                        store_t* c = reinterpret_cast<store_t*>(Cv) + (int64_t)i * ldc + l;
+                        CElem<T>::put(c, CElem<T>::get(c) - d);
+                        done = 1;
+                    }
+                }
+            }
+        }
+        loc[i] = l;
+        delta[i] = d;
+    }
+    const int cnt = __syncthreads_count(done);
+    if (threadIdx.x == 0 && cnt) atomicAdd(ncorrected, cnt);
+}
 
 static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -79,9 +162,9 @@ size_t gemm_workspace_bytes(const vabft_problem* p) {
     tile_shape(p->dtype, &bm, &bn);
     const size_t tiles_n = ((size_t)p->N + bn - 1) / bn;
     const bool is16 = p->dtype == VABFT_F16 || p->dtype == VABFT_BF16;
-    // 16-bit: rowpart + 4 A-statistics partials per tile-column; wide types: two row-sum partials
-    // per tile-column (one per wavefront column)
-    return tiles_n * (size_t)p->M * acc_bytes(p->dtype) * (is16 ? 5 : 2);
+    // 16-bit: rowpart + 4 A-statistics partials + weighted rowpart per tile-column; wide types: two
+    // row-sum partials per tile-column (one per wavefront column), plain and weighted
+    return tiles_n * (size_t)p->M * acc_bytes(p->dtype) * (is16 ? 6 : 4);
 }
 
 __global__ void fill_zero_kernel(uint32_t* p, size_t n) {
@@ -95,9 +178,9 @@ void workspace_init_launch(void* ws, size_t bytes, hipStream_t st) {
 }
 
 int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* dC, void* d_expected, void* d_T,
-                  int verify, const FusedArgs* fused, const vabft_inject* inj, void* d_rowsum, void* d_E,
-                  int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj, void* ws,
-                  hipStream_t st) {
+                  int verify, const FusedArgs* fused, const vabft_inject* inj, void* d_rowsum, void* d_rowsum2,
+                  void* d_E, int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
+                  void* ws, hipStream_t st) {
     GemmArgs a;
     a.A = dA;
     a.B = dB;
@@ -121,6 +204,9 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     a.tickets = reinterpret_cast<int32_t*>(wsb);
     a.rowpart = ws ? wsb + tickets_bytes(p) : nullptr;
     a.apart = ws ? wsb + tickets_bytes(p) + (size_t)a.tiles_n * p->M * ab : nullptr;
+    // weighted partials: behind rowpart + apart (16-bit) resp. behind the two plain partials (wide)
+    a.rowpart2 = ws ? wsb + tickets_bytes(p) + (size_t)a.tiles_n * p->M * ab * (is16 ? 5 : 2) : nullptr;
+    a.rowsum2 = d_rowsum2;
     a.d_nflag = d_nflag;
     a.expected = d_expected;
     a.T = d_T;
@@ -169,13 +255,13 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
             a.c_sigma = fused->c_sigma;
             a.astat = fused->d_astat;
         } else {
-            const int rc = threshold_dispatch(p, dA, fused->d_Be, fused->d_S, fused->e_max, fused->c_sigma,
-                                              fused->d_astat, d_expected, d_T, st);
+            const int rc = threshold_dispatch(p, dA, fused->d_Be, nullptr, fused->d_S, fused->e_max, fused->c_sigma,
+                                              fused->d_astat, d_expected, nullptr, d_T, st);
             if (rc != VABFT_OK) return rc;
         }
     }
     int rc;
-    const int mode = !verify ? 0 : (a.inj.mode != 0 ? 2 : 1);
+    const int mode = !verify ? 0 : (a.inj.mode != 0 ? 2 : (d_rowsum2 ? 3 : 1));
     switch (p->dtype) {
         case VABFT_BF16:
             rc = p->transB ? gemm16_launch_bf16_nt(a, mode, edge, st) : gemm16_launch_bf16_nn(a, mode, edge, st);
@@ -193,11 +279,13 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     if (p->dtype == VABFT_F64)
         finalize_kernel<double><<<grid, block, 0, st>>>((const double*)a.rowpart, nparts, p->M,
                                                         (const double*)d_expected, (const double*)d_T,
-                                                        (double*)d_rowsum, (double*)d_E, d_flags, d_nflag);
+                                                        (double*)d_rowsum, (double*)d_E, d_flags, d_nflag,
+                                                        (const double*)a.rowpart2, (double*)d_rowsum2);
     else
         finalize_kernel<float><<<grid, block, 0, st>>>((const float*)a.rowpart, nparts, p->M,
                                                        (const float*)d_expected, (const float*)d_T, (float*)d_rowsum,
-                                                       (float*)d_E, d_flags, d_nflag);
+                                                       (float*)d_E, d_flags, d_nflag, (const float*)a.rowpart2,
+                                                       (float*)d_rowsum2);
     return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
 }
 
@@ -258,7 +346,20 @@ int vabft_encode(const vabft_problem* p, const void* dB, void* d_Be, void* d_bst
     if (need && (!d_workspace || workspace_bytes < tickets_bytes(p) + need || !aligned_to(d_workspace, 16)))
         return VABFT_EWORKSPACE;
     void* scratch = d_workspace ? reinterpret_cast<unsigned char*>(d_workspace) + tickets_bytes(p) : nullptr;
-    return encode_dispatch(p, dB, d_Be, d_bstat, d_S, scratch, (hipStream_t)stream);
+    return encode_dispatch(p, dB, d_Be, nullptr, d_bstat, d_S, scratch, (hipStream_t)stream);
+}
+
+int vabft_encode_weighted(const vabft_problem* p, const void* dB, void* d_Be, void* d_Be2, void* d_bstat, double* d_S,
+                          void* d_workspace, size_t workspace_bytes, void* stream) {
+    if (!problem_ok(p) || !dB || !d_Be || !d_Be2 || !d_bstat || !d_S) return VABFT_EINVAL;
+    if (!aligned_to(dB, elem_bytes(p->dtype)) || !aligned_to(d_Be, acc_bytes(p->dtype)) ||
+        !aligned_to(d_Be2, acc_bytes(p->dtype)) || !aligned_to(d_bstat, acc_bytes(p->dtype)) || !aligned_to(d_S, 8))
+        return VABFT_EINVAL;
+    const size_t need = encode_workspace_bytes(p);
+    if (need && (!d_workspace || workspace_bytes < tickets_bytes(p) + need || !aligned_to(d_workspace, 16)))
+        return VABFT_EWORKSPACE;
+    void* scratch = d_workspace ? reinterpret_cast<unsigned char*>(d_workspace) + tickets_bytes(p) : nullptr;
+    return encode_dispatch(p, dB, d_Be, d_Be2, d_bstat, d_S, scratch, (hipStream_t)stream);
 }
 
 int vabft_threshold(const vabft_problem* p, const void* dA, const void* d_Be, const double* d_S, double e_max,
@@ -269,7 +370,23 @@ int vabft_threshold(const vabft_problem* p, const void* dA, const void* d_Be, co
     if (!aligned_to(dA, elem_bytes(p->dtype)) || !aligned_to(d_Be, ab) || !aligned_to(d_S, 8) ||
         !aligned_to(d_astat, ab) || !aligned_to(d_expected, ab) || !aligned_to(d_T, ab))
         return VABFT_EINVAL;
-    return threshold_dispatch(p, dA, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T, (hipStream_t)stream);
+    return threshold_dispatch(p, dA, d_Be, nullptr, d_S, e_max, c_sigma, d_astat, d_expected, nullptr, d_T,
+                              (hipStream_t)stream);
+}
+
+int vabft_threshold_weighted(const vabft_problem* p, const void* dA, const void* d_Be, const void* d_Be2,
+                             const double* d_S, double e_max, double c_sigma, void* d_astat, void* d_expected,
+                             void* d_expected2, void* d_T, void* stream) {
+    if (!problem_ok(p) || !dA || !d_Be || !d_Be2 || !d_S || !d_astat || !d_expected || !d_expected2 || !d_T)
+        return VABFT_EINVAL;
+    if (!(e_max > 0.0) || !(c_sigma >= 0.0) || !isfinite(e_max) || !isfinite(c_sigma)) return VABFT_EINVAL;
+    const size_t ab = acc_bytes(p->dtype);
+    if (!aligned_to(dA, elem_bytes(p->dtype)) || !aligned_to(d_Be, ab) || !aligned_to(d_Be2, ab) ||
+        !aligned_to(d_S, 8) || !aligned_to(d_astat, ab) || !aligned_to(d_expected, ab) ||
+        !aligned_to(d_expected2, ab) || !aligned_to(d_T, ab))
+        return VABFT_EINVAL;
+    return threshold_dispatch(p, dA, d_Be, d_Be2, d_S, e_max, c_sigma, d_astat, d_expected, d_expected2, d_T,
+                              (hipStream_t)stream);
 }
 
 static int check_gemm_args(const vabft_problem* p, const void* dA, const void* dB, void* dC, int verify,
@@ -312,7 +429,52 @@ int vabft_gemm_verified(const vabft_problem* p, const void* dA, const void* dB, 
                                    d_injlog, d_ninj, d_workspace, workspace_bytes);
     if (rc != VABFT_OK) return rc;
     return gemm_dispatch(p, dA, dB, dC, const_cast<void*>(d_expected), const_cast<void*>(d_T), verify, nullptr, inj,
-                         d_rowsum, d_E, d_flags, d_nflag, d_injlog, d_ninj, d_workspace, (hipStream_t)stream);
+                         d_rowsum, nullptr, d_E, d_flags, d_nflag, d_injlog, d_ninj, d_workspace, (hipStream_t)stream);
+}
+
+int vabft_gemm_verified_weighted(const vabft_problem* p, const void* dA, const void* dB, void* dC,
+                                 const void* d_expected, const void* d_T, const vabft_inject* inj, void* d_rowsum,
+                                 void* d_rowsum2, void* d_E, int32_t* d_flags, int32_t* d_nflag,
+                                 vabft_inject_rec* d_injlog, int32_t* d_ninj, void* d_workspace,
+                                 size_t workspace_bytes, void* stream) {
+    const int rc = check_gemm_args(p, dA, dB, dC, 1, inj, d_expected, d_T, d_rowsum, d_E, d_flags, d_nflag, d_injlog,
+                                   d_ninj, d_workspace, workspace_bytes);
+    if (rc != VABFT_OK) return rc;
+    if (!d_rowsum2 || !aligned_to(d_rowsum2, acc_bytes(p->dtype))) return VABFT_EINVAL;
+    return gemm_dispatch(p, dA, dB, dC, const_cast<void*>(d_expected), const_cast<void*>(d_T), 1, nullptr, inj,
+                         d_rowsum, d_rowsum2, d_E, d_flags, d_nflag, d_injlog, d_ninj, d_workspace,
+                         (hipStream_t)stream);
+}
+
+int vabft_locate_correct(const vabft_problem* p, void* dC, const void* d_expected, const void* d_expected2,
+                         const void* d_rowsum, const void* d_rowsum2, const int32_t* d_flags, int32_t correct,
+                         int32_t* d_loc, void* d_delta, int32_t* d_ncorrected, void* stream) {
+    if (!problem_ok(p) || !dC || !d_expected || !d_expected2 || !d_rowsum || !d_rowsum2 || !d_flags || !d_loc ||
+        !d_delta || !d_ncorrected)
+        return VABFT_EINVAL;
+    if (correct != 0 && correct != 1) return VABFT_EINVAL;
+    const size_t ab = acc_bytes(p->dtype);
+    if (!aligned_to(dC, elem_bytes(p->dtype)) || !aligned_to(d_expected, ab) || !aligned_to(d_expected2, ab) ||
+        !aligned_to(d_rowsum, ab) || !aligned_to(d_rowsum2, ab) || !aligned_to(d_flags, 4) || !aligned_to(d_loc, 4) ||
+        !aligned_to(d_delta, ab) || !aligned_to(d_ncorrected, 4))
+        return VABFT_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid((p->M + 255) / 256), block(256);
+    zero_int_kernel<<<1, 1, 0, st>>>(d_ncorrected);
+#define VABFT_LOC_CASE(T, A)                                                                                     \
+    locate_correct_kernel<T><<<grid, block, 0, st>>>(dC, p->M, p->N, p->ldc, (const A*)d_expected,               \
+                                                     (const A*)d_expected2, (const A*)d_rowsum,                  \
+                                                     (const A*)d_rowsum2, d_flags, correct, d_loc, (A*)d_delta,  \
+                                                     d_ncorrected)
+    switch (p->dtype) {
+        case VABFT_F64: VABFT_LOC_CASE(double, double); break;
+        case VABFT_F32: VABFT_LOC_CASE(float, float); break;
+        case VABFT_F16: VABFT_LOC_CASE(f16_t, float); break;
+        case VABFT_BF16: VABFT_LOC_CASE(bf16_t, float); break;
+        default: return VABFT_EINVAL;
+    }
+#undef VABFT_LOC_CASE
+    return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
 }
 
 int vabft_gemm_verified_fused(const vabft_problem* p, const void* dA, const void* dB, void* dC, const void* d_Be,
@@ -333,8 +495,8 @@ int vabft_gemm_verified_fused(const vabft_problem* p, const void* dA, const void
     f.e_max = e_max;
     f.c_sigma = c_sigma;
     f.d_astat = d_astat;
-    return gemm_dispatch(p, dA, dB, dC, d_expected, d_T, 1, &f, inj, d_rowsum, d_E, d_flags, d_nflag, d_injlog, d_ninj,
-                         d_workspace, (hipStream_t)stream);
+    return gemm_dispatch(p, dA, dB, dC, d_expected, d_T, 1, &f, inj, d_rowsum, nullptr, d_E, d_flags, d_nflag,
+                         d_injlog, d_ninj, d_workspace, (hipStream_t)stream);
 }
 
 }  // extern "C"

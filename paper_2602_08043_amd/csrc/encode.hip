@@ -57,9 +57,11 @@ template <> struct Unpack<double> {
 // ---------------------------------------------------------------------------
 // B stored K x N: one wavefront reduces one row k
 // ---------------------------------------------------------------------------
-template <typename T>
+// W: also the position-weighted checksum B*r2, r2 = [1..N] (section 2.2): Be2[k] = sum_n (n+1) B[k,n].
+template <typename T, bool W>
 __global__ __launch_bounds__(256) void encode_rows_kernel(const void* __restrict__ B, int K, int N, int64_t ldb,
                                                           typename Elem<T>::acc_t* __restrict__ Be,
+                                                          typename Elem<T>::acc_t* __restrict__ Be2,
                                                           typename Elem<T>::acc_t* __restrict__ bstat, int vec_ok) {
     using acc_t = typename Elem<T>::acc_t;
     constexpr int V = Elem<T>::vec;
@@ -67,7 +69,7 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const void* __restrict
     const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (k >= K) return;
     const char* row = reinterpret_cast<const char*>(B) + (int64_t)k * ldb * Elem<T>::bytes;
-    acc_t sum = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
+    acc_t sum = 0, sum2 = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
     int done = 0;
     if (vec_ok) {
         const int nchunks = N / V;
@@ -87,6 +89,7 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const void* __restrict
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
                     sum += v[u][e];
+                    if constexpr (W) sum2 = fma((acc_t)((c + 64 * u) * V + e + 1), v[u][e], sum2);
                     mx = v[u][e] > mx ? v[u][e] : mx;
                     mn = v[u][e] < mn ? v[u][e] : mn;
                 }
@@ -98,6 +101,7 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const void* __restrict
 #pragma unroll
             for (int e = 0; e < V; ++e) {
                 sum += v[e];
+                if constexpr (W) sum2 = fma((acc_t)(c * V + e + 1), v[e], sum2);
                 mx = v[e] > mx ? v[e] : mx;
                 mn = v[e] < mn ? v[e] : mn;
             }
@@ -107,12 +111,17 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const void* __restrict
     for (int n = done + lane; n < N; n += 64) {
         acc_t x = Unpack<T>::one(row, n);
         sum += x;
+        if constexpr (W) sum2 = fma((acc_t)(n + 1), x, sum2);
         mx = x > mx ? x : mx;
         mn = x < mn ? x : mn;
     }
     sum = wave_sum(sum);
     mx = wave_max(mx);
     mn = wave_min(mn);
+    if constexpr (W) {
+        sum2 = wave_sum(sum2);
+        if (lane == 0) Be2[k] = sum2;
+    }
     if (lane == 0) {
         Be[k] = sum;
         bstat[3 * (int64_t)k + 0] = mx;
@@ -124,23 +133,24 @@ __global__ __launch_bounds__(256) void encode_rows_kernel(const void* __restrict
 // ---------------------------------------------------------------------------
 // B stored N x K (weight layout): column reduction in two steps.
 // Step 1: block (kx, ny) reduces rows [ny*rows_per_block, ...) of 64*V columns.
-// part layout: [nsplit][3][K] (sum, max, min).
+// part layout: [nsplit][4][K] (sum, max, min, weighted sum; the last only when W).
 // ---------------------------------------------------------------------------
-template <typename T>
+template <typename T, bool W>
 __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict__ Bt, int K, int N, int64_t ldb,
                                                           int rows_per_block,
                                                           typename Elem<T>::acc_t* __restrict__ part, int vec_ok) {
     using acc_t = typename Elem<T>::acc_t;
     constexpr int V = Elem<T>::vec;
-    __shared__ acc_t red[3][3][64 * V];  // waves 1..3 park their partials here
+    __shared__ acc_t red[3][W ? 4 : 3][64 * V];  // waves 1..3 park their partials here
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int k0 = (blockIdx.x * 64 + lane) * V;
     const int n_begin = blockIdx.y * rows_per_block;
     const int n_end = min(N, n_begin + rows_per_block);
-    acc_t sum[V], mx[V], mn[V];
+    acc_t sum[V], sum2[V], mx[V], mn[V];
 #pragma unroll
     for (int e = 0; e < V; ++e) {
         sum[e] = 0;
+        sum2[e] = 0;
         mx[e] = -type_max<acc_t>();
         mn[e] = type_max<acc_t>();
     }
@@ -156,9 +166,11 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
             for (int u = 0; u < 4; ++u) {
                 acc_t v[V];
                 Unpack<T>::run(r[u], v);
+                const acc_t w = (acc_t)(n + 4 * u + 1);
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
                     sum[e] += v[e];
+                    if constexpr (W) sum2[e] = fma(w, v[e], sum2[e]);
                     mx[e] = v[e] > mx[e] ? v[e] : mx[e];
                     mn[e] = v[e] < mn[e] ? v[e] : mn[e];
                 }
@@ -168,9 +180,11 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
             raw16 r0 = ld16(reinterpret_cast<const char*>(Bt) + ((int64_t)n * ldb + k0) * Elem<T>::bytes);
             acc_t v[V];
             Unpack<T>::run(r0, v);
+            const acc_t w = (acc_t)(n + 1);
 #pragma unroll
             for (int e = 0; e < V; ++e) {
                 sum[e] += v[e];
+                if constexpr (W) sum2[e] = fma(w, v[e], sum2[e]);
                 mx[e] = v[e] > mx[e] ? v[e] : mx[e];
                 mn[e] = v[e] < mn[e] ? v[e] : mn[e];
             }
@@ -182,6 +196,7 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
                 if (k0 + e < K) {
                     acc_t x = Unpack<T>::one(Bt, (int64_t)n * ldb + k0 + e);
                     sum[e] += x;
+                    if constexpr (W) sum2[e] = fma((acc_t)(n + 1), x, sum2[e]);
                     mx[e] = x > mx[e] ? x : mx[e];
                     mn[e] = x < mn[e] ? x : mn[e];
                 }
@@ -194,6 +209,7 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
             red[wave - 1][0][lane * V + e] = sum[e];
             red[wave - 1][1][lane * V + e] = mx[e];
             red[wave - 1][2][lane * V + e] = mn[e];
+            if constexpr (W) red[wave - 1][3][lane * V + e] = sum2[e];
         }
     }
     __syncthreads();
@@ -206,14 +222,16 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
                 acc_t a = red[w][1][lane * V + e], b = red[w][2][lane * V + e];
                 mx[e] = a > mx[e] ? a : mx[e];
                 mn[e] = b < mn[e] ? b : mn[e];
+                if constexpr (W) sum2[e] += red[w][3][lane * V + e];
             }
-        acc_t* p = part + (int64_t)blockIdx.y * 3 * K;
+        acc_t* p = part + (int64_t)blockIdx.y * 4 * K;
 #pragma unroll
         for (int e = 0; e < V; ++e) {
             if (k0 + e < K) {
                 p[k0 + e] = sum[e];
                 p[(int64_t)K + k0 + e] = mx[e];
                 p[2 * (int64_t)K + k0 + e] = mn[e];
+                if constexpr (W) p[3 * (int64_t)K + k0 + e] = sum2[e];
             }
         }
     }
@@ -222,18 +240,20 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
 // Step 2: combine the nsplit partials of column k in a fixed order: 16 columns per block,
 // 16 groups of threads per column; group g folds splits g, g+16, ... in increasing order and
 // the 16 group results are folded in group order.
-template <typename acc_t>
+template <typename acc_t, bool W>
 __global__ __launch_bounds__(256) void encode_cols_combine_kernel(const acc_t* __restrict__ part, int nsplit, int K,
                                                                   int N, acc_t* __restrict__ Be,
+                                                                  acc_t* __restrict__ Be2,
                                                                   acc_t* __restrict__ bstat) {
-    __shared__ acc_t red[3][16][16];
+    __shared__ acc_t red[W ? 4 : 3][16][16];
     const int kl = threadIdx.x & 15, grp = threadIdx.x >> 4;
     const int k = blockIdx.x * 16 + kl;
-    acc_t sum = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
+    acc_t sum = 0, sum2 = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
     if (k < K) {
         for (int s = grp; s < nsplit; s += 16) {
-            const acc_t* p = part + (int64_t)s * 3 * K;
+            const acc_t* p = part + (int64_t)s * 4 * K;
             sum += p[k];
+            if constexpr (W) sum2 += p[3 * (int64_t)K + k];
             const acc_t a = p[(int64_t)K + k], b = p[2 * (int64_t)K + k];
             mx = a > mx ? a : mx;
             mn = b < mn ? b : mn;
@@ -242,19 +262,23 @@ __global__ __launch_bounds__(256) void encode_cols_combine_kernel(const acc_t* _
     red[0][grp][kl] = sum;
     red[1][grp][kl] = mx;
     red[2][grp][kl] = mn;
+    if constexpr (W) red[3][grp][kl] = sum2;
     __syncthreads();
     if (grp == 0 && k < K) {
         sum = red[0][0][kl];
         mx = red[1][0][kl];
         mn = red[2][0][kl];
+        if constexpr (W) sum2 = red[3][0][kl];
 #pragma unroll
         for (int g = 1; g < 16; ++g) {
             sum += red[0][g][kl];
+            if constexpr (W) sum2 += red[3][g][kl];
             const acc_t a = red[1][g][kl], b = red[2][g][kl];
             mx = a > mx ? a : mx;
             mn = b < mn ? b : mn;
         }
         Be[k] = sum;
+        if constexpr (W) Be2[k] = sum2;
         bstat[3 * (int64_t)k + 0] = mx;
         bstat[3 * (int64_t)k + 1] = mn;
         bstat[3 * (int64_t)k + 2] = (acc_t)((double)sum / (double)N);
@@ -314,14 +338,17 @@ __global__ __launch_bounds__(1024) void encode_aggregate_kernel(const acc_t* __r
 // ---------------------------------------------------------------------------
 // A side: one wavefront per row m: (max, min, mean), dot with Be, threshold
 // ---------------------------------------------------------------------------
-template <typename T>
+// W: also the expected weighted checksum C^{r2} = A (B r2) (section 2.2).
+template <typename T, bool W>
 __global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restrict__ A, int M, int K, int N,
                                                              int64_t lda,
                                                              const typename Elem<T>::acc_t* __restrict__ Be,
+                                                             const typename Elem<T>::acc_t* __restrict__ Be2,
                                                              const double* __restrict__ S, double e_max,
                                                              double c_sigma,
                                                              typename Elem<T>::acc_t* __restrict__ astat,
                                                              typename Elem<T>::acc_t* __restrict__ expected,
+                                                             typename Elem<T>::acc_t* __restrict__ expected2,
                                                              typename Elem<T>::acc_t* __restrict__ Tout, int vec_ok) {
     using acc_t = typename Elem<T>::acc_t;
     constexpr int V = Elem<T>::vec;
@@ -329,7 +356,7 @@ __global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restr
     const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (m >= M) return;
     const char* row = reinterpret_cast<const char*>(A) + (int64_t)m * lda * Elem<T>::bytes;
-    acc_t sum = 0, dot = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
+    acc_t sum = 0, dot = 0, dot2 = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
     int done = 0;
     if (vec_ok) {
         const int nchunks = K / V;
@@ -349,6 +376,7 @@ __global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restr
             for (int e = 0; e < V; ++e) {
                 sum += v0[e];
                 dot = fma(v0[e], b0[e], dot);
+                if constexpr (W) dot2 = fma(v0[e], Be2[(int64_t)c * V + e], dot2);
                 mx = v0[e] > mx ? v0[e] : mx;
                 mn = v0[e] < mn ? v0[e] : mn;
             }
@@ -356,6 +384,7 @@ __global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restr
             for (int e = 0; e < V; ++e) {
                 sum += v1[e];
                 dot = fma(v1[e], b1[e], dot);
+                if constexpr (W) dot2 = fma(v1[e], Be2[(int64_t)(c + 64) * V + e], dot2);
                 mx = v1[e] > mx ? v1[e] : mx;
                 mn = v1[e] < mn ? v1[e] : mn;
             }
@@ -369,6 +398,7 @@ __global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restr
                 const acc_t b = Be[(int64_t)c * V + e];
                 sum += v0[e];
                 dot = fma(v0[e], b, dot);
+                if constexpr (W) dot2 = fma(v0[e], Be2[(int64_t)c * V + e], dot2);
                 mx = v0[e] > mx ? v0[e] : mx;
                 mn = v0[e] < mn ? v0[e] : mn;
             }
@@ -379,11 +409,16 @@ __global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restr
         acc_t x = Unpack<T>::one(row, k);
         sum += x;
         dot = fma(x, Be[k], dot);
+        if constexpr (W) dot2 = fma(x, Be2[k], dot2);
         mx = x > mx ? x : mx;
         mn = x < mn ? x : mn;
     }
     sum = wave_sum(sum);
     dot = wave_sum(dot);
+    if constexpr (W) {
+        dot2 = wave_sum(dot2);
+        if (lane == 0) expected2[m] = dot2;
+    }
     mx = wave_max(mx);
     mn = wave_min(mn);
     if (lane == 0) {
@@ -414,63 +449,75 @@ size_t encode_workspace_bytes(const vabft_problem* p) {
     if (!p->transB) return 0;
     const size_t acc_bytes = p->dtype == VABFT_F64 ? 8 : 4;
     const size_t nsplit = ((size_t)p->N + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
-    return nsplit * 3 * (size_t)p->K * acc_bytes;
+    return nsplit * 4 * (size_t)p->K * acc_bytes;  // (sum, max, min, weighted sum) per slab
 }
 
-template <typename T>
-static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S, void* ws,
-                         hipStream_t st) {
+template <typename T, bool W>
+static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, void* d_Be2, void* d_bstat, double* d_S,
+                         void* ws, hipStream_t st) {
     using acc_t = typename Elem<T>::acc_t;
     const int vec_ok = aligned16(dB) && ((p->ldb * Elem<T>::bytes) % 16 == 0);
     if (!p->transB) {
-        encode_rows_kernel<T><<<dim3((p->K + 3) / 4), dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, (acc_t*)d_Be,
-                                                                          (acc_t*)d_bstat, vec_ok);
+        encode_rows_kernel<T, W><<<dim3((p->K + 3) / 4), dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, (acc_t*)d_Be,
+                                                                             (acc_t*)d_Be2, (acc_t*)d_bstat, vec_ok);
     } else {
         constexpr int V = Elem<T>::vec;
         const int nsplit = (p->N + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
         dim3 grid((p->K + 64 * V - 1) / (64 * V), nsplit);
-        encode_cols_kernel<T><<<grid, dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, ENC_ROWS_PER_BLOCK, (acc_t*)ws,
-                                                          vec_ok);
-        encode_cols_combine_kernel<acc_t><<<dim3((p->K + 15) / 16), dim3(256), 0, st>>>(
-            (const acc_t*)ws, nsplit, p->K, p->N, (acc_t*)d_Be, (acc_t*)d_bstat);
+        encode_cols_kernel<T, W><<<grid, dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, ENC_ROWS_PER_BLOCK, (acc_t*)ws,
+                                                             vec_ok);
+        encode_cols_combine_kernel<acc_t, W><<<dim3((p->K + 15) / 16), dim3(256), 0, st>>>(
+            (const acc_t*)ws, nsplit, p->K, p->N, (acc_t*)d_Be, (acc_t*)d_Be2, (acc_t*)d_bstat);
     }
     encode_aggregate_kernel<acc_t><<<dim3(1), dim3(1024), 0, st>>>((const acc_t*)d_Be, (const acc_t*)d_bstat, p->K,
                                                                    p->N, d_S);
     return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
 }
 
-int encode_dispatch(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S, void* ws,
-                    hipStream_t st) {
+// d_Be2 == nullptr: plain encode; otherwise the weighted checksum is produced in the same pass
+int encode_dispatch(const vabft_problem* p, const void* dB, void* d_Be, void* d_Be2, void* d_bstat, double* d_S,
+                    void* ws, hipStream_t st) {
+#define VABFT_ENC_CASE(T)                                                            \
+    return d_Be2 ? encode_launch<T, true>(p, dB, d_Be, d_Be2, d_bstat, d_S, ws, st) \
+                 : encode_launch<T, false>(p, dB, d_Be, nullptr, d_bstat, d_S, ws, st)
     switch (p->dtype) {
-        case VABFT_F64: return encode_launch<double>(p, dB, d_Be, d_bstat, d_S, ws, st);
-        case VABFT_F32: return encode_launch<float>(p, dB, d_Be, d_bstat, d_S, ws, st);
-        case VABFT_F16: return encode_launch<f16_t>(p, dB, d_Be, d_bstat, d_S, ws, st);
-        case VABFT_BF16: return encode_launch<bf16_t>(p, dB, d_Be, d_bstat, d_S, ws, st);
+        case VABFT_F64: VABFT_ENC_CASE(double);
+        case VABFT_F32: VABFT_ENC_CASE(float);
+        case VABFT_F16: VABFT_ENC_CASE(f16_t);
+        case VABFT_BF16: VABFT_ENC_CASE(bf16_t);
     }
+#undef VABFT_ENC_CASE
     return VABFT_EINVAL;
 }
 
-template <typename T>
-static int threshold_launch(const vabft_problem* p, const void* dA, const void* d_Be, const double* d_S, double e_max,
-                            double c_sigma, void* d_astat, void* d_expected, void* d_T, hipStream_t st) {
+template <typename T, bool W>
+static int threshold_launch(const vabft_problem* p, const void* dA, const void* d_Be, const void* d_Be2,
+                            const double* d_S, double e_max, double c_sigma, void* d_astat, void* d_expected,
+                            void* d_expected2, void* d_T, hipStream_t st) {
     using acc_t = typename Elem<T>::acc_t;
     const int vec_ok = aligned16(dA) && ((p->lda * Elem<T>::bytes) % 16 == 0);
-    threshold_rows_kernel<T><<<dim3((p->M + 3) / 4), dim3(256), 0, st>>>(dA, p->M, p->K, p->N, p->lda,
-                                                                         (const acc_t*)d_Be, d_S, e_max, c_sigma,
-                                                                         (acc_t*)d_astat, (acc_t*)d_expected,
-                                                                         (acc_t*)d_T, vec_ok);
+    threshold_rows_kernel<T, W><<<dim3((p->M + 3) / 4), dim3(256), 0, st>>>(
+        dA, p->M, p->K, p->N, p->lda, (const acc_t*)d_Be, (const acc_t*)d_Be2, d_S, e_max, c_sigma, (acc_t*)d_astat,
+        (acc_t*)d_expected, (acc_t*)d_expected2, (acc_t*)d_T, vec_ok);
     return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
 }
 
-int threshold_dispatch(const vabft_problem* p, const void* dA, const void* d_Be, const double* d_S, double e_max,
-                       double c_sigma, void* d_astat, void* d_expected, void* d_T, hipStream_t st) {
+// d_Be2 / d_expected2 == nullptr: plain pass; otherwise A (B r2) rides in the same read of A
+int threshold_dispatch(const vabft_problem* p, const void* dA, const void* d_Be, const void* d_Be2, const double* d_S,
+                       double e_max, double c_sigma, void* d_astat, void* d_expected, void* d_expected2, void* d_T,
+                       hipStream_t st) {
+#define VABFT_THR_CASE(T)                                                                                          \
+    return d_Be2 ? threshold_launch<T, true>(p, dA, d_Be, d_Be2, d_S, e_max, c_sigma, d_astat, d_expected,        \
+                                             d_expected2, d_T, st)                                                 \
+                 : threshold_launch<T, false>(p, dA, d_Be, nullptr, d_S, e_max, c_sigma, d_astat, d_expected,      \
+                                              nullptr, d_T, st)
     switch (p->dtype) {
-        case VABFT_F64: return threshold_launch<double>(p, dA, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T, st);
-        case VABFT_F32: return threshold_launch<float>(p, dA, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T, st);
-        case VABFT_F16: return threshold_launch<f16_t>(p, dA, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T, st);
-        case VABFT_BF16:
-            return threshold_launch<bf16_t>(p, dA, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T, st);
+        case VABFT_F64: VABFT_THR_CASE(double);
+        case VABFT_F32: VABFT_THR_CASE(float);
+        case VABFT_F16: VABFT_THR_CASE(f16_t);
+        case VABFT_BF16: VABFT_THR_CASE(bf16_t);
     }
+#undef VABFT_THR_CASE
     return VABFT_EINVAL;
 }
 

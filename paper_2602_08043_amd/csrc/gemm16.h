@@ -34,6 +34,10 @@ constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
 constexpr int STAGE = A_BYTES + B_BYTES;
 constexpr int LDS_BYTES = 2 * STAGE;  // double buffered: 128 KiB
+// epilogue scratch (the operand stages are free by then): row-sum staging at 0, the C staging slabs
+// from 4096, the fused A-statistics staging at 40960 and the weighted row sums behind it
+constexpr int SRED_OFFSET = 40960;
+constexpr int RED2_OFFSET = SRED_OFFSET + 2 * 4 * BM * 4;
 
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 __device__ __forceinline__ int lds_pos(int row, int chunk) { return row * 128 + ((chunk ^ swz(row)) << 4); }
@@ -123,6 +127,34 @@ __device__ __forceinline__ void gemm16_rowsum_to_lds(const f32x16_t (&acc)[4][4]
     }
 }
 
+// Position-weighted row sums of the wavefront's accumulator tile (section 2.2 C^{r2'} = C r2,
+// r2 = [1..N]): sum_j (j + 1) acc[i][j].  Inside the tile the weights are small compile-time
+// constants; the offset of the lane's first column is applied once to the plain partial sum.
+// Lanes 0..31 leave the result over the wavefront's 128 columns in red2[wn][row].
+__device__ __forceinline__ void gemm16_rowsum2_to_lds(const f32x16_t (&acc)[4][4], float* red2, int col0, int wm,
+                                                      int wn, int l32, int lh) {
+    using namespace g16;
+    const float w0 = (float)(col0 + wn * 128 + 4 * lh + 1);  // weight of the lane's first column
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+        float t1[4], t2[4];
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
+            float a1 = 0.f, a2 = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                a1 += acc[mi][ni][r];
+                a2 = fmaf((float)(ni * 32 + 8 * (r >> 2) + (r & 3)), acc[mi][ni][r], a2);
+            }
+            t1[ni] = a1;
+            t2[ni] = a2;
+        }
+        float s = fmaf(w0, (t1[0] + t1[1]) + (t1[2] + t1[3]), (t2[0] + t2[1]) + (t2[2] + t2[3]));
+        s += __shfl_xor(s, 32, WAVE);
+        if (lh == 0) red2[wn * BM + wm * 128 + mi * 32 + l32] = s;
+    }
+}
+
 // Quantise and store the wavefront's tile of C.
 template <typename T, bool EDGE>
 __device__ __forceinline__ void gemm16_store_c(const GemmArgs& g, const f32x16_t (&acc)[4][4], unsigned char* smem,
@@ -202,14 +234,19 @@ __device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x16_t (&ac
                                                 int row0, int col0, int bn, int tid, int lane, int wm, int wn,
                                                 int l32, int lh) {
     using namespace g16;
-    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2;
+    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE >= 2;
     gemm16_inject<INJECT>(g, acc, row0, col0, wm, wn, l32, lh);
     if (VERIFY) {
-        float* red = reinterpret_cast<float*>(smem);  // [2][256]
+        float* red = reinterpret_cast<float*>(smem);                       // [2][256]
+        float* red2 = reinterpret_cast<float*>(smem + g16::RED2_OFFSET);  // [2][256]
         gemm16_rowsum_to_lds(acc, red, wm, wn, l32, lh);
+        if (WSUM) gemm16_rowsum2_to_lds(acc, red2, col0, wm, wn, l32, lh);
         __syncthreads();
         const int gi = row0 + tid;
-        if (gi < g.M) reinterpret_cast<float*>(g.rowpart)[(int64_t)bn * g.M + gi] = red[tid] + red[BM + tid];
+        if (gi < g.M) {
+            reinterpret_cast<float*>(g.rowpart)[(int64_t)bn * g.M + gi] = red[tid] + red[BM + tid];
+            if (WSUM) reinterpret_cast<float*>(g.rowpart2)[(int64_t)bn * g.M + gi] = red2[tid] + red2[BM + tid];
+        }
     }
     gemm16_store_c<T, EDGE>(g, acc, smem, row0, col0, lane, wm, wn, l32, lh);
 }
@@ -362,6 +399,7 @@ static int gemm16_edge_launch_tb(const GemmArgs& a, int mode, hipStream_t st) {
     VABFT_G16_CASE(0)
     VABFT_G16_CASE(1)
     VABFT_G16_CASE(2)
+    VABFT_G16_CASE(3)
 #undef VABFT_G16_CASE
     return VABFT_EINVAL;
 }

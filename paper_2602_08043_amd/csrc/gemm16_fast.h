@@ -19,7 +19,8 @@
 //     the k-steps whose body index is congruent to bn modulo the number of tile-columns;
 //   * the compare-and-flag step: the last workgroup to finish a tile-row (an arrival ticket per
 //     tile-row) combines that row block's partials in a fixed order, evaluates the threshold
-//     in double precision, and writes rowsum, E, flags; the last row block writes nflag.
+//     in double precision, and writes rowsum, E, flags; the last row block writes nflag;
+//   * (MODE >= 2) the position-weighted row sums C r2 of section 2.2, through the same partials.
 #pragma once
 #include "gemm16.h"
 
@@ -82,7 +83,6 @@ template <> __device__ __forceinline__ float frag_elem<f16_t>(uint32_t d0, uint3
     return Elem<f16_t>::to_acc((uint16_t)((e & 1) ? (d >> 16) : (d & 0xffffu)));
 }
 
-constexpr int SRED_OFFSET = 40960;
 // Be values the workgroup will need, cached in LDS behind the two operand stages: one slot of
 // 128 floats per folded unit u (k = 128*u - 16 .. 128*u + 111).
 constexpr int BE_CACHE_OFFSET = LDS_BYTES;
@@ -93,7 +93,7 @@ constexpr int LDS_BYTES_FUSED = LDS_BYTES + BE_CACHE_SLOTS * 128 * 4;  // LDS of
 template <typename T, int TRANSB, int MODE, bool FUSED>
 __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     using namespace g16f;
-    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2;
+    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE >= 2;
     static_assert(!FUSED || VERIFY, "fused statistics belong to the verified kernel");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     lds_u8* const lds = (lds_u8*)smem;
@@ -365,8 +365,10 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     if (VERIFY) {
         float* red = reinterpret_cast<float*>(smem);                 // [2 wn][256 rows]
         float* sred = reinterpret_cast<float*>(smem + SRED_OFFSET);  // [2 wn][4][256 rows]
+        float* red2 = reinterpret_cast<float*>(smem + RED2_OFFSET);  // [2 wn][256 rows]
         int* s_last = reinterpret_cast<int*>(smem + 2048);
         gemm16_rowsum_to_lds(acc, red, wm, wn, l32, lh);
+        if (WSUM) gemm16_rowsum2_to_lds(acc, red2, col0, wm, wn, l32, lh);
         if (FUSED) {
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi) {
@@ -387,7 +389,9 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         const int gi = row0 + tid;
         float* rowpart = reinterpret_cast<float*>(g.rowpart);
         float* apart = reinterpret_cast<float*>(g.apart);
+        float* rowpart2 = reinterpret_cast<float*>(g.rowpart2);
         st_agent(rowpart + (int64_t)bn * g.M + gi, red[tid] + red[BM + tid]);
+        if (WSUM) st_agent(rowpart2 + (int64_t)bn * g.M + gi, red2[tid] + red2[BM + tid]);
         if (FUSED) {
             float* ap = apart + (int64_t)bn * 4 * g.M + gi;
             st_agent(ap, sred[0 * BM + tid] + sred[4 * BM + tid]);
@@ -407,13 +411,15 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         if (*s_last) {
             // Combine the tile-column partials in tile order.  The device-scope loads are issued
             // in batches of 16 tile-columns before anything is folded, so their latencies overlap.
-            float rs = 0.f, sum = 0.f, dot = 0.f, mx = -3.402823466e+38f, mn = 3.402823466e+38f;
+            float rs = 0.f, rs2 = 0.f, sum = 0.f, dot = 0.f, mx = -3.402823466e+38f, mn = 3.402823466e+38f;
             for (int t0 = 0; t0 < g.tiles_n; t0 += 16) {
                 float v[16][5];
+                float v2[16];
 #pragma unroll
                 for (int j = 0; j < 16; ++j) {
                     const int t = t0 + j < g.tiles_n ? t0 + j : g.tiles_n - 1;  // clamped duplicates are not folded
                     v[j][0] = ld_agent(rowpart + (int64_t)t * g.M + gi);
+                    if (WSUM) v2[j] = ld_agent(rowpart2 + (int64_t)t * g.M + gi);
                     if (FUSED) {
                         const float* ap = apart + (int64_t)t * 4 * g.M + gi;
                         v[j][1] = ld_agent(ap);
@@ -428,6 +434,7 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
                 for (int j = 0; j < 16; ++j)
                     if (!(t0 + j < g.tiles_n)) {
                         v[j][0] = 0.f;
+                        if (WSUM) v2[j] = 0.f;
                         v[j][1] = 0.f;
                         v[j][2] = 0.f;
                         v[j][3] = -3.402823466e+38f;
@@ -436,6 +443,7 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
 #pragma unroll
                 for (int j = 0; j < 16; j += 4) {
                     rs += (v[j][0] + v[j + 1][0]) + (v[j + 2][0] + v[j + 3][0]);
+                    if (WSUM) rs2 += (v2[j] + v2[j + 1]) + (v2[j + 2] + v2[j + 3]);
                     if (FUSED) {
                         sum += (v[j][1] + v[j + 1][1]) + (v[j + 2][1] + v[j + 3][1]);
                         dot += (v[j][2] + v[j + 1][2]) + (v[j + 2][2] + v[j + 3][2]);
@@ -468,6 +476,7 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
             const float e = expv - rs;
             const int f = !(fabsf(e) <= thr);
             reinterpret_cast<float*>(g.rowsum)[gi] = rs;
+            if (WSUM && g.rowsum2) reinterpret_cast<float*>(g.rowsum2)[gi] = rs2;
             reinterpret_cast<float*>(g.E)[gi] = e;
             g.flags[gi] = f;
             const int cnt = __syncthreads_count(f);
@@ -510,6 +519,7 @@ static int gemm16_fast_launch_tb(const GemmArgs& a, int mode, hipStream_t st) {
     VABFT_G16F_CASE(0, 0)
     VABFT_G16F_CASE(1, 0)
     VABFT_G16F_CASE(2, 0)
+    VABFT_G16F_CASE(3, 0)
     VABFT_G16F_CASE(1, 1)
     VABFT_G16F_CASE(2, 1)
 #undef VABFT_G16F_CASE

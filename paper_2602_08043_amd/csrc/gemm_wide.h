@@ -49,7 +49,7 @@ template <typename T> constexpr int lds_bytes() { return loop_bytes<T>() > epi_b
 template <typename T, int TRANSB, int MODE, bool EDGE>
 __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     using namespace gw;
-    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2;
+    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE >= 2;
     using Cfg = WideCfg<T>;
     using accv_t = typename Cfg::accv_t;
     constexpr int MT = Cfg::MT, KM = Cfg::KM, NR = Cfg::NR, V = Cfg::V;
@@ -244,6 +244,23 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
         const T s = (part[0] + part[1]) + (part[2] + part[3]);
         const int gi = trow0 + lane;
         if (gi < g.M) reinterpret_cast<T*>(g.rowpart)[(int64_t)(2 * bn + wn) * g.M + gi] = s;
+        if (WSUM) {
+            // position-weighted row sum (section 2.2 C^{r2'} = C r2, r2 = [1..N]): weights 0..63
+            // inside the tile, the offset of the tile's first column applied once to s
+            T part2[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int c = 0; c < 64; c += V) {
+                T v[V];
+                const raw16 q = *reinterpret_cast<const raw16*>(rowp + c);
+                __builtin_memcpy(v, &q, 16);
+                T cs = 0;
+#pragma unroll
+                for (int e = 0; e < V; ++e) cs = fma((T)(c + e), v[e], cs);
+                part2[(c / V) & 3] += cs;
+            }
+            const T s2 = fma((T)(tcol0 + 1), s, (part2[0] + part2[1]) + (part2[2] + part2[3]));
+            if (gi < g.M) reinterpret_cast<T*>(g.rowpart2)[(int64_t)(2 * bn + wn) * g.M + gi] = s2;
+        }
     }
 
     T* __restrict__ C = reinterpret_cast<T*>(g.C);
@@ -292,12 +309,16 @@ static int gemmw_launch(const GemmArgs& a, int transB, int mode, bool edge, hipS
     VABFT_GW_CASE(0, 1, true)
     VABFT_GW_CASE(0, 2, false)
     VABFT_GW_CASE(0, 2, true)
+    VABFT_GW_CASE(0, 3, false)
+    VABFT_GW_CASE(0, 3, true)
     VABFT_GW_CASE(1, 0, false)
     VABFT_GW_CASE(1, 0, true)
     VABFT_GW_CASE(1, 1, false)
     VABFT_GW_CASE(1, 1, true)
     VABFT_GW_CASE(1, 2, false)
     VABFT_GW_CASE(1, 2, true)
+    VABFT_GW_CASE(1, 3, false)
+    VABFT_GW_CASE(1, 3, true)
 #undef VABFT_GW_CASE
     return VABFT_EINVAL;
 }

@@ -10,10 +10,12 @@ namespace vabft {
 
 // encode.hip
 size_t encode_workspace_bytes(const vabft_problem* p);
-int encode_dispatch(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S, void* ws,
-                    hipStream_t st);
-int threshold_dispatch(const vabft_problem* p, const void* dA, const void* d_Be, const double* d_S, double e_max,
-                       double c_sigma, void* d_astat, void* d_expected, void* d_T, hipStream_t st);
+// d_Be2 / d_expected2 may be null (no position-weighted checksum)
+int encode_dispatch(const vabft_problem* p, const void* dB, void* d_Be, void* d_Be2, void* d_bstat, double* d_S,
+                    void* ws, hipStream_t st);
+int threshold_dispatch(const vabft_problem* p, const void* dA, const void* d_Be, const void* d_Be2, const double* d_S,
+                       double e_max, double c_sigma, void* d_astat, void* d_expected, void* d_expected2, void* d_T,
+                       hipStream_t st);
 
 // gemm*.hip
 struct InjectArgs {
@@ -55,6 +57,9 @@ struct GemmArgs {
     double e_max, c_sigma;
     void* astat;      // [M][3] acc, output
     void* apart;      // [tiles_n][4][M] acc: per-K-slice (sum, dot, max, min) of the rows of A
+    // position-weighted row sums C r2 (kernel modes 2 and 3)
+    void* rowpart2;   // partials, same shape as rowpart
+    void* rowsum2;    // [M] acc, output; may be null
 };
 
 size_t gemm_workspace_bytes(const vabft_problem* p);
@@ -64,14 +69,16 @@ struct FusedArgs {  // non-null d_Be selects the fused A-side path
     double e_max, c_sigma;
     void* d_astat;
 };
+// d_rowsum2 non-null selects the kernels that also form the position-weighted row sums
 int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* dC, void* d_expected, void* d_T,
-                  int verify, const FusedArgs* fused, const vabft_inject* inj, void* d_rowsum, void* d_E,
-                  int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj, void* ws,
-                  hipStream_t st);
+                  int verify, const FusedArgs* fused, const vabft_inject* inj, void* d_rowsum, void* d_rowsum2,
+                  void* d_E, int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
+                  void* ws, hipStream_t st);
 void workspace_init_launch(void* ws, size_t bytes, hipStream_t st);
 
 // per-dtype launchers (one translation unit each, to compile in parallel)
-// mode: 0 plain, 1 check, 2 check + injector.  With edge == false the 16-bit kernels do the
+// mode: 0 plain, 1 check, 2 check + injector + weighted row sums, 3 check + weighted row sums.
+// With edge == false the 16-bit kernels do the
 // compare-and-flag step themselves; otherwise the caller launches the finalize kernel.
 int gemm16_launch_bf16_nn(const GemmArgs& a, int mode, bool edge, hipStream_t st);
 int gemm16_launch_bf16_nt(const GemmArgs& a, int mode, bool edge, hipStream_t st);

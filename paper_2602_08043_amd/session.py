@@ -52,6 +52,13 @@ class VerifiedGemm:
         self.ninj = torch.zeros(1, dtype=torch.int32, device=dev)
         self.log_capacity = int(log_capacity)
         self.injlog = torch.zeros(max(1, self.log_capacity) * _REC_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+        # position-weighted checksum / localisation buffers
+        self.Be2 = torch.empty(K, dtype=acc, device=dev)
+        self.expected2 = torch.empty(M, dtype=acc, device=dev)
+        self.rowsum2 = torch.empty(M, dtype=acc, device=dev)
+        self.loc = torch.empty(M, dtype=torch.int32, device=dev)
+        self.delta = torch.empty(M, dtype=acc, device=dev)
+        self.ncorrected = torch.zeros(1, dtype=torch.int32, device=dev)
         self.ws_bytes = vb.vabft_workspace_bytes(self.problem)
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
         vb.vabft_workspace_init(self.ws.data_ptr(), self.ws_bytes, self._stream())
@@ -116,6 +123,43 @@ class VerifiedGemm:
         self.encode(B)
         self.gemm_fused(A, B, e_max, c_sigma, inj)
 
+    # ---- weighted checksum, localisation, correction ---------------------------------
+    def encode_weighted(self, B: torch.Tensor):
+        return vb.vabft_encode_weighted(self.problem, B.data_ptr(), self.Be.data_ptr(), self.Be2.data_ptr(),
+                                        self.bstat.data_ptr(), self.S.data_ptr(), self.ws.data_ptr(), self.ws_bytes,
+                                        self._stream())
+
+    def threshold_weighted(self, A: torch.Tensor, e_max=None, c_sigma=2.5):
+        if e_max is None:
+            e_max = vb.vabft_default_emax(self.dtype, self.K, self.N)
+        self.e_max = e_max
+        return vb.vabft_threshold_weighted(self.problem, A.data_ptr(), self.Be.data_ptr(), self.Be2.data_ptr(),
+                                           self.S.data_ptr(), e_max, c_sigma, self.astat.data_ptr(),
+                                           self.expected.data_ptr(), self.expected2.data_ptr(), self.T.data_ptr(),
+                                           self._stream())
+
+    def gemm_weighted(self, A: torch.Tensor, B: torch.Tensor, inj: vb.Inject | None = None):
+        return vb.vabft_gemm_verified_weighted(self.problem, A.data_ptr(), B.data_ptr(), self.C.data_ptr(),
+                                               self.expected.data_ptr(), self.T.data_ptr(), inj,
+                                               self.rowsum.data_ptr(), self.rowsum2.data_ptr(), self.E.data_ptr(),
+                                               self.flags.data_ptr(), self.nflag.data_ptr(), self.injlog.data_ptr(),
+                                               self.ninj.data_ptr(), self.ws.data_ptr(), self.ws_bytes,
+                                               self._stream())
+
+    def locate_correct(self, correct=1):
+        return vb.vabft_locate_correct(self.problem, self.C.data_ptr(), self.expected.data_ptr(),
+                                       self.expected2.data_ptr(), self.rowsum.data_ptr(), self.rowsum2.data_ptr(),
+                                       self.flags.data_ptr(), correct, self.loc.data_ptr(), self.delta.data_ptr(),
+                                       self.ncorrected.data_ptr(), self._stream())
+
+    def run_weighted(self, A, B, e_max=None, c_sigma=2.5, inj=None, correct=1):
+        """Detect, locate, correct: weighted encode, weighted threshold, weighted verified GEMM,
+        then localisation (and correction of the stored C)."""
+        self.encode_weighted(B)
+        self.threshold_weighted(A, e_max, c_sigma)
+        self.gemm_weighted(A, B, inj)
+        self.locate_correct(correct)
+
     def inject_records(self):
         """Downloaded injection log as a list of (row, col, bit, before, after), sorted."""
         n = int(self.ninj.item())
@@ -128,7 +172,9 @@ class VerifiedGemm:
     def results(self):
         torch.cuda.synchronize(self.device)
         out = {k: getattr(self, k).cpu().numpy() for k in
-               ("Be", "bstat", "S", "astat", "expected", "T", "rowsum", "E", "flags")}
+               ("Be", "bstat", "S", "astat", "expected", "T", "rowsum", "E", "flags", "Be2", "expected2", "rowsum2",
+                "loc", "delta")}
+        out["ncorrected"] = int(self.ncorrected.item())
         out["nflag"] = int(self.nflag.item())
         out["C"] = to_host(self.C, self.dtype)
         return out
