@@ -143,6 +143,17 @@ def main():
     ms_three_call = timed(three_call, args.steps, args.warmup)
     ms_gemm_verified_only = timed(lambda: vg.gemm(A, B, 1), args.steps, args.warmup)
 
+    # ---- position-weighted checksum route (detect + locate + correct): the same GEMM with the
+    #      weighted row sums, and the small locate / correct pass
+    vg.encode_weighted(B)
+    vg.threshold_weighted(A, e_max)
+    ms_gemm_weighted = timed(lambda: vg.gemm_weighted(A, B), args.steps, args.warmup)
+    ms_locate = timed(lambda: vg.locate_correct(1), args.steps, args.warmup)
+    ms_enc_w = timed(lambda: vg.encode_weighted(B), args.steps, args.warmup)
+    ms_thr_w = timed(lambda: vg.threshold_weighted(A, e_max), args.steps, args.warmup)
+    vg.encode(B)
+    vg.threshold(A, e_max)
+
     # ---- HBM-bound passes on rotating buffers (> 512 MB in total, so the 256 MB
     #      Infinity Cache cannot serve them)
     eb = ELEM_BYTES[dt]
@@ -202,6 +213,9 @@ def main():
         "encode": {"GBps": K * N * eb / (ms_enc * 1e-3) / 1e9, "frac": K * N * eb / (ms_enc * 1e-3) / 1e9 / HBM_PEAK_GBPS},
         "threshold": {"GBps": M * K * eb / (ms_thr * 1e-3) / 1e9, "frac": M * K * eb / (ms_thr * 1e-3) / 1e9 / HBM_PEAK_GBPS},
     }
+    out["weighted_route"] = {"ms_gemm_with_weighted_rowsums": ms_gemm_weighted, "ms_locate_correct": ms_locate,
+                             "ms_encode_weighted_warm": ms_enc_w, "ms_threshold_weighted_warm": ms_thr_w,
+                             "gemm_overhead_pct_vs_plain": 100.0 * (ms_gemm_weighted / ms_plain - 1.0)}
     out["flags_in_timed_region"] = nflag_timed
     out["ms"]["step_with_inner_events"] = ms_step_with_events
 
@@ -241,24 +255,33 @@ def main():
                           "worst_row_E_over_T": worst,
                           "inputs": "fresh seeded device-generated matrices of the configuration's distribution"}
         # detection rate by bit: single flips at seeded (i, j) on the configuration's own inputs
-        vg.run_fused(A, B, e_max)
+        # (through the weighted route, so the same runs also give the localisation rate: a flip counts
+        # as located when the reported column is the injected one)
+        vg.encode_weighted(B)
+        vg.threshold_weighted(A, e_max)
         rng = np.random.Generator(np.random.Philox(key=[2024, 7]))
         bits = list(range(52, 64)) if dt == "f64" else list(range(16, 32))
-        dr = {}
+        dr, lr = {}, {}
         for bit in bits:
-            det = tot = 0
+            det = located = tot = 0
             for _ in range(args.flips_per_bit):
                 i, j = int(rng.integers(0, M)), int(rng.integers(0, N))
                 inj = vg.make_inject(mode=1, faults=[(i, j, bit)])
-                vg.gemm(A, B, 1, inj)
+                vg.gemm_weighted(A, B, inj)
+                vg.locate_correct(1)
                 fl = int(vg.flags[i].item())
                 det += fl
+                located += int(fl and int(vg.loc[i].item()) == j)
                 tot += 1
             dr[str(bit)] = det / tot
+            lr[str(bit)] = located / tot
             if time.time() - t_q > 150:
                 break
         out["quality"]["detection_rate_by_acc_bit"] = dr
+        out["quality"]["localisation_rate_by_acc_bit"] = lr
         out["quality"]["flips_per_bit"] = args.flips_per_bit
+        vg.encode(B)
+        vg.threshold(A, e_max)
 
     # ---- the CPU oracle timed on the host cores (bounded: one full trial of the workload)
     if not args.no_cpu_baseline:
