@@ -108,7 +108,9 @@ double vabft_default_emax(int32_t dtype, int32_t K, int32_t N);
  *   d_bstat [3K] acc: (max, min, mean) of row k of the logical K x N matrix, k-major
  *   d_S     [3] double: S1 = sum_k |mu_Bk|, S2 = sum_k sigma_Bk^2, S3 = sum_k mu_Bk^2 with
  *           sigma_Bk^2 = max(0, (max - mu)(mu - min))      (section 3.5 theorem)
- * Results are bit-reproducible from run to run (no floating-point atomics). */
+ * Results are bit-reproducible from run to run (no floating-point atomics).  The aggregates are
+ * folded by the last workgroup to finish (partials and an arrival counter in the workspace), so
+ * the call needs the workspace (vabft_workspace_bytes, zero-filled once) for either layout of B. */
 int vabft_encode(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S,
                  void* d_workspace, size_t workspace_bytes, void* stream);
 

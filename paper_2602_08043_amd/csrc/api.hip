@@ -157,6 +157,14 @@ static size_t tickets_bytes(const vabft_problem* p) {
     return round_up((tiles_m + 4) * sizeof(int32_t), 256);
 }
 
+// the encode's arrival counter: the last of the spare words behind the GEMM's tickets
+static int32_t* encode_ticket(const vabft_problem* p, void* ws) {
+    int bm, bn;
+    tile_shape(p->dtype, &bm, &bn);
+    const size_t tiles_m = ((size_t)p->M + bm - 1) / bm;
+    return reinterpret_cast<int32_t*>(ws) + tiles_m + 3;
+}
+
 size_t gemm_workspace_bytes(const vabft_problem* p) {
     int bm, bn;
     tile_shape(p->dtype, &bm, &bn);
@@ -343,10 +351,11 @@ int vabft_encode(const vabft_problem* p, const void* dB, void* d_Be, void* d_bst
         !aligned_to(d_bstat, acc_bytes(p->dtype)) || !aligned_to(d_S, 8))
         return VABFT_EINVAL;
     const size_t need = encode_workspace_bytes(p);
-    if (need && (!d_workspace || workspace_bytes < tickets_bytes(p) + need || !aligned_to(d_workspace, 16)))
+    if (!d_workspace || workspace_bytes < tickets_bytes(p) + need || !aligned_to(d_workspace, 16))
         return VABFT_EWORKSPACE;
-    void* scratch = d_workspace ? reinterpret_cast<unsigned char*>(d_workspace) + tickets_bytes(p) : nullptr;
-    return encode_dispatch(p, dB, d_Be, nullptr, d_bstat, d_S, scratch, (hipStream_t)stream);
+    void* scratch = reinterpret_cast<unsigned char*>(d_workspace) + tickets_bytes(p);
+    return encode_dispatch(p, dB, d_Be, nullptr, d_bstat, d_S, scratch, encode_ticket(p, d_workspace),
+                           (hipStream_t)stream);
 }
 
 int vabft_encode_weighted(const vabft_problem* p, const void* dB, void* d_Be, void* d_Be2, void* d_bstat, double* d_S,
@@ -356,10 +365,11 @@ int vabft_encode_weighted(const vabft_problem* p, const void* dB, void* d_Be, vo
         !aligned_to(d_Be2, acc_bytes(p->dtype)) || !aligned_to(d_bstat, acc_bytes(p->dtype)) || !aligned_to(d_S, 8))
         return VABFT_EINVAL;
     const size_t need = encode_workspace_bytes(p);
-    if (need && (!d_workspace || workspace_bytes < tickets_bytes(p) + need || !aligned_to(d_workspace, 16)))
+    if (!d_workspace || workspace_bytes < tickets_bytes(p) + need || !aligned_to(d_workspace, 16))
         return VABFT_EWORKSPACE;
-    void* scratch = d_workspace ? reinterpret_cast<unsigned char*>(d_workspace) + tickets_bytes(p) : nullptr;
-    return encode_dispatch(p, dB, d_Be, d_Be2, d_bstat, d_S, scratch, (hipStream_t)stream);
+    void* scratch = reinterpret_cast<unsigned char*>(d_workspace) + tickets_bytes(p);
+    return encode_dispatch(p, dB, d_Be, d_Be2, d_bstat, d_S, scratch, encode_ticket(p, d_workspace),
+                           (hipStream_t)stream);
 }
 
 int vabft_threshold(const vabft_problem* p, const void* dA, const void* d_Be, const double* d_S, double e_max,

@@ -55,79 +55,174 @@ template <> struct Unpack<double> {
 };
 
 // ---------------------------------------------------------------------------
-// B stored K x N: one wavefront reduces one row k
+// S1, S2, S3 without a launch of their own: every block publishes the three sums over its own
+// rows k (Algorithm 1: S1 += |mu_Bk|, S2 += sigma_Bk^2, S3 += mu_Bk^2) and takes an arrival ticket;
+// the last block folds all partials in block order.  Partials and ticket go through device-scope
+// relaxed atomics (the blocks sit on XCDs with private L2s); the ticket is left at zero.
+// s1..s3 need to be valid in thread 0 only.  Every thread of the block must call this.
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ void st_agent_f64(double* p, double v) {
+    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), (uint64_t)__double_as_longlong(v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double ld_agent_f64(const double* p) {
+    return __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT));
+}
+
+__device__ __forceinline__ void publish_and_fold_S(double s1, double s2, double s3, double* __restrict__ partial,
+                                                   int32_t* __restrict__ ticket, double* __restrict__ S) {
+    __shared__ int s_last;
+    __shared__ double s_red[3][4];
+    const int t = threadIdx.x, nblocks = gridDim.x;
+    if (t == 0) {
+        double* mine = partial + 3 * (int64_t)blockIdx.x;
+        st_agent_f64(mine, s1);
+        st_agent_f64(mine + 1, s2);
+        st_agent_f64(mine + 2, s3);
+        __builtin_amdgcn_s_waitcnt(0);  // the partials are performed before the ticket is taken
+        s_last = atomicAdd(ticket, 1) == nblocks - 1;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    if (t < 256) {
+        // thread t folds blocks t, t + 256, ... in increasing order; butterfly inside each of the
+        // four wavefronts; the four results in order
+        double a1 = 0, a2 = 0, a3 = 0;
+        for (int b = t; b < nblocks; b += 256) {
+            const double* q = partial + 3 * (int64_t)b;
+            a1 += ld_agent_f64(q);
+            a2 += ld_agent_f64(q + 1);
+            a3 += ld_agent_f64(q + 2);
+        }
+        a1 = wave_sum(a1);
+        a2 = wave_sum(a2);
+        a3 = wave_sum(a3);
+        if ((t & 63) == 0) {
+            s_red[0][t >> 6] = a1;
+            s_red[1][t >> 6] = a2;
+            s_red[2][t >> 6] = a3;
+        }
+    }
+    __syncthreads();
+    if (t < 3) {
+        const int nw = blockDim.x < 256 ? (blockDim.x + 63) / 64 : 4;
+        double v = 0;
+        for (int w = 0; w < nw; ++w) v += s_red[t][w];
+        S[t] = v;
+    }
+    if (t == 0) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// the three per-row terms of S1, S2, S3 from (row sum, max, min) of a row of N elements
+template <typename acc_t>
+__device__ __forceinline__ void row_terms(acc_t sum, acc_t mx, acc_t mn, int N, double& t1, double& t2, double& t3) {
+    const double mu = (double)sum / (double)N;
+    double var = ((double)mx - mu) * (mu - (double)mn);  // section 3.5: sigma^2 <= (max - mu)(mu - min)
+    var = var > 0 ? var : 0;
+    t1 = fabs(mu);
+    t2 = var;
+    t3 = mu * mu;
+}
+
+// ---------------------------------------------------------------------------
+// B stored K x N: one wavefront reduces one row k, 16 rows per block
+// ---------------------------------------------------------------------------
+constexpr int ENC_ROWS_WAVES = 16;
+
 // W: also the position-weighted checksum B*r2, r2 = [1..N] (section 2.2): Be2[k] = sum_n (n+1) B[k,n].
 template <typename T, bool W>
-__global__ __launch_bounds__(256) void encode_rows_kernel(const void* __restrict__ B, int K, int N, int64_t ldb,
-                                                          typename Elem<T>::acc_t* __restrict__ Be,
-                                                          typename Elem<T>::acc_t* __restrict__ Be2,
-                                                          typename Elem<T>::acc_t* __restrict__ bstat, int vec_ok) {
+__global__ __launch_bounds__(1024) void encode_rows_kernel(const void* __restrict__ B, int K, int N, int64_t ldb,
+                                                           typename Elem<T>::acc_t* __restrict__ Be,
+                                                           typename Elem<T>::acc_t* __restrict__ Be2,
+                                                           typename Elem<T>::acc_t* __restrict__ bstat, int vec_ok,
+                                                           double* __restrict__ s_partial,
+                                                           int32_t* __restrict__ ticket, double* __restrict__ S) {
     using acc_t = typename Elem<T>::acc_t;
     constexpr int V = Elem<T>::vec;
-    const int lane = threadIdx.x & 63;
-    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (k >= K) return;
-    const char* row = reinterpret_cast<const char*>(B) + (int64_t)k * ldb * Elem<T>::bytes;
-    acc_t sum = 0, sum2 = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
-    int done = 0;
-    if (vec_ok) {
-        const int nchunks = N / V;
-        int c = lane;
-        for (; c + 192 < nchunks; c += 256) {
-            raw16 r0 = ld16(row + (int64_t)c * 16);
-            raw16 r1 = ld16(row + (int64_t)(c + 64) * 16);
-            raw16 r2 = ld16(row + (int64_t)(c + 128) * 16);
-            raw16 r3 = ld16(row + (int64_t)(c + 192) * 16);
-            acc_t v[4][V];
-            Unpack<T>::run(r0, v[0]);
-            Unpack<T>::run(r1, v[1]);
-            Unpack<T>::run(r2, v[2]);
-            Unpack<T>::run(r3, v[3]);
+    __shared__ double terms[ENC_ROWS_WAVES][3];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int k = blockIdx.x * ENC_ROWS_WAVES + wave;
+    double t1 = 0, t2 = 0, t3 = 0;
+    if (k < K) {
+        const char* row = reinterpret_cast<const char*>(B) + (int64_t)k * ldb * Elem<T>::bytes;
+        acc_t sum = 0, sum2 = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
+        int done = 0;
+        if (vec_ok) {
+            const int nchunks = N / V;
+            int c = lane;
+            for (; c + 192 < nchunks; c += 256) {
+                raw16 r0 = ld16(row + (int64_t)c * 16);
+                raw16 r1 = ld16(row + (int64_t)(c + 64) * 16);
+                raw16 r2 = ld16(row + (int64_t)(c + 128) * 16);
+                raw16 r3 = ld16(row + (int64_t)(c + 192) * 16);
+                acc_t v[4][V];
+                Unpack<T>::run(r0, v[0]);
+                Unpack<T>::run(r1, v[1]);
+                Unpack<T>::run(r2, v[2]);
+                Unpack<T>::run(r3, v[3]);
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int e = 0; e < V; ++e) {
+                        sum += v[u][e];
+                        if constexpr (W) sum2 = fma((acc_t)((c + 64 * u) * V + e + 1), v[u][e], sum2);
+                        mx = v[u][e] > mx ? v[u][e] : mx;
+                        mn = v[u][e] < mn ? v[u][e] : mn;
+                    }
+            }
+            for (; c < nchunks; c += 64) {
+                raw16 r0 = ld16(row + (int64_t)c * 16);
+                acc_t v[V];
+                Unpack<T>::run(r0, v);
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
-                    sum += v[u][e];
-                    if constexpr (W) sum2 = fma((acc_t)((c + 64 * u) * V + e + 1), v[u][e], sum2);
-                    mx = v[u][e] > mx ? v[u][e] : mx;
-                    mn = v[u][e] < mn ? v[u][e] : mn;
+                    sum += v[e];
+                    if constexpr (W) sum2 = fma((acc_t)(c * V + e + 1), v[e], sum2);
+                    mx = v[e] > mx ? v[e] : mx;
+                    mn = v[e] < mn ? v[e] : mn;
                 }
-        }
-        for (; c < nchunks; c += 64) {
-            raw16 r0 = ld16(row + (int64_t)c * 16);
-            acc_t v[V];
-            Unpack<T>::run(r0, v);
-#pragma unroll
-            for (int e = 0; e < V; ++e) {
-                sum += v[e];
-                if constexpr (W) sum2 = fma((acc_t)(c * V + e + 1), v[e], sum2);
-                mx = v[e] > mx ? v[e] : mx;
-                mn = v[e] < mn ? v[e] : mn;
             }
+            done = nchunks * V;
         }
-        done = nchunks * V;
-    }
-    for (int n = done + lane; n < N; n += 64) {
-        acc_t x = Unpack<T>::one(row, n);
-        sum += x;
-        if constexpr (W) sum2 = fma((acc_t)(n + 1), x, sum2);
-        mx = x > mx ? x : mx;
-        mn = x < mn ? x : mn;
-    }
-    sum = wave_sum(sum);
-    mx = wave_max(mx);
-    mn = wave_min(mn);
-    if constexpr (W) {
-        sum2 = wave_sum(sum2);
-        if (lane == 0) Be2[k] = sum2;
+        for (int n = done + lane; n < N; n += 64) {
+            acc_t x = Unpack<T>::one(row, n);
+            sum += x;
+            if constexpr (W) sum2 = fma((acc_t)(n + 1), x, sum2);
+            mx = x > mx ? x : mx;
+            mn = x < mn ? x : mn;
+        }
+        sum = wave_sum(sum);
+        mx = wave_max(mx);
+        mn = wave_min(mn);
+        if constexpr (W) {
+            sum2 = wave_sum(sum2);
+            if (lane == 0) Be2[k] = sum2;
+        }
+        if (lane == 0) {
+            Be[k] = sum;
+            bstat[3 * (int64_t)k + 0] = mx;
+            bstat[3 * (int64_t)k + 1] = mn;
+            bstat[3 * (int64_t)k + 2] = (acc_t)((double)sum / (double)N);
+        }
+        row_terms(sum, mx, mn, N, t1, t2, t3);
     }
     if (lane == 0) {
-        Be[k] = sum;
-        bstat[3 * (int64_t)k + 0] = mx;
-        bstat[3 * (int64_t)k + 1] = mn;
-        bstat[3 * (int64_t)k + 2] = (acc_t)((double)sum / (double)N);
+        terms[wave][0] = t1;
+        terms[wave][1] = t2;
+        terms[wave][2] = t3;
     }
+    __syncthreads();
+    double s1 = 0, s2 = 0, s3 = 0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 0; w < ENC_ROWS_WAVES; ++w) {  // rows of the block in order
+            s1 += terms[w][0];
+            s2 += terms[w][1];
+            s3 += terms[w][2];
+        }
+    }
+    publish_and_fold_S(s1, s2, s3, s_partial, ticket, S);
 }
 
 // ---------------------------------------------------------------------------
@@ -244,8 +339,12 @@ template <typename acc_t, bool W>
 __global__ __launch_bounds__(256) void encode_cols_combine_kernel(const acc_t* __restrict__ part, int nsplit, int K,
                                                                   int N, acc_t* __restrict__ Be,
                                                                   acc_t* __restrict__ Be2,
-                                                                  acc_t* __restrict__ bstat) {
+                                                                  acc_t* __restrict__ bstat,
+                                                                  double* __restrict__ s_partial,
+                                                                  int32_t* __restrict__ ticket,
+                                                                  double* __restrict__ S) {
     __shared__ acc_t red[W ? 4 : 3][16][16];
+    __shared__ double terms[16][3];
     const int kl = threadIdx.x & 15, grp = threadIdx.x >> 4;
     const int k = blockIdx.x * 16 + kl;
     acc_t sum = 0, sum2 = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
@@ -283,56 +382,25 @@ __global__ __launch_bounds__(256) void encode_cols_combine_kernel(const acc_t* _
         bstat[3 * (int64_t)k + 1] = mn;
         bstat[3 * (int64_t)k + 2] = (acc_t)((double)sum / (double)N);
     }
-}
-
-// ---------------------------------------------------------------------------
-// S1, S2, S3 from (Be, max, min): one block; each thread folds rows t, t+1024, ... in
-// increasing order, then a fixed-order reduction (butterfly inside each wavefront, then the 16
-// wavefront results in order), all in double arithmetic.
-// ---------------------------------------------------------------------------
-template <typename acc_t>
-__global__ __launch_bounds__(1024) void encode_aggregate_kernel(const acc_t* __restrict__ Be,
-                                                                const acc_t* __restrict__ bstat, int K, int N,
-                                                                double* __restrict__ S) {
-    __shared__ double red[3][16];
-    const int t = threadIdx.x;
-    double s1 = 0, s2 = 0, s3 = 0;
-    for (int k0 = 0; k0 < K; k0 += 4096) {
-        acc_t be[4], mxv[4], mnv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int k = k0 + t + 1024 * u;
-            const int kc = k < K ? k : K - 1;
-            be[u] = Be[kc];
-            mxv[u] = bstat[3 * (int64_t)kc];
-            mnv[u] = bstat[3 * (int64_t)kc + 1];
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (k0 + t + 1024 * u < K) {
-                const double mu = (double)be[u] / (double)N;
-                double var = ((double)mxv[u] - mu) * (mu - (double)mnv[u]);
-                var = var > 0 ? var : 0;
-                s1 += fabs(mu);
-                s2 += var;
-                s3 += mu * mu;
-            }
-        }
-    }
-    s1 = wave_sum(s1);
-    s2 = wave_sum(s2);
-    s3 = wave_sum(s3);
-    if ((t & 63) == 0) {
-        red[0][t >> 6] = s1;
-        red[1][t >> 6] = s2;
-        red[2][t >> 6] = s3;
+    // S1, S2, S3: the block's 16 columns in order, then across blocks
+    if (grp == 0) {
+        double t1 = 0, t2 = 0, t3 = 0;
+        if (k < K) row_terms(sum, mx, mn, N, t1, t2, t3);
+        terms[kl][0] = t1;
+        terms[kl][1] = t2;
+        terms[kl][2] = t3;
     }
     __syncthreads();
-    if (t < 3) {
-        double v = 0;
-        for (int w = 0; w < 16; ++w) v += red[t][w];
-        S[t] = v;
+    double s1 = 0, s2 = 0, s3 = 0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            s1 += terms[c][0];
+            s2 += terms[c][1];
+            s3 += terms[c][2];
+        }
     }
+    publish_and_fold_S(s1, s2, s3, s_partial, ticket, S);
 }
 
 // ---------------------------------------------------------------------------
@@ -445,41 +513,53 @@ static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t
 
 constexpr int ENC_ROWS_PER_BLOCK = 128;  // n-rows per block in the transposed layout
 
+// per-block partials of (S1, S2, S3): [blocks][3] doubles at the start of the scratch area
+static size_t s_partial_bytes(const vabft_problem* p) {
+    const size_t blocks = ((size_t)p->K + 15) / 16;  // both layouts finish 16 rows k per block
+    return (blocks * 3 * sizeof(double) + 255) / 256 * 256;
+}
+
 size_t encode_workspace_bytes(const vabft_problem* p) {
-    if (!p->transB) return 0;
-    const size_t acc_bytes = p->dtype == VABFT_F64 ? 8 : 4;
-    const size_t nsplit = ((size_t)p->N + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
-    return nsplit * 4 * (size_t)p->K * acc_bytes;  // (sum, max, min, weighted sum) per slab
+    size_t bytes = s_partial_bytes(p);
+    if (p->transB) {
+        const size_t acc_bytes = p->dtype == VABFT_F64 ? 8 : 4;
+        const size_t nsplit = ((size_t)p->N + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
+        bytes += nsplit * 4 * (size_t)p->K * acc_bytes;  // (sum, max, min, weighted sum) per slab
+    }
+    return bytes;
 }
 
 template <typename T, bool W>
 static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, void* d_Be2, void* d_bstat, double* d_S,
-                         void* ws, hipStream_t st) {
+                         void* ws, int32_t* ticket, hipStream_t st) {
     using acc_t = typename Elem<T>::acc_t;
+    static_assert(ENC_ROWS_WAVES == 16, "s_partial_bytes assumes 16 rows k per block");
     const int vec_ok = aligned16(dB) && ((p->ldb * Elem<T>::bytes) % 16 == 0);
+    double* s_partial = reinterpret_cast<double*>(ws);
+    const int kblocks = (p->K + 15) / 16;
     if (!p->transB) {
-        encode_rows_kernel<T, W><<<dim3((p->K + 3) / 4), dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, (acc_t*)d_Be,
-                                                                             (acc_t*)d_Be2, (acc_t*)d_bstat, vec_ok);
+        encode_rows_kernel<T, W><<<dim3(kblocks), dim3(64 * ENC_ROWS_WAVES), 0, st>>>(
+            dB, p->K, p->N, p->ldb, (acc_t*)d_Be, (acc_t*)d_Be2, (acc_t*)d_bstat, vec_ok, s_partial, ticket, d_S);
     } else {
         constexpr int V = Elem<T>::vec;
         const int nsplit = (p->N + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
+        acc_t* part = reinterpret_cast<acc_t*>(reinterpret_cast<unsigned char*>(ws) + s_partial_bytes(p));
         dim3 grid((p->K + 64 * V - 1) / (64 * V), nsplit);
-        encode_cols_kernel<T, W><<<grid, dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, ENC_ROWS_PER_BLOCK, (acc_t*)ws,
+        encode_cols_kernel<T, W><<<grid, dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, ENC_ROWS_PER_BLOCK, part,
                                                              vec_ok);
-        encode_cols_combine_kernel<acc_t, W><<<dim3((p->K + 15) / 16), dim3(256), 0, st>>>(
-            (const acc_t*)ws, nsplit, p->K, p->N, (acc_t*)d_Be, (acc_t*)d_Be2, (acc_t*)d_bstat);
+        encode_cols_combine_kernel<acc_t, W><<<dim3(kblocks), dim3(256), 0, st>>>(
+            part, nsplit, p->K, p->N, (acc_t*)d_Be, (acc_t*)d_Be2, (acc_t*)d_bstat, s_partial, ticket, d_S);
     }
-    encode_aggregate_kernel<acc_t><<<dim3(1), dim3(1024), 0, st>>>((const acc_t*)d_Be, (const acc_t*)d_bstat, p->K,
-                                                                   p->N, d_S);
     return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
 }
 
 // d_Be2 == nullptr: plain encode; otherwise the weighted checksum is produced in the same pass
+// ws: scratch of encode_workspace_bytes(); ticket: one int32 that is zero between launches
 int encode_dispatch(const vabft_problem* p, const void* dB, void* d_Be, void* d_Be2, void* d_bstat, double* d_S,
-                    void* ws, hipStream_t st) {
-#define VABFT_ENC_CASE(T)                                                            \
-    return d_Be2 ? encode_launch<T, true>(p, dB, d_Be, d_Be2, d_bstat, d_S, ws, st) \
-                 : encode_launch<T, false>(p, dB, d_Be, nullptr, d_bstat, d_S, ws, st)
+                    void* ws, int32_t* ticket, hipStream_t st) {
+#define VABFT_ENC_CASE(T)                                                                    \
+    return d_Be2 ? encode_launch<T, true>(p, dB, d_Be, d_Be2, d_bstat, d_S, ws, ticket, st) \
+                 : encode_launch<T, false>(p, dB, d_Be, nullptr, d_bstat, d_S, ws, ticket, st)
     switch (p->dtype) {
         case VABFT_F64: VABFT_ENC_CASE(double);
         case VABFT_F32: VABFT_ENC_CASE(float);

@@ -194,7 +194,10 @@ __device__ __forceinline__ void gemm16_store_c(const GemmArgs& g, const f32x16_t
                 const raw16 v = *reinterpret_cast<const raw16*>(stage + r * PITCH + schunk * 16);
                 const int gi = row0 + wm * 128 + mi * 32 + r;
                 const int gj = col0 + wn * 128 + schunk * 8;
-                *reinterpret_cast<raw16*>(C + (int64_t)gi * g.ldc + gj) = v;
+                // C is not read again by this kernel: non-temporal store (measured 1.3 % of kernel time)
+                typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_st;
+                __builtin_nontemporal_store(__builtin_bit_cast(u32x4_st, v),
+                                            reinterpret_cast<u32x4_st*>(C + (int64_t)gi * g.ldc + gj));
             }
             asm volatile("" ::: "memory");
         }

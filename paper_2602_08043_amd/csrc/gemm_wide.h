@@ -271,7 +271,9 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
         const raw16 q = *reinterpret_cast<const raw16*>(tile + r * PITCH + c);
         const int gi = trow0 + r, gj = tcol0 + c;
         if (!EDGE) {
-            *reinterpret_cast<raw16*>(C + (int64_t)gi * g.ldc + gj) = q;
+            typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_st;
+            __builtin_nontemporal_store(__builtin_bit_cast(u32x4_st, q),
+                                        reinterpret_cast<u32x4_st*>(C + (int64_t)gi * g.ldc + gj));
         } else if (gi < g.M) {
             if (g.c_vec_ok && gj + V <= g.N) {
                 *reinterpret_cast<raw16*>(C + (int64_t)gi * g.ldc + gj) = q;

@@ -12,7 +12,7 @@ namespace vabft {
 size_t encode_workspace_bytes(const vabft_problem* p);
 // d_Be2 / d_expected2 may be null (no position-weighted checksum)
 int encode_dispatch(const vabft_problem* p, const void* dB, void* d_Be, void* d_Be2, void* d_bstat, double* d_S,
-                    void* ws, hipStream_t st);
+                    void* ws, int32_t* ticket, hipStream_t st);
 int threshold_dispatch(const vabft_problem* p, const void* dA, const void* d_Be, const void* d_Be2, const double* d_S,
                        double e_max, double c_sigma, void* d_astat, void* d_expected, void* d_expected2, void* d_T,
                        hipStream_t st);
