@@ -283,6 +283,30 @@ def main():
         vg.encode(B)
         vg.threshold(A, e_max)
 
+    # ---- offline (post-quantisation) mode on the paper's BF16 tightness-table workloads: U(0,1),
+    #      n x n x n, e_max = 2 u_output, plain GEMM followed by the post-hoc check of the stored C
+    if not args.no_quality and dt == "bf16":
+        g2 = torch.Generator(device="cuda")
+        g2.manual_seed(4321)
+        table = {}
+        for n in (128, 256, 512, 1024, 2048):
+            vo = VerifiedGemm(n, n, n, "bf16", 0)
+            e_off = vb.vabft_default_emax_offline("bf16", n, n)
+            sT = sE = 0.0
+            fp = 0
+            trials = 50
+            for _ in range(trials):
+                Ao = torch.rand((n, n), generator=g2, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+                Bo = torch.rand((n, n), generator=g2, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+                vo.run_offline(Ao, Bo, e_off)
+                fp += int(vo.nflag.item() > 0)
+                sT += float(vo.T.double().mean())
+                sE += float(vo.E.double().abs().mean())
+            table[str(n)] = {"threshold_mean": sT / trials, "actual_diff_mean": sE / trials,
+                             "tightness": sT / max(sE, 1e-300), "false_positive_trials": fp, "trials": trials}
+        out["quality"]["offline_bf16_uniform01"] = {"e_max": vb.vabft_default_emax_offline("bf16", 128, 128),
+                                                    "by_size": table}
+
     # ---- the CPU oracle timed on the host cores (bounded: one full trial of the workload)
     if not args.no_cpu_baseline:
         from oracle import vabft_oracle as orc

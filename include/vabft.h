@@ -208,6 +208,19 @@ int vabft_locate_correct(const vabft_problem* p, void* dC, const void* d_expecte
                          const int32_t* d_flags, int32_t correct, int32_t* d_loc, void* d_delta,
                          int32_t* d_ncorrected, void* stream);
 
+/* ---- Offline (post-hoc) verification (section 3.6 "Verification output precision: Offline vs.
+ * Online ABFT"): the check is made on a product that already sits in memory in the output type,
+ * whoever computed it.  d_expected / d_T come from vabft_threshold, called with an e_max for the
+ * output precision (vabft_default_emax_offline: 2 u_output for BF16 / FP16 outputs, i.e. 2^-7 and
+ * 2^-10, the paper's "e_max ~ 2 u_output"; the accumulator-level default for FP32 / FP64).
+ *   d_rowsum [M] acc : sum_j C[i][j] over the stored elements, accumulated in acc
+ *   d_E, d_flags, d_nflag as in vabft_gemm_verified.
+ * One streaming pass over C. */
+double vabft_default_emax_offline(int32_t dtype, int32_t K, int32_t N);
+int vabft_check_offline(const vabft_problem* p, const void* dC, const void* d_expected,
+                        const void* d_T, void* d_rowsum, void* d_E, int32_t* d_flags,
+                        int32_t* d_nflag, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

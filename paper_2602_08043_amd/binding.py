@@ -20,7 +20,7 @@ DTYPE_CODE = {"f64": VABFT_F64, "f32": VABFT_F32, "f16": VABFT_F16, "bf16": VABF
 EXPORTS = ("vabft_status_string", "vabft_workspace_bytes", "vabft_workspace_init", "vabft_default_emax",
            "vabft_encode", "vabft_threshold", "vabft_gemm_verified", "vabft_gemm_verified_fused",
            "vabft_encode_weighted", "vabft_threshold_weighted", "vabft_gemm_verified_weighted",
-           "vabft_locate_correct")
+           "vabft_locate_correct", "vabft_default_emax_offline", "vabft_check_offline")
 
 
 class Problem(Structure):
@@ -95,6 +95,11 @@ def load(path: str | None = None):
     lib.vabft_locate_correct.restype = ctypes.c_int
     lib.vabft_locate_correct.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                          c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.vabft_default_emax_offline.restype = c_double
+    lib.vabft_default_emax_offline.argtypes = [c_int32, c_int32, c_int32]
+    lib.vabft_check_offline.restype = ctypes.c_int
+    lib.vabft_check_offline.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                        c_void_p, c_void_p]
     if path is None:
         _lib = lib
     return lib
@@ -186,3 +191,14 @@ def vabft_locate_correct(p: Problem, dC, d_expected, d_expected2, d_rowsum, d_ro
     rc = load().vabft_locate_correct(byref(p), dC, d_expected, d_expected2, d_rowsum, d_rowsum2, d_flags,
                                      int(correct), d_loc, d_delta, d_ncorrected, stream)
     return _check(rc, "vabft_locate_correct", check)
+
+
+def vabft_default_emax_offline(dtype, K: int, N: int) -> float:
+    code = DTYPE_CODE[dtype] if isinstance(dtype, str) else int(dtype)
+    return float(load().vabft_default_emax_offline(code, K, N))
+
+
+def vabft_check_offline(p: Problem, dC, d_expected, d_T, d_rowsum, d_E, d_flags, d_nflag, stream=None,
+                        check=True) -> int:
+    rc = load().vabft_check_offline(byref(p), dC, d_expected, d_T, d_rowsum, d_E, d_flags, d_nflag, stream)
+    return _check(rc, "vabft_check_offline", check)

@@ -344,6 +344,25 @@ double vabft_default_emax(int32_t dtype, int32_t K, int32_t N) {
     return paper > measured ? paper : measured;
 }
 
+double vabft_default_emax_offline(int32_t dtype, int32_t K, int32_t N) {
+    // section 3.6 "Practical recommendations": a check made after a 16-bit write-back sees one
+    // rounding of every element to the output type, e_max ~ 2 u_output
+    if (dtype == VABFT_BF16) return 2.0 * 0.00390625;       // 2 * 2^-8
+    if (dtype == VABFT_F16) return 2.0 * 0.00048828125;     // 2 * 2^-11
+    return vabft_default_emax(dtype, K, N);
+}
+
+int vabft_check_offline(const vabft_problem* p, const void* dC, const void* d_expected, const void* d_T,
+                        void* d_rowsum, void* d_E, int32_t* d_flags, int32_t* d_nflag, void* stream) {
+    if (!problem_ok(p) || !dC || !d_expected || !d_T || !d_rowsum || !d_E || !d_flags || !d_nflag) return VABFT_EINVAL;
+    const size_t ab = acc_bytes(p->dtype);
+    if (!aligned_to(dC, elem_bytes(p->dtype)) || !aligned_to(d_expected, ab) || !aligned_to(d_T, ab) ||
+        !aligned_to(d_rowsum, ab) || !aligned_to(d_E, ab) || !aligned_to(d_flags, 4) || !aligned_to(d_nflag, 4))
+        return VABFT_EINVAL;
+    zero_int_kernel<<<1, 1, 0, (hipStream_t)stream>>>(d_nflag);
+    return check_offline_dispatch(p, dC, d_expected, d_T, d_rowsum, d_E, d_flags, d_nflag, (hipStream_t)stream);
+}
+
 int vabft_encode(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S, void* d_workspace,
                  size_t workspace_bytes, void* stream) {
     if (!problem_ok(p) || !dB || !d_Be || !d_bstat || !d_S) return VABFT_EINVAL;

@@ -507,6 +507,63 @@ __global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restr
 }
 
 // ---------------------------------------------------------------------------
+// Offline check (section 3.6 "Offline ABFT"): row sums of the product as it sits in memory after
+// quantisation to the output type, compared with the expected checksum.  One wavefront per row.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void check_offline_kernel(const void* __restrict__ C, int M, int N, int64_t ldc,
+                                                            const typename Elem<T>::acc_t* __restrict__ expected,
+                                                            const typename Elem<T>::acc_t* __restrict__ Tthr,
+                                                            typename Elem<T>::acc_t* __restrict__ rowsum,
+                                                            typename Elem<T>::acc_t* __restrict__ E,
+                                                            int32_t* __restrict__ flags, int32_t* __restrict__ nflag,
+                                                            int vec_ok) {
+    using acc_t = typename Elem<T>::acc_t;
+    constexpr int V = Elem<T>::vec;
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= M) return;
+    const char* row = reinterpret_cast<const char*>(C) + (int64_t)m * ldc * Elem<T>::bytes;
+    acc_t part[4] = {0, 0, 0, 0};
+    int done = 0;
+    if (vec_ok) {
+        const int nchunks = N / V;
+        int c = lane;
+        for (; c + 192 < nchunks; c += 256) {
+            raw16 r[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) r[u] = ld16(row + (int64_t)(c + 64 * u) * 16);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                acc_t v[V];
+                Unpack<T>::run(r[u], v);
+                acc_t cs = 0;
+#pragma unroll
+                for (int e = 0; e < V; ++e) cs += v[e];
+                part[u] += cs;
+            }
+        }
+        for (; c < nchunks; c += 64) {
+            acc_t v[V];
+            Unpack<T>::run(ld16(row + (int64_t)c * 16), v);
+#pragma unroll
+            for (int e = 0; e < V; ++e) part[0] += v[e];
+        }
+        done = nchunks * V;
+    }
+    for (int n = done + lane; n < N; n += 64) part[1] += Unpack<T>::one(row, n);
+    const acc_t s = wave_sum((part[0] + part[1]) + (part[2] + part[3]));
+    if (lane == 0) {
+        const acc_t e = expected[m] - s;
+        const int f = !(fabs(e) <= Tthr[m]);
+        rowsum[m] = s;
+        E[m] = e;
+        flags[m] = f;
+        if (f) atomicAdd(nflag, 1);
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -599,6 +656,29 @@ int threshold_dispatch(const vabft_problem* p, const void* dA, const void* d_Be,
     }
 #undef VABFT_THR_CASE
     return VABFT_EINVAL;
+}
+
+int check_offline_dispatch(const vabft_problem* p, const void* dC, const void* d_expected, const void* d_T,
+                           void* d_rowsum, void* d_E, int32_t* d_flags, int32_t* d_nflag, hipStream_t st) {
+    const dim3 grid((p->M + 3) / 4), block(256);
+#define VABFT_OFF_CASE(T)                                                                                           \
+    {                                                                                                               \
+        using acc_t = typename Elem<T>::acc_t;                                                                      \
+        const int vec_ok = aligned16(dC) && ((p->ldc * Elem<T>::bytes) % 16 == 0);                                  \
+        check_offline_kernel<T><<<grid, block, 0, st>>>(dC, p->M, p->N, p->ldc, (const acc_t*)d_expected,           \
+                                                        (const acc_t*)d_T, (acc_t*)d_rowsum, (acc_t*)d_E, d_flags,  \
+                                                        d_nflag, vec_ok);                                           \
+        break;                                                                                                      \
+    }
+    switch (p->dtype) {
+        case VABFT_F64: VABFT_OFF_CASE(double)
+        case VABFT_F32: VABFT_OFF_CASE(float)
+        case VABFT_F16: VABFT_OFF_CASE(f16_t)
+        case VABFT_BF16: VABFT_OFF_CASE(bf16_t)
+        default: return VABFT_EINVAL;
+    }
+#undef VABFT_OFF_CASE
+    return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
 }
 
 }  // namespace vabft

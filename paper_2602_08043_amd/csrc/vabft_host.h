@@ -16,6 +16,8 @@ int encode_dispatch(const vabft_problem* p, const void* dB, void* d_Be, void* d_
 int threshold_dispatch(const vabft_problem* p, const void* dA, const void* d_Be, const void* d_Be2, const double* d_S,
                        double e_max, double c_sigma, void* d_astat, void* d_expected, void* d_expected2, void* d_T,
                        hipStream_t st);
+int check_offline_dispatch(const vabft_problem* p, const void* dC, const void* d_expected, const void* d_T,
+                           void* d_rowsum, void* d_E, int32_t* d_flags, int32_t* d_nflag, hipStream_t st);
 
 // gemm*.hip
 struct InjectArgs {

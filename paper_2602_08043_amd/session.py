@@ -160,6 +160,27 @@ class VerifiedGemm:
         self.gemm_weighted(A, B, inj)
         self.locate_correct(correct)
 
+    # ---- offline (post-quantisation) check ---------------------------------------------
+    def check_offline(self, C: torch.Tensor | None = None):
+        """Row sums of a stored product (default: this session's C) against expected / T."""
+        C = self.C if C is None else C
+        return vb.vabft_check_offline(self.problem, C.data_ptr(), self.expected.data_ptr(), self.T.data_ptr(),
+                                      self.rowsum.data_ptr(), self.E.data_ptr(), self.flags.data_ptr(),
+                                      self.nflag.data_ptr(), self._stream())
+
+    def run_offline(self, A, B, e_max=None, c_sigma=2.5, inj=None):
+        """Plain (or fault-injected) GEMM, then the post-hoc check on the stored C with an e_max for
+        the output precision."""
+        if e_max is None:
+            e_max = vb.vabft_default_emax_offline(self.dtype, self.K, self.N)
+        self.encode(B)
+        self.threshold(A, e_max, c_sigma)
+        if inj is None:
+            self.gemm(A, B, 0)
+        else:
+            self.gemm(A, B, 1, inj)  # the injector lives in the verified kernel; its check is overwritten below
+        self.check_offline()
+
     def inject_records(self):
         """Downloaded injection log as a list of (row, col, bit, before, after), sorted."""
         n = int(self.ninj.item())

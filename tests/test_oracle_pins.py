@@ -438,3 +438,72 @@ def test_verify_reports_weighted_quantities():
     assert np.allclose(o["expected2"], o["rowsum2"], rtol=0, atol=1e-9 * o["scale_rowsum2"].max())
     assert np.allclose(o["rowsum2"], ((A @ B) * w).sum(axis=1), rtol=1e-12, atol=1e-9)
     assert np.all(o["scale_rowsum2"] >= np.abs(o["rowsum2"]))
+
+
+# --------------------------------------------------------------------------
+# offline (post-quantisation) verification, section 3.6
+# --------------------------------------------------------------------------
+def test_quantize_known_values():
+    x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 3.14159, 65520.0, 1e39, -0.0])
+    assert orc.quantize(x, "bf16").tolist() == [1.0, 1.015625, 3.140625, 65536.0, math.inf, -0.0]
+    y = np.array([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 65519.9, 65520.0, 2.0 ** -25, 2.0 ** -24])
+    assert orc.quantize(y, "f16").tolist() == [1.0, 1.0 + 2.0 ** -9, 65504.0, math.inf, 0.0, 2.0 ** -24]
+    assert np.isnan(orc.quantize(np.array([np.nan]), "bf16")[0])
+    z = np.array([1.0 + 2.0 ** -24, 1.0 + 3 * 2.0 ** -24, 0.1])
+    assert orc.quantize(z, "f32").tolist() == [1.0, 1.0 + 2.0 ** -22, float(np.float32(0.1))]
+    assert orc.quantize(z, "f64").tolist() == z.tolist()
+
+
+def test_quantize_agrees_with_the_input_generators_rounding():
+    g = np.random.Generator(np.random.Philox(key=[5, 5]))
+    x = (g.standard_normal(20000) * np.exp(g.uniform(-20, 20, 20000))).astype(np.float32).astype(np.float64)
+    for dt in ("bf16", "f16"):
+        with np.errstate(over="ignore"):
+            want = orc.decode(wl.to_storage(x, dt), dt)
+        assert np.array_equal(orc.quantize(x, dt), want)
+
+
+def test_offline_difference_is_online_difference_plus_rounding_of_c():
+    cfg = wl.make_config("c2_bf16_4096", seed=2, shape=(48, 200, 64))
+    o = orc.verify(cfg["A"], cfg["B"], "bf16", 0)
+    rs_off = orc.row_sums_offline(o["C"], "bf16")
+    E_off = orc.verification_difference(o["expected"], rs_off)
+    resid = (o["C"] - orc.quantize(o["C"], "bf16")).sum(axis=1)
+    assert np.allclose(E_off - o["E"], resid, rtol=0, atol=1e-9)
+    # every element moves by at most half a unit in the last place of the output type
+    assert np.all(np.abs(o["C"] - orc.quantize(o["C"], "bf16")) <= 2.0 ** -8 * np.abs(o["C"]) * (1 + 1e-6))
+    # small integers survive the rounding: the offline difference is exactly zero
+    g = np.random.Generator(np.random.Philox(key=[5, 6]))
+    A = g.integers(-1, 2, size=(16, 24)).astype(np.float64)
+    B = g.integers(-1, 2, size=(24, 40)).astype(np.float64)
+    C = orc.gemm(A, B)
+    assert not orc.verification_difference(orc.expected_checksum(A, orc.encode_checksum(B)),
+                                           orc.row_sums_offline(C, "bf16")).any()
+
+
+def test_offline_difference_follows_the_uniform_rounding_model():
+    """U(0,1) BF16 inputs: each stored element carries an independent rounding error, uniform over
+    one unit in the last place, so E_i ~ N(0, sum_j ulp_ij^2 / 12) and mean |E| = sqrt(2/pi) sigma."""
+    n = 256
+    g = np.random.Generator(np.random.Philox(key=[5, 7]))
+    A = wl.to_storage(g.random((n, n)), "bf16")
+    B = wl.to_storage(g.random((n, n)), "bf16")
+    o = orc.verify(A, B, "bf16", 0)
+    E_off = orc.verification_difference(o["expected"], orc.row_sums_offline(o["C"], "bf16"))
+    ulp = 2.0 ** (np.floor(np.log2(o["C"])) - 7)
+    sigma = np.sqrt((ulp ** 2).sum(axis=1) / 12.0)
+    ratio = np.abs(E_off).mean() / (math.sqrt(2.0 / math.pi) * sigma.mean())
+    assert 0.85 < ratio < 1.15, ratio
+    # with e_max = 2 u_output (2^-7, the paper quotes 8e-3) nothing is flagged and the threshold is
+    # one to two orders of magnitude above the actual difference (the paper's table: 48x - 158x)
+    T = orc.threshold(orc.decode(A, "bf16"), orc.decode(B, "bf16"), orc.default_emax_offline("bf16", n, n))
+    assert not orc.fault_flags(E_off, T).any()
+    assert 40 < T.mean() / np.abs(E_off).mean() < 400
+
+
+def test_offline_emax_is_twice_the_output_unit_roundoff():
+    assert orc.default_emax_offline("bf16", 4096, 4096) == 2.0 ** -7
+    assert abs(orc.default_emax_offline("bf16", 1, 1) - 8e-3) < 0.03 * 8e-3      # the table's e_max for BF16
+    assert abs(orc.default_emax_offline("f16", 1, 1) - 1e-3) < 0.03 * 1e-3       # "~1e-3 for FP16"
+    assert orc.default_emax_offline("f32", 512, 256) == orc.default_emax("f32", 512, 256)
+    assert orc.default_emax_offline("f64", 512, 256) == orc.default_emax("f64", 512, 256)
