@@ -151,6 +151,15 @@ def main():
     ms_locate = timed(lambda: vg.locate_correct(1), args.steps, args.warmup)
     ms_enc_w = timed(lambda: vg.encode_weighted(B), args.steps, args.warmup)
     ms_thr_w = timed(lambda: vg.threshold_weighted(A, e_max), args.steps, args.warmup)
+    # ---- row + column check in one launch
+    vg.encode(B)
+    vg.threshold(A, e_max)
+    vg.encode_a(A)
+    vg.threshold_cols(B)
+    ms_gemm_rc = timed(lambda: vg.gemm_rc(A, B), args.steps, args.warmup)
+    ncol_timed = int(vg.ncolflag.item())
+    ms_enc_a = timed(lambda: vg.encode_a(A), args.steps, args.warmup)
+    ms_thr_cols = timed(lambda: vg.threshold_cols(B), args.steps, args.warmup)
     vg.encode(B)
     vg.threshold(A, e_max)
 
@@ -216,6 +225,10 @@ def main():
     out["weighted_route"] = {"ms_gemm_with_weighted_rowsums": ms_gemm_weighted, "ms_locate_correct": ms_locate,
                              "ms_encode_weighted_warm": ms_enc_w, "ms_threshold_weighted_warm": ms_thr_w,
                              "gemm_overhead_pct_vs_plain": 100.0 * (ms_gemm_weighted / ms_plain - 1.0)}
+    out["row_column_route"] = {"ms_gemm_with_row_and_column_check": ms_gemm_rc, "ms_encode_a_warm": ms_enc_a,
+                               "ms_threshold_cols_warm": ms_thr_cols,
+                               "gemm_overhead_pct_vs_plain": 100.0 * (ms_gemm_rc / ms_plain - 1.0),
+                               "column_flags_in_timed_region": ncol_timed}
     out["flags_in_timed_region"] = nflag_timed
     out["ms"]["step_with_inner_events"] = ms_step_with_events
 

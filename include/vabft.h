@@ -208,6 +208,38 @@ int vabft_locate_correct(const vabft_problem* p, void* dC, const void* d_expecte
                          const int32_t* d_flags, int32_t correct, int32_t* d_loc, void* d_delta,
                          int32_t* d_ncorrected, void* stream);
 
+/* ---- Column checksums (section 2.2: c1 = [1 .. 1], A^c = [A; c1 A], C^{c1} = c1 A B, C^{c1'} = c1 C).
+ * A faulty element then raises the flag of its row AND of its column: the intersection localises it
+ * without the weighted checksum.  By the symmetry C^T = B^T A^T the column threshold is Algorithm 1 with
+ * the roles exchanged: column j of B (K entries) plays the row of A, column k of A (M entries) plays the
+ * row of B, M replaces N. */
+
+/* c1 A and the column statistics of A.  One streaming pass over A.
+ *   d_eA       [K] acc : sum_m A[m][k]
+ *   d_acolstat [3K] acc: (max, min, mean) of column k of A
+ *   d_SA       [3] double: S1, S2, S3 of Algorithm 1 formed from the columns of A */
+int vabft_encode_a(const vabft_problem* p, const void* dA, void* d_eA, void* d_acolstat,
+                   double* d_SA, void* d_workspace, size_t workspace_bytes, void* stream);
+
+/* Column statistics of B, expected column checksum and column thresholds.  One pass over B.
+ *   d_bcolstat     [3N] acc: (max, min, mean) of column n of the logical K x N matrix
+ *   d_expected_col [N] acc : sum_k eA[k] * B[k][n]
+ *   d_Tcol         [N] acc : e_max * (T_det + T_var23 + T_var4) with the roles exchanged */
+int vabft_threshold_cols(const vabft_problem* p, const void* dB, const void* d_eA,
+                         const double* d_SA, double e_max, double c_sigma, void* d_bcolstat,
+                         void* d_expected_col, void* d_Tcol, void* d_workspace,
+                         size_t workspace_bytes, void* stream);
+
+/* vabft_gemm_verified(verify = 1) plus the column check in the same launch:
+ *   d_colsum [N] acc : sum_i acc[i][j] on the accumulator tile before quantisation (after the injector)
+ *   d_Ecol [N] acc, d_colflags [N] int32, d_ncolflag [1] int32: as their row counterparts. */
+int vabft_gemm_verified_rc(const vabft_problem* p, const void* dA, const void* dB, void* dC,
+                           const void* d_expected, const void* d_T, const void* d_expected_col,
+                           const void* d_Tcol, const vabft_inject* inj, void* d_rowsum, void* d_E,
+                           int32_t* d_flags, int32_t* d_nflag, void* d_colsum, void* d_Ecol,
+                           int32_t* d_colflags, int32_t* d_ncolflag, vabft_inject_rec* d_injlog,
+                           int32_t* d_ninj, void* d_workspace, size_t workspace_bytes, void* stream);
+
 /* ---- Offline (post-hoc) verification (section 3.6 "Verification output precision: Offline vs.
  * Online ABFT"): the check is made on a product that already sits in memory in the output type,
  * whoever computed it.  d_expected / d_T come from vabft_threshold, called with an e_max for the

@@ -21,6 +21,8 @@ no blocking, fusion or reordering beyond what the definitions state:
   * Offline (post-quantisation) verification: row sums of the product after it was rounded to the
     output type, with e_max = 2 u_output: section 3.6 "Verification output precision: Offline vs.
     Online ABFT" and "Practical recommendations".
+  * Column checksums c1 = [1 .. 1], A^c = [A; c1 A], C^{c1} = c1 A B, C^{c1'} = c1 C (section 2.2) with the
+    threshold of Algorithm 1 applied to C^T = B^T A^T (our reading: the paper gives the row form only).
   * Position-weighted checksum r2, checksum differences D1 / D2, localisation
     j = D2 / D1 - 1 and correction C[i][j] -= D1: section 2.2 "Error
     localization and correction".
@@ -424,3 +426,56 @@ def default_emax_offline(dtype: str, K: int, N: int) -> float:
     if dtype in ("bf16", "f16"):
         return 2.0 * UNIT_ROUNDOFF[dtype]
     return default_emax(dtype, K, N)
+
+
+# --------------------------------------------------------------------------
+# column checksums (section 2.2), threshold by the symmetry C^T = B^T A^T
+# --------------------------------------------------------------------------
+def verify_columns(A_st, B_st, dtype: str, transB: int = 0, e_max: float | None = None,
+                   c_sigma: float = C_SIGMA_DEFAULT, full_gemm: bool = True):
+    """All oracle quantities of the column check of one GEMM.
+
+    eA = c1 A (column sums of A); expected_col = eA B = C^{c1}; colsum = c1 C = C^{c1'};
+    E_col = expected_col - colsum; a column is flagged if |E_col| > T_col.  T_col is Algorithm 1 with
+    the roles exchanged: column j of B (K entries) is the "row of A", column k of A (M entries) is
+    the "row of B", and M (the number of terms of every checksum entry) takes the place of N."""
+    A = decode(A_st, dtype)
+    B = logical_B(B_st, dtype, transB)
+    M, K = A.shape
+    N = B.shape[1]
+    if e_max is None:
+        e_max = default_emax(dtype, K, max(N, M))
+    out = {"e_max": e_max}
+    out["eA"] = A.sum(axis=0)
+    mxa, mna, mua = A.max(axis=0), A.min(axis=0), A.mean(axis=0)
+    out["acolstat"] = np.stack([mxa, mna, mua], axis=1)
+    var_a = extrema_variance(mxa, mna, mua)
+    S1, S2, S3 = float(np.abs(mua).sum()), float(var_a.sum()), float((mua * mua).sum())
+    out["SA"] = np.array([S1, S2, S3])
+    mxb, mnb, mub = B.max(axis=0), B.min(axis=0), B.mean(axis=0)
+    out["bcolstat"] = np.stack([mxb, mnb, mub], axis=1)
+    var_b = extrema_variance(mxb, mnb, mub)
+    out["expected_col"] = out["eA"] @ B
+    t_det = M * np.abs(mub) * S1
+    t_var23 = c_sigma * np.sqrt(M * mub * mub * S2 + float(M) * M * var_b * S3)
+    t_var4 = c_sigma * math.sqrt(M) * np.sqrt(var_b) * math.sqrt(S2)
+    out["T_col"] = e_max * (t_det + t_var23 + t_var4)
+    absA_colsum = np.abs(A).sum(axis=0)
+    out["scale_eA"] = absA_colsum
+    out["scale_expected_col"] = np.abs(out["eA"]) @ np.abs(B)
+    out["scale_colsum"] = absA_colsum @ np.abs(B)
+    if full_gemm:
+        C = gemm(A, B)
+        out["C"] = C
+        out["colsum"] = C.sum(axis=0)
+        out["E_col"] = out["expected_col"] - out["colsum"]
+        out["colflags"] = fault_flags(out["E_col"], out["T_col"])
+    return out
+
+
+def replay_faults_columns(colsum: np.ndarray, records) -> np.ndarray:
+    """Column sums after the logged faults: colsum[j] += (after - before)."""
+    out = np.array(colsum, dtype=np.float64, copy=True)
+    for (_i, j, _bit, before, after) in records:
+        out[j] = out[j] + (after - before)
+    return out

@@ -20,7 +20,8 @@ DTYPE_CODE = {"f64": VABFT_F64, "f32": VABFT_F32, "f16": VABFT_F16, "bf16": VABF
 EXPORTS = ("vabft_status_string", "vabft_workspace_bytes", "vabft_workspace_init", "vabft_default_emax",
            "vabft_encode", "vabft_threshold", "vabft_gemm_verified", "vabft_gemm_verified_fused",
            "vabft_encode_weighted", "vabft_threshold_weighted", "vabft_gemm_verified_weighted",
-           "vabft_locate_correct", "vabft_default_emax_offline", "vabft_check_offline")
+           "vabft_locate_correct", "vabft_default_emax_offline", "vabft_check_offline",
+           "vabft_encode_a", "vabft_threshold_cols", "vabft_gemm_verified_rc")
 
 
 class Problem(Structure):
@@ -100,6 +101,17 @@ def load(path: str | None = None):
     lib.vabft_check_offline.restype = ctypes.c_int
     lib.vabft_check_offline.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                         c_void_p, c_void_p]
+    lib.vabft_encode_a.restype = ctypes.c_int
+    lib.vabft_encode_a.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
+                                   c_void_p]
+    lib.vabft_threshold_cols.restype = ctypes.c_int
+    lib.vabft_threshold_cols.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_double, c_double, c_void_p,
+                                         c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.vabft_gemm_verified_rc.restype = ctypes.c_int
+    lib.vabft_gemm_verified_rc.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                           c_void_p, c_void_p, POINTER(Inject), c_void_p, c_void_p, c_void_p,
+                                           c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                           c_void_p, c_size_t, c_void_p]
     if path is None:
         _lib = lib
     return lib
@@ -202,3 +214,26 @@ def vabft_check_offline(p: Problem, dC, d_expected, d_T, d_rowsum, d_E, d_flags,
                         check=True) -> int:
     rc = load().vabft_check_offline(byref(p), dC, d_expected, d_T, d_rowsum, d_E, d_flags, d_nflag, stream)
     return _check(rc, "vabft_check_offline", check)
+
+
+def vabft_encode_a(p: Problem, dA, d_eA, d_acolstat, d_SA, d_workspace, workspace_bytes, stream=None,
+                   check=True) -> int:
+    rc = load().vabft_encode_a(byref(p), dA, d_eA, d_acolstat, d_SA, d_workspace, workspace_bytes, stream)
+    return _check(rc, "vabft_encode_a", check)
+
+
+def vabft_threshold_cols(p: Problem, dB, d_eA, d_SA, e_max, c_sigma, d_bcolstat, d_expected_col, d_Tcol, d_workspace,
+                         workspace_bytes, stream=None, check=True) -> int:
+    rc = load().vabft_threshold_cols(byref(p), dB, d_eA, d_SA, float(e_max), float(c_sigma), d_bcolstat,
+                                     d_expected_col, d_Tcol, d_workspace, workspace_bytes, stream)
+    return _check(rc, "vabft_threshold_cols", check)
+
+
+def vabft_gemm_verified_rc(p: Problem, dA, dB, dC, d_expected, d_T, d_expected_col, d_Tcol, inj, d_rowsum, d_E,
+                           d_flags, d_nflag, d_colsum, d_Ecol, d_colflags, d_ncolflag, d_injlog, d_ninj, d_workspace,
+                           workspace_bytes, stream=None, check=True) -> int:
+    rc = load().vabft_gemm_verified_rc(byref(p), dA, dB, dC, d_expected, d_T, d_expected_col, d_Tcol,
+                                       byref(inj) if inj is not None else None, d_rowsum, d_E, d_flags, d_nflag,
+                                       d_colsum, d_Ecol, d_colflags, d_ncolflag, d_injlog, d_ninj, d_workspace,
+                                       workspace_bytes, stream)
+    return _check(rc, "vabft_gemm_verified_rc", check)

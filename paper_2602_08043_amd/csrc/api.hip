@@ -48,6 +48,33 @@ __global__ __launch_bounds__(256) void finalize_kernel(const acc_t* __restrict__
 
 __global__ void zero_int_kernel(int32_t* p) { *p = 0; }
 
+// colsum[j] = sum over tile-rows of colpart[t][j] in a fixed order; E_col = expected_col - colsum;
+// flag = !(|E_col| <= T_col)   (section 2.2, the column form of Eq. abft-check)
+template <typename acc_t>
+__global__ __launch_bounds__(256) void finalize_cols_kernel(const acc_t* __restrict__ colpart, int nparts, int N,
+                                                            const acc_t* __restrict__ expected_col,
+                                                            const acc_t* __restrict__ Tcol, acc_t* __restrict__ colsum,
+                                                            acc_t* __restrict__ Ecol, int32_t* __restrict__ colflags,
+                                                            int32_t* __restrict__ ncolflag) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    int f = 0;
+    if (j < N) {
+        acc_t s = 0;
+        int t = 0;
+        for (; t + 3 < nparts; t += 4)
+            s += (colpart[(int64_t)t * N + j] + colpart[(int64_t)(t + 1) * N + j]) +
+                 (colpart[(int64_t)(t + 2) * N + j] + colpart[(int64_t)(t + 3) * N + j]);
+        for (; t < nparts; ++t) s += colpart[(int64_t)t * N + j];
+        const acc_t e = expected_col[j] - s;
+        f = !(fabs(e) <= Tcol[j]);
+        colsum[j] = s;
+        Ecol[j] = e;
+        colflags[j] = f;
+    }
+    const int cnt = __syncthreads_count(f);
+    if (threadIdx.x == 0 && cnt) atomicAdd(ncolflag, cnt);
+}
+
 // one stored element of C, read and written in the accumulator type
 template <typename T> struct CElem;
 template <> struct CElem<bf16_t> {
@@ -172,7 +199,9 @@ size_t gemm_workspace_bytes(const vabft_problem* p) {
     const bool is16 = p->dtype == VABFT_F16 || p->dtype == VABFT_BF16;
     // 16-bit: rowpart + 4 A-statistics partials + weighted rowpart per tile-column; wide types: two
     // row-sum partials per tile-column (one per wavefront column), plain and weighted
-    return tiles_n * (size_t)p->M * acc_bytes(p->dtype) * (is16 ? 6 : 4);
+    const size_t tiles_m = ((size_t)p->M + bm - 1) / bm;
+    // ... and the column-sum partials: one (16-bit) or two (wide) vectors of N per tile-row
+    return (tiles_n * (size_t)p->M * (is16 ? 6 : 4) + tiles_m * (size_t)p->N * (is16 ? 1 : 2)) * acc_bytes(p->dtype);
 }
 
 __global__ void fill_zero_kernel(uint32_t* p, size_t n) {
@@ -188,7 +217,7 @@ void workspace_init_launch(void* ws, size_t bytes, hipStream_t st) {
 int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* dC, void* d_expected, void* d_T,
                   int verify, const FusedArgs* fused, const vabft_inject* inj, void* d_rowsum, void* d_rowsum2,
                   void* d_E, int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
-                  void* ws, hipStream_t st) {
+                  void* ws, hipStream_t st, const ColArgs* cols) {
     GemmArgs a;
     a.A = dA;
     a.B = dB;
@@ -215,6 +244,8 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     // weighted partials: behind rowpart + apart (16-bit) resp. behind the two plain partials (wide)
     a.rowpart2 = ws ? wsb + tickets_bytes(p) + (size_t)a.tiles_n * p->M * ab * (is16 ? 5 : 2) : nullptr;
     a.rowsum2 = d_rowsum2;
+    a.colpart = ws ? wsb + tickets_bytes(p) + (size_t)a.tiles_n * p->M * ab * (is16 ? 6 : 4) : nullptr;
+    a.d_ncolflag = cols ? cols->d_ncolflag : nullptr;
     a.d_nflag = d_nflag;
     a.expected = d_expected;
     a.T = d_T;
@@ -269,7 +300,9 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
         }
     }
     int rc;
-    const int mode = !verify ? 0 : (a.inj.mode != 0 ? 2 : (d_rowsum2 ? 3 : 1));
+    // injector runs form every kind of sum; otherwise one extra kind per launch
+    const int mode = !verify ? 0 : (a.inj.mode != 0 ? 2 : (cols ? 4 : (d_rowsum2 ? 3 : 1)));
+    if (cols && d_rowsum2 && mode != 2) return VABFT_EUNSUPPORTED;
     switch (p->dtype) {
         case VABFT_BF16:
             rc = p->transB ? gemm16_launch_bf16_nt(a, mode, edge, st) : gemm16_launch_bf16_nn(a, mode, edge, st);
@@ -281,7 +314,22 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
         case VABFT_F64: rc = gemmw_launch_f64(a, p->transB, mode, edge, st); break;
         default: return VABFT_EINVAL;
     }
-    if (rc != VABFT_OK || !verify || in_kernel_finalize) return rc;
+    if (rc != VABFT_OK || !verify) return rc;
+    if (cols) {
+        const dim3 cgrid((p->N + 255) / 256), cblock(256);
+        const int ncparts = is16 ? a.tiles_m : 2 * a.tiles_m;
+        if (p->dtype == VABFT_F64)
+            finalize_cols_kernel<double><<<cgrid, cblock, 0, st>>>(
+                (const double*)a.colpart, ncparts, p->N, (const double*)cols->d_expected_col,
+                (const double*)cols->d_Tcol, (double*)cols->d_colsum, (double*)cols->d_Ecol, cols->d_colflags,
+                cols->d_ncolflag);
+        else
+            finalize_cols_kernel<float><<<cgrid, cblock, 0, st>>>(
+                (const float*)a.colpart, ncparts, p->N, (const float*)cols->d_expected_col, (const float*)cols->d_Tcol,
+                (float*)cols->d_colsum, (float*)cols->d_Ecol, cols->d_colflags, cols->d_ncolflag);
+        if (hipGetLastError() != hipSuccess) return VABFT_EDEVICE;
+    }
+    if (in_kernel_finalize) return rc;
     const dim3 grid((p->M + 255) / 256), block(256);
     const int nparts = is16 ? a.tiles_n : 2 * a.tiles_n;
     if (p->dtype == VABFT_F64)
@@ -316,8 +364,9 @@ const char* vabft_status_string(int status) {
 
 size_t vabft_workspace_bytes(const vabft_problem* p) {
     if (!problem_ok(p)) return 0;
-    const size_t a = encode_workspace_bytes(p), b = gemm_workspace_bytes(p);
-    return tickets_bytes(p) + round_up((a > b ? a : b) + 256, 256);
+    const size_t a = encode_workspace_bytes(p), b = gemm_workspace_bytes(p), c = cols_workspace_bytes(p);
+    const size_t m = a > b ? (a > c ? a : c) : (b > c ? b : c);
+    return tickets_bytes(p) + round_up(m + 256, 256);
 }
 
 int vabft_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream) {
@@ -473,6 +522,61 @@ int vabft_gemm_verified_weighted(const vabft_problem* p, const void* dA, const v
     return gemm_dispatch(p, dA, dB, dC, const_cast<void*>(d_expected), const_cast<void*>(d_T), 1, nullptr, inj,
                          d_rowsum, d_rowsum2, d_E, d_flags, d_nflag, d_injlog, d_ninj, d_workspace,
                          (hipStream_t)stream);
+}
+
+int vabft_encode_a(const vabft_problem* p, const void* dA, void* d_eA, void* d_acolstat, double* d_SA,
+                   void* d_workspace, size_t workspace_bytes, void* stream) {
+    if (!problem_ok(p) || !dA || !d_eA || !d_acolstat || !d_SA) return VABFT_EINVAL;
+    const size_t ab = acc_bytes(p->dtype);
+    if (!aligned_to(dA, elem_bytes(p->dtype)) || !aligned_to(d_eA, ab) || !aligned_to(d_acolstat, ab) ||
+        !aligned_to(d_SA, 8))
+        return VABFT_EINVAL;
+    if (!d_workspace || workspace_bytes < tickets_bytes(p) + cols_workspace_bytes(p) || !aligned_to(d_workspace, 16))
+        return VABFT_EWORKSPACE;
+    void* scratch = reinterpret_cast<unsigned char*>(d_workspace) + tickets_bytes(p);
+    return encode_a_dispatch(p, dA, d_eA, d_acolstat, d_SA, scratch, encode_ticket(p, d_workspace),
+                             (hipStream_t)stream);
+}
+
+int vabft_threshold_cols(const vabft_problem* p, const void* dB, const void* d_eA, const double* d_SA, double e_max,
+                         double c_sigma, void* d_bcolstat, void* d_expected_col, void* d_Tcol, void* d_workspace,
+                         size_t workspace_bytes, void* stream) {
+    if (!problem_ok(p) || !dB || !d_eA || !d_SA || !d_bcolstat || !d_expected_col || !d_Tcol) return VABFT_EINVAL;
+    if (!(e_max > 0.0) || !(c_sigma >= 0.0) || !isfinite(e_max) || !isfinite(c_sigma)) return VABFT_EINVAL;
+    const size_t ab = acc_bytes(p->dtype);
+    if (!aligned_to(dB, elem_bytes(p->dtype)) || !aligned_to(d_eA, ab) || !aligned_to(d_SA, 8) ||
+        !aligned_to(d_bcolstat, ab) || !aligned_to(d_expected_col, ab) || !aligned_to(d_Tcol, ab))
+        return VABFT_EINVAL;
+    if (!d_workspace || workspace_bytes < tickets_bytes(p) + cols_workspace_bytes(p) || !aligned_to(d_workspace, 16))
+        return VABFT_EWORKSPACE;
+    void* scratch = reinterpret_cast<unsigned char*>(d_workspace) + tickets_bytes(p);
+    return threshold_cols_dispatch(p, dB, d_eA, d_SA, e_max, c_sigma, d_bcolstat, d_expected_col, d_Tcol, scratch,
+                                   (hipStream_t)stream);
+}
+
+int vabft_gemm_verified_rc(const vabft_problem* p, const void* dA, const void* dB, void* dC, const void* d_expected,
+                           const void* d_T, const void* d_expected_col, const void* d_Tcol, const vabft_inject* inj,
+                           void* d_rowsum, void* d_E, int32_t* d_flags, int32_t* d_nflag, void* d_colsum, void* d_Ecol,
+                           int32_t* d_colflags, int32_t* d_ncolflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
+                           void* d_workspace, size_t workspace_bytes, void* stream) {
+    const int rc = check_gemm_args(p, dA, dB, dC, 1, inj, d_expected, d_T, d_rowsum, d_E, d_flags, d_nflag, d_injlog,
+                                   d_ninj, d_workspace, workspace_bytes);
+    if (rc != VABFT_OK) return rc;
+    if (!d_expected_col || !d_Tcol || !d_colsum || !d_Ecol || !d_colflags || !d_ncolflag) return VABFT_EINVAL;
+    const size_t ab = acc_bytes(p->dtype);
+    if (!aligned_to(d_expected_col, ab) || !aligned_to(d_Tcol, ab) || !aligned_to(d_colsum, ab) ||
+        !aligned_to(d_Ecol, ab) || !aligned_to(d_colflags, 4) || !aligned_to(d_ncolflag, 4))
+        return VABFT_EINVAL;
+    ColArgs c;
+    c.d_expected_col = d_expected_col;
+    c.d_Tcol = d_Tcol;
+    c.d_colsum = d_colsum;
+    c.d_Ecol = d_Ecol;
+    c.d_colflags = d_colflags;
+    c.d_ncolflag = d_ncolflag;
+    return gemm_dispatch(p, dA, dB, dC, const_cast<void*>(d_expected), const_cast<void*>(d_T), 1, nullptr, inj,
+                         d_rowsum, nullptr, d_E, d_flags, d_nflag, d_injlog, d_ninj, d_workspace, (hipStream_t)stream,
+                         &c);
 }
 
 int vabft_locate_correct(const vabft_problem* p, void* dC, const void* d_expected, const void* d_expected2,

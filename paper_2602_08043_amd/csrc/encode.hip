@@ -229,11 +229,14 @@ __global__ __launch_bounds__(1024) void encode_rows_kernel(const void* __restric
 // B stored N x K (weight layout): column reduction in two steps.
 // Step 1: block (kx, ny) reduces rows [ny*rows_per_block, ...) of 64*V columns.
 // part layout: [nsplit][4][K] (sum, max, min, weighted sum; the last only when W).
+// The weight of row n is n + 1 (the vector r2), or wvec[n] when a weight vector is given (then the
+// weighted sum is the dot product of every column with that vector).
 // ---------------------------------------------------------------------------
 template <typename T, bool W>
 __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict__ Bt, int K, int N, int64_t ldb,
                                                           int rows_per_block,
-                                                          typename Elem<T>::acc_t* __restrict__ part, int vec_ok) {
+                                                          typename Elem<T>::acc_t* __restrict__ part, int vec_ok,
+                                                          const typename Elem<T>::acc_t* __restrict__ wvec) {
     using acc_t = typename Elem<T>::acc_t;
     constexpr int V = Elem<T>::vec;
     __shared__ acc_t red[3][W ? 4 : 3][64 * V];  // waves 1..3 park their partials here
@@ -261,7 +264,7 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
             for (int u = 0; u < 4; ++u) {
                 acc_t v[V];
                 Unpack<T>::run(r[u], v);
-                const acc_t w = (acc_t)(n + 4 * u + 1);
+                const acc_t w = !W ? (acc_t)0 : (wvec ? wvec[n + 4 * u] : (acc_t)(n + 4 * u + 1));
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
                     sum[e] += v[e];
@@ -275,7 +278,7 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
             raw16 r0 = ld16(reinterpret_cast<const char*>(Bt) + ((int64_t)n * ldb + k0) * Elem<T>::bytes);
             acc_t v[V];
             Unpack<T>::run(r0, v);
-            const acc_t w = (acc_t)(n + 1);
+            const acc_t w = !W ? (acc_t)0 : (wvec ? wvec[n] : (acc_t)(n + 1));
 #pragma unroll
             for (int e = 0; e < V; ++e) {
                 sum[e] += v[e];
@@ -291,7 +294,7 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
                 if (k0 + e < K) {
                     acc_t x = Unpack<T>::one(Bt, (int64_t)n * ldb + k0 + e);
                     sum[e] += x;
-                    if constexpr (W) sum2[e] = fma((acc_t)(n + 1), x, sum2[e]);
+                    if constexpr (W) sum2[e] = fma(wvec ? wvec[n] : (acc_t)(n + 1), x, sum2[e]);
                     mx[e] = x > mx[e] ? x : mx[e];
                     mn[e] = x < mn[e] ? x : mn[e];
                 }
@@ -603,7 +606,7 @@ static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, voi
         acc_t* part = reinterpret_cast<acc_t*>(reinterpret_cast<unsigned char*>(ws) + s_partial_bytes(p));
         dim3 grid((p->K + 64 * V - 1) / (64 * V), nsplit);
         encode_cols_kernel<T, W><<<grid, dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, ENC_ROWS_PER_BLOCK, part,
-                                                             vec_ok);
+                                                             vec_ok, nullptr);
         encode_cols_combine_kernel<acc_t, W><<<dim3(kblocks), dim3(256), 0, st>>>(
             part, nsplit, p->K, p->N, (acc_t*)d_Be, (acc_t*)d_Be2, (acc_t*)d_bstat, s_partial, ticket, d_S);
     }
@@ -655,6 +658,120 @@ int threshold_dispatch(const vabft_problem* p, const void* dA, const void* d_Be,
         case VABFT_BF16: VABFT_THR_CASE(bf16_t);
     }
 #undef VABFT_THR_CASE
+    return VABFT_EINVAL;
+}
+
+// ---------------------------------------------------------------------------
+// Column checksums (section 2.2: c1 = [1 .. 1], A^c = [A; c1 A], C^{c1} = c1 A B).  By the symmetry
+// C^T = B^T A^T the column check is Algorithm 1 with the roles exchanged: column j of B (K entries) plays
+// the row of A, column k of A (M entries) plays the row of B, and M replaces N.
+// ---------------------------------------------------------------------------
+
+// Per column n of a K x N row-major B: fold the row-slab partials (sum, max, min, dot with c1 A) in slab
+// order and evaluate the column threshold.
+template <typename acc_t>
+__global__ __launch_bounds__(256) void threshold_cols_finish_kernel(const acc_t* __restrict__ part, int nsplit,
+                                                                    int N, int K, int M, const double* __restrict__ SA,
+                                                                    double e_max, double c_sigma,
+                                                                    acc_t* __restrict__ colstat,
+                                                                    acc_t* __restrict__ expected_col,
+                                                                    acc_t* __restrict__ Tcol) {
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    acc_t sum = 0, dot = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
+    for (int s = 0; s < nsplit; ++s) {
+        const acc_t* q = part + (int64_t)s * 4 * N;
+        sum += q[n];
+        const acc_t a = q[(int64_t)N + n], b = q[2 * (int64_t)N + n];
+        mx = a > mx ? a : mx;
+        mn = b < mn ? b : mn;
+        dot += q[3 * (int64_t)N + n];
+    }
+    const double mu = (double)sum / (double)K;
+    double var = ((double)mx - mu) * (mu - (double)mn);
+    var = var > 0 ? var : 0;
+    const double S1 = SA[0], S2 = SA[1], S3 = SA[2], dM = (double)M;
+    const double t_det = dM * fabs(mu) * S1;
+    const double t_var23 = c_sigma * sqrt(dM * mu * mu * S2 + dM * dM * var * S3);
+    const double t_var4 = c_sigma * sqrt(dM) * sqrt(var) * sqrt(S2);
+    colstat[3 * (int64_t)n + 0] = mx;
+    colstat[3 * (int64_t)n + 1] = mn;
+    colstat[3 * (int64_t)n + 2] = (acc_t)mu;
+    expected_col[n] = dot;
+    Tcol[n] = (acc_t)(e_max * (t_det + t_var23 + t_var4));
+}
+
+static vabft_problem swapped_problem(const vabft_problem* p, int32_t M, int32_t N, int32_t transB, int64_t lda,
+                                     int64_t ldb) {
+    vabft_problem q = *p;
+    q.M = M;
+    q.N = N;
+    q.transB = transB;
+    q.lda = lda;
+    q.ldb = ldb;
+    return q;
+}
+
+// scratch of the two column-side passes: encode of A as an (M rows) x (K columns) "weight layout" matrix, and
+// the slab partials of the column reduction over a K x N B
+size_t cols_workspace_bytes(const vabft_problem* p) {
+    const vabft_problem qa = swapped_problem(p, p->M, p->M, 1, p->lda, p->lda);
+    const size_t a = encode_workspace_bytes(&qa);
+    const size_t acc_bytes = p->dtype == VABFT_F64 ? 8 : 4;
+    const size_t nsplit = ((size_t)p->K + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
+    const size_t b = p->transB ? 0 : nsplit * 4 * (size_t)p->N * acc_bytes;
+    return a > b ? a : b;
+}
+
+// c1 A, column statistics of A and their aggregates: the encode of the N x K layout applied to A (M x K)
+int encode_a_dispatch(const vabft_problem* p, const void* dA, void* d_eA, void* d_acolstat, double* d_SA, void* ws,
+                      int32_t* ticket, hipStream_t st) {
+    const vabft_problem q = swapped_problem(p, p->M, p->M, 1, p->lda, p->lda);
+    return encode_dispatch(&q, dA, d_eA, nullptr, d_acolstat, d_SA, ws, ticket, st);
+}
+
+template <typename T>
+static int threshold_cols_launch(const vabft_problem* p, const void* dB, const void* d_eA, const double* d_SA,
+                                 double e_max, double c_sigma, void* d_bcolstat, void* d_expected_col, void* d_Tcol,
+                                 void* ws, hipStream_t st) {
+    using acc_t = typename Elem<T>::acc_t;
+    constexpr int V = Elem<T>::vec;
+    const int vec_ok = aligned16(dB) && ((p->ldb * Elem<T>::bytes) % 16 == 0);
+    const int nsplit = (p->K + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
+    acc_t* part = reinterpret_cast<acc_t*>(ws);
+    dim3 grid((p->N + 64 * V - 1) / (64 * V), nsplit);
+    // rows of the reduction = k (K of them), columns = n (N of them), weight of row k = (c1 A)[k]
+    encode_cols_kernel<T, true><<<grid, dim3(256), 0, st>>>(dB, p->N, p->K, p->ldb, ENC_ROWS_PER_BLOCK, part, vec_ok,
+                                                            (const acc_t*)d_eA);
+    threshold_cols_finish_kernel<acc_t><<<dim3((p->N + 255) / 256), dim3(256), 0, st>>>(
+        part, nsplit, p->N, p->K, p->M, d_SA, e_max, c_sigma, (acc_t*)d_bcolstat, (acc_t*)d_expected_col,
+        (acc_t*)d_Tcol);
+    return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
+}
+
+int threshold_cols_dispatch(const vabft_problem* p, const void* dB, const void* d_eA, const double* d_SA, double e_max,
+                            double c_sigma, void* d_bcolstat, void* d_expected_col, void* d_Tcol, void* ws,
+                            hipStream_t st) {
+    if (p->transB) {
+        // B stored N x K: its rows are the columns of the logical B, so this is the row pass with M := N, N := M
+        const vabft_problem q = swapped_problem(p, p->N, p->M, 0, p->ldb, p->ldb);
+        return threshold_dispatch(&q, dB, d_eA, nullptr, d_SA, e_max, c_sigma, d_bcolstat, d_expected_col, nullptr,
+                                  d_Tcol, st);
+    }
+    switch (p->dtype) {
+        case VABFT_F64:
+            return threshold_cols_launch<double>(p, dB, d_eA, d_SA, e_max, c_sigma, d_bcolstat, d_expected_col, d_Tcol,
+                                                 ws, st);
+        case VABFT_F32:
+            return threshold_cols_launch<float>(p, dB, d_eA, d_SA, e_max, c_sigma, d_bcolstat, d_expected_col, d_Tcol,
+                                                ws, st);
+        case VABFT_F16:
+            return threshold_cols_launch<f16_t>(p, dB, d_eA, d_SA, e_max, c_sigma, d_bcolstat, d_expected_col, d_Tcol,
+                                                ws, st);
+        case VABFT_BF16:
+            return threshold_cols_launch<bf16_t>(p, dB, d_eA, d_SA, e_max, c_sigma, d_bcolstat, d_expected_col, d_Tcol,
+                                                 ws, st);
+    }
     return VABFT_EINVAL;
 }
 

@@ -38,6 +38,7 @@ constexpr int LDS_BYTES = 2 * STAGE;  // double buffered: 128 KiB
 // from 4096, the fused A-statistics staging at 40960 and the weighted row sums behind it
 constexpr int SRED_OFFSET = 40960;
 constexpr int RED2_OFFSET = SRED_OFFSET + 2 * 4 * BM * 4;
+constexpr int CRED_OFFSET = RED2_OFFSET + 2 * BM * 4;  // column sums, [2 wm][256 columns]
 
 __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 __device__ __forceinline__ int lds_pos(int row, int chunk) { return row * 128 + ((chunk ^ swz(row)) << 4); }
@@ -155,6 +156,52 @@ __device__ __forceinline__ void gemm16_rowsum2_to_lds(const f32x16_t (&acc)[4][4
     }
 }
 
+// Column sums of the wavefront's accumulator tile (section 2.2 C^{c1'} = c1 C): the four row blocks in
+// registers first (64 values per lane, index v = ni*16 + r), then a reduce-scatter butterfly over the 32
+// lanes that hold the 32 rows of a block: in step s the lanes that differ in bit 4-s exchange the half of
+// their values whose index bit 5-s belongs to the partner and add what they receive, so the number of
+// values per lane halves in every step (62 exchanges instead of 320).  Lane l ends with the complete sums
+// of values 2*(l%32) and 2*(l%32)+1 and stores them to cred[wm][column].
+template <int NV> struct ColReduce {
+    static __device__ __forceinline__ void run(const float (&cur)[NV], int l32, float (&out)[2]) {
+        constexpr int H = NV / 2;
+        // NV = 64, 32, 16, 8, 4 pairs with lane bit 4, 3, 2, 1, 0
+        constexpr int BIT = NV == 64 ? 4 : NV == 32 ? 3 : NV == 16 ? 2 : NV == 8 ? 1 : 0;
+        const bool up = (l32 >> BIT) & 1;
+        float nxt[H];
+#pragma unroll
+        for (int i = 0; i < H; ++i) {
+            const float lo = cur[i], hi = cur[i + H];
+            const float keep = up ? hi : lo, send = up ? lo : hi;
+            nxt[i] = keep + __shfl_xor(send, 1 << BIT, WAVE);
+        }
+        if constexpr (H == 2) {
+            out[0] = nxt[0];
+            out[1] = nxt[1];
+        } else {
+            ColReduce<H>::run(nxt, l32, out);
+        }
+    }
+};
+
+__device__ __forceinline__ void gemm16_colsum_to_lds(const f32x16_t (&acc)[4][4], float* cred, int wm, int wn, int l32,
+                                                     int lh) {
+    using namespace g16;
+    float v[64];
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            v[ni * 16 + r] = (acc[0][ni][r] + acc[1][ni][r]) + (acc[2][ni][r] + acc[3][ni][r]);
+    float out[2];
+    ColReduce<64>::run(v, l32, out);
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int idx = 2 * l32 + e, ni = idx >> 4, r = idx & 15;
+        cred[wm * BN + wn * 128 + ni * 32 + 8 * (r >> 2) + 4 * lh + (r & 3)] = out[e];
+    }
+}
+
 // Quantise and store the wavefront's tile of C.
 template <typename T, bool EDGE>
 __device__ __forceinline__ void gemm16_store_c(const GemmArgs& g, const f32x16_t (&acc)[4][4], unsigned char* smem,
@@ -237,19 +284,24 @@ __device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x16_t (&ac
                                                 int row0, int col0, int bn, int tid, int lane, int wm, int wn,
                                                 int l32, int lh) {
     using namespace g16;
-    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE >= 2;
+    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE == 2 || MODE == 3;
+    constexpr bool CSUM = MODE == 2 || MODE == 4;
     gemm16_inject<INJECT>(g, acc, row0, col0, wm, wn, l32, lh);
     if (VERIFY) {
         float* red = reinterpret_cast<float*>(smem);                       // [2][256]
         float* red2 = reinterpret_cast<float*>(smem + g16::RED2_OFFSET);  // [2][256]
+        float* cred = reinterpret_cast<float*>(smem + g16::CRED_OFFSET);  // [2][256]
         gemm16_rowsum_to_lds(acc, red, wm, wn, l32, lh);
         if (WSUM) gemm16_rowsum2_to_lds(acc, red2, col0, wm, wn, l32, lh);
+        if (CSUM) gemm16_colsum_to_lds(acc, cred, wm, wn, l32, lh);
         __syncthreads();
         const int gi = row0 + tid;
         if (gi < g.M) {
             reinterpret_cast<float*>(g.rowpart)[(int64_t)bn * g.M + gi] = red[tid] + red[BM + tid];
             if (WSUM) reinterpret_cast<float*>(g.rowpart2)[(int64_t)bn * g.M + gi] = red2[tid] + red2[BM + tid];
         }
+        const int gj = col0 + tid;
+        if (CSUM && gj < g.N) reinterpret_cast<float*>(g.colpart)[(int64_t)(row0 / BM) * g.N + gj] = cred[tid] + cred[BN + tid];
     }
     gemm16_store_c<T, EDGE>(g, acc, smem, row0, col0, lane, wm, wn, l32, lh);
 }
@@ -266,6 +318,7 @@ __global__ __launch_bounds__(256) void gemm16_kernel(const GemmArgs g) {
     int bm, bn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
     if (VERIFY && blockIdx.x == 0 && tid == 0) *g.d_nflag = 0;
+    if ((MODE == 2 || MODE == 4) && blockIdx.x == 0 && tid == 0 && g.d_ncolflag) *g.d_ncolflag = 0;
     const int row0 = bm * BM, col0 = bn * BN;
     const uint16_t* __restrict__ A = reinterpret_cast<const uint16_t*>(g.A);
     const uint16_t* __restrict__ B = reinterpret_cast<const uint16_t*>(g.B);
@@ -403,6 +456,7 @@ static int gemm16_edge_launch_tb(const GemmArgs& a, int mode, hipStream_t st) {
     VABFT_G16_CASE(1)
     VABFT_G16_CASE(2)
     VABFT_G16_CASE(3)
+    VABFT_G16_CASE(4)
 #undef VABFT_G16_CASE
     return VABFT_EINVAL;
 }

@@ -20,7 +20,8 @@
 //   * the compare-and-flag step: the last workgroup to finish a tile-row (an arrival ticket per
 //     tile-row) combines that row block's partials in a fixed order, evaluates the threshold
 //     in double precision, and writes rowsum, E, flags; the last row block writes nflag;
-//   * (MODE >= 2) the position-weighted row sums C r2 of section 2.2, through the same partials.
+//   * (MODE 2, 3) the position-weighted row sums C r2 of section 2.2, through the same partials;
+//   * (MODE 2, 4) the column sums c1 C of section 2.2, as per-tile-row partials for a later compare.
 #pragma once
 #include "gemm16.h"
 
@@ -93,7 +94,8 @@ constexpr int LDS_BYTES_FUSED = LDS_BYTES + BE_CACHE_SLOTS * 128 * 4;  // LDS of
 template <typename T, int TRANSB, int MODE, bool FUSED>
 __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     using namespace g16f;
-    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE >= 2;
+    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE == 2 || MODE == 3;
+    constexpr bool CSUM = MODE == 2 || MODE == 4;
     static_assert(!FUSED || VERIFY, "fused statistics belong to the verified kernel");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     lds_u8* const lds = (lds_u8*)smem;
@@ -103,6 +105,7 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     const int l32 = lane & 31, lh = lane >> 5;
     int bm, bn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
+    if (CSUM && blockIdx.x == 0 && tid == 0 && g.d_ncolflag) *g.d_ncolflag = 0;
     const int row0 = bm * BM, col0 = bn * BN;
     const unsigned char* __restrict__ A = reinterpret_cast<const unsigned char*>(g.A);
     const unsigned char* __restrict__ B = reinterpret_cast<const unsigned char*>(g.B);
@@ -369,6 +372,8 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         int* s_last = reinterpret_cast<int*>(smem + 2048);
         gemm16_rowsum_to_lds(acc, red, wm, wn, l32, lh);
         if (WSUM) gemm16_rowsum2_to_lds(acc, red2, col0, wm, wn, l32, lh);
+        float* cred = reinterpret_cast<float*>(smem + CRED_OFFSET);  // [2 wm][256 columns]
+        if (CSUM) gemm16_colsum_to_lds(acc, cred, wm, wn, l32, lh);
         if (FUSED) {
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi) {
@@ -392,6 +397,8 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         float* rowpart2 = reinterpret_cast<float*>(g.rowpart2);
         st_agent(rowpart + (int64_t)bn * g.M + gi, red[tid] + red[BM + tid]);
         if (WSUM) st_agent(rowpart2 + (int64_t)bn * g.M + gi, red2[tid] + red2[BM + tid]);
+        // column-sum partials are compared by a kernel of their own after this one: plain stores
+        if (CSUM) reinterpret_cast<float*>(g.colpart)[(int64_t)bm * g.N + col0 + tid] = cred[tid] + cred[BN + tid];
         if (FUSED) {
             float* ap = apart + (int64_t)bn * 4 * g.M + gi;
             st_agent(ap, sred[0 * BM + tid] + sred[4 * BM + tid]);
@@ -520,6 +527,7 @@ static int gemm16_fast_launch_tb(const GemmArgs& a, int mode, hipStream_t st) {
     VABFT_G16F_CASE(1, 0)
     VABFT_G16F_CASE(2, 0)
     VABFT_G16F_CASE(3, 0)
+    VABFT_G16F_CASE(4, 0)
     VABFT_G16F_CASE(1, 1)
     VABFT_G16F_CASE(2, 1)
 #undef VABFT_G16F_CASE

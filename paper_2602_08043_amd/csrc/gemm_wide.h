@@ -49,7 +49,8 @@ template <typename T> constexpr int lds_bytes() { return loop_bytes<T>() > epi_b
 template <typename T, int TRANSB, int MODE, bool EDGE>
 __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     using namespace gw;
-    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE >= 2;
+    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE == 2 || MODE == 3;
+    constexpr bool CSUM = MODE == 2 || MODE == 4;
     using Cfg = WideCfg<T>;
     using accv_t = typename Cfg::accv_t;
     constexpr int MT = Cfg::MT, KM = Cfg::KM, NR = Cfg::NR, V = Cfg::V;
@@ -62,6 +63,7 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     int bm, bn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
     if (VERIFY && blockIdx.x == 0 && tid == 0) *g.d_nflag = 0;
+    if (CSUM && blockIdx.x == 0 && tid == 0 && g.d_ncolflag) *g.d_ncolflag = 0;
     const int row0 = bm * BM, col0 = bn * BN;
     const T* __restrict__ A = reinterpret_cast<const T*>(g.A);
     const T* __restrict__ B = reinterpret_cast<const T*>(g.B);
@@ -263,6 +265,17 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
         }
     }
 
+    if (CSUM) {
+        // column sums of the accumulator tile (section 2.2 C^{c1'} = c1 C): lane c adds the 64 rows of
+        // column c (consecutive lanes read consecutive LDS words); partial index 2*bm + wm
+        T part[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int r = 0; r < 64; ++r) part[r & 3] += tile[r * PITCH + lane];
+        const int gj = tcol0 + lane;
+        if (gj < g.N)
+            reinterpret_cast<T*>(g.colpart)[(int64_t)(2 * bm + wm) * g.N + gj] = (part[0] + part[1]) + (part[2] + part[3]);
+    }
+
     T* __restrict__ C = reinterpret_cast<T*>(g.C);
     constexpr int CPRW = 64 / V;  // 16-byte chunks per tile row
 #pragma unroll 4
@@ -313,6 +326,8 @@ static int gemmw_launch(const GemmArgs& a, int transB, int mode, bool edge, hipS
     VABFT_GW_CASE(0, 2, true)
     VABFT_GW_CASE(0, 3, false)
     VABFT_GW_CASE(0, 3, true)
+    VABFT_GW_CASE(0, 4, false)
+    VABFT_GW_CASE(0, 4, true)
     VABFT_GW_CASE(1, 0, false)
     VABFT_GW_CASE(1, 0, true)
     VABFT_GW_CASE(1, 1, false)
@@ -321,6 +336,8 @@ static int gemmw_launch(const GemmArgs& a, int transB, int mode, bool edge, hipS
     VABFT_GW_CASE(1, 2, true)
     VABFT_GW_CASE(1, 3, false)
     VABFT_GW_CASE(1, 3, true)
+    VABFT_GW_CASE(1, 4, false)
+    VABFT_GW_CASE(1, 4, true)
 #undef VABFT_GW_CASE
     return VABFT_EINVAL;
 }

@@ -16,6 +16,13 @@ int encode_dispatch(const vabft_problem* p, const void* dB, void* d_Be, void* d_
 int threshold_dispatch(const vabft_problem* p, const void* dA, const void* d_Be, const void* d_Be2, const double* d_S,
                        double e_max, double c_sigma, void* d_astat, void* d_expected, void* d_expected2, void* d_T,
                        hipStream_t st);
+// column checksums (c1 A, per-column thresholds)
+size_t cols_workspace_bytes(const vabft_problem* p);
+int encode_a_dispatch(const vabft_problem* p, const void* dA, void* d_eA, void* d_acolstat, double* d_SA, void* ws,
+                      int32_t* ticket, hipStream_t st);
+int threshold_cols_dispatch(const vabft_problem* p, const void* dB, const void* d_eA, const double* d_SA, double e_max,
+                            double c_sigma, void* d_bcolstat, void* d_expected_col, void* d_Tcol, void* ws,
+                            hipStream_t st);
 int check_offline_dispatch(const vabft_problem* p, const void* dC, const void* d_expected, const void* d_T,
                            void* d_rowsum, void* d_E, int32_t* d_flags, int32_t* d_nflag, hipStream_t st);
 
@@ -62,6 +69,9 @@ struct GemmArgs {
     // position-weighted row sums C r2 (kernel modes 2 and 3)
     void* rowpart2;   // partials, same shape as rowpart
     void* rowsum2;    // [M] acc, output; may be null
+    // column sums c1 C (kernel modes 2 and 4): [tiles_m][N] acc partials (wide kernels: [2 * tiles_m][N])
+    void* colpart;
+    int32_t* d_ncolflag;  // zeroed by the GEMM kernel for the column compare that follows it; may be null
 };
 
 size_t gemm_workspace_bytes(const vabft_problem* p);
@@ -71,15 +81,25 @@ struct FusedArgs {  // non-null d_Be selects the fused A-side path
     double e_max, c_sigma;
     void* d_astat;
 };
-// d_rowsum2 non-null selects the kernels that also form the position-weighted row sums
+// d_rowsum2 non-null selects the kernels that also form the position-weighted row sums; cols non-null those
+// that also form the column sums and compares them
+struct ColArgs {
+    const void* d_expected_col;  // [N] acc
+    const void* d_Tcol;          // [N] acc
+    void* d_colsum;              // [N] acc
+    void* d_Ecol;                // [N] acc
+    int32_t* d_colflags;         // [N]
+    int32_t* d_ncolflag;         // [1]
+};
 int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* dC, void* d_expected, void* d_T,
                   int verify, const FusedArgs* fused, const vabft_inject* inj, void* d_rowsum, void* d_rowsum2,
                   void* d_E, int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
-                  void* ws, hipStream_t st);
+                  void* ws, hipStream_t st, const ColArgs* cols = nullptr);
 void workspace_init_launch(void* ws, size_t bytes, hipStream_t st);
 
 // per-dtype launchers (one translation unit each, to compile in parallel)
-// mode: 0 plain, 1 check, 2 check + injector + weighted row sums, 3 check + weighted row sums.
+// mode: 0 plain, 1 check, 2 check + injector + weighted row sums + column sums, 3 check + weighted row
+// sums, 4 check + column sums.
 // With edge == false the 16-bit kernels do the
 // compare-and-flag step themselves; otherwise the caller launches the finalize kernel.
 int gemm16_launch_bf16_nn(const GemmArgs& a, int mode, bool edge, hipStream_t st);

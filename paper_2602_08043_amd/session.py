@@ -59,6 +59,17 @@ class VerifiedGemm:
         self.loc = torch.empty(M, dtype=torch.int32, device=dev)
         self.delta = torch.empty(M, dtype=acc, device=dev)
         self.ncorrected = torch.zeros(1, dtype=torch.int32, device=dev)
+        # column-checksum buffers
+        self.eA = torch.empty(K, dtype=acc, device=dev)
+        self.acolstat = torch.empty((K, 3), dtype=acc, device=dev)
+        self.SA = torch.empty(3, dtype=torch.float64, device=dev)
+        self.bcolstat = torch.empty((N, 3), dtype=acc, device=dev)
+        self.expected_col = torch.empty(N, dtype=acc, device=dev)
+        self.T_col = torch.empty(N, dtype=acc, device=dev)
+        self.colsum = torch.empty(N, dtype=acc, device=dev)
+        self.E_col = torch.empty(N, dtype=acc, device=dev)
+        self.colflags = torch.empty(N, dtype=torch.int32, device=dev)
+        self.ncolflag = torch.zeros(1, dtype=torch.int32, device=dev)
         self.ws_bytes = vb.vabft_workspace_bytes(self.problem)
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
         vb.vabft_workspace_init(self.ws.data_ptr(), self.ws_bytes, self._stream())
@@ -160,6 +171,35 @@ class VerifiedGemm:
         self.gemm_weighted(A, B, inj)
         self.locate_correct(correct)
 
+    # ---- column checksums --------------------------------------------------------------
+    def encode_a(self, A: torch.Tensor):
+        return vb.vabft_encode_a(self.problem, A.data_ptr(), self.eA.data_ptr(), self.acolstat.data_ptr(),
+                                 self.SA.data_ptr(), self.ws.data_ptr(), self.ws_bytes, self._stream())
+
+    def threshold_cols(self, B: torch.Tensor, e_max=None, c_sigma=2.5):
+        if e_max is None:
+            e_max = vb.vabft_default_emax(self.dtype, self.K, max(self.N, self.M))
+        return vb.vabft_threshold_cols(self.problem, B.data_ptr(), self.eA.data_ptr(), self.SA.data_ptr(), e_max,
+                                       c_sigma, self.bcolstat.data_ptr(), self.expected_col.data_ptr(),
+                                       self.T_col.data_ptr(), self.ws.data_ptr(), self.ws_bytes, self._stream())
+
+    def gemm_rc(self, A: torch.Tensor, B: torch.Tensor, inj: vb.Inject | None = None):
+        return vb.vabft_gemm_verified_rc(self.problem, A.data_ptr(), B.data_ptr(), self.C.data_ptr(),
+                                         self.expected.data_ptr(), self.T.data_ptr(), self.expected_col.data_ptr(),
+                                         self.T_col.data_ptr(), inj, self.rowsum.data_ptr(), self.E.data_ptr(),
+                                         self.flags.data_ptr(), self.nflag.data_ptr(), self.colsum.data_ptr(),
+                                         self.E_col.data_ptr(), self.colflags.data_ptr(), self.ncolflag.data_ptr(),
+                                         self.injlog.data_ptr(), self.ninj.data_ptr(), self.ws.data_ptr(),
+                                         self.ws_bytes, self._stream())
+
+    def run_rc(self, A, B, e_max=None, e_max_col=None, c_sigma=2.5, inj=None):
+        """Row and column check of one GEMM: both encodes, both threshold passes, one GEMM launch."""
+        self.encode(B)
+        self.threshold(A, e_max, c_sigma)
+        self.encode_a(A)
+        self.threshold_cols(B, e_max_col, c_sigma)
+        self.gemm_rc(A, B, inj)
+
     # ---- offline (post-quantisation) check ---------------------------------------------
     def check_offline(self, C: torch.Tensor | None = None):
         """Row sums of a stored product (default: this session's C) against expected / T."""
@@ -194,7 +234,9 @@ class VerifiedGemm:
         torch.cuda.synchronize(self.device)
         out = {k: getattr(self, k).cpu().numpy() for k in
                ("Be", "bstat", "S", "astat", "expected", "T", "rowsum", "E", "flags", "Be2", "expected2", "rowsum2",
-                "loc", "delta")}
+                "loc", "delta", "eA", "acolstat", "SA", "bcolstat", "expected_col", "T_col", "colsum", "E_col",
+                "colflags")}
+        out["ncolflag"] = int(self.ncolflag.item())
         out["ncorrected"] = int(self.ncorrected.item())
         out["nflag"] = int(self.nflag.item())
         out["C"] = to_host(self.C, self.dtype)

@@ -507,3 +507,52 @@ def test_offline_emax_is_twice_the_output_unit_roundoff():
     assert abs(orc.default_emax_offline("f16", 1, 1) - 1e-3) < 0.03 * 1e-3       # "~1e-3 for FP16"
     assert orc.default_emax_offline("f32", 512, 256) == orc.default_emax("f32", 512, 256)
     assert orc.default_emax_offline("f64", 512, 256) == orc.default_emax("f64", 512, 256)
+
+
+# --------------------------------------------------------------------------
+# column checksums (section 2.2)
+# --------------------------------------------------------------------------
+def test_column_check_is_the_row_check_of_the_transposed_product():
+    """C^T = B^T A^T: every column quantity of (A, B) equals the row quantity of (B^T, A^T)."""
+    g = np.random.Generator(np.random.Philox(key=[6, 1]))
+    A = g.standard_normal((37, 23)) + 0.3
+    B = g.standard_normal((23, 51)) * 2 - 0.1
+    col = orc.verify_columns(A.astype(np.float64), B.astype(np.float64), "f64", 0, e_max=1e-15)
+    row = orc.verify(np.ascontiguousarray(B.T), np.ascontiguousarray(A.T), "f64", 0, e_max=1e-15)
+    assert np.allclose(col["eA"], row["Be"], rtol=1e-14)
+    assert np.allclose(col["acolstat"], row["bstat"], rtol=1e-14)
+    assert np.allclose(col["SA"], row["S"], rtol=1e-13)
+    assert np.allclose(col["bcolstat"], row["astat"], rtol=1e-14)
+    assert np.allclose(col["expected_col"], row["expected"], rtol=1e-12, atol=1e-12)
+    assert np.allclose(col["T_col"], row["T"], rtol=1e-12)
+    assert np.allclose(col["colsum"], row["rowsum"], rtol=1e-12, atol=1e-12)
+    assert np.array_equal(col["colflags"], row["flags"])
+
+
+def test_column_checksums_match_brute_force_and_catch_a_planted_error():
+    g = np.random.Generator(np.random.Philox(key=[6, 2]))
+    A = g.integers(-5, 6, size=(6, 4)).astype(np.float64)
+    B = g.integers(-5, 6, size=(4, 7)).astype(np.float64)
+    col = orc.verify_columns(A, B, "f64", 0, e_max=1e-12)
+    eA = [sum(A[m][k] for m in range(6)) for k in range(4)]
+    exp = [sum(eA[k] * B[k][n] for k in range(4)) for n in range(7)]
+    C = [[sum(A[i][k] * B[k][j] for k in range(4)) for j in range(7)] for i in range(6)]
+    cs = [sum(C[i][j] for i in range(6)) for j in range(7)]
+    assert col["eA"].tolist() == eA and col["expected_col"].tolist() == exp and col["colsum"].tolist() == cs
+    assert exp == cs and not col["colflags"].any()                       # c1 (A B) == (c1 A) B exactly
+    assert col["acolstat"][:, 0].tolist() == [max(A[m][k] for m in range(6)) for k in range(4)]
+    assert col["bcolstat"][:, 1].tolist() == [min(B[k][n] for k in range(4)) for n in range(7)]
+    # an error in C[2][5] shows up in column 5 only, with E_col = -delta
+    bad = orc.replay_faults_columns(col["colsum"], [(2, 5, 0, C[2][5], C[2][5] + 9.0)])
+    E = col["expected_col"] - bad
+    assert E.tolist() == [0, 0, 0, 0, 0, -9.0, 0]
+    assert orc.fault_flags(E, col["T_col"]).tolist() == [0, 0, 0, 0, 0, 1, 0]
+
+
+def test_column_threshold_counts_m_terms():
+    """Constant matrices: A = a, B = b.  Every variance vanishes and T_col = e_max * M |b| * K |a|
+    (M terms per checksum entry, K columns of A each with mean a)."""
+    M, K, N, a, b = 12, 5, 9, 0.5, -3.0
+    col = orc.verify_columns(np.full((M, K), a), np.full((K, N), b), "f64", 0, e_max=1e-3)
+    assert np.allclose(col["T_col"], 1e-3 * M * abs(b) * K * abs(a), rtol=1e-14)
+    assert np.allclose(col["expected_col"], M * a * K * b)
