@@ -22,9 +22,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6, "f32": 157.3, "f64": 78.6}  # MI355X dense matrix peaks
+PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6, "f8": 5033.2, "f32": 157.3, "f64": 78.6}  # MI355X dense matrix peaks
 HBM_PEAK_GBPS = 8000.0
-ELEM_BYTES = {"bf16": 2, "f16": 2, "f32": 4, "f64": 8}
+ELEM_BYTES = {"bf16": 2, "f16": 2, "f8": 1, "f32": 4, "f64": 8}
 # HBM-side bytes per launch of the verified GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by the same counters on 1 GiB device copies (profiles/gemm16_fast_bf16_c2_4096_hbm_traffic.md).
 # A counter figure cannot be taken live inside this script; workloads without a profile report null.
@@ -38,6 +38,8 @@ WORKLOAD_TEXT = {
                    "activations N(0,1) with 1% outlier columns x20",
     "c4_f16_8192": "FP16 GEMM M=N=K=8192, A,B ~ U(-1,1), FP32 accumulation",
     "c5_f64_2048": "FP64 GEMM M=N=K=2048, A ~ N(0,1), B ~ N(0,1) truncated 3 sigma",
+    "c6_f8_4096": "FP8 E4M3 GEMM M=N=K=4096, FP32 accumulation, FP16 output, A,B ~ N(0,1), B stored N x K "
+                  "(not one of the five benchmark configurations)",
 }
 
 
@@ -237,7 +239,8 @@ def main():
         t_q = time.time()
         g = torch.Generator(device="cuda")
         g.manual_seed(1234)
-        tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32, "f64": torch.float64}[dt]
+        tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32, "f64": torch.float64,
+               "f8": torch.float8_e4m3fn}[dt]
         fp_rows = fp_trials = 0
         sumT = sumE = 0.0
         worst = 0.0

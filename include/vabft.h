@@ -48,11 +48,16 @@ typedef enum {
     VABFT_EDEVICE = 4       /* the HIP runtime reported an error at launch */
 } vabft_status;
 
-typedef enum { VABFT_F64 = 0, VABFT_F32 = 1, VABFT_F16 = 2, VABFT_BF16 = 3 } vabft_dtype;
+/* VABFT_F8E4M3: A and B are OCP FP8 E4M3 (one byte per element), the accumulator is FP32 and C is
+ * FP16 ("FP8 inputs -> FP32 accumulation -> FP16 output", section 3.6).  The GEMM entry points take
+ * this type only for B stored N x K (transB = 1) and problems made of whole 256 x 256 x 256 tiles with
+ * 16-byte aligned rows (VABFT_EUNSUPPORTED otherwise); encode, threshold and the offline check take any
+ * shape. */
+typedef enum { VABFT_F64 = 0, VABFT_F32 = 1, VABFT_F16 = 2, VABFT_BF16 = 3, VABFT_F8E4M3 = 4 } vabft_dtype;
 
 typedef struct {
     int32_t M, N, K;
-    int32_t dtype;  /* vabft_dtype of A, B and C */
+    int32_t dtype;  /* vabft_dtype of A, B and C (C is FP16 for VABFT_F8E4M3) */
     int32_t transB; /* 0: B is K x N row-major; 1: B is stored N x K row-major */
     int32_t reserved;
     int64_t lda, ldb, ldc; /* leading dimensions in elements */
@@ -99,7 +104,9 @@ int vabft_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream
  * the larger of the paper's GPU law (table "Recommended e_max across platforms":
  * 5.0e-9*sqrt(n)+1.2e-7 for a float accumulator, 1.0e-17*sqrt(n)+2.5e-16 for double) and the
  * law measured on MI355X with this library's kernels by the paper's calibration protocol
- * (3.0e-9*sqrt(n)+3.8e-7, resp. 8.0e-18*sqrt(n)+4.6e-16). */
+ * (3.0e-9*sqrt(n)+3.8e-7, resp. 8.0e-18*sqrt(n)+4.6e-16).  VABFT_F8E4M3: the constant 5.5e-6 measured
+ * the same way (the FP8 matrix instruction accumulates its 64-term dot products with less than FP32
+ * precision). */
 double vabft_default_emax(int32_t dtype, int32_t K, int32_t N);
 
 /* Checksum encode and B-side statistics (section 2.2 Eq. for r1 and the encoded matrix

@@ -66,6 +66,15 @@ def decode(x: np.ndarray, dtype: str) -> np.ndarray:
     if dtype == "f32":
         assert x.dtype == np.float32
         return x.astype(np.float64)
+    if dtype == "f8":
+        # OCP FP8 E4M3: sign, 4 exponent bits (bias 7), 3 mantissa bits; exponent 0 is subnormal
+        # (m / 8 * 2^-6); there are no infinities; S.1111.111 is NaN; the largest finite value is 448
+        assert x.dtype == np.uint8
+        c = x.astype(np.int64)
+        e, m = (c >> 3) & 0xF, c & 7
+        mag = np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * np.exp2(e.astype(np.float64) - 7.0))
+        mag = np.where((e == 15) & (m == 7), np.nan, mag)
+        return np.where(c & 0x80, -mag, mag)
     if dtype == "f64":
         assert x.dtype == np.float64
         return x
@@ -392,6 +401,12 @@ def replay_faults_weighted(rowsum2: np.ndarray, records, row_index=None) -> np.n
 UNIT_ROUNDOFF = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11, "f32": 2.0 ** -24, "f64": 2.0 ** -53}
 
 
+def output_dtype(dtype: str) -> str:
+    """Type of the stored product: FP8 problems write FP16 (section 3.6: FP8 inputs -> FP32
+    accumulation -> FP16 output); every other type writes its own."""
+    return "f16" if dtype == "f8" else dtype
+
+
 def quantize(x: np.ndarray, dtype: str) -> np.ndarray:
     """Round float64 values to the storage type (nearest even) and return them as float64.
     16-bit types are reached through float32, the accumulator the product is held in."""
@@ -423,8 +438,9 @@ def row_sums_offline(C: np.ndarray, dtype: str) -> np.ndarray:
 def default_emax_offline(dtype: str, K: int, N: int) -> float:
     """e_max ~ 2 u_output for a check made after a 16-bit write-back; a full-precision output has
     no extra rounding and keeps the accumulator-level value."""
-    if dtype in ("bf16", "f16"):
-        return 2.0 * UNIT_ROUNDOFF[dtype]
+    out = output_dtype(dtype)
+    if out in ("bf16", "f16"):
+        return 2.0 * UNIT_ROUNDOFF[out]
     return default_emax(dtype, K, N)
 
 

@@ -22,7 +22,8 @@ import torch
 from . import binding as vb
 from .session import VerifiedGemm
 
-_TDT = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32, "f64": torch.float64}
+_TDT = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32, "f64": torch.float64,
+        "f8": torch.float8_e4m3fn}
 
 
 def calibrate_one(dtype: str, M: int, N: int, K: int, transB: int, trials: int, seed: int = 0, dist: str = "abs_n_1_1",

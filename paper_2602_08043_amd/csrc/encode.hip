@@ -35,6 +35,20 @@ template <> struct Unpack<f16_t> {
         return Elem<f16_t>::to_acc(reinterpret_cast<const uint16_t*>(base)[idx]);
     }
 };
+template <> struct Unpack<f8_t> {
+    static __device__ __forceinline__ void run(const raw16& r, float (&v)[16]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[4 * i + 0] = __builtin_amdgcn_cvt_f32_fp8((int)r.w[i], 0);
+            v[4 * i + 1] = __builtin_amdgcn_cvt_f32_fp8((int)r.w[i], 1);
+            v[4 * i + 2] = __builtin_amdgcn_cvt_f32_fp8((int)r.w[i], 2);
+            v[4 * i + 3] = __builtin_amdgcn_cvt_f32_fp8((int)r.w[i], 3);
+        }
+    }
+    static __device__ __forceinline__ float one(const void* base, int64_t idx) {
+        return Elem<f8_t>::to_acc(reinterpret_cast<const uint8_t*>(base)[idx]);
+    }
+};
 template <> struct Unpack<float> {
     static __device__ __forceinline__ void run(const raw16& r, float (&v)[4]) {
 #pragma unroll
@@ -625,6 +639,7 @@ int encode_dispatch(const vabft_problem* p, const void* dB, void* d_Be, void* d_
         case VABFT_F32: VABFT_ENC_CASE(float);
         case VABFT_F16: VABFT_ENC_CASE(f16_t);
         case VABFT_BF16: VABFT_ENC_CASE(bf16_t);
+        case VABFT_F8E4M3: VABFT_ENC_CASE(f8_t);
     }
 #undef VABFT_ENC_CASE
     return VABFT_EINVAL;
@@ -656,6 +671,7 @@ int threshold_dispatch(const vabft_problem* p, const void* dA, const void* d_Be,
         case VABFT_F32: VABFT_THR_CASE(float);
         case VABFT_F16: VABFT_THR_CASE(f16_t);
         case VABFT_BF16: VABFT_THR_CASE(bf16_t);
+        case VABFT_F8E4M3: VABFT_THR_CASE(f8_t);
     }
 #undef VABFT_THR_CASE
     return VABFT_EINVAL;
@@ -679,13 +695,24 @@ __global__ __launch_bounds__(256) void threshold_cols_finish_kernel(const acc_t*
     const int n = blockIdx.x * 256 + threadIdx.x;
     if (n >= N) return;
     acc_t sum = 0, dot = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
-    for (int s = 0; s < nsplit; ++s) {
-        const acc_t* q = part + (int64_t)s * 4 * N;
-        sum += q[n];
-        const acc_t a = q[(int64_t)N + n], b = q[2 * (int64_t)N + n];
-        mx = a > mx ? a : mx;
-        mn = b < mn ? b : mn;
-        dot += q[3 * (int64_t)N + n];
+    for (int s0 = 0; s0 < nsplit; s0 += 8) {
+        // eight slabs' loads in flight at once; folded in slab order
+        acc_t v[8][4];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int sc = s0 + u < nsplit ? s0 + u : nsplit - 1;
+            const acc_t* q = part + (int64_t)sc * 4 * N;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) v[u][c] = q[c * (int64_t)N + n];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (s0 + u < nsplit) {
+                sum += v[u][0];
+                mx = v[u][1] > mx ? v[u][1] : mx;
+                mn = v[u][2] < mn ? v[u][2] : mn;
+                dot += v[u][3];
+            }
     }
     const double mu = (double)sum / (double)K;
     double var = ((double)mx - mu) * (mu - (double)mn);
@@ -771,6 +798,9 @@ int threshold_cols_dispatch(const vabft_problem* p, const void* dB, const void* 
         case VABFT_BF16:
             return threshold_cols_launch<bf16_t>(p, dB, d_eA, d_SA, e_max, c_sigma, d_bcolstat, d_expected_col, d_Tcol,
                                                  ws, st);
+        case VABFT_F8E4M3:
+            return threshold_cols_launch<f8_t>(p, dB, d_eA, d_SA, e_max, c_sigma, d_bcolstat, d_expected_col, d_Tcol,
+                                               ws, st);
     }
     return VABFT_EINVAL;
 }
@@ -791,6 +821,7 @@ int check_offline_dispatch(const vabft_problem* p, const void* dC, const void* d
         case VABFT_F64: VABFT_OFF_CASE(double)
         case VABFT_F32: VABFT_OFF_CASE(float)
         case VABFT_F16: VABFT_OFF_CASE(f16_t)
+        case VABFT_F8E4M3: VABFT_OFF_CASE(f16_t)  // the stored product of an FP8 problem is FP16
         case VABFT_BF16: VABFT_OFF_CASE(bf16_t)
         default: return VABFT_EINVAL;
     }

@@ -91,6 +91,157 @@ constexpr int BE_CACHE_SLOTS = 16;
 constexpr int LDS_BYTES_FUSED = LDS_BYTES + BE_CACHE_SLOTS * 128 * 4;  // LDS offset of the A-statistics staging area in the epilogue
 }  // namespace g16f
 
+// Epilogue shared by the whole-tile kernels (16-bit and FP8 inputs; T is the OUTPUT element type): injector,
+// row sums (and weighted / column sums), publication of the partials, the compare-and-flag step in the last
+// workgroup of the tile-row, and the store of C.  st[mi] = (sum, dot with Be, max, min) of the A rows when FUSED.
+template <typename T, int MODE, bool FUSED>
+__device__ __forceinline__ void gemm16_fast_epilogue(const GemmArgs& g, f32x16_t (&acc)[4][4], float (&st)[4][4],
+                                                     unsigned char* smem, int bm, int bn, int row0, int col0, int tid,
+                                                     int lane, int wm, int wn, int l32, int lh) {
+    using namespace g16f;
+    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE == 2 || MODE == 3;
+    constexpr bool CSUM = MODE == 2 || MODE == 4;
+    gemm16_inject<INJECT>(g, acc, row0, col0, wm, wn, l32, lh);
+    if (VERIFY) {
+        float* red = reinterpret_cast<float*>(smem);                 // [2 wn][256 rows]
+        float* sred = reinterpret_cast<float*>(smem + SRED_OFFSET);  // [2 wn][4][256 rows]
+        float* red2 = reinterpret_cast<float*>(smem + RED2_OFFSET);  // [2 wn][256 rows]
+        int* s_last = reinterpret_cast<int*>(smem + 2048);
+        gemm16_rowsum_to_lds(acc, red, wm, wn, l32, lh);
+        if (WSUM) gemm16_rowsum2_to_lds(acc, red2, col0, wm, wn, l32, lh);
+        float* cred = reinterpret_cast<float*>(smem + CRED_OFFSET);  // [2 wm][256 columns]
+        if (CSUM) gemm16_colsum_to_lds(acc, cred, wm, wn, l32, lh);
+        if (FUSED) {
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) {
+                const float s0 = st[mi][0] + __shfl_xor(st[mi][0], 32, WAVE);
+                const float s1 = st[mi][1] + __shfl_xor(st[mi][1], 32, WAVE);
+                const float s2 = fmaxf(st[mi][2], __shfl_xor(st[mi][2], 32, WAVE));
+                const float s3 = fminf(st[mi][3], __shfl_xor(st[mi][3], 32, WAVE));
+                if (lh == 0) {
+                    const int r = wm * 128 + mi * 32 + l32;
+                    sred[(wn * 4 + 0) * BM + r] = s0;
+                    sred[(wn * 4 + 1) * BM + r] = s1;
+                    sred[(wn * 4 + 2) * BM + r] = s2;
+                    sred[(wn * 4 + 3) * BM + r] = s3;
+                }
+            }
+        }
+        __syncthreads();
+        const int gi = row0 + tid;
+        float* rowpart = reinterpret_cast<float*>(g.rowpart);
+        float* apart = reinterpret_cast<float*>(g.apart);
+        float* rowpart2 = reinterpret_cast<float*>(g.rowpart2);
+        st_agent(rowpart + (int64_t)bn * g.M + gi, red[tid] + red[BM + tid]);
+        if (WSUM) st_agent(rowpart2 + (int64_t)bn * g.M + gi, red2[tid] + red2[BM + tid]);
+        // column-sum partials are compared by a kernel of their own after this one: plain stores
+        if (CSUM) reinterpret_cast<float*>(g.colpart)[(int64_t)bm * g.N + col0 + tid] = cred[tid] + cred[BN + tid];
+        if (FUSED) {
+            float* ap = apart + (int64_t)bn * 4 * g.M + gi;
+            st_agent(ap, sred[0 * BM + tid] + sred[4 * BM + tid]);
+            st_agent(ap + (int64_t)g.M, sred[1 * BM + tid] + sred[5 * BM + tid]);
+            st_agent(ap + 2 * (int64_t)g.M, fmaxf(sred[2 * BM + tid], sred[6 * BM + tid]));
+            st_agent(ap + 3 * (int64_t)g.M, fminf(sred[3 * BM + tid], sred[7 * BM + tid]));
+        }
+        // every thread's partials are performed (vmcnt(0)) before the workgroup takes this
+        // tile-row's arrival ticket.  These round trips are short because no workgroup has issued
+        // its C stores yet (all tiles finish together); behind the store burst they would each
+        // cost several microseconds, which is why the check runs before the store and not in its
+        // shadow.
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (tid == 0) *s_last = (atomicAdd(&g.tickets[bm], 1) == g.tiles_n - 1);
+        __syncthreads();
+        if (*s_last) {
+            // Combine the tile-column partials in tile order.  The device-scope loads are issued
+            // in batches of 16 tile-columns before anything is folded, so their latencies overlap.
+            float rs = 0.f, rs2 = 0.f, sum = 0.f, dot = 0.f, mx = -3.402823466e+38f, mn = 3.402823466e+38f;
+            for (int t0 = 0; t0 < g.tiles_n; t0 += 16) {
+                float v[16][5];
+                float v2[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int t = t0 + j < g.tiles_n ? t0 + j : g.tiles_n - 1;  // clamped duplicates are not folded
+                    v[j][0] = ld_agent(rowpart + (int64_t)t * g.M + gi);
+                    if (WSUM) v2[j] = ld_agent(rowpart2 + (int64_t)t * g.M + gi);
+                    if (FUSED) {
+                        const float* ap = apart + (int64_t)t * 4 * g.M + gi;
+                        v[j][1] = ld_agent(ap);
+                        v[j][2] = ld_agent(ap + (int64_t)g.M);
+                        v[j][3] = ld_agent(ap + 2 * (int64_t)g.M);
+                        v[j][4] = ld_agent(ap + 3 * (int64_t)g.M);
+                    }
+                }
+                // fold four at a time, pairwise inside each group (absent tile-columns count as
+                // the neutral element)
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    if (!(t0 + j < g.tiles_n)) {
+                        v[j][0] = 0.f;
+                        if (WSUM) v2[j] = 0.f;
+                        v[j][1] = 0.f;
+                        v[j][2] = 0.f;
+                        v[j][3] = -3.402823466e+38f;
+                        v[j][4] = 3.402823466e+38f;
+                    }
+#pragma unroll
+                for (int j = 0; j < 16; j += 4) {
+                    rs += (v[j][0] + v[j + 1][0]) + (v[j + 2][0] + v[j + 3][0]);
+                    if (WSUM) rs2 += (v2[j] + v2[j + 1]) + (v2[j + 2] + v2[j + 3]);
+                    if (FUSED) {
+                        sum += (v[j][1] + v[j + 1][1]) + (v[j + 2][1] + v[j + 3][1]);
+                        dot += (v[j][2] + v[j + 1][2]) + (v[j + 2][2] + v[j + 3][2]);
+                        mx = fmaxf(mx, fmaxf(fmaxf(v[j][3], v[j + 1][3]), fmaxf(v[j + 2][3], v[j + 3][3])));
+                        mn = fminf(mn, fminf(fminf(v[j][4], v[j + 1][4]), fminf(v[j + 2][4], v[j + 3][4])));
+                    }
+                }
+            }
+            float expv, thr;
+            if (FUSED) {
+                const double mu = (double)sum / (double)g.K;
+                double var = ((double)mx - mu) * (mu - (double)mn);
+                var = var > 0 ? var : 0;
+                const double S1 = g.S[0], S2 = g.S[1], S3 = g.S[2], dN = (double)g.N;
+                const double t_det = dN * fabs(mu) * S1;
+                const double t_var23 = g.c_sigma * sqrt(dN * mu * mu * S2 + dN * dN * var * S3);
+                const double t_var4 = g.c_sigma * sqrt(dN) * sqrt(var) * sqrt(S2);
+                expv = dot;
+                thr = (float)(g.e_max * (t_det + t_var23 + t_var4));
+                float* astat = reinterpret_cast<float*>(g.astat);
+                astat[3 * (int64_t)gi + 0] = mx;
+                astat[3 * (int64_t)gi + 1] = mn;
+                astat[3 * (int64_t)gi + 2] = (float)mu;
+                reinterpret_cast<float*>(const_cast<void*>(g.expected))[gi] = expv;
+                reinterpret_cast<float*>(const_cast<void*>(g.T))[gi] = thr;
+            } else {
+                expv = reinterpret_cast<const float*>(g.expected)[gi];
+                thr = reinterpret_cast<const float*>(g.T)[gi];
+            }
+            const float e = expv - rs;
+            const int f = !(fabsf(e) <= thr);
+            reinterpret_cast<float*>(g.rowsum)[gi] = rs;
+            if (WSUM && g.rowsum2) reinterpret_cast<float*>(g.rowsum2)[gi] = rs2;
+            reinterpret_cast<float*>(g.E)[gi] = e;
+            g.flags[gi] = f;
+            const int cnt = __syncthreads_count(f);
+            if (tid == 0) {
+                // this tile-row is done: reset its ticket, then one 64-bit atomic both counts the
+                // finished row blocks (high word) and accumulates the flagged rows (low word);
+                // whoever completes the count publishes nflag and leaves the counter zero
+                __hip_atomic_store(&g.tickets[bm], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                unsigned long long* done = reinterpret_cast<unsigned long long*>(g.tickets + ((g.tiles_m + 1) & ~1));
+                const unsigned long long old = atomicAdd(done, (1ull << 32) | (unsigned long long)(unsigned)cnt);
+                if ((int)(old >> 32) == g.tiles_m - 1) {
+                    *g.d_nflag = (int)(unsigned)(old & 0xffffffffull) + cnt;
+                    __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+        __syncthreads();  // the store below reuses the LDS the reductions read
+    }
+    gemm16_store_c<T, false>(g, acc, smem, row0, col0, lane, wm, wn, l32, lh);
+}
+
 template <typename T, int TRANSB, int MODE, bool FUSED>
 __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     using namespace g16f;
@@ -364,145 +515,7 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     }
 
     // ---- epilogue -------------------------------------------------------------------------
-    gemm16_inject<INJECT>(g, acc, row0, col0, wm, wn, l32, lh);
-    if (VERIFY) {
-        float* red = reinterpret_cast<float*>(smem);                 // [2 wn][256 rows]
-        float* sred = reinterpret_cast<float*>(smem + SRED_OFFSET);  // [2 wn][4][256 rows]
-        float* red2 = reinterpret_cast<float*>(smem + RED2_OFFSET);  // [2 wn][256 rows]
-        int* s_last = reinterpret_cast<int*>(smem + 2048);
-        gemm16_rowsum_to_lds(acc, red, wm, wn, l32, lh);
-        if (WSUM) gemm16_rowsum2_to_lds(acc, red2, col0, wm, wn, l32, lh);
-        float* cred = reinterpret_cast<float*>(smem + CRED_OFFSET);  // [2 wm][256 columns]
-        if (CSUM) gemm16_colsum_to_lds(acc, cred, wm, wn, l32, lh);
-        if (FUSED) {
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi) {
-                const float s0 = st[mi][0] + __shfl_xor(st[mi][0], 32, WAVE);
-                const float s1 = st[mi][1] + __shfl_xor(st[mi][1], 32, WAVE);
-                const float s2 = fmaxf(st[mi][2], __shfl_xor(st[mi][2], 32, WAVE));
-                const float s3 = fminf(st[mi][3], __shfl_xor(st[mi][3], 32, WAVE));
-                if (lh == 0) {
-                    const int r = wm * 128 + mi * 32 + l32;
-                    sred[(wn * 4 + 0) * BM + r] = s0;
-                    sred[(wn * 4 + 1) * BM + r] = s1;
-                    sred[(wn * 4 + 2) * BM + r] = s2;
-                    sred[(wn * 4 + 3) * BM + r] = s3;
-                }
-            }
-        }
-        __syncthreads();
-        const int gi = row0 + tid;
-        float* rowpart = reinterpret_cast<float*>(g.rowpart);
-        float* apart = reinterpret_cast<float*>(g.apart);
-        float* rowpart2 = reinterpret_cast<float*>(g.rowpart2);
-        st_agent(rowpart + (int64_t)bn * g.M + gi, red[tid] + red[BM + tid]);
-        if (WSUM) st_agent(rowpart2 + (int64_t)bn * g.M + gi, red2[tid] + red2[BM + tid]);
-        // column-sum partials are compared by a kernel of their own after this one: plain stores
-        if (CSUM) reinterpret_cast<float*>(g.colpart)[(int64_t)bm * g.N + col0 + tid] = cred[tid] + cred[BN + tid];
-        if (FUSED) {
-            float* ap = apart + (int64_t)bn * 4 * g.M + gi;
-            st_agent(ap, sred[0 * BM + tid] + sred[4 * BM + tid]);
-            st_agent(ap + (int64_t)g.M, sred[1 * BM + tid] + sred[5 * BM + tid]);
-            st_agent(ap + 2 * (int64_t)g.M, fmaxf(sred[2 * BM + tid], sred[6 * BM + tid]));
-            st_agent(ap + 3 * (int64_t)g.M, fminf(sred[3 * BM + tid], sred[7 * BM + tid]));
-        }
-        // every thread's partials are performed (vmcnt(0)) before the workgroup takes this
-        // tile-row's arrival ticket.  These round trips are short because no workgroup has issued
-        // its C stores yet (all tiles finish together); behind the store burst they would each
-        // cost several microseconds, which is why the check runs before the store and not in its
-        // shadow.
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        if (tid == 0) *s_last = (atomicAdd(&g.tickets[bm], 1) == g.tiles_n - 1);
-        __syncthreads();
-        if (*s_last) {
-            // Combine the tile-column partials in tile order.  The device-scope loads are issued
-            // in batches of 16 tile-columns before anything is folded, so their latencies overlap.
-            float rs = 0.f, rs2 = 0.f, sum = 0.f, dot = 0.f, mx = -3.402823466e+38f, mn = 3.402823466e+38f;
-            for (int t0 = 0; t0 < g.tiles_n; t0 += 16) {
-                float v[16][5];
-                float v2[16];
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int t = t0 + j < g.tiles_n ? t0 + j : g.tiles_n - 1;  // clamped duplicates are not folded
-                    v[j][0] = ld_agent(rowpart + (int64_t)t * g.M + gi);
-                    if (WSUM) v2[j] = ld_agent(rowpart2 + (int64_t)t * g.M + gi);
-                    if (FUSED) {
-                        const float* ap = apart + (int64_t)t * 4 * g.M + gi;
-                        v[j][1] = ld_agent(ap);
-                        v[j][2] = ld_agent(ap + (int64_t)g.M);
-                        v[j][3] = ld_agent(ap + 2 * (int64_t)g.M);
-                        v[j][4] = ld_agent(ap + 3 * (int64_t)g.M);
-                    }
-                }
-                // fold four at a time, pairwise inside each group (absent tile-columns count as
-                // the neutral element)
-#pragma unroll
-                for (int j = 0; j < 16; ++j)
-                    if (!(t0 + j < g.tiles_n)) {
-                        v[j][0] = 0.f;
-                        if (WSUM) v2[j] = 0.f;
-                        v[j][1] = 0.f;
-                        v[j][2] = 0.f;
-                        v[j][3] = -3.402823466e+38f;
-                        v[j][4] = 3.402823466e+38f;
-                    }
-#pragma unroll
-                for (int j = 0; j < 16; j += 4) {
-                    rs += (v[j][0] + v[j + 1][0]) + (v[j + 2][0] + v[j + 3][0]);
-                    if (WSUM) rs2 += (v2[j] + v2[j + 1]) + (v2[j + 2] + v2[j + 3]);
-                    if (FUSED) {
-                        sum += (v[j][1] + v[j + 1][1]) + (v[j + 2][1] + v[j + 3][1]);
-                        dot += (v[j][2] + v[j + 1][2]) + (v[j + 2][2] + v[j + 3][2]);
-                        mx = fmaxf(mx, fmaxf(fmaxf(v[j][3], v[j + 1][3]), fmaxf(v[j + 2][3], v[j + 3][3])));
-                        mn = fminf(mn, fminf(fminf(v[j][4], v[j + 1][4]), fminf(v[j + 2][4], v[j + 3][4])));
-                    }
-                }
-            }
-            float expv, thr;
-            if (FUSED) {
-                const double mu = (double)sum / (double)g.K;
-                double var = ((double)mx - mu) * (mu - (double)mn);
-                var = var > 0 ? var : 0;
-                const double S1 = g.S[0], S2 = g.S[1], S3 = g.S[2], dN = (double)g.N;
-                const double t_det = dN * fabs(mu) * S1;
-                const double t_var23 = g.c_sigma * sqrt(dN * mu * mu * S2 + dN * dN * var * S3);
-                const double t_var4 = g.c_sigma * sqrt(dN) * sqrt(var) * sqrt(S2);
-                expv = dot;
-                thr = (float)(g.e_max * (t_det + t_var23 + t_var4));
-                float* astat = reinterpret_cast<float*>(g.astat);
-                astat[3 * (int64_t)gi + 0] = mx;
-                astat[3 * (int64_t)gi + 1] = mn;
-                astat[3 * (int64_t)gi + 2] = (float)mu;
-                reinterpret_cast<float*>(const_cast<void*>(g.expected))[gi] = expv;
-                reinterpret_cast<float*>(const_cast<void*>(g.T))[gi] = thr;
-            } else {
-                expv = reinterpret_cast<const float*>(g.expected)[gi];
-                thr = reinterpret_cast<const float*>(g.T)[gi];
-            }
-            const float e = expv - rs;
-            const int f = !(fabsf(e) <= thr);
-            reinterpret_cast<float*>(g.rowsum)[gi] = rs;
-            if (WSUM && g.rowsum2) reinterpret_cast<float*>(g.rowsum2)[gi] = rs2;
-            reinterpret_cast<float*>(g.E)[gi] = e;
-            g.flags[gi] = f;
-            const int cnt = __syncthreads_count(f);
-            if (tid == 0) {
-                // this tile-row is done: reset its ticket, then one 64-bit atomic both counts the
-                // finished row blocks (high word) and accumulates the flagged rows (low word);
-                // whoever completes the count publishes nflag and leaves the counter zero
-                __hip_atomic_store(&g.tickets[bm], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                unsigned long long* done = reinterpret_cast<unsigned long long*>(g.tickets + ((g.tiles_m + 1) & ~1));
-                const unsigned long long old = atomicAdd(done, (1ull << 32) | (unsigned long long)(unsigned)cnt);
-                if ((int)(old >> 32) == g.tiles_m - 1) {
-                    *g.d_nflag = (int)(unsigned)(old & 0xffffffffull) + cnt;
-                    __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            }
-        }
-        __syncthreads();  // the store below reuses the LDS the reductions read
-    }
-    gemm16_store_c<T, false>(g, acc, smem, row0, col0, lane, wm, wn, l32, lh);
+    gemm16_fast_epilogue<T, MODE, FUSED>(g, acc, st, smem, bm, bn, row0, col0, tid, lane, wm, wn, l32, lh);
 }
 
 template <typename T, int TRANSB>

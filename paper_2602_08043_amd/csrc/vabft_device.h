@@ -14,6 +14,7 @@ constexpr int WAVE = 64;
 // ---------------------------------------------------------------------------
 struct bf16_t { uint16_t bits; };
 struct f16_t { _Float16 v; };
+struct f8_t { uint8_t bits; };  // OCP FP8 E4M3
 
 template <typename T> struct Elem;
 
@@ -46,6 +47,13 @@ template <> struct Elem<f16_t> {
         __builtin_memcpy(&r, &h, 2);
         return r;
     }
+};
+
+template <> struct Elem<f8_t> {
+    using acc_t = float;
+    static constexpr int bytes = 1;
+    static constexpr int vec = 16;  // elements per 16-byte chunk
+    static __device__ __forceinline__ float to_acc(uint8_t raw) { return __builtin_amdgcn_cvt_f32_fp8((int)raw, 0); }
 };
 
 template <> struct Elem<float> {

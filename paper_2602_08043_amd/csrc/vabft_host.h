@@ -106,6 +106,7 @@ int gemm16_launch_bf16_nn(const GemmArgs& a, int mode, bool edge, hipStream_t st
 int gemm16_launch_bf16_nt(const GemmArgs& a, int mode, bool edge, hipStream_t st);
 int gemm16_launch_f16_nn(const GemmArgs& a, int mode, bool edge, hipStream_t st);
 int gemm16_launch_f16_nt(const GemmArgs& a, int mode, bool edge, hipStream_t st);
+int gemm8_launch_f8_nt(const GemmArgs& a, int mode, hipStream_t st);  // whole tiles only
 int gemmw_launch_f32(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st);
 int gemmw_launch_f64(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st);
 

@@ -9,7 +9,9 @@ import torch
 
 from . import binding as vb
 
-_TORCH_DTYPE = {"f64": torch.float64, "f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+_TORCH_DTYPE = {"f64": torch.float64, "f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16,
+                "f8": torch.float8_e4m3fn}
+_OUT_DTYPE = {"f8": "f16"}  # FP8 problems store an FP16 product
 _REC_DTYPE = np.dtype([("row", "<i4"), ("col", "<i4"), ("bit", "<i4"), ("pad", "<i4"), ("before", "<f8"),
                        ("after", "<f8")])
 
@@ -18,6 +20,8 @@ def to_device(x: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
     """Storage array (see workloads.py) -> device tensor of the matching torch dtype."""
     if dtype == "bf16":
         return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).to(device).view(torch.bfloat16)
+    if dtype == "f8":
+        return torch.from_numpy(np.ascontiguousarray(x, dtype=np.uint8)).to(device).view(torch.float8_e4m3fn)
     return torch.from_numpy(np.ascontiguousarray(x)).to(device)
 
 
@@ -38,7 +42,8 @@ class VerifiedGemm:
         acc = torch.float64 if dtype == "f64" else torch.float32
         self.acc = acc
         dev = self.device
-        self.C = torch.empty((M, N), dtype=_TORCH_DTYPE[dtype], device=dev)
+        self.out_dtype = _OUT_DTYPE.get(dtype, dtype)
+        self.C = torch.empty((M, N), dtype=_TORCH_DTYPE[self.out_dtype], device=dev)
         self.Be = torch.empty(K, dtype=acc, device=dev)
         self.bstat = torch.empty((K, 3), dtype=acc, device=dev)
         self.S = torch.empty(3, dtype=torch.float64, device=dev)
@@ -239,5 +244,5 @@ class VerifiedGemm:
         out["ncolflag"] = int(self.ncolflag.item())
         out["ncorrected"] = int(self.ncorrected.item())
         out["nflag"] = int(self.nflag.item())
-        out["C"] = to_host(self.C, self.dtype)
+        out["C"] = to_host(self.C, self.out_dtype)
         return out

@@ -1,0 +1,137 @@
+"""FP8 (OCP E4M3) inputs with FP32 accumulation and FP16 output (paper section 3.6: "FP8 inputs -> FP32
+accumulation -> FP16 output"): parity of the whole path with the CPU oracle.  The GEMM takes whole
+256 x 256 x 256 tiles with B stored N x K; the streaming passes take any shape."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import vabft_oracle as orc
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from test_gpu_parity import (OUT_TINY, U_OUT, _dev, _emax, _session, _tol, check_light, check_rows)  # noqa: E402
+from test_gpu_weighted import check_weighted  # noqa: E402
+from test_gpu_columns import check_columns  # noqa: E402
+
+
+def _gen8(M, N, K, transB, seed, dist="n_1e-6_1"):
+    g = wl.rng(seed, 19)
+    A = wl.to_storage(wl.paper_distribution(g, dist, (M, K)), "f8")
+    Bl = wl.paper_distribution(g, dist, (K, N))
+    B = wl.to_storage(np.ascontiguousarray(Bl.T) if transB else Bl, "f8")
+    return A, B
+
+
+def check_C8(r, o, A_st, B_st, transB):
+    C = r["C"].astype(np.float64)                       # FP16 product
+    absprod = np.abs(orc.decode(A_st, "f8")) @ np.abs(orc.logical_B(B_st, "f8", transB))
+    bound = U_OUT["f16"] * np.abs(o["C"]) + _tol("f8") * absprod + OUT_TINY["f16"]
+    assert np.all(np.abs(C - o["C"]) <= bound), "C"
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 256, 256), (512, 768, 512), (256, 512, 1024)])
+def test_fp8_fault_free_parity(M, N, K):
+    for seed, dist in ((1, "n_1e-6_1"), (2, "n_1_1"), (3, "u_-1_1")):
+        A, B = _gen8(M, N, K, 1, seed, dist)
+        print(f"fp8 {M}x{N}x{K} {dist}", flush=True)
+        vg = _session(M, N, K, "f8", 1)
+        dA, dB = _dev(A, "f8"), _dev(B, "f8")
+        o = orc.verify(A, B, "f8", 1, e_max=_emax("f8", K, N))
+        for route in ("run", "run_fused", "run_weighted", "run_rc"):
+            getattr(vg, route)(dA, dB)
+            r = vg.results()
+            check_light(r, o, "f8", M, N, K)
+            check_rows(r, o, "f8")
+            check_C8(r, o, A, B, 1)
+            assert r["nflag"] == 0 and not r["flags"].any() and not o["flags"].any()
+            if route == "run_weighted":
+                check_weighted(r, o, "f8")
+            if route == "run_rc":
+                oc = orc.verify_columns(A, B, "f8", 1, e_max=_emax("f8", K, max(N, M)))
+                check_columns(r, oc, "f8", M, N, K)
+                assert r["ncolflag"] == 0
+        # plain GEMM gives the same C
+        C1 = vg.results()["C"].copy()
+        vg.gemm(dA, dB, 0)
+        assert np.array_equal(vg.results()["C"], C1)
+
+
+def test_fp8_exact_arithmetic_flips_and_localisation():
+    M, N, K = 512, 512, 256
+    g = wl.rng(5, 5)
+    A = wl.to_storage(g.integers(-2, 3, size=(M, K)).astype(np.float64), "f8")
+    B = wl.to_storage(g.integers(-2, 3, size=(N, K)).astype(np.float64), "f8")
+    dA, dB = _dev(A, "f8"), _dev(B, "f8")
+    vg = _session(M, N, K, "f8", 1)
+    vg.run_weighted(dA, dB)
+    r = vg.results()
+    o = orc.verify(A, B, "f8", 1, e_max=_emax("f8", K, N))
+    assert np.array_equal(r["Be"].astype(np.float64), o["Be"])
+    assert np.array_equal(r["expected"].astype(np.float64), o["expected"])
+    assert np.array_equal(r["rowsum"].astype(np.float64), o["rowsum"])
+    assert np.array_equal(r["rowsum2"].astype(np.float64), o["rowsum2"])
+    assert np.array_equal(r["C"].astype(np.float64), o["C"])      # |C| <= 4 * 256: exact in FP16
+    assert not r["E"].any() and r["nflag"] == 0
+    # planted flips of the top mantissa bit: detected, located, corrected exactly
+    cand = [(0, 0), (M - 1, N - 1), (255, 256), (300, 17)]
+    faults = [(i, j, 22) for (i, j) in cand if abs(o["C"][i, j]) >= 1]
+    assert len(faults) >= 2
+    vg.run_weighted(dA, dB, inj=vg.make_inject(mode=1, faults=faults), correct=1)
+    r = vg.results()
+    n, recs = vg.inject_records()
+    assert n == len(faults) and [x[:3] for x in recs] == sorted(faults)
+    for (i, j, b, before, after) in recs:
+        assert before == o["C"][i, j] and after == orc.bitflip(before, b, np.float32)
+        assert r["flags"][i] == 1 and r["loc"][i] == j and r["E"][i] == -(after - before)
+    assert r["nflag"] == len(faults) and r["ncorrected"] == len(faults)
+    assert np.array_equal(r["C"].astype(np.float64), o["C"])
+
+
+@pytest.mark.parametrize("M,N,K,transB", [(300, 200, 77, 1), (100, 130, 50, 0), (64, 48, 16, 1)])
+def test_fp8_streaming_passes_take_any_shape(M, N, K, transB):
+    """encode / threshold / offline check on ragged FP8 problems; the GEMM itself reports 'unsupported'."""
+    from paper_2602_08043_amd import binding as vb
+    A, B = _gen8(M, N, K, transB, 7)
+    vg = _session(M, N, K, "f8", transB)
+    dA, dB = _dev(A, "f8"), _dev(B, "f8")
+    vg.encode(dB)
+    vg.threshold(dA)
+    r = vg.results()
+    o = orc.verify(A, B, "f8", transB, e_max=_emax("f8", K, N))
+    check_light(r, o, "f8", M, N, K)
+    with pytest.raises(vb.VabftError) as ei:
+        vg.gemm(dA, dB, 1)
+    assert ei.value.status == vb.VABFT_EUNSUPPORTED
+    # offline check of an FP16 product computed elsewhere, with e_max = 2 u_FP16
+    e_off = vb.vabft_default_emax_offline("f8", K, N)
+    assert e_off == 2.0 ** -10
+    vg.threshold(dA, e_off)
+    Bl = orc.logical_B(B, "f8", transB)
+    C16 = torch.from_numpy((orc.decode(A, "f8") @ Bl).astype(np.float16)).cuda()
+    vg.check_offline(C16)
+    r = vg.results()
+    assert r["nflag"] == 0
+    rs_off = orc.row_sums_offline(orc.decode(A, "f8") @ Bl, "f16")
+    assert np.all(np.abs(r["rowsum"] - rs_off) <= 4 * U_OUT["f32"] * np.abs(C16.float().cpu().numpy()).sum(axis=1) + 1e-30)
+
+
+def test_fp8_full_size_sampled():
+    cfg = wl.make_config("c6_f8_4096", seed=0)
+    dt, M, N, K, tb = cfg["dtype"], cfg["M"], cfg["N"], cfg["K"], cfg["transB"]
+    dA, dB = _dev(cfg["A"], dt), _dev(cfg["B"], dt)
+    vg = _session(M, N, K, dt, tb)
+    vg.run_fused(dA, dB)
+    r = vg.results()
+    rows = np.unique(np.concatenate([wl.rng(3, 78).choice(M, size=48, replace=False), [0, 255, 256, M - 1]]))
+    o = orc.verify(cfg["A"], cfg["B"], dt, tb, e_max=_emax(dt, K, N), rows=rows)
+    check_light(r, o, dt, M, N, K)
+    check_rows(r, o, dt, rows)
+    C = r["C"].astype(np.float64)[rows]
+    absprod = np.abs(orc.decode(cfg["A"], dt)[rows]) @ np.abs(orc.logical_B(cfg["B"], dt, tb))
+    assert np.all(np.abs(C - o["C"]) <= U_OUT["f16"] * np.abs(o["C"]) + _tol(dt) * absprod + OUT_TINY["f16"])
+    assert r["nflag"] == 0 and np.all(np.abs(r["E"]) <= r["T"])
+    i = int(rows[7])
+    vg.gemm(dA, dB, 1, vg.make_inject(mode=1, faults=[(i, N - 5, 28)]))
+    r2 = vg.results()
+    assert np.nonzero(r2["flags"])[0].tolist() == [i] and r2["nflag"] == 1

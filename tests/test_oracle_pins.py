@@ -556,3 +556,32 @@ def test_column_threshold_counts_m_terms():
     col = orc.verify_columns(np.full((M, K), a), np.full((K, N), b), "f64", 0, e_max=1e-3)
     assert np.allclose(col["T_col"], 1e-3 * M * abs(b) * K * abs(a), rtol=1e-14)
     assert np.allclose(col["expected_col"], M * a * K * b)
+
+
+# --------------------------------------------------------------------------
+# FP8 E4M3 storage (OCP): decode and the input generator's rounding
+# --------------------------------------------------------------------------
+def test_e4m3_decode_known_codes():
+    codes = np.array([0x00, 0x01, 0x07, 0x08, 0x38, 0x3C, 0x40, 0x7E, 0xB8, 0x80, 0xFE], dtype=np.uint8)
+    want = [0.0, 2.0 ** -9, 7 * 2.0 ** -9, 2.0 ** -6, 1.0, 1.5, 2.0, 448.0, -1.0, -0.0, -448.0]
+    assert orc.decode(codes, "f8").tolist() == want
+    assert np.isnan(orc.decode(np.array([0x7F, 0xFF], dtype=np.uint8), "f8")).all()
+    # all 254 finite codes are distinct, symmetric, and increase with the code within a sign
+    allv = orc.decode(np.arange(256, dtype=np.uint8), "f8")
+    pos = allv[:0x7F]
+    assert np.all(np.diff(pos) > 0) and np.array_equal(allv[0x80:0xFF], -pos)
+
+
+def test_e4m3_rounding_of_the_generators():
+    # every representable value survives; midpoints go to the even code; beyond the range saturates
+    codes = np.arange(0x7F, dtype=np.uint8)
+    vals = orc.decode(codes, "f8")
+    assert np.array_equal(wl.to_storage(vals, "f8"), codes)
+    assert np.array_equal(wl.to_storage(-vals[1:], "f8"), codes[1:] | 0x80)
+    mid = (vals[:-1] + vals[1:]) / 2
+    got = wl.to_storage(mid, "f8")
+    assert np.all(got % 2 == 0) and np.all((got == codes[:-1]) | (got == codes[1:]))
+    assert wl.to_storage(np.array([1e6, -1e6, 449.0]), "f8").tolist() == [0x7E, 0xFE, 0x7E]
+    assert orc.output_dtype("f8") == "f16" and orc.output_dtype("bf16") == "bf16"
+    assert orc.default_emax_offline("f8", 64, 64) == 2.0 ** -10   # "FP8 ... e_max ~ 2 u_FP16 ~ 1e-3"
+    assert orc.acc_dtype("f8") == np.float32

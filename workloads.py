@@ -52,7 +52,30 @@ def to_storage(x: np.ndarray, dtype: str) -> np.ndarray:
         return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16)
     if dtype == "bf16":
         return f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+    if dtype == "f8":
+        return f64_to_e4m3_bits(np.asarray(x, dtype=np.float64))
     raise ValueError(f"unknown dtype {dtype!r}")
+
+
+def _e4m3_positive_values() -> np.ndarray:
+    """The 127 finite non-negative values of OCP FP8 E4M3 (1 sign, 4 exponent bits with bias 7, 3
+    mantissa bits, no infinities, code 0x7F is NaN), indexed by code 0x00 .. 0x7E."""
+    codes = np.arange(0x7F)
+    e, m = codes >> 3, codes & 7
+    return np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * 2.0 ** (e.astype(np.float64) - 7))
+
+
+def f64_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """Nearest E4M3 code, ties to the even code, magnitudes beyond 448 saturate to +-448 (uint8)."""
+    vals = _e4m3_positive_values()
+    a = np.minimum(np.abs(x), vals[-1])
+    hi = np.clip(np.searchsorted(vals, a, side="left"), 1, len(vals) - 1)
+    lo = hi - 1
+    dlo, dhi = a - vals[lo], vals[hi] - a
+    pick_hi = (dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0))
+    code = np.where(pick_hi, hi, lo).astype(np.uint8)
+    code = np.where(a == 0, 0, code).astype(np.uint8)
+    return (code | np.where(np.signbit(x), 0x80, 0).astype(np.uint8)).astype(np.uint8)
 
 
 # --------------------------------------------------------------------------
@@ -107,6 +130,8 @@ CONFIGS = {
     "c3_bf16_ffn": dict(dtype="bf16", M=4096, N=11008, K=4096, transB=1),
     "c4_f16_8192": dict(dtype="f16", M=8192, N=8192, K=8192, transB=0),
     "c5_f64_2048": dict(dtype="f64", M=2048, N=2048, K=2048, transB=0),
+    # beyond the five benchmark configurations: FP8 E4M3 inputs, FP32 accumulation, FP16 output
+    "c6_f8_4096": dict(dtype="f8", M=4096, N=4096, K=4096, transB=1),
 }
 
 
@@ -132,6 +157,9 @@ def make_config(name: str, seed: int = 0, variant: int = 0, shape=None):
         cfg["outlier_cols"] = cols
         # weights drawn directly in the (N, K) layout a linear layer stores
         B = truncated_normal(gb, (N, K), 0.0, 0.02, 2.0)
+    elif name == "c6_f8_4096":
+        A = normal(ga, (M, K))
+        B = normal(gb, (N, K))  # weight layout
     elif name == "c4_f16_8192":
         A = uniform(ga, (M, K))
         B = uniform(gb, (K, N))
