@@ -153,6 +153,14 @@ def main():
     ms_locate = timed(lambda: vg.locate_correct(1), args.steps, args.warmup)
     ms_enc_w = timed(lambda: vg.encode_weighted(B), args.steps, args.warmup)
     ms_thr_w = timed(lambda: vg.threshold_weighted(A, e_max), args.steps, args.warmup)
+    # ---- block-wise check (per block of W columns): the GEMM leaves partials, a small kernel compares
+    vg.encode_blocks(B)
+    vg.threshold_blocks(A)
+    ms_gemm_blocks = timed(lambda: vg.gemm_blocks(A, B), args.steps, args.warmup)
+    nblk_timed = int(vg.nblockflag.item())
+    ms_enc_blocks = timed(lambda: vg.encode_blocks(B), args.steps, args.warmup)
+    ms_thr_blocks = timed(lambda: vg.threshold_blocks(A), args.steps, args.warmup)
+
     # ---- row + column check in one launch
     vg.encode(B)
     vg.threshold(A, e_max)
@@ -231,6 +239,10 @@ def main():
                                "ms_threshold_cols_warm": ms_thr_cols,
                                "gemm_overhead_pct_vs_plain": 100.0 * (ms_gemm_rc / ms_plain - 1.0),
                                "column_flags_in_timed_region": ncol_timed}
+    out["block_route"] = {"block_width": vg.W, "ms_gemm_with_block_check": ms_gemm_blocks,
+                          "ms_encode_blocks_warm": ms_enc_blocks, "ms_threshold_blocks_warm": ms_thr_blocks,
+                          "gemm_overhead_pct_vs_plain": 100.0 * (ms_gemm_blocks / ms_plain - 1.0),
+                          "block_flags_in_timed_region": nblk_timed}
     out["flags_in_timed_region"] = nflag_timed
     out["ms"]["step_with_inner_events"] = ms_step_with_events
 

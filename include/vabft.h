@@ -247,6 +247,37 @@ int vabft_gemm_verified_rc(const vabft_problem* p, const void* dA, const void* d
                            int32_t* d_colflags, int32_t* d_ncolflag, vabft_inject_rec* d_injlog,
                            int32_t* d_ninj, void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* ---- Block-wise verification (section 3.7 "Integration with Block-wise ABFT").  The product is checked
+ * in blocks of W = vabft_block_width(dtype) columns (256; 64 for FP32 / FP64): block t holds columns
+ * [tW, min(N, (t+1)W)), nblocks = ceil(N / W).  Per block: row statistics of the block of B, Algorithm 1 with
+ * the block's width in place of N, block checksums compared on their own; a row's aggregate difference is
+ * the sum of its block differences and its flag the OR of its block flags.  K is not split.
+ * All block arrays are [nblocks][len] (block-major), in the accumulator type unless stated. */
+int32_t vabft_block_width(int32_t dtype);
+
+/*   d_Be_blk [nblocks][K] acc   : Be_t[k] = sum of B[k][n] over the block's columns
+ *   d_S_blk  [nblocks][3] double: S1, S2, S3 of Algorithm 1 over the block's columns */
+int vabft_encode_blocks(const vabft_problem* p, const void* dB, void* d_Be_blk, double* d_S_blk,
+                        void* d_workspace, size_t workspace_bytes, void* stream);
+
+/*   d_astat [3M] acc (as vabft_threshold); d_expected_blk [nblocks][M]: sum_k A[m][k] * Be_t[k];
+ *   d_T_blk [nblocks][M]: the block thresholds */
+int vabft_threshold_blocks(const vabft_problem* p, const void* dA, const void* d_Be_blk,
+                           const double* d_S_blk, double e_max, double c_sigma, void* d_astat,
+                           void* d_expected_blk, void* d_T_blk, void* stream);
+
+/* GEMM with the per-block check:
+ *   d_rowsum_blk, d_E_blk [nblocks][M] acc; d_blockflags [nblocks][M] int32; d_nblockflag [1] int32;
+ *   d_E [M] acc: sum over blocks of E_blk (the full-row difference); d_flags [M]: OR of the block flags;
+ *   d_nflag [1]: number of flagged rows. */
+int vabft_gemm_verified_blocks(const vabft_problem* p, const void* dA, const void* dB, void* dC,
+                               const void* d_expected_blk, const void* d_T_blk,
+                               const vabft_inject* inj, void* d_rowsum_blk, void* d_E_blk,
+                               int32_t* d_blockflags, int32_t* d_nblockflag, void* d_E,
+                               int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog,
+                               int32_t* d_ninj, void* d_workspace, size_t workspace_bytes,
+                               void* stream);
+
 /* ---- Offline (post-hoc) verification (section 3.6 "Verification output precision: Offline vs.
  * Online ABFT"): the check is made on a product that already sits in memory in the output type,
  * whoever computed it.  d_expected / d_T come from vabft_threshold, called with an e_max for the

@@ -23,6 +23,8 @@ no blocking, fusion or reordering beyond what the definitions state:
     Online ABFT" and "Practical recommendations".
   * Column checksums c1 = [1 .. 1], A^c = [A; c1 A], C^{c1} = c1 A B, C^{c1'} = c1 C (section 2.2) with the
     threshold of Algorithm 1 applied to C^T = B^T A^T (our reading: the paper gives the row form only).
+  * Block-wise verification (section 3.7 "Integration with Block-wise ABFT"): statistics, threshold and
+    checksums per block of columns, block results aggregated per row.
   * Position-weighted checksum r2, checksum differences D1 / D2, localisation
     j = D2 / D1 - 1 and correction C[i][j] -= D1: section 2.2 "Error
     localization and correction".
@@ -494,4 +496,61 @@ def replay_faults_columns(colsum: np.ndarray, records) -> np.ndarray:
     out = np.array(colsum, dtype=np.float64, copy=True)
     for (_i, j, _bit, before, after) in records:
         out[j] = out[j] + (after - before)
+    return out
+
+
+# --------------------------------------------------------------------------
+# block-wise verification (section 3.7), blocks of W columns
+# --------------------------------------------------------------------------
+def verify_blocks(A_st, B_st, dtype: str, transB: int, W: int, e_max: float, c_sigma: float = C_SIGMA_DEFAULT,
+                  full_gemm: bool = True):
+    """The product is verified block by block: block t holds columns [tW, min(N, (t+1)W)).  For each block the
+    three steps of the section are taken literally: (1) row statistics of the block of B (A's rows are whole:
+    K is not split), (2) Algorithm 1 with those statistics and the block's width in place of N, (3) block
+    checksums Be_t = B_t r1, expected_t = A Be_t, rowsum_t = C_t r1, compared per block; the aggregate of a
+    row is the sum of its block differences (the full-row difference) and its flag the OR of its block flags."""
+    A = decode(A_st, dtype)
+    B = logical_B(B_st, dtype, transB)
+    M, K = A.shape
+    N = B.shape[1]
+    nb = (N + W - 1) // W
+    out = {"W": W, "nblocks": nb}
+    out["Be_blk"] = np.zeros((nb, K))
+    out["S_blk"] = np.zeros((nb, 3))
+    out["expected_blk"] = np.zeros((nb, M))
+    out["T_blk"] = np.zeros((nb, M))
+    out["scale_Be_blk"] = np.zeros((nb, K))
+    out["scale_expected_blk"] = np.zeros((nb, M))
+    out["scale_rowsum_blk"] = np.zeros((nb, M))
+    if full_gemm:
+        C = gemm(A, B)
+        out["C"] = C
+        out["rowsum_blk"] = np.zeros((nb, M))
+    for t in range(nb):
+        Bt = B[:, t * W:min(N, (t + 1) * W)]
+        out["Be_blk"][t] = encode_checksum(Bt)
+        out["S_blk"][t] = b_aggregates(Bt)
+        out["expected_blk"][t] = expected_checksum(A, out["Be_blk"][t])
+        out["T_blk"][t] = threshold(A, Bt, e_max, c_sigma)
+        absBt = np.abs(Bt).sum(axis=1)
+        out["scale_Be_blk"][t] = absBt
+        out["scale_expected_blk"][t] = np.abs(A) @ np.abs(out["Be_blk"][t])
+        out["scale_rowsum_blk"][t] = np.abs(A) @ absBt
+        if full_gemm:
+            out["rowsum_blk"][t] = row_sums(C[:, t * W:min(N, (t + 1) * W)])
+    mxa, mna, mua = row_stats(A)
+    out["astat"] = np.stack([mxa, mna, mua], axis=1)
+    if full_gemm:
+        out["E_blk"] = out["expected_blk"] - out["rowsum_blk"]
+        out["blockflags"] = fault_flags(out["E_blk"], out["T_blk"])
+        out["E"] = out["E_blk"].sum(axis=0)
+        out["flags"] = (out["blockflags"].sum(axis=0) > 0).astype(np.int32)
+    return out
+
+
+def replay_faults_blocks(rowsum_blk: np.ndarray, records, W: int) -> np.ndarray:
+    """Block row sums after the logged faults: rowsum_blk[col // W][row] += (after - before)."""
+    out = np.array(rowsum_blk, dtype=np.float64, copy=True)
+    for (i, j, _bit, before, after) in records:
+        out[j // W, i] = out[j // W, i] + (after - before)
     return out

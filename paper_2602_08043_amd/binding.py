@@ -21,7 +21,8 @@ EXPORTS = ("vabft_status_string", "vabft_workspace_bytes", "vabft_workspace_init
            "vabft_encode", "vabft_threshold", "vabft_gemm_verified", "vabft_gemm_verified_fused",
            "vabft_encode_weighted", "vabft_threshold_weighted", "vabft_gemm_verified_weighted",
            "vabft_locate_correct", "vabft_default_emax_offline", "vabft_check_offline",
-           "vabft_encode_a", "vabft_threshold_cols", "vabft_gemm_verified_rc")
+           "vabft_encode_a", "vabft_threshold_cols", "vabft_gemm_verified_rc",
+           "vabft_block_width", "vabft_encode_blocks", "vabft_threshold_blocks", "vabft_gemm_verified_blocks")
 
 
 class Problem(Structure):
@@ -112,6 +113,17 @@ def load(path: str | None = None):
                                            c_void_p, c_void_p, POINTER(Inject), c_void_p, c_void_p, c_void_p,
                                            c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                            c_void_p, c_size_t, c_void_p]
+    lib.vabft_block_width.restype = c_int32
+    lib.vabft_block_width.argtypes = [c_int32]
+    lib.vabft_encode_blocks.restype = ctypes.c_int
+    lib.vabft_encode_blocks.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.vabft_threshold_blocks.restype = ctypes.c_int
+    lib.vabft_threshold_blocks.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_double, c_double,
+                                           c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.vabft_gemm_verified_blocks.restype = ctypes.c_int
+    lib.vabft_gemm_verified_blocks.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                               POINTER(Inject), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                               c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     if path is None:
         _lib = lib
     return lib
@@ -237,3 +249,31 @@ def vabft_gemm_verified_rc(p: Problem, dA, dB, dC, d_expected, d_T, d_expected_c
                                        d_colsum, d_Ecol, d_colflags, d_ncolflag, d_injlog, d_ninj, d_workspace,
                                        workspace_bytes, stream)
     return _check(rc, "vabft_gemm_verified_rc", check)
+
+
+def vabft_block_width(dtype) -> int:
+    code = DTYPE_CODE[dtype] if isinstance(dtype, str) else int(dtype)
+    return int(load().vabft_block_width(code))
+
+
+def vabft_encode_blocks(p: Problem, dB, d_Be_blk, d_S_blk, d_workspace, workspace_bytes, stream=None,
+                        check=True) -> int:
+    rc = load().vabft_encode_blocks(byref(p), dB, d_Be_blk, d_S_blk, d_workspace, workspace_bytes, stream)
+    return _check(rc, "vabft_encode_blocks", check)
+
+
+def vabft_threshold_blocks(p: Problem, dA, d_Be_blk, d_S_blk, e_max, c_sigma, d_astat, d_expected_blk, d_T_blk,
+                           stream=None, check=True) -> int:
+    rc = load().vabft_threshold_blocks(byref(p), dA, d_Be_blk, d_S_blk, float(e_max), float(c_sigma), d_astat,
+                                       d_expected_blk, d_T_blk, stream)
+    return _check(rc, "vabft_threshold_blocks", check)
+
+
+def vabft_gemm_verified_blocks(p: Problem, dA, dB, dC, d_expected_blk, d_T_blk, inj, d_rowsum_blk, d_E_blk,
+                               d_blockflags, d_nblockflag, d_E, d_flags, d_nflag, d_injlog, d_ninj, d_workspace,
+                               workspace_bytes, stream=None, check=True) -> int:
+    rc = load().vabft_gemm_verified_blocks(byref(p), dA, dB, dC, d_expected_blk, d_T_blk,
+                                           byref(inj) if inj is not None else None, d_rowsum_blk, d_E_blk,
+                                           d_blockflags, d_nblockflag, d_E, d_flags, d_nflag, d_injlog, d_ninj,
+                                           d_workspace, workspace_bytes, stream)
+    return _check(rc, "vabft_gemm_verified_blocks", check)

@@ -223,7 +223,7 @@ void workspace_init_launch(void* ws, size_t bytes, hipStream_t st) {
 int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* dC, void* d_expected, void* d_T,
                   int verify, const FusedArgs* fused, const vabft_inject* inj, void* d_rowsum, void* d_rowsum2,
                   void* d_E, int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
-                  void* ws, hipStream_t st, const ColArgs* cols) {
+                  void* ws, hipStream_t st, const ColArgs* cols, const BlockArgs* blocks) {
     GemmArgs a;
     a.A = dA;
     a.B = dB;
@@ -252,6 +252,7 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     a.rowsum2 = d_rowsum2;
     a.colpart = ws ? wsb + tickets_bytes(p) + (size_t)a.tiles_n * p->M * ab * (is16 ? 6 : 4) : nullptr;
     a.d_ncolflag = cols ? cols->d_ncolflag : nullptr;
+    a.block_mode = blocks ? 1 : 0;
     a.d_nflag = d_nflag;
     a.expected = d_expected;
     a.T = d_T;
@@ -308,8 +309,12 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     }
     int rc;
     // injector runs form every kind of sum; otherwise one extra kind per launch
-    const int mode = !verify ? 0 : (a.inj.mode != 0 ? 2 : (cols ? 4 : (d_rowsum2 ? 3 : 1)));
+    int mode = !verify ? 0 : (a.inj.mode != 0 ? 2 : (cols ? 4 : (d_rowsum2 ? 3 : 1)));
     if (cols && d_rowsum2 && mode != 2) return VABFT_EUNSUPPORTED;
+    if (blocks) {
+        if (cols || d_rowsum2) return VABFT_EUNSUPPORTED;
+        if (mode == 1 && in_kernel_finalize) mode = 5;  // whole-tile kernels: partials only, no in-kernel compare
+    }
     switch (p->dtype) {
         case VABFT_F8E4M3:
             if (edge || !p->transB) return VABFT_EUNSUPPORTED;
@@ -326,6 +331,10 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
         default: return VABFT_EINVAL;
     }
     if (rc != VABFT_OK || !verify) return rc;
+    if (blocks)
+        return finalize_blocks_dispatch(p, a.rowpart, blocks->d_expected_blk, blocks->d_T_blk, blocks->d_rowsum_blk,
+                                        blocks->d_E_blk, blocks->d_blockflags, d_E, d_flags, d_nflag,
+                                        blocks->d_nblockflag, st);
     if (cols) {
         const dim3 cgrid((p->N + 255) / 256), cblock(256);
         const int ncparts = is16 ? a.tiles_m : 2 * a.tiles_m;
@@ -375,8 +384,11 @@ const char* vabft_status_string(int status) {
 
 size_t vabft_workspace_bytes(const vabft_problem* p) {
     if (!problem_ok(p)) return 0;
-    const size_t a = encode_workspace_bytes(p), b = gemm_workspace_bytes(p), c = cols_workspace_bytes(p);
-    const size_t m = a > b ? (a > c ? a : c) : (b > c ? b : c);
+    const size_t a = encode_workspace_bytes(p), b = gemm_workspace_bytes(p), c = cols_workspace_bytes(p),
+                 d = blocks_workspace_bytes(p);
+    size_t m = a > b ? a : b;
+    m = m > c ? m : c;
+    m = m > d ? m : d;
     return tickets_bytes(p) + round_up(m + 256, 256);
 }
 
@@ -592,6 +604,55 @@ int vabft_gemm_verified_rc(const vabft_problem* p, const void* dA, const void* d
     return gemm_dispatch(p, dA, dB, dC, const_cast<void*>(d_expected), const_cast<void*>(d_T), 1, nullptr, inj,
                          d_rowsum, nullptr, d_E, d_flags, d_nflag, d_injlog, d_ninj, d_workspace, (hipStream_t)stream,
                          &c);
+}
+
+int32_t vabft_block_width(int32_t dtype) { return block_width(dtype); }
+
+int vabft_encode_blocks(const vabft_problem* p, const void* dB, void* d_Be_blk, double* d_S_blk, void* d_workspace,
+                        size_t workspace_bytes, void* stream) {
+    if (!problem_ok(p) || !dB || !d_Be_blk || !d_S_blk) return VABFT_EINVAL;
+    if (!aligned_to(dB, elem_bytes(p->dtype)) || !aligned_to(d_Be_blk, acc_bytes(p->dtype)) || !aligned_to(d_S_blk, 8))
+        return VABFT_EINVAL;
+    if (!d_workspace || workspace_bytes < tickets_bytes(p) + blocks_workspace_bytes(p) || !aligned_to(d_workspace, 16))
+        return VABFT_EWORKSPACE;
+    void* scratch = reinterpret_cast<unsigned char*>(d_workspace) + tickets_bytes(p);
+    return encode_blocks_dispatch(p, dB, d_Be_blk, d_S_blk, scratch, (hipStream_t)stream);
+}
+
+int vabft_threshold_blocks(const vabft_problem* p, const void* dA, const void* d_Be_blk, const double* d_S_blk,
+                           double e_max, double c_sigma, void* d_astat, void* d_expected_blk, void* d_T_blk,
+                           void* stream) {
+    if (!problem_ok(p) || !dA || !d_Be_blk || !d_S_blk || !d_astat || !d_expected_blk || !d_T_blk) return VABFT_EINVAL;
+    if (!(e_max > 0.0) || !(c_sigma >= 0.0) || !isfinite(e_max) || !isfinite(c_sigma)) return VABFT_EINVAL;
+    const size_t ab = acc_bytes(p->dtype);
+    if (!aligned_to(dA, elem_bytes(p->dtype)) || !aligned_to(d_Be_blk, ab) || !aligned_to(d_S_blk, 8) ||
+        !aligned_to(d_astat, ab) || !aligned_to(d_expected_blk, ab) || !aligned_to(d_T_blk, ab))
+        return VABFT_EINVAL;
+    return threshold_blocks_dispatch(p, dA, d_Be_blk, d_S_blk, e_max, c_sigma, d_astat, d_expected_blk, d_T_blk,
+                                     (hipStream_t)stream);
+}
+
+int vabft_gemm_verified_blocks(const vabft_problem* p, const void* dA, const void* dB, void* dC,
+                               const void* d_expected_blk, const void* d_T_blk, const vabft_inject* inj,
+                               void* d_rowsum_blk, void* d_E_blk, int32_t* d_blockflags, int32_t* d_nblockflag,
+                               void* d_E, int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog,
+                               int32_t* d_ninj, void* d_workspace, size_t workspace_bytes, void* stream) {
+    // the row-level vectors of the plain check are not inputs here: pass the block vectors through the checker
+    const int rc = check_gemm_args(p, dA, dB, dC, 1, inj, d_expected_blk, d_T_blk, d_rowsum_blk, d_E, d_flags, d_nflag,
+                                   d_injlog, d_ninj, d_workspace, workspace_bytes);
+    if (rc != VABFT_OK) return rc;
+    if (!d_E_blk || !d_blockflags || !d_nblockflag) return VABFT_EINVAL;
+    if (!aligned_to(d_E_blk, acc_bytes(p->dtype)) || !aligned_to(d_blockflags, 4) || !aligned_to(d_nblockflag, 4))
+        return VABFT_EINVAL;
+    BlockArgs b;
+    b.d_expected_blk = d_expected_blk;
+    b.d_T_blk = d_T_blk;
+    b.d_rowsum_blk = d_rowsum_blk;
+    b.d_E_blk = d_E_blk;
+    b.d_blockflags = d_blockflags;
+    b.d_nblockflag = d_nblockflag;
+    return gemm_dispatch(p, dA, dB, dC, nullptr, nullptr, 1, nullptr, inj, nullptr, nullptr, d_E, d_flags, d_nflag,
+                         d_injlog, d_ninj, d_workspace, (hipStream_t)stream, nullptr, &b);
 }
 
 int vabft_locate_correct(const vabft_problem* p, void* dC, const void* d_expected, const void* d_expected2,

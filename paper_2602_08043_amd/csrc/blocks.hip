@@ -1,0 +1,367 @@
+// Block-wise V-ABFT (paper section 3.7 "Integration with Block-wise ABFT"): the product is verified in blocks
+// of W columns -- the width one GEMM workgroup (256; 64 for the FP32 / FP64 kernels) sums before it writes a
+// partial row sum.  The section's three steps, per block t = columns [tW, min(N, (t+1)W)):
+//   1. row statistics of the block of B (the rows of A are whole, K is not split);
+//   2. Algorithm 1 with those statistics and the block's width in place of N;
+//   3. block checksums Be_t = B_t r1, expected_t = A Be_t, rowsum_t = C_t r1, compared per block; a row's
+//      aggregate is the sum of its block differences, its flag the OR of its block flags.
+#include <math.h>
+
+#include "unpack.h"
+#include "vabft_device.h"
+#include "vabft_host.h"
+
+namespace vabft {
+
+// ---------------------------------------------------------------------------
+// step 1 + block checksum of B.  part layout: [nblocks][3][K] (sum, max, min)
+// ---------------------------------------------------------------------------
+
+// B stored K x N: one wavefront per row k walks the blocks of that row
+template <typename T>
+__global__ __launch_bounds__(256) void encode_blocks_rows_kernel(const void* __restrict__ B, int K, int N, int64_t ldb,
+                                                                 int W, typename Elem<T>::acc_t* __restrict__ part) {
+    using acc_t = typename Elem<T>::acc_t;
+    const int lane = threadIdx.x & 63;
+    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (k >= K) return;
+    const int nblocks = (N + W - 1) / W;
+    for (int t = 0; t < nblocks; ++t) {
+        const int n_end = min(N, (t + 1) * W);
+        acc_t sum = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
+        for (int n = t * W + lane; n < n_end; n += 64) {
+            const acc_t x = Unpack<T>::one(B, (int64_t)k * ldb + n);
+            sum += x;
+            mx = x > mx ? x : mx;
+            mn = x < mn ? x : mn;
+        }
+        sum = wave_sum(sum);
+        mx = wave_max(mx);
+        mn = wave_min(mn);
+        if (lane == 0) {
+            acc_t* q = part + (int64_t)t * 3 * K;
+            q[k] = sum;
+            q[(int64_t)K + k] = mx;
+            q[2 * (int64_t)K + k] = mn;
+        }
+    }
+}
+
+// B stored N x K: one thread per (k, block) walks the block's rows n (consecutive threads read consecutive k)
+template <typename T>
+__global__ __launch_bounds__(256) void encode_blocks_cols_kernel(const void* __restrict__ Bt, int K, int N,
+                                                                 int64_t ldb, int W,
+                                                                 typename Elem<T>::acc_t* __restrict__ part) {
+    using acc_t = typename Elem<T>::acc_t;
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    const int t = blockIdx.y;
+    if (k >= K) return;
+    const int n_end = min(N, (t + 1) * W);
+    acc_t s[4] = {0, 0, 0, 0}, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
+    int n = t * W;
+    for (; n + 3 < n_end; n += 4) {
+        acc_t x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x[u] = Unpack<T>::one(Bt, (int64_t)(n + u) * ldb + k);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            s[u] += x[u];
+            mx = x[u] > mx ? x[u] : mx;
+            mn = x[u] < mn ? x[u] : mn;
+        }
+    }
+    for (; n < n_end; ++n) {
+        const acc_t x = Unpack<T>::one(Bt, (int64_t)n * ldb + k);
+        s[0] += x;
+        mx = x > mx ? x : mx;
+        mn = x < mn ? x : mn;
+    }
+    acc_t* q = part + (int64_t)t * 3 * K;
+    q[k] = (s[0] + s[1]) + (s[2] + s[3]);
+    q[(int64_t)K + k] = mx;
+    q[2 * (int64_t)K + k] = mn;
+}
+
+// Be_blk[t][k] and S1, S2, S3 of block t (Algorithm 1, loop over k, with the block's width): one workgroup per block
+template <typename acc_t>
+__global__ __launch_bounds__(256) void blocks_aggregate_kernel(const acc_t* __restrict__ part, int K, int N, int W,
+                                                               acc_t* __restrict__ Be_blk,
+                                                               double* __restrict__ S_blk) {
+    __shared__ double red[3][4];
+    const int t = blockIdx.x, tid = threadIdx.x;
+    const int width = min(N, (t + 1) * W) - t * W;
+    const acc_t* q = part + (int64_t)t * 3 * K;
+    double s1 = 0, s2 = 0, s3 = 0;
+    for (int k = tid; k < K; k += 256) {
+        const acc_t sum = q[k];
+        Be_blk[(int64_t)t * K + k] = sum;
+        const double mu = (double)sum / (double)width;
+        double var = ((double)q[(int64_t)K + k] - mu) * (mu - (double)q[2 * (int64_t)K + k]);
+        var = var > 0 ? var : 0;
+        s1 += fabs(mu);
+        s2 += var;
+        s3 += mu * mu;
+    }
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    s3 = wave_sum(s3);
+    if ((tid & 63) == 0) {
+        red[0][tid >> 6] = s1;
+        red[1][tid >> 6] = s2;
+        red[2][tid >> 6] = s3;
+    }
+    __syncthreads();
+    if (tid < 3) S_blk[3 * t + tid] = (red[tid][0] + red[tid][1]) + (red[tid][2] + red[tid][3]);
+}
+
+// ---------------------------------------------------------------------------
+// steps 2 + 3 on the A side: row statistics of A, expected_t = A Be_t and T_t for every block.
+// A workgroup takes 16 rows (4 per wavefront).  K is walked in chunks of 256; the Be_t slices of a chunk are
+// staged in LDS for up to 16 blocks at a time and every slice read serves the wavefront's 4 rows.
+// ---------------------------------------------------------------------------
+constexpr int TB_ROWS = 16, TB_KC = 256, TB_T = 16;
+
+template <typename T>
+__global__ __launch_bounds__(256) void threshold_blocks_kernel(const void* __restrict__ A, int M, int K, int N, int W,
+                                                               int64_t lda,
+                                                               const typename Elem<T>::acc_t* __restrict__ Be_blk,
+                                                               const double* __restrict__ S_blk, double e_max,
+                                                               double c_sigma,
+                                                               typename Elem<T>::acc_t* __restrict__ astat,
+                                                               typename Elem<T>::acc_t* __restrict__ expected_blk,
+                                                               typename Elem<T>::acc_t* __restrict__ T_blk) {
+    using acc_t = typename Elem<T>::acc_t;
+    __shared__ acc_t be[TB_T][TB_KC];
+    __shared__ acc_t rstat[TB_ROWS][3];  // (sum, max, min) of the rows, from the first pass
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nblocks = (N + W - 1) / W;
+    const int r0 = blockIdx.x * TB_ROWS + wave * 4;  // the wavefront's first row
+    for (int t0 = 0; t0 < nblocks; t0 += TB_T) {
+        const int nt = min(TB_T, nblocks - t0);
+        acc_t dot[4][TB_T];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int t = 0; t < TB_T; ++t) dot[r][t] = 0;
+        acc_t sum[4] = {0, 0, 0, 0}, mx[4], mn[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            mx[r] = -type_max<acc_t>();
+            mn[r] = type_max<acc_t>();
+        }
+        for (int kc = 0; kc < K; kc += TB_KC) {
+            __syncthreads();  // the previous chunk's slices are no longer read
+            for (int idx = tid; idx < TB_T * TB_KC; idx += 256) {
+                const int t = idx / TB_KC, kk = idx % TB_KC;
+                be[t][kk] = (t < nt && kc + kk < K) ? Be_blk[(int64_t)(t0 + t) * K + kc + kk] : (acc_t)0;
+            }
+            __syncthreads();
+            // lane l takes k = kc + l + 64 j, j = 0..3; all 16 loads of the chunk are issued before any is used
+            acc_t a[4][4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int k = kc + lane + 64 * j;
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    a[j][r] = (k < K && r0 + r < M) ? Unpack<T>::one(A, (int64_t)(r0 + r) * lda + k) : (acc_t)0;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int kk = lane + 64 * j, k = kc + kk;
+                if (t0 == 0 && k < K) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        sum[r] += a[j][r];
+                        mx[r] = a[j][r] > mx[r] ? a[j][r] : mx[r];
+                        mn[r] = a[j][r] < mn[r] ? a[j][r] : mn[r];
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < TB_T; ++t) {
+                    const acc_t b = be[t][kk];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) dot[r][t] = fma(a[j][r], b, dot[r][t]);
+                }
+            }
+        }
+        if (t0 == 0) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const acc_t s = wave_sum(sum[r]), hi = wave_max(mx[r]), lo = wave_min(mn[r]);
+                if (lane == 0) {
+                    rstat[wave * 4 + r][0] = s;
+                    rstat[wave * 4 + r][1] = hi;
+                    rstat[wave * 4 + r][2] = lo;
+                    if (r0 + r < M) {
+                        astat[3 * (int64_t)(r0 + r) + 0] = hi;
+                        astat[3 * (int64_t)(r0 + r) + 1] = lo;
+                        astat[3 * (int64_t)(r0 + r) + 2] = (acc_t)((double)s / (double)K);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int t = 0; t < TB_T; ++t) dot[r][t] = wave_sum(dot[r][t]);
+        // lane (r, t) = lane % 4, lane / 4 writes one (row, block) pair
+        {
+            const int r = lane & 3, t = lane >> 2;
+            acc_t d = 0;
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+                for (int tt = 0; tt < TB_T; ++tt)
+                    if (rr == r && tt == t) d = dot[rr][tt];
+            const int row = r0 + r;
+            if (t < nt && row < M) {
+                const int tb = t0 + t;
+                const int width = min(N, (tb + 1) * W) - tb * W;
+                const double mu = (double)rstat[wave * 4 + r][0] / (double)K;
+                double var = ((double)rstat[wave * 4 + r][1] - mu) * (mu - (double)rstat[wave * 4 + r][2]);
+                var = var > 0 ? var : 0;
+                const double S1 = S_blk[3 * tb], S2 = S_blk[3 * tb + 1], S3 = S_blk[3 * tb + 2], dN = (double)width;
+                const double t_det = dN * fabs(mu) * S1;
+                const double t_var23 = c_sigma * sqrt(dN * mu * mu * S2 + dN * dN * var * S3);
+                const double t_var4 = c_sigma * sqrt(dN) * sqrt(var) * sqrt(S2);
+                expected_blk[(int64_t)tb * M + row] = d;
+                T_blk[(int64_t)tb * M + row] = (acc_t)(e_max * (t_det + t_var23 + t_var4));
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// compare per block and aggregate per row.  rowpart holds `sub` partials per block (1 for the 256-wide
+// kernels, whose workgroup sums a whole block; the wide kernels leave the block's value directly too)
+// ---------------------------------------------------------------------------
+template <typename acc_t>
+__global__ __launch_bounds__(256) void finalize_blocks_kernel(const acc_t* __restrict__ rowpart, int nblocks, int M,
+                                                              const acc_t* __restrict__ expected_blk,
+                                                              const acc_t* __restrict__ T_blk,
+                                                              acc_t* __restrict__ rowsum_blk, acc_t* __restrict__ E_blk,
+                                                              int32_t* __restrict__ blockflags,
+                                                              acc_t* __restrict__ E, int32_t* __restrict__ flags,
+                                                              int32_t* __restrict__ nflag,
+                                                              int32_t* __restrict__ nblockflag) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    int any = 0, nb = 0;
+    if (i < M) {
+        acc_t esum = 0;
+        for (int t = 0; t < nblocks; ++t) {
+            const int64_t idx = (int64_t)t * M + i;
+            const acc_t s = rowpart[idx];
+            const acc_t e = expected_blk[idx] - s;
+            const int f = !(fabs(e) <= T_blk[idx]);
+            rowsum_blk[idx] = s;
+            E_blk[idx] = e;
+            blockflags[idx] = f;
+            esum += e;
+            nb += f;
+        }
+        any = nb > 0;
+        E[i] = esum;
+        flags[i] = any;
+    }
+    const int cnt = __syncthreads_count(any);
+    __shared__ int s_nb[4];
+    int w = nb;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) w += __shfl_xor(w, off, WAVE);
+    if ((threadIdx.x & 63) == 0) s_nb[threadIdx.x >> 6] = w;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (cnt) atomicAdd(nflag, cnt);
+        const int tot = s_nb[0] + s_nb[1] + s_nb[2] + s_nb[3];
+        if (tot) atomicAdd(nblockflag, tot);
+    }
+}
+
+__global__ void zero_int2_kernel(int32_t* a, int32_t* b) {
+    *a = 0;
+    *b = 0;
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+int block_width(int dtype) { return (dtype == VABFT_F64 || dtype == VABFT_F32) ? 64 : 256; }
+
+size_t blocks_workspace_bytes(const vabft_problem* p) {
+    const size_t W = block_width(p->dtype);
+    const size_t nblocks = ((size_t)p->N + W - 1) / W;
+    return nblocks * 3 * (size_t)p->K * (p->dtype == VABFT_F64 ? 8 : 4);
+}
+
+template <typename T>
+static int encode_blocks_launch(const vabft_problem* p, const void* dB, void* d_Be_blk, double* d_S_blk, void* ws,
+                                hipStream_t st) {
+    using acc_t = typename Elem<T>::acc_t;
+    const int W = block_width(p->dtype), nblocks = (p->N + W - 1) / W;
+    acc_t* part = reinterpret_cast<acc_t*>(ws);
+    if (!p->transB)
+        encode_blocks_rows_kernel<T><<<dim3((p->K + 3) / 4), dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, W, part);
+    else
+        encode_blocks_cols_kernel<T><<<dim3((p->K + 255) / 256, nblocks), dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, W,
+                                                                                              part);
+    blocks_aggregate_kernel<acc_t><<<dim3(nblocks), dim3(256), 0, st>>>(part, p->K, p->N, W, (acc_t*)d_Be_blk, d_S_blk);
+    return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
+}
+
+int encode_blocks_dispatch(const vabft_problem* p, const void* dB, void* d_Be_blk, double* d_S_blk, void* ws,
+                           hipStream_t st) {
+    switch (p->dtype) {
+        case VABFT_F64: return encode_blocks_launch<double>(p, dB, d_Be_blk, d_S_blk, ws, st);
+        case VABFT_F32: return encode_blocks_launch<float>(p, dB, d_Be_blk, d_S_blk, ws, st);
+        case VABFT_F16: return encode_blocks_launch<f16_t>(p, dB, d_Be_blk, d_S_blk, ws, st);
+        case VABFT_BF16: return encode_blocks_launch<bf16_t>(p, dB, d_Be_blk, d_S_blk, ws, st);
+        case VABFT_F8E4M3: return encode_blocks_launch<f8_t>(p, dB, d_Be_blk, d_S_blk, ws, st);
+    }
+    return VABFT_EINVAL;
+}
+
+template <typename T>
+static int threshold_blocks_launch(const vabft_problem* p, const void* dA, const void* d_Be_blk, const double* d_S_blk,
+                                   double e_max, double c_sigma, void* d_astat, void* d_expected_blk, void* d_T_blk,
+                                   hipStream_t st) {
+    using acc_t = typename Elem<T>::acc_t;
+    threshold_blocks_kernel<T><<<dim3((p->M + TB_ROWS - 1) / TB_ROWS), dim3(256), 0, st>>>(
+        dA, p->M, p->K, p->N, block_width(p->dtype), p->lda, (const acc_t*)d_Be_blk, d_S_blk, e_max, c_sigma,
+        (acc_t*)d_astat, (acc_t*)d_expected_blk, (acc_t*)d_T_blk);
+    return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
+}
+
+int threshold_blocks_dispatch(const vabft_problem* p, const void* dA, const void* d_Be_blk, const double* d_S_blk,
+                              double e_max, double c_sigma, void* d_astat, void* d_expected_blk, void* d_T_blk,
+                              hipStream_t st) {
+#define VABFT_TB_CASE(T) \
+    return threshold_blocks_launch<T>(p, dA, d_Be_blk, d_S_blk, e_max, c_sigma, d_astat, d_expected_blk, d_T_blk, st)
+    switch (p->dtype) {
+        case VABFT_F64: VABFT_TB_CASE(double);
+        case VABFT_F32: VABFT_TB_CASE(float);
+        case VABFT_F16: VABFT_TB_CASE(f16_t);
+        case VABFT_BF16: VABFT_TB_CASE(bf16_t);
+        case VABFT_F8E4M3: VABFT_TB_CASE(f8_t);
+    }
+#undef VABFT_TB_CASE
+    return VABFT_EINVAL;
+}
+
+int finalize_blocks_dispatch(const vabft_problem* p, const void* rowpart, const void* d_expected_blk,
+                             const void* d_T_blk, void* d_rowsum_blk, void* d_E_blk, int32_t* d_blockflags, void* d_E,
+                             int32_t* d_flags, int32_t* d_nflag, int32_t* d_nblockflag, hipStream_t st) {
+    const int W = block_width(p->dtype), nblocks = (p->N + W - 1) / W;
+    zero_int2_kernel<<<1, 1, 0, st>>>(d_nflag, d_nblockflag);
+    const dim3 grid((p->M + 255) / 256), block(256);
+    if (p->dtype == VABFT_F64)
+        finalize_blocks_kernel<double><<<grid, block, 0, st>>>(
+            (const double*)rowpart, nblocks, p->M, (const double*)d_expected_blk, (const double*)d_T_blk,
+            (double*)d_rowsum_blk, (double*)d_E_blk, d_blockflags, (double*)d_E, d_flags, d_nflag, d_nblockflag);
+    else
+        finalize_blocks_kernel<float><<<grid, block, 0, st>>>(
+            (const float*)rowpart, nblocks, p->M, (const float*)d_expected_blk, (const float*)d_T_blk,
+            (float*)d_rowsum_blk, (float*)d_E_blk, d_blockflags, (float*)d_E, d_flags, d_nflag, d_nblockflag);
+    return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
+}
+
+}  // namespace vabft

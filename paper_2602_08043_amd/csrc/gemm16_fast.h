@@ -143,6 +143,13 @@ __device__ __forceinline__ void gemm16_fast_epilogue(const GemmArgs& g, f32x16_t
             st_agent(ap + 2 * (int64_t)g.M, fmaxf(sred[2 * BM + tid], sred[6 * BM + tid]));
             st_agent(ap + 3 * (int64_t)g.M, fminf(sred[3 * BM + tid], sred[7 * BM + tid]));
         }
+        // block-wise check: the partials are all this kernel leaves; a later kernel compares them per block
+        const bool partials_only = MODE == 5 || (MODE == 2 && g.block_mode);
+        if (partials_only) {
+            __syncthreads();  // the store below reuses the LDS the reductions read
+            gemm16_store_c<T, false>(g, acc, smem, row0, col0, lane, wm, wn, l32, lh);
+            return;
+        }
         // every thread's partials are performed (vmcnt(0)) before the workgroup takes this
         // tile-row's arrival ticket.  These round trips are short because no workgroup has issued
         // its C stores yet (all tiles finish together); behind the store burst they would each
@@ -541,6 +548,7 @@ static int gemm16_fast_launch_tb(const GemmArgs& a, int mode, hipStream_t st) {
     VABFT_G16F_CASE(2, 0)
     VABFT_G16F_CASE(3, 0)
     VABFT_G16F_CASE(4, 0)
+    VABFT_G16F_CASE(5, 0)
     VABFT_G16F_CASE(1, 1)
     VABFT_G16F_CASE(2, 1)
 #undef VABFT_G16F_CASE

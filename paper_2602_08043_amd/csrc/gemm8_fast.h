@@ -192,6 +192,7 @@ static int gemm8_fast_launch(const GemmArgs& a, int mode, hipStream_t st) {
     VABFT_G8F_CASE(2)
     VABFT_G8F_CASE(3)
     VABFT_G8F_CASE(4)
+    VABFT_G8F_CASE(5)
 #undef VABFT_G8F_CASE
     return VABFT_EINVAL;
 }

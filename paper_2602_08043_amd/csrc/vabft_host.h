@@ -23,6 +23,17 @@ int encode_a_dispatch(const vabft_problem* p, const void* dA, void* d_eA, void* 
 int threshold_cols_dispatch(const vabft_problem* p, const void* dB, const void* d_eA, const double* d_SA, double e_max,
                             double c_sigma, void* d_bcolstat, void* d_expected_col, void* d_Tcol, void* ws,
                             hipStream_t st);
+// blocks.hip: block-wise verification
+int block_width(int dtype);
+size_t blocks_workspace_bytes(const vabft_problem* p);
+int encode_blocks_dispatch(const vabft_problem* p, const void* dB, void* d_Be_blk, double* d_S_blk, void* ws,
+                           hipStream_t st);
+int threshold_blocks_dispatch(const vabft_problem* p, const void* dA, const void* d_Be_blk, const double* d_S_blk,
+                              double e_max, double c_sigma, void* d_astat, void* d_expected_blk, void* d_T_blk,
+                              hipStream_t st);
+int finalize_blocks_dispatch(const vabft_problem* p, const void* rowpart, const void* d_expected_blk,
+                             const void* d_T_blk, void* d_rowsum_blk, void* d_E_blk, int32_t* d_blockflags, void* d_E,
+                             int32_t* d_flags, int32_t* d_nflag, int32_t* d_nblockflag, hipStream_t st);
 int check_offline_dispatch(const vabft_problem* p, const void* dC, const void* d_expected, const void* d_T,
                            void* d_rowsum, void* d_E, int32_t* d_flags, int32_t* d_nflag, hipStream_t st);
 
@@ -72,6 +83,8 @@ struct GemmArgs {
     // column sums c1 C (kernel modes 2 and 4): [tiles_m][N] acc partials (wide kernels: [2 * tiles_m][N])
     void* colpart;
     int32_t* d_ncolflag;  // zeroed by the GEMM kernel for the column compare that follows it; may be null
+    // block-wise check: the kernels only leave their partial row sums; a kernel of its own compares per block
+    int32_t block_mode;
 };
 
 size_t gemm_workspace_bytes(const vabft_problem* p);
@@ -83,6 +96,14 @@ struct FusedArgs {  // non-null d_Be selects the fused A-side path
 };
 // d_rowsum2 non-null selects the kernels that also form the position-weighted row sums; cols non-null those
 // that also form the column sums and compares them
+struct BlockArgs {
+    const void* d_expected_blk;  // [nblocks][M] acc
+    const void* d_T_blk;         // [nblocks][M] acc
+    void* d_rowsum_blk;          // [nblocks][M] acc
+    void* d_E_blk;               // [nblocks][M] acc
+    int32_t* d_blockflags;       // [nblocks][M]
+    int32_t* d_nblockflag;       // [1]
+};
 struct ColArgs {
     const void* d_expected_col;  // [N] acc
     const void* d_Tcol;          // [N] acc
@@ -94,12 +115,12 @@ struct ColArgs {
 int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* dC, void* d_expected, void* d_T,
                   int verify, const FusedArgs* fused, const vabft_inject* inj, void* d_rowsum, void* d_rowsum2,
                   void* d_E, int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj,
-                  void* ws, hipStream_t st, const ColArgs* cols = nullptr);
+                  void* ws, hipStream_t st, const ColArgs* cols = nullptr, const BlockArgs* blocks = nullptr);
 void workspace_init_launch(void* ws, size_t bytes, hipStream_t st);
 
 // per-dtype launchers (one translation unit each, to compile in parallel)
 // mode: 0 plain, 1 check, 2 check + injector + weighted row sums + column sums, 3 check + weighted row
-// sums, 4 check + column sums.
+// sums, 4 check + column sums, 5 row-sum partials only (block-wise check, whole-tile kernels).
 // With edge == false the 16-bit kernels do the
 // compare-and-flag step themselves; otherwise the caller launches the finalize kernel.
 int gemm16_launch_bf16_nn(const GemmArgs& a, int mode, bool edge, hipStream_t st);

@@ -75,6 +75,18 @@ class VerifiedGemm:
         self.E_col = torch.empty(N, dtype=acc, device=dev)
         self.colflags = torch.empty(N, dtype=torch.int32, device=dev)
         self.ncolflag = torch.zeros(1, dtype=torch.int32, device=dev)
+        # block-wise verification buffers
+        self.W = vb.vabft_block_width(dtype)
+        self.nblocks = (N + self.W - 1) // self.W
+        nb = self.nblocks
+        self.Be_blk = torch.empty((nb, K), dtype=acc, device=dev)
+        self.S_blk = torch.empty((nb, 3), dtype=torch.float64, device=dev)
+        self.expected_blk = torch.empty((nb, M), dtype=acc, device=dev)
+        self.T_blk = torch.empty((nb, M), dtype=acc, device=dev)
+        self.rowsum_blk = torch.empty((nb, M), dtype=acc, device=dev)
+        self.E_blk = torch.empty((nb, M), dtype=acc, device=dev)
+        self.blockflags = torch.empty((nb, M), dtype=torch.int32, device=dev)
+        self.nblockflag = torch.zeros(1, dtype=torch.int32, device=dev)
         self.ws_bytes = vb.vabft_workspace_bytes(self.problem)
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
         vb.vabft_workspace_init(self.ws.data_ptr(), self.ws_bytes, self._stream())
@@ -205,6 +217,32 @@ class VerifiedGemm:
         self.threshold_cols(B, e_max_col, c_sigma)
         self.gemm_rc(A, B, inj)
 
+    # ---- block-wise verification --------------------------------------------------------
+    def encode_blocks(self, B: torch.Tensor):
+        return vb.vabft_encode_blocks(self.problem, B.data_ptr(), self.Be_blk.data_ptr(), self.S_blk.data_ptr(),
+                                      self.ws.data_ptr(), self.ws_bytes, self._stream())
+
+    def threshold_blocks(self, A: torch.Tensor, e_max=None, c_sigma=2.5):
+        if e_max is None:
+            e_max = vb.vabft_default_emax(self.dtype, self.K, min(self.N, self.W))
+        return vb.vabft_threshold_blocks(self.problem, A.data_ptr(), self.Be_blk.data_ptr(), self.S_blk.data_ptr(),
+                                         e_max, c_sigma, self.astat.data_ptr(), self.expected_blk.data_ptr(),
+                                         self.T_blk.data_ptr(), self._stream())
+
+    def gemm_blocks(self, A: torch.Tensor, B: torch.Tensor, inj: vb.Inject | None = None):
+        return vb.vabft_gemm_verified_blocks(self.problem, A.data_ptr(), B.data_ptr(), self.C.data_ptr(),
+                                             self.expected_blk.data_ptr(), self.T_blk.data_ptr(), inj,
+                                             self.rowsum_blk.data_ptr(), self.E_blk.data_ptr(),
+                                             self.blockflags.data_ptr(), self.nblockflag.data_ptr(),
+                                             self.E.data_ptr(), self.flags.data_ptr(), self.nflag.data_ptr(),
+                                             self.injlog.data_ptr(), self.ninj.data_ptr(), self.ws.data_ptr(),
+                                             self.ws_bytes, self._stream())
+
+    def run_blocks(self, A, B, e_max=None, c_sigma=2.5, inj=None):
+        self.encode_blocks(B)
+        self.threshold_blocks(A, e_max, c_sigma)
+        self.gemm_blocks(A, B, inj)
+
     # ---- offline (post-quantisation) check ---------------------------------------------
     def check_offline(self, C: torch.Tensor | None = None):
         """Row sums of a stored product (default: this session's C) against expected / T."""
@@ -240,7 +278,8 @@ class VerifiedGemm:
         out = {k: getattr(self, k).cpu().numpy() for k in
                ("Be", "bstat", "S", "astat", "expected", "T", "rowsum", "E", "flags", "Be2", "expected2", "rowsum2",
                 "loc", "delta", "eA", "acolstat", "SA", "bcolstat", "expected_col", "T_col", "colsum", "E_col",
-                "colflags")}
+                "colflags", "Be_blk", "S_blk", "expected_blk", "T_blk", "rowsum_blk", "E_blk", "blockflags")}
+        out["nblockflag"] = int(self.nblockflag.item())
         out["ncolflag"] = int(self.ncolflag.item())
         out["ncorrected"] = int(self.ncorrected.item())
         out["nflag"] = int(self.nflag.item())

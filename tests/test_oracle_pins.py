@@ -585,3 +585,43 @@ def test_e4m3_rounding_of_the_generators():
     assert orc.output_dtype("f8") == "f16" and orc.output_dtype("bf16") == "bf16"
     assert orc.default_emax_offline("f8", 64, 64) == 2.0 ** -10   # "FP8 ... e_max ~ 2 u_FP16 ~ 1e-3"
     assert orc.acc_dtype("f8") == np.float32
+
+
+# --------------------------------------------------------------------------
+# block-wise verification (section 3.7)
+# --------------------------------------------------------------------------
+def test_blockwise_reduces_to_the_plain_check_and_adds_up():
+    g = np.random.Generator(np.random.Philox(key=[7, 1]))
+    A = g.standard_normal((9, 14)) + 0.2
+    B = g.standard_normal((14, 23)) - 0.1
+    full = orc.verify(A, B, "f64", 0, e_max=1e-15)
+    # one block as wide as the matrix is Algorithm 1 itself
+    one = orc.verify_blocks(A, B, "f64", 0, 64, 1e-15)
+    assert one["nblocks"] == 1
+    assert np.allclose(one["T_blk"][0], full["T"], rtol=1e-14) and np.allclose(one["Be_blk"][0], full["Be"])
+    assert np.allclose(one["S_blk"][0], full["S"])
+    # blocks of 8 columns (the last one ragged: 23 = 8 + 8 + 7)
+    blk = orc.verify_blocks(A, B, "f64", 0, 8, 1e-15)
+    assert blk["nblocks"] == 3
+    assert np.allclose(blk["Be_blk"].sum(axis=0), full["Be"], rtol=1e-13)
+    assert np.allclose(blk["expected_blk"].sum(axis=0), full["expected"], rtol=1e-12, atol=1e-12)
+    assert np.allclose(blk["rowsum_blk"].sum(axis=0), full["rowsum"], rtol=1e-12, atol=1e-12)
+    assert np.allclose(blk["E"], full["E"], rtol=0, atol=1e-12)
+    # each block's threshold is Algorithm 1 on the block alone (brute force on the last, ragged block)
+    Bt = B[:, 16:23]
+    assert np.allclose(blk["T_blk"][2], orc.threshold(A, Bt, 1e-15), rtol=1e-14)
+    assert np.allclose(blk["S_blk"][2], orc.b_aggregates(Bt))
+
+
+def test_blockwise_localises_a_planted_error_to_its_block():
+    g = np.random.Generator(np.random.Philox(key=[7, 2]))
+    A = g.integers(-3, 4, size=(6, 10)).astype(np.float64)
+    B = g.integers(-3, 4, size=(10, 20)).astype(np.float64)
+    blk = orc.verify_blocks(A, B, "f64", 0, 8, 1e-12)
+    assert not blk["E_blk"].any() and not blk["blockflags"].any()     # exact arithmetic
+    rs = orc.replay_faults_blocks(blk["rowsum_blk"], [(4, 17, 0, blk["C"][4, 17], blk["C"][4, 17] + 5.0)], 8)
+    E = blk["expected_blk"] - rs
+    want = np.zeros((3, 6))
+    want[2, 4] = -5.0                                                   # column 17 lies in block 2
+    assert np.array_equal(E, want)
+    assert orc.fault_flags(E, blk["T_blk"]).sum() == 1 and orc.fault_flags(E, blk["T_blk"])[2, 4] == 1
