@@ -253,6 +253,7 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     a.colpart = ws ? wsb + tickets_bytes(p) + (size_t)a.tiles_n * p->M * ab * (is16 ? 6 : 4) : nullptr;
     a.d_ncolflag = cols ? cols->d_ncolflag : nullptr;
     a.block_mode = blocks ? 1 : 0;
+    a.d_nblockflag = blocks ? blocks->d_nblockflag : nullptr;
     a.d_nflag = d_nflag;
     a.expected = d_expected;
     a.T = d_T;

@@ -119,7 +119,8 @@ __global__ __launch_bounds__(256) void blocks_aggregate_kernel(const acc_t* __re
 // A workgroup takes 16 rows (4 per wavefront).  K is walked in chunks of 256; the Be_t slices of a chunk are
 // staged in LDS for up to 16 blocks at a time and every slice read serves the wavefront's 4 rows.
 // ---------------------------------------------------------------------------
-constexpr int TB_ROWS = 16, TB_KC = 256, TB_T = 16;
+constexpr int TB_RW = 1;  // rows per wavefront: small, so that many workgroups share a compute unit and hide latency
+constexpr int TB_ROWS = 4 * TB_RW, TB_KC = 256, TB_T = 16;
 
 template <typename T>
 __global__ __launch_bounds__(256) void threshold_blocks_kernel(const void* __restrict__ A, int M, int K, int N, int W,
@@ -135,34 +136,42 @@ __global__ __launch_bounds__(256) void threshold_blocks_kernel(const void* __res
     __shared__ acc_t rstat[TB_ROWS][3];  // (sum, max, min) of the rows, from the first pass
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nblocks = (N + W - 1) / W;
-    const int r0 = blockIdx.x * TB_ROWS + wave * 4;  // the wavefront's first row
+    const int r0 = blockIdx.x * TB_ROWS + wave * TB_RW;  // the wavefront's first row
     for (int t0 = 0; t0 < nblocks; t0 += TB_T) {
         const int nt = min(TB_T, nblocks - t0);
-        acc_t dot[4][TB_T];
+        acc_t dot[TB_RW][TB_T];
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < TB_RW; ++r)
 #pragma unroll
             for (int t = 0; t < TB_T; ++t) dot[r][t] = 0;
-        acc_t sum[4] = {0, 0, 0, 0}, mx[4], mn[4];
+        acc_t sum[TB_RW] = {}, mx[TB_RW], mn[TB_RW];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < TB_RW; ++r) {
             mx[r] = -type_max<acc_t>();
             mn[r] = type_max<acc_t>();
         }
         for (int kc = 0; kc < K; kc += TB_KC) {
             __syncthreads();  // the previous chunk's slices are no longer read
-            for (int idx = tid; idx < TB_T * TB_KC; idx += 256) {
-                const int t = idx / TB_KC, kk = idx % TB_KC;
-                be[t][kk] = (t < nt && kc + kk < K) ? Be_blk[(int64_t)(t0 + t) * K + kc + kk] : (acc_t)0;
+            {
+                // thread tid stages element kk = tid of every block's slice: all loads first, then all stores
+                static_assert(TB_KC == 256, "one element per thread and block");
+                acc_t stage[TB_T];
+#pragma unroll
+                for (int t = 0; t < TB_T; ++t) {
+                    const int tc = t < nt ? t : nt - 1, kq = kc + tid < K ? kc + tid : K - 1;  // clamped, masked below
+                    stage[t] = Be_blk[(int64_t)(t0 + tc) * K + kq];
+                }
+#pragma unroll
+                for (int t = 0; t < TB_T; ++t) be[t][tid] = (t < nt && kc + tid < K) ? stage[t] : (acc_t)0;
             }
             __syncthreads();
             // lane l takes k = kc + l + 64 j, j = 0..3; all 16 loads of the chunk are issued before any is used
-            acc_t a[4][4];
+            acc_t a[4][TB_RW];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int k = kc + lane + 64 * j;
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
+                for (int r = 0; r < TB_RW; ++r)
                     a[j][r] = (k < K && r0 + r < M) ? Unpack<T>::one(A, (int64_t)(r0 + r) * lda + k) : (acc_t)0;
             }
 #pragma unroll
@@ -170,7 +179,7 @@ __global__ __launch_bounds__(256) void threshold_blocks_kernel(const void* __res
                 const int kk = lane + 64 * j, k = kc + kk;
                 if (t0 == 0 && k < K) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
+                    for (int r = 0; r < TB_RW; ++r) {
                         sum[r] += a[j][r];
                         mx[r] = a[j][r] > mx[r] ? a[j][r] : mx[r];
                         mn[r] = a[j][r] < mn[r] ? a[j][r] : mn[r];
@@ -180,18 +189,18 @@ __global__ __launch_bounds__(256) void threshold_blocks_kernel(const void* __res
                 for (int t = 0; t < TB_T; ++t) {
                     const acc_t b = be[t][kk];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) dot[r][t] = fma(a[j][r], b, dot[r][t]);
+                    for (int r = 0; r < TB_RW; ++r) dot[r][t] = fma(a[j][r], b, dot[r][t]);
                 }
             }
         }
         if (t0 == 0) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
+            for (int r = 0; r < TB_RW; ++r) {
                 const acc_t s = wave_sum(sum[r]), hi = wave_max(mx[r]), lo = wave_min(mn[r]);
                 if (lane == 0) {
-                    rstat[wave * 4 + r][0] = s;
-                    rstat[wave * 4 + r][1] = hi;
-                    rstat[wave * 4 + r][2] = lo;
+                    rstat[wave * TB_RW + r][0] = s;
+                    rstat[wave * TB_RW + r][1] = hi;
+                    rstat[wave * TB_RW + r][2] = lo;
                     if (r0 + r < M) {
                         astat[3 * (int64_t)(r0 + r) + 0] = hi;
                         astat[3 * (int64_t)(r0 + r) + 1] = lo;
@@ -201,15 +210,15 @@ __global__ __launch_bounds__(256) void threshold_blocks_kernel(const void* __res
             }
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < TB_RW; ++r)
 #pragma unroll
             for (int t = 0; t < TB_T; ++t) dot[r][t] = wave_sum(dot[r][t]);
-        // lane (r, t) = lane % 4, lane / 4 writes one (row, block) pair
+        // lane (r, t) = (lane % TB_RW, lane / TB_RW) writes one (row, block) pair
         {
-            const int r = lane & 3, t = lane >> 2;
+            const int r = lane % TB_RW, t = lane / TB_RW;  // t >= TB_T for the upper lanes when TB_RW < 4
             acc_t d = 0;
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr)
+            for (int rr = 0; rr < TB_RW; ++rr)
 #pragma unroll
                 for (int tt = 0; tt < TB_T; ++tt)
                     if (rr == r && tt == t) d = dot[rr][tt];
@@ -217,8 +226,8 @@ __global__ __launch_bounds__(256) void threshold_blocks_kernel(const void* __res
             if (t < nt && row < M) {
                 const int tb = t0 + t;
                 const int width = min(N, (tb + 1) * W) - tb * W;
-                const double mu = (double)rstat[wave * 4 + r][0] / (double)K;
-                double var = ((double)rstat[wave * 4 + r][1] - mu) * (mu - (double)rstat[wave * 4 + r][2]);
+                const double mu = (double)rstat[wave * TB_RW + r][0] / (double)K;
+                double var = ((double)rstat[wave * TB_RW + r][1] - mu) * (mu - (double)rstat[wave * TB_RW + r][2]);
                 var = var > 0 ? var : 0;
                 const double S1 = S_blk[3 * tb], S2 = S_blk[3 * tb + 1], S3 = S_blk[3 * tb + 2], dN = (double)width;
                 const double t_det = dN * fabs(mu) * S1;
@@ -275,11 +284,6 @@ __global__ __launch_bounds__(256) void finalize_blocks_kernel(const acc_t* __res
         const int tot = s_nb[0] + s_nb[1] + s_nb[2] + s_nb[3];
         if (tot) atomicAdd(nblockflag, tot);
     }
-}
-
-__global__ void zero_int2_kernel(int32_t* a, int32_t* b) {
-    *a = 0;
-    *b = 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -351,7 +355,7 @@ int finalize_blocks_dispatch(const vabft_problem* p, const void* rowpart, const 
                              const void* d_T_blk, void* d_rowsum_blk, void* d_E_blk, int32_t* d_blockflags, void* d_E,
                              int32_t* d_flags, int32_t* d_nflag, int32_t* d_nblockflag, hipStream_t st) {
     const int W = block_width(p->dtype), nblocks = (p->N + W - 1) / W;
-    zero_int2_kernel<<<1, 1, 0, st>>>(d_nflag, d_nblockflag);
+    // d_nflag and d_nblockflag were zeroed by the GEMM kernel that produced the partials
     const dim3 grid((p->M + 255) / 256), block(256);
     if (p->dtype == VABFT_F64)
         finalize_blocks_kernel<double><<<grid, block, 0, st>>>(

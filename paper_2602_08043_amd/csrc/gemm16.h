@@ -318,6 +318,7 @@ __global__ __launch_bounds__(256) void gemm16_kernel(const GemmArgs g) {
     int bm, bn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
     if (VERIFY && blockIdx.x == 0 && tid == 0) *g.d_nflag = 0;
+    if (VERIFY && blockIdx.x == 0 && tid == 0 && g.block_mode) *g.d_nblockflag = 0;
     if ((MODE == 2 || MODE == 4) && blockIdx.x == 0 && tid == 0 && g.d_ncolflag) *g.d_ncolflag = 0;
     const int row0 = bm * BM, col0 = bn * BN;
     const uint16_t* __restrict__ A = reinterpret_cast<const uint16_t*>(g.A);

@@ -264,6 +264,10 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     int bm, bn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
     if (CSUM && blockIdx.x == 0 && tid == 0 && g.d_ncolflag) *g.d_ncolflag = 0;
+    if ((MODE == 5 || MODE == 2) && blockIdx.x == 0 && tid == 0 && g.block_mode) {
+        *g.d_nflag = 0;
+        *g.d_nblockflag = 0;
+    }
     const int row0 = bm * BM, col0 = bn * BN;
     const unsigned char* __restrict__ A = reinterpret_cast<const unsigned char*>(g.A);
     const unsigned char* __restrict__ B = reinterpret_cast<const unsigned char*>(g.B);

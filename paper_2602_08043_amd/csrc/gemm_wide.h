@@ -63,6 +63,7 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     int bm, bn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
     if (VERIFY && blockIdx.x == 0 && tid == 0) *g.d_nflag = 0;
+    if (VERIFY && blockIdx.x == 0 && tid == 0 && g.block_mode) *g.d_nblockflag = 0;
     if (CSUM && blockIdx.x == 0 && tid == 0 && g.d_ncolflag) *g.d_ncolflag = 0;
     const int row0 = bm * BM, col0 = bn * BN;
     const T* __restrict__ A = reinterpret_cast<const T*>(g.A);

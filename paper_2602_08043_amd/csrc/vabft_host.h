@@ -85,6 +85,7 @@ struct GemmArgs {
     int32_t* d_ncolflag;  // zeroed by the GEMM kernel for the column compare that follows it; may be null
     // block-wise check: the kernels only leave their partial row sums; a kernel of its own compares per block
     int32_t block_mode;
+    int32_t* d_nblockflag;  // block mode: zeroed (with d_nflag) by the GEMM kernel for the compare that follows
 };
 
 size_t gemm_workspace_bytes(const vabft_problem* p);
