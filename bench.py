@@ -59,7 +59,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path is built and measured on ONE GPU; run with --gpus 1 "
-              "(sharding is described in DESIGN.md, no multi-GPU figure exists)", file=sys.stderr)
+              "(the path shards without an exchange step -- by rows, by column blocks or by K -- but no multi-GPU figure exists)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

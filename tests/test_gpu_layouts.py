@@ -1,5 +1,5 @@
 """Leading dimensions larger than the row length, and the largest benchmark workload under the
-Bernoulli injector (BASELINE configuration 4: FP16 8192^3, rate 1e-6 per element)."""
+Bernoulli injector (benchmark configuration 4: FP16 8192^3, rate 1e-6 per element)."""
 import numpy as np
 import pytest
 

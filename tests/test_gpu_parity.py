@@ -1,6 +1,6 @@
 """Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
 
-Tolerances (written from the arithmetic, see DESIGN.md "Tolerances"):
+Tolerances (written from the arithmetic):
   FP32 accumulation: 1e-5 x (sum of absolute values of the terms of the quantity)
   FP64 accumulation: 1e-12 x the same scale
   max / min: exact.  Flags: exact.  Injection records: exact (set of (row, col, bit),
