@@ -361,7 +361,7 @@ def main():
             o = orc.verify(cfg["A"], cfg["B"], dt, tb, e_max=e_max, rows=rows)
             n_pass += 1
             t_cpu = time.time() - t0
-            if t_cpu >= 10.0 or n_pass >= 200:
+            if t_cpu >= 10.0 or n_pass >= 100000:
                 break
         done_flops = (flops if rows is None else flops * len(rows) / M) * n_pass
         sample = f"{n_pass} x " + sample
