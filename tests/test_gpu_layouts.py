@@ -108,3 +108,58 @@ def test_full_size_bernoulli_c4():
             decided += 1
     assert decided >= len(per_row) // 2
     assert r["nflag"] == int(r["flags"].sum())
+
+
+def test_full_size_c3_every_route():
+    """BF16 FFN shape 4096 x 11008 x 4096 with B stored N x K (43 tile-columns, an odd count): the
+    weighted, row+column and block-wise routes at full size on sampled rows and columns."""
+    from test_gpu_weighted import check_weighted
+    from paper_2602_08043_amd import binding as vb
+    cfg = wl.make_config("c3_bf16_ffn", seed=1)
+    dt, M, N, K, tb = cfg["dtype"], cfg["M"], cfg["N"], cfg["K"], cfg["transB"]
+    dA, dB = _dev(cfg["A"], dt), _dev(cfg["B"], dt)
+    vg = _session(M, N, K, dt, tb)
+    rows = np.unique(np.concatenate([wl.rng(1, 5).choice(M, size=20, replace=False), [0, 255, 256, M - 1]]))
+    o = orc.verify(cfg["A"], cfg["B"], dt, tb, e_max=_emax(dt, K, N), rows=rows)
+    tol = 1e-5
+    # weighted route
+    vg.run_weighted(dA, dB, correct=1)
+    r = vg.results()
+    check_light(r, o, dt, M, N, K)
+    check_rows(r, o, dt, rows)
+    check_weighted(r, o, dt, rows)
+    assert r["nflag"] == 0 and r["ncorrected"] == 0 and np.all(r["loc"] == orc.LOC_NOT_FLAGGED)
+    # row + column route: sampled columns against the product of A with those columns
+    vg.run_rc(dA, dB)
+    r = vg.results()
+    oc = orc.verify_columns(cfg["A"], cfg["B"], dt, tb, e_max=_emax(dt, K, max(N, M)), full_gemm=False)
+    assert np.all(np.abs(r["eA"] - oc["eA"]) <= tol * oc["scale_eA"])
+    assert np.all(np.abs(r["expected_col"] - oc["expected_col"]) <= tol * oc["scale_expected_col"])
+    assert np.all(np.abs(r["T_col"] - oc["T_col"]) <= 2e-5 * oc["T_col"])
+    cols = np.unique(np.concatenate([wl.rng(1, 6).choice(N, size=20, replace=False), [0, 255, 256, N - 1]]))
+    A64 = orc.decode(cfg["A"], dt)
+    B64 = orc.logical_B(cfg["B"], dt, tb)
+    colsum = (A64 @ B64[:, cols]).sum(axis=0)
+    assert np.all(np.abs(r["colsum"][cols] - colsum) <= tol * oc["scale_colsum"][cols])
+    assert r["nflag"] == 0 and r["ncolflag"] == 0
+    assert np.all(np.abs(r["E_col"]) <= r["T_col"])
+    # block-wise route
+    W = vb.vabft_block_width(dt)
+    vg.run_blocks(dA, dB)
+    r = vg.results()
+    ob = orc.verify_blocks(cfg["A"], cfg["B"], dt, tb, W, vb.vabft_default_emax(dt, K, W), full_gemm=False)
+    assert np.all(np.abs(r["Be_blk"] - ob["Be_blk"]) <= tol * ob["scale_Be_blk"] + 1e-30)
+    assert np.all(np.abs(r["expected_blk"] - ob["expected_blk"]) <= tol * ob["scale_expected_blk"] + 1e-30)
+    assert np.all(np.abs(r["T_blk"] - ob["T_blk"]) <= 1e-4 * ob["T_blk"])
+    rs = o["C"].reshape(len(rows), N // W, W).sum(axis=2).T
+    assert np.all(np.abs(r["rowsum_blk"][:, rows] - rs) <= tol * ob["scale_rowsum_blk"][:, rows])
+    assert r["nflag"] == 0 and r["nblockflag"] == 0
+    # one fault: its row, its column, its block
+    i, j = int(rows[9]), 10999
+    inj = vg.make_inject(mode=1, faults=[(i, j, 29)])
+    vg.gemm_blocks(dA, dB, inj)
+    r = vg.results()
+    assert list(zip(*np.nonzero(r["blockflags"]))) == [(j // W, i)] and r["nblockflag"] == 1 and r["nflag"] == 1
+    vg.run_rc(dA, dB, inj=inj)
+    r = vg.results()
+    assert np.nonzero(r["flags"])[0].tolist() == [i] and np.nonzero(r["colflags"])[0].tolist() == [j]
