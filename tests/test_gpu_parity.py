@@ -407,3 +407,57 @@ def test_full_size_sampled(name, variant):
     assert n == 1 and recs[0][:3] == (i, j, bit)
     assert r2["flags"][i] == 1 and r2["nflag"] == 1
     assert r2["flags"].sum() == 1
+
+
+# --------------------------------------------------------------------------
+# degenerate inputs
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,M,N,K,transB", [("bf16", 512, 512, 256, 0), ("bf16", 300, 200, 100, 1),
+                                                 ("f32", 256, 128, 64, 0), ("f64", 130, 70, 40, 1)])
+def test_constant_and_zero_matrices(dtype, M, N, K, transB):
+    """Zero matrices: every statistic, checksum, threshold and difference is exactly zero and nothing is flagged
+    (0 <= 0).  Constant matrices a, b: variances vanish, T = e_max N |a| K |b|, and with small-integer constants
+    both checksum paths are exact."""
+    for a, b in ((0.0, 0.0), (0.0, 3.0), (2.0, -0.5)):
+        A = wl.to_storage(np.full((M, K), a), dtype)
+        B = wl.to_storage(np.full((N, K) if transB else (K, N), b), dtype)
+        vg = _session(M, N, K, dtype, transB)
+        for route in ("run", "run_fused"):
+            getattr(vg, route)(_dev(A, dtype), _dev(B, dtype))
+            r = vg.results()
+            e_max = _emax(dtype, K, N)
+            assert np.all(r["Be"] == N * b) and np.all(r["expected"] == K * a * N * b)
+            assert np.all(r["rowsum"] == K * a * N * b) and not r["E"].any()
+            assert np.allclose(r["T"], e_max * N * abs(a) * K * abs(b), rtol=1e-6, atol=0)
+            assert np.all(r["S"] == [K * abs(b), 0.0, K * b * b])
+            assert r["nflag"] == 0 and not r["flags"].any()
+            assert np.all(orc.decode(r["C"], dtype) == K * a * b)
+
+
+@pytest.mark.parametrize("dtype,M,N,K,transB", [("bf16", 512, 512, 256, 0), ("f16", 300, 200, 100, 1),
+                                                 ("f32", 256, 128, 64, 0), ("f64", 130, 70, 40, 0)])
+def test_nan_and_inf_inputs_flag_their_rows(dtype, M, N, K, transB):
+    """A NaN or an infinity in a row of A poisons that row's checksums; `flag = !(|E| <= T)` flags it (the oracle
+    agrees) and leaves the other rows alone.  A NaN in B poisons every row."""
+    A, B = _gen(dtype, M, N, K, transB, 77, "n_1e-6_1")
+    A = A.copy()
+    nan_code = {"bf16": np.uint16(0x7FC0)}.get(dtype)
+    inf_code = {"bf16": np.uint16(0x7F80)}.get(dtype)
+    A[5, 7] = nan_code if nan_code is not None else np.nan
+    A[M - 2, K - 1] = inf_code if inf_code is not None else np.inf
+    vg = _session(M, N, K, dtype, transB)
+    for route in ("run", "run_fused"):
+        getattr(vg, route)(_dev(A, dtype), _dev(B, dtype))
+        r = vg.results()
+        with np.errstate(invalid="ignore", over="ignore"):
+            o = orc.verify(A, B, dtype, transB, e_max=_emax(dtype, K, N))
+        assert o["flags"][5] == 1 and o["flags"][M - 2] == 1 and o["flags"].sum() == 2
+        assert np.array_equal(r["flags"], o["flags"]) and r["nflag"] == 2
+        ok = np.ones(M, dtype=bool)
+        ok[[5, M - 2]] = False
+        assert np.all(np.abs(r["E"][ok]) <= r["T"][ok])
+    Bn = B.copy()
+    Bn[3, 4] = nan_code if nan_code is not None else np.nan
+    vg.run_fused(_dev(A, dtype), _dev(Bn, dtype))
+    r = vg.results()
+    assert r["nflag"] == M and r["flags"].all()
