@@ -179,9 +179,11 @@ static void tile_shape(int dtype, int* bm, int* bn) {
 }
 
 // Workspace layout: [tickets: tiles_m int32 + one 64-bit counter, rounded to 256 B][scratch].
-// The scratch area holds, for the GEMM, rowpart[tiles_n][M] acc followed (16-bit types) by
-// apart[tiles_n][4][M] acc, and for the encode of an N x K B its column partials; the two
-// calls are ordered on one stream, so they share it.  The tickets must be zero between
+// The scratch area holds, for the GEMM, in units of tiles_n * M accumulator words: 16-bit
+// types rowpart [0,1), apart [1,5), rowpart2 [5,6); wide types (two row-sum partials per
+// tile-column) rowpart [0,2), rowpart2 [2,4), apart [4,8); then the column-sum partials.  The
+// encode of an N x K B keeps its column partials there; the calls are ordered on one stream,
+// so they share it.  The tickets must be zero between
 // launches: the kernels leave them zero, vabft_workspace_init zeroes them the first time.
 static size_t tickets_bytes(const vabft_problem* p) {
     int bm, bn;
@@ -204,10 +206,10 @@ size_t gemm_workspace_bytes(const vabft_problem* p) {
     const size_t tiles_n = ((size_t)p->N + bn - 1) / bn;
     const bool is16 = is_tile256(p->dtype);
     // 16-bit: rowpart + 4 A-statistics partials + weighted rowpart per tile-column; wide types: two
-    // row-sum partials per tile-column (one per wavefront column), plain and weighted
+    // row-sum partials per tile-column (one per wavefront column), plain and weighted, + 4 A-statistics partials
     const size_t tiles_m = ((size_t)p->M + bm - 1) / bm;
     // ... and the column-sum partials: one (16-bit) or two (wide) vectors of N per tile-row
-    return (tiles_n * (size_t)p->M * (is16 ? 6 : 4) + tiles_m * (size_t)p->N * (is16 ? 1 : 2)) * acc_bytes(p->dtype);
+    return (tiles_n * (size_t)p->M * (is16 ? 6 : 8) + tiles_m * (size_t)p->N * (is16 ? 1 : 2)) * acc_bytes(p->dtype);
 }
 
 __global__ void fill_zero_kernel(uint32_t* p, size_t n) {
@@ -246,11 +248,11 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     unsigned char* wsb = reinterpret_cast<unsigned char*>(ws);
     a.tickets = reinterpret_cast<int32_t*>(wsb);
     a.rowpart = ws ? wsb + tickets_bytes(p) : nullptr;
-    a.apart = ws ? wsb + tickets_bytes(p) + (size_t)a.tiles_n * p->M * ab : nullptr;
+    a.apart = ws ? wsb + tickets_bytes(p) + (size_t)a.tiles_n * p->M * ab * (is16 ? 1 : 4) : nullptr;
     // weighted partials: behind rowpart + apart (16-bit) resp. behind the two plain partials (wide)
     a.rowpart2 = ws ? wsb + tickets_bytes(p) + (size_t)a.tiles_n * p->M * ab * (is16 ? 5 : 2) : nullptr;
     a.rowsum2 = d_rowsum2;
-    a.colpart = ws ? wsb + tickets_bytes(p) + (size_t)a.tiles_n * p->M * ab * (is16 ? 6 : 4) : nullptr;
+    a.colpart = ws ? wsb + tickets_bytes(p) + (size_t)a.tiles_n * p->M * ab * (is16 ? 6 : 8) : nullptr;
     a.d_ncolflag = cols ? cols->d_ncolflag : nullptr;
     a.block_mode = blocks ? 1 : 0;
     a.d_nblockflag = blocks ? blocks->d_nblockflag : nullptr;
@@ -290,12 +292,13 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     // the unguarded kernels need whole tiles and 16-byte aligned rows
     const int bk = p->dtype == VABFT_F8E4M3 ? 256 : (is16 ? 64 : 16);
     const bool edge = (p->M % bm) || (p->N % bn) || (p->K % bk) || !a.a_vec_ok || !a.b_vec_ok || !a.c_vec_ok;
-    // whole-tile 16-bit kernels do the compare-and-flag step (and, if asked, the A-side pass) in-kernel
-    const bool in_kernel_finalize = is16 && !edge;
+    // whole-tile kernels do the compare-and-flag step (and, if asked, the A-side pass) in-kernel
+    const bool in_kernel_finalize = !edge;
     if (fused) {
-        // the fused kernel caches the Be slices of the k-units a tile-column folds: at most 16
-        if (in_kernel_finalize && p->dtype != VABFT_F8E4M3 && a.tiles_n >= 2 && p->K % 128 == 0 &&
-            (p->K / 128) / a.tiles_n + 2 <= 16) {
+        // the fused 16-bit kernel caches the Be slices of the k-units a tile-column folds: at most 16
+        const bool fits16 = p->dtype != VABFT_F8E4M3 && a.tiles_n >= 2 && p->K % 128 == 0 &&
+                            (p->K / 128) / a.tiles_n + 2 <= 16;
+        if (in_kernel_finalize && (!is16 || fits16)) {
             a.fused_stats = 1;
             a.Be = fused->d_Be;
             a.S = fused->d_S;
@@ -314,7 +317,8 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     if (cols && d_rowsum2 && mode != 2) return VABFT_EUNSUPPORTED;
     if (blocks) {
         if (cols || d_rowsum2) return VABFT_EUNSUPPORTED;
-        if (mode == 1 && in_kernel_finalize) mode = 5;  // whole-tile kernels: partials only, no in-kernel compare
+        if (mode == 1 && in_kernel_finalize && is16) mode = 5;  // partials only, no in-kernel compare (the wide
+                                                                // kernels read block_mode at run time)
     }
     switch (p->dtype) {
         case VABFT_F8E4M3:

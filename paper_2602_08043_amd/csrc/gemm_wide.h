@@ -10,6 +10,15 @@
 // The epilogue goes through LDS: each wavefront parks its tile there, one lane per row adds
 // the row in column order (two partial row sums per tile-column, one per wavefront), and C
 // leaves in 16-byte pieces contiguous along rows.
+//
+// Whole-tile problems (EDGE == false) also finish the check inside this kernel, the way the
+// 16-bit kernels do: the partials are published with device-scope stores, the last workgroup
+// to finish a tile-row (an arrival ticket per tile-row) folds them in a fixed order, compares
+// with the threshold and writes rowsum, E and flags; the last row block writes nflag.  With
+// FUSED the A-side of Algorithm 1 rides along: every A tile passes through registers on its
+// way to LDS, and tile-column bn folds the k-tiles kt with kt % tiles_n == bn into
+// (sum, dot with Be, max, min) per row of A, from which the last workgroup forms the row's
+// mean, extrema-variance bound, expected checksum A (B r1) and threshold.
 #pragma once
 #include "gemm_common.h"
 
@@ -42,15 +51,43 @@ template <typename T> constexpr int b_elems() { return (BN * LDK) > (BK * ldn<T>
 template <typename T> constexpr int stage_elems() { return a_elems<T>() + b_elems<T>(); }
 template <typename T> constexpr int loop_bytes() { return 2 * stage_elems<T>() * (int)sizeof(T); }
 template <typename T> constexpr int epi_bytes() { return 4 * 64 * (64 + 16 / (int)sizeof(T)) * (int)sizeof(T); }
-template <typename T> constexpr int lds_bytes() { return loop_bytes<T>() > epi_bytes<T>() ? loop_bytes<T>() : epi_bytes<T>(); }
+// 16 more bytes behind the larger of the two for the "last workgroup of the tile-row" flag
+template <typename T> constexpr int flag_offset() { return loop_bytes<T>() > epi_bytes<T>() ? loop_bytes<T>() : epi_bytes<T>(); }
+template <typename T> constexpr int lds_bytes() { return flag_offset<T>() + 16; }
+
+// Partials exchanged between workgroups (possibly on different XCDs, each with a private L2) go
+// through device-scope relaxed atomic stores and loads, performed at the device's coherence
+// point: no cache write-back / invalidate is needed around the ticket.
+__device__ __forceinline__ float ld_dev(const float* p) {
+    return __builtin_bit_cast(float, __hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ double ld_dev(const double* p) {
+    return __builtin_bit_cast(double, __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ void st_dev(float* p, float v) {
+    __hip_atomic_store(reinterpret_cast<uint32_t*>(p), __builtin_bit_cast(uint32_t, v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(double* p, double v) {
+    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), __builtin_bit_cast(uint64_t, v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T> __device__ __forceinline__ constexpr T lowest();
+template <> __device__ __forceinline__ constexpr float lowest<float>() { return -3.402823466e+38f; }
+template <> __device__ __forceinline__ constexpr double lowest<double>() { return -1.7976931348623157e+308; }
 }  // namespace gw
 
-// MODE 0: plain GEMM; 1: fused row-sum check; 2: check plus the fault injector.
-template <typename T, int TRANSB, int MODE, bool EDGE>
+// MODE 0: plain GEMM; 1: fused row-sum check; 2: check, fault injector, weighted row sums and
+// column sums; 3: check and weighted row sums; 4: check and column sums.
+// FUSED (whole tiles only): also the A-side statistics, expected checksum and thresholds.
+template <typename T, int TRANSB, int MODE, bool EDGE, bool FUSED>
 __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     using namespace gw;
     constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE == 2 || MODE == 3;
     constexpr bool CSUM = MODE == 2 || MODE == 4;
+    static_assert(!FUSED || (VERIFY && !EDGE), "fused statistics belong to the whole-tile verified kernel");
     using Cfg = WideCfg<T>;
     using accv_t = typename Cfg::accv_t;
     constexpr int MT = Cfg::MT, KM = Cfg::KM, NR = Cfg::NR, V = Cfg::V;
@@ -62,7 +99,8 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     const int lm = lane % MT, lk = lane / MT;
     int bm, bn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
-    if (VERIFY && blockIdx.x == 0 && tid == 0) *g.d_nflag = 0;
+    // a compare kernel that follows this one counts into nflag; the in-kernel compare writes it itself
+    if (VERIFY && (EDGE || g.block_mode) && blockIdx.x == 0 && tid == 0) *g.d_nflag = 0;
     if (VERIFY && blockIdx.x == 0 && tid == 0 && g.block_mode) *g.d_nblockflag = 0;
     if (CSUM && blockIdx.x == 0 && tid == 0 && g.d_ncolflag) *g.d_ncolflag = 0;
     const int row0 = bm * BM, col0 = bn * BN;
@@ -141,6 +179,35 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
         }
     };
 
+    // ---- fused A-side statistics (FUSED) ------------------------------------------------
+    // Chunk p of this thread is V consecutive k of row (tid + 256 p) / CPR of the tile; the
+    // chunk's position in the k-tile, tid % CPR, is the same for every p, so one 16-byte
+    // piece of Be serves all of them.  st[p] = (sum, dot with Be, max, min).
+    T st[NCH_A][4];
+    raw16 be_raw = {{0u, 0u, 0u, 0u}};
+#pragma unroll
+    for (int p = 0; p < NCH_A; ++p) {
+        st[p][0] = 0;
+        st[p][1] = 0;
+        st[p][2] = lowest<T>();
+        st[p][3] = -lowest<T>();
+    }
+    auto load_be = [&](int kt) { be_raw = ld16(reinterpret_cast<const T*>(g.Be) + kt * BK + (tid % CPR) * V); };
+    auto fold_stats = [&]() {
+        T bev[V];
+        __builtin_memcpy(bev, &be_raw, 16);
+#pragma unroll
+        for (int p = 0; p < NCH_A; ++p)
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const T x = ra[p][e];
+                st[p][0] += x;
+                st[p][1] = fma(x, bev[e], st[p][1]);
+                st[p][2] = fmax(st[p][2], x);
+                st[p][3] = fmin(st[p][3], x);
+            }
+    };
+
     auto compute = [&](int s) {
         const T* As = smem + s * stage_elems<T>();
         const T* Bs = As + a_elems<T>();
@@ -161,15 +228,61 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     };
 
     const int nk = (g.K + BK - 1) / BK;
+    int next_fold = bn;  // FUSED: the next k-tile this tile-column folds into the statistics
+    if (FUSED) load_be(0);
     load_tiles(0);
     store_tiles(0);
+    if (FUSED && next_fold == 0) {
+        fold_stats();
+        next_fold += g.tiles_n;
+    }
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const bool more = kt + 1 < nk;
+        const bool fold = FUSED && more && kt + 1 == next_fold;  // workgroup-uniform
+        // the 16 bytes of Be are fetched for every k-tile, in front of the tile's own loads: loads
+        // return in order, so the waits of store_tiles cover them, and a conditional load here
+        // would make the compiler drain the whole load queue in front of it
+        if (FUSED && more) load_be(kt + 1);
         if (more) load_tiles(kt + 1);
         compute(kt & 1);
         if (more) store_tiles((kt + 1) & 1);
+        if (fold) {
+            fold_stats();
+            next_fold += g.tiles_n;
+        }
         __syncthreads();
+    }
+
+    if constexpr (FUSED) {
+        // Publish this tile-column's A statistics while the operand stages of LDS are free: the
+        // CPR threads that share a row of the A tile are neighbouring lanes; after their
+        // exchange the row's four values pass through LDS so that the device-scope stores are
+        // contiguous along the rows (64 consecutive words per wavefront and store).
+        T* sred = smem;  // [4][BM]
+#pragma unroll
+        for (int p = 0; p < NCH_A; ++p) {
+#pragma unroll
+            for (int d = 1; d < CPR; d <<= 1) {
+                st[p][0] += __shfl_xor(st[p][0], d, 64);
+                st[p][1] += __shfl_xor(st[p][1], d, 64);
+                st[p][2] = fmax(st[p][2], __shfl_xor(st[p][2], d, 64));
+                st[p][3] = fmin(st[p][3], __shfl_xor(st[p][3], d, 64));
+            }
+            if (tid % CPR == 0) {
+                const int r = (tid + 256 * p) / CPR;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) sred[q * BM + r] = st[p][q];
+            }
+        }
+        __syncthreads();
+        T* ap = reinterpret_cast<T*>(g.apart) + (int64_t)bn * 4 * g.M + row0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int q = 2 * (tid / BM) + h, r = tid % BM;
+            st_dev(ap + q * (int64_t)g.M + r, sred[q * BM + r]);
+        }
+        __syncthreads();  // the accumulator tiles are parked over this area next
     }
 
     // ---- epilogue through LDS ------------------------------------------------------------
@@ -246,7 +359,10 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
         }
         const T s = (part[0] + part[1]) + (part[2] + part[3]);
         const int gi = trow0 + lane;
-        if (gi < g.M) reinterpret_cast<T*>(g.rowpart)[(int64_t)(2 * bn + wn) * g.M + gi] = s;
+        if (!EDGE)
+            st_dev(reinterpret_cast<T*>(g.rowpart) + (int64_t)(2 * bn + wn) * g.M + gi, s);
+        else if (gi < g.M)
+            reinterpret_cast<T*>(g.rowpart)[(int64_t)(2 * bn + wn) * g.M + gi] = s;
         if (WSUM) {
             // position-weighted row sum (section 2.2 C^{r2'} = C r2, r2 = [1..N]): weights 0..63
             // inside the tile, the offset of the tile's first column applied once to s
@@ -262,7 +378,10 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
                 part2[(c / V) & 3] += cs;
             }
             const T s2 = fma((T)(tcol0 + 1), s, (part2[0] + part2[1]) + (part2[2] + part2[3]));
-            if (gi < g.M) reinterpret_cast<T*>(g.rowpart2)[(int64_t)(2 * bn + wn) * g.M + gi] = s2;
+            if (!EDGE)
+                st_dev(reinterpret_cast<T*>(g.rowpart2) + (int64_t)(2 * bn + wn) * g.M + gi, s2);
+            else if (gi < g.M)
+                reinterpret_cast<T*>(g.rowpart2)[(int64_t)(2 * bn + wn) * g.M + gi] = s2;
         }
     }
 
@@ -275,6 +394,124 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
         const int gj = tcol0 + lane;
         if (gj < g.N)
             reinterpret_cast<T*>(g.colpart)[(int64_t)(2 * bm + wm) * g.N + gj] = (part[0] + part[1]) + (part[2] + part[3]);
+    }
+
+    if constexpr (VERIFY && !EDGE) {
+        T* const rowpart = reinterpret_cast<T*>(g.rowpart);
+        T* const rowpart2 = reinterpret_cast<T*>(g.rowpart2);
+        T* const apart = reinterpret_cast<T*>(g.apart);
+        // block-wise check: the partials are all this kernel leaves; a later kernel compares them per block
+        if (!g.block_mode) {
+            // Every thread's partials are performed (vmcnt(0)) before the workgroup takes this
+            // tile-row's arrival ticket; the check runs before the store of C because behind that
+            // burst of stores each of these round trips would cost several microseconds.
+            int* s_last = reinterpret_cast<int*>(smem_raw + flag_offset<T>());
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            if (tid == 0) *s_last = (atomicAdd(&g.tickets[bm], 1) == g.tiles_n - 1);
+            __syncthreads();
+            if (*s_last) {
+                // fold the partials in tile order (loads issued in batches so their latencies
+                // overlap; absent entries count as the neutral element)
+                const bool act = tid < BM;
+                const int gi = row0 + (act ? tid : 0);
+                const int np = 2 * g.tiles_n;
+                T rs = 0, rs2 = 0, sum = 0, dot = 0, mx = lowest<T>(), mn = -lowest<T>();
+                if (act) {
+                    for (int t0 = 0; t0 < np; t0 += 16) {
+                        T v[16], v2[16];
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) {
+                            const int t = t0 + j < np ? t0 + j : np - 1;
+                            v[j] = ld_dev(rowpart + (int64_t)t * g.M + gi);
+                            if (WSUM) v2[j] = ld_dev(rowpart2 + (int64_t)t * g.M + gi);
+                        }
+#pragma unroll
+                        for (int j = 0; j < 16; ++j)
+                            if (!(t0 + j < np)) {
+                                v[j] = 0;
+                                if (WSUM) v2[j] = 0;
+                            }
+#pragma unroll
+                        for (int j = 0; j < 16; j += 4) {
+                            rs += (v[j] + v[j + 1]) + (v[j + 2] + v[j + 3]);
+                            if (WSUM) rs2 += (v2[j] + v2[j + 1]) + (v2[j + 2] + v2[j + 3]);
+                        }
+                    }
+                    if (FUSED) {
+                        for (int t0 = 0; t0 < g.tiles_n; t0 += 8) {
+                            T v[8][4];
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) {
+                                const int t = t0 + j < g.tiles_n ? t0 + j : g.tiles_n - 1;
+                                const T* ap = apart + (int64_t)t * 4 * g.M + gi;
+#pragma unroll
+                                for (int q = 0; q < 4; ++q) v[j][q] = ld_dev(ap + q * (int64_t)g.M);
+                            }
+#pragma unroll
+                            for (int j = 0; j < 8; ++j)
+                                if (!(t0 + j < g.tiles_n)) {
+                                    v[j][0] = 0;
+                                    v[j][1] = 0;
+                                    v[j][2] = lowest<T>();
+                                    v[j][3] = -lowest<T>();
+                                }
+#pragma unroll
+                            for (int j = 0; j < 8; j += 4) {
+                                sum += (v[j][0] + v[j + 1][0]) + (v[j + 2][0] + v[j + 3][0]);
+                                dot += (v[j][1] + v[j + 1][1]) + (v[j + 2][1] + v[j + 3][1]);
+                                mx = fmax(mx, fmax(fmax(v[j][2], v[j + 1][2]), fmax(v[j + 2][2], v[j + 3][2])));
+                                mn = fmin(mn, fmin(fmin(v[j][3], v[j + 1][3]), fmin(v[j + 2][3], v[j + 3][3])));
+                            }
+                        }
+                    }
+                }
+                int f = 0;
+                if (act) {
+                    T expv, thr;
+                    if (FUSED) {
+                        // Algorithm 1 for this row of A, in double precision
+                        const double mu = (double)sum / (double)g.K;
+                        double var = ((double)mx - mu) * (mu - (double)mn);
+                        var = var > 0 ? var : 0;
+                        const double S1 = g.S[0], S2 = g.S[1], S3 = g.S[2], dN = (double)g.N;
+                        const double t_det = dN * fabs(mu) * S1;
+                        const double t_var23 = g.c_sigma * sqrt(dN * mu * mu * S2 + dN * dN * var * S3);
+                        const double t_var4 = g.c_sigma * sqrt(dN) * sqrt(var) * sqrt(S2);
+                        expv = dot;
+                        thr = (T)(g.e_max * (t_det + t_var23 + t_var4));
+                        T* astat = reinterpret_cast<T*>(g.astat);
+                        astat[3 * (int64_t)gi + 0] = mx;
+                        astat[3 * (int64_t)gi + 1] = mn;
+                        astat[3 * (int64_t)gi + 2] = (T)mu;
+                        reinterpret_cast<T*>(const_cast<void*>(g.expected))[gi] = expv;
+                        reinterpret_cast<T*>(const_cast<void*>(g.T))[gi] = thr;
+                    } else {
+                        expv = reinterpret_cast<const T*>(g.expected)[gi];
+                        thr = reinterpret_cast<const T*>(g.T)[gi];
+                    }
+                    const T e = expv - rs;
+                    f = !(fabs(e) <= thr);
+                    reinterpret_cast<T*>(g.rowsum)[gi] = rs;
+                    if (WSUM && g.rowsum2) reinterpret_cast<T*>(g.rowsum2)[gi] = rs2;
+                    reinterpret_cast<T*>(g.E)[gi] = e;
+                    g.flags[gi] = f;
+                }
+                const int cnt = __syncthreads_count(f);
+                if (tid == 0) {
+                    // this tile-row is done: reset its ticket, then one 64-bit atomic both counts the
+                    // finished row blocks (high word) and accumulates the flagged rows (low word);
+                    // whoever completes the count publishes nflag and leaves the counter zero
+                    __hip_atomic_store(&g.tickets[bm], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    unsigned long long* done = reinterpret_cast<unsigned long long*>(g.tickets + ((g.tiles_m + 1) & ~1));
+                    const unsigned long long old = atomicAdd(done, (1ull << 32) | (unsigned long long)(unsigned)cnt);
+                    if ((int)(old >> 32) == g.tiles_m - 1) {
+                        *g.d_nflag = (int)(unsigned)(old & 0xffffffffull) + cnt;
+                        __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+            }
+        }
     }
 
     T* __restrict__ C = reinterpret_cast<T*>(g.C);
@@ -304,11 +541,12 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
 
 template <typename T>
 static int gemmw_launch(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st) {
+    const bool fused = a.fused_stats != 0;
     const dim3 grid(a.tiles_m * a.tiles_n), block(256);
     const size_t lds = gw::lds_bytes<T>();
-#define VABFT_GW_CASE(TB, VF, ED)                                                                          \
-    if (transB == TB && mode == VF && edge == ED) {                                               \
-        auto kern = gemmw_kernel<T, TB, VF, ED>;                                                           \
+#define VABFT_GW_CASE(TB, VF, ED, FU)                                                                      \
+    if (transB == TB && mode == VF && edge == ED && fused == FU) {                                         \
+        auto kern = gemmw_kernel<T, TB, VF, ED, FU>;                                                       \
         static bool attr_set = false;                                                                      \
         if (!attr_set) {                                                                                   \
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
@@ -319,26 +557,31 @@ static int gemmw_launch(const GemmArgs& a, int transB, int mode, bool edge, hipS
         kern<<<grid, block, lds, st>>>(a);                                                                 \
         return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;                                 \
     }
-    VABFT_GW_CASE(0, 0, false)
-    VABFT_GW_CASE(0, 0, true)
-    VABFT_GW_CASE(0, 1, false)
-    VABFT_GW_CASE(0, 1, true)
-    VABFT_GW_CASE(0, 2, false)
-    VABFT_GW_CASE(0, 2, true)
-    VABFT_GW_CASE(0, 3, false)
-    VABFT_GW_CASE(0, 3, true)
-    VABFT_GW_CASE(0, 4, false)
-    VABFT_GW_CASE(0, 4, true)
-    VABFT_GW_CASE(1, 0, false)
-    VABFT_GW_CASE(1, 0, true)
-    VABFT_GW_CASE(1, 1, false)
-    VABFT_GW_CASE(1, 1, true)
-    VABFT_GW_CASE(1, 2, false)
-    VABFT_GW_CASE(1, 2, true)
-    VABFT_GW_CASE(1, 3, false)
-    VABFT_GW_CASE(1, 3, true)
-    VABFT_GW_CASE(1, 4, false)
-    VABFT_GW_CASE(1, 4, true)
+    VABFT_GW_CASE(0, 0, false, false)
+    VABFT_GW_CASE(0, 0, true, false)
+    VABFT_GW_CASE(0, 1, false, false)
+    VABFT_GW_CASE(0, 1, true, false)
+    VABFT_GW_CASE(0, 2, false, false)
+    VABFT_GW_CASE(0, 2, true, false)
+    VABFT_GW_CASE(0, 3, false, false)
+    VABFT_GW_CASE(0, 3, true, false)
+    VABFT_GW_CASE(0, 4, false, false)
+    VABFT_GW_CASE(0, 4, true, false)
+    VABFT_GW_CASE(1, 0, false, false)
+    VABFT_GW_CASE(1, 0, true, false)
+    VABFT_GW_CASE(1, 1, false, false)
+    VABFT_GW_CASE(1, 1, true, false)
+    VABFT_GW_CASE(1, 2, false, false)
+    VABFT_GW_CASE(1, 2, true, false)
+    VABFT_GW_CASE(1, 3, false, false)
+    VABFT_GW_CASE(1, 3, true, false)
+    VABFT_GW_CASE(1, 4, false, false)
+    VABFT_GW_CASE(1, 4, true, false)
+    // with the A-side statistics: the check alone, and the injector runs
+    VABFT_GW_CASE(0, 1, false, true)
+    VABFT_GW_CASE(0, 2, false, true)
+    VABFT_GW_CASE(1, 1, false, true)
+    VABFT_GW_CASE(1, 2, false, true)
 #undef VABFT_GW_CASE
     return VABFT_EINVAL;
 }
