@@ -159,9 +159,10 @@ int vabft_gemm_verified(const vabft_problem* p, const void* dA, const void* dB, 
  * once.  Inputs d_Be / d_S come from vabft_encode; e_max, c_sigma as in vabft_threshold.
  * Outputs: d_astat [3M], d_expected [M], d_T [M] (as vabft_threshold) and d_rowsum, d_E,
  * d_flags, d_nflag, dC, injection log (as vabft_gemm_verified).  For BF16 / FP16 problems made
- * of whole 256 x 256 x 128 tiles with 16-byte aligned rows the statistics ride on the operand
- * fragments inside the GEMM kernel and the compare-and-flag step runs in the last workgroup of
- * each row block (a single launch); other problems run the two passes back to back.  The
+ * of whole 256 x 256 x 128 tiles, and FP32 / FP64 problems made of whole 128 x 128 x 16 tiles,
+ * with 16-byte aligned rows the statistics ride on the operand tiles inside the GEMM kernel
+ * and the compare-and-flag step runs in the last workgroup of each row block (a single
+ * launch); other problems run the two passes back to back.  The
  * summation order of the A-side sums differs between the two routes (both are fixed and
  * bit-reproducible). */
 int vabft_gemm_verified_fused(const vabft_problem* p, const void* dA, const void* dB, void* dC,

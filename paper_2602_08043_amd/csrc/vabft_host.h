@@ -61,7 +61,7 @@ struct GemmArgs {
     void* rowpart;    // [tiles_n][M] acc: per-tile-column partial row sums
     int32_t* d_nflag; // number of flagged rows
     InjectArgs inj;
-    // in-kernel compare-and-flag (whole-tile 16-bit kernels): the last workgroup to finish a
+    // in-kernel compare-and-flag (whole-tile kernels): the last workgroup to finish a
     // tile-row combines the partials of that row block
     const void* expected;  // [M] acc: input, or output when fused_stats
     const void* T;         // [M] acc: input, or output when fused_stats
@@ -76,7 +76,7 @@ struct GemmArgs {
     const double* S;  // [3]
     double e_max, c_sigma;
     void* astat;      // [M][3] acc, output
-    void* apart;      // [tiles_n][4][M] acc: per-K-slice (sum, dot, max, min) of the rows of A
+    void* apart;      // [tiles_n][4][M] acc: per-K-slice (sum, dot, max, min) of the rows of A (fused_stats)
     // position-weighted row sums C r2 (kernel modes 2 and 3)
     void* rowpart2;   // partials, same shape as rowpart
     void* rowsum2;    // [M] acc, output; may be null
@@ -122,8 +122,9 @@ void workspace_init_launch(void* ws, size_t bytes, hipStream_t st);
 // per-dtype launchers (one translation unit each, to compile in parallel)
 // mode: 0 plain, 1 check, 2 check + injector + weighted row sums + column sums, 3 check + weighted row
 // sums, 4 check + column sums, 5 row-sum partials only (block-wise check, whole-tile kernels).
-// With edge == false the 16-bit kernels do the
-// compare-and-flag step themselves; otherwise the caller launches the finalize kernel.
+// With edge == false the kernels do the compare-and-flag step themselves (and, with
+// GemmArgs::fused_stats, the A-side statistics and thresholds); otherwise the caller launches the
+// finalize kernel.
 int gemm16_launch_bf16_nn(const GemmArgs& a, int mode, bool edge, hipStream_t st);
 int gemm16_launch_bf16_nt(const GemmArgs& a, int mode, bool edge, hipStream_t st);
 int gemm16_launch_f16_nn(const GemmArgs& a, int mode, bool edge, hipStream_t st);
