@@ -117,7 +117,11 @@ double vabft_default_emax(int32_t dtype, int32_t K, int32_t N);
  *           sigma_Bk^2 = max(0, (max - mu)(mu - min))      (section 3.5 theorem)
  * Results are bit-reproducible from run to run (no floating-point atomics).  The aggregates are
  * folded by the last workgroup to finish (partials and an arrival counter in the workspace), so
- * the call needs the workspace (vabft_workspace_bytes, zero-filled once) for either layout of B. */
+ * the call needs the workspace (vabft_workspace_bytes, zero-filled once) for either layout of B.
+ * d_S may be NULL: then the fold is deferred -- S1..S3 stay as the per-workgroup partials in the
+ * workspace, where they remain valid until the next encode call on that workspace, and
+ * vabft_gemm_verified_fused called with d_S = NULL folds them itself (same order, same bits).
+ * This takes the arrival-counter round trips out of the encode's tail. */
 int vabft_encode(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S,
                  void* d_workspace, size_t workspace_bytes, void* stream);
 
@@ -156,7 +160,9 @@ int vabft_gemm_verified(const vabft_problem* p, const void* dA, const void* dB, 
 /* The same check with the A-side pass of Algorithm 1 folded into the GEMM launch: one call
  * computes what vabft_threshold followed by vabft_gemm_verified(verify = 1) computes
  * (Algorithm 1 for every row of A; section 2.2 C^{r1} = A (B r1); Eq. abft-check), reading A
- * once.  Inputs d_Be / d_S come from vabft_encode; e_max, c_sigma as in vabft_threshold.
+ * once.  Inputs d_Be / d_S come from vabft_encode (d_S = NULL: the preceding vabft_encode on this
+ * workspace was called with d_S = NULL and its partials are folded here; without such a call the
+ * thresholds are undefined); e_max, c_sigma as in vabft_threshold.
  * Outputs: d_astat [3M], d_expected [M], d_T [M] (as vabft_threshold) and d_rowsum, d_E,
  * d_flags, d_nflag, dC, injection log (as vabft_gemm_verified).  For BF16 / FP16 problems made
  * of whole 256 x 256 x 128 tiles, and FP32 / FP64 problems made of whole 128 x 128 x 16 tiles,

@@ -178,18 +178,41 @@ static void tile_shape(int dtype, int* bm, int* bn) {
     }
 }
 
-// Workspace layout: [tickets: tiles_m int32 + one 64-bit counter, rounded to 256 B][scratch].
+// Workspace layout: [tickets: tiles_m int32 + one 64-bit counter, rounded to 256 B][S area: three doubles
+// (the fold of the partials, when a kernel of its own has to make it) at +0, the per-workgroup partials of
+// S1..S3 of the last encode at +64][scratch].
 // The scratch area holds, for the GEMM, in units of tiles_n * M accumulator words: 16-bit
 // types rowpart [0,1), apart [1,5), rowpart2 [5,6); wide types (two row-sum partials per
 // tile-column) rowpart [0,2), rowpart2 [2,4), apart [4,8); then the column-sum partials.  The
 // encode of an N x K B keeps its column partials there; the calls are ordered on one stream,
 // so they share it.  The tickets must be zero between
 // launches: the kernels leave them zero, vabft_workspace_init zeroes them the first time.
-static size_t tickets_bytes(const vabft_problem* p) {
+static size_t s_area_offset(const vabft_problem* p) {
     int bm, bn;
     tile_shape(p->dtype, &bm, &bn);
     const size_t tiles_m = ((size_t)p->M + bm - 1) / bm;
     return round_up((tiles_m + 4) * sizeof(int32_t), 256);
+}
+// everything in front of the scratch area
+static size_t tickets_bytes(const vabft_problem* p) {
+    return s_area_offset(p) + round_up(64 + (size_t)s_partial_count(p) * 3 * sizeof(double), 256);
+}
+static double* s_folded(const vabft_problem* p, void* ws) {
+    return reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(ws) + s_area_offset(p));
+}
+static double* s_partials(const vabft_problem* p, void* ws) {
+    return reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(ws) + s_area_offset(p) + 64);
+}
+
+__global__ __launch_bounds__(256) void fold_s_kernel(const double* __restrict__ partial, int count,
+                                                     double* __restrict__ S) {
+    __shared__ double s_red[12];
+    fold_s_partials_to_lds(partial, count, threadIdx.x, s_red);
+    __syncthreads();
+    if (threadIdx.x < 3) S[threadIdx.x] = folded_s(s_red, threadIdx.x);
+}
+void fold_s_launch(const double* s_partial, int count, double* S, hipStream_t st) {
+    fold_s_kernel<<<1, 256, 0, st>>>(s_partial, count, S);
 }
 
 // the encode's arrival counter: the last of the spare words behind the GEMM's tickets
@@ -265,6 +288,8 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     a.fused_stats = 0;
     a.Be = nullptr;
     a.S = nullptr;
+    a.s_partial = nullptr;
+    a.s_nparts = 0;
     a.e_max = 0;
     a.c_sigma = 0;
     a.astat = nullptr;
@@ -302,11 +327,18 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
             a.fused_stats = 1;
             a.Be = fused->d_Be;
             a.S = fused->d_S;
+            a.s_partial = s_partials(p, ws);
+            a.s_nparts = s_partial_count(p);
             a.e_max = fused->e_max;
             a.c_sigma = fused->c_sigma;
             a.astat = fused->d_astat;
         } else {
-            const int rc = threshold_dispatch(p, dA, fused->d_Be, nullptr, fused->d_S, fused->e_max, fused->c_sigma,
+            const double* dS = fused->d_S;
+            if (!dS) {  // the pass of its own needs S1..S3 folded
+                fold_s_launch(s_partials(p, ws), s_partial_count(p), s_folded(p, ws), st);
+                dS = s_folded(p, ws);
+            }
+            const int rc = threshold_dispatch(p, dA, fused->d_Be, nullptr, dS, fused->e_max, fused->c_sigma,
                                               fused->d_astat, d_expected, nullptr, d_T, st);
             if (rc != VABFT_OK) return rc;
         }
@@ -446,7 +478,7 @@ int vabft_check_offline(const vabft_problem* p, const void* dC, const void* d_ex
 
 int vabft_encode(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S, void* d_workspace,
                  size_t workspace_bytes, void* stream) {
-    if (!problem_ok(p) || !dB || !d_Be || !d_bstat || !d_S) return VABFT_EINVAL;
+    if (!problem_ok(p) || !dB || !d_Be || !d_bstat) return VABFT_EINVAL;  // d_S may be null: deferred fold
     if (!aligned_to(dB, elem_bytes(p->dtype)) || !aligned_to(d_Be, acc_bytes(p->dtype)) ||
         !aligned_to(d_bstat, acc_bytes(p->dtype)) || !aligned_to(d_S, 8))
         return VABFT_EINVAL;
@@ -454,8 +486,8 @@ int vabft_encode(const vabft_problem* p, const void* dB, void* d_Be, void* d_bst
     if (!d_workspace || workspace_bytes < tickets_bytes(p) + need || !aligned_to(d_workspace, 16))
         return VABFT_EWORKSPACE;
     void* scratch = reinterpret_cast<unsigned char*>(d_workspace) + tickets_bytes(p);
-    return encode_dispatch(p, dB, d_Be, nullptr, d_bstat, d_S, scratch, encode_ticket(p, d_workspace),
-                           (hipStream_t)stream);
+    return encode_dispatch(p, dB, d_Be, nullptr, d_bstat, d_S, s_partials(p, d_workspace), scratch,
+                           encode_ticket(p, d_workspace), (hipStream_t)stream);
 }
 
 int vabft_encode_weighted(const vabft_problem* p, const void* dB, void* d_Be, void* d_Be2, void* d_bstat, double* d_S,
@@ -468,8 +500,8 @@ int vabft_encode_weighted(const vabft_problem* p, const void* dB, void* d_Be, vo
     if (!d_workspace || workspace_bytes < tickets_bytes(p) + need || !aligned_to(d_workspace, 16))
         return VABFT_EWORKSPACE;
     void* scratch = reinterpret_cast<unsigned char*>(d_workspace) + tickets_bytes(p);
-    return encode_dispatch(p, dB, d_Be, d_Be2, d_bstat, d_S, scratch, encode_ticket(p, d_workspace),
-                           (hipStream_t)stream);
+    return encode_dispatch(p, dB, d_Be, d_Be2, d_bstat, d_S, s_partials(p, d_workspace), scratch,
+                           encode_ticket(p, d_workspace), (hipStream_t)stream);
 }
 
 int vabft_threshold(const vabft_problem* p, const void* dA, const void* d_Be, const double* d_S, double e_max,
@@ -566,8 +598,8 @@ int vabft_encode_a(const vabft_problem* p, const void* dA, void* d_eA, void* d_a
     if (!d_workspace || workspace_bytes < tickets_bytes(p) + cols_workspace_bytes(p) || !aligned_to(d_workspace, 16))
         return VABFT_EWORKSPACE;
     void* scratch = reinterpret_cast<unsigned char*>(d_workspace) + tickets_bytes(p);
-    return encode_a_dispatch(p, dA, d_eA, d_acolstat, d_SA, scratch, encode_ticket(p, d_workspace),
-                             (hipStream_t)stream);
+    return encode_a_dispatch(p, dA, d_eA, d_acolstat, d_SA, s_partials(p, d_workspace), scratch,
+                             encode_ticket(p, d_workspace), (hipStream_t)stream);
 }
 
 int vabft_threshold_cols(const vabft_problem* p, const void* dB, const void* d_eA, const double* d_SA, double e_max,
@@ -700,7 +732,7 @@ int vabft_gemm_verified_fused(const vabft_problem* p, const void* dA, const void
     const int rc = check_gemm_args(p, dA, dB, dC, 1, inj, d_expected, d_T, d_rowsum, d_E, d_flags, d_nflag, d_injlog,
                                    d_ninj, d_workspace, workspace_bytes);
     if (rc != VABFT_OK) return rc;
-    if (!d_Be || !d_S || !d_astat) return VABFT_EINVAL;
+    if (!d_Be || !d_astat) return VABFT_EINVAL;  // d_S may be null: S1..S3 are the partials of the last encode
     if (!(e_max > 0.0) || !(c_sigma >= 0.0) || !isfinite(e_max) || !isfinite(c_sigma)) return VABFT_EINVAL;
     const size_t ab = acc_bytes(p->dtype);
     if (!aligned_to(d_Be, ab) || !aligned_to(d_S, 8) || !aligned_to(d_astat, ab)) return VABFT_EINVAL;

@@ -29,6 +29,17 @@ __device__ __forceinline__ void publish_and_fold_S(double s1, double s2, double 
     __shared__ int s_last;
     __shared__ double s_red[3][4];
     const int t = threadIdx.x, nblocks = gridDim.x;
+    if (S == nullptr) {
+        // deferred fold: the partials stay where they are (plain stores: the consumer is a later kernel
+        // on the stream, which folds them in this same order)
+        if (t == 0) {
+            double* mine = partial + 3 * (int64_t)blockIdx.x;
+            mine[0] = s1;
+            mine[1] = s2;
+            mine[2] = s3;
+        }
+        return;
+    }
     if (t == 0) {
         double* mine = partial + 3 * (int64_t)blockIdx.x;
         st_agent_f64(mine, s1);
@@ -80,12 +91,14 @@ __device__ __forceinline__ void row_terms(acc_t sum, acc_t mx, acc_t mn, int N, 
 }
 
 // ---------------------------------------------------------------------------
-// B stored K x N: one wavefront reduces one row k, 16 rows per block
+// B stored K x N: 16 wavefronts per block reduce RPB rows k, 16 / RPB wavefronts per row (each a
+// contiguous segment of the row, combined in segment order).  RPB is 16 when that gives enough
+// blocks to fill the chip, else 8, 4, 2 or 1.
 // ---------------------------------------------------------------------------
 constexpr int ENC_ROWS_WAVES = 16;
 
 // W: also the position-weighted checksum B*r2, r2 = [1..N] (section 2.2): Be2[k] = sum_n (n+1) B[k,n].
-template <typename T, bool W>
+template <typename T, bool W, int RPB>
 __global__ __launch_bounds__(1024) void encode_rows_kernel(const void* __restrict__ B, int K, int N, int64_t ldb,
                                                            typename Elem<T>::acc_t* __restrict__ Be,
                                                            typename Elem<T>::acc_t* __restrict__ Be2,
@@ -94,18 +107,22 @@ __global__ __launch_bounds__(1024) void encode_rows_kernel(const void* __restric
                                                            int32_t* __restrict__ ticket, double* __restrict__ S) {
     using acc_t = typename Elem<T>::acc_t;
     constexpr int V = Elem<T>::vec;
-    __shared__ double terms[ENC_ROWS_WAVES][3];
+    constexpr int WPR = ENC_ROWS_WAVES / RPB;  // wavefronts per row
+    __shared__ double terms[RPB][3];
+    __shared__ acc_t seg[ENC_ROWS_WAVES][4];  // (sum, weighted sum, max, min) of each wavefront's segment
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int k = blockIdx.x * ENC_ROWS_WAVES + wave;
-    double t1 = 0, t2 = 0, t3 = 0;
+    const int k = blockIdx.x * RPB + wave / WPR, part = wave % WPR;
+    acc_t sum = 0, sum2 = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
     if (k < K) {
         const char* row = reinterpret_cast<const char*>(B) + (int64_t)k * ldb * Elem<T>::bytes;
-        acc_t sum = 0, sum2 = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
         int done = 0;
         if (vec_ok) {
             const int nchunks = N / V;
-            int c = lane;
-            for (; c + 192 < nchunks; c += 256) {
+            // segment of this wavefront: a multiple of 64 chunks, the last one takes what is left
+            const int per = ((nchunks + WPR - 1) / WPR + 63) / 64 * 64;
+            const int c_end = part == WPR - 1 ? nchunks : min(nchunks, (part + 1) * per);
+            int c = part * per + lane;
+            for (; c + 192 < c_end; c += 256) {
                 raw16 r0 = ld16(row + (int64_t)c * 16);
                 raw16 r1 = ld16(row + (int64_t)(c + 64) * 16);
                 raw16 r2 = ld16(row + (int64_t)(c + 128) * 16);
@@ -125,7 +142,7 @@ __global__ __launch_bounds__(1024) void encode_rows_kernel(const void* __restric
                         mn = v[u][e] < mn ? v[u][e] : mn;
                     }
             }
-            for (; c < nchunks; c += 64) {
+            for (; c < c_end; c += 64) {
                 raw16 r0 = ld16(row + (int64_t)c * 16);
                 acc_t v[V];
                 Unpack<T>::run(r0, v);
@@ -139,38 +156,62 @@ __global__ __launch_bounds__(1024) void encode_rows_kernel(const void* __restric
             }
             done = nchunks * V;
         }
-        for (int n = done + lane; n < N; n += 64) {
-            acc_t x = Unpack<T>::one(row, n);
-            sum += x;
-            if constexpr (W) sum2 = fma((acc_t)(n + 1), x, sum2);
-            mx = x > mx ? x : mx;
-            mn = x < mn ? x : mn;
+        // what the 16-byte pieces do not cover (everything, for unaligned rows): the last segment's wavefront
+        if (part == WPR - 1) {
+            for (int n = done + lane; n < N; n += 64) {
+                acc_t x = Unpack<T>::one(row, n);
+                sum += x;
+                if constexpr (W) sum2 = fma((acc_t)(n + 1), x, sum2);
+                mx = x > mx ? x : mx;
+                mn = x < mn ? x : mn;
+            }
         }
         sum = wave_sum(sum);
         mx = wave_max(mx);
         mn = wave_min(mn);
-        if constexpr (W) {
-            sum2 = wave_sum(sum2);
-            if (lane == 0) Be2[k] = sum2;
-        }
+        if constexpr (W) sum2 = wave_sum(sum2);
+    }
+    if constexpr (WPR > 1) {
         if (lane == 0) {
-            Be[k] = sum;
-            bstat[3 * (int64_t)k + 0] = mx;
-            bstat[3 * (int64_t)k + 1] = mn;
-            bstat[3 * (int64_t)k + 2] = (acc_t)((double)sum / (double)N);
+            seg[wave][0] = sum;
+            seg[wave][1] = sum2;
+            seg[wave][2] = mx;
+            seg[wave][3] = mn;
         }
+        __syncthreads();
+        if (part == 0 && lane == 0) {
+            sum = seg[wave][0];
+            sum2 = seg[wave][1];
+            mx = seg[wave][2];
+            mn = seg[wave][3];
+#pragma unroll
+            for (int q = 1; q < WPR; ++q) {  // segments in order
+                sum += seg[wave + q][0];
+                sum2 += seg[wave + q][1];
+                mx = seg[wave + q][2] > mx ? seg[wave + q][2] : mx;
+                mn = seg[wave + q][3] < mn ? seg[wave + q][3] : mn;
+            }
+        }
+    }
+    double t1 = 0, t2 = 0, t3 = 0;
+    if (k < K && part == 0 && lane == 0) {
+        if constexpr (W) Be2[k] = sum2;
+        Be[k] = sum;
+        bstat[3 * (int64_t)k + 0] = mx;
+        bstat[3 * (int64_t)k + 1] = mn;
+        bstat[3 * (int64_t)k + 2] = (acc_t)((double)sum / (double)N);
         row_terms(sum, mx, mn, N, t1, t2, t3);
     }
-    if (lane == 0) {
-        terms[wave][0] = t1;
-        terms[wave][1] = t2;
-        terms[wave][2] = t3;
+    if (part == 0 && lane == 0) {
+        terms[wave / WPR][0] = t1;
+        terms[wave / WPR][1] = t2;
+        terms[wave / WPR][2] = t3;
     }
     __syncthreads();
     double s1 = 0, s2 = 0, s3 = 0;
     if (threadIdx.x == 0) {
 #pragma unroll
-        for (int w = 0; w < ENC_ROWS_WAVES; ++w) {  // rows of the block in order
+        for (int w = 0; w < RPB; ++w) {  // rows of the block in order
             s1 += terms[w][0];
             s2 += terms[w][1];
             s3 += terms[w][2];
@@ -526,14 +567,22 @@ __global__ __launch_bounds__(256) void check_offline_kernel(const void* __restri
 
 constexpr int ENC_ROWS_PER_BLOCK = 128;  // n-rows per block in the transposed layout
 
-// per-block partials of (S1, S2, S3): [blocks][3] doubles at the start of the scratch area
-static size_t s_partial_bytes(const vabft_problem* p) {
-    const size_t blocks = ((size_t)p->K + 15) / 16;  // both layouts finish 16 rows k per block
-    return (blocks * 3 * sizeof(double) + 255) / 256 * 256;
+// Rows k per block of the finishing kernel: 16, or fewer (K x N layout) when 16 would leave most of the
+// chip's 256 compute units without a block
+static int encode_rows_per_block(const vabft_problem* p) {
+    if (p->transB) return 16;
+    int rpb = 16;
+    while (rpb > 1 && (p->K + rpb - 1) / rpb < 256) rpb >>= 1;
+    return rpb;
+}
+// per-block partials of (S1, S2, S3): [blocks][3] doubles
+int s_partial_count(const vabft_problem* p) {
+    const int rpb = encode_rows_per_block(p);
+    return (p->K + rpb - 1) / rpb;
 }
 
 size_t encode_workspace_bytes(const vabft_problem* p) {
-    size_t bytes = s_partial_bytes(p);
+    size_t bytes = 0;
     if (p->transB) {
         const size_t acc_bytes = p->dtype == VABFT_F64 ? 8 : 4;
         const size_t nsplit = ((size_t)p->N + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
@@ -544,19 +593,26 @@ size_t encode_workspace_bytes(const vabft_problem* p) {
 
 template <typename T, bool W>
 static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, void* d_Be2, void* d_bstat, double* d_S,
-                         void* ws, int32_t* ticket, hipStream_t st) {
+                         double* s_partial, void* ws, int32_t* ticket, hipStream_t st) {
     using acc_t = typename Elem<T>::acc_t;
-    static_assert(ENC_ROWS_WAVES == 16, "s_partial_bytes assumes 16 rows k per block");
     const int vec_ok = aligned16(dB) && ((p->ldb * Elem<T>::bytes) % 16 == 0);
-    double* s_partial = reinterpret_cast<double*>(ws);
-    const int kblocks = (p->K + 15) / 16;
+    const int kblocks = s_partial_count(p);
     if (!p->transB) {
-        encode_rows_kernel<T, W><<<dim3(kblocks), dim3(64 * ENC_ROWS_WAVES), 0, st>>>(
-            dB, p->K, p->N, p->ldb, (acc_t*)d_Be, (acc_t*)d_Be2, (acc_t*)d_bstat, vec_ok, s_partial, ticket, d_S);
+#define VABFT_ENC_ROWS(R)                                                                                       \
+    encode_rows_kernel<T, W, R><<<dim3(kblocks), dim3(64 * ENC_ROWS_WAVES), 0, st>>>(                           \
+        dB, p->K, p->N, p->ldb, (acc_t*)d_Be, (acc_t*)d_Be2, (acc_t*)d_bstat, vec_ok, s_partial, ticket, d_S)
+        switch (encode_rows_per_block(p)) {
+            case 16: VABFT_ENC_ROWS(16); break;
+            case 8: VABFT_ENC_ROWS(8); break;
+            case 4: VABFT_ENC_ROWS(4); break;
+            case 2: VABFT_ENC_ROWS(2); break;
+            default: VABFT_ENC_ROWS(1); break;
+        }
+#undef VABFT_ENC_ROWS
     } else {
         constexpr int V = Elem<T>::vec;
         const int nsplit = (p->N + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
-        acc_t* part = reinterpret_cast<acc_t*>(reinterpret_cast<unsigned char*>(ws) + s_partial_bytes(p));
+        acc_t* part = reinterpret_cast<acc_t*>(ws);
         dim3 grid((p->K + 64 * V - 1) / (64 * V), nsplit);
         encode_cols_kernel<T, W><<<grid, dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, ENC_ROWS_PER_BLOCK, part,
                                                              vec_ok, nullptr);
@@ -567,12 +623,13 @@ static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, voi
 }
 
 // d_Be2 == nullptr: plain encode; otherwise the weighted checksum is produced in the same pass
+// d_S == nullptr: S1..S3 stay as the s_partial_count() per-workgroup partials in s_partial
 // ws: scratch of encode_workspace_bytes(); ticket: one int32 that is zero between launches
 int encode_dispatch(const vabft_problem* p, const void* dB, void* d_Be, void* d_Be2, void* d_bstat, double* d_S,
-                    void* ws, int32_t* ticket, hipStream_t st) {
-#define VABFT_ENC_CASE(T)                                                                    \
-    return d_Be2 ? encode_launch<T, true>(p, dB, d_Be, d_Be2, d_bstat, d_S, ws, ticket, st) \
-                 : encode_launch<T, false>(p, dB, d_Be, nullptr, d_bstat, d_S, ws, ticket, st)
+                    double* s_partial, void* ws, int32_t* ticket, hipStream_t st) {
+#define VABFT_ENC_CASE(T)                                                                               \
+    return d_Be2 ? encode_launch<T, true>(p, dB, d_Be, d_Be2, d_bstat, d_S, s_partial, ws, ticket, st) \
+                 : encode_launch<T, false>(p, dB, d_Be, nullptr, d_bstat, d_S, s_partial, ws, ticket, st)
     switch (p->dtype) {
         case VABFT_F64: VABFT_ENC_CASE(double);
         case VABFT_F32: VABFT_ENC_CASE(float);
@@ -690,10 +747,10 @@ size_t cols_workspace_bytes(const vabft_problem* p) {
 }
 
 // c1 A, column statistics of A and their aggregates: the encode of the N x K layout applied to A (M x K)
-int encode_a_dispatch(const vabft_problem* p, const void* dA, void* d_eA, void* d_acolstat, double* d_SA, void* ws,
-                      int32_t* ticket, hipStream_t st) {
+int encode_a_dispatch(const vabft_problem* p, const void* dA, void* d_eA, void* d_acolstat, double* d_SA,
+                      double* s_partial, void* ws, int32_t* ticket, hipStream_t st) {
     const vabft_problem q = swapped_problem(p, p->M, p->M, 1, p->lda, p->lda);
-    return encode_dispatch(&q, dA, d_eA, nullptr, d_acolstat, d_SA, ws, ticket, st);
+    return encode_dispatch(&q, dA, d_eA, nullptr, d_acolstat, d_SA, s_partial, ws, ticket, st);
 }
 
 template <typename T>

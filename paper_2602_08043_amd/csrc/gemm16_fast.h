@@ -88,7 +88,9 @@ template <> __device__ __forceinline__ float frag_elem<f16_t>(uint32_t d0, uint3
 // 128 floats per folded unit u (k = 128*u - 16 .. 128*u + 111).
 constexpr int BE_CACHE_OFFSET = LDS_BYTES;
 constexpr int BE_CACHE_SLOTS = 16;
-constexpr int LDS_BYTES_FUSED = LDS_BYTES + BE_CACHE_SLOTS * 128 * 4;  // LDS offset of the A-statistics staging area in the epilogue
+// behind the cache: 12 doubles for the fold of the S1..S3 partials of an encode that deferred it
+constexpr int S_RED_OFFSET = LDS_BYTES + BE_CACHE_SLOTS * 128 * 4;
+constexpr int LDS_BYTES_FUSED = S_RED_OFFSET + 128;
 }  // namespace g16f
 
 // Epilogue shared by the whole-tile kernels (16-bit and FP8 inputs; T is the OUTPUT element type): injector,
@@ -208,7 +210,9 @@ __device__ __forceinline__ void gemm16_fast_epilogue(const GemmArgs& g, f32x16_t
                 const double mu = (double)sum / (double)g.K;
                 double var = ((double)mx - mu) * (mu - (double)mn);
                 var = var > 0 ? var : 0;
-                const double S1 = g.S[0], S2 = g.S[1], S3 = g.S[2], dN = (double)g.N;
+                const double* s_red = reinterpret_cast<const double*>(smem + S_RED_OFFSET);
+                const double S1 = g.S ? g.S[0] : folded_s(s_red, 0), S2 = g.S ? g.S[1] : folded_s(s_red, 1),
+                             S3 = g.S ? g.S[2] : folded_s(s_red, 2), dN = (double)g.N;
                 const double t_det = dN * fabs(mu) * S1;
                 const double t_var23 = g.c_sigma * sqrt(dN * mu * mu * S2 + dN * dN * var * S3);
                 const double t_var4 = g.c_sigma * sqrt(dN) * sqrt(var) * sqrt(S2);
@@ -455,6 +459,8 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
                 cache[j * 128 + tid] = (k >= 0 && k < g.K) ? Be[k] : 0.f;
             }
         }
+        // S1..S3 still in partials: every workgroup folds them here, under the latency of its first tile
+        if (!g.S) fold_s_partials_to_lds(g.s_partial, g.s_nparts, tid, reinterpret_cast<double*>(smem + S_RED_OFFSET));
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();

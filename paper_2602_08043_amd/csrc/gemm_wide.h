@@ -53,7 +53,8 @@ template <typename T> constexpr int loop_bytes() { return 2 * stage_elems<T>() *
 template <typename T> constexpr int epi_bytes() { return 4 * 64 * (64 + 16 / (int)sizeof(T)) * (int)sizeof(T); }
 // 16 more bytes behind the larger of the two for the "last workgroup of the tile-row" flag
 template <typename T> constexpr int flag_offset() { return loop_bytes<T>() > epi_bytes<T>() ? loop_bytes<T>() : epi_bytes<T>(); }
-template <typename T> constexpr int lds_bytes() { return flag_offset<T>() + 16; }
+// ... and 12 doubles for the fold of the S1..S3 partials of an encode that deferred it
+template <typename T> constexpr int lds_bytes() { return flag_offset<T>() + 16 + 96; }
 
 // Partials exchanged between workgroups (possibly on different XCDs, each with a private L2) go
 // through device-scope relaxed atomic stores and loads, performed at the device's coherence
@@ -230,6 +231,8 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     const int nk = (g.K + BK - 1) / BK;
     int next_fold = bn;  // FUSED: the next k-tile this tile-column folds into the statistics
     if (FUSED) load_be(0);
+    if (FUSED && !g.S)
+        fold_s_partials_to_lds(g.s_partial, g.s_nparts, tid, reinterpret_cast<double*>(smem_raw + flag_offset<T>() + 16));
     load_tiles(0);
     store_tiles(0);
     if (FUSED && next_fold == 0) {
@@ -474,7 +477,9 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
                         const double mu = (double)sum / (double)g.K;
                         double var = ((double)mx - mu) * (mu - (double)mn);
                         var = var > 0 ? var : 0;
-                        const double S1 = g.S[0], S2 = g.S[1], S3 = g.S[2], dN = (double)g.N;
+                        const double* s_red = reinterpret_cast<const double*>(smem_raw + flag_offset<T>() + 16);
+                        const double S1 = g.S ? g.S[0] : folded_s(s_red, 0), S2 = g.S ? g.S[1] : folded_s(s_red, 1),
+                                     S3 = g.S ? g.S[2] : folded_s(s_red, 2), dN = (double)g.N;
                         const double t_det = dN * fabs(mu) * S1;
                         const double t_var23 = g.c_sigma * sqrt(dN * mu * mu * S2 + dN * dN * var * S3);
                         const double t_var4 = g.c_sigma * sqrt(dN) * sqrt(var) * sqrt(S2);

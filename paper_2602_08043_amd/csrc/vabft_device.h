@@ -93,6 +93,38 @@ template <typename T> __device__ __forceinline__ T wave_min(T v) {
     return v;
 }
 
+// Fold of the per-workgroup partials [count][3] of (S1, S2, S3) (Algorithm 1, k-loop) by the first 256
+// threads of a workgroup, in the order the encode kernels use when they fold them themselves:
+// thread t adds partials t, t + 256, ... in increasing order, a butterfly inside each of the four
+// wavefronts, and (after a workgroup barrier) the four wavefront results in order.
+// s_red: 12 doubles of LDS, [3][4].
+__device__ __forceinline__ void fold_s_partials_to_lds(const double* __restrict__ partial, int count, int t,
+                                                       double* s_red) {
+    if (t < 256) {
+        double a1 = 0, a2 = 0, a3 = 0;
+        for (int b = t; b < count; b += 256) {
+            const double* q = partial + 3 * (int64_t)b;
+            a1 += q[0];
+            a2 += q[1];
+            a3 += q[2];
+        }
+        a1 = wave_sum(a1);
+        a2 = wave_sum(a2);
+        a3 = wave_sum(a3);
+        if ((t & 63) == 0) {
+            s_red[0 * 4 + (t >> 6)] = a1;
+            s_red[1 * 4 + (t >> 6)] = a2;
+            s_red[2 * 4 + (t >> 6)] = a3;
+        }
+    }
+}
+__device__ __forceinline__ double folded_s(const double* s_red, int q) {
+    double v = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) v += s_red[q * 4 + w];
+    return v;
+}
+
 template <typename T> __device__ __forceinline__ T type_max();
 template <> __device__ __forceinline__ float type_max<float>() { return 3.402823466e+38f; }
 template <> __device__ __forceinline__ double type_max<double>() { return 1.7976931348623157e+308; }

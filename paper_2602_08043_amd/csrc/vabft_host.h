@@ -10,16 +10,19 @@ namespace vabft {
 
 // encode.hip
 size_t encode_workspace_bytes(const vabft_problem* p);
-// d_Be2 / d_expected2 may be null (no position-weighted checksum)
+int s_partial_count(const vabft_problem* p);  // per-workgroup partials of S1..S3 an encode leaves: [count][3] double
+// d_Be2 / d_expected2 may be null (no position-weighted checksum); d_S null: S1..S3 stay as partials in s_partial
 int encode_dispatch(const vabft_problem* p, const void* dB, void* d_Be, void* d_Be2, void* d_bstat, double* d_S,
-                    void* ws, int32_t* ticket, hipStream_t st);
+                    double* s_partial, void* ws, int32_t* ticket, hipStream_t st);
+// folds the partials an encode left into S[3] (the same fixed order the encode itself uses)
+void fold_s_launch(const double* s_partial, int count, double* S, hipStream_t st);
 int threshold_dispatch(const vabft_problem* p, const void* dA, const void* d_Be, const void* d_Be2, const double* d_S,
                        double e_max, double c_sigma, void* d_astat, void* d_expected, void* d_expected2, void* d_T,
                        hipStream_t st);
 // column checksums (c1 A, per-column thresholds)
 size_t cols_workspace_bytes(const vabft_problem* p);
-int encode_a_dispatch(const vabft_problem* p, const void* dA, void* d_eA, void* d_acolstat, double* d_SA, void* ws,
-                      int32_t* ticket, hipStream_t st);
+int encode_a_dispatch(const vabft_problem* p, const void* dA, void* d_eA, void* d_acolstat, double* d_SA,
+                      double* s_partial, void* ws, int32_t* ticket, hipStream_t st);
 int threshold_cols_dispatch(const vabft_problem* p, const void* dB, const void* d_eA, const double* d_SA, double e_max,
                             double c_sigma, void* d_bcolstat, void* d_expected_col, void* d_Tcol, void* ws,
                             hipStream_t st);
@@ -73,7 +76,9 @@ struct GemmArgs {
     // fused A-side statistics (Algorithm 1 for the rows of A, inside the GEMM)
     int32_t fused_stats;
     const void* Be;   // [K] acc
-    const double* S;  // [3]
+    const double* S;  // [3]; null: fold s_partial[s_nparts][3] (left by an encode with a deferred fold)
+    const double* s_partial;
+    int32_t s_nparts;
     double e_max, c_sigma;
     void* astat;      // [M][3] acc, output
     void* apart;      // [tiles_n][4][M] acc: per-K-slice (sum, dot, max, min) of the rows of A (fused_stats)
@@ -91,7 +96,7 @@ struct GemmArgs {
 size_t gemm_workspace_bytes(const vabft_problem* p);
 struct FusedArgs {  // non-null d_Be selects the fused A-side path
     const void* d_Be;
-    const double* d_S;
+    const double* d_S;  // null: S1..S3 are still the partials of the preceding encode
     double e_max, c_sigma;
     void* d_astat;
 };

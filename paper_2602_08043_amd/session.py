@@ -96,9 +96,11 @@ class VerifiedGemm:
     def _stream():
         return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
-    def encode(self, B: torch.Tensor):
+    def encode(self, B: torch.Tensor, defer_S: bool = False):
+        """defer_S: leave S1..S3 as partials in the workspace for gemm_fused(..., deferred_S=True)."""
         return vb.vabft_encode(self.problem, B.data_ptr(), self.Be.data_ptr(), self.bstat.data_ptr(),
-                               self.S.data_ptr(), self.ws.data_ptr(), self.ws_bytes, self._stream())
+                               None if defer_S else self.S.data_ptr(), self.ws.data_ptr(), self.ws_bytes,
+                               self._stream())
 
     def threshold(self, A: torch.Tensor, e_max=None, c_sigma=2.5):
         if e_max is None:
@@ -128,14 +130,16 @@ class VerifiedGemm:
                                       self.nflag.data_ptr(), self.injlog.data_ptr(), self.ninj.data_ptr(),
                                       self.ws.data_ptr(), self.ws_bytes, self._stream())
 
-    def gemm_fused(self, A: torch.Tensor, B: torch.Tensor, e_max=None, c_sigma=2.5, inj: vb.Inject | None = None):
-        """A-side pass, GEMM and check in one call (needs encode(B) first)."""
+    def gemm_fused(self, A: torch.Tensor, B: torch.Tensor, e_max=None, c_sigma=2.5, inj: vb.Inject | None = None,
+                   deferred_S: bool = False):
+        """A-side pass, GEMM and check in one call (needs encode(B) first; deferred_S after encode(B, defer_S=True))."""
         if e_max is None:
             e_max = vb.vabft_default_emax(self.dtype, self.K, self.N)
         self.e_max = e_max
         return vb.vabft_gemm_verified_fused(self.problem, A.data_ptr(), B.data_ptr(), self.C.data_ptr(),
-                                            self.Be.data_ptr(), self.S.data_ptr(), e_max, c_sigma,
-                                            self.astat.data_ptr(), self.expected.data_ptr(), self.T.data_ptr(), inj,
+                                            self.Be.data_ptr(), None if deferred_S else self.S.data_ptr(), e_max,
+                                            c_sigma, self.astat.data_ptr(), self.expected.data_ptr(),
+                                            self.T.data_ptr(), inj,
                                             self.rowsum.data_ptr(), self.E.data_ptr(), self.flags.data_ptr(),
                                             self.nflag.data_ptr(), self.injlog.data_ptr(), self.ninj.data_ptr(),
                                             self.ws.data_ptr(), self.ws_bytes, self._stream())
@@ -146,10 +150,11 @@ class VerifiedGemm:
         self.threshold(A, e_max, c_sigma)
         self.gemm(A, B, 1, inj)
 
-    def run_fused(self, A, B, e_max=None, c_sigma=2.5, inj=None):
-        """One pass of the whole path in two calls: encode, fused threshold + verified GEMM."""
-        self.encode(B)
-        self.gemm_fused(A, B, e_max, c_sigma, inj)
+    def run_fused(self, A, B, e_max=None, c_sigma=2.5, inj=None, defer_S: bool = False):
+        """One pass of the whole path in two calls: encode, fused threshold + verified GEMM.
+        defer_S: S1..S3 travel as partials through the workspace and are folded inside the second call."""
+        self.encode(B, defer_S)
+        self.gemm_fused(A, B, e_max, c_sigma, inj, deferred_S=defer_S)
 
     # ---- weighted checksum, localisation, correction ---------------------------------
     def encode_weighted(self, B: torch.Tensor):

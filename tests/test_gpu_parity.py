@@ -465,3 +465,47 @@ def test_nan_and_inf_inputs_flag_their_rows(dtype, M, N, K, transB):
     vg.run_fused(_dev(A, dtype), _dev(Bn, dtype))
     r = vg.results()
     assert r["nflag"] == M and r["flags"].all()
+
+
+DEFERRED = [
+    # single-launch kernels (the GEMM folds the partials in its prologue), both layouts of B
+    ("bf16", 512, 512, 256, 0), ("f16", 768, 512, 128, 1), ("bf16", 256, 512, 1152, 0), ("f32", 384, 512, 272, 1),
+    ("f32", 128, 128, 16, 0), ("f64", 256, 384, 128, 0), ("f64", 128, 640, 48, 1),
+    # K over 4096: more partials than folding threads
+    ("bf16", 256, 512, 4352, 0),
+    # the passes back to back (a small kernel folds the partials first)
+    ("bf16", 300, 520, 200, 1), ("f16", 100, 99, 50, 0), ("f32", 200, 260, 70, 0), ("f64", 131, 67, 33, 1),
+]
+
+
+@pytest.mark.parametrize("dtype,M,N,K,transB", DEFERRED)
+def test_deferred_fold_of_S_gives_the_same_bits(dtype, M, N, K, transB):
+    """vabft_encode(d_S = NULL) + vabft_gemm_verified_fused(d_S = NULL): S1..S3 travel as per-workgroup partials and
+    are folded by the consumer in the encode's own order, so thresholds, flags and everything else must equal the
+    ordinary route bit for bit (Algorithm 1: S1, S2, S3 are plain sums over k)."""
+    for seed, dist in ((21, "n_1e-6_1"), (22, "u_-1_1")):
+        A, B = _gen(dtype, M, N, K, transB, seed, dist)
+        dA, dB = _dev(A, dtype), _dev(B, dtype)
+        vg = _session(M, N, K, dtype, transB)
+        vg.run_fused(dA, dB)
+        r0 = {k: np.copy(v) for k, v in vg.results().items()}
+        o = orc.verify(A, B, dtype, transB, e_max=_emax(dtype, K, N))
+        check_light(r0, o, dtype, M, N, K)
+        for rep in range(2):
+            vg.S.fill_(float("nan"))  # the deferred route must not read it
+            vg.T.fill_(-1.0)
+            vg.expected.fill_(0.0)
+            vg.flags.fill_(7)
+            vg.run_fused(dA, dB, defer_S=True)
+            r = vg.results()
+            for key in ("T", "expected", "rowsum", "E", "flags", "astat", "C", "Be", "bstat"):
+                assert np.array_equal(r[key], r0[key]), (key, rep)
+            assert r["nflag"] == r0["nflag"] == 0
+            assert np.isnan(r["S"]).all()
+    # a fault through the deferred route
+    i, j = M // 3, N // 2
+    bit = 61 if dtype == "f64" else 29
+    inj = vg.make_inject(mode=1, faults=[(i, j, bit)])
+    vg.run_fused(dA, dB, inj=inj, defer_S=True)
+    r = vg.results()
+    assert r["flags"][i] == 1 and r["nflag"] == 1 and r["flags"].sum() == 1
