@@ -47,6 +47,66 @@ __global__ __launch_bounds__(256) void encode_blocks_rows_kernel(const void* __r
     }
 }
 
+// B stored K x N, rows 16-byte aligned, N a multiple of the chunk width: one wavefront per row k, 16-byte loads.
+// A block of W columns is W / V chunks = 16 or 32 consecutive lanes of one load, so each lane folds its chunk
+// and a butterfly over those lanes finishes the block; four loads are in flight per lane.
+template <typename T>
+__global__ __launch_bounds__(256) void encode_blocks_rows_vec_kernel(const void* __restrict__ B, int K, int N,
+                                                                     int64_t ldb, int W,
+                                                                     typename Elem<T>::acc_t* __restrict__ part) {
+    using acc_t = typename Elem<T>::acc_t;
+    constexpr int V = Elem<T>::vec;
+    const int lane = threadIdx.x & 63;
+    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (k >= K) return;
+    const int cpb = W / V;  // chunks (lanes) per block: 16 or 32
+    const int nchunks = N / V;
+    const char* row = reinterpret_cast<const char*>(B) + (int64_t)k * ldb * Elem<T>::bytes;
+    for (int c0 = 0; c0 < nchunks; c0 += 256) {
+        raw16 r[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + 64 * u + lane;
+            r[u] = ld16(row + (int64_t)(c < nchunks ? c : nchunks - 1) * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + 64 * u + lane;
+            const bool ok = c < nchunks;
+            acc_t v[V];
+            Unpack<T>::run(r[u], v);
+            acc_t sum = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
+            if (ok) {
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    sum += v[e];
+                    mx = v[e] > mx ? v[e] : mx;
+                    mn = v[e] < mn ? v[e] : mn;
+                }
+            }
+            if (cpb == 32) {
+                sum += __shfl_xor(sum, 16, WAVE);
+                const acc_t a = __shfl_xor(mx, 16, WAVE), b = __shfl_xor(mn, 16, WAVE);
+                mx = a > mx ? a : mx;
+                mn = b < mn ? b : mn;
+            }
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) {
+                sum += __shfl_xor(sum, off, WAVE);
+                const acc_t a = __shfl_xor(mx, off, WAVE), b = __shfl_xor(mn, off, WAVE);
+                mx = a > mx ? a : mx;
+                mn = b < mn ? b : mn;
+            }
+            if (ok && lane % cpb == 0) {
+                acc_t* q = part + (int64_t)(c / cpb) * 3 * K;
+                q[k] = sum;
+                q[(int64_t)K + k] = mx;
+                q[2 * (int64_t)K + k] = mn;
+            }
+        }
+    }
+}
+
 // B stored N x K: one thread per (k, block) walks the block's rows n (consecutive threads read consecutive k)
 template <typename T>
 __global__ __launch_bounds__(256) void encode_blocks_cols_kernel(const void* __restrict__ Bt, int K, int N,
@@ -240,49 +300,222 @@ __global__ __launch_bounds__(256) void threshold_blocks_kernel(const void* __res
     }
 }
 
+// The same pass for 16-byte aligned rows of A with K a multiple of the chunk width: a lane takes CH 16-byte
+// chunks (V consecutive k each) of each of the wavefront's R rows per step, a workgroup 4 R rows, and K is walked
+// in steps of KC = 64 V CH.  The Be_t slices of a step sit in LDS as [block][chunk][piece][lane][16 bytes], so that
+// the 16-byte reads of a wavefront are contiguous, and every slice read serves R rows.  The chunks of A and the
+// slice values of the next step are fetched into registers before the current step is multiplied.
+template <typename T, int R>
+__global__ __launch_bounds__(256) void threshold_blocks_vec_kernel(const void* __restrict__ A, int M, int K, int N,
+                                                                   int W, int64_t lda,
+                                                                   const typename Elem<T>::acc_t* __restrict__ Be_blk,
+                                                                   const double* __restrict__ S_blk, double e_max,
+                                                                   double c_sigma,
+                                                                   typename Elem<T>::acc_t* __restrict__ astat,
+                                                                   typename Elem<T>::acc_t* __restrict__ expected_blk,
+                                                                   typename Elem<T>::acc_t* __restrict__ T_blk) {
+    using acc_t = typename Elem<T>::acc_t;
+    constexpr int V = Elem<T>::vec;                   // elements per 16-byte chunk of A
+    constexpr int E = 16 / (int)sizeof(acc_t);        // accumulator-typed values per 16 bytes of LDS
+    constexpr int P = V / E;                          // 16-byte pieces of a slice per chunk
+    constexpr int CH = V >= 8 ? 1 : 8 / V;            // chunks per lane and step
+    constexpr int KC = 64 * V * CH;                   // k per step: 512 (1024 for 1-byte elements)
+    constexpr int TT = 32768 / (KC * (int)sizeof(acc_t));  // blocks per pass: 32 KiB of slices
+    constexpr int NJ = KC / 256;
+    static_assert(R * TT <= 64, "one lane per (row, block) pair at the end");
+    struct alignas(16) piece_t { acc_t v[E]; };
+    __shared__ piece_t be[TT][CH][P][64];
+    __shared__ acc_t rstat[4 * R][3];  // (sum, max, min) of the rows, from the first pass
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nblocks = (N + W - 1) / W;
+    const int r0 = blockIdx.x * 4 * R + wave * R;  // the wavefront's first row
+    const char* rowp[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int row = r0 + r < M ? r0 + r : M - 1;  // clamped; results of rows past M are not written
+        rowp[r] = reinterpret_cast<const char*>(A) + (int64_t)row * lda * Elem<T>::bytes;
+    }
+    for (int t0 = 0; t0 < nblocks; t0 += TT) {
+        const int nt = min(TT, nblocks - t0);
+        acc_t dot[R][TT];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int t = 0; t < TT; ++t) dot[r][t] = 0;
+        acc_t sum[R], mx[R], mn[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            sum[r] = 0;
+            mx[r] = -type_max<acc_t>();
+            mn[r] = type_max<acc_t>();
+        }
+        raw16 araw[R][CH];
+        acc_t stage[TT][NJ];
+        // thread tid fetches elements kk = tid + 256 j of every block's slice, lane l chunk c of every row
+        auto prefetch = [&](int kc) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    const int k0 = kc + (c * 64 + lane) * V;
+                    araw[r][c] = ld16(rowp[r] + (int64_t)(k0 < K ? k0 : 0) * Elem<T>::bytes);  // masked below
+                }
+#pragma unroll
+            for (int t = 0; t < TT; ++t)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    const int tc = t < nt ? t : nt - 1, kq = kc + tid + 256 * j;  // clamped, masked below
+                    stage[t][j] = Be_blk[(int64_t)(t0 + tc) * K + (kq < K ? kq : K - 1)];
+                }
+        };
+        prefetch(0);
+        for (int kc = 0; kc < K; kc += KC) {
+            __syncthreads();  // the previous step's slices are no longer read
+#pragma unroll
+            for (int t = 0; t < TT; ++t)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    const int kk = tid + 256 * j;
+                    const int c = kk / (64 * V), l = (kk / V) % 64, w = kk % V;
+                    be[t][c][w / E][l].v[w % E] = (t < nt && kc + kk < K) ? stage[t][j] : (acc_t)0;
+                }
+            acc_t av[R][CH][V];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < CH; ++c) Unpack<T>::run(araw[r][c], av[r][c]);
+            __syncthreads();
+            if (kc + KC < K) prefetch(kc + KC);
+            if (t0 == 0) {
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    if (kc + (c * 64 + lane) * V < K) {
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int e = 0; e < V; ++e) {
+                                sum[r] += av[r][c][e];
+                                mx[r] = av[r][c][e] > mx[r] ? av[r][c][e] : mx[r];
+                                mn[r] = av[r][c][e] < mn[r] ? av[r][c][e] : mn[r];
+                            }
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < TT; ++t)
+#pragma unroll
+                for (int c = 0; c < CH; ++c)
+#pragma unroll
+                    for (int pc = 0; pc < P; ++pc) {
+                        const piece_t b = be[t][c][pc][lane];
+#pragma unroll
+                        for (int e = 0; e < E; ++e)
+#pragma unroll
+                            for (int r = 0; r < R; ++r) dot[r][t] = fma(av[r][c][pc * E + e], b.v[e], dot[r][t]);
+                    }
+        }
+        if (t0 == 0) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const acc_t s = wave_sum(sum[r]), hi = wave_max(mx[r]), lo = wave_min(mn[r]);
+                if (lane == 0) {
+                    rstat[wave * R + r][0] = s;
+                    rstat[wave * R + r][1] = hi;
+                    rstat[wave * R + r][2] = lo;
+                    if (r0 + r < M) {
+                        astat[3 * (int64_t)(r0 + r) + 0] = hi;
+                        astat[3 * (int64_t)(r0 + r) + 1] = lo;
+                        astat[3 * (int64_t)(r0 + r) + 2] = (acc_t)((double)s / (double)K);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int t = 0; t < TT; ++t) dot[r][t] = wave_sum(dot[r][t]);
+        // lane r * TT + t writes one (row, block) pair; rstat was written by this wavefront's own lane 0
+        {
+            const int r = lane / TT, t = lane % TT;
+            acc_t d = 0;
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr)
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+                    if (rr == r && tt == t) d = dot[rr][tt];
+            const int row = r0 + r;
+            if (r < R && t < nt && row < M) {
+                const int tb = t0 + t;
+                const int width = min(N, (tb + 1) * W) - tb * W;
+                const double mu = (double)rstat[wave * R + r][0] / (double)K;
+                double var = ((double)rstat[wave * R + r][1] - mu) * (mu - (double)rstat[wave * R + r][2]);
+                var = var > 0 ? var : 0;
+                const double S1 = S_blk[3 * tb], S2 = S_blk[3 * tb + 1], S3 = S_blk[3 * tb + 2], dN = (double)width;
+                const double t_det = dN * fabs(mu) * S1;
+                const double t_var23 = c_sigma * sqrt(dN * mu * mu * S2 + dN * dN * var * S3);
+                const double t_var4 = c_sigma * sqrt(dN) * sqrt(var) * sqrt(S2);
+                expected_blk[(int64_t)tb * M + row] = d;
+                T_blk[(int64_t)tb * M + row] = (acc_t)(e_max * (t_det + t_var23 + t_var4));
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // compare per block and aggregate per row.  rowpart holds `sub` partials per block (1 for the 256-wide
 // kernels, whose workgroup sums a whole block; the wide kernels leave the block's value directly too)
 // ---------------------------------------------------------------------------
 template <typename acc_t>
-__global__ __launch_bounds__(256) void finalize_blocks_kernel(const acc_t* __restrict__ rowpart, int nblocks, int M,
-                                                              const acc_t* __restrict__ expected_blk,
-                                                              const acc_t* __restrict__ T_blk,
-                                                              acc_t* __restrict__ rowsum_blk, acc_t* __restrict__ E_blk,
-                                                              int32_t* __restrict__ blockflags,
-                                                              acc_t* __restrict__ E, int32_t* __restrict__ flags,
-                                                              int32_t* __restrict__ nflag,
-                                                              int32_t* __restrict__ nblockflag) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
+__global__ __launch_bounds__(64) void finalize_blocks_kernel(const acc_t* __restrict__ rowpart, int nblocks, int M,
+                                                             const acc_t* __restrict__ expected_blk,
+                                                             const acc_t* __restrict__ T_blk,
+                                                             acc_t* __restrict__ rowsum_blk, acc_t* __restrict__ E_blk,
+                                                             int32_t* __restrict__ blockflags,
+                                                             acc_t* __restrict__ E, int32_t* __restrict__ flags,
+                                                             int32_t* __restrict__ nflag,
+                                                             int32_t* __restrict__ nblockflag) {
+    // one wavefront per 64 rows (many small workgroups: the pass is a few dependent round trips long), the
+    // loads of eight blocks in flight at once, blocks folded in order
+    const int i = blockIdx.x * 64 + threadIdx.x;
     int any = 0, nb = 0;
     if (i < M) {
         acc_t esum = 0;
-        for (int t = 0; t < nblocks; ++t) {
-            const int64_t idx = (int64_t)t * M + i;
-            const acc_t s = rowpart[idx];
-            const acc_t e = expected_blk[idx] - s;
-            const int f = !(fabs(e) <= T_blk[idx]);
-            rowsum_blk[idx] = s;
-            E_blk[idx] = e;
-            blockflags[idx] = f;
-            esum += e;
-            nb += f;
+        for (int t0 = 0; t0 < nblocks; t0 += 8) {
+            acc_t s[8], x[8], thr[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t idx = (int64_t)(t0 + u < nblocks ? t0 + u : nblocks - 1) * M + i;
+                s[u] = rowpart[idx];
+                x[u] = expected_blk[idx];
+                thr[u] = T_blk[idx];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (t0 + u < nblocks) {
+                    const int64_t idx = (int64_t)(t0 + u) * M + i;
+                    const acc_t e = x[u] - s[u];
+                    const int f = !(fabs(e) <= thr[u]);
+                    rowsum_blk[idx] = s[u];
+                    E_blk[idx] = e;
+                    blockflags[idx] = f;
+                    esum += e;
+                    nb += f;
+                }
+            }
         }
         any = nb > 0;
         E[i] = esum;
         flags[i] = any;
     }
-    const int cnt = __syncthreads_count(any);
-    __shared__ int s_nb[4];
-    int w = nb;
+    int cnt = any, w = nb;
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) w += __shfl_xor(w, off, WAVE);
-    if ((threadIdx.x & 63) == 0) s_nb[threadIdx.x >> 6] = w;
-    __syncthreads();
+    for (int off = 32; off >= 1; off >>= 1) {
+        cnt += __shfl_xor(cnt, off, WAVE);
+        w += __shfl_xor(w, off, WAVE);
+    }
     if (threadIdx.x == 0) {
         if (cnt) atomicAdd(nflag, cnt);
-        const int tot = s_nb[0] + s_nb[1] + s_nb[2] + s_nb[3];
-        if (tot) atomicAdd(nblockflag, tot);
+        if (w) atomicAdd(nblockflag, w);
     }
 }
 
@@ -303,7 +536,12 @@ static int encode_blocks_launch(const vabft_problem* p, const void* dB, void* d_
     using acc_t = typename Elem<T>::acc_t;
     const int W = block_width(p->dtype), nblocks = (p->N + W - 1) / W;
     acc_t* part = reinterpret_cast<acc_t*>(ws);
-    if (!p->transB)
+    constexpr int V = Elem<T>::vec;
+    const bool vec = aligned16(dB) && (p->ldb * Elem<T>::bytes) % 16 == 0 && p->N % V == 0 && W % V == 0 &&
+                     (W / V == 16 || W / V == 32);
+    if (!p->transB && vec)
+        encode_blocks_rows_vec_kernel<T><<<dim3((p->K + 3) / 4), dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, W, part);
+    else if (!p->transB)
         encode_blocks_rows_kernel<T><<<dim3((p->K + 3) / 4), dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, W, part);
     else
         encode_blocks_cols_kernel<T><<<dim3((p->K + 255) / 256, nblocks), dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, W,
@@ -329,9 +567,15 @@ static int threshold_blocks_launch(const vabft_problem* p, const void* dA, const
                                    double e_max, double c_sigma, void* d_astat, void* d_expected_blk, void* d_T_blk,
                                    hipStream_t st) {
     using acc_t = typename Elem<T>::acc_t;
-    threshold_blocks_kernel<T><<<dim3((p->M + TB_ROWS - 1) / TB_ROWS), dim3(256), 0, st>>>(
-        dA, p->M, p->K, p->N, block_width(p->dtype), p->lda, (const acc_t*)d_Be_blk, d_S_blk, e_max, c_sigma,
-        (acc_t*)d_astat, (acc_t*)d_expected_blk, (acc_t*)d_T_blk);
+    constexpr int V = Elem<T>::vec, R = 2;
+    if (aligned16(dA) && (p->lda * Elem<T>::bytes) % 16 == 0 && p->K % V == 0)
+        threshold_blocks_vec_kernel<T, R><<<dim3((p->M + 4 * R - 1) / (4 * R)), dim3(256), 0, st>>>(
+            dA, p->M, p->K, p->N, block_width(p->dtype), p->lda, (const acc_t*)d_Be_blk, d_S_blk, e_max, c_sigma,
+            (acc_t*)d_astat, (acc_t*)d_expected_blk, (acc_t*)d_T_blk);
+    else
+        threshold_blocks_kernel<T><<<dim3((p->M + TB_ROWS - 1) / TB_ROWS), dim3(256), 0, st>>>(
+            dA, p->M, p->K, p->N, block_width(p->dtype), p->lda, (const acc_t*)d_Be_blk, d_S_blk, e_max, c_sigma,
+            (acc_t*)d_astat, (acc_t*)d_expected_blk, (acc_t*)d_T_blk);
     return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
 }
 
@@ -356,7 +600,7 @@ int finalize_blocks_dispatch(const vabft_problem* p, const void* rowpart, const 
                              int32_t* d_flags, int32_t* d_nflag, int32_t* d_nblockflag, hipStream_t st) {
     const int W = block_width(p->dtype), nblocks = (p->N + W - 1) / W;
     // d_nflag and d_nblockflag were zeroed by the GEMM kernel that produced the partials
-    const dim3 grid((p->M + 255) / 256), block(256);
+    const dim3 grid((p->M + 63) / 64), block(64);
     if (p->dtype == VABFT_F64)
         finalize_blocks_kernel<double><<<grid, block, 0, st>>>(
             (const double*)rowpart, nblocks, p->M, (const double*)d_expected_blk, (const double*)d_T_blk,
