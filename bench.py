@@ -28,7 +28,7 @@ ELEM_BYTES = {"bf16": 2, "f16": 2, "f8": 1, "f32": 4, "f64": 8}
 # HBM-side bytes per launch of the verified GEMM kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by the same counters on 1 GiB device copies (profiles/gemm16_fast_bf16_c2_4096_hbm_traffic.md).
 # A counter figure cannot be taken live inside this script; workloads without a profile report null.
-PROFILED_TRAFFIC_BYTES = {"c2_bf16_4096": (2.0 * 99869 + 1.0 * 34954) * 1024}
+PROFILED_TRAFFIC_BYTES = {"c2_bf16_4096": (2.0 * 99887 + 1.0 * 35209) * 1024}
 
 WORKLOAD_TEXT = {
     "c1_f32_256": "FP32 GEMM M=N=K=256, A,B ~ N(0,1), row-checksum V-ABFT check",
