@@ -509,3 +509,57 @@ def test_deferred_fold_of_S_gives_the_same_bits(dtype, M, N, K, transB):
     vg.run_fused(dA, dB, inj=inj, defer_S=True)
     r = vg.results()
     assert r["flags"][i] == 1 and r["nflag"] == 1 and r["flags"].sum() == 1
+
+
+def _random_shapes():
+    """Seeded shapes: a mix of whole-tile problems (the single-launch kernels) and ragged ones (the guarded kernels
+    and the passes of their own), both layouts of B, every floating-point type of the paper's table."""
+    g = np.random.default_rng(20260208)
+    cases = []
+    for dtype, tile, kstep in (("bf16", 256, 128), ("f16", 256, 128), ("f32", 128, 16), ("f64", 128, 16)):
+        for whole in (True, True, False, False, False):
+            if whole:
+                M, N = tile * int(g.integers(1, 4)), tile * int(g.integers(1, 4))
+                K = kstep * int(g.integers(1, 6))
+            else:
+                M, N, K = (int(g.integers(1, 420)) for _ in range(3))
+            cases.append((dtype, M, N, K, int(g.integers(0, 2)), int(g.integers(0, 1 << 30))))
+    return cases
+
+
+@pytest.mark.parametrize("dtype,M,N,K,transB,seed", _random_shapes())
+def test_random_shapes_every_main_route(dtype, M, N, K, transB, seed):
+    """The three-call route, the fused call and the fused call with the deferred fold against the oracle on seeded
+    random shapes, a planted exponent flip through each, and clean counters afterwards."""
+    print(f"random case {dtype} {M}x{N}x{K} transB={transB} seed={seed}", flush=True)
+    A, B = _gen(dtype, M, N, K, transB, seed, "n_1_1" if seed & 1 else "n_1e-6_1")
+    dA, dB = _dev(A, dtype), _dev(B, dtype)
+    vg = _session(M, N, K, dtype, transB)
+    o = orc.verify(A, B, dtype, transB, e_max=_emax(dtype, K, N))
+    assert not o["flags"].any()
+    i, j = (seed >> 3) % M, (seed >> 11) % N
+    bit = 62 if dtype == "f64" else 30
+    routes = (lambda inj=None: vg.run(dA, dB, inj=inj), lambda inj=None: vg.run_fused(dA, dB, inj=inj),
+              lambda inj=None: vg.run_fused(dA, dB, inj=inj, defer_S=True))
+    for route in routes:
+        vg.T.fill_(-1.0)
+        vg.flags.fill_(3)
+        route()
+        r = vg.results()
+        if route is not routes[2]:
+            check_light(r, o, dtype, M, N, K)
+        else:
+            assert np.all(np.abs(r["T"] - o["T"]) <= max(_tol(dtype), 2e-7 if dtype != "f64" else 0) * o["T"] + 1e-300)
+        check_rows(r, o, dtype)
+        check_C(r, o, A, B, dtype, transB)
+        assert not r["flags"].any() and r["nflag"] == 0
+        assert np.all(np.abs(r["E"]) <= r["T"])
+        route(vg.make_inject(mode=1, faults=[(i, j, bit)]))
+        rf = vg.results()
+        n, recs = vg.inject_records()
+        assert n == 1 and recs[0][:3] == (i, j, bit)
+        before, after = recs[0][3], recs[0][4]
+        if abs(after - before) > 4 * o["T"][i]:  # a flip of a tiny value can stay under the threshold
+            assert rf["flags"][i] == 1 and rf["nflag"] == 1 and rf["flags"].sum() == 1
+        route()
+        assert vg.results()["nflag"] == 0
