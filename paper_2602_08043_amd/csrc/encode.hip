@@ -234,7 +234,7 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
                                                           const typename Elem<T>::acc_t* __restrict__ wvec) {
     using acc_t = typename Elem<T>::acc_t;
     constexpr int V = Elem<T>::vec;
-    __shared__ acc_t red[3][W ? 4 : 3][64 * V];  // waves 1..3 park their partials here
+    __shared__ acc_t red[3][W ? 4 : 3][65 * V];  // waves 1..3 park their partials here, [e][lane] with pitch 65
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int k0 = (blockIdx.x * 64 + lane) * V;
     const int n_begin = blockIdx.y * rows_per_block;
@@ -296,13 +296,16 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
             }
         }
     }
+    // LDS layout [e][lane] with a pitch of 65: conflict free both for a wavefront writing one e at a time and for
+    // consecutive threads reading consecutive columns (lane * V + e) afterwards
+    constexpr int PITCH = 65;
     if (wave > 0) {
 #pragma unroll
         for (int e = 0; e < V; ++e) {
-            red[wave - 1][0][lane * V + e] = sum[e];
-            red[wave - 1][1][lane * V + e] = mx[e];
-            red[wave - 1][2][lane * V + e] = mn[e];
-            if constexpr (W) red[wave - 1][3][lane * V + e] = sum2[e];
+            red[wave - 1][0][e * PITCH + lane] = sum[e];
+            red[wave - 1][1][e * PITCH + lane] = mx[e];
+            red[wave - 1][2][e * PITCH + lane] = mn[e];
+            if constexpr (W) red[wave - 1][3][e * PITCH + lane] = sum2[e];
         }
     }
     __syncthreads();
@@ -311,20 +314,35 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
         for (int w = 0; w < 3; ++w)
 #pragma unroll
             for (int e = 0; e < V; ++e) {
-                sum[e] += red[w][0][lane * V + e];
-                acc_t a = red[w][1][lane * V + e], b = red[w][2][lane * V + e];
+                sum[e] += red[w][0][e * PITCH + lane];
+                acc_t a = red[w][1][e * PITCH + lane], b = red[w][2][e * PITCH + lane];
                 mx[e] = a > mx[e] ? a : mx[e];
                 mn[e] = b < mn[e] ? b : mn[e];
-                if constexpr (W) sum2[e] += red[w][3][lane * V + e];
+                if constexpr (W) sum2[e] += red[w][3][e * PITCH + lane];
             }
-        acc_t* p = part + (int64_t)blockIdx.y * 4 * K;
+        // the block's results go back through the first area so that the global stores are contiguous
+        // (LDS operations of one wavefront complete in order: the reads above are done)
 #pragma unroll
         for (int e = 0; e < V; ++e) {
-            if (k0 + e < K) {
-                p[k0 + e] = sum[e];
-                p[(int64_t)K + k0 + e] = mx[e];
-                p[2 * (int64_t)K + k0 + e] = mn[e];
-                if constexpr (W) p[3 * (int64_t)K + k0 + e] = sum2[e];
+            red[0][0][e * PITCH + lane] = sum[e];
+            red[0][1][e * PITCH + lane] = mx[e];
+            red[0][2][e * PITCH + lane] = mn[e];
+            if constexpr (W) red[0][3][e * PITCH + lane] = sum2[e];
+        }
+    }
+    __syncthreads();
+    {
+        acc_t* p = part + (int64_t)blockIdx.y * 4 * K;
+        const int kbase = blockIdx.x * 64 * V;
+#pragma unroll
+        for (int j = 0; j < (64 * V + 255) / 256; ++j) {
+            const int idx = threadIdx.x + 256 * j;  // column kbase + idx = lane idx / V, element idx % V
+            if (idx < 64 * V && kbase + idx < K) {
+                const int at = (idx % V) * PITCH + idx / V;
+                p[kbase + idx] = red[0][0][at];
+                p[(int64_t)K + kbase + idx] = red[0][1][at];
+                p[2 * (int64_t)K + kbase + idx] = red[0][2][at];
+                if constexpr (W) p[3 * (int64_t)K + kbase + idx] = red[0][3][at];
             }
         }
     }
