@@ -26,18 +26,23 @@ def test_graph_replay_matches_eager(dtype, M, N, K, transB):
             "colflags")
 
     def whole_path():
+        vg.encode(dB, defer_S=True)                # S1..S3 left as partials, folded inside the fused call
+        vg.gemm_fused(dA, dB, deferred_S=True)
+        t_deferred = vg.T.clone()
         vg.encode(dB)
         vg.gemm_fused(dA, dB)                      # fault-free fused call
+        t_plain = vg.T.clone()
         c_clean = vg.C.clone()
         vg.run_weighted(dA, dB, inj=inj, correct=1)  # weighted route with the planted fault, corrected
         vg.encode_a(dA)
         vg.threshold_cols(dB)
         vg.gemm_rc(dA, dB, inj)                    # row + column check with the fault
-        return c_clean
+        return c_clean, t_deferred, t_plain
 
     # eager reference
-    c_ref = whole_path()
+    c_ref, t_ref, t_plain_ref = whole_path()
     torch.cuda.synchronize()
+    assert torch.equal(t_ref, t_plain_ref)  # the deferred fold gives the same thresholds bit for bit
     ref = {k: getattr(vg, k).clone() for k in keys}
     ref["C"] = vg.C.clone()
     ref["nflag"], ref["ncolflag"], ref["ncorrected"] = (int(vg.nflag.item()), int(vg.ncolflag.item()),
@@ -52,7 +57,7 @@ def test_graph_replay_matches_eager(dtype, M, N, K, transB):
     torch.cuda.current_stream().wait_stream(s)
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
-        c_graph = whole_path()
+        c_graph, t_graph, t_plain_graph = whole_path()
 
     for replay in range(4):
         # other work between replays: different inputs through the same session (same workspace, same outputs)
@@ -64,6 +69,6 @@ def test_graph_replay_matches_eager(dtype, M, N, K, transB):
         torch.cuda.synchronize()
         for k in keys:
             assert torch.equal(getattr(vg, k), ref[k]), (replay, k)
-        assert torch.equal(vg.C, ref["C"]) and torch.equal(c_graph, c_ref)
+        assert torch.equal(vg.C, ref["C"]) and torch.equal(c_graph, c_ref) and torch.equal(t_graph, t_ref) and torch.equal(t_plain_graph, t_ref)
         assert int(vg.nflag.item()) == ref["nflag"] and int(vg.ncolflag.item()) == ref["ncolflag"]
         assert int(vg.ncorrected.item()) == ref["ncorrected"]
