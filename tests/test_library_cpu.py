@@ -70,3 +70,21 @@ def test_rejects_bad_arguments_without_a_gpu(lib):
     assert vb.vabft_encode(p, 18, 16, 16, 16, None, 0, None, check=False) == vb.VABFT_EINVAL
     with pytest.raises(vb.VabftError):
         vb.vabft_encode(p, None, None, None, None, None, 0, None)
+
+
+def test_deferred_fold_arguments_without_a_gpu(lib):
+    """d_S may be NULL for vabft_encode and vabft_gemm_verified_fused (the fold of S1..S3 deferred to the fused
+    call): the argument checks then go on to the workspace, which is what these calls lack."""
+    p = vb.make_problem(256, 256, 256, "f32")
+    assert vb.vabft_encode(p, 16, 16, 16, None, None, 0, None, check=False) == vb.VABFT_EWORKSPACE
+    assert vb.vabft_encode(p, 16, 16, 16, 24, None, 0, None, check=False) == vb.VABFT_EWORKSPACE
+    # a misaligned d_S is still rejected when it is given
+    assert vb.vabft_encode(p, 16, 16, 16, 20, None, 0, None, check=False) == vb.VABFT_EINVAL
+    args = dict(d_astat=16, d_expected=16, d_T=16, inj=None, d_rowsum=16, d_E=16, d_flags=16, d_nflag=16, d_injlog=16,
+                d_ninj=16, d_workspace=None, workspace_bytes=0)
+    assert vb.vabft_gemm_verified_fused(p, 16, 16, 16, 16, None, 1e-6, 2.5, check=False, **args) == vb.VABFT_EWORKSPACE
+    assert vb.vabft_gemm_verified_fused(p, 16, 16, 16, None, None, 1e-6, 2.5, check=False, **args) in (
+        vb.VABFT_EINVAL, vb.VABFT_EWORKSPACE)
+    # the workspace covers the partials of S1..S3 (three doubles per 16 rows of B) beside the GEMM's areas
+    small, big = vb.make_problem(256, 256, 256, "f32"), vb.make_problem(256, 256, 16384, "f32")
+    assert vb.vabft_workspace_bytes(big) - vb.vabft_workspace_bytes(small) >= (16384 - 256) // 16 * 24
