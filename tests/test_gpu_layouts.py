@@ -163,3 +163,34 @@ def test_full_size_c3_every_route():
     vg.run_rc(dA, dB, inj=inj)
     r = vg.results()
     assert np.nonzero(r["flags"])[0].tolist() == [i] and np.nonzero(r["colflags"])[0].tolist() == [j]
+
+
+@pytest.mark.parametrize("dtype,M,N,K,transB", [
+    # more than 65535 rows / columns / tile indices in one direction; whole tiles and ragged
+    ("bf16", 196608, 256, 128, 0), ("bf16", 256, 196608, 128, 1), ("f16", 100003, 130, 72, 0),
+    ("f32", 131072, 128, 16, 0), ("f32", 70001, 40, 33, 1), ("f64", 128, 66000, 16, 0),
+    ("bf16", 256, 256, 16384, 0), ("f64", 130, 70, 20001, 1),
+])
+def test_long_dimensions(dtype, M, N, K, transB):
+    """One dimension far beyond the benchmark shapes (index arithmetic, grids, the S1..S3 partials of a long K)."""
+    print(f"long {dtype} {M}x{N}x{K} transB={transB}", flush=True)
+    A, B = _gen(dtype, M, N, K, transB, 33, "n_1e-6_1")
+    dA, dB = _dev(A, dtype), _dev(B, dtype)
+    vg = _session(M, N, K, dtype, transB)
+    o = orc.verify(A, B, dtype, transB, e_max=_emax(dtype, K, N))
+    for route, kw in (("run", {}), ("run_fused", {"defer_S": True})):
+        vg.flags.fill_(5)
+        getattr(vg, route)(dA, dB, **kw)
+        r = vg.results()
+        if route == "run":
+            check_light(r, o, dtype, M, N, K)
+        check_rows(r, o, dtype)
+        check_C(r, o, A, B, dtype, transB)
+        assert r["nflag"] == 0 and not r["flags"].any()
+    i, j = M - 1, N - 1
+    bit = 62 if dtype == "f64" else 30
+    vg.run_fused(dA, dB, inj=vg.make_inject(mode=1, faults=[(i, j, bit)]))
+    r = vg.results()
+    n, recs = vg.inject_records()
+    assert n == 1 and recs[0][:3] == (i, j, bit)
+    assert r["flags"][i] == 1 and r["nflag"] == 1 and r["flags"].sum() == 1
