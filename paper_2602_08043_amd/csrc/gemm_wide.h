@@ -197,16 +197,26 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     auto fold_stats = [&]() {
         T bev[V];
         __builtin_memcpy(bev, &be_raw, 16);
+        // the chunk's sum and dot product are formed pairwise and then added to the running values, so the
+        // sequential rounding chain of a thread is one add per folded k-tile, not one per element
 #pragma unroll
-        for (int p = 0; p < NCH_A; ++p)
+        for (int p = 0; p < NCH_A; ++p) {
+            T cs, cd;
+            if constexpr (V == 2) {
+                cs = ra[p][0] + ra[p][1];
+                cd = fma(ra[p][1], bev[1], ra[p][0] * bev[0]);
+            } else {
+                cs = (ra[p][0] + ra[p][1]) + (ra[p][2] + ra[p][3]);
+                cd = fma(ra[p][1], bev[1], ra[p][0] * bev[0]) + fma(ra[p][3], bev[3], ra[p][2] * bev[2]);
+            }
+            st[p][0] += cs;
+            st[p][1] += cd;
 #pragma unroll
             for (int e = 0; e < V; ++e) {
-                const T x = ra[p][e];
-                st[p][0] += x;
-                st[p][1] = fma(x, bev[e], st[p][1]);
-                st[p][2] = fmax(st[p][2], x);
-                st[p][3] = fmin(st[p][3], x);
+                st[p][2] = fmax(st[p][2], ra[p][e]);
+                st[p][3] = fmin(st[p][3], ra[p][e]);
             }
+        }
     };
 
     auto compute = [&](int s) {
@@ -419,7 +429,10 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
                 const bool act = tid < BM;
                 const int gi = row0 + (act ? tid : 0);
                 const int np = 2 * g.tiles_n;
-                T rs = 0, rs2 = 0, sum = 0, dot = 0, mx = lowest<T>(), mn = -lowest<T>();
+                // every batch is folded as a tree and lands in one of four rotating accumulators, themselves
+                // folded pairwise at the end: the rounding chain of a sum is log-like in the number of partials
+                T rs4[4] = {0, 0, 0, 0}, rs24[4] = {0, 0, 0, 0}, sum4[4] = {0, 0, 0, 0}, dot4[4] = {0, 0, 0, 0};
+                T mx = lowest<T>(), mn = -lowest<T>();
                 if (act) {
                     for (int t0 = 0; t0 < np; t0 += 16) {
                         T v[16], v2[16];
@@ -435,10 +448,18 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
                                 v[j] = 0;
                                 if (WSUM) v2[j] = 0;
                             }
+                        T q[4], q2[4];
 #pragma unroll
-                        for (int j = 0; j < 16; j += 4) {
-                            rs += (v[j] + v[j + 1]) + (v[j + 2] + v[j + 3]);
-                            if (WSUM) rs2 += (v2[j] + v2[j + 1]) + (v2[j + 2] + v2[j + 3]);
+                        for (int j = 0; j < 4; ++j) {
+                            q[j] = (v[4 * j] + v[4 * j + 1]) + (v[4 * j + 2] + v[4 * j + 3]);
+                            if (WSUM) q2[j] = (v2[4 * j] + v2[4 * j + 1]) + (v2[4 * j + 2] + v2[4 * j + 3]);
+                        }
+                        const T b = (q[0] + q[1]) + (q[2] + q[3]), b2 = WSUM ? (q2[0] + q2[1]) + (q2[2] + q2[3]) : (T)0;
+                        const int slot = (t0 >> 4) & 3;  // x + 0 is exact: the other three stay as they are
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            rs4[k] += slot == k ? b : (T)0;
+                            if (WSUM) rs24[k] += slot == k ? b2 : (T)0;
                         }
                     }
                     if (FUSED) {
@@ -459,16 +480,26 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
                                     v[j][2] = lowest<T>();
                                     v[j][3] = -lowest<T>();
                                 }
+                            const T bs = ((v[0][0] + v[1][0]) + (v[2][0] + v[3][0])) +
+                                         ((v[4][0] + v[5][0]) + (v[6][0] + v[7][0]));
+                            const T bd = ((v[0][1] + v[1][1]) + (v[2][1] + v[3][1])) +
+                                         ((v[4][1] + v[5][1]) + (v[6][1] + v[7][1]));
+                            const int slot = (t0 >> 3) & 3;
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                sum4[k] += slot == k ? bs : (T)0;
+                                dot4[k] += slot == k ? bd : (T)0;
+                            }
 #pragma unroll
                             for (int j = 0; j < 8; j += 4) {
-                                sum += (v[j][0] + v[j + 1][0]) + (v[j + 2][0] + v[j + 3][0]);
-                                dot += (v[j][1] + v[j + 1][1]) + (v[j + 2][1] + v[j + 3][1]);
                                 mx = fmax(mx, fmax(fmax(v[j][2], v[j + 1][2]), fmax(v[j + 2][2], v[j + 3][2])));
                                 mn = fmin(mn, fmin(fmin(v[j][3], v[j + 1][3]), fmin(v[j + 2][3], v[j + 3][3])));
                             }
                         }
                     }
                 }
+                const T rs = (rs4[0] + rs4[1]) + (rs4[2] + rs4[3]), rs2 = (rs24[0] + rs24[1]) + (rs24[2] + rs24[3]);
+                const T sum = (sum4[0] + sum4[1]) + (sum4[2] + sum4[3]), dot = (dot4[0] + dot4[1]) + (dot4[2] + dot4[3]);
                 int f = 0;
                 if (act) {
                     T expv, thr;
