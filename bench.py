@@ -226,8 +226,10 @@ def main():
     # (gemm_ms) adds the event records' own bubbles to each figure and reads 3 - 5 % longer than rocprofv3's
     # kernel trace; it is reported beside it.
     single_launch = ((dt in ("bf16", "f16") and M % 256 == 0 and N % 256 == 0 and K % 128 == 0) or
-                     (dt in ("f32", "f64") and M % 128 == 0 and N % 128 == 0 and K % 16 == 0))
-    # other cases (FP8, ragged shapes) run the A-side pass (and the compare) as launches of their own inside the
+                     (dt in ("f32", "f64") and M % 128 == 0 and N % 128 == 0 and K % 16 == 0) or
+                     (dt == "f8" and tb == 1 and M % 256 == 0 and N % 256 == 0 and N >= 512 and K % 256 == 0 and
+                      (K // 256) // (N // 256) + 2 <= 8))
+    # other cases (ragged shapes) run the A-side pass (and the compare) as launches of their own inside the
     # fused call: for them the dominant kernel is timed through the call that takes the threshold as an input
     ms_dom = ms_steady if single_launch else ms_gemm_verified_only
     achieved = flops / (ms_dom * 1e-3) / 1e12

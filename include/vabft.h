@@ -165,7 +165,8 @@ int vabft_gemm_verified(const vabft_problem* p, const void* dA, const void* dB, 
  * thresholds are undefined); e_max, c_sigma as in vabft_threshold.
  * Outputs: d_astat [3M], d_expected [M], d_T [M] (as vabft_threshold) and d_rowsum, d_E,
  * d_flags, d_nflag, dC, injection log (as vabft_gemm_verified).  For BF16 / FP16 problems made
- * of whole 256 x 256 x 128 tiles, and FP32 / FP64 problems made of whole 128 x 128 x 16 tiles,
+ * of whole 256 x 256 x 128 tiles (FP8: 256 x 256 x 256, B stored N x K), and FP32 / FP64 problems
+ * made of whole 128 x 128 x 16 tiles,
  * with 16-byte aligned rows the statistics ride on the operand tiles inside the GEMM kernel
  * and the compare-and-flag step runs in the last workgroup of each row block (a single
  * launch); other problems run the two passes back to back.  The

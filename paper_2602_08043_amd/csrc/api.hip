@@ -321,8 +321,10 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     const bool in_kernel_finalize = !edge;
     if (fused) {
         // the fused 16-bit kernel caches the Be slices of the k-units a tile-column folds: at most 16
-        const bool fits16 = p->dtype != VABFT_F8E4M3 && a.tiles_n >= 2 && p->K % 128 == 0 &&
-                            (p->K / 128) / a.tiles_n + 2 <= 16;
+        // (units of 128 k, 16 cache slots; the FP8 kernel: units of 256 k, 8 slots, B stored N x K)
+        const bool fits16 = p->dtype == VABFT_F8E4M3
+                                ? (a.tiles_n >= 2 && p->K % 256 == 0 && p->transB && (p->K / 256) / a.tiles_n + 2 <= 8)
+                                : (a.tiles_n >= 2 && p->K % 128 == 0 && (p->K / 128) / a.tiles_n + 2 <= 16);
         if (in_kernel_finalize && (!is16 || fits16)) {
             a.fused_stats = 1;
             a.Be = fused->d_Be;

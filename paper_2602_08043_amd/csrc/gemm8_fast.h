@@ -15,7 +15,11 @@
 //   * per k-step 16 MFMAs of 64 cycles; each slot also issues one fragment read of the next k-step and,
 //     in the first k-step after the barrier, one of the 16 loads of the next tile;
 //   * the epilogue (row sums before quantisation, compare-and-flag, injector, weighted and column sums,
-//     FP16 store) is the 16-bit kernel's.
+//     FP16 store) is the 16-bit kernel's;
+//   * FUSED: the A-side of Algorithm 1 as in the 16-bit kernel.  Tile-column bn folds the units (two k-tiles,
+//     256 k) u with u % tiles_n == bn; a lane's 32 fragment bytes are consecutive k of its row, wavefront wn
+//     takes 16 of them, four per slot (convert, sum, FMA with Be, max, min); the Be values of a k-step are read
+//     from the LDS cache when the k-step starts.
 #pragma once
 #include "gemm16_fast.h"
 
@@ -36,10 +40,11 @@ __device__ __forceinline__ f32x16_t mfma_f8(const raw32& a, const raw32& b, f32x
 }
 }  // namespace g8f
 
-template <int MODE>
+template <int MODE, bool FUSED>
 __global__ __launch_bounds__(256) void gemm8_fast_kernel(const GemmArgs g) {
     using namespace g8f;
     constexpr bool CSUM = MODE == 2 || MODE == 4;
+    static_assert(!FUSED || MODE == 1 || MODE == 2, "fused statistics belong to the verified kernel");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     lds_u8* const lds = (lds_u8*)smem;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -117,12 +122,56 @@ __global__ __launch_bounds__(256) void gemm8_fast_kernel(const GemmArgs g) {
         }
     };
 
+    // ---- fused A-side statistics (FUSED) ----------------------------------------------------------------
+    // st[mi] = (sum, dot with Be, max, min) of rows wm*128 + mi*32 + l32 over the k this lane folds.  A unit is
+    // two k-tiles; its four k-steps, in the order the bodies multiply them, cover k = 256u - 64 + 64 s .. + 63
+    // (s = 0..3; the first belongs to the previous tile because fragments run one k-step ahead).  The lane's
+    // 16 bytes of a k-step are k = 256u - 64 + 64 s + 32 lh + 16 wn + 0..15; bev holds their Be values.
+    float st[4][4];
+    f32x4_t bev[4];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+        st[mi][0] = 0.f;
+        st[mi][1] = 0.f;
+        st[mi][2] = -3.402823466e+38f;
+        st[mi][3] = 3.402823466e+38f;
+    }
+    // Be cache: slot j (256 floats) holds the unit u = bn + j * tiles_n
+    auto load_bev = [&](int j, auto sidx_c) {
+        constexpr int SIDX = decltype(sidx_c)::value;
+        const float* p = reinterpret_cast<const float*>(smem + BE_CACHE_OFFSET) + j * 256 + 64 * SIDX + 32 * lh + 16 * wn;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) bev[d] = *reinterpret_cast<const f32x4_t*>(p + 4 * d);
+    };
+    // slot (mi, d) folds dword d of this wavefront's half of fragment mi: four consecutive k
+    auto stats_slot = [&](const raw32 (&af)[4], auto slot_c, auto sidx_c, bool skip) {
+        constexpr int slot = decltype(slot_c)::value, SIDX = decltype(sidx_c)::value;
+        constexpr int mi = slot >> 2, d = slot & 3;
+        const uint32_t lo = af[mi].lo.w[d], hi = af[mi].hi.w[d];
+        const int w = (int)(wn ? hi : lo);
+        const float x0 = __builtin_amdgcn_cvt_f32_fp8(w, 0), x1 = __builtin_amdgcn_cvt_f32_fp8(w, 1);
+        const float x2 = __builtin_amdgcn_cvt_f32_fp8(w, 2), x3 = __builtin_amdgcn_cvt_f32_fp8(w, 3);
+        st[mi][0] += (x0 + x1) + (x2 + x3);
+        st[mi][1] += fmaf(x1, bev[d][1], x0 * bev[d][0]) + fmaf(x3, bev[d][3], x2 * bev[d][2]);
+        st[mi][2] = fmaxf(fmaxf(fmaxf(st[mi][2], x0), x1), fmaxf(x2, x3));
+        st[mi][3] = fminf(fminf(fminf(st[mi][3], x0), x1), fminf(x2, x3));
+        if constexpr (SIDX == 0 && d == 3) {
+            // `skip` (wave-uniform): the all-zero fragments of the very first pass; it can only be the first
+            // k-step this workgroup folds, so max / min go back to their initial values behind it
+            st[mi][2] = skip ? -3.402823466e+38f : st[mi][2];
+            st[mi][3] = skip ? 3.402823466e+38f : st[mi][3];
+        }
+    };
+
     // One k-step = 16 slots of one MFMA (64 cycles).  Slot i also issues fragment read i of the NEXT k-step
-    // and, when LOADS, global -> LDS load i of the next tile into stage S^1.
-    auto kstep = [&](auto s_c, auto ks_c, auto loads_c, const raw32 (&af)[4], const raw32 (&bf)[4], raw32 (&naf)[4],
-                     raw32 (&nbf)[4], const unsigned char* ap, const unsigned char* bp) {
-        constexpr int S = decltype(s_c)::value;
+    // and, when LOADS, global -> LDS load i of the next tile into stage S^1; with SIDX >= 0 it also folds four
+    // elements of the fragments being multiplied into the A statistics (k-step SIDX of folded unit number hj).
+    auto kstep = [&](auto s_c, auto ks_c, auto loads_c, auto sidx_c, const raw32 (&af)[4], const raw32 (&bf)[4],
+                     raw32 (&naf)[4], raw32 (&nbf)[4], const unsigned char* ap, const unsigned char* bp, int hj,
+                     bool skip) {
+        constexpr int S = decltype(s_c)::value, SIDX = decltype(sidx_c)::value;
         constexpr bool LOADS = decltype(loads_c)::value != 0;
+        if constexpr (FUSED && SIDX >= 0) load_bev(hj, sidx_c);
         static_for<0, 16>([&](auto slot_c) {
             constexpr int slot = decltype(slot_c)::value;
             constexpr int mi = slot >> 2, ni = slot & 3;
@@ -130,6 +179,7 @@ __global__ __launch_bounds__(256) void gemm8_fast_kernel(const GemmArgs g) {
             __builtin_amdgcn_sched_barrier(0);  // MFMA first, the rest of the slot in its shadow
             frag_op(s_c, ks_c, slot_c, naf, nbf);
             if constexpr (LOADS) issue_load(std::integral_constant<int, S ^ 1>{}, slot_c, ap, bp);
+            if constexpr (FUSED && SIDX >= 0) stats_slot(af, slot_c, sidx_c, skip);
             __builtin_amdgcn_sched_barrier(0);
         });
     };
@@ -144,6 +194,18 @@ __global__ __launch_bounds__(256) void gemm8_fast_kernel(const GemmArgs g) {
         bf1[i].lo = bf1[i].hi = raw16{{0u, 0u, 0u, 0u}};
     }
     static_for<0, 16>([&](auto l_c) { issue_load(I0{}, l_c, a_base, b_base); });
+    if (FUSED) {
+        // cache the Be slices of every unit this tile-column folds (the host guarantees they fit)
+        float* cache = reinterpret_cast<float*>(smem + BE_CACHE_OFFSET);
+        const float* const Be = reinterpret_cast<const float*>(g.Be);
+        const int nunits = nk >> 1;
+        for (int j = 0, u = bn; u <= nunits && j < BE_CACHE_SLOTS / 2; ++j, u += g.tiles_n) {
+            const int k = 256 * u - 64 + tid;
+            cache[j * 256 + tid] = (k >= 0 && k < g.K) ? Be[k] : 0.f;
+        }
+        // S1..S3 still in partials: every workgroup folds them here, under the latency of its first tile
+        if (!g.S) fold_s_partials_to_lds(g.s_partial, g.s_nparts, tid, reinterpret_cast<double*>(smem + S_RED_OFFSET));
+    }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -151,36 +213,73 @@ __global__ __launch_bounds__(256) void gemm8_fast_kernel(const GemmArgs g) {
     // in registers; the very first pass multiplies zeros) and the first k-step of tile kt.  The 16 loads of
     // tile kt+1 (clamped at the last tile; the reload is harmless) ride in the first of the two, into the
     // stage that held tile kt-1, whose last reads completed before the previous barrier.
-    auto tile_body = [&](auto s_c, int kt) {
+    using IN = std::integral_constant<int, -1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+    // stc: 0 plain, 1 with the statistics (the two k-steps of the body are k-steps 2S and 2S+1 of the unit)
+    auto tile_body = [&](auto s_c, auto stc, int kt, int hj, bool skip) {
+        constexpr int S = decltype(s_c)::value;
+        constexpr bool STATS = decltype(stc)::value != 0;
+        using SA = std::integral_constant<int, STATS ? 2 * S : -1>;
+        using SB = std::integral_constant<int, STATS ? 2 * S + 1 : -1>;
         const int ktn = kt + 1 < nk ? kt + 1 : nk - 1;
         const unsigned char* ap = a_base + (int64_t)ktn * BKB;
         const unsigned char* bp = b_base + (int64_t)ktn * BKB;
-        kstep(s_c, I0{}, I1{}, af1, bf1, af0, bf0, ap, bp);  // step (kt-1, 1); reads (kt, 0)
-        kstep(s_c, I1{}, I0{}, af0, bf0, af1, bf1, ap, bp);  // step (kt, 0);   reads (kt, 1)
+        kstep(s_c, I0{}, I1{}, SA{}, af1, bf1, af0, bf0, ap, bp, hj, skip);   // step (kt-1, 1); reads (kt, 0)
+        kstep(s_c, I1{}, I0{}, SB{}, af0, bf0, af1, bf1, ap, bp, hj, false);  // step (kt, 0);   reads (kt, 1)
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     };
-    // K is a multiple of 256 (the host checks): tiles come in pairs, so the stage parity is a compile-time
-    // constant and there is no odd tail (a branch here makes the compiler shuffle the 256 accumulators)
-    for (int kt = 0; kt < nk; kt += 2) {
-        tile_body(I0{}, kt);
-        tile_body(I1{}, kt + 1);
+    // K is a multiple of 256 (the host checks): tiles come in pairs (units), so the stage parity is a
+    // compile-time constant and there is no odd tail (a branch here makes the compiler shuffle the 256
+    // accumulators)
+    if constexpr (FUSED) {
+        // plain units run in a branch-free inner loop, the folded unit in straight-line code between two such loops
+        const int nunits = nk >> 1;
+        int hu = bn, hj = 0, u = 0;
+        for (;;) {
+            const int stop = hu < nunits ? hu : nunits;
+            for (; u < stop; ++u) {
+                tile_body(I0{}, I0{}, 2 * u, 0, false);
+                tile_body(I1{}, I0{}, 2 * u + 1, 0, false);
+            }
+            if (u >= nunits) break;
+            tile_body(I0{}, I1{}, 2 * u, hj, u == 0);
+            tile_body(I1{}, I1{}, 2 * u + 1, hj, false);
+            ++u;
+            hu += g.tiles_n;
+            ++hj;
+        }
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = mfma_f8(bf1[ni], af1[mi], acc[mi][ni]);  // step (nk-1, 1)
+        // ... which is k-step 0 of the unit that would follow the last one
+        if (hu == nunits) {
+            load_bev(hj, I0{});
+            static_for<0, 16>([&](auto slot_c) { stats_slot(af1, slot_c, I0{}, false); });
+        }
+    } else {
+        for (int kt = 0; kt < nk; kt += 2) {
+            tile_body(I0{}, I0{}, kt, 0, false);
+            tile_body(I1{}, I0{}, kt + 1, 0, false);
+        }
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = mfma_f8(bf1[ni], af1[mi], acc[mi][ni]);  // step (nk-1, 1)
     }
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = mfma_f8(bf1[ni], af1[mi], acc[mi][ni]);  // step (nk-1, 1)
 
-    float st[4][4] = {};
-    gemm16_fast_epilogue<f16_t, MODE, false>(g, acc, st, smem, bm, bn, row0, col0, tid, lane, wm, wn, l32, lh);
+    gemm16_fast_epilogue<f16_t, MODE, FUSED>(g, acc, st, smem, bm, bn, row0, col0, tid, lane, wm, wn, l32, lh);
 }
 
 static int gemm8_fast_launch(const GemmArgs& a, int mode, hipStream_t st) {
     const dim3 grid(a.tiles_m * a.tiles_n), block(256);
-    const size_t lds = g16::LDS_BYTES;
-#define VABFT_G8F_CASE(VF)                                                                                 \
-    if (mode == VF) {                                                                                      \
-        auto kern = gemm8_fast_kernel<VF>;                                                                 \
+    const bool fused = a.fused_stats != 0;
+    const size_t lds = fused ? g16f::LDS_BYTES_FUSED : g16::LDS_BYTES;
+#define VABFT_G8F_CASE(VF, FU)                                                                             \
+    if (mode == VF && fused == FU) {                                                                       \
+        auto kern = gemm8_fast_kernel<VF, FU>;                                                             \
         static bool attr_set = false;                                                                      \
         if (!attr_set) {                                                                                   \
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
@@ -191,12 +290,14 @@ static int gemm8_fast_launch(const GemmArgs& a, int mode, hipStream_t st) {
         kern<<<grid, block, lds, st>>>(a);                                                                 \
         return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;                                 \
     }
-    VABFT_G8F_CASE(0)
-    VABFT_G8F_CASE(1)
-    VABFT_G8F_CASE(2)
-    VABFT_G8F_CASE(3)
-    VABFT_G8F_CASE(4)
-    VABFT_G8F_CASE(5)
+    VABFT_G8F_CASE(0, false)
+    VABFT_G8F_CASE(1, false)
+    VABFT_G8F_CASE(2, false)
+    VABFT_G8F_CASE(3, false)
+    VABFT_G8F_CASE(4, false)
+    VABFT_G8F_CASE(5, false)
+    VABFT_G8F_CASE(1, true)
+    VABFT_G8F_CASE(2, true)
 #undef VABFT_G8F_CASE
     return VABFT_EINVAL;
 }

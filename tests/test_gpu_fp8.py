@@ -135,3 +135,43 @@ def test_fp8_full_size_sampled():
     vg.gemm(dA, dB, 1, vg.make_inject(mode=1, faults=[(i, N - 5, 28)]))
     r2 = vg.results()
     assert np.nonzero(r2["flags"])[0].tolist() == [i] and r2["nflag"] == 1
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 512, 256), (512, 1024, 2048), (768, 512, 3072), (256, 512, 3584),
+                                   (256, 768, 768)])
+def test_fp8_fused_call_single_launch(M, N, K):
+    """vabft_gemm_verified_fused on FP8 problems the single-launch kernel takes (statistics of A folded from the
+    operand fragments: units of 256 k dealt to the tile-columns, up to eight per workgroup) and one it hands to
+    the two-pass route (3584 / 256 = 14 units on two tile-columns), with and without the deferred fold of S1..S3,
+    against the oracle and against the three-call route."""
+    for seed, dist in ((41, "n_1e-6_1"), (42, "u_-1_1")):
+        A, B = _gen8(M, N, K, 1, seed, dist)
+        print(f"fp8 fused {M}x{N}x{K} {dist}", flush=True)
+        vg = _session(M, N, K, "f8", 1)
+        dA, dB = _dev(A, "f8"), _dev(B, "f8")
+        o = orc.verify(A, B, "f8", 1, e_max=_emax("f8", K, N))
+        vg.run(dA, dB)
+        r3 = {k: np.copy(v) for k, v in vg.results().items()}
+        for defer in (False, True, False):
+            vg.T.fill_(-1.0)
+            vg.astat.fill_(9.0)
+            vg.flags.fill_(3)
+            vg.run_fused(dA, dB, defer_S=defer)
+            r = vg.results()
+            if not defer:
+                check_light(r, o, "f8", M, N, K)
+            check_rows(r, o, "f8")
+            check_C8(r, o, A, B, 1)
+            assert np.array_equal(r["astat"][:, 0].astype(np.float64), o["astat"][:, 0])
+            assert np.array_equal(r["astat"][:, 1].astype(np.float64), o["astat"][:, 1])
+            assert np.allclose(r["T"], r3["T"], rtol=2e-6, atol=0)
+            assert np.array_equal(r["C"], r3["C"]) and np.array_equal(r["rowsum"], r3["rowsum"])
+            assert r["nflag"] == 0 and not r["flags"].any()
+    i, j = M - 1, N // 2
+    vg.run_fused(dA, dB, inj=vg.make_inject(mode=1, faults=[(i, j, 30)]), defer_S=True)
+    r = vg.results()
+    n, recs = vg.inject_records()
+    assert n == 1 and recs[0][:3] == (i, j, 30)
+    assert r["flags"][i] == 1 and r["nflag"] == 1 and r["flags"].sum() == 1
+    vg.run_fused(dA, dB)
+    assert vg.results()["nflag"] == 0
