@@ -7,6 +7,29 @@
 
 namespace vabft {
 
+// sum_t part[t][i] in a fixed order: batches of 16 folded as trees into four rotating accumulators, themselves
+// folded pairwise at the end (the order the whole-tile kernels use for their partials)
+template <typename acc_t>
+__device__ __forceinline__ acc_t fold_partials(const acc_t* __restrict__ part, int nparts, int M, int i) {
+    acc_t a4[4] = {0, 0, 0, 0};
+    for (int t0 = 0; t0 < nparts; t0 += 16) {
+        acc_t v[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = part[(int64_t)(t0 + j < nparts ? t0 + j : nparts - 1) * M + i];
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if (!(t0 + j < nparts)) v[j] = 0;
+        acc_t q[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) q[j] = (v[4 * j] + v[4 * j + 1]) + (v[4 * j + 2] + v[4 * j + 3]);
+        const acc_t b = (q[0] + q[1]) + (q[2] + q[3]);
+        const int slot = (t0 >> 4) & 3;  // x + 0 is exact: the other three stay as they are
+#pragma unroll
+        for (int k = 0; k < 4; ++k) a4[k] += slot == k ? b : (acc_t)0;
+    }
+    return (a4[0] + a4[1]) + (a4[2] + a4[3]);
+}
+
 // rowsum[i] = sum_t rowpart[t][i] in a fixed order; E = expected - rowsum; flag = !(|E| <= T)
 template <typename acc_t>
 __global__ __launch_bounds__(256) void finalize_kernel(const acc_t* __restrict__ rowpart, int tiles_n, int M,
@@ -19,23 +42,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(const acc_t* __restrict__
     const int i = blockIdx.x * 256 + threadIdx.x;
     int f = 0;
     if (i < M) {
-        if (rowsum2) {
-            // position-weighted row sums C r2, same fold
-            acc_t s2 = 0;
-            int t = 0;
-            for (; t + 3 < tiles_n; t += 4)
-                s2 += (rowpart2[(int64_t)t * M + i] + rowpart2[(int64_t)(t + 1) * M + i]) +
-                      (rowpart2[(int64_t)(t + 2) * M + i] + rowpart2[(int64_t)(t + 3) * M + i]);
-            for (; t < tiles_n; ++t) s2 += rowpart2[(int64_t)t * M + i];
-            rowsum2[i] = s2;
-        }
-        // partials folded four at a time, pairwise inside each group of four
-        acc_t s = 0;
-        int t = 0;
-        for (; t + 3 < tiles_n; t += 4)
-            s += (rowpart[(int64_t)t * M + i] + rowpart[(int64_t)(t + 1) * M + i]) +
-                 (rowpart[(int64_t)(t + 2) * M + i] + rowpart[(int64_t)(t + 3) * M + i]);
-        for (; t < tiles_n; ++t) s += rowpart[(int64_t)t * M + i];
+        if (rowsum2) rowsum2[i] = fold_partials(rowpart2, tiles_n, M, i);  // position-weighted row sums C r2
+        const acc_t s = fold_partials(rowpart, tiles_n, M, i);
         const acc_t e = expected[i] - s;
         f = !(fabs(e) <= T[i]);
         rowsum[i] = s;
@@ -451,7 +459,7 @@ double vabft_default_emax(int32_t dtype, int32_t K, int32_t N) {
     if (dtype == VABFT_F8E4M3) return 5.5e-6;
     if (dtype == VABFT_F64) {
         paper = 1.0e-17 * sqrt(n) + 2.5e-16;
-        measured = 8.0e-18 * sqrt(n) + 4.6e-16;
+        measured = 8.0e-18 * sqrt(n) + 5.2e-16;
     } else {
         paper = 5.0e-9 * sqrt(n) + 1.2e-7;
         measured = 3.0e-9 * sqrt(n) + 3.8e-7;

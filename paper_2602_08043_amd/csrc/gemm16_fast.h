@@ -164,7 +164,11 @@ __device__ __forceinline__ void gemm16_fast_epilogue(const GemmArgs& g, f32x16_t
         if (*s_last) {
             // Combine the tile-column partials in tile order.  The device-scope loads are issued
             // in batches of 16 tile-columns before anything is folded, so their latencies overlap.
-            float rs = 0.f, rs2 = 0.f, sum = 0.f, dot = 0.f, mx = -3.402823466e+38f, mn = 3.402823466e+38f;
+            // every batch of 16 is folded as a tree and lands in one of four rotating accumulators, themselves
+            // folded pairwise at the end: the rounding chain of a sum is log-like in the number of tile-columns
+            float rs4[4] = {0.f, 0.f, 0.f, 0.f}, rs24[4] = {0.f, 0.f, 0.f, 0.f}, sum4[4] = {0.f, 0.f, 0.f, 0.f},
+                  dot4[4] = {0.f, 0.f, 0.f, 0.f};
+            float mx = -3.402823466e+38f, mn = 3.402823466e+38f;
             for (int t0 = 0; t0 < g.tiles_n; t0 += 16) {
                 float v[16][5];
                 float v2[16];
@@ -181,8 +185,7 @@ __device__ __forceinline__ void gemm16_fast_epilogue(const GemmArgs& g, f32x16_t
                         v[j][4] = ld_agent(ap + 3 * (int64_t)g.M);
                     }
                 }
-                // fold four at a time, pairwise inside each group (absent tile-columns count as
-                // the neutral element)
+                // absent tile-columns count as the neutral element
 #pragma unroll
                 for (int j = 0; j < 16; ++j)
                     if (!(t0 + j < g.tiles_n)) {
@@ -193,18 +196,35 @@ __device__ __forceinline__ void gemm16_fast_epilogue(const GemmArgs& g, f32x16_t
                         v[j][3] = -3.402823466e+38f;
                         v[j][4] = 3.402823466e+38f;
                     }
+                float q[4], q2[4], qs[4], qd[4];
 #pragma unroll
-                for (int j = 0; j < 16; j += 4) {
-                    rs += (v[j][0] + v[j + 1][0]) + (v[j + 2][0] + v[j + 3][0]);
-                    if (WSUM) rs2 += (v2[j] + v2[j + 1]) + (v2[j + 2] + v2[j + 3]);
+                for (int j = 0; j < 4; ++j) {
+                    q[j] = (v[4 * j][0] + v[4 * j + 1][0]) + (v[4 * j + 2][0] + v[4 * j + 3][0]);
+                    if (WSUM) q2[j] = (v2[4 * j] + v2[4 * j + 1]) + (v2[4 * j + 2] + v2[4 * j + 3]);
                     if (FUSED) {
-                        sum += (v[j][1] + v[j + 1][1]) + (v[j + 2][1] + v[j + 3][1]);
-                        dot += (v[j][2] + v[j + 1][2]) + (v[j + 2][2] + v[j + 3][2]);
-                        mx = fmaxf(mx, fmaxf(fmaxf(v[j][3], v[j + 1][3]), fmaxf(v[j + 2][3], v[j + 3][3])));
-                        mn = fminf(mn, fminf(fminf(v[j][4], v[j + 1][4]), fminf(v[j + 2][4], v[j + 3][4])));
+                        qs[j] = (v[4 * j][1] + v[4 * j + 1][1]) + (v[4 * j + 2][1] + v[4 * j + 3][1]);
+                        qd[j] = (v[4 * j][2] + v[4 * j + 1][2]) + (v[4 * j + 2][2] + v[4 * j + 3][2]);
+                        mx = fmaxf(mx, fmaxf(fmaxf(v[4 * j][3], v[4 * j + 1][3]), fmaxf(v[4 * j + 2][3], v[4 * j + 3][3])));
+                        mn = fminf(mn, fminf(fminf(v[4 * j][4], v[4 * j + 1][4]), fminf(v[4 * j + 2][4], v[4 * j + 3][4])));
+                    }
+                }
+                const int slot = (t0 >> 4) & 3;  // x + 0 is exact: the other three accumulators stay as they are
+                const float b = (q[0] + q[1]) + (q[2] + q[3]);
+                const float b2 = WSUM ? (q2[0] + q2[1]) + (q2[2] + q2[3]) : 0.f;
+                const float bs = FUSED ? (qs[0] + qs[1]) + (qs[2] + qs[3]) : 0.f;
+                const float bd = FUSED ? (qd[0] + qd[1]) + (qd[2] + qd[3]) : 0.f;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    rs4[k] += slot == k ? b : 0.f;
+                    if (WSUM) rs24[k] += slot == k ? b2 : 0.f;
+                    if (FUSED) {
+                        sum4[k] += slot == k ? bs : 0.f;
+                        dot4[k] += slot == k ? bd : 0.f;
                     }
                 }
             }
+            const float rs = (rs4[0] + rs4[1]) + (rs4[2] + rs4[3]), rs2 = (rs24[0] + rs24[1]) + (rs24[2] + rs24[3]);
+            const float sum = (sum4[0] + sum4[1]) + (sum4[2] + sum4[3]), dot = (dot4[0] + dot4[1]) + (dot4[2] + dot4[3]);
             float expv, thr;
             if (FUSED) {
                 const double mu = (double)sum / (double)g.K;
