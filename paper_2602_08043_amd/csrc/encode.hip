@@ -583,7 +583,14 @@ __global__ __launch_bounds__(256) void check_offline_kernel(const void* __restri
 // host launchers
 // ---------------------------------------------------------------------------
 
-constexpr int ENC_ROWS_PER_BLOCK = 128;  // n-rows per block in the transposed layout
+// Rows per block of the column reduction over a (rows x cols) row-major matrix: 128, or 64 when 128 would give
+// fewer than 512 blocks (the pass is bound by the loads in flight; every halving doubles the slab partials the
+// finishing kernel folds, and below 64 that costs more than it brings)
+static int col_rows_per_block(int dtype, int64_t rows, int64_t cols) {
+    const int64_t v = dtype == VABFT_F64 ? 2 : dtype == VABFT_F32 ? 4 : dtype == VABFT_F8E4M3 ? 16 : 8;
+    const int64_t xblocks = (cols + 64 * v - 1) / (64 * v);
+    return xblocks * ((rows + 127) / 128) < 512 ? 64 : 128;
+}
 
 // Rows k per block of the finishing kernel: 16, or fewer (K x N layout) when 16 would leave most of the
 // chip's 256 compute units without a block
@@ -603,7 +610,8 @@ size_t encode_workspace_bytes(const vabft_problem* p) {
     size_t bytes = 0;
     if (p->transB) {
         const size_t acc_bytes = p->dtype == VABFT_F64 ? 8 : 4;
-        const size_t nsplit = ((size_t)p->N + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
+        const size_t rpb = col_rows_per_block(p->dtype, p->N, p->K);
+        const size_t nsplit = ((size_t)p->N + rpb - 1) / rpb;
         bytes += nsplit * 4 * (size_t)p->K * acc_bytes;  // (sum, max, min, weighted sum) per slab
     }
     return bytes;
@@ -629,11 +637,11 @@ static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, voi
 #undef VABFT_ENC_ROWS
     } else {
         constexpr int V = Elem<T>::vec;
-        const int nsplit = (p->N + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
+        const int rpb = col_rows_per_block(p->dtype, p->N, p->K);
+        const int nsplit = (p->N + rpb - 1) / rpb;
         acc_t* part = reinterpret_cast<acc_t*>(ws);
         dim3 grid((p->K + 64 * V - 1) / (64 * V), nsplit);
-        encode_cols_kernel<T, W><<<grid, dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, ENC_ROWS_PER_BLOCK, part,
-                                                             vec_ok, nullptr);
+        encode_cols_kernel<T, W><<<grid, dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, rpb, part, vec_ok, nullptr);
         encode_cols_combine_kernel<acc_t, W><<<dim3(kblocks), dim3(256), 0, st>>>(
             part, nsplit, p->K, p->N, (acc_t*)d_Be, (acc_t*)d_Be2, (acc_t*)d_bstat, s_partial, ticket, d_S);
     }
@@ -759,7 +767,8 @@ size_t cols_workspace_bytes(const vabft_problem* p) {
     const vabft_problem qa = swapped_problem(p, p->M, p->M, 1, p->lda, p->lda);
     const size_t a = encode_workspace_bytes(&qa);
     const size_t acc_bytes = p->dtype == VABFT_F64 ? 8 : 4;
-    const size_t nsplit = ((size_t)p->K + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
+    const size_t rpb = col_rows_per_block(p->dtype, p->K, p->N);
+    const size_t nsplit = ((size_t)p->K + rpb - 1) / rpb;
     const size_t b = p->transB ? 0 : nsplit * 4 * (size_t)p->N * acc_bytes;
     return a > b ? a : b;
 }
@@ -778,11 +787,12 @@ static int threshold_cols_launch(const vabft_problem* p, const void* dB, const v
     using acc_t = typename Elem<T>::acc_t;
     constexpr int V = Elem<T>::vec;
     const int vec_ok = aligned16(dB) && ((p->ldb * Elem<T>::bytes) % 16 == 0);
-    const int nsplit = (p->K + ENC_ROWS_PER_BLOCK - 1) / ENC_ROWS_PER_BLOCK;
+    const int rpb = col_rows_per_block(p->dtype, p->K, p->N);
+    const int nsplit = (p->K + rpb - 1) / rpb;
     acc_t* part = reinterpret_cast<acc_t*>(ws);
     dim3 grid((p->N + 64 * V - 1) / (64 * V), nsplit);
     // rows of the reduction = k (K of them), columns = n (N of them), weight of row k = (c1 A)[k]
-    encode_cols_kernel<T, true><<<grid, dim3(256), 0, st>>>(dB, p->N, p->K, p->ldb, ENC_ROWS_PER_BLOCK, part, vec_ok,
+    encode_cols_kernel<T, true><<<grid, dim3(256), 0, st>>>(dB, p->N, p->K, p->ldb, rpb, part, vec_ok,
                                                             (const acc_t*)d_eA);
     threshold_cols_finish_kernel<acc_t><<<dim3((p->N + 255) / 256), dim3(256), 0, st>>>(
         part, nsplit, p->N, p->K, p->M, d_SA, e_max, c_sigma, (acc_t*)d_bcolstat, (acc_t*)d_expected_col,
