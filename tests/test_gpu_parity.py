@@ -563,3 +563,35 @@ def test_random_shapes_every_main_route(dtype, M, N, K, transB, seed):
             assert rf["flags"][i] == 1 and rf["nflag"] == 1 and rf["flags"].sum() == 1
         route()
         assert vg.results()["nflag"] == 0
+
+
+@pytest.mark.parametrize("dtype,M,N,K,transB", [("bf16", 512, 512, 256, 0), ("f16", 300, 520, 200, 1),
+                                                 ("f32", 256, 256, 64, 1), ("f64", 128, 256, 48, 0)])
+@pytest.mark.parametrize("e_max,c_sigma", [(1e-6, 0.0), (3e-7, 1.0), (2e-5, 6.0)])
+def test_caller_chosen_emax_and_csigma(dtype, M, N, K, transB, e_max, c_sigma):
+    """e_max and c_sigma are parameters of Algorithm 1: with c_sigma = 0 only the deterministic term remains, and
+    the thresholds scale linearly with e_max; every route takes the caller's values."""
+    if dtype == "f64":
+        e_max *= 1e-9
+    A, B = _gen(dtype, M, N, K, transB, 61, "n_1_1")
+    dA, dB = _dev(A, dtype), _dev(B, dtype)
+    vg = _session(M, N, K, dtype, transB)
+    o = orc.verify(A, B, dtype, transB, e_max=e_max, c_sigma=c_sigma)
+    rtol = max(_tol(dtype), 2e-7 if dtype != "f64" else 0)
+    for route in ("three", "fused", "deferred"):
+        vg.T.fill_(-1.0)
+        if route == "three":
+            vg.encode(dB)
+            vg.threshold(dA, e_max, c_sigma)
+            vg.gemm(dA, dB, 1)
+        else:
+            vg.encode(dB, defer_S=route == "deferred")
+            vg.gemm_fused(dA, dB, e_max, c_sigma, deferred_S=route == "deferred")
+        r = vg.results()
+        assert np.all(np.abs(r["T"] - o["T"]) <= rtol * o["T"] + 1e-300), route
+        assert np.array_equal(r["flags"], o["flags"]), route
+        assert r["nflag"] == int(o["flags"].sum())
+    if c_sigma == 0.0:
+        # T = e_max N |mu_A| S1 exactly (section 3.4, deterministic term)
+        mu = np.abs(o["astat"][:, 2])
+        assert np.allclose(o["T"], e_max * N * mu * o["S"][0], rtol=1e-12)
