@@ -88,3 +88,16 @@ def test_deferred_fold_arguments_without_a_gpu(lib):
     # the workspace covers the partials of S1..S3 (three doubles per 16 rows of B) beside the GEMM's areas
     small, big = vb.make_problem(256, 256, 256, "f32"), vb.make_problem(256, 256, 16384, "f32")
     assert vb.vabft_workspace_bytes(big) - vb.vabft_workspace_bytes(small) >= (16384 - 256) // 16 * 24
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The path is built and measured on one GPU: bench.py --gpus N with N > 1 exits with a message, before
+    anything touches a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
