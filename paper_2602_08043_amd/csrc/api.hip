@@ -67,12 +67,7 @@ __global__ __launch_bounds__(256) void finalize_cols_kernel(const acc_t* __restr
     const int j = blockIdx.x * 256 + threadIdx.x;
     int f = 0;
     if (j < N) {
-        acc_t s = 0;
-        int t = 0;
-        for (; t + 3 < nparts; t += 4)
-            s += (colpart[(int64_t)t * N + j] + colpart[(int64_t)(t + 1) * N + j]) +
-                 (colpart[(int64_t)(t + 2) * N + j] + colpart[(int64_t)(t + 3) * N + j]);
-        for (; t < nparts; ++t) s += colpart[(int64_t)t * N + j];
+        const acc_t s = fold_partials(colpart, nparts, N, j);
         const acc_t e = expected_col[j] - s;
         f = !(fabs(e) <= Tcol[j]);
         colsum[j] = s;
