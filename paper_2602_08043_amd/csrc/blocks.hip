@@ -32,8 +32,8 @@ __global__ __launch_bounds__(256) void encode_blocks_rows_kernel(const void* __r
         for (int n = t * W + lane; n < n_end; n += 64) {
             const acc_t x = Unpack<T>::one(B, (int64_t)k * ldb + n);
             sum += x;
-            mx = x > mx ? x : mx;
-            mn = x < mn ? x : mn;
+            mx = fmax(mx, x);
+            mn = fmin(mn, x);
         }
         sum = wave_sum(sum);
         mx = wave_max(mx);
@@ -80,22 +80,22 @@ __global__ __launch_bounds__(256) void encode_blocks_rows_vec_kernel(const void*
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
                     sum += v[e];
-                    mx = v[e] > mx ? v[e] : mx;
-                    mn = v[e] < mn ? v[e] : mn;
+                    mx = fmax(mx, v[e]);
+                    mn = fmin(mn, v[e]);
                 }
             }
             if (cpb == 32) {
                 sum += __shfl_xor(sum, 16, WAVE);
                 const acc_t a = __shfl_xor(mx, 16, WAVE), b = __shfl_xor(mn, 16, WAVE);
-                mx = a > mx ? a : mx;
-                mn = b < mn ? b : mn;
+                mx = fmax(mx, a);
+                mn = fmin(mn, b);
             }
 #pragma unroll
             for (int off = 8; off >= 1; off >>= 1) {
                 sum += __shfl_xor(sum, off, WAVE);
                 const acc_t a = __shfl_xor(mx, off, WAVE), b = __shfl_xor(mn, off, WAVE);
-                mx = a > mx ? a : mx;
-                mn = b < mn ? b : mn;
+                mx = fmax(mx, a);
+                mn = fmin(mn, b);
             }
             if (ok && lane % cpb == 0) {
                 acc_t* q = part + (int64_t)(c / cpb) * 3 * K;
@@ -126,15 +126,15 @@ __global__ __launch_bounds__(256) void encode_blocks_cols_kernel(const void* __r
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             s[u] += x[u];
-            mx = x[u] > mx ? x[u] : mx;
-            mn = x[u] < mn ? x[u] : mn;
+            mx = fmax(mx, x[u]);
+            mn = fmin(mn, x[u]);
         }
     }
     for (; n < n_end; ++n) {
         const acc_t x = Unpack<T>::one(Bt, (int64_t)n * ldb + k);
         s[0] += x;
-        mx = x > mx ? x : mx;
-        mn = x < mn ? x : mn;
+        mx = fmax(mx, x);
+        mn = fmin(mn, x);
     }
     acc_t* q = part + (int64_t)t * 3 * K;
     q[k] = (s[0] + s[1]) + (s[2] + s[3]);
@@ -241,8 +241,8 @@ __global__ __launch_bounds__(256) void threshold_blocks_kernel(const void* __res
 #pragma unroll
                     for (int r = 0; r < TB_RW; ++r) {
                         sum[r] += a[j][r];
-                        mx[r] = a[j][r] > mx[r] ? a[j][r] : mx[r];
-                        mn[r] = a[j][r] < mn[r] ? a[j][r] : mn[r];
+                        mx[r] = fmax(mx[r], a[j][r]);
+                        mn[r] = fmin(mn[r], a[j][r]);
                     }
                 }
 #pragma unroll
@@ -395,8 +395,8 @@ __global__ __launch_bounds__(256) void threshold_blocks_vec_kernel(const void* _
 #pragma unroll
                             for (int e = 0; e < V; ++e) {
                                 sum[r] += av[r][c][e];
-                                mx[r] = av[r][c][e] > mx[r] ? av[r][c][e] : mx[r];
-                                mn[r] = av[r][c][e] < mn[r] ? av[r][c][e] : mn[r];
+                                mx[r] = fmax(mx[r], av[r][c][e]);
+                                mn[r] = fmin(mn[r], av[r][c][e]);
                             }
                     }
                 }

@@ -138,8 +138,8 @@ __global__ __launch_bounds__(1024) void encode_rows_kernel(const void* __restric
                     for (int e = 0; e < V; ++e) {
                         sum += v[u][e];
                         if constexpr (W) sum2 = fma((acc_t)((c + 64 * u) * V + e + 1), v[u][e], sum2);
-                        mx = v[u][e] > mx ? v[u][e] : mx;
-                        mn = v[u][e] < mn ? v[u][e] : mn;
+                        mx = fmax(mx, v[u][e]);
+                        mn = fmin(mn, v[u][e]);
                     }
             }
             for (; c < c_end; c += 64) {
@@ -150,8 +150,8 @@ __global__ __launch_bounds__(1024) void encode_rows_kernel(const void* __restric
                 for (int e = 0; e < V; ++e) {
                     sum += v[e];
                     if constexpr (W) sum2 = fma((acc_t)(c * V + e + 1), v[e], sum2);
-                    mx = v[e] > mx ? v[e] : mx;
-                    mn = v[e] < mn ? v[e] : mn;
+                    mx = fmax(mx, v[e]);
+                    mn = fmin(mn, v[e]);
                 }
             }
             done = nchunks * V;
@@ -162,8 +162,8 @@ __global__ __launch_bounds__(1024) void encode_rows_kernel(const void* __restric
                 acc_t x = Unpack<T>::one(row, n);
                 sum += x;
                 if constexpr (W) sum2 = fma((acc_t)(n + 1), x, sum2);
-                mx = x > mx ? x : mx;
-                mn = x < mn ? x : mn;
+                mx = fmax(mx, x);
+                mn = fmin(mn, x);
             }
         }
         sum = wave_sum(sum);
@@ -188,8 +188,8 @@ __global__ __launch_bounds__(1024) void encode_rows_kernel(const void* __restric
             for (int q = 1; q < WPR; ++q) {  // segments in order
                 sum += seg[wave + q][0];
                 sum2 += seg[wave + q][1];
-                mx = seg[wave + q][2] > mx ? seg[wave + q][2] : mx;
-                mn = seg[wave + q][3] < mn ? seg[wave + q][3] : mn;
+                mx = fmax(mx, seg[wave + q][2]);
+                mn = fmin(mn, seg[wave + q][3]);
             }
         }
     }
@@ -264,8 +264,8 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
                 for (int e = 0; e < V; ++e) {
                     sum[e] += v[e];
                     if constexpr (W) sum2[e] = fma(w, v[e], sum2[e]);
-                    mx[e] = v[e] > mx[e] ? v[e] : mx[e];
-                    mn[e] = v[e] < mn[e] ? v[e] : mn[e];
+                    mx[e] = fmax(mx[e], v[e]);
+                    mn[e] = fmin(mn[e], v[e]);
                 }
             }
         }
@@ -278,8 +278,8 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
             for (int e = 0; e < V; ++e) {
                 sum[e] += v[e];
                 if constexpr (W) sum2[e] = fma(w, v[e], sum2[e]);
-                mx[e] = v[e] > mx[e] ? v[e] : mx[e];
-                mn[e] = v[e] < mn[e] ? v[e] : mn[e];
+                mx[e] = fmax(mx[e], v[e]);
+                mn[e] = fmin(mn[e], v[e]);
             }
         }
     } else {
@@ -290,8 +290,8 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
                     acc_t x = Unpack<T>::one(Bt, (int64_t)n * ldb + k0 + e);
                     sum[e] += x;
                     if constexpr (W) sum2[e] = fma(wvec ? wvec[n] : (acc_t)(n + 1), x, sum2[e]);
-                    mx[e] = x > mx[e] ? x : mx[e];
-                    mn[e] = x < mn[e] ? x : mn[e];
+                    mx[e] = fmax(mx[e], x);
+                    mn[e] = fmin(mn[e], x);
                 }
             }
         }
@@ -316,8 +316,8 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
             for (int e = 0; e < V; ++e) {
                 sum[e] += red[w][0][e * PITCH + lane];
                 acc_t a = red[w][1][e * PITCH + lane], b = red[w][2][e * PITCH + lane];
-                mx[e] = a > mx[e] ? a : mx[e];
-                mn[e] = b < mn[e] ? b : mn[e];
+                mx[e] = fmax(mx[e], a);
+                mn[e] = fmin(mn[e], b);
                 if constexpr (W) sum2[e] += red[w][3][e * PITCH + lane];
             }
         // the block's results go back through the first area so that the global stores are contiguous
@@ -370,8 +370,8 @@ __global__ __launch_bounds__(256) void encode_cols_combine_kernel(const acc_t* _
             sum += p[k];
             if constexpr (W) sum2 += p[3 * (int64_t)K + k];
             const acc_t a = p[(int64_t)K + k], b = p[2 * (int64_t)K + k];
-            mx = a > mx ? a : mx;
-            mn = b < mn ? b : mn;
+            mx = fmax(mx, a);
+            mn = fmin(mn, b);
         }
     }
     red[0][grp][kl] = sum;
@@ -389,8 +389,8 @@ __global__ __launch_bounds__(256) void encode_cols_combine_kernel(const acc_t* _
             sum += red[0][g][kl];
             if constexpr (W) sum2 += red[3][g][kl];
             const acc_t a = red[1][g][kl], b = red[2][g][kl];
-            mx = a > mx ? a : mx;
-            mn = b < mn ? b : mn;
+            mx = fmax(mx, a);
+            mn = fmin(mn, b);
         }
         Be[k] = sum;
         if constexpr (W) Be2[k] = sum2;
@@ -461,16 +461,16 @@ __global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restr
                 sum += v0[e];
                 dot = fma(v0[e], b0[e], dot);
                 if constexpr (W) dot2 = fma(v0[e], Be2[(int64_t)c * V + e], dot2);
-                mx = v0[e] > mx ? v0[e] : mx;
-                mn = v0[e] < mn ? v0[e] : mn;
+                mx = fmax(mx, v0[e]);
+                mn = fmin(mn, v0[e]);
             }
 #pragma unroll
             for (int e = 0; e < V; ++e) {
                 sum += v1[e];
                 dot = fma(v1[e], b1[e], dot);
                 if constexpr (W) dot2 = fma(v1[e], Be2[(int64_t)(c + 64) * V + e], dot2);
-                mx = v1[e] > mx ? v1[e] : mx;
-                mn = v1[e] < mn ? v1[e] : mn;
+                mx = fmax(mx, v1[e]);
+                mn = fmin(mn, v1[e]);
             }
         }
         for (; c < nchunks; c += 64) {
@@ -483,8 +483,8 @@ __global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restr
                 sum += v0[e];
                 dot = fma(v0[e], b, dot);
                 if constexpr (W) dot2 = fma(v0[e], Be2[(int64_t)c * V + e], dot2);
-                mx = v0[e] > mx ? v0[e] : mx;
-                mn = v0[e] < mn ? v0[e] : mn;
+                mx = fmax(mx, v0[e]);
+                mn = fmin(mn, v0[e]);
             }
         }
         done = nchunks * V;
@@ -494,8 +494,8 @@ __global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restr
         sum += x;
         dot = fma(x, Be[k], dot);
         if constexpr (W) dot2 = fma(x, Be2[k], dot2);
-        mx = x > mx ? x : mx;
-        mn = x < mn ? x : mn;
+        mx = fmax(mx, x);
+        mn = fmin(mn, x);
     }
     sum = wave_sum(sum);
     dot = wave_sum(dot);
@@ -731,8 +731,8 @@ __global__ __launch_bounds__(256) void threshold_cols_finish_kernel(const acc_t*
         for (int u = 0; u < 8; ++u)
             if (s0 + u < nsplit) {
                 sum += v[u][0];
-                mx = v[u][1] > mx ? v[u][1] : mx;
-                mn = v[u][2] < mn ? v[u][2] : mn;
+                mx = fmax(mx, v[u][1]);
+                mn = fmin(mn, v[u][2]);
                 dot += v[u][3];
             }
     }
