@@ -101,3 +101,11 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    """There is no CPU fallback: loading a library that is not there raises, with the build command in the text."""
+    missing = str(tmp_path / "libvabft_not_built.so")
+    with pytest.raises(ImportError) as e:
+        vb.load(missing)
+    assert "has not been built" in str(e.value) and "no fallback" in str(e.value)
