@@ -457,7 +457,7 @@ double vabft_default_emax(int32_t dtype, int32_t K, int32_t N) {
         measured = 8.0e-18 * sqrt(n) + 5.2e-16;
     } else {
         paper = 5.0e-9 * sqrt(n) + 1.2e-7;
-        measured = 3.0e-9 * sqrt(n) + 3.8e-7;
+        measured = 3.0e-9 * sqrt(n) + 3.9e-7;
     }
     return paper > measured ? paper : measured;
 }

@@ -39,7 +39,7 @@ def test_status_strings_and_default_emax(lib):
     assert "workspace" in vb.status_string(vb.VABFT_EWORKSPACE)
     # larger of the paper's GPU law and the MI355X-calibrated law, n = max(K, N)
     for n in (128, 512, 4096, 8192, 65536):
-        paper, meas = 5.0e-9 * n ** 0.5 + 1.2e-7, 3.0e-9 * n ** 0.5 + 3.8e-7
+        paper, meas = 5.0e-9 * n ** 0.5 + 1.2e-7, 3.0e-9 * n ** 0.5 + 3.9e-7
         assert vb.vabft_default_emax("bf16", n, n) == pytest.approx(max(paper, meas))
         paper, meas = 1.0e-17 * n ** 0.5 + 2.5e-16, 8.0e-18 * n ** 0.5 + 5.2e-16
         assert vb.vabft_default_emax("f64", n, n) == pytest.approx(max(paper, meas))
