@@ -33,10 +33,15 @@ EXTRA_FLAGS = {
 
 def _run(cmd):
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
+    out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l and "--hip-link" not in l)
     if r.returncode != 0:
         raise RuntimeError("command failed: %s\n%s" % (" ".join(cmd), out))
     return out
+
+
+# Translation units whose kernels issue MFMAs and global -> LDS loads from inline assembly: their device
+# assembly is checked for pipeline hazards the compiler cannot pad (asm_lint.py).
+LINTED = ["gemm16_bf16_nn.hip", "gemm16_bf16_nt.hip", "gemm16_f16_nn.hip", "gemm16_f16_nt.hip"]
 
 
 def build_library(verbose: bool = True, jobs: int = 8) -> str:
@@ -45,14 +50,27 @@ def build_library(verbose: bool = True, jobs: int = 8) -> str:
     objs = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES]
 
     def compile_one(pair):
-        src, obj = pair
-        out = _run([hipcc, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj])
+        src, out_path = pair
+        mode = ["-S", "--cuda-device-only"] if out_path.endswith(".s") else ["-c"]
+        out = _run([hipcc, *FLAGS, *EXTRA_FLAGS.get(src, []), *mode, os.path.join(CSRC, src), "-o", out_path])
         if verbose and out.strip():
             print(out, file=sys.stderr)
-        return obj
+        return out_path
 
+    asms = [os.path.join(OBJ, s.replace(".hip", ".s")) for s in LINTED]
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        list(ex.map(compile_one, zip(SOURCES, objs)))
+        list(ex.map(compile_one, list(zip(SOURCES, objs)) + list(zip(LINTED, asms))))
+    sys.path.insert(0, PKG)
+    try:
+        import asm_lint
+    finally:
+        sys.path.pop(0)
+    problems = []
+    for a in asms:
+        with open(a) as f:
+            problems += asm_lint.lint(f.read())
+    if problems:
+        raise RuntimeError("pipeline hazards in the generated assembly:\n" + "\n".join(problems))
     out = _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     if verbose and out.strip():
         print(out, file=sys.stderr)

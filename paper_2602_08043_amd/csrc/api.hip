@@ -319,15 +319,19 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     }
     // the unguarded kernels need whole tiles and 16-byte aligned rows
     const int bk = p->dtype == VABFT_F8E4M3 ? 256 : (is16 ? 64 : 16);
-    const bool edge = (p->M % bm) || (p->N % bn) || (p->K % bk) || !a.a_vec_ok || !a.b_vec_ok || !a.c_vec_ok;
+    // (the whole-tile 16-bit kernels address a tile's rows with 32-bit byte offsets from a per-wavefront base)
+    const bool wide_rows = is16 && (p->lda > (1 << 24) || p->ldb > (1 << 24));
+    const bool edge =
+        (p->M % bm) || (p->N % bn) || (p->K % bk) || !a.a_vec_ok || !a.b_vec_ok || !a.c_vec_ok || wide_rows;
     // whole-tile kernels do the compare-and-flag step (and, if asked, the A-side pass) in-kernel
     const bool in_kernel_finalize = !edge;
     if (fused) {
-        // the fused 16-bit kernel caches the Be slices of the k-units a tile-column folds: at most 16
-        // (units of 128 k, 16 cache slots; the FP8 kernel: units of 256 k, 8 slots, B stored N x K)
+        // the fused 16-bit kernel caches the checksum panel of the k-units a tile-column folds: at most 16
+        // (units of 128 k, dealt round-robin to the tile-columns; the FP8 kernel: units of 256 k, 8 slots,
+        // B stored N x K)
         const bool fits16 = p->dtype == VABFT_F8E4M3
                                 ? (a.tiles_n >= 2 && p->K % 256 == 0 && p->transB && (p->K / 256) / a.tiles_n + 2 <= 8)
-                                : (a.tiles_n >= 2 && p->K % 128 == 0 && (p->K / 128) / a.tiles_n + 2 <= 16);
+                                : (p->K % 128 == 0 && (p->K / 128 + a.tiles_n - 1) / a.tiles_n <= 16);
         if (in_kernel_finalize && (!is16 || fits16)) {
             a.fused_stats = 1;
             a.Be = fused->d_Be;

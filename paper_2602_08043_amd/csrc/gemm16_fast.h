@@ -1,131 +1,716 @@
-// BF16 / FP16 GEMM main loop for whole-tile problems (M % 256 == 0, N % 256 == 0,
-// K % 64 == 0, 16-byte aligned rows): global memory -> LDS without passing through
-// registers (global_load_lds_dwordx4), fragments software-pipelined one k-step ahead of the
-// MFMAs, one workgroup barrier per 64-wide k-tile, and the loads of the tile after next
-// spread between the MFMAs so that the texture path never backs up into the MFMA issue.
+// BF16 / FP16 GEMM for whole-tile problems (M % 256 == 0, N % 256 == 0, K % 64 == 0, 16-byte aligned rows)
+// on v_mfma_f32_16x16x32: 256 x 256 x 64 tile per workgroup of 4 wavefronts (2 x 2), 128 x 128 per
+// wavefront = 8 x 8 MFMA tiles of 16 x 16, 256 accumulator registers, one wavefront per SIMD.
 //
-// LDS has 64 banks on gfx950 and serves 16 lanes of a ds_read_b128 per cycle, so 16
-// consecutive rows must land on 16 distinct 16-byte slots of a 256-byte window.
-// Layouts (per stage, 64 KiB, two stages):
-//   A tile, and B tile when B is stored N x K:  [256 rows][8 chunks of 16 B], chunk c of row r
-//       at position c ^ ((r >> 1) & 7); fragments by ds_read_b128.
-//   B tile when B is stored K x N:  [64 k][32 chunks of 16 B] (n contiguous), chunk c of row k
-//       at position c ^ (4 * (k & 3)); fragments by ds_read_b64_tr_b16, which hands lane i of a
+// Why the 16 x 16 x 32 instruction: on N(0,1)-like operands the chip is power-limited, not issue-limited, and
+// this shape moves half the accumulator bytes per flop of the 32 x 32 x 16 one (a register-only loop of it
+// sustains 2035 TFLOP/s at 2.04 GHz against 1792 at 1.78 GHz).
+//
+// The MFMA is issued with the operands swapped (D' = B^T A^T): lane l of a 16 x 16 result tile then owns
+// C row (l % 16) and the four consecutive columns 4 * (l / 16) + 0..3, so a row sum of the accumulator tile
+// (section 2.2 C^{r1'} = C r1, taken before quantisation: section 3.6 fused check) is in-register adds plus
+// two cross-lane adds.  Accumulator element (mi, ni, r) of a wavefront is
+//   C[row0 + wm*128 + mi*16 + lane%16][col0 + wn*128 + ni*16 + 4*(lane/16) + r].
+//
+// LDS (two stages per operand, 32 KiB each, [A0 | A1 | B0 | B1] so that the stages of an operand are an
+// instruction immediate apart):
+//   A tile, and B tile when B is stored N x K:  [256 rows][8 chunks of 16 B], chunk c of row r at position
+//       c ^ ((r >> 1) & 7); a 16 x 32 fragment is one ds_read_b128 (lane: row l%16, chunk 4*ks + l/16), whose
+//       16 lanes of a row group hit 16 distinct 16-byte slots of a 256-byte window.
+//   B tile when B is stored K x N:  [64 k][32 chunks of 16 B] (n contiguous), chunk c of row k at position
+//       c ^ 2*((k & 3) | 4*((k >> 3) & 1)); a fragment is two ds_read_b64_tr_b16, each handing lane i of a
 //       16-lane block the 4 k-consecutive values of column i of a 4(k) x 16(n) sub-tile.
-// Check-side work fused into this kernel (MODE >= 1):
-//   * row sums of the accumulator tile before quantisation (section 3.6 fused check);
-//   * optionally (FUSED) the A-side of Algorithm 1: every A fragment passes through registers
-//     on its way to the MFMA, so tile-column bn accumulates sum / max / min / dot-with-Be of
-//     the k-steps whose body index is congruent to bn modulo the number of tile-columns;
-//   * the compare-and-flag step: the last workgroup to finish a tile-row (an arrival ticket per
-//     tile-row) combines that row block's partials in a fixed order, evaluates the threshold
-//     in double precision, and writes rowsum, E, flags; the last row block writes nflag;
-//   * (MODE 2, 3) the position-weighted row sums C r2 of section 2.2, through the same partials;
-//   * (MODE 2, 4) the column sums c1 C of section 2.2, as per-tile-row partials for a later compare.
+// Global memory -> LDS without passing through registers (global_load_lds_dwordx4), issued from inline
+// assembly with a scalar base and a 32-bit lane offset: four loads share one M0 (LDS base) through their
+// immediate offsets, so a load costs one issue slot and the address arithmetic is four scalar adds per k-tile.
+//
+// The MFMAs are inline assembly with the accumulator tied to its register ("+a"): left to the register
+// allocator, a quarter of the 64 accumulator tiles changed registers every iteration and were copied
+// through the vector file.  The compiler's hazard handling does not see into them; the only hazards in
+// reach are at the ends of the loop and are padded by hand.
+//
+// Check-side work fused into this kernel (MODE >= 1): see gemm_tile32.h.  FUSED adds the A-side of Algorithm 1
+// on the matrix cores: tile-column bn folds the k-units (128 k) u = bn, bn + tiles_n, ... of its rows of A.
+// For those units a 16-column panel [1, Be_hi, Be_mid, Be_lo, 0 ...] (Be split into three pieces of the
+// input type, so that the FP32-accumulated products carry Be to FP32 precision) is multiplied like one more
+// B fragment: its result tile holds sum_k A[i][k] and the three partial dot products A[i] . Be.  Only max and
+// min of the row stay in the vector ALU, as packed 16-bit operations on the fragment registers.
 #pragma once
-#include "gemm16.h"
+#include "gemm_tile32.h"
 
 namespace vabft {
 
-typedef __attribute__((ext_vector_type(4))) short s16x4_t;
-
-namespace g16f {
-using namespace g16;
-typedef __attribute__((address_space(3))) unsigned char lds_u8;
-typedef const __attribute__((address_space(1))) unsigned char glb_u8;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) short s16x2_t;
+typedef __attribute__((ext_vector_type(2))) unsigned short u16x2_t;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 
-__device__ __forceinline__ raw16 lds_read16(const lds_u8* p) {
-    const u32x4_t v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4_t*>(p);
-    return __builtin_bit_cast(raw16, v);
+// v_mfma_f32_16x16x32 as inline assembly with the accumulator tied to its registers.  The compiler's hazard
+// handling does not see into it: a vector instruction that writes one of its operands must not sit within a
+// few issue slots in front of it (measured: a v_cndmask three slots ahead corrupted the product), and to the
+// compiler the statement has read its operands once it is issued, so the next vector instruction may get
+// their registers.  acc_a (the GEMM tiles, AGPRs): its operands only ever come from LDS reads, and nothing but
+// loads (whose results land later), scalar code and other MFMAs follows it.  acc_v (the statistics tiles,
+// amid ordinary vector code): eight idle issue slots behind it, and the caller puts five in front of a group.
+template <typename T> struct Mfma16x;
+template <> struct Mfma16x<bf16_t> {
+    static __device__ __forceinline__ void acc_a(f32x4_t& c, const raw16& a, const raw16& b) {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"
+                     : "+a"(c)
+                     : "v"(__builtin_bit_cast(u32x4_t, a)), "v"(__builtin_bit_cast(u32x4_t, b)));
+    }
+    static __device__ __forceinline__ void acc_v(f32x4_t& c, const raw16& a, const raw16& b) {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0\n\ts_nop 7"
+                     : "+v"(c)
+                     : "v"(__builtin_bit_cast(u32x4_t, a)), "v"(__builtin_bit_cast(u32x4_t, b)));
+    }
+};
+template <> struct Mfma16x<f16_t> {
+    static __device__ __forceinline__ void acc_a(f32x4_t& c, const raw16& a, const raw16& b) {
+        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0"
+                     : "+a"(c)
+                     : "v"(__builtin_bit_cast(u32x4_t, a)), "v"(__builtin_bit_cast(u32x4_t, b)));
+    }
+    static __device__ __forceinline__ void acc_v(f32x4_t& c, const raw16& a, const raw16& b) {
+        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0\n\ts_nop 7"
+                     : "+v"(c)
+                     : "v"(__builtin_bit_cast(u32x4_t, a)), "v"(__builtin_bit_cast(u32x4_t, b)));
+    }
+};
+
+namespace g16x {
+using namespace g16;
+using namespace g16f;
+constexpr int HALF = 32768;       // one operand stage
+constexpr int B_BASE = 2 * HALF;  // B stages behind the two A stages
+// FUSED: behind the operand stages, the panel [1, Be_hi, Be_mid, Be_lo] of every k32-step this tile-column
+// folds: per folded unit (slot) 4 steps x 4 panel rows x 32 k x 2 B = 1 KiB, at most 16 units
+constexpr int PANEL_OFFSET = LDS_BYTES;
+constexpr int PANEL_SLOTS = 16;
+constexpr int S_RED_X = PANEL_OFFSET + PANEL_SLOTS * 1024;  // 12 doubles: fold of the S1..S3 partials
+constexpr int SCALE_X = S_RED_X + 128;                      // 4 floats: per-wavefront max |Be| of the cached slices
+constexpr int LDS_BYTES_FUSED_X = SCALE_X + 64;
+
+// a wave-uniform pointer, made visibly so (the inline assembly below needs it in scalar registers)
+__device__ __forceinline__ const unsigned char* uniform_ptr(const unsigned char* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const unsigned char*>(((uint64_t)hi << 32) | lo);
+}
+// Pins two uniform pointers in scalar registers and keeps the following instructions clear of whatever produced
+// them: a scalar register written by the vector ALU (v_readfirstlane, v_readlane) must not be read by a memory
+// instruction within five issue slots.  The compiler pads that hazard for instructions it knows, but it cannot
+// see that the assembly statements below are memory instructions (measured: a load issued right behind the
+// v_readfirstlane of its base took a stale base and faulted).
+__device__ __forceinline__ void settle_bases(const unsigned char*& a, const unsigned char*& b) {
+    asm volatile("s_nop 4" : "+s"(a), "+s"(b));
+}
+// M0 <- LDS base of the next group of four loads (one issue slot must separate it from the load that uses it)
+__device__ __forceinline__ void set_m0(uint32_t lds_addr) { asm volatile("s_mov_b32 m0, %0" ::"s"(lds_addr)); }
+// 16 bytes per lane: global (scalar base + lane offset + IMM) -> LDS (M0 + IMM + lane * 16)
+template <int IMM> __device__ __forceinline__ void g2l16_m0(uint32_t voff, const unsigned char* sbase) {
+    static_assert(IMM >= 0 && IMM < 4096, "13-bit signed immediate");
+    asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(voff), "s"(sbase), "n"(IMM));
+}
+}  // namespace g16x
+
+// ---- epilogue pieces for the 16 x 16 accumulator layout -------------------------------------------------------
+
+// Fault injector on the accumulator registers (section 6.1 "Error injection").
+template <bool INJECT>
+__device__ __forceinline__ void gemm16x_inject(const GemmArgs& g, f32x4_t (&acc)[8][8], int row0, int col0, int wm,
+                                               int wn, int l16, int lq) {
+    using namespace g16;
+    if (INJECT) {
+        const InjectArgs& inj = g.inj;
+        if (inj.mode == 1) {
+            for (int e = 0; e < inj.n_list; ++e) {
+                const int fr = inj.d_list[3 * e], fc = inj.d_list[3 * e + 1], fb = inj.d_list[3 * e + 2];
+                if (fr < row0 || fr >= row0 + BM || fc < col0 || fc >= col0 + BN) continue;
+                if (fr >= g.M || fc >= g.N || fb < 0 || fb > 31) continue;
+                const int rl = fr - row0, cl = fc - col0;
+                const bool own = (rl >> 7) == wm && (cl >> 7) == wn && (rl & 15) == l16 && ((cl >> 2) & 3) == lq;
+                if (own) {
+                    const int idx = ((rl >> 4) & 7) * 32 + ((cl >> 4) & 7) * 4 + (cl & 3);
+                    float before = 0.f, after = 0.f;
+                    static_for<0, 8>([&](auto mi_c) {
+                        static_for<0, 8>([&](auto ni_c) {
+                            static_for<0, 4>([&](auto r_c) {
+                                constexpr int mi = decltype(mi_c)::value, ni = decltype(ni_c)::value,
+                                              r = decltype(r_c)::value;
+                                if (idx == mi * 32 + ni * 4 + r) {
+                                    before = acc[mi][ni][r];
+                                    after = flip_bit(before, fb);
+                                    acc[mi][ni][r] = after;
+                                }
+                            });
+                        });
+                    });
+                    log_fault(inj, fr, fc, fb, (double)before, (double)after);
+                }
+            }
+        } else if (inj.mode == 2) {
+            static_for<0, 8>([&](auto mi_c) {
+                static_for<0, 8>([&](auto ni_c) {
+                    static_for<0, 4>([&](auto r_c) {
+                        constexpr int mi = decltype(mi_c)::value, ni = decltype(ni_c)::value, r = decltype(r_c)::value;
+                        const int gi = row0 + wm * 128 + mi * 16 + l16;
+                        const int gj = col0 + wn * 128 + ni * 16 + 4 * lq + r;
+                        const int bit = bernoulli_bit(inj, gi, gj, g.N);
+                        if (bit >= 0) acc[mi][ni][r] = flip_and_log<float>(inj, acc[mi][ni][r], gi, gj, bit);
+                    });
+                });
+            });
+        }
+    }
 }
 
-// s_waitcnt lgkmcnt(0) only (vmcnt and expcnt fields left at their maxima)
-__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
-
-// Transposing 8-byte LDS read, issued as inline assembly: the compiler treats the intrinsic
-// form as possibly aliasing the asynchronous global -> LDS loads and would wait for ALL of
-// them (vmcnt(0)) in front of every such read.  The caller must wait for lgkmcnt before it
-// uses the result (LDS operations of a wavefront complete in order).
-template <int OFFSET> __device__ __forceinline__ uint64_t lds_read_tr16_b64(const lds_u8* p) {
-    static_assert(OFFSET >= 0 && OFFSET < 65536, "ds offset field is 16 bits");
-    uint64_t v;
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
-                 : "=v"(v)
-                 : "v"((uint32_t) reinterpret_cast<uintptr_t>(p)), "n"(OFFSET));
-    return v;
+// Row sums of the wavefront's accumulator tile, taken before quantisation: 31 in-register adds per row,
+// arranged pairwise, plus two cross-lane adds.  Lanes 0..15 leave the sum of row wm*128 + mi*16 + lane over
+// the wavefront's 128 columns in red[wn][row].
+__device__ __forceinline__ void gemm16x_rowsum_to_lds(const f32x4_t (&acc)[8][8], float* red, int wm, int wn, int l16,
+                                                      int lq) {
+    using namespace g16;
+#pragma unroll
+    for (int mi = 0; mi < 8; ++mi) {
+        float t[8];
+#pragma unroll
+        for (int ni = 0; ni < 8; ++ni) t[ni] = (acc[mi][ni][0] + acc[mi][ni][1]) + (acc[mi][ni][2] + acc[mi][ni][3]);
+        float s = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+        s += __shfl_xor(s, 16, WAVE);
+        s += __shfl_xor(s, 32, WAVE);
+        if (lq == 0) red[wn * BM + wm * 128 + mi * 16 + l16] = s;
+    }
 }
 
-// 16 bytes per lane, global -> LDS at (wave-uniform) lds_base + lane * 16
-__device__ __forceinline__ void g2l16(const void* gptr, lds_u8* lds_base) {
-    __builtin_amdgcn_global_load_lds((glb_u8*)gptr, (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+// Position-weighted row sums (section 2.2 C^{r2'} = C r2, r2 = [1..N]): sum_j (j + 1) acc[i][j].  Inside the
+// tile the weights are small compile-time constants; the offset of the lane's first column is applied once
+// to the plain partial sum.
+__device__ __forceinline__ void gemm16x_rowsum2_to_lds(const f32x4_t (&acc)[8][8], float* red2, int col0, int wm,
+                                                       int wn, int l16, int lq) {
+    using namespace g16;
+    const float w0 = (float)(col0 + wn * 128 + 4 * lq + 1);  // weight of the lane's first column
+#pragma unroll
+    for (int mi = 0; mi < 8; ++mi) {
+        float t1[8], t2[8];
+#pragma unroll
+        for (int ni = 0; ni < 8; ++ni) {
+            float a1 = 0.f, a2 = 0.f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                a1 += acc[mi][ni][r];
+                a2 = fmaf((float)(ni * 16 + r), acc[mi][ni][r], a2);
+            }
+            t1[ni] = a1;
+            t2[ni] = a2;
+        }
+        const float p1 = ((t1[0] + t1[1]) + (t1[2] + t1[3])) + ((t1[4] + t1[5]) + (t1[6] + t1[7]));
+        const float p2 = ((t2[0] + t2[1]) + (t2[2] + t2[3])) + ((t2[4] + t2[5]) + (t2[6] + t2[7]));
+        float s = fmaf(w0, p1, p2);
+        s += __shfl_xor(s, 16, WAVE);
+        s += __shfl_xor(s, 32, WAVE);
+        if (lq == 0) red2[wn * BM + wm * 128 + mi * 16 + l16] = s;
+    }
 }
 
-// Partials exchanged between workgroups (which may sit on different XCDs with private L2s) go
-// through device-scope relaxed atomic stores and loads: they are performed at the device's
-// coherence point, so no cache write-back / invalidate fence is needed around the ticket.
-__device__ __forceinline__ float ld_agent(const float* p) {
-    return __builtin_bit_cast(float, __hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED,
-                                                        __HIP_MEMORY_SCOPE_AGENT));
-}
-__device__ __forceinline__ void st_agent(float* p, float v) {
-    __hip_atomic_store(reinterpret_cast<uint32_t*>(p), __builtin_bit_cast(uint32_t, v), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
+// Column sums of the wavefront's accumulator tile (section 2.2 C^{c1'} = c1 C): the eight row blocks in
+// registers first (32 values per lane, index v = ni*4 + r), then a reduce-scatter butterfly over the 16 lanes
+// that hold the 16 rows of a block.  Lane l ends with the complete sums of values 2*(l%16) and 2*(l%16)+1.
+template <int NV> struct ColReduce16 {
+    static __device__ __forceinline__ void run(const float (&cur)[NV], int l16, float (&out)[2]) {
+        constexpr int H = NV / 2;
+        constexpr int BIT = NV == 32 ? 3 : NV == 16 ? 2 : NV == 8 ? 1 : 0;
+        const bool up = (l16 >> BIT) & 1;
+        float nxt[H];
+#pragma unroll
+        for (int i = 0; i < H; ++i) {
+            const float lo = cur[i], hi = cur[i + H];
+            const float keep = up ? hi : lo, send = up ? lo : hi;
+            nxt[i] = keep + __shfl_xor(send, 1 << BIT, WAVE);
+        }
+        if constexpr (H == 2) {
+            out[0] = nxt[0];
+            out[1] = nxt[1];
+        } else {
+            ColReduce16<H>::run(nxt, l16, out);
+        }
+    }
+};
+__device__ __forceinline__ void gemm16x_colsum_to_lds(const f32x4_t (&acc)[8][8], float* cred, int wm, int wn, int l16,
+                                                      int lq) {
+    using namespace g16;
+    float v[32];
+#pragma unroll
+    for (int ni = 0; ni < 8; ++ni)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            v[ni * 4 + r] = ((acc[0][ni][r] + acc[1][ni][r]) + (acc[2][ni][r] + acc[3][ni][r])) +
+                            ((acc[4][ni][r] + acc[5][ni][r]) + (acc[6][ni][r] + acc[7][ni][r]));
+    float out[2];
+    ColReduce16<32>::run(v, l16, out);
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int idx = 2 * l16 + e, ni = idx >> 2, r = idx & 3;
+        cred[wm * BN + wn * 128 + ni * 16 + 4 * lq + r] = out[e];
+    }
 }
 
-// element e (0..3) of the two selected dwords of a 16-byte fragment, as float
-template <typename T> __device__ __forceinline__ float frag_elem(uint32_t d0, uint32_t d1, int e);
-template <> __device__ __forceinline__ float frag_elem<bf16_t>(uint32_t d0, uint32_t d1, int e) {
-    const uint32_t d = e < 2 ? d0 : d1;
-    return __uint_as_float((e & 1) ? (d & 0xffff0000u) : (d << 16));
+// two accumulator values -> packed pair of output elements, round to nearest even (v_cvt_pk_bf16_f32 /
+// v_cvt_pk_f16_f32)
+template <typename T> __device__ __forceinline__ uint32_t pack2(float a, float b);
+template <> __device__ __forceinline__ uint32_t pack2<bf16_t>(float a, float b) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{a, b}, bf16x2_t));
 }
-template <> __device__ __forceinline__ float frag_elem<f16_t>(uint32_t d0, uint32_t d1, int e) {
-    const uint32_t d = e < 2 ? d0 : d1;
-    return Elem<f16_t>::to_acc((uint16_t)((e & 1) ? (d >> 16) : (d & 0xffffu)));
+template <> __device__ __forceinline__ uint32_t pack2<f16_t>(float a, float b) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{a, b}, f16x2_t));
 }
 
-// Be values the workgroup will need, cached in LDS behind the two operand stages: one slot of
-// 128 floats per folded unit u (k = 128*u - 16 .. 128*u + 111).
-constexpr int BE_CACHE_OFFSET = LDS_BYTES;
-constexpr int BE_CACHE_SLOTS = 16;
-// behind the cache: 12 doubles for the fold of the S1..S3 partials of an encode that deferred it
-constexpr int S_RED_OFFSET = LDS_BYTES + BE_CACHE_SLOTS * 128 * 4;
-constexpr int LDS_BYTES_FUSED = S_RED_OFFSET + 128;
-}  // namespace g16f
+// Quantise and store the wavefront's tile of C: each 16 x 128 slab passes through a private LDS buffer so
+// that global stores are 16 bytes per lane and 256 contiguous bytes per row (a lane owns 4 consecutive
+// columns of one row, which alone would give 8-byte pieces scattered over 16 rows).
+template <typename T>
+__device__ __forceinline__ void gemm16x_store_c(const GemmArgs& g, const f32x4_t (&acc)[8][8], unsigned char* smem,
+                                                int row0, int col0, int lane, int wm, int wn, int l16, int lq) {
+    // row pitch 272 B: the 8-byte writes of 16 rows x 2 column groups hit 32 distinct bank pairs
+    constexpr int PITCH = 272;
+    constexpr int SLAB = 16 * PITCH;
+    unsigned char* stage = smem + 4096 + (wm * 2 + wn) * (2 * SLAB);
+    uint16_t* __restrict__ C = reinterpret_cast<uint16_t*>(g.C);
+    const int srow = lane >> 4, schunk = lane & 15;
+#pragma unroll
+    for (int mi = 0; mi < 8; ++mi) {
+        unsigned char* sl = stage + (mi & 1) * SLAB;
+#pragma unroll
+        for (int ni = 0; ni < 8; ++ni) {
+            uint2 v;
+            v.x = pack2<T>(acc[mi][ni][0], acc[mi][ni][1]);
+            v.y = pack2<T>(acc[mi][ni][2], acc[mi][ni][3]);
+            *reinterpret_cast<uint2*>(sl + l16 * PITCH + ni * 32 + lq * 8) = v;
+        }
+        // LDS operations of one wavefront complete in order; only the compiler must not move the reads
+        // above the writes
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int r = srow + 4 * t;
+            const raw16 v = *reinterpret_cast<const raw16*>(sl + r * PITCH + schunk * 16);
+            const int gi = row0 + wm * 128 + mi * 16 + r;
+            const int gj = col0 + wn * 128 + schunk * 8;
+            // C is not read again by this kernel: non-temporal store
+            typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_st;
+            __builtin_nontemporal_store(__builtin_bit_cast(u32x4_st, v),
+                                        reinterpret_cast<u32x4_st*>(C + (int64_t)gi * g.ldc + gj));
+        }
+        asm volatile("" ::: "memory");
+    }
+}
 
-// Epilogue shared by the whole-tile kernels (16-bit and FP8 inputs; T is the OUTPUT element type): injector,
-// row sums (and weighted / column sums), publication of the partials, the compare-and-flag step in the last
-// workgroup of the tile-row, and the store of C.  st[mi] = (sum, dot with Be, max, min) of the A rows when FUSED.
-template <typename T, int MODE, bool FUSED>
-__device__ __forceinline__ void gemm16_fast_epilogue(const GemmArgs& g, f32x16_t (&acc)[4][4], float (&st)[4][4],
-                                                     unsigned char* smem, int bm, int bn, int row0, int col0, int tid,
-                                                     int lane, int wm, int wn, int l32, int lh) {
-    using namespace g16f;
+// ---- fused A-side statistics: helpers ---------------------------------------------------------------------
+
+// Running (max, min) of 16-bit floating-point values held two per dword.
+// BF16 has no packed max / min: with the bit patterns read as integers, non-negative values order like
+// signed integers and negative values order reversed, so three integer trackers suffice:
+//   smax = signed max, smin = signed min, umax = unsigned max;
+//   max = smax >= 0 ? smax : smin  (no non-negative value: the negative of smallest magnitude),
+//   min = umax has its sign bit ? umax : smin  (a negative value exists: the one of largest magnitude).
+template <typename T> struct MinMax16;
+template <> struct MinMax16<bf16_t> {
+    uint32_t smax, smin, umax;
+    __device__ __forceinline__ void init() {
+        smax = 0x80008000u;
+        smin = 0x7fff7fffu;
+        umax = 0u;
+    }
+    __device__ __forceinline__ void fold(uint32_t d) {
+        smax = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2_t, smax),
+                                                                     __builtin_bit_cast(s16x2_t, d)));
+        smin = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(s16x2_t, smin),
+                                                                     __builtin_bit_cast(s16x2_t, d)));
+        umax = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, umax),
+                                                                     __builtin_bit_cast(u16x2_t, d)));
+    }
+    // the tracker of the lane `off` away, combined kind by kind
+    __device__ __forceinline__ void merge_xor(int off) {
+        const uint32_t a = __shfl_xor(smax, off, WAVE), b = __shfl_xor(smin, off, WAVE), c = __shfl_xor(umax, off, WAVE);
+        smax = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2_t, smax),
+                                                                     __builtin_bit_cast(s16x2_t, a)));
+        smin = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(s16x2_t, smin),
+                                                                     __builtin_bit_cast(s16x2_t, b)));
+        umax = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, umax),
+                                                                     __builtin_bit_cast(u16x2_t, c)));
+    }
+    // the two halves of the trackers, then as floats
+    __device__ __forceinline__ void result(float& mx, float& mn) const {
+        const int a = (int)(short)(smax & 0xffffu), b = (int)(short)(smax >> 16);
+        const int c = (int)(short)(smin & 0xffffu), d = (int)(short)(smin >> 16);
+        const uint32_t e = umax & 0xffffu, f = umax >> 16;
+        const int sM = a > b ? a : b, sm = c < d ? c : d;
+        const uint32_t uM = e > f ? e : f;
+        const uint32_t bmx = (uint32_t)(sM >= 0 ? sM : sm) & 0xffffu;
+        const uint32_t bmn = (uM & 0x8000u) ? uM : ((uint32_t)sm & 0xffffu);
+        mx = __uint_as_float(bmx << 16);
+        mn = __uint_as_float(bmn << 16);
+    }
+};
+template <> struct MinMax16<f16_t> {
+    uint32_t vmax, vmin;
+    __device__ __forceinline__ void init() {
+        vmax = 0xfbfffbffu;  // -65504
+        vmin = 0x7bff7bffu;  // +65504
+    }
+    __device__ __forceinline__ void fold(uint32_t d) {
+        vmax = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(f16x2_t, vmax),
+                                                                     __builtin_bit_cast(f16x2_t, d)));
+        vmin = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(f16x2_t, vmin),
+                                                                     __builtin_bit_cast(f16x2_t, d)));
+    }
+    __device__ __forceinline__ void merge_xor(int off) {
+        const uint32_t a = __shfl_xor(vmax, off, WAVE), b = __shfl_xor(vmin, off, WAVE);
+        vmax = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(f16x2_t, vmax),
+                                                                     __builtin_bit_cast(f16x2_t, a)));
+        vmin = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(f16x2_t, vmin),
+                                                                     __builtin_bit_cast(f16x2_t, b)));
+    }
+    __device__ __forceinline__ void result(float& mx, float& mn) const {
+        const f16x2_t a = __builtin_bit_cast(f16x2_t, vmax), b = __builtin_bit_cast(f16x2_t, vmin);
+        mx = fmaxf((float)a[0], (float)a[1]);
+        mn = fminf((float)b[0], (float)b[1]);
+    }
+};
+
+// x as three pieces of the input type whose sum is x to (at least) FP32 precision
+template <typename T> __device__ __forceinline__ void split3(float x, uint16_t (&p)[3]) {
+    p[0] = Elem<T>::from_acc(x);
+    const float r1 = x - Elem<T>::to_acc(p[0]);
+    p[1] = Elem<T>::from_acc(r1);
+    const float r2 = r1 - Elem<T>::to_acc(p[1]);
+    p[2] = Elem<T>::from_acc(r2);
+}
+template <typename T> __device__ __forceinline__ uint16_t one16();
+template <> __device__ __forceinline__ uint16_t one16<bf16_t>() { return 0x3f80; }
+template <> __device__ __forceinline__ uint16_t one16<f16_t>() { return 0x3c00; }
+
+template <typename T, int TRANSB, int MODE, bool FUSED>
+__global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
+    using namespace g16x;
     constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE == 2 || MODE == 3;
     constexpr bool CSUM = MODE == 2 || MODE == 4;
-    gemm16_inject<INJECT>(g, acc, row0, col0, wm, wn, l32, lh);
+    static_assert(!FUSED || VERIFY, "fused statistics belong to the verified kernel");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    lds_u8* const lds = (lds_u8*)smem;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int l32 = lane & 31, lh = lane >> 5;
+    int bm, bn;
+    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
+    if (CSUM && blockIdx.x == 0 && tid == 0 && g.d_ncolflag) *g.d_ncolflag = 0;
+    if ((MODE == 5 || MODE == 2) && blockIdx.x == 0 && tid == 0 && g.block_mode) {
+        *g.d_nflag = 0;
+        *g.d_nblockflag = 0;
+    }
+    const int row0 = bm * BM, col0 = bn * BN;
+    const unsigned char* __restrict__ A = reinterpret_cast<const unsigned char*>(g.A);
+    const unsigned char* __restrict__ B = reinterpret_cast<const unsigned char*>(g.B);
+
+    f32x4_t acc[8][8];
+#pragma unroll
+    for (int mi = 0; mi < 8; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 8; ++ni)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[mi][ni][r] = 0.f;
+
+    // ---- global -> LDS: each wavefront issues 8 + 8 loads of 1 KiB per k-tile -----------------------------
+    // A (and an N x K B): load l covers rows wave*64 + 8l .. +7; lane sits at row lane/8, chunk position lane%8
+    // and fetches chunk (lane%8) ^ ((row>>1)&7), (row>>1)&7 = 4*(l&1) + lane/16.
+    // K x N B: load l covers k rows wave*16 + 2l, +1; lane sits at row lane/32, position lane%32 and fetches
+    // chunk (lane%32) ^ f(k) with k&3 = 2*(l&1) + lane/32, (k>>3)&1 = l>>2.
+    // Load l of a tile lands at LDS offset l*1024 of the wavefront's area: M0 holds the base of a group of
+    // four, the immediate (l&3)*1024 is added to both addresses, so the lane offset carries -(l&3)*1024.
+    const unsigned char* const a_base = uniform_ptr(A + (int64_t)(row0 + wave * 64) * g.lda * 2);
+    const unsigned char* const b_base = uniform_ptr(TRANSB ? B + (int64_t)(col0 + wave * 64) * g.ldb * 2
+                                                           : B + ((int64_t)(wave * 16) * g.ldb + col0) * 2);
+    uint32_t a_voff[8], b_voff[8];
+#pragma unroll
+    for (int l = 0; l < 8; ++l) {
+        const uint32_t rk = ((lane & 7) ^ (lane >> 4) ^ (4 * (l & 1))) << 4;
+        a_voff[l] = (uint32_t)((lane >> 3) + 8 * l) * (uint32_t)g.lda * 2 + rk - (l & 3) * 1024;
+        if (TRANSB) {
+            b_voff[l] = (uint32_t)((lane >> 3) + 8 * l) * (uint32_t)g.ldb * 2 + rk - (l & 3) * 1024;
+        } else {
+            const int f = 2 * ((2 * (l & 1) + lh) | (4 * (l >> 2)));
+            b_voff[l] = (uint32_t)(lh + 2 * l) * (uint32_t)g.ldb * 2 + ((l32 ^ f) << 4) - (l & 3) * 1024;
+        }
+    }
+    const int64_t b_ktile = TRANSB ? (int64_t)(BK * 2) : (int64_t)BK * g.ldb * 2;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+    const uint32_t a_dst = __builtin_amdgcn_readfirstlane(lds0 + wave * 8192);
+    const uint32_t b_dst = __builtin_amdgcn_readfirstlane(lds0 + B_BASE + wave * 8192);
+    // load l (0..7: A, 8..15: B) of the tile whose scalar bases are (ap, bp), into stage LS; M0 must hold the
+    // group's base (set_group)
+    auto set_group = [&](auto ls_c, auto l_c) {
+        constexpr int LS = decltype(ls_c)::value, l = decltype(l_c)::value;
+        set_m0((l < 8 ? a_dst : b_dst) + LS * HALF + ((l & 7) >> 2) * 4096);
+    };
+    auto issue_load = [&](auto l_c, const unsigned char* ap, const unsigned char* bp) {
+        constexpr int l = decltype(l_c)::value;
+        if constexpr (l < 8)
+            g2l16_m0<(l & 3) * 1024>(a_voff[l], ap);
+        else
+            g2l16_m0<(l & 3) * 1024>(b_voff[l - 8], bp);
+    };
+
+    // ---- LDS -> fragments ---------------------------------------------------------------------------------
+    const int f_swz = (l16 >> 1) & 7;
+    lds_u8* a_rd[2];  // [k32-step]: row wm*128 + l16, chunk 4*ks + lq; fragment mi and the stage are immediates
+    lds_u8* b_rd[8];  // N x K B: [k32-step] (first two);  K x N B: [ni]
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) a_rd[ks] = lds + (wm * 128 + l16) * 128 + (((ks * 4 + lq) ^ f_swz) << 4);
+    if (TRANSB) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            b_rd[q] = lds + B_BASE + (wn * 128 + l16) * 128 + ((((q & 1) * 4 + lq) ^ f_swz) << 4);
+    } else {
+        // 16-lane block lq reads the 4(k) x 16(n) sub-tile at k = 8*lq + s/4 (+4 for the second half),
+        // n = 16*ni + 4*(s%4), s = l16; f(k) of those rows is 2*((s/4) | 4*(lq&1))
+        const int k_l = 8 * lq + (l16 >> 2);
+        const int f = 2 * ((l16 >> 2) | (4 * (lq & 1)));
+#pragma unroll
+        for (int ni = 0; ni < 8; ++ni) {
+            const int chunk = wn * 16 + 2 * ni + ((l16 & 3) >> 1);
+            b_rd[ni] = lds + B_BASE + k_l * 512 + ((chunk ^ f) << 4) + 8 * (l16 & 1);
+        }
+    }
+    // Fragment read `op` of k32-step KS of stage S: 8 A fragments, then 8 B fragments (N x K B) or 16
+    // transposing 8-byte reads (K x N B: the low halves of all fragments, then the high halves).
+    constexpr int NRD = TRANSB ? 16 : 24;
+    auto frag_op = [&](auto s_c, auto ks_c, auto op_c, raw16 (&af)[8], raw16 (&bf)[8]) {
+        constexpr int S = decltype(s_c)::value, KS = decltype(ks_c)::value, op = decltype(op_c)::value;
+        if constexpr (op < 8) {
+            af[op] = lds_read16(a_rd[KS] + S * HALF + op * 2048);
+        } else if constexpr (TRANSB != 0) {
+            bf[op - 8] = lds_read16(b_rd[KS] + S * HALF + (op - 8) * 2048);
+        } else {
+            constexpr int ni = (op - 8) & 7, hi = (op - 8) >> 3;
+            const uint64_t v = lds_read_tr16_b64<S * HALF + KS * 16384 + hi * 2048>(b_rd[ni]);
+            bf[ni].w[2 * hi] = (uint32_t)v;
+            bf[ni].w[2 * hi + 1] = (uint32_t)(v >> 32);
+        }
+    };
+
+    // ---- fused A-side statistics (FUSED) ----------------------------------------------------------------
+    // Both wavefronts of a wm pair hold the same A fragments; wavefront wn takes fragments 4*wn .. 4*wn+3.
+    // sacc[j]: result tile of panel x fragment 4*wn + j; lanes 0..15 hold (sum, dot_hi, dot_mid, dot_lo) of
+    // row wm*128 + (4*wn + j)*16 + lane.
+    f32x4_t sacc[4];
+    MinMax16<T> mm[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        sacc[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        mm[j].init();
+    }
+    const lds_u8* const panel_rd = lds + PANEL_OFFSET + (l16 & 3) * 64 + lq * 16;
+    const lds_u8* const a_rd_st[2] = {a_rd[0] + wn * 8192, a_rd[1] + wn * 8192};
+    // The statistics of k32-step KS of the tile in stage S (step t of folded unit number hj): the wavefront's
+    // four fragments are read once more from LDS, so that the statistics do not lengthen the lives of the
+    // pipeline's fragment registers, and multiplied by the panel of that step.
+    auto stats_step = [&](auto s_c, auto ks_c, int hj) {
+        constexpr int S = decltype(s_c)::value, KS = decltype(ks_c)::value;
+        asm volatile("s_nop 4");  // the step's last MFMA has read its operands before vector code reuses them
+        raw16 xf = lds_read16(panel_rd + hj * 1024 + (2 * S + KS) * 256);
+        raw16 a[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] = lds_read16(a_rd_st[KS] + S * HALF + j * 2048);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) xf.w[d] = l16 < 4 ? xf.w[d] : 0u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) mm[j].fold(a[j].w[d]);
+        // vector code wrote the panel fragment (see Mfma16x): the idle slots are tied to its final value
+        u32x4_t xv = __builtin_bit_cast(u32x4_t, xf);
+        asm volatile("s_nop 4" : "+v"(xv));
+        xf = __builtin_bit_cast(raw16, xv);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) Mfma16x<T>::acc_v(sacc[j], xf, a[j]);
+    };
+
+    // One k32-step = 64 slots of one MFMA (16 cycles, four issue cycles).  Even slots issue fragment read
+    // slot/2 of the NEXT step (stage S, step KS, into the other register set).  With LBASE >= 0 the step
+    // carries loads LBASE .. LBASE+7 of the next tile into stage S^1: slot 8j + 1 issues load LBASE + j, and
+    // slots 0 and 32 move M0 to the group of four.
+    auto kstep = [&](auto s_c, auto ks_c, auto lbase_c, const raw16 (&af)[8], const raw16 (&bf)[8], raw16 (&naf)[8],
+                     raw16 (&nbf)[8], const unsigned char* ap, const unsigned char* bp) {
+        constexpr int S = decltype(s_c)::value, LBASE = decltype(lbase_c)::value;
+        if (!TRANSB) wait_lgkmcnt0();  // the assembly reads of (af, bf) issued during the previous step
+        static_for<0, 64>([&](auto slot_c) {
+            constexpr int slot = decltype(slot_c)::value;
+            constexpr int mi = slot >> 3, ni = slot & 7;
+            Mfma16x<T>::acc_a(acc[mi][ni], bf[ni], af[mi]);
+            __builtin_amdgcn_sched_barrier(0);  // MFMA first, the rest of the slot in its shadow
+            if constexpr ((slot & 1) == 0 && slot / 2 < NRD)
+                frag_op(s_c, ks_c, std::integral_constant<int, slot / 2>{}, naf, nbf);
+            if constexpr (LBASE >= 0 && (slot & 31) == 0)
+                set_group(std::integral_constant<int, S ^ 1>{}, std::integral_constant<int, LBASE + slot / 8>{});
+            if constexpr (LBASE >= 0 && (slot & 7) == 1)
+                issue_load(std::integral_constant<int, LBASE + slot / 8>{}, ap, bp);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I8 = std::integral_constant<int, 8>;
+
+    const int nk = g.K / BK;
+    raw16 af0[8], bf0[8], af1[8], bf1[8];
+    // first tile
+    {
+        const unsigned char* ap = a_base;
+        const unsigned char* bp = b_base;
+        settle_bases(ap, bp);
+        static_for<0, 16>([&](auto l_c) {
+            constexpr int l = decltype(l_c)::value;
+            if constexpr ((l & 3) == 0) {
+                set_group(I0{}, l_c);
+                asm volatile("s_nop 0");
+            }
+            issue_load(l_c, ap, bp);
+        });
+    }
+    int n_slots = 0;  // FUSED: number of k-units this tile-column folds
+    if (FUSED) {
+        // Panel cache: for slot j (unit u = bn + j*tiles_n), step t, k = 128u + 32t + q: rows
+        // (1, Be_hi, Be_mid, Be_lo) of 32 k each.  Be is scaled by a
+        // power of two sigma so that its pieces fit the input type's range (FP16); the dot product is scaled
+        // back when it is published.
+        const float* const Be = reinterpret_cast<const float*>(g.Be);
+        const int nunits = nk >> 1;
+        float m = 0.f;
+        for (int j = 0, u = bn; u < nunits && j < PANEL_SLOTS; ++j, u += g.tiles_n) {
+            n_slots = j + 1;
+            if (tid < 128) m = fmaxf(m, fabsf(Be[128 * u + tid]));
+        }
+        m = wave_max(m);
+        float* const s_scale = reinterpret_cast<float*>(smem + SCALE_X);
+        if (lane == 0) s_scale[wave] = m;
+        // S1..S3 still in partials: every workgroup folds them here, under the latency of its first tile
+        if (!g.S) fold_s_partials_to_lds(g.s_partial, g.s_nparts, tid, reinterpret_cast<double*>(smem + S_RED_X));
+        __syncthreads();
+        m = fmaxf(fmaxf(s_scale[0], s_scale[1]), fmaxf(s_scale[2], s_scale[3]));
+        // sigma = 2^(exponent(m) - 13): |Be / sigma| < 2^14 (BF16 shares FP32's exponent range: sigma = 1)
+        float inv_sigma = 1.f;
+        if (sizeof(T) == 2 && std::is_same<T, f16_t>::value && m > 0.f && m < 3.0e38f)
+            inv_sigma = ldexpf(1.f, 13 - ilogbf(m));
+        uint16_t* const panel = reinterpret_cast<uint16_t*>(smem + PANEL_OFFSET);
+        for (int j = 0, u = bn; j < n_slots; ++j, u += g.tiles_n) {
+            if (tid < 128) {
+                uint16_t p[3];
+                split3<T>(Be[128 * u + tid] * inv_sigma, p);
+                uint16_t* dst = panel + (j * 4 + (tid >> 5)) * 128 + (tid & 31);
+                dst[0] = one16<T>();
+                dst[32] = p[0];
+                dst[64] = p[1];
+                dst[96] = p[2];
+            }
+        }
+        if (tid == 0) s_scale[4] = 1.f / inv_sigma;
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    // the very first step multiplies register set 1 before any tile has been read into it: zeros
+#pragma unroll
+    for (int i = 0; i < 8; ++i) af1[i] = bf1[i] = raw16{{0u, 0u, 0u, 0u}};
+    asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");  // vector code wrote these operands: see Mfma16x
+
+    // Body of k-tile kt (stage kt & 1), from barrier to barrier: step (kt-1, 1) multiplies register set 1 while
+    // the fragments of (kt, 0) arrive in set 0, then step (kt, 0) multiplies set 0 while (kt, 1) arrives in set
+    // 1.  The 16 loads of tile kt+1 (clamped at the last tile; the reload is harmless) go to the other stage,
+    // whose last reads completed before the barrier that opened this body.  STATS: the tile belongs to a k-unit
+    // this tile-column folds (unit u = kt/2, its steps t = 2*(kt&1), +1: the statistics read the tile itself, not
+    // the pipeline's registers, so they are not one step behind).
+    auto tile_body = [&](auto s_c, auto st_c, int kt, int hj) {
+        constexpr bool STATS = decltype(st_c)::value != 0;
+        const int ktn = kt + 1 < nk ? kt + 1 : nk - 1;
+        const unsigned char* ap = uniform_ptr(a_base + (int64_t)ktn * (BK * 2));
+        const unsigned char* bp = uniform_ptr(b_base + ktn * b_ktile);
+        settle_bases(ap, bp);
+        kstep(s_c, I0{}, I0{}, af1, bf1, af0, bf0, ap, bp);  // step (kt-1, 1)
+        if constexpr (FUSED && STATS) stats_step(s_c, I0{}, hj);
+        kstep(s_c, I1{}, I8{}, af0, bf0, af1, bf1, ap, bp);  // step (kt, 0)
+        if constexpr (FUSED && STATS) stats_step(s_c, I1{}, hj);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+    };
+    if (FUSED) {
+        // Tiles are walked in units of two (so the stage parity stays a compile-time constant): plain units in
+        // an inner loop, the folded unit between two such loops.  K is a multiple of 128 here (the host checks).
+        const int nunits = nk >> 1;
+        int hu = bn, hj = 0;
+        int u = 0;
+        for (;;) {
+            const int stop = hu < nunits ? hu : nunits;
+            for (; u < stop; ++u) {
+                tile_body(I0{}, I0{}, 2 * u, 0);
+                tile_body(I1{}, I0{}, 2 * u + 1, 0);
+            }
+            if (u >= nunits) break;
+            tile_body(I0{}, I1{}, 2 * u, hj);
+            tile_body(I1{}, I1{}, 2 * u + 1, hj);
+            ++u;
+            hu += g.tiles_n;
+            ++hj;
+        }
+        if (!TRANSB) wait_lgkmcnt0();
+#pragma unroll
+        for (int mi = 0; mi < 8; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 8; ++ni) Mfma16x<T>::acc_a(acc[mi][ni], bf1[ni], af1[mi]);
+    } else {
+        int kt = 0;
+        for (; kt + 1 < nk; kt += 2) {
+            tile_body(I0{}, I0{}, kt, 0);
+            tile_body(I1{}, I0{}, kt + 1, 0);
+        }
+        if (kt < nk) tile_body(I0{}, I0{}, kt, 0);
+        if (!TRANSB) wait_lgkmcnt0();
+#pragma unroll
+        for (int mi = 0; mi < 8; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 8; ++ni) Mfma16x<T>::acc_a(acc[mi][ni], bf1[ni], af1[mi]);
+    }
+    // the MFMAs are opaque to the compiler's hazard handling: let the last results land before anything reads them
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+
+    // ---- epilogue -------------------------------------------------------------------------------------------
+    gemm16x_inject<INJECT>(g, acc, row0, col0, wm, wn, l16, lq);
     if (VERIFY) {
         float* red = reinterpret_cast<float*>(smem);                 // [2 wn][256 rows]
-        float* sred = reinterpret_cast<float*>(smem + SRED_OFFSET);  // [2 wn][4][256 rows]
+        float* sred = reinterpret_cast<float*>(smem + SRED_OFFSET);  // [4][256 rows]
         float* red2 = reinterpret_cast<float*>(smem + RED2_OFFSET);  // [2 wn][256 rows]
-        int* s_last = reinterpret_cast<int*>(smem + 2048);
-        gemm16_rowsum_to_lds(acc, red, wm, wn, l32, lh);
-        if (WSUM) gemm16_rowsum2_to_lds(acc, red2, col0, wm, wn, l32, lh);
         float* cred = reinterpret_cast<float*>(smem + CRED_OFFSET);  // [2 wm][256 columns]
-        if (CSUM) gemm16_colsum_to_lds(acc, cred, wm, wn, l32, lh);
+        gemm16x_rowsum_to_lds(acc, red, wm, wn, l16, lq);
+        if (WSUM) gemm16x_rowsum2_to_lds(acc, red2, col0, wm, wn, l16, lq);
+        if (CSUM) gemm16x_colsum_to_lds(acc, cred, wm, wn, l16, lq);
         if (FUSED) {
+            const float sigma = reinterpret_cast<const float*>(smem + SCALE_X)[4];
 #pragma unroll
-            for (int mi = 0; mi < 4; ++mi) {
-                const float s0 = st[mi][0] + __shfl_xor(st[mi][0], 32, WAVE);
-                const float s1 = st[mi][1] + __shfl_xor(st[mi][1], 32, WAVE);
-                const float s2 = fmaxf(st[mi][2], __shfl_xor(st[mi][2], 32, WAVE));
-                const float s3 = fminf(st[mi][3], __shfl_xor(st[mi][3], 32, WAVE));
-                if (lh == 0) {
-                    const int r = wm * 128 + mi * 32 + l32;
-                    sred[(wn * 4 + 0) * BM + r] = s0;
-                    sred[(wn * 4 + 1) * BM + r] = s1;
-                    sred[(wn * 4 + 2) * BM + r] = s2;
-                    sred[(wn * 4 + 3) * BM + r] = s3;
+            for (int j = 0; j < 4; ++j) {
+                // the four k-chunk lanes of a row hold partial (max, min); lanes 0..15 hold the panel's result
+                mm[j].merge_xor(16);
+                mm[j].merge_xor(32);
+                float mx, mn;
+                mm[j].result(mx, mn);
+                if (lq == 0) {
+                    const int r = wm * 128 + (4 * wn + j) * 16 + l16;
+                    const bool any = n_slots > 0;  // a tile-column beyond the last k-unit folds nothing
+                    sred[0 * BM + r] = sacc[j][0];
+                    sred[1 * BM + r] = sigma * (sacc[j][1] + (sacc[j][2] + sacc[j][3]));
+                    sred[2 * BM + r] = any ? mx : -3.402823466e+38f;
+                    sred[3 * BM + r] = any ? mn : 3.402823466e+38f;
                 }
             }
         }
@@ -140,426 +725,25 @@ __device__ __forceinline__ void gemm16_fast_epilogue(const GemmArgs& g, f32x16_t
         if (CSUM) reinterpret_cast<float*>(g.colpart)[(int64_t)bm * g.N + col0 + tid] = cred[tid] + cred[BN + tid];
         if (FUSED) {
             float* ap = apart + (int64_t)bn * 4 * g.M + gi;
-            st_agent(ap, sred[0 * BM + tid] + sred[4 * BM + tid]);
-            st_agent(ap + (int64_t)g.M, sred[1 * BM + tid] + sred[5 * BM + tid]);
-            st_agent(ap + 2 * (int64_t)g.M, fmaxf(sred[2 * BM + tid], sred[6 * BM + tid]));
-            st_agent(ap + 3 * (int64_t)g.M, fminf(sred[3 * BM + tid], sred[7 * BM + tid]));
+            st_agent(ap, sred[0 * BM + tid]);
+            st_agent(ap + (int64_t)g.M, sred[1 * BM + tid]);
+            st_agent(ap + 2 * (int64_t)g.M, sred[2 * BM + tid]);
+            st_agent(ap + 3 * (int64_t)g.M, sred[3 * BM + tid]);
         }
         // block-wise check: the partials are all this kernel leaves; a later kernel compares them per block
         const bool partials_only = MODE == 5 || (MODE == 2 && g.block_mode);
-        if (partials_only) {
-            __syncthreads();  // the store below reuses the LDS the reductions read
-            gemm16_store_c<T, false>(g, acc, smem, row0, col0, lane, wm, wn, l32, lh);
-            return;
-        }
-        // every thread's partials are performed (vmcnt(0)) before the workgroup takes this
-        // tile-row's arrival ticket.  These round trips are short because no workgroup has issued
-        // its C stores yet (all tiles finish together); behind the store burst they would each
-        // cost several microseconds, which is why the check runs before the store and not in its
-        // shadow.
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        if (tid == 0) *s_last = (atomicAdd(&g.tickets[bm], 1) == g.tiles_n - 1);
-        __syncthreads();
-        if (*s_last) {
-            // Combine the tile-column partials in tile order.  The device-scope loads are issued
-            // in batches of 16 tile-columns before anything is folded, so their latencies overlap.
-            // every batch of 16 is folded as a tree and lands in one of four rotating accumulators, themselves
-            // folded pairwise at the end: the rounding chain of a sum is log-like in the number of tile-columns
-            float rs4[4] = {0.f, 0.f, 0.f, 0.f}, rs24[4] = {0.f, 0.f, 0.f, 0.f}, sum4[4] = {0.f, 0.f, 0.f, 0.f},
-                  dot4[4] = {0.f, 0.f, 0.f, 0.f};
-            float mx = -3.402823466e+38f, mn = 3.402823466e+38f;
-            for (int t0 = 0; t0 < g.tiles_n; t0 += 16) {
-                float v[16][5];
-                float v2[16];
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int t = t0 + j < g.tiles_n ? t0 + j : g.tiles_n - 1;  // clamped duplicates are not folded
-                    v[j][0] = ld_agent(rowpart + (int64_t)t * g.M + gi);
-                    if (WSUM) v2[j] = ld_agent(rowpart2 + (int64_t)t * g.M + gi);
-                    if (FUSED) {
-                        const float* ap = apart + (int64_t)t * 4 * g.M + gi;
-                        v[j][1] = ld_agent(ap);
-                        v[j][2] = ld_agent(ap + (int64_t)g.M);
-                        v[j][3] = ld_agent(ap + 2 * (int64_t)g.M);
-                        v[j][4] = ld_agent(ap + 3 * (int64_t)g.M);
-                    }
-                }
-                // absent tile-columns count as the neutral element
-#pragma unroll
-                for (int j = 0; j < 16; ++j)
-                    if (!(t0 + j < g.tiles_n)) {
-                        v[j][0] = 0.f;
-                        if (WSUM) v2[j] = 0.f;
-                        v[j][1] = 0.f;
-                        v[j][2] = 0.f;
-                        v[j][3] = -3.402823466e+38f;
-                        v[j][4] = 3.402823466e+38f;
-                    }
-                float q[4], q2[4], qs[4], qd[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    q[j] = (v[4 * j][0] + v[4 * j + 1][0]) + (v[4 * j + 2][0] + v[4 * j + 3][0]);
-                    if (WSUM) q2[j] = (v2[4 * j] + v2[4 * j + 1]) + (v2[4 * j + 2] + v2[4 * j + 3]);
-                    if (FUSED) {
-                        qs[j] = (v[4 * j][1] + v[4 * j + 1][1]) + (v[4 * j + 2][1] + v[4 * j + 3][1]);
-                        qd[j] = (v[4 * j][2] + v[4 * j + 1][2]) + (v[4 * j + 2][2] + v[4 * j + 3][2]);
-                        mx = fmaxf(mx, fmaxf(fmaxf(v[4 * j][3], v[4 * j + 1][3]), fmaxf(v[4 * j + 2][3], v[4 * j + 3][3])));
-                        mn = fminf(mn, fminf(fminf(v[4 * j][4], v[4 * j + 1][4]), fminf(v[4 * j + 2][4], v[4 * j + 3][4])));
-                    }
-                }
-                const int slot = (t0 >> 4) & 3;  // x + 0 is exact: the other three accumulators stay as they are
-                const float b = (q[0] + q[1]) + (q[2] + q[3]);
-                const float b2 = WSUM ? (q2[0] + q2[1]) + (q2[2] + q2[3]) : 0.f;
-                const float bs = FUSED ? (qs[0] + qs[1]) + (qs[2] + qs[3]) : 0.f;
-                const float bd = FUSED ? (qd[0] + qd[1]) + (qd[2] + qd[3]) : 0.f;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    rs4[k] += slot == k ? b : 0.f;
-                    if (WSUM) rs24[k] += slot == k ? b2 : 0.f;
-                    if (FUSED) {
-                        sum4[k] += slot == k ? bs : 0.f;
-                        dot4[k] += slot == k ? bd : 0.f;
-                    }
-                }
-            }
-            const float rs = (rs4[0] + rs4[1]) + (rs4[2] + rs4[3]), rs2 = (rs24[0] + rs24[1]) + (rs24[2] + rs24[3]);
-            const float sum = (sum4[0] + sum4[1]) + (sum4[2] + sum4[3]), dot = (dot4[0] + dot4[1]) + (dot4[2] + dot4[3]);
-            float expv, thr;
-            if (FUSED) {
-                const double mu = (double)sum / (double)g.K;
-                double var = ((double)mx - mu) * (mu - (double)mn);
-                var = var > 0 ? var : 0;
-                const double* s_red = reinterpret_cast<const double*>(smem + S_RED_OFFSET);
-                const double S1 = g.S ? g.S[0] : folded_s(s_red, 0), S2 = g.S ? g.S[1] : folded_s(s_red, 1),
-                             S3 = g.S ? g.S[2] : folded_s(s_red, 2), dN = (double)g.N;
-                const double t_det = dN * fabs(mu) * S1;
-                const double t_var23 = g.c_sigma * sqrt(dN * mu * mu * S2 + dN * dN * var * S3);
-                const double t_var4 = g.c_sigma * sqrt(dN) * sqrt(var) * sqrt(S2);
-                expv = dot;
-                thr = (float)(g.e_max * (t_det + t_var23 + t_var4));
-                float* astat = reinterpret_cast<float*>(g.astat);
-                astat[3 * (int64_t)gi + 0] = mx;
-                astat[3 * (int64_t)gi + 1] = mn;
-                astat[3 * (int64_t)gi + 2] = (float)mu;
-                reinterpret_cast<float*>(const_cast<void*>(g.expected))[gi] = expv;
-                reinterpret_cast<float*>(const_cast<void*>(g.T))[gi] = thr;
-            } else {
-                expv = reinterpret_cast<const float*>(g.expected)[gi];
-                thr = reinterpret_cast<const float*>(g.T)[gi];
-            }
-            const float e = expv - rs;
-            const int f = !(fabsf(e) <= thr);
-            reinterpret_cast<float*>(g.rowsum)[gi] = rs;
-            if (WSUM && g.rowsum2) reinterpret_cast<float*>(g.rowsum2)[gi] = rs2;
-            reinterpret_cast<float*>(g.E)[gi] = e;
-            g.flags[gi] = f;
-            const int cnt = __syncthreads_count(f);
-            if (tid == 0) {
-                // this tile-row is done: reset its ticket, then one 64-bit atomic both counts the
-                // finished row blocks (high word) and accumulates the flagged rows (low word);
-                // whoever completes the count publishes nflag and leaves the counter zero
-                __hip_atomic_store(&g.tickets[bm], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                unsigned long long* done = reinterpret_cast<unsigned long long*>(g.tickets + ((g.tiles_m + 1) & ~1));
-                const unsigned long long old = atomicAdd(done, (1ull << 32) | (unsigned long long)(unsigned)cnt);
-                if ((int)(old >> 32) == g.tiles_m - 1) {
-                    *g.d_nflag = (int)(unsigned)(old & 0xffffffffull) + cnt;
-                    __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            }
-        }
+        if (!partials_only)
+            gemm_tile_row_check<WSUM, FUSED>(g, smem, reinterpret_cast<const double*>(smem + S_RED_X), bm, gi, tid);
         __syncthreads();  // the store below reuses the LDS the reductions read
     }
-    gemm16_store_c<T, false>(g, acc, smem, row0, col0, lane, wm, wn, l32, lh);
-}
-
-template <typename T, int TRANSB, int MODE, bool FUSED>
-__global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
-    using namespace g16f;
-    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE == 2 || MODE == 3;
-    constexpr bool CSUM = MODE == 2 || MODE == 4;
-    static_assert(!FUSED || VERIFY, "fused statistics belong to the verified kernel");
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    lds_u8* const lds = (lds_u8*)smem;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
-    const int l32 = lane & 31, lh = lane >> 5;
-    int bm, bn;
-    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
-    if (CSUM && blockIdx.x == 0 && tid == 0 && g.d_ncolflag) *g.d_ncolflag = 0;
-    if ((MODE == 5 || MODE == 2) && blockIdx.x == 0 && tid == 0 && g.block_mode) {
-        *g.d_nflag = 0;
-        *g.d_nblockflag = 0;
-    }
-    const int row0 = bm * BM, col0 = bn * BN;
-    const unsigned char* __restrict__ A = reinterpret_cast<const unsigned char*>(g.A);
-    const unsigned char* __restrict__ B = reinterpret_cast<const unsigned char*>(g.B);
-
-    f32x16_t acc[4][4];
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-
-    // ---- global -> LDS: each wavefront issues 8 + 8 loads of 1 KiB per k-tile -----------
-    // Addresses are a wave-uniform 64-bit base (scalar registers) plus a 32-bit lane offset.
-    // A (and N x K B): load i of a wavefront covers rows wave*64 + i*8 .. +7; lane l sits at row
-    // l/8, chunk position l%8, and fetches chunk (l%8) ^ ((row>>1)&7) with
-    // (row>>1)&7 = 4*(i&1) + l/16.  Two lane offsets (even / odd i) cover all loads.
-    const uint32_t rk_e = ((lane & 7) ^ (lane >> 4)) << 4, rk_o = ((lane & 7) ^ (lane >> 4) ^ 4) << 4;
-    const unsigned char* const a_base = A + (int64_t)(row0 + wave * 64) * g.lda * 2;
-    const uint32_t a_lane_e = (uint32_t)(lane >> 3) * (uint32_t)g.lda * 2 + rk_e;
-    const uint32_t a_lane_o = (uint32_t)(lane >> 3) * (uint32_t)g.lda * 2 + rk_o;
-    const int64_t a_step = 8 * g.lda * 2;
-    const unsigned char* b_base;
-    uint32_t b_lane_e, b_lane_o;
-    int64_t b_step;
-    if (TRANSB) {
-        b_base = B + (int64_t)(col0 + wave * 64) * g.ldb * 2;
-        b_lane_e = (uint32_t)(lane >> 3) * (uint32_t)g.ldb * 2 + rk_e;
-        b_lane_o = (uint32_t)(lane >> 3) * (uint32_t)g.ldb * 2 + rk_o;
-        b_step = 8 * g.ldb * 2;
-    } else {
-        // K x N B: load i covers k rows wave*16 + 2*i, +1; lane l sits at row l/32, chunk position
-        // l%32 and fetches chunk (l%32) ^ (4*(k&3)), k & 3 = (2*i + l/32) & 3.
-        b_base = B + ((int64_t)(wave * 16) * g.ldb + col0) * 2;
-        b_lane_e = (uint32_t)lh * (uint32_t)g.ldb * 2 + ((l32 ^ (4 * lh)) << 4);
-        b_lane_o = (uint32_t)lh * (uint32_t)g.ldb * 2 + ((l32 ^ (4 * (2 + lh))) << 4);
-        b_step = 2 * g.ldb * 2;
-    }
-    const int64_t b_ktile = TRANSB ? (int64_t)(BK * 2) : (int64_t)BK * g.ldb * 2;
-    lds_u8* const a_dst = lds + wave * (64 * 128);
-    lds_u8* const b_dst = lds + A_BYTES + (TRANSB ? wave * (64 * 128) : wave * (16 * 512));
-
-    // load `l` (0..7: A, 8..15: B) of the tile whose uniform bases are (ap, bp), into stage LS
-    auto issue_load = [&](auto ls_c, auto l_c, const unsigned char* ap, const unsigned char* bp) {
-        constexpr int LS = decltype(ls_c)::value, l = decltype(l_c)::value;
-        if constexpr (l < 8)
-            g2l16(ap + l * a_step + ((l & 1) ? a_lane_o : a_lane_e), a_dst + LS * STAGE + l * 1024);
-        else
-            g2l16(bp + (l - 8) * b_step + ((l & 1) ? b_lane_o : b_lane_e), b_dst + LS * STAGE + (l - 8) * 1024);
-    };
-
-    // ---- LDS -> fragments: loop-invariant lane addresses, everything else is an immediate ----
-    const int f_swz = (l32 >> 1) & 7;  // ((row >> 1) & 7) for row = 32*x + l32
-    lds_u8* a_rd[2][4];                // [stage][k-step]
-    lds_u8* b_rd[2][4];                // N x K B: [stage][k-step];  K x N B: [stage][ni]
-#pragma unroll
-    for (int st = 0; st < 2; ++st)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            a_rd[st][q] = lds + st * STAGE + (wm * 128 + l32) * 128 + (((q * 2 + lh) ^ f_swz) << 4);
-            if (TRANSB) {
-                b_rd[st][q] = lds + st * STAGE + A_BYTES + (wn * 128 + l32) * 128 + (((q * 2 + lh) ^ f_swz) << 4);
-            } else {
-                // 16-lane block b = lane/16 reads the 4(k) x 16(n) sub-tile at
-                //   k = 8*(b/2) + s/4 (+4 for the second half), n = 16*(b%2) + 4*(s%4), s = lane%16
-                const int t_s = lane & 15, t_b = lane >> 4;
-                const int t_k = 8 * (t_b >> 1) + (t_s >> 2);
-                const int t_n = wn * 128 + 16 * (t_b & 1) + 4 * (t_s & 3) + q * 32;
-                b_rd[st][q] = lds + st * STAGE + A_BYTES + t_k * 512 + (((t_n >> 3) ^ (4 * (t_k & 3))) << 4) +
-                              (t_n & 4) * 2;
-            }
-        }
-
-    // One fragment read operation `op` of k-step KS from stage S into (af, bf).  A k-step needs
-    // NRD operations: 4 ds_read_b128 for A, then 4 ds_read_b128 (N x K B) or 8 transposing
-    // 8-byte reads (K x N B: low halves first, then high halves).
-    constexpr int NRD = TRANSB ? 8 : 12;
-    auto frag_op = [&](auto s_c, auto ks_c, auto op_c, raw16 (&af)[4], raw16 (&bf)[4]) {
-        constexpr int S = decltype(s_c)::value, KS = decltype(ks_c)::value, op = decltype(op_c)::value;
-        if constexpr (op < 4) {
-            af[op] = lds_read16(a_rd[S][KS] + op * 4096);
-        } else if constexpr (TRANSB != 0) {
-            bf[op - 4] = lds_read16(b_rd[S][KS] + (op - 4) * 4096);
-        } else {
-            constexpr int ni = (op - 4) & 3, hi = (op - 4) >> 2;
-            const uint64_t v = lds_read_tr16_b64<(KS * 16 + 4 * hi) * 512>(b_rd[S][ni]);
-            bf[ni].w[2 * hi] = (uint32_t)v;
-            bf[ni].w[2 * hi + 1] = (uint32_t)(v >> 32);
-        }
-    };
-
-    // ---- fused A-side statistics (FUSED) ------------------------------------------------
-    // Both wavefronts of a wm pair hold the same A fragments; wavefront wn takes elements
-    // 4*wn .. 4*wn+3 of each 8-element fragment, so a lane accumulates, per mi, over
-    // k = kbase + 8*(lane/32) + 4*wn + 0..3 of row wm*128 + mi*32 + lane%32.
-    // st[mi] = (sum, dot with Be, max, min); bev[q] = the four Be values of k-step q of the body.
-    float st[4][4];
-    f32x4_t bev[2][4];  // [tile of the unit][k-step of the body]
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
-        st[mi][0] = 0.f;
-        st[mi][1] = 0.f;
-        st[mi][2] = -3.402823466e+38f;
-        st[mi][3] = 3.402823466e+38f;
-    }
-    const float* const Be = reinterpret_cast<const float*>(g.Be);
-    // Be values of folded unit number j of this workgroup (unit u = bn + j*tiles_n, tiles 2u and
-    // 2u+1), from the LDS cache filled in the prologue.  k-step q of body kb = 2u + t multiplies
-    // step (kb-1, 3) for q = 0 and (kb, q-1) otherwise, i.e. k = 128u - 16 + 64t + 16q + ...
-    auto load_bev = [&](int j) {
-        const float* slot = reinterpret_cast<const float*>(smem + BE_CACHE_OFFSET) + j * 128 + 8 * lh + 4 * wn;
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) bev[t][q] = *reinterpret_cast<const f32x4_t*>(slot + 64 * t + 16 * q);
-    };
-    uint32_t sd0 = 0, sd1 = 0;  // the two dwords of the current fragment that this wavefront folds
-    // `skip` (wave-uniform) keeps the all-zero fragments of the very first pass out of max / min
-    auto stats_elem = [&](const raw16 (&af)[4], auto t_c, auto q_c, auto slot_c, bool skip) {
-        constexpr int t = decltype(t_c)::value, q = decltype(q_c)::value, slot = decltype(slot_c)::value;
-        constexpr int mi = slot >> 2, e = slot & 3;
-        if constexpr (e == 0) {
-            // select by value (a conditional between the two array elements themselves would
-            // become a pointer select and push the fragment arrays out of registers)
-            const uint32_t lo0 = af[mi].w[0], lo1 = af[mi].w[1], hi0 = af[mi].w[2], hi1 = af[mi].w[3];
-            sd0 = wn ? hi0 : lo0;
-            sd1 = wn ? hi1 : lo1;
-        }
-        const float x = frag_elem<T>(sd0, sd1, e);
-        st[mi][0] += x;
-        st[mi][1] = fmaf(x, bev[t][q][e], st[mi][1]);
-        if constexpr (q == 0 && t == 0) {
-            st[mi][2] = fmaxf(st[mi][2], skip ? -3.402823466e+38f : x);
-            st[mi][3] = fminf(st[mi][3], skip ? 3.402823466e+38f : x);
-        } else {
-            st[mi][2] = fmaxf(st[mi][2], x);
-            st[mi][3] = fminf(st[mi][3], x);
-        }
-    };
-
-    // One k-step = 16 slots of one MFMA.  Slot i also issues fragment read i of the NEXT k-step
-    // (stage S, k-step KS, into the other register set) and, on odd slots when LBASE >= 0,
-    // global -> LDS load LBASE + i/2 of the next tile into stage S^1; with STATS it also folds one
-    // element per mi-slot of the fragments being multiplied into the A statistics.  Everything a
-    // slot issues besides its MFMA should fit under that MFMA's 32 cycles; a scheduling barrier
-    // closes every slot so the compiler keeps the interleaving.
-    auto kstep = [&](auto s_c, auto ks_c, auto lbase_c, auto stats_c, auto q_c, const raw16 (&af)[4],
-                     const raw16 (&bf)[4], raw16 (&naf)[4], raw16 (&nbf)[4], const unsigned char* ap,
-                     const unsigned char* bp, bool skip) {
-        constexpr int S = decltype(s_c)::value, LBASE = decltype(lbase_c)::value;
-        constexpr bool STATS = decltype(stats_c)::value != 0;
-        if (!TRANSB) wait_lgkmcnt0();  // the assembly reads of (af, bf) issued during the previous k-step
-        static_for<0, 16>([&](auto slot_c) {
-            constexpr int slot = decltype(slot_c)::value;
-            constexpr int mi = slot >> 2, ni = slot & 3;
-            acc[mi][ni] = Mfma16<T>::run(bf[ni], af[mi], acc[mi][ni]);
-            __builtin_amdgcn_sched_barrier(0);  // MFMA first, the rest of the slot in its shadow
-            if constexpr (slot < NRD) frag_op(s_c, ks_c, slot_c, naf, nbf);  // one read per slot, front-loaded
-            if constexpr (LBASE >= 0 && (slot & 1))
-                issue_load(std::integral_constant<int, S ^ 1>{}, std::integral_constant<int, LBASE + slot / 2>{}, ap,
-                           bp);
-            if constexpr (FUSED && STATS) stats_elem(af, s_c, q_c, slot_c, skip);
-            __builtin_amdgcn_sched_barrier(0);
-        });
-    };
-    using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
-    using I2 = std::integral_constant<int, 2>;
-    using I3 = std::integral_constant<int, 3>;
-    using I8 = std::integral_constant<int, 8>;
-    using IN = std::integral_constant<int, -1>;
-
-    const int nk = g.K / BK;
-    raw16 af0[4], bf0[4], af1[4], bf1[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) af1[i] = bf1[i] = raw16{{0u, 0u, 0u, 0u}};
-    static_for<0, 16>([&](auto l_c) { issue_load(I0{}, l_c, a_base, b_base); });
-    if (FUSED) {
-        // cache the Be slices of every unit this tile-column folds (the host guarantees they fit)
-        float* cache = reinterpret_cast<float*>(smem + BE_CACHE_OFFSET);
-        const int nunits = nk >> 1;
-        for (int j = 0, u = bn; u <= nunits && j < BE_CACHE_SLOTS; ++j, u += g.tiles_n) {
-            if (tid < 128) {
-                const int k = 128 * u - 16 + tid;
-                cache[j * 128 + tid] = (k >= 0 && k < g.K) ? Be[k] : 0.f;
-            }
-        }
-        // S1..S3 still in partials: every workgroup folds them here, under the latency of its first tile
-        if (!g.S) fold_s_partials_to_lds(g.s_partial, g.s_nparts, tid, reinterpret_cast<double*>(smem + S_RED_OFFSET));
-    }
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-
-    // One body per k-tile, running from barrier to barrier.  Global k-step j = 4*kt + ks
-    // multiplies register set j%2 and fetches the fragments of step j+1 into the other set.
-    // The barrier that publishes tile kt sits BEFORE the last k-step of tile kt-1, so that
-    // step's MFMAs cover the latency of the first fragment reads of tile kt (the very first
-    // pass multiplies zeros).  The 16 loads of tile kt+1 (clamped at the last tile; the reload
-    // is harmless) ride in the first two k-steps after the barrier; the stage they fill held
-    // tile kt-1, whose last reads completed before that barrier.  The body is instantiated for
-    // both stage parities so that every LDS offset is an instruction immediate, with and
-    // without the statistics.  (The stage parity of tile kt is kt & 1 = its position in a unit.)
-    auto tile_body = [&](auto s_c, auto st_c, int kt, bool skip) {
-        const int ktn = kt + 1 < nk ? kt + 1 : nk - 1;
-        const unsigned char* ap = a_base + (int64_t)ktn * (BK * 2);
-        const unsigned char* bp = b_base + ktn * b_ktile;
-        kstep(s_c, I0{}, I0{}, st_c, I0{}, af1, bf1, af0, bf0, ap, bp, skip);  // step (kt-1, 3)
-        kstep(s_c, I1{}, I8{}, st_c, I1{}, af0, bf0, af1, bf1, ap, bp, false);  // step (kt, 0)
-        kstep(s_c, I2{}, IN{}, st_c, I2{}, af1, bf1, af0, bf0, ap, bp, false);  // step (kt, 1)
-        kstep(s_c, I3{}, IN{}, st_c, I3{}, af0, bf0, af1, bf1, ap, bp, false);  // step (kt, 2)
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-    };
-    if (FUSED) {
-        // Tiles are walked in units of two (so the stage parity stays a compile-time constant).
-        // Tile-column bn folds the units u with u % tiles_n == bn into the statistics: plain
-        // units run in a branch-free inner loop, the folded unit in straight-line code between
-        // two such loops.  K is a multiple of 128 here (the host checks), so there is no odd tile.
-        const int nunits = nk >> 1;
-        int hu = bn, hj = 0;
-        int u = 0;
-        for (;;) {
-            const int stop = hu < nunits ? hu : nunits;
-            for (; u < stop; ++u) {
-                tile_body(I0{}, I0{}, 2 * u, false);
-                tile_body(I1{}, I0{}, 2 * u + 1, false);
-            }
-            if (u >= nunits) break;
-            load_bev(hj);
-            tile_body(I0{}, I1{}, 2 * u, u == 0);
-            tile_body(I1{}, I1{}, 2 * u + 1, false);
-            ++u;
-            hu += g.tiles_n;
-            ++hj;
-        }
-        // step (nk-1, 3) is the first k-step of the unit that would follow the last one
-        if (!TRANSB) wait_lgkmcnt0();
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = Mfma16<T>::run(bf1[ni], af1[mi], acc[mi][ni]);
-        if (hu == nunits) {
-            load_bev(hj);
-            static_for<0, 16>([&](auto slot_c) { stats_elem(af1, I0{}, I0{}, slot_c, false); });
-        }
-    } else {
-        int kt = 0;
-        for (; kt + 1 < nk; kt += 2) {
-            tile_body(I0{}, I0{}, kt, false);
-            tile_body(I1{}, I0{}, kt + 1, false);
-        }
-        if (kt < nk) tile_body(I0{}, I0{}, kt, false);
-        if (!TRANSB) wait_lgkmcnt0();
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = Mfma16<T>::run(bf1[ni], af1[mi], acc[mi][ni]);
-    }
-
-    // ---- epilogue -------------------------------------------------------------------------
-    gemm16_fast_epilogue<T, MODE, FUSED>(g, acc, st, smem, bm, bn, row0, col0, tid, lane, wm, wn, l32, lh);
+    gemm16x_store_c<T>(g, acc, smem, row0, col0, lane, wm, wn, l16, lq);
 }
 
 template <typename T, int TRANSB>
 static int gemm16_fast_launch_tb(const GemmArgs& a, int mode, hipStream_t st) {
     const dim3 grid(a.tiles_m * a.tiles_n), block(256);
     const int fused = a.fused_stats ? 1 : 0;
-    const size_t lds = fused ? g16f::LDS_BYTES_FUSED : g16::LDS_BYTES;
+    const size_t lds = fused ? g16x::LDS_BYTES_FUSED_X : g16::LDS_BYTES;
 #define VABFT_G16F_CASE(VF, FU)                                                                            \
     if (mode == VF && fused == FU) {                                                                       \
         auto kern = gemm16_fast_kernel<T, TRANSB, VF, FU != 0>;                                            \

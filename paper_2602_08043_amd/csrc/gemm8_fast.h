@@ -21,7 +21,7 @@
 //     takes 16 of them, four per slot (convert, sum, FMA with Be, max, min); the Be values of a k-step are read
 //     from the LDS cache when the k-step starts.
 #pragma once
-#include "gemm16_fast.h"
+#include "gemm_tile32.h"
 
 namespace vabft {
 
