@@ -25,10 +25,13 @@
  *   - Return value: a vabft_status.  Argument errors are detected on the host before
  *     anything is launched (null pointer, non-positive size, leading dimension
  *     smaller than the row length, unknown dtype, workspace too small).
- *   - Calls that share a workspace must be ordered on one stream.  The first bytes of the
- *     workspace hold arrival counters that must be zero when a call starts: zero-fill the
+ *   - Calls that share a workspace must be ordered on one stream.  The head of the
+ *     workspace holds arrival counters that must be zero when a call starts: zero-fill the
  *     workspace once after allocating it (vabft_workspace_init, or any fill); every call
  *     leaves the counters zero again.
+ *   - A workspace sized for one problem serves every problem with the same dtype, transB, N
+ *     and K and at most as many rows M: what vabft_encode leaves in it (the deferred partials
+ *     of S1..S3) sits at a place that depends on B's shape only.
  */
 #ifndef VABFT_H
 #define VABFT_H
@@ -119,7 +122,8 @@ double vabft_default_emax(int32_t dtype, int32_t K, int32_t N);
  * folded by the last workgroup to finish (partials and an arrival counter in the workspace), so
  * the call needs the workspace (vabft_workspace_bytes, zero-filled once) for either layout of B.
  * d_S may be NULL: then the fold is deferred -- S1..S3 stay as the per-workgroup partials in the
- * workspace, where they remain valid until the next encode call on that workspace, and
+ * workspace, where they remain valid until the next encode call (vabft_encode, vabft_encode_weighted,
+ * vabft_encode_a) on that workspace, for GEMMs with any number of rows M, and
  * vabft_gemm_verified_fused called with d_S = NULL folds them itself (same order, same bits).
  * This takes the arrival-counter round trips out of the encode's tail. */
 int vabft_encode(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S,
@@ -232,7 +236,9 @@ int vabft_locate_correct(const vabft_problem* p, void* dC, const void* d_expecte
 /* c1 A and the column statistics of A.  One streaming pass over A.
  *   d_eA       [K] acc : sum_m A[m][k]
  *   d_acolstat [3K] acc: (max, min, mean) of column k of A
- *   d_SA       [3] double: S1, S2, S3 of Algorithm 1 formed from the columns of A */
+ *   d_SA       [3] double: S1, S2, S3 of Algorithm 1 formed from the columns of A
+ * The call uses the workspace area in which an encode of B with d_S = NULL leaves its partials: such a
+ * deferred fold is lost if this call comes between that encode and its fused GEMM. */
 int vabft_encode_a(const vabft_problem* p, const void* dA, void* d_eA, void* d_acolstat,
                    double* d_SA, void* d_workspace, size_t workspace_bytes, void* stream);
 

@@ -181,30 +181,32 @@ static void tile_shape(int dtype, int* bm, int* bn) {
     }
 }
 
-// Workspace layout: [tickets: tiles_m int32 + one 64-bit counter, rounded to 256 B][S area: three doubles
-// (the fold of the partials, when a kernel of its own has to make it) at +0, the per-workgroup partials of
-// S1..S3 of the last encode at +64][scratch].
+// Workspace layout: [S area][tickets][scratch].
+// S area (its place and size depend on B's shape only, never on M, so an encode of B stays valid for GEMMs
+// with any number of rows): three doubles at +0 (the fold of the partials, when a kernel of its own has to
+// make it), the encode's arrival counter at +32, the per-workgroup partials of S1..S3 of the last encode at
+// +64, rounded up to 256 B.
+// Tickets: tiles_m int32 arrival counters + one 64-bit counter, rounded to 256 B.  They must be zero between
+// launches: the kernels leave them zero, vabft_workspace_init zeroes them the first time.
 // The scratch area holds, for the GEMM, in units of tiles_n * M accumulator words: 16-bit
 // types rowpart [0,1), apart [1,5), rowpart2 [5,6); wide types (two row-sum partials per
 // tile-column) rowpart [0,2), rowpart2 [2,4), apart [4,8); then the column-sum partials.  The
 // encode of an N x K B keeps its column partials there; the calls are ordered on one stream,
-// so they share it.  The tickets must be zero between
-// launches: the kernels leave them zero, vabft_workspace_init zeroes them the first time.
-static size_t s_area_offset(const vabft_problem* p) {
+// so they share it.
+static size_t s_area_bytes(const vabft_problem* p) {
+    return round_up(64 + (size_t)s_partial_count(p) * 3 * sizeof(double), 256);
+}
+static size_t tickets_offset(const vabft_problem* p) { return s_area_bytes(p); }
+// everything in front of the scratch area
+static size_t tickets_bytes(const vabft_problem* p) {
     int bm, bn;
     tile_shape(p->dtype, &bm, &bn);
     const size_t tiles_m = ((size_t)p->M + bm - 1) / bm;
-    return round_up((tiles_m + 4) * sizeof(int32_t), 256);
+    return tickets_offset(p) + round_up((tiles_m + 4) * sizeof(int32_t), 256);
 }
-// everything in front of the scratch area
-static size_t tickets_bytes(const vabft_problem* p) {
-    return s_area_offset(p) + round_up(64 + (size_t)s_partial_count(p) * 3 * sizeof(double), 256);
-}
-static double* s_folded(const vabft_problem* p, void* ws) {
-    return reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(ws) + s_area_offset(p));
-}
-static double* s_partials(const vabft_problem* p, void* ws) {
-    return reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(ws) + s_area_offset(p) + 64);
+static double* s_folded(const vabft_problem*, void* ws) { return reinterpret_cast<double*>(ws); }
+static double* s_partials(const vabft_problem*, void* ws) {
+    return reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(ws) + 64);
 }
 
 __global__ __launch_bounds__(256) void fold_s_kernel(const double* __restrict__ partial, int count,
@@ -218,12 +220,9 @@ void fold_s_launch(const double* s_partial, int count, double* S, hipStream_t st
     fold_s_kernel<<<1, 256, 0, st>>>(s_partial, count, S);
 }
 
-// the encode's arrival counter: the last of the spare words behind the GEMM's tickets
-static int32_t* encode_ticket(const vabft_problem* p, void* ws) {
-    int bm, bn;
-    tile_shape(p->dtype, &bm, &bn);
-    const size_t tiles_m = ((size_t)p->M + bm - 1) / bm;
-    return reinterpret_cast<int32_t*>(ws) + tiles_m + 3;
+// the encode's arrival counter (in the S area's header)
+static int32_t* encode_ticket(const vabft_problem*, void* ws) {
+    return reinterpret_cast<int32_t*>(reinterpret_cast<unsigned char*>(ws) + 32);
 }
 
 size_t gemm_workspace_bytes(const vabft_problem* p) {
@@ -272,7 +271,7 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     a.b_vec_ok = aligned_to(dB, 16) && (p->ldb * eb) % 16 == 0;
     a.c_vec_ok = aligned_to(dC, 16) && (p->ldc * out_bytes(p->dtype)) % 16 == 0;
     unsigned char* wsb = reinterpret_cast<unsigned char*>(ws);
-    a.tickets = reinterpret_cast<int32_t*>(wsb);
+    a.tickets = ws ? reinterpret_cast<int32_t*>(wsb + tickets_offset(p)) : nullptr;
     a.rowpart = ws ? wsb + tickets_bytes(p) : nullptr;
     a.apart = ws ? wsb + tickets_bytes(p) + (size_t)a.tiles_n * p->M * ab * (is16 ? 1 : 4) : nullptr;
     // weighted partials: behind rowpart + apart (16-bit) resp. behind the two plain partials (wide)

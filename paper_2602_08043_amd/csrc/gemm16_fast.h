@@ -52,8 +52,9 @@ typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 // few issue slots in front of it (measured: a v_cndmask three slots ahead corrupted the product), and to the
 // compiler the statement has read its operands once it is issued, so the next vector instruction may get
 // their registers.  acc_a (the GEMM tiles, AGPRs): its operands only ever come from LDS reads, and nothing but
-// loads (whose results land later), scalar code and other MFMAs follows it.  acc_v (the statistics tiles,
-// amid ordinary vector code): eight idle issue slots behind it, and the caller puts five in front of a group.
+// loads (whose results land later), scalar code and other MFMAs follows it.  acc_v4 (the four statistics tiles,
+// VGPRs, amid ordinary vector code): eight idle issue slots behind the group, and the caller puts five in
+// front of it.
 template <typename T> struct Mfma16x;
 template <> struct Mfma16x<bf16_t> {
     static __device__ __forceinline__ void acc_a(f32x4_t& c, const raw16& a, const raw16& b) {
@@ -61,10 +62,15 @@ template <> struct Mfma16x<bf16_t> {
                      : "+a"(c)
                      : "v"(__builtin_bit_cast(u32x4_t, a)), "v"(__builtin_bit_cast(u32x4_t, b)));
     }
-    static __device__ __forceinline__ void acc_v(f32x4_t& c, const raw16& a, const raw16& b) {
-        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0\n\ts_nop 7"
-                     : "+v"(c)
-                     : "v"(__builtin_bit_cast(u32x4_t, a)), "v"(__builtin_bit_cast(u32x4_t, b)));
+    // c[j] += x * b[j], j = 0..3, as one statement (nothing can be scheduled between the four)
+    static __device__ __forceinline__ void acc_v4(f32x4_t (&c)[4], const raw16& x, const raw16 (&b)[4]) {
+        asm volatile(
+            "v_mfma_f32_16x16x32_bf16 %0, %4, %5, %0\n\tv_mfma_f32_16x16x32_bf16 %1, %4, %6, %1\n\t"
+            "v_mfma_f32_16x16x32_bf16 %2, %4, %7, %2\n\tv_mfma_f32_16x16x32_bf16 %3, %4, %8, %3\n\ts_nop 7"
+            : "+v"(c[0]), "+v"(c[1]), "+v"(c[2]), "+v"(c[3])
+            : "v"(__builtin_bit_cast(u32x4_t, x)), "v"(__builtin_bit_cast(u32x4_t, b[0])),
+              "v"(__builtin_bit_cast(u32x4_t, b[1])), "v"(__builtin_bit_cast(u32x4_t, b[2])),
+              "v"(__builtin_bit_cast(u32x4_t, b[3])));
     }
 };
 template <> struct Mfma16x<f16_t> {
@@ -73,10 +79,14 @@ template <> struct Mfma16x<f16_t> {
                      : "+a"(c)
                      : "v"(__builtin_bit_cast(u32x4_t, a)), "v"(__builtin_bit_cast(u32x4_t, b)));
     }
-    static __device__ __forceinline__ void acc_v(f32x4_t& c, const raw16& a, const raw16& b) {
-        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0\n\ts_nop 7"
-                     : "+v"(c)
-                     : "v"(__builtin_bit_cast(u32x4_t, a)), "v"(__builtin_bit_cast(u32x4_t, b)));
+    static __device__ __forceinline__ void acc_v4(f32x4_t (&c)[4], const raw16& x, const raw16 (&b)[4]) {
+        asm volatile(
+            "v_mfma_f32_16x16x32_f16 %0, %4, %5, %0\n\tv_mfma_f32_16x16x32_f16 %1, %4, %6, %1\n\t"
+            "v_mfma_f32_16x16x32_f16 %2, %4, %7, %2\n\tv_mfma_f32_16x16x32_f16 %3, %4, %8, %3\n\ts_nop 7"
+            : "+v"(c[0]), "+v"(c[1]), "+v"(c[2]), "+v"(c[3])
+            : "v"(__builtin_bit_cast(u32x4_t, x)), "v"(__builtin_bit_cast(u32x4_t, b[0])),
+              "v"(__builtin_bit_cast(u32x4_t, b[1])), "v"(__builtin_bit_cast(u32x4_t, b[2])),
+              "v"(__builtin_bit_cast(u32x4_t, b[3])));
     }
 };
 
@@ -535,8 +545,7 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         u32x4_t xv = __builtin_bit_cast(u32x4_t, xf);
         asm volatile("s_nop 4" : "+v"(xv));
         xf = __builtin_bit_cast(raw16, xv);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) Mfma16x<T>::acc_v(sacc[j], xf, a[j]);
+        Mfma16x<T>::acc_v4(sacc, xf, a);
     };
 
     // One k32-step = 64 slots of one MFMA (16 cycles, four issue cycles).  Even slots issue fragment read
@@ -589,27 +598,36 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         // back when it is published.
         const float* const Be = reinterpret_cast<const float*>(g.Be);
         const int nunits = nk >> 1;
-        float m = 0.f;
-        for (int j = 0, u = bn; u < nunits && j < PANEL_SLOTS; ++j, u += g.tiles_n) {
-            n_slots = j + 1;
-            if (tid < 128) m = fmaxf(m, fabsf(Be[128 * u + tid]));
+        if (bn < nunits) {
+            n_slots = (nunits - bn + g.tiles_n - 1) / g.tiles_n;
+            n_slots = n_slots < PANEL_SLOTS ? n_slots : PANEL_SLOTS;
         }
-        m = wave_max(m);
+        // the Be values of this thread (k = 128u + tid of every folded unit), all loads in flight together
+        float bek[PANEL_SLOTS];
+#pragma unroll
+        for (int j = 0; j < PANEL_SLOTS; ++j)
+            bek[j] = (j < n_slots && tid < 128) ? Be[128 * (bn + j * g.tiles_n) + tid] : 0.f;
         float* const s_scale = reinterpret_cast<float*>(smem + SCALE_X);
-        if (lane == 0) s_scale[wave] = m;
         // S1..S3 still in partials: every workgroup folds them here, under the latency of its first tile
         if (!g.S) fold_s_partials_to_lds(g.s_partial, g.s_nparts, tid, reinterpret_cast<double*>(smem + S_RED_X));
-        __syncthreads();
-        m = fmaxf(fmaxf(s_scale[0], s_scale[1]), fmaxf(s_scale[2], s_scale[3]));
-        // sigma = 2^(exponent(m) - 13): |Be / sigma| < 2^14 (BF16 shares FP32's exponent range: sigma = 1)
+        // sigma = 2^(exponent(max |Be|) - 13): |Be / sigma| < 2^14 (BF16 shares FP32's exponent range: sigma = 1)
         float inv_sigma = 1.f;
-        if (sizeof(T) == 2 && std::is_same<T, f16_t>::value && m > 0.f && m < 3.0e38f)
-            inv_sigma = ldexpf(1.f, 13 - ilogbf(m));
+        if constexpr (std::is_same<T, f16_t>::value) {
+            float m = 0.f;
+#pragma unroll
+            for (int j = 0; j < PANEL_SLOTS; ++j) m = fmaxf(m, fabsf(bek[j]));
+            m = wave_max(m);
+            if (lane == 0) s_scale[wave] = m;
+            __syncthreads();
+            m = fmaxf(fmaxf(s_scale[0], s_scale[1]), fmaxf(s_scale[2], s_scale[3]));
+            if (m > 0.f && m < 3.0e38f) inv_sigma = ldexpf(1.f, 13 - ilogbf(m));
+        }
         uint16_t* const panel = reinterpret_cast<uint16_t*>(smem + PANEL_OFFSET);
-        for (int j = 0, u = bn; j < n_slots; ++j, u += g.tiles_n) {
-            if (tid < 128) {
+#pragma unroll
+        for (int j = 0; j < PANEL_SLOTS; ++j) {
+            if (j < n_slots && tid < 128) {
                 uint16_t p[3];
-                split3<T>(Be[128 * u + tid] * inv_sigma, p);
+                split3<T>(bek[j] * inv_sigma, p);
                 uint16_t* dst = panel + (j * 4 + (tid >> 5)) * 128 + (tid & 31);
                 dst[0] = one16<T>();
                 dst[32] = p[0];

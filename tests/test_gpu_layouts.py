@@ -194,3 +194,31 @@ def test_long_dimensions(dtype, M, N, K, transB):
     n, recs = vg.inject_records()
     assert n == 1 and recs[0][:3] == (i, j, bit)
     assert r["flags"][i] == 1 and r["nflag"] == 1 and r["flags"].sum() == 1
+
+
+@pytest.mark.parametrize("dtype,Ms,Ml,N,K,transB", [("bf16", 256, 15616, 256, 128, 0), ("f16", 256, 15616, 256, 128, 1),
+                                                    ("f32", 128, 7808, 128, 64, 0), ("f64", 128, 7808, 128, 64, 1)])
+def test_encode_of_B_serves_any_row_count(dtype, Ms, Ml, N, K, transB):
+    """B is encoded once through a problem with few rows (fold of S1..S3 deferred); a fused GEMM with many rows
+    on the same workspace must find the partials: their place depends on B's shape only, not on M (61 tile-rows
+    put the arrival counters of the large problem past one 256-byte step, 2 tile-rows do not)."""
+    A, B = _gen(dtype, Ml, N, K, transB, 77)
+    dA, dB = _dev(A, dtype), _dev(B, dtype)
+    big = _session(Ml, N, K, dtype, transB)
+    small = _session(Ms, N, K, dtype, transB)
+    small.ws, small.ws_bytes = big.ws, big.ws_bytes  # one workspace, sized for the larger problem
+    small.Be, small.bstat = big.Be, big.bstat
+    print(f"encode through M={Ms}, fused GEMM with M={Ml}: {dtype} N={N} K={K} transB={transB}", flush=True)
+    big.S.fill_(float("nan"))  # the deferred route must not read it
+    small.encode(dB, defer_S=True)
+    big.gemm_fused(dA, dB, deferred_S=True)
+    r = big.results()
+    ref = _session(Ml, N, K, dtype, transB)
+    ref.run_fused(dA, dB)
+    r2 = ref.results()
+    assert r["nflag"] == 0 and r2["nflag"] == 0
+    for key in ("T", "expected", "rowsum", "E"):
+        assert np.array_equal(r[key], r2[key]), key
+    # ... and an encode of the columns of A takes that place: documented to invalidate the deferred fold
+    o = orc.verify(A, B, dtype, transB, e_max=_emax(dtype, K, N))
+    assert np.all(np.abs(r["T"] - o["T"]) <= 1e-5 * o["T"] + 1e-300)
