@@ -183,6 +183,25 @@ int vabft_gemm_verified_fused(const vabft_problem* p, const void* dA, const void
                               vabft_inject_rec* d_injlog, int32_t* d_ninj, void* d_workspace,
                               size_t workspace_bytes, void* stream);
 
+/* The fused call for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same inputs, outputs and results as vabft_gemm_verified_fused, but
+ * without a workspace argument: the partials and arrival counters live in a fixed array of
+ * VABFT_STATIC_SCRATCH_BYTES (16 MiB) of device memory inside the library, one copy per GPU, held until the
+ * process ends.  The call allocates nothing and frees nothing.
+ *   - d_S must not be NULL (no encode runs on this array, so there are no deferred partials to fold).
+ *   - A problem whose workspace need (vabft_workspace_bytes) exceeds the array returns VABFT_EWORKSPACE;
+ *     every benchmark configuration fits (the largest, FP16 8192^3, needs 8.4 MB).
+ *   - Every call on a GPU shares that GPU's array, which keeps the previous call's contents; the call clears
+ *     the arrival counters itself.  Calls that overlap on one GPU (two streams, two threads) race: order them.
+ *   - VABFT_EDEVICE if the array's address cannot be obtained on the current device. */
+#define VABFT_STATIC_SCRATCH_BYTES (16u << 20)
+size_t vabft_static_scratch_bytes(void);
+int vabft_gemm_verified_fused_static(const vabft_problem* p, const void* dA, const void* dB, void* dC,
+                                     const void* d_Be, const double* d_S, double e_max, double c_sigma,
+                                     void* d_astat, void* d_expected, void* d_T, const vabft_inject* inj,
+                                     void* d_rowsum, void* d_E, int32_t* d_flags, int32_t* d_nflag,
+                                     vabft_inject_rec* d_injlog, int32_t* d_ninj, void* stream);
+
 /* ---- Position-weighted checksum, localisation and correction (section 2.2: r2 = [1..N]^T,
  * C^{r2} = A (B r2), C^{r2'} = C r2, "Error localization and correction") -------------------
  * The three calls below are the weighted forms of vabft_encode, vabft_threshold and

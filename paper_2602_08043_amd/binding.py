@@ -22,7 +22,8 @@ EXPORTS = ("vabft_status_string", "vabft_workspace_bytes", "vabft_workspace_init
            "vabft_encode_weighted", "vabft_threshold_weighted", "vabft_gemm_verified_weighted",
            "vabft_locate_correct", "vabft_default_emax_offline", "vabft_check_offline",
            "vabft_encode_a", "vabft_threshold_cols", "vabft_gemm_verified_rc",
-           "vabft_block_width", "vabft_encode_blocks", "vabft_threshold_blocks", "vabft_gemm_verified_blocks")
+           "vabft_block_width", "vabft_encode_blocks", "vabft_threshold_blocks", "vabft_gemm_verified_blocks",
+           "vabft_static_scratch_bytes", "vabft_gemm_verified_fused_static")
 
 
 class Problem(Structure):
@@ -84,6 +85,13 @@ def load(path: str | None = None):
                                               c_double, c_double, c_void_p, c_void_p, c_void_p, POINTER(Inject),
                                               c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                               c_size_t, c_void_p]
+    lib.vabft_static_scratch_bytes.restype = c_size_t
+    lib.vabft_static_scratch_bytes.argtypes = []
+    lib.vabft_gemm_verified_fused_static.restype = ctypes.c_int
+    lib.vabft_gemm_verified_fused_static.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p,
+                                                     c_void_p, c_double, c_double, c_void_p, c_void_p, c_void_p,
+                                                     POINTER(Inject), c_void_p, c_void_p, c_void_p, c_void_p,
+                                                     c_void_p, c_void_p, c_void_p]
     lib.vabft_encode_weighted.restype = ctypes.c_int
     lib.vabft_encode_weighted.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                           c_size_t, c_void_p]
@@ -186,6 +194,19 @@ def vabft_gemm_verified_fused(p: Problem, dA, dB, dC, d_Be, d_S, e_max, c_sigma,
                                           d_expected, d_T, byref(inj) if inj is not None else None, d_rowsum, d_E,
                                           d_flags, d_nflag, d_injlog, d_ninj, d_workspace, workspace_bytes, stream)
     return _check(rc, "vabft_gemm_verified_fused", check)
+
+
+def vabft_static_scratch_bytes() -> int:
+    return int(load().vabft_static_scratch_bytes())
+
+
+def vabft_gemm_verified_fused_static(p: Problem, dA, dB, dC, d_Be, d_S, e_max, c_sigma, d_astat, d_expected, d_T,
+                                     inj, d_rowsum, d_E, d_flags, d_nflag, d_injlog, d_ninj, stream=None,
+                                     check=True) -> int:
+    rc = load().vabft_gemm_verified_fused_static(byref(p), dA, dB, dC, d_Be, d_S, float(e_max), float(c_sigma),
+                                                 d_astat, d_expected, d_T, byref(inj) if inj is not None else None,
+                                                 d_rowsum, d_E, d_flags, d_nflag, d_injlog, d_ninj, stream)
+    return _check(rc, "vabft_gemm_verified_fused_static", check)
 
 
 def vabft_encode_weighted(p: Problem, dB, d_Be, d_Be2, d_bstat, d_S, d_workspace, workspace_bytes, stream=None,

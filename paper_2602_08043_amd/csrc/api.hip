@@ -2,6 +2,8 @@
 // step (paper section 2.2 Eq. abft-check, E_i = C^{r1}[i] - C^{r1'}[i]).
 #include <math.h>
 
+#include <mutex>
+
 #include "vabft_device.h"
 #include "vabft_host.h"
 
@@ -410,6 +412,28 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
 }
 
+// Scratch of the entry point that allocates nothing (vabft_gemm_verified_fused_static): device memory that
+// lives in the library's code object, one copy per GPU, held until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress; kernels receive the address that call returns.
+static __device__ __align__(256) unsigned char scratch[VABFT_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// address of the current device's copy of `scratch` (looked up once per device); null on failure
+static void* static_scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
 }  // namespace vabft
 
 using namespace vabft;
@@ -752,6 +776,41 @@ int vabft_gemm_verified_fused(const vabft_problem* p, const void* dA, const void
     f.d_astat = d_astat;
     return gemm_dispatch(p, dA, dB, dC, d_expected, d_T, 1, &f, inj, d_rowsum, nullptr, d_E, d_flags, d_nflag,
                          d_injlog, d_ninj, d_workspace, (hipStream_t)stream);
+}
+
+size_t vabft_static_scratch_bytes(void) { return VABFT_STATIC_SCRATCH_BYTES; }
+
+int vabft_gemm_verified_fused_static(const vabft_problem* p, const void* dA, const void* dB, void* dC, const void* d_Be,
+                                     const double* d_S, double e_max, double c_sigma, void* d_astat, void* d_expected,
+                                     void* d_T, const vabft_inject* inj, void* d_rowsum, void* d_E, int32_t* d_flags,
+                                     int32_t* d_nflag, vabft_inject_rec* d_injlog, int32_t* d_ninj, void* stream) {
+    if (!problem_ok(p)) return VABFT_EINVAL;
+    if (!d_S) return VABFT_EINVAL;  // no encode runs on this scratch: S1..S3 must come folded
+    const size_t need = tickets_bytes(p) + gemm_workspace_bytes(p);
+    if (need > VABFT_STATIC_SCRATCH_BYTES) return VABFT_EWORKSPACE;
+    void* ws = static_scratch_of_current_device();
+    if (!ws) return VABFT_EDEVICE;
+    const int rc = check_gemm_args(p, dA, dB, dC, 1, inj, d_expected, d_T, d_rowsum, d_E, d_flags, d_nflag, d_injlog,
+                                   d_ninj, ws, VABFT_STATIC_SCRATCH_BYTES);
+    if (rc != VABFT_OK) return rc;
+    if (!d_Be || !d_astat) return VABFT_EINVAL;
+    if (!(e_max > 0.0) || !(c_sigma >= 0.0) || !isfinite(e_max) || !isfinite(c_sigma)) return VABFT_EINVAL;
+    const size_t ab = acc_bytes(p->dtype);
+    if (!aligned_to(d_Be, ab) || !aligned_to(d_S, 8) || !aligned_to(d_astat, ab)) return VABFT_EINVAL;
+    // every call on this GPU shares the array, which keeps the last call's contents: the arrival counters
+    // must start at zero (a fill kernel, not a memset, so that the call can be captured into a graph)
+    const size_t tb = tickets_bytes(p) - tickets_offset(p);
+    fill_zero_kernel<<<1, 256, 0, (hipStream_t)stream>>>(
+        reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(ws) + tickets_offset(p)), tb / 4);
+    if (hipGetLastError() != hipSuccess) return VABFT_EDEVICE;
+    FusedArgs f;
+    f.d_Be = d_Be;
+    f.d_S = d_S;
+    f.e_max = e_max;
+    f.c_sigma = c_sigma;
+    f.d_astat = d_astat;
+    return gemm_dispatch(p, dA, dB, dC, d_expected, d_T, 1, &f, inj, d_rowsum, nullptr, d_E, d_flags, d_nflag,
+                         d_injlog, d_ninj, ws, (hipStream_t)stream);
 }
 
 }  // extern "C"
