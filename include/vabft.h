@@ -66,7 +66,7 @@ typedef struct {
     int64_t lda, ldb, ldc; /* leading dimensions in elements */
 } vabft_problem;
 
-/* Fault injector (section 5.1 "Error injection": single bit flips).  The flip is applied
+/* Fault injector (section 6.1 "Error injection": single bit flips).  The flip is applied
  * to the accumulator word of C[i][j] after the K loop, before the row sum and before
  * output quantisation; the corrupted value is also what is stored to C.
  *   mode 0: off.
@@ -202,6 +202,15 @@ int vabft_gemm_verified_fused_static(const vabft_problem* p, const void* dA, con
                                      void* d_rowsum, void* d_E, int32_t* d_flags, int32_t* d_nflag,
                                      vabft_inject_rec* d_injlog, int32_t* d_ninj, void* stream);
 
+/* Measurement aid (not a step of the verified path): one launch of a register-only loop of the matrix
+ * instruction that the GEMM of `dtype` issues (BF16 / FP16: v_mfma_f32_16x16x32; FP32: 32x32x2; FP64: 16x16x4),
+ * 256 workgroups of 4 wavefronts, `iters` iterations, pseudo-random operands.  On N(0,1)-like data the chip
+ * sustains a lower clock under matrix load than the one its published peak assumes; the benchmark times this
+ * launch and reports the verified GEMM as a fraction of the rate it reaches, beside the published peak.
+ *   d_out [65536] float (device): a value per thread, so that the loop is not removed
+ *   flops (host): floating-point operations of the launch */
+int vabft_probe_mfma(int32_t dtype, int32_t iters, void* d_out, double* flops, void* stream);
+
 /* ---- Position-weighted checksum, localisation and correction (section 2.2: r2 = [1..N]^T,
  * C^{r2} = A (B r2), C^{r2'} = C r2, "Error localization and correction") -------------------
  * The three calls below are the weighted forms of vabft_encode, vabft_threshold and
@@ -280,7 +289,7 @@ int vabft_gemm_verified_rc(const vabft_problem* p, const void* dA, const void* d
                            int32_t* d_colflags, int32_t* d_ncolflag, vabft_inject_rec* d_injlog,
                            int32_t* d_ninj, void* d_workspace, size_t workspace_bytes, void* stream);
 
-/* ---- Block-wise verification (section 3.7 "Integration with Block-wise ABFT").  The product is checked
+/* ---- Block-wise verification (section 5.2 "Integration with Block-wise ABFT").  The product is checked
  * in blocks of W = vabft_block_width(dtype) columns (256; 64 for FP32 / FP64): block t holds columns
  * [tW, min(N, (t+1)W)), nblocks = ceil(N / W).  Per block: row statistics of the block of B, Algorithm 1 with
  * the block's width in place of N, block checksums compared on their own; a row's aggregate difference is

@@ -16,14 +16,14 @@ no blocking, fusion or reordering beyond what the definitions state:
   * Threshold: the boxed T_bound of section 3.4 / Algorithm 1 (T_det, T_var23,
     T_var4), with c_sigma = 2.5 (section 3.4) and e_max from the
     "Recommended e_max across platforms" table (GPU rows) as default.
-  * Fault model: single bit flips in a stored floating-point word (section 5.1
+  * Fault model: single bit flips in a stored floating-point word (section 6.1
     "Error injection"), replayed on the row sum.
   * Offline (post-quantisation) verification: row sums of the product after it was rounded to the
     output type, with e_max = 2 u_output: section 3.6 "Verification output precision: Offline vs.
     Online ABFT" and "Practical recommendations".
   * Column checksums c1 = [1 .. 1], A^c = [A; c1 A], C^{c1} = c1 A B, C^{c1'} = c1 C (section 2.2) with the
     threshold of Algorithm 1 applied to C^T = B^T A^T (our reading: the paper gives the row form only).
-  * Block-wise verification (section 3.7 "Integration with Block-wise ABFT"): statistics, threshold and
+  * Block-wise verification (section 5.2 "Integration with Block-wise ABFT"): statistics, threshold and
     checksums per block of columns, block results aggregated per row.
   * Position-weighted checksum r2, checksum differences D1 / D2, localisation
     j = D2 / D1 - 1 and correction C[i][j] -= D1: section 2.2 "Error
@@ -248,7 +248,7 @@ def accumulator_path(A_st, B_st, dtype: str, transB: int = 0):
 
 
 def tightness(T: np.ndarray, E: np.ndarray):
-    """Threshold divided by actual verification difference (section 5.1,
+    """Threshold divided by actual verification difference (section 6.1,
     "Metrics"): (mean T / mean |E|, max T / max |E|)."""
     aE = np.abs(E)
     return float(T.mean() / aE.mean()), float(T.max() / aE.max())
@@ -500,7 +500,7 @@ def replay_faults_columns(colsum: np.ndarray, records) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
-# block-wise verification (section 3.7), blocks of W columns
+# block-wise verification (section 5.2), blocks of W columns
 # --------------------------------------------------------------------------
 def verify_blocks(A_st, B_st, dtype: str, transB: int, W: int, e_max: float, c_sigma: float = C_SIGMA_DEFAULT,
                   full_gemm: bool = True):

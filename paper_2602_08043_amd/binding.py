@@ -23,7 +23,7 @@ EXPORTS = ("vabft_status_string", "vabft_workspace_bytes", "vabft_workspace_init
            "vabft_locate_correct", "vabft_default_emax_offline", "vabft_check_offline",
            "vabft_encode_a", "vabft_threshold_cols", "vabft_gemm_verified_rc",
            "vabft_block_width", "vabft_encode_blocks", "vabft_threshold_blocks", "vabft_gemm_verified_blocks",
-           "vabft_static_scratch_bytes", "vabft_gemm_verified_fused_static")
+           "vabft_static_scratch_bytes", "vabft_gemm_verified_fused_static", "vabft_probe_mfma")
 
 
 class Problem(Structure):
@@ -85,6 +85,8 @@ def load(path: str | None = None):
                                               c_double, c_double, c_void_p, c_void_p, c_void_p, POINTER(Inject),
                                               c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                               c_size_t, c_void_p]
+    lib.vabft_probe_mfma.restype = ctypes.c_int
+    lib.vabft_probe_mfma.argtypes = [c_int32, c_int32, c_void_p, POINTER(c_double), c_void_p]
     lib.vabft_static_scratch_bytes.restype = c_size_t
     lib.vabft_static_scratch_bytes.argtypes = []
     lib.vabft_gemm_verified_fused_static.restype = ctypes.c_int
@@ -194,6 +196,14 @@ def vabft_gemm_verified_fused(p: Problem, dA, dB, dC, d_Be, d_S, e_max, c_sigma,
                                           d_expected, d_T, byref(inj) if inj is not None else None, d_rowsum, d_E,
                                           d_flags, d_nflag, d_injlog, d_ninj, d_workspace, workspace_bytes, stream)
     return _check(rc, "vabft_gemm_verified_fused", check)
+
+
+def vabft_probe_mfma(dtype: str, iters: int, d_out, stream=None) -> float:
+    """One launch of the register-only matrix-instruction loop; returns the launch's flop count."""
+    flops = c_double(0.0)
+    rc = load().vabft_probe_mfma(DTYPE_CODE[dtype], int(iters), d_out, byref(flops), stream)
+    _check(rc, "vabft_probe_mfma", True)
+    return float(flops.value)
 
 
 def vabft_static_scratch_bytes() -> int:

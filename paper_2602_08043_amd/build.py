@@ -13,7 +13,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libvabft.so")
 
 SOURCES = ["gemm16_bf16_nn.hip", "gemm16_bf16_nt.hip", "gemm16_f16_nn.hip", "gemm16_f16_nt.hip", "gemm8_f8_nt.hip", "api.hip",
-           "encode.hip", "blocks.hip", "gemm_f32.hip", "gemm_f64.hip"]
+           "encode.hip", "blocks.hip", "gemm_f32.hip", "gemm_f64.hip", "probe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
@@ -28,6 +28,7 @@ FLAGS = [
 EXTRA_FLAGS = {
     "gemm_f32.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "gemm_f64.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "probe.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 

@@ -1,4 +1,4 @@
-// Block-wise V-ABFT (paper section 3.7 "Integration with Block-wise ABFT"): the product is verified in blocks
+// Block-wise V-ABFT (paper section 5.2 "Integration with Block-wise ABFT"): the product is verified in blocks
 // of W columns -- the width one GEMM workgroup (256; 64 for the FP32 / FP64 kernels) sums before it writes a
 // partial row sum.  The section's three steps, per block t = columns [tW, min(N, (t+1)W)):
 //   1. row statistics of the block of B (the rows of A are whole, K is not split);

@@ -1,7 +1,7 @@
 // BF16 / FP16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16) with the fused V-ABFT
 // epilogue: row sums of the FP32 accumulator tile before output quantisation (paper section
 // 3.6 "Online (Fused Kernel) ABFT"; section 2.2 C^{r1'} = C r1), and the accumulator bit-flip
-// injector (section 5.1).
+// injector (section 6.1).
 //
 // Tile 256 x 256 x 64 per workgroup of 4 wavefronts (2 x 2), 128 x 128 per wavefront as
 // 4 x 4 MFMA tiles.  Operands are staged in LDS as [row][64 k] with the eight 16-byte chunks
@@ -48,7 +48,7 @@ __device__ __forceinline__ int lds_pos(int row, int chunk) { return row * 128 + 
 // wavefront is
 //   C[row0 + wm*128 + mi*32 + lane%32][col0 + wn*128 + ni*32 + 8*(r/4) + 4*(lane/32) + r%4].
 
-// Fault injector on the accumulator registers (paper section 5.1 "Error injection").
+// Fault injector on the accumulator registers (paper section 6.1 "Error injection").
 template <bool INJECT>
 __device__ __forceinline__ void gemm16_inject(const GemmArgs& g, f32x16_t (&acc)[4][4], int row0, int col0, int wm,
                                               int wn, int l32, int lh) {

@@ -514,13 +514,17 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
 
     // ---- fused A-side statistics (FUSED) ----------------------------------------------------------------
     // Both wavefronts of a wm pair hold the same A fragments; wavefront wn takes fragments 4*wn .. 4*wn+3.
-    // sacc[j]: result tile of panel x fragment 4*wn + j; lanes 0..15 hold (sum, dot_hi, dot_mid, dot_lo) of
+    // sacc[t][j]: result tile of panel x fragment 4*wn + j, accumulated over the steps t (of four) of the folded
+    // units: four short accumulation chains per row, added as a tree at the end, instead of one chain over all
+    // steps (every MFMA rounds the running sum once; the chain was the largest term of the check's rounding
+    // noise at sizes where one tile-column folds a whole row).  Lanes 0..15 hold (sum, dot_hi, dot_mid, dot_lo) of
     // row wm*128 + (4*wn + j)*16 + lane.
-    f32x4_t sacc[4];
+    f32x4_t sacc[4][4];
     MinMax16<T> mm[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        sacc[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) sacc[t][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         mm[j].init();
     }
     const lds_u8* const panel_rd = lds + PANEL_OFFSET + (l16 & 3) * 64 + lq * 16;
@@ -545,7 +549,7 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         u32x4_t xv = __builtin_bit_cast(u32x4_t, xf);
         asm volatile("s_nop 4" : "+v"(xv));
         xf = __builtin_bit_cast(raw16, xv);
-        Mfma16x<T>::acc_v4(sacc, xf, a);
+        Mfma16x<T>::acc_v4(sacc[2 * S + KS], xf, a);
     };
 
     // One k32-step = 64 slots of one MFMA (16 cycles, four issue cycles).  Even slots issue fragment read
@@ -725,8 +729,11 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
                 if (lq == 0) {
                     const int r = wm * 128 + (4 * wn + j) * 16 + l16;
                     const bool any = n_slots > 0;  // a tile-column beyond the last k-unit folds nothing
-                    sred[0 * BM + r] = sacc[j][0];
-                    sred[1 * BM + r] = sigma * (sacc[j][1] + (sacc[j][2] + sacc[j][3]));
+                    f32x4_t q;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) q[e] = (sacc[0][j][e] + sacc[1][j][e]) + (sacc[2][j][e] + sacc[3][j][e]);
+                    sred[0 * BM + r] = q[0];
+                    sred[1 * BM + r] = sigma * (q[1] + (q[2] + q[3]));
                     sred[2 * BM + r] = any ? mx : -3.402823466e+38f;
                     sred[3 * BM + r] = any ? mn : 3.402823466e+38f;
                 }

@@ -1,5 +1,5 @@
 // Pieces shared by the GEMM kernels: block -> tile mapping, guarded loads, the fault
-// injector applied to accumulator registers (paper section 5.1 "Error injection").
+// injector applied to accumulator registers (paper section 6.1 "Error injection").
 #pragma once
 #include <type_traits>
 

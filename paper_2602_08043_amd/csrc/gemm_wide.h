@@ -1,6 +1,6 @@
 // FP32 / FP64 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x2f32, v_mfma_f64_16x16x4f64)
 // with the fused V-ABFT epilogue (paper section 2.2 C^{r1'} = C r1 on the accumulator tile;
-// section 5.1 injector).  These MFMAs take one element per lane and are 16 passes long, so
+// section 6.1 injector).  These MFMAs take one element per lane and are 16 passes long, so
 // the kernel is matrix-core bound with a simple LDS staging.
 //
 // Tile 128 x 128 x 16 per workgroup of 4 wavefronts (2 x 2), 64 x 64 per wavefront.

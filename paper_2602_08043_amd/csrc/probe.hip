@@ -1,0 +1,146 @@
+// Measurement aid, not part of the verified path: a register-only loop of the matrix instruction that the
+// GEMM of a dtype issues, on pseudo-random operands (the chip's sustained clock under matrix load depends
+// on how many operand bits toggle: an all-ones loop runs at the full clock, N(0,1)-like data does not).
+// The benchmark reports the GEMM's rate as a fraction of this measured ceiling beside the published peak.
+#include "gemm_common.h"
+
+namespace vabft {
+
+// value in (-2, 2) from a counter (inputs of a timing loop only)
+__device__ __forceinline__ float probe_value(uint32_t i) {
+    uint32_t z = (i + 1u) * 0x9E3779B9u;
+    z ^= z >> 15;
+    z *= 0x85EBCA6Bu;
+    z ^= z >> 13;
+    return ((float)(z >> 8) * (1.0f / 8388608.0f) - 1.0f) * 2.0f;
+}
+
+template <typename T> __global__ __launch_bounds__(256) void mfma_probe16_kernel(float* out, int iters) {
+    const int tid = threadIdx.x;
+    raw16 a[8], b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t s = (uint32_t)(tid * 64 + i * 8 + d * 2) + blockIdx.x * 16384u;
+            uint16_t lo, hi, lo2, hi2;
+            if constexpr (std::is_same<T, bf16_t>::value) {
+                lo = Elem<bf16_t>::from_acc(probe_value(s));
+                hi = Elem<bf16_t>::from_acc(probe_value(s + 1));
+                lo2 = Elem<bf16_t>::from_acc(probe_value(s + 70001));
+                hi2 = Elem<bf16_t>::from_acc(probe_value(s + 70002));
+            } else {
+                lo = Elem<f16_t>::from_acc(probe_value(s));
+                hi = Elem<f16_t>::from_acc(probe_value(s + 1));
+                lo2 = Elem<f16_t>::from_acc(probe_value(s + 70001));
+                hi2 = Elem<f16_t>::from_acc(probe_value(s + 70002));
+            }
+            a[i].w[d] = (uint32_t)lo | ((uint32_t)hi << 16);
+            b[i].w[d] = (uint32_t)lo2 | ((uint32_t)hi2 << 16);
+        }
+    f32x4_t acc[64];
+#pragma unroll
+    for (int i = 0; i < 64; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    // the accumulators are tied to their registers, as in the GEMM kernel (left to the register allocator they
+    // are copied between the register files inside the loop); idle slots separate the vector code that wrote
+    // the operands from the first matrix instruction, and the last one from the code that reads the results
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+    asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 64; ++s) {
+            if constexpr (std::is_same<T, bf16_t>::value)
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"
+                             : "+a"(acc[s])
+                             : "v"(__builtin_bit_cast(u32x4_t, b[s & 7])), "v"(__builtin_bit_cast(u32x4_t, a[s >> 3])));
+            else
+                asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0"
+                             : "+a"(acc[s])
+                             : "v"(__builtin_bit_cast(u32x4_t, b[s & 7])), "v"(__builtin_bit_cast(u32x4_t, a[s >> 3])));
+        }
+    }
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 64; ++i) s += (acc[i][0] + acc[i][1]) + (acc[i][2] + acc[i][3]);
+    out[blockIdx.x * 256 + tid] = s;
+}
+
+__global__ __launch_bounds__(256) void mfma_probe_f32_kernel(float* out, int iters) {
+    const int tid = threadIdx.x;
+    float a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i] = probe_value(tid * 8 + i + blockIdx.x * 4096u);
+        b[i] = probe_value(tid * 8 + i + 50021u + blockIdx.x * 4096u);
+    }
+    f32x16_t acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 16; ++s) acc[s] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[s & 3], a[s >> 2], acc[s], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    out[blockIdx.x * 256 + tid] = s;
+}
+
+__global__ __launch_bounds__(256) void mfma_probe_f64_kernel(float* out, int iters) {
+    const int tid = threadIdx.x;
+    double a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i] = (double)probe_value(tid * 8 + i + blockIdx.x * 4096u) + 1e-9 * probe_value(tid * 8 + i + 999u);
+        b[i] = (double)probe_value(tid * 8 + i + 50021u + blockIdx.x * 4096u) + 1e-9 * probe_value(tid * 8 + i + 1999u);
+    }
+    f64x4_t acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = f64x4_t{0., 0., 0., 0.};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 16; ++s) acc[s] = __builtin_amdgcn_mfma_f64_16x16x4f64(b[s & 3], a[s >> 2], acc[s], 0, 0, 0);
+    }
+    double s = 0.;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += (acc[i][0] + acc[i][1]) + (acc[i][2] + acc[i][3]);
+    out[blockIdx.x * 256 + tid] = (float)s;
+}
+
+}  // namespace vabft
+
+using namespace vabft;
+
+extern "C" int vabft_probe_mfma(int32_t dtype, int32_t iters, void* d_out, double* flops, void* stream) {
+    if (!d_out || !flops || iters <= 0) return VABFT_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid(256), block(256);
+    float* out = reinterpret_cast<float*>(d_out);
+    double per_wave_iter;
+    switch (dtype) {
+        case VABFT_BF16:
+            mfma_probe16_kernel<bf16_t><<<grid, block, 0, st>>>(out, iters);
+            per_wave_iter = 64.0 * 16384.0;  // 64 x v_mfma_f32_16x16x32: 2*16*16*32 flop each
+            break;
+        case VABFT_F16:
+            mfma_probe16_kernel<f16_t><<<grid, block, 0, st>>>(out, iters);
+            per_wave_iter = 64.0 * 16384.0;
+            break;
+        case VABFT_F32:
+            mfma_probe_f32_kernel<<<grid, block, 0, st>>>(out, iters);
+            per_wave_iter = 16.0 * 4096.0;  // 16 x v_mfma_f32_32x32x2: 2*32*32*2
+            break;
+        case VABFT_F64:
+            mfma_probe_f64_kernel<<<grid, block, 0, st>>>(out, iters);
+            per_wave_iter = 16.0 * 2048.0;  // 16 x v_mfma_f64_16x16x4: 2*16*16*4
+            break;
+        default: return VABFT_EUNSUPPORTED;
+    }
+    *flops = 256.0 * 4.0 * (double)iters * per_wave_iter;
+    return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
+}

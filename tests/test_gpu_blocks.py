@@ -1,4 +1,4 @@
-"""Parity of the block-wise verification path (paper section 3.7 "Integration with Block-wise ABFT") with the
+"""Parity of the block-wise verification path (paper section 5.2 "Integration with Block-wise ABFT") with the
 CPU oracle, through the C ABI: statistics, thresholds and checksums per block of W columns (W is the width
 the GEMM kernels sum before they write a partial: 256, or 64 for FP32 / FP64)."""
 import numpy as np

@@ -588,7 +588,7 @@ def test_e4m3_rounding_of_the_generators():
 
 
 # --------------------------------------------------------------------------
-# block-wise verification (section 3.7)
+# block-wise verification (section 5.2)
 # --------------------------------------------------------------------------
 def test_blockwise_reduces_to_the_plain_check_and_adds_up():
     g = np.random.Generator(np.random.Philox(key=[7, 1]))
@@ -625,3 +625,66 @@ def test_blockwise_localises_a_planted_error_to_its_block():
     want[2, 4] = -5.0                                                   # column 17 lies in block 2
     assert np.array_equal(E, want)
     assert orc.fault_flags(E, blk["T_blk"]).sum() == 1 and orc.fault_flags(E, blk["T_blk"])[2, 4] == 1
+
+
+# ---------------------------------------------------------------------------------------------------------
+# the magnitude scales that the GPU parity tolerances are multiplied with (a too-large scale would loosen
+# every parity assertion silently): brute force on small integer matrices, every term written out
+# ---------------------------------------------------------------------------------------------------------
+def _int_matrices(seed, M, K, N):
+    g = wl.rng(seed, 31)
+    A = g.integers(-4, 5, size=(M, K)).astype(np.float64)
+    B = g.integers(-3, 4, size=(K, N)).astype(np.float64)
+    return A, B
+
+
+def test_row_check_tolerance_scales_match_brute_force():
+    M, K, N = 5, 7, 6
+    A, B = _int_matrices(11, M, K, N)
+    o = orc.verify(A, B, "f64", 0, e_max=1e-9)
+    Be = [sum(B[k][n] for n in range(N)) for k in range(K)]
+    Be2 = [sum((n + 1) * B[k][n] for n in range(N)) for k in range(K)]
+    for k in range(K):
+        assert o["scale_Be"][k] == sum(abs(B[k][n]) for n in range(N))
+        assert o["scale_Be2"][k] == sum((n + 1) * abs(B[k][n]) for n in range(N))
+    for i in range(M):
+        assert o["scale_expected"][i] == sum(abs(A[i][k]) * abs(Be[k]) for k in range(K))
+        assert o["scale_expected2"][i] == sum(abs(A[i][k]) * abs(Be2[k]) for k in range(K))
+        # every product term of every element of the row: sum_j sum_k |a_ik| |b_kj|
+        assert o["scale_rowsum"][i] == sum(abs(A[i][k]) * abs(B[k][j]) for k in range(K) for j in range(N))
+        assert o["scale_rowsum2"][i] == sum((j + 1) * abs(A[i][k]) * abs(B[k][j]) for k in range(K) for j in range(N))
+    # a scale bounds the quantity it belongs to, and is attained by a sign-free row (so it is not larger than needed)
+    assert np.all(np.abs(o["Be"]) <= o["scale_Be"]) and np.all(np.abs(o["expected"]) <= o["scale_expected"])
+    assert np.all(np.abs(o["rowsum"]) <= o["scale_rowsum"])
+    op = orc.verify(np.abs(A), np.abs(B), "f64", 0, e_max=1e-9)
+    assert np.array_equal(op["scale_Be"], op["Be"]) and np.array_equal(op["scale_expected"], op["expected"])
+    assert np.array_equal(op["scale_rowsum"], op["rowsum"])
+    # the transposed storage of B gives the same scales
+    ot = orc.verify(A, np.ascontiguousarray(B.T), "f64", 1, e_max=1e-9)
+    for key in ("scale_Be", "scale_expected", "scale_rowsum"):
+        assert np.array_equal(o[key], ot[key]), key
+
+
+def test_column_and_block_tolerance_scales_match_brute_force():
+    M, K, N, W = 6, 5, 8, 3
+    A, B = _int_matrices(12, M, K, N)
+    oc = orc.verify_columns(A, B, "f64", 0, e_max=1e-9)
+    eA = [sum(A[m][k] for m in range(M)) for k in range(K)]
+    for k in range(K):
+        assert oc["scale_eA"][k] == sum(abs(A[m][k]) for m in range(M))
+    for j in range(N):
+        assert oc["scale_expected_col"][j] == sum(abs(eA[k]) * abs(B[k][j]) for k in range(K))
+        assert oc["scale_colsum"][j] == sum(abs(A[m][k]) * abs(B[k][j]) for m in range(M) for k in range(K))
+    assert np.all(np.abs(oc["colsum"]) <= oc["scale_colsum"])
+    ob = orc.verify_blocks(A, B, "f64", 0, W, e_max=1e-9)
+    for t in range(ob["nblocks"]):
+        cols = range(t * W, min(N, (t + 1) * W))
+        Be_t = [sum(B[k][n] for n in cols) for k in range(K)]
+        for k in range(K):
+            assert ob["scale_Be_blk"][t][k] == sum(abs(B[k][n]) for n in cols)
+        for i in range(M):
+            assert ob["scale_expected_blk"][t][i] == sum(abs(A[i][k]) * abs(Be_t[k]) for k in range(K))
+            assert ob["scale_rowsum_blk"][t][i] == sum(abs(A[i][k]) * abs(B[k][j]) for k in range(K) for j in cols)
+    # the block scales of a row add up to the row scale of the plain check
+    o = orc.verify(A, B, "f64", 0, e_max=1e-9)
+    assert np.array_equal(ob["scale_rowsum_blk"].sum(axis=0), o["scale_rowsum"])

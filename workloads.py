@@ -132,6 +132,8 @@ CONFIGS = {
     "c5_f64_2048": dict(dtype="f64", M=2048, N=2048, K=2048, transB=0),
     # beyond the five benchmark configurations: FP8 E4M3 inputs, FP32 accumulation, FP16 output
     "c6_f8_4096": dict(dtype="f8", M=4096, N=4096, K=4096, transB=1),
+    # ... and an FP32 problem large enough to be bound by the FP32 matrix instruction rather than by latency
+    "c7_f32_4096": dict(dtype="f32", M=4096, N=4096, K=4096, transB=0),
 }
 
 
@@ -149,7 +151,7 @@ def make_config(name: str, seed: int = 0, variant: int = 0, shape=None):
         cfg["M"], cfg["N"], cfg["K"] = (int(v) for v in shape)
     M, N, K, dt = cfg["M"], cfg["N"], cfg["K"], cfg["dtype"]
     ga, gb = rng(seed, 1), rng(seed, 2)
-    if name == "c1_f32_256" or name == "c2_bf16_4096":
+    if name in ("c1_f32_256", "c2_bf16_4096", "c7_f32_4096"):
         A = normal(ga, (M, K))
         B = normal(gb, (K, N))
     elif name == "c3_bf16_ffn":
@@ -194,3 +196,53 @@ def paper_distribution(g: np.random.Generator, which: str, shape) -> np.ndarray:
 
 
 PAPER_DISTRIBUTIONS = ("n_1e-6_1", "n_1_1", "u_-1_1", "trunc_n_0_1")
+
+
+# --------------------------------------------------------------------------
+# the same configurations drawn on the device (fresh matrices for many-trial statistics)
+# --------------------------------------------------------------------------
+def _device_truncated_normal(torch, g, shape, std, bound_sigmas, dtype):
+    """N(0, std) conditioned on |x| <= bound_sigmas * std, by rejection (rejected entries are redrawn)."""
+    z = torch.randn(shape, generator=g, device="cuda", dtype=dtype)
+    while True:
+        bad = z.abs() > bound_sigmas
+        n_bad = int(bad.sum().item())
+        if n_bad == 0:
+            break
+        z[bad] = torch.randn(n_bad, generator=g, device="cuda", dtype=dtype)
+    return z.mul_(std)
+
+
+def device_trial(name: str, g, variant: int = 0, shape=None):
+    """One trial's (A, B) of a benchmark configuration as torch tensors on the GPU, in storage type and layout,
+    from the torch generator `g` (seeded by the caller).  Same distributions as make_config: N(0,1);
+    c3: round(0.01 K) seeded outlier columns of A times 20 and weights N(0, 0.02) truncated at 2 sigma by
+    rejection, N x K layout; c4: U(-1,1); c5: B ~ N(0,1) truncated at 3 sigma (variant 0) or U(0,1) (variant 1)."""
+    import torch
+
+    cfg = dict(CONFIGS[name])
+    if shape is not None:
+        cfg["M"], cfg["N"], cfg["K"] = (int(v) for v in shape)
+    M, N, K, dt, tb = cfg["M"], cfg["N"], cfg["K"], cfg["dtype"], cfg["transB"]
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32, "f64": torch.float64,
+           "f8": torch.float8_e4m3fn}[dt]
+    gen = torch.float64 if dt == "f64" else torch.float32
+    bshape = (N, K) if tb else (K, N)
+    if name in ("c1_f32_256", "c2_bf16_4096", "c6_f8_4096", "c7_f32_4096"):
+        A = torch.randn((M, K), generator=g, device="cuda", dtype=gen)
+        B = torch.randn(bshape, generator=g, device="cuda", dtype=gen)
+    elif name == "c3_bf16_ffn":
+        A = torch.randn((M, K), generator=g, device="cuda", dtype=gen)
+        cols = torch.randperm(K, generator=g, device="cuda")[:int(round(0.01 * K))]
+        A[:, cols] *= 20.0
+        B = _device_truncated_normal(torch, g, bshape, 0.02, 2.0, gen)
+    elif name == "c4_f16_8192":
+        A = torch.rand((M, K), generator=g, device="cuda", dtype=gen).mul_(2.0).sub_(1.0)
+        B = torch.rand(bshape, generator=g, device="cuda", dtype=gen).mul_(2.0).sub_(1.0)
+    elif name == "c5_f64_2048":
+        A = torch.randn((M, K), generator=g, device="cuda", dtype=gen)
+        B = (_device_truncated_normal(torch, g, bshape, 1.0, 3.0, gen) if variant == 0 else
+             torch.rand(bshape, generator=g, device="cuda", dtype=gen))
+    else:
+        raise KeyError(name)
+    return A.to(tdt), B.to(tdt)
