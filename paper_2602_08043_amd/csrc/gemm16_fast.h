@@ -195,11 +195,12 @@ __device__ __forceinline__ void gemm16x_rowsum_to_lds(const f32x4_t (&acc)[8][8]
     }
 }
 
-// Position-weighted row sums (section 2.2 C^{r2'} = C r2, r2 = [1..N]): sum_j (j + 1) acc[i][j].  Inside the
-// tile the weights are small compile-time constants; the offset of the lane's first column is applied once
-// to the plain partial sum.
-__device__ __forceinline__ void gemm16x_rowsum2_to_lds(const f32x4_t (&acc)[8][8], float* red2, int col0, int wm,
-                                                       int wn, int l16, int lq) {
+// Plain and position-weighted row sums together (section 2.2 C^{r2'} = C r2, r2 = [1..N]: sum_j (j + 1) acc[i][j]):
+// every accumulator value is read once for both.  Inside the tile the weights are small compile-time constants;
+// the offset of the lane's first column is applied once to the plain partial sum, which is formed exactly as
+// gemm16x_rowsum_to_lds forms it (same tree, same bits).
+__device__ __forceinline__ void gemm16x_rowsums12_to_lds(const f32x4_t (&acc)[8][8], float* red, float* red2, int col0,
+                                                         int wm, int wn, int l16, int lq) {
     using namespace g16;
     const float w0 = (float)(col0 + wn * 128 + 4 * lq + 1);  // weight of the lane's first column
 #pragma unroll
@@ -207,21 +208,22 @@ __device__ __forceinline__ void gemm16x_rowsum2_to_lds(const f32x4_t (&acc)[8][8
         float t1[8], t2[8];
 #pragma unroll
         for (int ni = 0; ni < 8; ++ni) {
-            float a1 = 0.f, a2 = 0.f;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                a1 += acc[mi][ni][r];
-                a2 = fmaf((float)(ni * 16 + r), acc[mi][ni][r], a2);
-            }
-            t1[ni] = a1;
-            t2[ni] = a2;
+            const float a0 = acc[mi][ni][0], a1 = acc[mi][ni][1], a2 = acc[mi][ni][2], a3 = acc[mi][ni][3];
+            t1[ni] = (a0 + a1) + (a2 + a3);
+            t2[ni] = fmaf((float)(ni * 16 + 3), a3, fmaf((float)(ni * 16 + 2), a2, fmaf((float)(ni * 16 + 1), a1, (float)(ni * 16) * a0)));
         }
         const float p1 = ((t1[0] + t1[1]) + (t1[2] + t1[3])) + ((t1[4] + t1[5]) + (t1[6] + t1[7]));
         const float p2 = ((t2[0] + t2[1]) + (t2[2] + t2[3])) + ((t2[4] + t2[5]) + (t2[6] + t2[7]));
-        float s = fmaf(w0, p1, p2);
-        s += __shfl_xor(s, 16, WAVE);
-        s += __shfl_xor(s, 32, WAVE);
-        if (lq == 0) red2[wn * BM + wm * 128 + mi * 16 + l16] = s;
+        float s1 = p1;
+        s1 += __shfl_xor(s1, 16, WAVE);
+        s1 += __shfl_xor(s1, 32, WAVE);
+        float s2 = fmaf(w0, p1, p2);
+        s2 += __shfl_xor(s2, 16, WAVE);
+        s2 += __shfl_xor(s2, 32, WAVE);
+        if (lq == 0) {
+            red[wn * BM + wm * 128 + mi * 16 + l16] = s1;
+            red2[wn * BM + wm * 128 + mi * 16 + l16] = s2;
+        }
     }
 }
 
@@ -714,8 +716,10 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         float* sred = reinterpret_cast<float*>(smem + SRED_OFFSET);  // [4][256 rows]
         float* red2 = reinterpret_cast<float*>(smem + RED2_OFFSET);  // [2 wn][256 rows]
         float* cred = reinterpret_cast<float*>(smem + CRED_OFFSET);  // [2 wm][256 columns]
-        gemm16x_rowsum_to_lds(acc, red, wm, wn, l16, lq);
-        if (WSUM) gemm16x_rowsum2_to_lds(acc, red2, col0, wm, wn, l16, lq);
+        if (WSUM)
+            gemm16x_rowsums12_to_lds(acc, red, red2, col0, wm, wn, l16, lq);
+        else
+            gemm16x_rowsum_to_lds(acc, red, wm, wn, l16, lq);
         if (CSUM) gemm16x_colsum_to_lds(acc, cred, wm, wn, l16, lq);
         if (FUSED) {
             const float sigma = reinterpret_cast<const float*>(smem + SCALE_X)[4];

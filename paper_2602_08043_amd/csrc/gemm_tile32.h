@@ -174,7 +174,7 @@ __device__ __forceinline__ void gemm_tile_row_check(const GemmArgs& g, unsigned 
                          S3 = g.S ? g.S[2] : folded_s(s_red, 2), dN = (double)g.N;
             const double t_det = dN * fabs(mu) * S1;
             const double t_var23 = g.c_sigma * sqrt(dN * mu * mu * S2 + dN * dN * var * S3);
-            const double t_var4 = g.c_sigma * sqrt(dN) * sqrt(var) * sqrt(S2);
+            const double t_var4 = g.c_sigma * sqrt(dN * var * S2);  // = c sqrt(N) sigma_A sqrt(S2), one root
             expv = dot;
             thr = (float)(g.e_max * (t_det + t_var23 + t_var4));
             float* astat = reinterpret_cast<float*>(g.astat);
