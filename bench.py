@@ -26,9 +26,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6, "f8": 5033.2, "f32": 157.3, "f64": 78.6}  # MI355X dense matrix peaks
+PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6, "f8": 5033.2, "f8e5m2": 5033.2, "f32": 157.3, "f64": 78.6}  # MI355X dense matrix peaks
 HBM_PEAK_GBPS = 8000.0
-ELEM_BYTES = {"bf16": 2, "f16": 2, "f8": 1, "f32": 4, "f64": 8}
+ELEM_BYTES = {"bf16": 2, "f16": 2, "f8": 1, "f8e5m2": 1, "f32": 4, "f64": 8}
 # Bytes per launch of the verified GEMM kernel that crossed the L2 boundary, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE scaled by the same counters on 1 GiB device copies (profiles/*_hbm_traffic.md, one table per
 # workload).  A counter figure cannot be taken live inside this script; workloads without a profile report null.
@@ -83,7 +83,7 @@ def spin_up(torch, fn, seconds=0.3):
 
 def mfma_probe_tflops(torch, vb, dt, cache={}):
     """Sustained rate of a register-only loop of the GEMM's matrix instruction on random operands."""
-    if dt in cache or dt == "f8":
+    if dt in cache or dt in ("f8", "f8e5m2"):
         return cache.get(dt)
     out = torch.empty(65536, dtype=torch.float32, device="cuda")
     iters = {"bf16": 2000, "f16": 2000, "f32": 1000, "f64": 500}[dt]
@@ -273,7 +273,7 @@ def bench_config(mods, name, variant, steps, warmup, args, headline):
 
     single_launch = ((dt in ("bf16", "f16") and M % 256 == 0 and N % 256 == 0 and K % 128 == 0) or
                      (dt in ("f32", "f64") and M % 128 == 0 and N % 128 == 0 and K % 16 == 0) or
-                     (dt == "f8" and tb == 1 and M % 256 == 0 and N % 256 == 0 and N >= 512 and K % 256 == 0 and
+                     (dt in ("f8", "f8e5m2") and tb == 1 and M % 256 == 0 and N % 256 == 0 and N >= 512 and K % 256 == 0 and
                       (K // 256) // (N // 256) + 2 <= 8))
     ms_dom = ms_steady if single_launch else ms_check
     achieved = flops / (ms_dom * 1e-3) / 1e12

@@ -51,16 +51,17 @@ typedef enum {
     VABFT_EDEVICE = 4       /* the HIP runtime reported an error at launch */
 } vabft_status;
 
-/* VABFT_F8E4M3: A and B are OCP FP8 E4M3 (one byte per element), the accumulator is FP32 and C is
- * FP16 ("FP8 inputs -> FP32 accumulation -> FP16 output", section 3.6).  The GEMM entry points take
- * this type only for B stored N x K (transB = 1) and problems made of whole 256 x 256 x 256 tiles with
+/* VABFT_F8E4M3, VABFT_F8E5M2: A and B are OCP FP8 (one byte per element, both in the same encoding), the
+ * accumulator is FP32 and C is FP16 ("FP8 inputs -> FP32 accumulation -> FP16 output", section 3.6, which names
+ * both encodings).  The GEMM entry points take
+ * these types only for B stored N x K (transB = 1) and problems made of whole 256 x 256 x 256 tiles with
  * 16-byte aligned rows (VABFT_EUNSUPPORTED otherwise); encode, threshold and the offline check take any
  * shape. */
-typedef enum { VABFT_F64 = 0, VABFT_F32 = 1, VABFT_F16 = 2, VABFT_BF16 = 3, VABFT_F8E4M3 = 4 } vabft_dtype;
+typedef enum { VABFT_F64 = 0, VABFT_F32 = 1, VABFT_F16 = 2, VABFT_BF16 = 3, VABFT_F8E4M3 = 4, VABFT_F8E5M2 = 5 } vabft_dtype;
 
 typedef struct {
     int32_t M, N, K;
-    int32_t dtype;  /* vabft_dtype of A, B and C (C is FP16 for VABFT_F8E4M3) */
+    int32_t dtype;  /* vabft_dtype of A, B and C (C is FP16 for the FP8 types) */
     int32_t transB; /* 0: B is K x N row-major; 1: B is stored N x K row-major */
     int32_t reserved;
     int64_t lda, ldb, ldc; /* leading dimensions in elements */

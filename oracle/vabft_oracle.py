@@ -77,6 +77,15 @@ def decode(x: np.ndarray, dtype: str) -> np.ndarray:
         mag = np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * np.exp2(e.astype(np.float64) - 7.0))
         mag = np.where((e == 15) & (m == 7), np.nan, mag)
         return np.where(c & 0x80, -mag, mag)
+    if dtype == "f8e5m2":
+        # OCP FP8 E5M2: sign, 5 exponent bits (bias 15), 2 mantissa bits; exponent 0 is subnormal
+        # (m / 4 * 2^-14), exponent 31 is infinity (m = 0) or NaN; the largest finite value is 57344
+        assert x.dtype == np.uint8
+        c = x.astype(np.int64)
+        e, m = (c >> 2) & 0x1F, c & 3
+        mag = np.where(e == 0, m * 2.0 ** -16, (1.0 + m / 4.0) * np.exp2(e.astype(np.float64) - 15.0))
+        mag = np.where(e == 31, np.where(m == 0, np.inf, np.nan), mag)
+        return np.where(c & 0x80, -mag, mag)
     if dtype == "f64":
         assert x.dtype == np.float64
         return x
@@ -406,7 +415,7 @@ UNIT_ROUNDOFF = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11, "f32": 2.0 ** -24, "f64":
 def output_dtype(dtype: str) -> str:
     """Type of the stored product: FP8 problems write FP16 (section 3.6: FP8 inputs -> FP32
     accumulation -> FP16 output); every other type writes its own."""
-    return "f16" if dtype == "f8" else dtype
+    return "f16" if dtype in ("f8", "f8e5m2") else dtype
 
 
 def quantize(x: np.ndarray, dtype: str) -> np.ndarray:

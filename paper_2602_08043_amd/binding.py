@@ -14,8 +14,9 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libvabft.so")
 
 VABFT_OK, VABFT_EINVAL, VABFT_EUNSUPPORTED, VABFT_EWORKSPACE, VABFT_EDEVICE = range(5)
-VABFT_F64, VABFT_F32, VABFT_F16, VABFT_BF16, VABFT_F8E4M3 = range(5)
-DTYPE_CODE = {"f64": VABFT_F64, "f32": VABFT_F32, "f16": VABFT_F16, "bf16": VABFT_BF16, "f8": VABFT_F8E4M3}
+VABFT_F64, VABFT_F32, VABFT_F16, VABFT_BF16, VABFT_F8E4M3, VABFT_F8E5M2 = range(6)
+DTYPE_CODE = {"f64": VABFT_F64, "f32": VABFT_F32, "f16": VABFT_F16, "bf16": VABFT_BF16, "f8": VABFT_F8E4M3,
+              "f8e5m2": VABFT_F8E5M2}
 
 EXPORTS = ("vabft_status_string", "vabft_workspace_bytes", "vabft_workspace_init", "vabft_default_emax",
            "vabft_encode", "vabft_threshold", "vabft_gemm_verified", "vabft_gemm_verified_fused",

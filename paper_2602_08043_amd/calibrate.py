@@ -33,7 +33,7 @@ def calibrate_one(dtype: str, M: int, N: int, K: int, transB: int, trials: int, 
     from .session import VerifiedGemm
 
     tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32, "f64": torch.float64,
-           "f8": torch.float8_e4m3fn}[dtype]
+           "f8": torch.float8_e4m3fn, "f8e5m2": torch.float8_e5m2}[dtype]
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
     vg = VerifiedGemm(M, N, K, dtype, transB)
@@ -43,6 +43,7 @@ def calibrate_one(dtype: str, M: int, N: int, K: int, transB: int, trials: int, 
     worst_over_T = torch.zeros((), dtype=torch.float64, device="cuda")
     flagged = torch.zeros((), dtype=torch.int64, device="cuda")
     t0 = time.time()
+    t_said = t0
     done = 0
     bshape = (N, K) if transB else (K, N)
     gen_dt = torch.float64 if dtype == "f64" else torch.float32
@@ -63,7 +64,12 @@ def calibrate_one(dtype: str, M: int, N: int, K: int, transB: int, trials: int, 
         done += 1
         if done % 64 == 0:
             torch.cuda.synchronize()
-            if time.time() - t0 > max_seconds:
+            now = time.time()
+            if now - t_said > 30.0:  # a progress line of the work itself, for whoever watches a long run
+                print(f"calibrate: {dtype} n={K} transB={transB}: {done} trials, {now - t0:.0f} s", file=sys.stderr,
+                      flush=True)
+                t_said = now
+            if now - t0 > max_seconds:
                 break
     u = _U.get(dtype, 2.0 ** -24)
     wr = float(worst_rel.item())
@@ -98,7 +104,7 @@ def merge(paths):
                 a["flagged"] += r["flagged_rows_at_default"]
                 a["over_T"] = max(a["over_T"], r["max_E_over_T_at_default"])
                 a["default"] = r["default_e_max"]
-    order = {"bf16": 0, "f16": 1, "f32": 2, "f64": 3, "f8": 4}
+    order = {"bf16": 0, "f16": 1, "f32": 2, "f64": 3, "f8": 4, "f8e5m2": 5}
     print("| dtype | B stored | n | trials | max rel. difference | in units of u | +20 % | paper law | library default "
           "| default / (+20 %) | flagged rows | max abs(E)/T during the run |")
     print("|---|---|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|")
@@ -113,7 +119,7 @@ def merge(paths):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16", "f32", "f64", "f8"])
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16", "f32", "f64", "f8", "f8e5m2"])
     ap.add_argument("--sizes", type=int, nargs="+", default=[256, 512, 1024, 2048, 4096])
     ap.add_argument("--trials", type=int, default=100)
     ap.add_argument("--transB", type=int, default=0)

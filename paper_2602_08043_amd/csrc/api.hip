@@ -156,7 +156,7 @@ static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; 
 static bool problem_ok(const vabft_problem* p) {
     if (!p) return false;
     if (p->M <= 0 || p->N <= 0 || p->K <= 0) return false;
-    if (p->dtype < VABFT_F64 || p->dtype > VABFT_F8E4M3) return false;
+    if (p->dtype < VABFT_F64 || p->dtype > VABFT_F8E5M2) return false;
     if (p->transB != 0 && p->transB != 1) return false;
     if (p->lda < p->K || p->ldc < p->N) return false;
     if (p->ldb < (p->transB ? p->K : p->N)) return false;
@@ -164,19 +164,30 @@ static bool problem_ok(const vabft_problem* p) {
 }
 
 // bytes of an element of A / B, and of C (an FP8 problem stores FP16)
+static inline bool is_fp8(int dtype) { return dtype == VABFT_F8E4M3 || dtype == VABFT_F8E5M2; }
 static inline size_t elem_bytes(int dtype) {
-    return dtype == VABFT_F64 ? 8 : dtype == VABFT_F32 ? 4 : dtype == VABFT_F8E4M3 ? 1 : 2;
+    return dtype == VABFT_F64 ? 8 : dtype == VABFT_F32 ? 4 : is_fp8(dtype) ? 1 : 2;
 }
-static inline size_t out_bytes(int dtype) { return dtype == VABFT_F8E4M3 ? 2 : elem_bytes(dtype); }
+static inline size_t out_bytes(int dtype) { return is_fp8(dtype) ? 2 : elem_bytes(dtype); }
 // types that run on the 256 x 256 tile kernels with FP32 accumulation
-static inline bool is_tile256(int dtype) { return dtype == VABFT_F16 || dtype == VABFT_BF16 || dtype == VABFT_F8E4M3; }
+static inline bool is_tile256(int dtype) { return dtype == VABFT_F16 || dtype == VABFT_BF16 || is_fp8(dtype); }
 static inline size_t acc_bytes(int dtype) { return dtype == VABFT_F64 ? 8 : 4; }
 static inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-static void tile_shape(int dtype, int* bm, int* bn) {
-    if (is_tile256(dtype)) {
+// FP32 / FP64 problems with fewer than 128 tiles of 128 x 128 (half the compute units or fewer would work) run
+// 64 x 64 tiles instead: 256^3 is 16 workgroups of 16 k-tiles then, not 4.  The block-wise route keeps the large
+// tile: its column blocks are what one wavefront of that tile sums.
+static bool small_wide_tiles(const vabft_problem* p) {
+    if (is_tile256(p->dtype)) return false;
+    return (((int64_t)p->M + 127) / 128) * (((int64_t)p->N + 127) / 128) < 128;
+}
+static void tile_shape(const vabft_problem* p, bool blockwise, int* bm, int* bn) {
+    if (is_tile256(p->dtype)) {
         *bm = 256;
         *bn = 256;
+    } else if (!blockwise && small_wide_tiles(p)) {
+        *bm = 64;
+        *bn = 64;
     } else {
         *bm = 128;
         *bn = 128;
@@ -202,7 +213,7 @@ static size_t tickets_offset(const vabft_problem* p) { return s_area_bytes(p); }
 // everything in front of the scratch area
 static size_t tickets_bytes(const vabft_problem* p) {
     int bm, bn;
-    tile_shape(p->dtype, &bm, &bn);
+    tile_shape(p, false, &bm, &bn);  // the smaller tile of the two routes: the larger count
     const size_t tiles_m = ((size_t)p->M + bm - 1) / bm;
     return tickets_offset(p) + round_up((tiles_m + 4) * sizeof(int32_t), 256);
 }
@@ -229,7 +240,7 @@ static int32_t* encode_ticket(const vabft_problem*, void* ws) {
 
 size_t gemm_workspace_bytes(const vabft_problem* p) {
     int bm, bn;
-    tile_shape(p->dtype, &bm, &bn);
+    tile_shape(p, false, &bm, &bn);  // the smaller tile of the two routes: the larger need
     const size_t tiles_n = ((size_t)p->N + bn - 1) / bn;
     const bool is16 = is_tile256(p->dtype);
     // 16-bit: rowpart + 4 A-statistics partials + weighted rowpart per tile-column; wide types: two
@@ -264,7 +275,7 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     a.ldb = p->ldb;
     a.ldc = p->ldc;
     int bm, bn;
-    tile_shape(p->dtype, &bm, &bn);
+    tile_shape(p, blocks != nullptr, &bm, &bn);
     a.tiles_m = (p->M + bm - 1) / bm;
     a.tiles_n = (p->N + bn - 1) / bn;
     const size_t eb = elem_bytes(p->dtype), ab = acc_bytes(p->dtype);
@@ -319,7 +330,7 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
         zero_int_kernel<<<1, 1, 0, st>>>(d_ninj);
     }
     // the unguarded kernels need whole tiles and 16-byte aligned rows
-    const int bk = p->dtype == VABFT_F8E4M3 ? 256 : (is16 ? 64 : 16);
+    const int bk = is_fp8(p->dtype) ? 256 : (is16 ? 64 : 16);
     // (the whole-tile 16-bit kernels address a tile's rows with 32-bit byte offsets from a per-wavefront base)
     const bool wide_rows = is16 && (p->lda > (1 << 24) || p->ldb > (1 << 24));
     const bool edge =
@@ -330,7 +341,7 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
         // the fused 16-bit kernel caches the checksum panel of the k-units a tile-column folds: at most 16
         // (units of 128 k, dealt round-robin to the tile-columns; the FP8 kernel: units of 256 k, 8 slots,
         // B stored N x K)
-        const bool fits16 = p->dtype == VABFT_F8E4M3
+        const bool fits16 = is_fp8(p->dtype)
                                 ? (a.tiles_n >= 2 && p->K % 256 == 0 && p->transB && (p->K / 256) / a.tiles_n + 2 <= 8)
                                 : (p->K % 128 == 0 && (p->K / 128 + a.tiles_n - 1) / a.tiles_n <= 16);
         if (in_kernel_finalize && (!is16 || fits16)) {
@@ -364,8 +375,9 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     }
     switch (p->dtype) {
         case VABFT_F8E4M3:
+        case VABFT_F8E5M2:
             if (edge || !p->transB) return VABFT_EUNSUPPORTED;
-            rc = gemm8_launch_f8_nt(a, mode, st);
+            rc = p->dtype == VABFT_F8E4M3 ? gemm8_launch_f8_nt(a, mode, st) : gemm8_launch_bf8_nt(a, mode, st);
             break;
         case VABFT_BF16:
             rc = p->transB ? gemm16_launch_bf16_nt(a, mode, edge, st) : gemm16_launch_bf16_nn(a, mode, edge, st);
@@ -373,8 +385,8 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
         case VABFT_F16:
             rc = p->transB ? gemm16_launch_f16_nt(a, mode, edge, st) : gemm16_launch_f16_nn(a, mode, edge, st);
             break;
-        case VABFT_F32: rc = gemmw_launch_f32(a, p->transB, mode, edge, st); break;
-        case VABFT_F64: rc = gemmw_launch_f64(a, p->transB, mode, edge, st); break;
+        case VABFT_F32: rc = gemmw_launch_f32(a, p->transB, mode, edge, bm / 2, st); break;
+        case VABFT_F64: rc = gemmw_launch_f64(a, p->transB, mode, edge, bm / 2, st); break;
         default: return VABFT_EINVAL;
     }
     if (rc != VABFT_OK || !verify) return rc;
@@ -478,7 +490,7 @@ double vabft_default_emax(int32_t dtype, int32_t K, int32_t N) {
     // FP8: the 32x32x64 matrix instruction does not carry full FP32 precision through its 64-term dot
     // product; measured by the same protocol (n = 256 .. 8192, 7 000 - 48 000 trials per size) the relative
     // difference is 31 - 72 u_FP32, largest at small n: a constant above every +20 % value.
-    if (dtype == VABFT_F8E4M3) return 5.5e-6;
+    if (is_fp8(dtype)) return 5.5e-6;
     if (dtype == VABFT_F64) {
         paper = 1.0e-17 * sqrt(n) + 2.5e-16;
         measured = 8.0e-18 * sqrt(n) + 5.2e-16;
@@ -493,7 +505,7 @@ double vabft_default_emax_offline(int32_t dtype, int32_t K, int32_t N) {
     // section 3.6 "Practical recommendations": a check made after a 16-bit write-back sees one
     // rounding of every element to the output type, e_max ~ 2 u_output
     if (dtype == VABFT_BF16) return 2.0 * 0.00390625;       // 2 * 2^-8
-    if (dtype == VABFT_F16 || dtype == VABFT_F8E4M3) return 2.0 * 0.00048828125;  // 2 * 2^-11 (FP16 output)
+    if (dtype == VABFT_F16 || is_fp8(dtype)) return 2.0 * 0.00048828125;  // 2 * 2^-11 (FP16 output)
     return vabft_default_emax(dtype, K, N);
 }
 
@@ -749,7 +761,8 @@ int vabft_locate_correct(const vabft_problem* p, void* dC, const void* d_expecte
         case VABFT_F32: VABFT_LOC_CASE(float, float); break;
         case VABFT_F16: VABFT_LOC_CASE(f16_t, float); break;
         case VABFT_BF16: VABFT_LOC_CASE(bf16_t, float); break;
-        case VABFT_F8E4M3: VABFT_LOC_CASE(f16_t, float); break;  // C of an FP8 problem is FP16
+        case VABFT_F8E4M3:
+        case VABFT_F8E5M2: VABFT_LOC_CASE(f16_t, float); break;  // C of an FP8 problem is FP16
         default: return VABFT_EINVAL;
     }
 #undef VABFT_LOC_CASE

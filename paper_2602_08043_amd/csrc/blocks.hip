@@ -558,6 +558,7 @@ int encode_blocks_dispatch(const vabft_problem* p, const void* dB, void* d_Be_bl
         case VABFT_F16: return encode_blocks_launch<f16_t>(p, dB, d_Be_blk, d_S_blk, ws, st);
         case VABFT_BF16: return encode_blocks_launch<bf16_t>(p, dB, d_Be_blk, d_S_blk, ws, st);
         case VABFT_F8E4M3: return encode_blocks_launch<f8_t>(p, dB, d_Be_blk, d_S_blk, ws, st);
+        case VABFT_F8E5M2: return encode_blocks_launch<bf8_t>(p, dB, d_Be_blk, d_S_blk, ws, st);
     }
     return VABFT_EINVAL;
 }
@@ -590,6 +591,7 @@ int threshold_blocks_dispatch(const vabft_problem* p, const void* dA, const void
         case VABFT_F16: VABFT_TB_CASE(f16_t);
         case VABFT_BF16: VABFT_TB_CASE(bf16_t);
         case VABFT_F8E4M3: VABFT_TB_CASE(f8_t);
+        case VABFT_F8E5M2: VABFT_TB_CASE(bf8_t);
     }
 #undef VABFT_TB_CASE
     return VABFT_EINVAL;

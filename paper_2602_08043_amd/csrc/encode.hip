@@ -95,11 +95,14 @@ __device__ __forceinline__ void row_terms(acc_t sum, acc_t mx, acc_t mn, int N, 
 // contiguous segment of the row, combined in segment order).  RPB is 16 when that gives enough
 // blocks to fill the chip, else 8, 4, 2 or 1.
 // ---------------------------------------------------------------------------
-constexpr int ENC_ROWS_WAVES = 16;
+#ifndef VABFT_ENC_ROWS_WAVES
+#define VABFT_ENC_ROWS_WAVES 16
+#endif
+constexpr int ENC_ROWS_WAVES = VABFT_ENC_ROWS_WAVES;
 
 // W: also the position-weighted checksum B*r2, r2 = [1..N] (section 2.2): Be2[k] = sum_n (n+1) B[k,n].
 template <typename T, bool W, int RPB>
-__global__ __launch_bounds__(1024) void encode_rows_kernel(const void* __restrict__ B, int K, int N, int64_t ldb,
+__global__ __launch_bounds__(64 * ENC_ROWS_WAVES) void encode_rows_kernel(const void* __restrict__ B, int K, int N, int64_t ldb,
                                                            typename Elem<T>::acc_t* __restrict__ Be,
                                                            typename Elem<T>::acc_t* __restrict__ Be2,
                                                            typename Elem<T>::acc_t* __restrict__ bstat, int vec_ok,
@@ -423,6 +426,10 @@ __global__ __launch_bounds__(256) void encode_cols_combine_kernel(const acc_t* _
 // A side: one wavefront per row m: (max, min, mean), dot with Be, threshold
 // ---------------------------------------------------------------------------
 // W: also the expected weighted checksum C^{r2} = A (B r2) (section 2.2).
+#ifndef VABFT_THR_NL
+#define VABFT_THR_NL 4
+#endif
+constexpr int THR_NL = VABFT_THR_NL;
 template <typename T, bool W>
 __global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restrict__ A, int M, int K, int N,
                                                              int64_t lda,
@@ -445,32 +452,25 @@ __global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restr
     if (vec_ok) {
         const int nchunks = K / V;
         int c = lane;
-        for (; c + 64 < nchunks; c += 128) {
-            raw16 r0 = ld16(row + (int64_t)c * 16);
-            raw16 r1 = ld16(row + (int64_t)(c + 64) * 16);
-            acc_t v0[V], v1[V], b0[V], b1[V];
+        // THR_NL 16-byte pieces of the row in flight per lane; the matching pieces of Be come from the caches
+        for (; c + 64 * (THR_NL - 1) < nchunks; c += 64 * THR_NL) {
+            raw16 r[THR_NL];
 #pragma unroll
-            for (int e = 0; e < V; ++e) {
-                b0[e] = Be[(int64_t)c * V + e];
-                b1[e] = Be[(int64_t)(c + 64) * V + e];
-            }
-            Unpack<T>::run(r0, v0);
-            Unpack<T>::run(r1, v1);
+            for (int u = 0; u < THR_NL; ++u) r[u] = ld16(row + (int64_t)(c + 64 * u) * 16);
 #pragma unroll
-            for (int e = 0; e < V; ++e) {
-                sum += v0[e];
-                dot = fma(v0[e], b0[e], dot);
-                if constexpr (W) dot2 = fma(v0[e], Be2[(int64_t)c * V + e], dot2);
-                mx = fmax(mx, v0[e]);
-                mn = fmin(mn, v0[e]);
-            }
+            for (int u = 0; u < THR_NL; ++u) {
+                acc_t v[V], b[V];
 #pragma unroll
-            for (int e = 0; e < V; ++e) {
-                sum += v1[e];
-                dot = fma(v1[e], b1[e], dot);
-                if constexpr (W) dot2 = fma(v1[e], Be2[(int64_t)(c + 64) * V + e], dot2);
-                mx = fmax(mx, v1[e]);
-                mn = fmin(mn, v1[e]);
+                for (int e = 0; e < V; ++e) b[e] = Be[(int64_t)(c + 64 * u) * V + e];
+                Unpack<T>::run(r[u], v);
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    sum += v[e];
+                    dot = fma(v[e], b[e], dot);
+                    if constexpr (W) dot2 = fma(v[e], Be2[(int64_t)(c + 64 * u) * V + e], dot2);
+                    mx = fmax(mx, v[e]);
+                    mn = fmin(mn, v[e]);
+                }
             }
         }
         for (; c < nchunks; c += 64) {
@@ -587,7 +587,7 @@ __global__ __launch_bounds__(256) void check_offline_kernel(const void* __restri
 // fewer than 512 blocks (the pass is bound by the loads in flight; every halving doubles the slab partials the
 // finishing kernel folds, and below 64 that costs more than it brings)
 static int col_rows_per_block(int dtype, int64_t rows, int64_t cols) {
-    const int64_t v = dtype == VABFT_F64 ? 2 : dtype == VABFT_F32 ? 4 : dtype == VABFT_F8E4M3 ? 16 : 8;
+    const int64_t v = dtype == VABFT_F64 ? 2 : dtype == VABFT_F32 ? 4 : (dtype == VABFT_F8E4M3 || dtype == VABFT_F8E5M2) ? 16 : 8;
     const int64_t xblocks = (cols + 64 * v - 1) / (64 * v);
     return xblocks * ((rows + 127) / 128) < 512 ? 64 : 128;
 }
@@ -596,7 +596,7 @@ static int col_rows_per_block(int dtype, int64_t rows, int64_t cols) {
 // chip's 256 compute units without a block
 static int encode_rows_per_block(const vabft_problem* p) {
     if (p->transB) return 16;
-    int rpb = 16;
+    int rpb = ENC_ROWS_WAVES;
     while (rpb > 1 && (p->K + rpb - 1) / rpb < 256) rpb >>= 1;
     return rpb;
 }
@@ -625,8 +625,9 @@ static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, voi
     const int kblocks = s_partial_count(p);
     if (!p->transB) {
 #define VABFT_ENC_ROWS(R)                                                                                       \
-    encode_rows_kernel<T, W, R><<<dim3(kblocks), dim3(64 * ENC_ROWS_WAVES), 0, st>>>(                           \
-        dB, p->K, p->N, p->ldb, (acc_t*)d_Be, (acc_t*)d_Be2, (acc_t*)d_bstat, vec_ok, s_partial, ticket, d_S)
+    if constexpr (R <= ENC_ROWS_WAVES)                                                                          \
+        encode_rows_kernel<T, W, R><<<dim3(kblocks), dim3(64 * ENC_ROWS_WAVES), 0, st>>>(                       \
+            dB, p->K, p->N, p->ldb, (acc_t*)d_Be, (acc_t*)d_Be2, (acc_t*)d_bstat, vec_ok, s_partial, ticket, d_S)
         switch (encode_rows_per_block(p)) {
             case 16: VABFT_ENC_ROWS(16); break;
             case 8: VABFT_ENC_ROWS(8); break;
@@ -662,6 +663,7 @@ int encode_dispatch(const vabft_problem* p, const void* dB, void* d_Be, void* d_
         case VABFT_F16: VABFT_ENC_CASE(f16_t);
         case VABFT_BF16: VABFT_ENC_CASE(bf16_t);
         case VABFT_F8E4M3: VABFT_ENC_CASE(f8_t);
+        case VABFT_F8E5M2: VABFT_ENC_CASE(bf8_t);
     }
 #undef VABFT_ENC_CASE
     return VABFT_EINVAL;
@@ -694,6 +696,7 @@ int threshold_dispatch(const vabft_problem* p, const void* dA, const void* d_Be,
         case VABFT_F16: VABFT_THR_CASE(f16_t);
         case VABFT_BF16: VABFT_THR_CASE(bf16_t);
         case VABFT_F8E4M3: VABFT_THR_CASE(f8_t);
+        case VABFT_F8E5M2: VABFT_THR_CASE(bf8_t);
     }
 #undef VABFT_THR_CASE
     return VABFT_EINVAL;
@@ -825,6 +828,9 @@ int threshold_cols_dispatch(const vabft_problem* p, const void* dB, const void* 
         case VABFT_F8E4M3:
             return threshold_cols_launch<f8_t>(p, dB, d_eA, d_SA, e_max, c_sigma, d_bcolstat, d_expected_col, d_Tcol,
                                                ws, st);
+        case VABFT_F8E5M2:
+            return threshold_cols_launch<bf8_t>(p, dB, d_eA, d_SA, e_max, c_sigma, d_bcolstat, d_expected_col, d_Tcol,
+                                                ws, st);
     }
     return VABFT_EINVAL;
 }
@@ -845,7 +851,8 @@ int check_offline_dispatch(const vabft_problem* p, const void* dC, const void* d
         case VABFT_F64: VABFT_OFF_CASE(double)
         case VABFT_F32: VABFT_OFF_CASE(float)
         case VABFT_F16: VABFT_OFF_CASE(f16_t)
-        case VABFT_F8E4M3: VABFT_OFF_CASE(f16_t)  // the stored product of an FP8 problem is FP16
+        case VABFT_F8E4M3:
+        case VABFT_F8E5M2: VABFT_OFF_CASE(f16_t)  // the stored product of an FP8 problem is FP16
         case VABFT_BF16: VABFT_OFF_CASE(bf16_t)
         default: return VABFT_EINVAL;
     }

@@ -1,5 +1,6 @@
-// FP8 (OCP E4M3) GEMM with FP32 accumulation and FP16 output on the gfx950 matrix cores
-// (v_mfma_f32_32x32x64_f8f6f4), for whole-tile problems with B stored N x K:
+// FP8 (OCP E4M3 or E5M2) GEMM with FP32 accumulation and FP16 output on the gfx950 matrix cores
+// (v_mfma_f32_32x32x64_f8f6f4; the instruction's format selectors choose between the two encodings, and
+// the conversion instruction of the fused statistics follows), for whole-tile problems with B stored N x K:
 // M % 256 == 0, N % 256 == 0, K % 256 == 0, 16-byte aligned rows.
 //
 // The paper treats FP8 as one more input precision of the same accumulation strategy ("FP8 inputs ->
@@ -33,14 +34,18 @@ constexpr int BKB = 128;  // bytes (= k-values) per tile row
 struct alignas(16) raw32 {
     raw16 lo, hi;
 };
-__device__ __forceinline__ f32x16_t mfma_f8(const raw32& a, const raw32& b, f32x16_t c) {
-    // cbsz = blgp = 0: both operands E4M3; no block scaling
+// FMT: 0 = E4M3, 1 = E5M2 (the instruction's cbsz / blgp format codes), both operands alike; no block scaling
+template <int FMT> __device__ __forceinline__ f32x16_t mfma_f8(const raw32& a, const raw32& b, f32x16_t c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(__builtin_bit_cast(i32x8_t, a), __builtin_bit_cast(i32x8_t, b),
-                                                           c, 0, 0, 0, 0, 0, 0);
+                                                           c, FMT, FMT, 0, 0, 0, 0);
+}
+template <int FMT, int BYTE> __device__ __forceinline__ float cvt_f8(int w) {
+    if constexpr (FMT == 0) return __builtin_amdgcn_cvt_f32_fp8(w, BYTE);
+    else return __builtin_amdgcn_cvt_f32_bf8(w, BYTE);
 }
 }  // namespace g8f
 
-template <int MODE, bool FUSED>
+template <int FMT, int MODE, bool FUSED>
 __global__ __launch_bounds__(256) void gemm8_fast_kernel(const GemmArgs g) {
     using namespace g8f;
     constexpr bool CSUM = MODE == 2 || MODE == 4;
@@ -149,8 +154,7 @@ __global__ __launch_bounds__(256) void gemm8_fast_kernel(const GemmArgs g) {
         constexpr int mi = slot >> 2, d = slot & 3;
         const uint32_t lo = af[mi].lo.w[d], hi = af[mi].hi.w[d];
         const int w = (int)(wn ? hi : lo);
-        const float x0 = __builtin_amdgcn_cvt_f32_fp8(w, 0), x1 = __builtin_amdgcn_cvt_f32_fp8(w, 1);
-        const float x2 = __builtin_amdgcn_cvt_f32_fp8(w, 2), x3 = __builtin_amdgcn_cvt_f32_fp8(w, 3);
+        const float x0 = cvt_f8<FMT, 0>(w), x1 = cvt_f8<FMT, 1>(w), x2 = cvt_f8<FMT, 2>(w), x3 = cvt_f8<FMT, 3>(w);
         st[mi][0] += (x0 + x1) + (x2 + x3);
         st[mi][1] += fmaf(x1, bev[d][1], x0 * bev[d][0]) + fmaf(x3, bev[d][3], x2 * bev[d][2]);
         st[mi][2] = fmaxf(fmaxf(fmaxf(st[mi][2], x0), x1), fmaxf(x2, x3));
@@ -175,7 +179,7 @@ __global__ __launch_bounds__(256) void gemm8_fast_kernel(const GemmArgs g) {
         static_for<0, 16>([&](auto slot_c) {
             constexpr int slot = decltype(slot_c)::value;
             constexpr int mi = slot >> 2, ni = slot & 3;
-            acc[mi][ni] = mfma_f8(bf[ni], af[mi], acc[mi][ni]);
+            acc[mi][ni] = mfma_f8<FMT>(bf[ni], af[mi], acc[mi][ni]);
             __builtin_amdgcn_sched_barrier(0);  // MFMA first, the rest of the slot in its shadow
             frag_op(s_c, ks_c, slot_c, naf, nbf);
             if constexpr (LOADS) issue_load(std::integral_constant<int, S ^ 1>{}, slot_c, ap, bp);
@@ -253,7 +257,7 @@ __global__ __launch_bounds__(256) void gemm8_fast_kernel(const GemmArgs g) {
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = mfma_f8(bf1[ni], af1[mi], acc[mi][ni]);  // step (nk-1, 1)
+            for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = mfma_f8<FMT>(bf1[ni], af1[mi], acc[mi][ni]);  // step (nk-1, 1)
         // ... which is k-step 0 of the unit that would follow the last one
         if (hu == nunits) {
             load_bev(hj, I0{});
@@ -267,19 +271,19 @@ __global__ __launch_bounds__(256) void gemm8_fast_kernel(const GemmArgs g) {
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = mfma_f8(bf1[ni], af1[mi], acc[mi][ni]);  // step (nk-1, 1)
+            for (int ni = 0; ni < 4; ++ni) acc[mi][ni] = mfma_f8<FMT>(bf1[ni], af1[mi], acc[mi][ni]);  // step (nk-1, 1)
     }
 
     gemm16_fast_epilogue<f16_t, MODE, FUSED>(g, acc, st, smem, bm, bn, row0, col0, tid, lane, wm, wn, l32, lh);
 }
 
-static int gemm8_fast_launch(const GemmArgs& a, int mode, hipStream_t st) {
+template <int FMT> static int gemm8_fast_launch(const GemmArgs& a, int mode, hipStream_t st) {
     const dim3 grid(a.tiles_m * a.tiles_n), block(256);
     const bool fused = a.fused_stats != 0;
     const size_t lds = fused ? g16f::LDS_BYTES_FUSED : g16::LDS_BYTES;
 #define VABFT_G8F_CASE(VF, FU)                                                                             \
     if (mode == VF && fused == FU) {                                                                       \
-        auto kern = gemm8_fast_kernel<VF, FU>;                                                             \
+        auto kern = gemm8_fast_kernel<FMT, VF, FU>;                                                             \
         static bool attr_set = false;                                                                      \
         if (!attr_set) {                                                                                   \
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \

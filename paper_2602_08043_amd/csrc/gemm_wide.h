@@ -3,7 +3,8 @@
 // section 6.1 injector).  These MFMAs take one element per lane and are 16 passes long, so
 // the kernel is matrix-core bound with a simple LDS staging.
 //
-// Tile 128 x 128 x 16 per workgroup of 4 wavefronts (2 x 2), 64 x 64 per wavefront.
+// Tile 128 x 128 x 16 per workgroup of 4 wavefronts (2 x 2), 64 x 64 per wavefront (WT = 64); problems with so
+// few such tiles that most compute units would idle run 64 x 64 x 16 tiles, 32 x 32 per wavefront (WT = 32).
 // Result layout per MFMA tile (probed on the device): lane l owns column (l % MT);
 //   32x32 (FP32): register r is row 8*(r/4) + 4*(l/32) + r%4
 //   16x16 (FP64): register r is row (l/16) + 4*r
@@ -43,18 +44,23 @@ template <> struct WideCfg<double> {
 };
 
 namespace gw {
-constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int BK = 16;
 constexpr int LDK = BK + 1;  // [row][k] layout, padded
-template <typename T> constexpr int ldn() { return BN + 16 / (int)sizeof(T); }  // [k][n] layout, padded, 16 B aligned
-template <typename T> constexpr int a_elems() { return BM * LDK; }
-template <typename T> constexpr int b_elems() { return (BN * LDK) > (BK * ldn<T>()) ? (BN * LDK) : (BK * ldn<T>()); }
-template <typename T> constexpr int stage_elems() { return a_elems<T>() + b_elems<T>(); }
-template <typename T> constexpr int loop_bytes() { return 2 * stage_elems<T>() * (int)sizeof(T); }
-template <typename T> constexpr int epi_bytes() { return 4 * 64 * (64 + 16 / (int)sizeof(T)) * (int)sizeof(T); }
+// WT: rows = columns of a wavefront's tile; the workgroup's tile is 2 WT x 2 WT
+template <typename T, int WT> constexpr int ldn() { return 2 * WT + 16 / (int)sizeof(T); }  // [k][n] layout, padded, 16 B aligned
+template <typename T, int WT> constexpr int a_elems() { return 2 * WT * LDK; }
+template <typename T, int WT> constexpr int b_elems() {
+    return (2 * WT * LDK) > (BK * ldn<T, WT>()) ? (2 * WT * LDK) : (BK * ldn<T, WT>());
+}
+template <typename T, int WT> constexpr int stage_elems() { return a_elems<T, WT>() + b_elems<T, WT>(); }
+template <typename T, int WT> constexpr int loop_bytes() { return 2 * stage_elems<T, WT>() * (int)sizeof(T); }
+template <typename T, int WT> constexpr int epi_bytes() { return 4 * WT * (WT + 16 / (int)sizeof(T)) * (int)sizeof(T); }
 // 16 more bytes behind the larger of the two for the "last workgroup of the tile-row" flag
-template <typename T> constexpr int flag_offset() { return loop_bytes<T>() > epi_bytes<T>() ? loop_bytes<T>() : epi_bytes<T>(); }
+template <typename T, int WT> constexpr int flag_offset() {
+    return loop_bytes<T, WT>() > epi_bytes<T, WT>() ? loop_bytes<T, WT>() : epi_bytes<T, WT>();
+}
 // ... and 12 doubles for the fold of the S1..S3 partials of an encode that deferred it
-template <typename T> constexpr int lds_bytes() { return flag_offset<T>() + 16 + 96; }
+template <typename T, int WT> constexpr int lds_bytes() { return flag_offset<T, WT>() + 16 + 96; }
 
 // Partials exchanged between workgroups (possibly on different XCDs, each with a private L2) go
 // through device-scope relaxed atomic stores and loads, performed at the device's coherence
@@ -83,16 +89,17 @@ template <> __device__ __forceinline__ constexpr double lowest<double>() { retur
 // MODE 0: plain GEMM; 1: fused row-sum check; 2: check, fault injector, weighted row sums and
 // column sums; 3: check and weighted row sums; 4: check and column sums.
 // FUSED (whole tiles only): also the A-side statistics, expected checksum and thresholds.
-template <typename T, int TRANSB, int MODE, bool EDGE, bool FUSED>
+template <typename T, int WT, int TRANSB, int MODE, bool EDGE, bool FUSED>
 __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     using namespace gw;
+    constexpr int BM = 2 * WT, BN = 2 * WT;
     constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE == 2 || MODE == 3;
     constexpr bool CSUM = MODE == 2 || MODE == 4;
     static_assert(!FUSED || (VERIFY && !EDGE), "fused statistics belong to the whole-tile verified kernel");
     using Cfg = WideCfg<T>;
     using accv_t = typename Cfg::accv_t;
     constexpr int MT = Cfg::MT, KM = Cfg::KM, NR = Cfg::NR, V = Cfg::V;
-    constexpr int TM = 64 / MT;  // MFMA tiles per wavefront in each direction
+    constexpr int TM = WT / MT;  // MFMA tiles per wavefront in each direction
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     T* smem = reinterpret_cast<T*>(smem_raw);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -155,8 +162,8 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     };
 
     auto store_tiles = [&](int s) {
-        T* As = smem + s * stage_elems<T>();
-        T* Bs = As + a_elems<T>();
+        T* As = smem + s * stage_elems<T, WT>();
+        T* Bs = As + a_elems<T, WT>();
 #pragma unroll
         for (int p = 0; p < NCH_A; ++p) {
             const int id = tid + 256 * p, r = id / CPR, c = id % CPR;
@@ -175,7 +182,7 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
             for (int p = 0; p < NCH_B; ++p) {
                 const int id = tid + 256 * p, kr = id / CPK, c = id % CPK;
 #pragma unroll
-                for (int e = 0; e < V; ++e) Bs[kr * ldn<T>() + c * V + e] = rb[p][e];
+                for (int e = 0; e < V; ++e) Bs[kr * ldn<T, WT>() + c * V + e] = rb[p][e];
             }
         }
     };
@@ -220,17 +227,17 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     };
 
     auto compute = [&](int s) {
-        const T* As = smem + s * stage_elems<T>();
-        const T* Bs = As + a_elems<T>();
+        const T* As = smem + s * stage_elems<T, WT>();
+        const T* Bs = As + a_elems<T, WT>();
 #pragma unroll
         for (int ks = 0; ks < BK / KM; ++ks) {
             T af[TM], bf[TM];
             const int k = ks * KM + lk;
 #pragma unroll
-            for (int mi = 0; mi < TM; ++mi) af[mi] = As[(wm * 64 + mi * MT + lm) * LDK + k];
+            for (int mi = 0; mi < TM; ++mi) af[mi] = As[(wm * WT + mi * MT + lm) * LDK + k];
 #pragma unroll
             for (int ni = 0; ni < TM; ++ni)
-                bf[ni] = TRANSB ? Bs[(wn * 64 + ni * MT + lm) * LDK + k] : Bs[k * ldn<T>() + wn * 64 + ni * MT + lm];
+                bf[ni] = TRANSB ? Bs[(wn * WT + ni * MT + lm) * LDK + k] : Bs[k * ldn<T, WT>() + wn * WT + ni * MT + lm];
 #pragma unroll
             for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
@@ -242,7 +249,7 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     int next_fold = bn;  // FUSED: the next k-tile this tile-column folds into the statistics
     if (FUSED) load_be(0);
     if (FUSED && !g.S)
-        fold_s_partials_to_lds(g.s_partial, g.s_nparts, tid, reinterpret_cast<double*>(smem_raw + flag_offset<T>() + 16));
+        fold_s_partials_to_lds(g.s_partial, g.s_nparts, tid, reinterpret_cast<double*>(smem_raw + flag_offset<T, WT>() + 16));
     load_tiles(0);
     store_tiles(0);
     if (FUSED && next_fold == 0) {
@@ -290,23 +297,24 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
         }
         __syncthreads();
         T* ap = reinterpret_cast<T*>(g.apart) + (int64_t)bn * 4 * g.M + row0;
+        constexpr int QPT = 4 * BM / 256;  // values per thread: 256 threads publish 4 x BM values
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int q = 2 * (tid / BM) + h, r = tid % BM;
+        for (int h = 0; h < QPT; ++h) {
+            const int q = QPT * (tid / BM) + h, r = tid % BM;
             st_dev(ap + q * (int64_t)g.M + r, sred[q * BM + r]);
         }
         __syncthreads();  // the accumulator tiles are parked over this area next
     }
 
     // ---- epilogue through LDS ------------------------------------------------------------
-    // Each wavefront parks its 64 x 64 accumulator tile in a private, padded LDS buffer (the
+    // Each wavefront parks its WT x WT accumulator tile in a private, padded LDS buffer (the
     // accumulators are only stored, never used as vector operands, so they stay in the
     // accumulation registers through the main loop).  Element (mi, ni, r) is tile row
     // mi*MT + row_of(r, lane), tile column ni*MT + lane%MT.  From there: the injector edits
     // elements in place, lane l sums row l in column order, and rows are copied to C in
     // 16-byte pieces that are contiguous along a row.
-    constexpr int PITCH = 64 + 16 / (int)sizeof(T);  // elements; 4 banks of skew per row
-    T* tile = smem + wave * (64 * PITCH);
+    constexpr int PITCH = WT + 16 / (int)sizeof(T);  // elements; 4 banks of skew per row
+    T* tile = smem + wave * (WT * PITCH);
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
@@ -316,14 +324,14 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
                 tile[(mi * MT + Cfg::row_of(r, lane)) * PITCH + ni * MT + lm] = acc[mi][ni][r];
     // LDS operations of one wavefront complete in order; the compiler must keep that order too
     asm volatile("" ::: "memory");
-    const int trow0 = row0 + wm * 64, tcol0 = col0 + wn * 64;
+    const int trow0 = row0 + wm * WT, tcol0 = col0 + wn * WT;
 
     if (INJECT) {
         const InjectArgs& inj = g.inj;
         if (inj.mode == 1) {
             for (int e = 0; e < inj.n_list; ++e) {
                 const int fr = inj.d_list[3 * e], fc = inj.d_list[3 * e + 1], fb = inj.d_list[3 * e + 2];
-                if (fr < trow0 || fr >= trow0 + 64 || fc < tcol0 || fc >= tcol0 + 64) continue;
+                if (fr < trow0 || fr >= trow0 + WT || fc < tcol0 || fc >= tcol0 + WT) continue;
                 if (fr >= g.M || fc >= g.N || fb < 0 || fb >= acc_bits<T>()) continue;
                 if (lane == 0) {
                     T* p = tile + (fr - trow0) * PITCH + (fc - tcol0);
@@ -334,8 +342,8 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
             }
         } else if (inj.mode == 2) {
             const int gi = trow0 + lane;  // lane l walks row l of the tile
-            if (gi < g.M) {
-                for (int c = 0; c < 64; ++c) {
+            if (lane < WT && gi < g.M) {
+                for (int c = 0; c < WT; ++c) {
                     const int gj = tcol0 + c;
                     if (gj >= g.N) break;
                     const int bit = bernoulli_bit(inj, gi, gj, g.N);
@@ -353,13 +361,14 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
 
     if (VERIFY) {
         // row sum of the accumulator tile (section 2.2 C^{r1'} = C r1, before any rounding of C):
-        // lane l adds the 64 columns of row l; partial index 2*bn + wn
+        // lane l < WT adds the WT columns of row l; partial index 2*bn + wn
         // (pairwise inside each 16-byte chunk, chunk sums into four rotating accumulators that
-        // are folded pairwise at the end: a short error chain instead of 64 sequential adds)
-        const T* rowp = tile + lane * PITCH;
+        // are folded pairwise at the end: a short error chain instead of WT sequential adds)
+        const bool has_row = WT == 64 || lane < WT;
+        const T* rowp = tile + (has_row ? lane : 0) * PITCH;
         T part[4] = {0, 0, 0, 0};
 #pragma unroll
-        for (int c = 0; c < 64; c += V) {
+        for (int c = 0; c < WT; c += V) {
             T v[V];
             const raw16 q = *reinterpret_cast<const raw16*>(rowp + c);
             __builtin_memcpy(v, &q, 16);
@@ -372,16 +381,17 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
         }
         const T s = (part[0] + part[1]) + (part[2] + part[3]);
         const int gi = trow0 + lane;
-        if (!EDGE)
-            st_dev(reinterpret_cast<T*>(g.rowpart) + (int64_t)(2 * bn + wn) * g.M + gi, s);
-        else if (gi < g.M)
+        if (!EDGE) {
+            if (has_row) st_dev(reinterpret_cast<T*>(g.rowpart) + (int64_t)(2 * bn + wn) * g.M + gi, s);
+        } else if (has_row && gi < g.M) {
             reinterpret_cast<T*>(g.rowpart)[(int64_t)(2 * bn + wn) * g.M + gi] = s;
+        }
         if (WSUM) {
-            // position-weighted row sum (section 2.2 C^{r2'} = C r2, r2 = [1..N]): weights 0..63
+            // position-weighted row sum (section 2.2 C^{r2'} = C r2, r2 = [1..N]): weights 0..WT-1
             // inside the tile, the offset of the tile's first column applied once to s
             T part2[4] = {0, 0, 0, 0};
 #pragma unroll
-            for (int c = 0; c < 64; c += V) {
+            for (int c = 0; c < WT; c += V) {
                 T v[V];
                 const raw16 q = *reinterpret_cast<const raw16*>(rowp + c);
                 __builtin_memcpy(v, &q, 16);
@@ -391,21 +401,23 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
                 part2[(c / V) & 3] += cs;
             }
             const T s2 = fma((T)(tcol0 + 1), s, (part2[0] + part2[1]) + (part2[2] + part2[3]));
-            if (!EDGE)
-                st_dev(reinterpret_cast<T*>(g.rowpart2) + (int64_t)(2 * bn + wn) * g.M + gi, s2);
-            else if (gi < g.M)
+            if (!EDGE) {
+                if (has_row) st_dev(reinterpret_cast<T*>(g.rowpart2) + (int64_t)(2 * bn + wn) * g.M + gi, s2);
+            } else if (has_row && gi < g.M) {
                 reinterpret_cast<T*>(g.rowpart2)[(int64_t)(2 * bn + wn) * g.M + gi] = s2;
+            }
         }
     }
 
     if (CSUM) {
-        // column sums of the accumulator tile (section 2.2 C^{c1'} = c1 C): lane c adds the 64 rows of
+        // column sums of the accumulator tile (section 2.2 C^{c1'} = c1 C): lane c < WT adds the WT rows of
         // column c (consecutive lanes read consecutive LDS words); partial index 2*bm + wm
+        const bool has_col = WT == 64 || lane < WT;
         T part[4] = {0, 0, 0, 0};
 #pragma unroll
-        for (int r = 0; r < 64; ++r) part[r & 3] += tile[r * PITCH + lane];
+        for (int r = 0; r < WT; ++r) part[r & 3] += tile[r * PITCH + (has_col ? lane : 0)];
         const int gj = tcol0 + lane;
-        if (gj < g.N)
+        if (has_col && gj < g.N)
             reinterpret_cast<T*>(g.colpart)[(int64_t)(2 * bm + wm) * g.N + gj] = (part[0] + part[1]) + (part[2] + part[3]);
     }
 
@@ -418,7 +430,7 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
             // Every thread's partials are performed (vmcnt(0)) before the workgroup takes this
             // tile-row's arrival ticket; the check runs before the store of C because behind that
             // burst of stores each of these round trips would cost several microseconds.
-            int* s_last = reinterpret_cast<int*>(smem_raw + flag_offset<T>());
+            int* s_last = reinterpret_cast<int*>(smem_raw + flag_offset<T, WT>());
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
             if (tid == 0) *s_last = (atomicAdd(&g.tickets[bm], 1) == g.tiles_n - 1);
@@ -508,7 +520,7 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
                         const double mu = (double)sum / (double)g.K;
                         double var = ((double)mx - mu) * (mu - (double)mn);
                         var = var > 0 ? var : 0;
-                        const double* s_red = reinterpret_cast<const double*>(smem_raw + flag_offset<T>() + 16);
+                        const double* s_red = reinterpret_cast<const double*>(smem_raw + flag_offset<T, WT>() + 16);
                         const double S1 = g.S ? g.S[0] : folded_s(s_red, 0), S2 = g.S ? g.S[1] : folded_s(s_red, 1),
                                      S3 = g.S ? g.S[2] : folded_s(s_red, 2), dN = (double)g.N;
                         const double t_det = dN * fabs(mu) * S1;
@@ -551,9 +563,9 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     }
 
     T* __restrict__ C = reinterpret_cast<T*>(g.C);
-    constexpr int CPRW = 64 / V;  // 16-byte chunks per tile row
+    constexpr int CPRW = WT / V;  // 16-byte chunks per tile row
 #pragma unroll 4
-    for (int it = 0; it < 64 * CPRW / 64; ++it) {
+    for (int it = 0; it < WT * CPRW / 64; ++it) {
         const int idx = lane + 64 * it, r = idx / CPRW, c = (idx % CPRW) * V;
         const raw16 q = *reinterpret_cast<const raw16*>(tile + r * PITCH + c);
         const int gi = trow0 + r, gj = tcol0 + c;
@@ -575,14 +587,15 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     }
 }
 
-template <typename T>
-static int gemmw_launch(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st) {
+// WT: 64 (128 x 128 tiles) or 32 (64 x 64 tiles); a.tiles_m / a.tiles_n count tiles of that size
+template <typename T, int WT>
+static int gemmw_launch_wt(const GemmArgs& a, int transB, int mode, bool edge, hipStream_t st) {
     const bool fused = a.fused_stats != 0;
     const dim3 grid(a.tiles_m * a.tiles_n), block(256);
-    const size_t lds = gw::lds_bytes<T>();
+    const size_t lds = gw::lds_bytes<T, WT>();
 #define VABFT_GW_CASE(TB, VF, ED, FU)                                                                      \
     if (transB == TB && mode == VF && edge == ED && fused == FU) {                                         \
-        auto kern = gemmw_kernel<T, TB, VF, ED, FU>;                                                       \
+        auto kern = gemmw_kernel<T, WT, TB, VF, ED, FU>;                                                   \
         static bool attr_set = false;                                                                      \
         if (!attr_set) {                                                                                   \
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
@@ -620,6 +633,12 @@ static int gemmw_launch(const GemmArgs& a, int transB, int mode, bool edge, hipS
     VABFT_GW_CASE(1, 2, false, true)
 #undef VABFT_GW_CASE
     return VABFT_EINVAL;
+}
+
+template <typename T>
+static int gemmw_launch(const GemmArgs& a, int transB, int mode, bool edge, int wave_tile, hipStream_t st) {
+    return wave_tile == 32 ? gemmw_launch_wt<T, 32>(a, transB, mode, edge, st)
+                           : gemmw_launch_wt<T, 64>(a, transB, mode, edge, st);
 }
 
 }  // namespace vabft

@@ -46,6 +46,20 @@ template <> struct Unpack<f8_t> {
         return Elem<f8_t>::to_acc(reinterpret_cast<const uint8_t*>(base)[idx]);
     }
 };
+template <> struct Unpack<bf8_t> {
+    static __device__ __forceinline__ void run(const raw16& r, float (&v)[16]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[4 * i + 0] = __builtin_amdgcn_cvt_f32_bf8((int)r.w[i], 0);
+            v[4 * i + 1] = __builtin_amdgcn_cvt_f32_bf8((int)r.w[i], 1);
+            v[4 * i + 2] = __builtin_amdgcn_cvt_f32_bf8((int)r.w[i], 2);
+            v[4 * i + 3] = __builtin_amdgcn_cvt_f32_bf8((int)r.w[i], 3);
+        }
+    }
+    static __device__ __forceinline__ float one(const void* base, int64_t idx) {
+        return Elem<bf8_t>::to_acc(reinterpret_cast<const uint8_t*>(base)[idx]);
+    }
+};
 template <> struct Unpack<float> {
     static __device__ __forceinline__ void run(const raw16& r, float (&v)[4]) {
 #pragma unroll

@@ -14,7 +14,8 @@ constexpr int WAVE = 64;
 // ---------------------------------------------------------------------------
 struct bf16_t { uint16_t bits; };
 struct f16_t { _Float16 v; };
-struct f8_t { uint8_t bits; };  // OCP FP8 E4M3
+struct f8_t { uint8_t bits; };   // OCP FP8 E4M3
+struct bf8_t { uint8_t bits; };  // OCP FP8 E5M2
 
 template <typename T> struct Elem;
 
@@ -54,6 +55,13 @@ template <> struct Elem<f8_t> {
     static constexpr int bytes = 1;
     static constexpr int vec = 16;  // elements per 16-byte chunk
     static __device__ __forceinline__ float to_acc(uint8_t raw) { return __builtin_amdgcn_cvt_f32_fp8((int)raw, 0); }
+};
+
+template <> struct Elem<bf8_t> {
+    using acc_t = float;
+    static constexpr int bytes = 1;
+    static constexpr int vec = 16;
+    static __device__ __forceinline__ float to_acc(uint8_t raw) { return __builtin_amdgcn_cvt_f32_bf8((int)raw, 0); }
 };
 
 template <> struct Elem<float> {

@@ -10,8 +10,8 @@ import torch
 from . import binding as vb
 
 _TORCH_DTYPE = {"f64": torch.float64, "f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16,
-                "f8": torch.float8_e4m3fn}
-_OUT_DTYPE = {"f8": "f16"}  # FP8 problems store an FP16 product
+                "f8": torch.float8_e4m3fn, "f8e5m2": torch.float8_e5m2}
+_OUT_DTYPE = {"f8": "f16", "f8e5m2": "f16"}  # FP8 problems store an FP16 product
 _REC_DTYPE = np.dtype([("row", "<i4"), ("col", "<i4"), ("bit", "<i4"), ("pad", "<i4"), ("before", "<f8"),
                        ("after", "<f8")])
 
@@ -20,8 +20,8 @@ def to_device(x: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
     """Storage array (see workloads.py) -> device tensor of the matching torch dtype."""
     if dtype == "bf16":
         return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).to(device).view(torch.bfloat16)
-    if dtype == "f8":
-        return torch.from_numpy(np.ascontiguousarray(x, dtype=np.uint8)).to(device).view(torch.float8_e4m3fn)
+    if dtype in ("f8", "f8e5m2"):
+        return torch.from_numpy(np.ascontiguousarray(x, dtype=np.uint8)).to(device).view(_TORCH_DTYPE[dtype])
     return torch.from_numpy(np.ascontiguousarray(x)).to(device)
 
 

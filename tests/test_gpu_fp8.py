@@ -1,4 +1,4 @@
-"""FP8 (OCP E4M3) inputs with FP32 accumulation and FP16 output (paper section 3.6: "FP8 inputs -> FP32
+"""FP8 (OCP E4M3 and E5M2) inputs with FP32 accumulation and FP16 output (paper section 3.6: "FP8 inputs -> FP32
 accumulation -> FP16 output"): parity of the whole path with the CPU oracle.  The GEMM takes whole
 256 x 256 x 256 tiles with B stored N x K; the streaming passes take any shape."""
 import numpy as np
@@ -15,41 +15,45 @@ from test_gpu_weighted import check_weighted  # noqa: E402
 from test_gpu_columns import check_columns  # noqa: E402
 
 
-def _gen8(M, N, K, transB, seed, dist="n_1e-6_1"):
+FORMATS = ["f8", "f8e5m2"]   # E4M3, E5M2 (section 3.6 names both)
+
+
+def _gen8(M, N, K, transB, seed, dist="n_1e-6_1", f8="f8"):
     g = wl.rng(seed, 19)
-    A = wl.to_storage(wl.paper_distribution(g, dist, (M, K)), "f8")
+    A = wl.to_storage(wl.paper_distribution(g, dist, (M, K)), f8)
     Bl = wl.paper_distribution(g, dist, (K, N))
-    B = wl.to_storage(np.ascontiguousarray(Bl.T) if transB else Bl, "f8")
+    B = wl.to_storage(np.ascontiguousarray(Bl.T) if transB else Bl, f8)
     return A, B
 
 
-def check_C8(r, o, A_st, B_st, transB):
+def check_C8(r, o, A_st, B_st, transB, f8="f8"):
     C = r["C"].astype(np.float64)                       # FP16 product
-    absprod = np.abs(orc.decode(A_st, "f8")) @ np.abs(orc.logical_B(B_st, "f8", transB))
-    bound = U_OUT["f16"] * np.abs(o["C"]) + _tol("f8") * absprod + OUT_TINY["f16"]
+    absprod = np.abs(orc.decode(A_st, f8)) @ np.abs(orc.logical_B(B_st, f8, transB))
+    bound = U_OUT["f16"] * np.abs(o["C"]) + _tol(f8) * absprod + OUT_TINY["f16"]
     assert np.all(np.abs(C - o["C"]) <= bound), "C"
 
 
+@pytest.mark.parametrize("f8", FORMATS)
 @pytest.mark.parametrize("M,N,K", [(256, 256, 256), (512, 768, 512), (256, 512, 1024)])
-def test_fp8_fault_free_parity(M, N, K):
+def test_fp8_fault_free_parity(M, N, K, f8):
     for seed, dist in ((1, "n_1e-6_1"), (2, "n_1_1"), (3, "u_-1_1")):
-        A, B = _gen8(M, N, K, 1, seed, dist)
-        print(f"fp8 {M}x{N}x{K} {dist}", flush=True)
-        vg = _session(M, N, K, "f8", 1)
-        dA, dB = _dev(A, "f8"), _dev(B, "f8")
-        o = orc.verify(A, B, "f8", 1, e_max=_emax("f8", K, N))
+        A, B = _gen8(M, N, K, 1, seed, dist, f8)
+        print(f"{f8} {M}x{N}x{K} {dist}", flush=True)
+        vg = _session(M, N, K, f8, 1)
+        dA, dB = _dev(A, f8), _dev(B, f8)
+        o = orc.verify(A, B, f8, 1, e_max=_emax(f8, K, N))
         for route in ("run", "run_fused", "run_weighted", "run_rc"):
             getattr(vg, route)(dA, dB)
             r = vg.results()
-            check_light(r, o, "f8", M, N, K)
-            check_rows(r, o, "f8")
-            check_C8(r, o, A, B, 1)
+            check_light(r, o, f8, M, N, K)
+            check_rows(r, o, f8)
+            check_C8(r, o, A, B, 1, f8)
             assert r["nflag"] == 0 and not r["flags"].any() and not o["flags"].any()
             if route == "run_weighted":
-                check_weighted(r, o, "f8")
+                check_weighted(r, o, f8)
             if route == "run_rc":
-                oc = orc.verify_columns(A, B, "f8", 1, e_max=_emax("f8", K, max(N, M)))
-                check_columns(r, oc, "f8", M, N, K)
+                oc = orc.verify_columns(A, B, f8, 1, e_max=_emax(f8, K, max(N, M)))
+                check_columns(r, oc, f8, M, N, K)
                 assert r["ncolflag"] == 0
         # plain GEMM gives the same C
         C1 = vg.results()["C"].copy()
@@ -57,16 +61,17 @@ def test_fp8_fault_free_parity(M, N, K):
         assert np.array_equal(vg.results()["C"], C1)
 
 
-def test_fp8_exact_arithmetic_flips_and_localisation():
+@pytest.mark.parametrize("f8", FORMATS)
+def test_fp8_exact_arithmetic_flips_and_localisation(f8):
     M, N, K = 512, 512, 256
     g = wl.rng(5, 5)
-    A = wl.to_storage(g.integers(-2, 3, size=(M, K)).astype(np.float64), "f8")
-    B = wl.to_storage(g.integers(-2, 3, size=(N, K)).astype(np.float64), "f8")
-    dA, dB = _dev(A, "f8"), _dev(B, "f8")
-    vg = _session(M, N, K, "f8", 1)
+    A = wl.to_storage(g.integers(-2, 3, size=(M, K)).astype(np.float64), f8)
+    B = wl.to_storage(g.integers(-2, 3, size=(N, K)).astype(np.float64), f8)
+    dA, dB = _dev(A, f8), _dev(B, f8)
+    vg = _session(M, N, K, f8, 1)
     vg.run_weighted(dA, dB)
     r = vg.results()
-    o = orc.verify(A, B, "f8", 1, e_max=_emax("f8", K, N))
+    o = orc.verify(A, B, f8, 1, e_max=_emax(f8, K, N))
     assert np.array_equal(r["Be"].astype(np.float64), o["Be"])
     assert np.array_equal(r["expected"].astype(np.float64), o["expected"])
     assert np.array_equal(r["rowsum"].astype(np.float64), o["rowsum"])
@@ -88,36 +93,38 @@ def test_fp8_exact_arithmetic_flips_and_localisation():
     assert np.array_equal(r["C"].astype(np.float64), o["C"])
 
 
+@pytest.mark.parametrize("f8", FORMATS)
 @pytest.mark.parametrize("M,N,K,transB", [(300, 200, 77, 1), (100, 130, 50, 0), (64, 48, 16, 1)])
-def test_fp8_streaming_passes_take_any_shape(M, N, K, transB):
+def test_fp8_streaming_passes_take_any_shape(M, N, K, transB, f8):
     """encode / threshold / offline check on ragged FP8 problems; the GEMM itself reports 'unsupported'."""
     from paper_2602_08043_amd import binding as vb
-    A, B = _gen8(M, N, K, transB, 7)
-    vg = _session(M, N, K, "f8", transB)
-    dA, dB = _dev(A, "f8"), _dev(B, "f8")
+    A, B = _gen8(M, N, K, transB, 7, f8=f8)
+    vg = _session(M, N, K, f8, transB)
+    dA, dB = _dev(A, f8), _dev(B, f8)
     vg.encode(dB)
     vg.threshold(dA)
     r = vg.results()
-    o = orc.verify(A, B, "f8", transB, e_max=_emax("f8", K, N))
-    check_light(r, o, "f8", M, N, K)
+    o = orc.verify(A, B, f8, transB, e_max=_emax(f8, K, N))
+    check_light(r, o, f8, M, N, K)
     with pytest.raises(vb.VabftError) as ei:
         vg.gemm(dA, dB, 1)
     assert ei.value.status == vb.VABFT_EUNSUPPORTED
     # offline check of an FP16 product computed elsewhere, with e_max = 2 u_FP16
-    e_off = vb.vabft_default_emax_offline("f8", K, N)
+    e_off = vb.vabft_default_emax_offline(f8, K, N)
     assert e_off == 2.0 ** -10
     vg.threshold(dA, e_off)
-    Bl = orc.logical_B(B, "f8", transB)
-    C16 = torch.from_numpy((orc.decode(A, "f8") @ Bl).astype(np.float16)).cuda()
+    Bl = orc.logical_B(B, f8, transB)
+    C16 = torch.from_numpy((orc.decode(A, f8) @ Bl).astype(np.float16)).cuda()
     vg.check_offline(C16)
     r = vg.results()
     assert r["nflag"] == 0
-    rs_off = orc.row_sums_offline(orc.decode(A, "f8") @ Bl, "f16")
+    rs_off = orc.row_sums_offline(orc.decode(A, f8) @ Bl, "f16")
     assert np.all(np.abs(r["rowsum"] - rs_off) <= 4 * U_OUT["f32"] * np.abs(C16.float().cpu().numpy()).sum(axis=1) + 1e-30)
 
 
-def test_fp8_full_size_sampled():
-    cfg = wl.make_config("c6_f8_4096", seed=0)
+@pytest.mark.parametrize("name", ["c6_f8_4096", "c8_f8e5m2_4096"])
+def test_fp8_full_size_sampled(name):
+    cfg = wl.make_config(name, seed=0)
     dt, M, N, K, tb = cfg["dtype"], cfg["M"], cfg["N"], cfg["K"], cfg["transB"]
     dA, dB = _dev(cfg["A"], dt), _dev(cfg["B"], dt)
     vg = _session(M, N, K, dt, tb)
@@ -139,17 +146,18 @@ def test_fp8_full_size_sampled():
 
 @pytest.mark.parametrize("M,N,K", [(256, 512, 256), (512, 1024, 2048), (768, 512, 3072), (256, 512, 3584),
                                    (256, 768, 768)])
-def test_fp8_fused_call_single_launch(M, N, K):
+@pytest.mark.parametrize("f8", FORMATS)
+def test_fp8_fused_call_single_launch(M, N, K, f8):
     """vabft_gemm_verified_fused on FP8 problems the single-launch kernel takes (statistics of A folded from the
     operand fragments: units of 256 k dealt to the tile-columns, up to eight per workgroup) and one it hands to
     the two-pass route (3584 / 256 = 14 units on two tile-columns), with and without the deferred fold of S1..S3,
     against the oracle and against the three-call route."""
     for seed, dist in ((41, "n_1e-6_1"), (42, "u_-1_1")):
-        A, B = _gen8(M, N, K, 1, seed, dist)
-        print(f"fp8 fused {M}x{N}x{K} {dist}", flush=True)
-        vg = _session(M, N, K, "f8", 1)
-        dA, dB = _dev(A, "f8"), _dev(B, "f8")
-        o = orc.verify(A, B, "f8", 1, e_max=_emax("f8", K, N))
+        A, B = _gen8(M, N, K, 1, seed, dist, f8)
+        print(f"{f8} fused {M}x{N}x{K} {dist}", flush=True)
+        vg = _session(M, N, K, f8, 1)
+        dA, dB = _dev(A, f8), _dev(B, f8)
+        o = orc.verify(A, B, f8, 1, e_max=_emax(f8, K, N))
         vg.run(dA, dB)
         r3 = {k: np.copy(v) for k, v in vg.results().items()}
         for defer in (False, True, False):
@@ -159,9 +167,9 @@ def test_fp8_fused_call_single_launch(M, N, K):
             vg.run_fused(dA, dB, defer_S=defer)
             r = vg.results()
             if not defer:
-                check_light(r, o, "f8", M, N, K)
-            check_rows(r, o, "f8")
-            check_C8(r, o, A, B, 1)
+                check_light(r, o, f8, M, N, K)
+            check_rows(r, o, f8)
+            check_C8(r, o, A, B, 1, f8)
             assert np.array_equal(r["astat"][:, 0].astype(np.float64), o["astat"][:, 0])
             assert np.array_equal(r["astat"][:, 1].astype(np.float64), o["astat"][:, 1])
             assert np.allclose(r["T"], r3["T"], rtol=2e-6, atol=0)

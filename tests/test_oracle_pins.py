@@ -587,6 +587,38 @@ def test_e4m3_rounding_of_the_generators():
     assert orc.acc_dtype("f8") == np.float32
 
 
+def test_e5m2_decode_is_the_top_byte_of_binary16():
+    # OCP E5M2 has binary16's sign / exponent layout with the mantissa cut to two bits: code c is the
+    # half-precision number with bit pattern c << 8 (numpy's float16 decodes that independently)
+    codes = np.arange(256, dtype=np.uint8)
+    half = (codes.astype(np.uint16) << np.uint16(8)).view(np.float16).astype(np.float64)
+    got = orc.decode(codes, "f8e5m2")
+    assert np.array_equal(got, half, equal_nan=True)
+    assert np.array_equal(np.signbit(got), np.signbit(half))
+    assert got[0x3C] == 1.0 and got[0x7B] == 57344.0 and got[0x01] == 2.0 ** -16 and np.isinf(got[0x7C])
+    assert np.isnan(got[[0x7D, 0x7E, 0x7F, 0xFD]]).all()
+
+
+def test_e5m2_rounding_of_the_generators():
+    codes = np.arange(0x7C, dtype=np.uint8)          # finite non-negative values
+    vals = orc.decode(codes, "f8e5m2")
+    assert np.all(np.diff(vals) > 0)
+    assert np.array_equal(wl.to_storage(vals, "f8e5m2"), codes)
+    assert np.array_equal(wl.to_storage(-vals[1:], "f8e5m2"), codes[1:] | 0x80)
+    mid = (vals[:-1] + vals[1:]) / 2
+    got = wl.to_storage(mid, "f8e5m2")
+    assert np.all(got % 2 == 0) and np.all((got == codes[:-1]) | (got == codes[1:]))
+    assert wl.to_storage(np.array([1e9, -1e9, 60000.0]), "f8e5m2").tolist() == [0x7B, 0xFB, 0x7B]
+    # values of binary16 that need no more than two mantissa bits survive a trip through numpy's float16
+    x = np.array([0.75, -1.25, 3.5, 1.0e-3, 448.0, -6.1e-5])
+    h = x.astype(np.float16)
+    st = wl.to_storage(h.astype(np.float64), "f8e5m2")
+    back = orc.decode(st, "f8e5m2")
+    assert np.all(np.abs(back - h.astype(np.float64)) <= 0.125 * np.abs(h.astype(np.float64)))
+    assert orc.output_dtype("f8e5m2") == "f16" and orc.acc_dtype("f8e5m2") == np.float32
+    assert orc.default_emax_offline("f8e5m2", 64, 64) == 2.0 ** -10
+
+
 # --------------------------------------------------------------------------
 # block-wise verification (section 5.2)
 # --------------------------------------------------------------------------

@@ -54,6 +54,8 @@ def to_storage(x: np.ndarray, dtype: str) -> np.ndarray:
         return f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
     if dtype == "f8":
         return f64_to_e4m3_bits(np.asarray(x, dtype=np.float64))
+    if dtype == "f8e5m2":
+        return f64_to_e5m2_bits(np.asarray(x, dtype=np.float64))
     raise ValueError(f"unknown dtype {dtype!r}")
 
 
@@ -68,6 +70,23 @@ def _e4m3_positive_values() -> np.ndarray:
 def f64_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
     """Nearest E4M3 code, ties to the even code, magnitudes beyond 448 saturate to +-448 (uint8)."""
     vals = _e4m3_positive_values()
+    a = np.minimum(np.abs(x), vals[-1])
+    hi = np.clip(np.searchsorted(vals, a, side="left"), 1, len(vals) - 1)
+    lo = hi - 1
+    dlo, dhi = a - vals[lo], vals[hi] - a
+    pick_hi = (dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0))
+    code = np.where(pick_hi, hi, lo).astype(np.uint8)
+    code = np.where(a == 0, 0, code).astype(np.uint8)
+    return (code | np.where(np.signbit(x), 0x80, 0).astype(np.uint8)).astype(np.uint8)
+
+
+def f64_to_e5m2_bits(x: np.ndarray) -> np.ndarray:
+    """Nearest OCP FP8 E5M2 code (1 sign, 5 exponent bits with bias 15, 2 mantissa bits; codes 0x00 .. 0x7B are the
+    finite non-negative values in increasing order), ties to the even code, magnitudes beyond 57344 saturate to
+    +-57344 (uint8)."""
+    codes = np.arange(0x7C)
+    e, m = codes >> 2, codes & 3
+    vals = np.where(e == 0, m * 2.0 ** -16, (1.0 + m / 4.0) * 2.0 ** (e.astype(np.float64) - 15))
     a = np.minimum(np.abs(x), vals[-1])
     hi = np.clip(np.searchsorted(vals, a, side="left"), 1, len(vals) - 1)
     lo = hi - 1
@@ -132,6 +151,7 @@ CONFIGS = {
     "c5_f64_2048": dict(dtype="f64", M=2048, N=2048, K=2048, transB=0),
     # beyond the five benchmark configurations: FP8 E4M3 inputs, FP32 accumulation, FP16 output
     "c6_f8_4096": dict(dtype="f8", M=4096, N=4096, K=4096, transB=1),
+    "c8_f8e5m2_4096": dict(dtype="f8e5m2", M=4096, N=4096, K=4096, transB=1),
     # ... and an FP32 problem large enough to be bound by the FP32 matrix instruction rather than by latency
     "c7_f32_4096": dict(dtype="f32", M=4096, N=4096, K=4096, transB=0),
 }
@@ -159,7 +179,7 @@ def make_config(name: str, seed: int = 0, variant: int = 0, shape=None):
         cfg["outlier_cols"] = cols
         # weights drawn directly in the (N, K) layout a linear layer stores
         B = truncated_normal(gb, (N, K), 0.0, 0.02, 2.0)
-    elif name == "c6_f8_4096":
+    elif name in ("c6_f8_4096", "c8_f8e5m2_4096"):
         A = normal(ga, (M, K))
         B = normal(gb, (N, K))  # weight layout
     elif name == "c4_f16_8192":
@@ -225,10 +245,10 @@ def device_trial(name: str, g, variant: int = 0, shape=None):
         cfg["M"], cfg["N"], cfg["K"] = (int(v) for v in shape)
     M, N, K, dt, tb = cfg["M"], cfg["N"], cfg["K"], cfg["dtype"], cfg["transB"]
     tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32, "f64": torch.float64,
-           "f8": torch.float8_e4m3fn}[dt]
+           "f8": torch.float8_e4m3fn, "f8e5m2": torch.float8_e5m2}[dt]
     gen = torch.float64 if dt == "f64" else torch.float32
     bshape = (N, K) if tb else (K, N)
-    if name in ("c1_f32_256", "c2_bf16_4096", "c6_f8_4096", "c7_f32_4096"):
+    if name in ("c1_f32_256", "c2_bf16_4096", "c6_f8_4096", "c7_f32_4096", "c8_f8e5m2_4096"):
         A = torch.randn((M, K), generator=g, device="cuda", dtype=gen)
         B = torch.randn(bshape, generator=g, device="cuda", dtype=gen)
     elif name == "c3_bf16_ffn":
