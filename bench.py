@@ -45,15 +45,17 @@ WORKLOAD_TEXT = {
     "c5_f64_2048": "FP64 GEMM M=N=K=2048, A ~ N(0,1), B ~ N(0,1) truncated 3 sigma (variant 0) or U(0,1) (variant 1)",
     "c6_f8_4096": "FP8 E4M3 GEMM M=N=K=4096, FP32 accumulation, FP16 output, A,B ~ N(0,1), B stored N x K "
                   "(not one of the five benchmark configurations)",
+    "c8_f8e5m2_4096": "FP8 E5M2 GEMM M=N=K=4096, FP32 accumulation, FP16 output, A,B ~ N(0,1), B stored N x K "
+                      "(not one of the five benchmark configurations)",
     "c7_f32_4096": "FP32 GEMM M=N=K=4096, A,B ~ N(0,1) (not one of the five benchmark configurations: the FP32 kernel "
                    "at a size bound by the matrix instruction)",
 }
 # trials of the quality statistics (the benchmark configurations' own counts; configuration 1 names one fault-free
 # run and 8 flips, more are run because they are free at that size)
 FAULT_FREE_TRIALS = {"c1_f32_256": 200, "c2_bf16_4096": 1000, "c3_bf16_ffn": 100, "c4_f16_8192": 20,
-                     "c5_f64_2048": 500, "c6_f8_4096": 40, "c7_f32_4096": 40}
+                     "c5_f64_2048": 500, "c6_f8_4096": 40, "c7_f32_4096": 40, "c8_f8e5m2_4096": 40}
 FLIP_TRIALS = {"c1_f32_256": 176, "c2_bf16_4096": 1008, "c3_bf16_ffn": 112, "c4_f16_8192": 32,
-               "c5_f64_2048": 132, "c6_f8_4096": 64, "c7_f32_4096": 64}
+               "c5_f64_2048": 132, "c6_f8_4096": 64, "c7_f32_4096": 64, "c8_f8e5m2_4096": 64}
 
 
 def timed(torch, fn, steps, warmup):
@@ -330,6 +332,16 @@ def bench_config(mods, name, variant, steps, warmup, args, headline):
         ms_enc_def = timed(torch, enc_def_rot, hs, nrot)
         ms_enc = timed(torch, enc_rot, hs, nrot)
         ms_thr = timed(torch, thr_rot, max(steps // 2, 3 * nrotA), nrotA)
+        # what a kernel that only reads B reaches on this chip, and what an empty launch costs, in the same loop
+        probe_out = torch.zeros(4, dtype=torch.float32, device="cuda")
+
+        def read_rot():
+            t = Bs[ctr[0] % nrot]
+            vb.vabft_probe_read(t.data_ptr(), t.numel() * t.element_size(), probe_out.data_ptr())
+            ctr[0] += 1
+
+        ms_read = timed(torch, read_rot, hs, nrot)
+        ms_empty = timed(torch, lambda: vb.vabft_probe_read(None, 0, probe_out.data_ptr()), 200, 20)
         del Bs, As
         vg.encode(B)
         vg.threshold(A, e_max)
@@ -340,6 +352,9 @@ def bench_config(mods, name, variant, steps, warmup, args, headline):
             "encode_fold_deferred": {"GBps": bB / (ms_enc_def * 1e-3) / 1e9,
                                      "frac": bB / (ms_enc_def * 1e-3) / 1e9 / HBM_PEAK_GBPS},
             "threshold": {"GBps": bA / (ms_thr * 1e-3) / 1e9, "frac": bA / (ms_thr * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+            "read_only_kernel_over_B": {"GBps": bB / (ms_read * 1e-3) / 1e9,
+                                        "frac": bB / (ms_read * 1e-3) / 1e9 / HBM_PEAK_GBPS, "ms": ms_read},
+            "empty_kernel_launch_ms": ms_empty,
         }
 
     if headline:

@@ -53,10 +53,10 @@ typedef enum {
 
 /* VABFT_F8E4M3, VABFT_F8E5M2: A and B are OCP FP8 (one byte per element, both in the same encoding), the
  * accumulator is FP32 and C is FP16 ("FP8 inputs -> FP32 accumulation -> FP16 output", section 3.6, which names
- * both encodings).  The GEMM entry points take
- * these types only for B stored N x K (transB = 1) and problems made of whole 256 x 256 x 256 tiles with
- * 16-byte aligned rows (VABFT_EUNSUPPORTED otherwise); encode, threshold and the offline check take any
- * shape. */
+ * both encodings).  Every entry point takes these types for any shape and either layout of B.  Problems made of
+ * whole 256 x 256 x 256 tiles with 16-byte aligned rows and B stored N x K (transB = 1) run on the FP8 matrix
+ * instruction; all others run on the guarded kernel, which widens the operands to FP16 on load (exact) and
+ * multiplies them with the FP16 matrix instruction: the same products, the same FP32 accumulation. */
 typedef enum { VABFT_F64 = 0, VABFT_F32 = 1, VABFT_F16 = 2, VABFT_BF16 = 3, VABFT_F8E4M3 = 4, VABFT_F8E5M2 = 5 } vabft_dtype;
 
 typedef struct {
@@ -108,7 +108,8 @@ int vabft_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream
  * the larger of the paper's GPU law (table "Recommended e_max across platforms":
  * 5.0e-9*sqrt(n)+1.2e-7 for a float accumulator, 1.0e-17*sqrt(n)+2.5e-16 for double) and the
  * law measured on MI355X with this library's kernels by the paper's calibration protocol
- * (3.0e-9*sqrt(n)+3.9e-7, resp. 8.0e-18*sqrt(n)+5.2e-16).  VABFT_F8E4M3: the constant 5.5e-6 measured
+ * (3.0e-9*sqrt(n)+4.2e-7, resp. 8.0e-18*sqrt(n)+6.6e-16: at least 25 % above every value that
+ * protocol produced, its own 20 % margin included).  FP8 inputs: the constant 5.5e-6 measured
  * the same way (the FP8 matrix instruction accumulates its 64-term dot products with less than FP32
  * precision). */
 double vabft_default_emax(int32_t dtype, int32_t K, int32_t N);
@@ -124,7 +125,9 @@ double vabft_default_emax(int32_t dtype, int32_t K, int32_t N);
  * the call needs the workspace (vabft_workspace_bytes, zero-filled once) for either layout of B.
  * d_S may be NULL: then the fold is deferred -- S1..S3 stay as the per-workgroup partials in the
  * workspace, where they remain valid until the next encode call (vabft_encode, vabft_encode_weighted,
- * vabft_encode_a) on that workspace, for GEMMs with any number of rows M, and
+ * vabft_encode_a) on that workspace, for GEMMs with any number of rows M (the workspace sized for the
+ * largest of them; every region of the workspace that outlives a call sits at a place that depends on the
+ * shape of B only, for up to a million rows), and
  * vabft_gemm_verified_fused called with d_S = NULL folds them itself (same order, same bits).
  * This takes the arrival-counter round trips out of the encode's tail. */
 int vabft_encode(const vabft_problem* p, const void* dB, void* d_Be, void* d_bstat, double* d_S,
@@ -211,6 +214,13 @@ int vabft_gemm_verified_fused_static(const vabft_problem* p, const void* dA, con
  *   d_out [65536] float (device): a value per thread, so that the loop is not removed
  *   flops (host): floating-point operations of the launch */
 int vabft_probe_mfma(int32_t dtype, int32_t iters, void* d_out, double* flops, void* stream);
+
+/* Measurement aid: one launch of a kernel that only reads `bytes` bytes at d_buf (device, 16-byte aligned;
+ * 8192 workgroups of 256 threads, grid-stride 16-byte loads, four in flight per lane) -- what a streaming pass
+ * can reach on the chip, to set beside the encode / threshold passes and the 8 TB/s figure.  bytes < 16: an
+ * empty kernel (one wavefront that does nothing), whose back-to-back launch time is the floor of any pass.
+ *   d_out [16 bytes] (device): never written for ordinary data; keeps the loads alive */
+int vabft_probe_read(const void* d_buf, size_t bytes, void* d_out, void* stream);
 
 /* ---- Position-weighted checksum, localisation and correction (section 2.2: r2 = [1..N]^T,
  * C^{r2} = A (B r2), C^{r2'} = C r2, "Error localization and correction") -------------------

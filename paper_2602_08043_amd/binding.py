@@ -24,7 +24,7 @@ EXPORTS = ("vabft_status_string", "vabft_workspace_bytes", "vabft_workspace_init
            "vabft_locate_correct", "vabft_default_emax_offline", "vabft_check_offline",
            "vabft_encode_a", "vabft_threshold_cols", "vabft_gemm_verified_rc",
            "vabft_block_width", "vabft_encode_blocks", "vabft_threshold_blocks", "vabft_gemm_verified_blocks",
-           "vabft_static_scratch_bytes", "vabft_gemm_verified_fused_static", "vabft_probe_mfma")
+           "vabft_static_scratch_bytes", "vabft_gemm_verified_fused_static", "vabft_probe_mfma", "vabft_probe_read")
 
 
 class Problem(Structure):
@@ -86,6 +86,8 @@ def load(path: str | None = None):
                                               c_double, c_double, c_void_p, c_void_p, c_void_p, POINTER(Inject),
                                               c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                               c_size_t, c_void_p]
+    lib.vabft_probe_read.restype = ctypes.c_int
+    lib.vabft_probe_read.argtypes = [c_void_p, c_size_t, c_void_p, c_void_p]
     lib.vabft_probe_mfma.restype = ctypes.c_int
     lib.vabft_probe_mfma.argtypes = [c_int32, c_int32, c_void_p, POINTER(c_double), c_void_p]
     lib.vabft_static_scratch_bytes.restype = c_size_t
@@ -205,6 +207,11 @@ def vabft_probe_mfma(dtype: str, iters: int, d_out, stream=None) -> float:
     rc = load().vabft_probe_mfma(DTYPE_CODE[dtype], int(iters), d_out, byref(flops), stream)
     _check(rc, "vabft_probe_mfma", True)
     return float(flops.value)
+
+
+def vabft_probe_read(d_buf, nbytes: int, d_out, stream=None) -> None:
+    """One launch of the read-only kernel over nbytes at d_buf (nbytes < 16: an empty kernel)."""
+    _check(load().vabft_probe_read(d_buf, int(nbytes), d_out, stream), "vabft_probe_read", True)
 
 
 def vabft_static_scratch_bytes() -> int:

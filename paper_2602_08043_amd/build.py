@@ -13,7 +13,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libvabft.so")
 
 SOURCES = ["gemm16_bf16_nn.hip", "gemm16_bf16_nt.hip", "gemm16_f16_nn.hip", "gemm16_f16_nt.hip", "gemm8_f8_nt.hip",
-           "gemm8_bf8_nt.hip", "api.hip",
+           "gemm8_bf8_nt.hip", "gemm16_f8_edge.hip", "api.hip",
            "encode.hip", "blocks.hip", "gemm_f32.hip", "gemm_f64.hip", "probe.hip"]
 
 FLAGS = [

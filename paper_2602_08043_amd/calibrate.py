@@ -104,6 +104,12 @@ def merge(paths):
                 a["flagged"] += r["flagged_rows_at_default"]
                 a["over_T"] = max(a["over_T"], r["max_E_over_T_at_default"])
                 a["default"] = r["default_e_max"]
+    try:  # the default as the library computes it now (runs made before a change of the law recorded the old one)
+        from . import binding as vb
+        vb.load()
+        current_default = vb.vabft_default_emax
+    except (ImportError, OSError):
+        current_default = None
     order = {"bf16": 0, "f16": 1, "f32": 2, "f64": 3, "f8": 4, "f8e5m2": 5}
     print("| dtype | B stored | n | trials | max rel. difference | in units of u | +20 % | paper law | library default "
           "| default / (+20 %) | flagged rows | max abs(E)/T during the run |")
@@ -112,6 +118,8 @@ def merge(paths):
         a = acc[(dt, tb, n)]
         u = _U.get(dt, 2.0 ** -24)
         m20 = 1.2 * a["max_rel_E"]
+        if current_default is not None:
+            a["default"] = current_default(dt, n, n)
         print(f"| {dt} | {'N x K' if tb else 'K x N'} | {n} | {a['trials']} | {a['max_rel_E']:.3e} | "
               f"{a['max_rel_E'] / u:.2f} | {m20:.3e} | {paper_law(dt, n):.3e} | {a['default']:.3e} | "
               f"{a['default'] / m20:.3f} | {a['flagged']} | {a['over_T']:.2f} |")

@@ -199,8 +199,8 @@ static void tile_shape(const vabft_problem* p, bool blockwise, int* bm, int* bn)
 // with any number of rows): three doubles at +0 (the fold of the partials, when a kernel of its own has to
 // make it), the encode's arrival counter at +32, the per-workgroup partials of S1..S3 of the last encode at
 // +64, rounded up to 256 B.
-// Tickets: tiles_m int32 arrival counters + one 64-bit counter, rounded to 256 B.  They must be zero between
-// launches: the kernels leave them zero, vabft_workspace_init zeroes them the first time.
+// Tickets: tiles_m int32 arrival counters + one 64-bit counter, in a region of fixed size (TICKETS_REGION).  They
+// must be zero between launches: the kernels leave them zero, vabft_workspace_init zeroes them the first time.
 // The scratch area holds, for the GEMM, in units of tiles_n * M accumulator words: 16-bit
 // types rowpart [0,1), apart [1,5), rowpart2 [5,6); wide types (two row-sum partials per
 // tile-column) rowpart [0,2), rowpart2 [2,4), apart [4,8); then the column-sum partials.  The
@@ -210,12 +210,23 @@ static size_t s_area_bytes(const vabft_problem* p) {
     return round_up(64 + (size_t)s_partial_count(p) * 3 * sizeof(double), 256);
 }
 static size_t tickets_offset(const vabft_problem* p) { return s_area_bytes(p); }
-// everything in front of the scratch area
-static size_t tickets_bytes(const vabft_problem* p) {
+// bytes of arrival counters a problem uses: tiles_m int32 + the 64-bit done counter, rounded to 256 B
+static size_t tickets_used_bytes(const vabft_problem* p) {
     int bm, bn;
     tile_shape(p, false, &bm, &bn);  // the smaller tile of the two routes: the larger count
     const size_t tiles_m = ((size_t)p->M + bm - 1) / bm;
-    return tickets_offset(p) + round_up((tiles_m + 4) * sizeof(int32_t), 256);
+    return round_up((tiles_m + 4) * sizeof(int32_t), 256);
+}
+// The counters' region has a fixed size (64 KiB: 16 380 tile-rows, a million rows of the smallest tile), so the
+// scratch area behind it starts at a place that depends on B's shape only.  Otherwise a call that shares the
+// workspace with a problem of more rows (an encode of B made through a problem with few rows, say) would put its
+// transient partials where the larger problem keeps counters that must stay zero.  Problems with more tile-rows
+// than that get a larger region; they only share a workspace with problems of the same M.
+constexpr size_t TICKETS_REGION = 64u << 10;
+// everything in front of the scratch area
+static size_t tickets_bytes(const vabft_problem* p) {
+    const size_t used = tickets_used_bytes(p);
+    return tickets_offset(p) + (used > TICKETS_REGION ? used : TICKETS_REGION);
 }
 static double* s_folded(const vabft_problem*, void* ws) { return reinterpret_cast<double*>(ws); }
 static double* s_partials(const vabft_problem*, void* ws) {
@@ -333,8 +344,9 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     const int bk = is_fp8(p->dtype) ? 256 : (is16 ? 64 : 16);
     // (the whole-tile 16-bit kernels address a tile's rows with 32-bit byte offsets from a per-wavefront base)
     const bool wide_rows = is16 && (p->lda > (1 << 24) || p->ldb > (1 << 24));
-    const bool edge =
-        (p->M % bm) || (p->N % bn) || (p->K % bk) || !a.a_vec_ok || !a.b_vec_ok || !a.c_vec_ok || wide_rows;
+    // (the whole-tile FP8 kernel exists for B stored N x K only; a K x N B takes the guarded kernel)
+    const bool edge = (p->M % bm) || (p->N % bn) || (p->K % bk) || !a.a_vec_ok || !a.b_vec_ok || !a.c_vec_ok ||
+                      wide_rows || (is_fp8(p->dtype) && !p->transB);
     // whole-tile kernels do the compare-and-flag step (and, if asked, the A-side pass) in-kernel
     const bool in_kernel_finalize = !edge;
     if (fused) {
@@ -376,8 +388,10 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     switch (p->dtype) {
         case VABFT_F8E4M3:
         case VABFT_F8E5M2:
-            if (edge || !p->transB) return VABFT_EUNSUPPORTED;
-            rc = p->dtype == VABFT_F8E4M3 ? gemm8_launch_f8_nt(a, mode, st) : gemm8_launch_bf8_nt(a, mode, st);
+            if (edge)
+                rc = gemm16_launch_f8_edge(a, mode, p->dtype == VABFT_F8E5M2, p->transB, st);
+            else
+                rc = p->dtype == VABFT_F8E4M3 ? gemm8_launch_f8_nt(a, mode, st) : gemm8_launch_bf8_nt(a, mode, st);
             break;
         case VABFT_BF16:
             rc = p->transB ? gemm16_launch_bf16_nt(a, mode, edge, st) : gemm16_launch_bf16_nn(a, mode, edge, st);
@@ -481,10 +495,12 @@ int vabft_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream
 
 double vabft_default_emax(int32_t dtype, int32_t K, int32_t N) {
     // The larger of (a) the paper's recommended GPU law (table "Recommended e_max across
-    // platforms", H100 rows) and (b) the law measured on MI355X with these kernels by the paper's
-    // calibration protocol (|N(1,1)| matrices, max |E| / |checksum| over trials, +20 %): the
-    // relative difference of these kernels is 3.6 - 9 u over n = 128 .. 8192 (about 100 000 trials per
-    // size), nearly flat in n, which is above (a) at small n.  (b) is the envelope of the +20 % values.
+    // platforms", H100 rows) and (b) a law measured on MI355X with these kernels by the paper's
+    // calibration protocol (|N(1,1)| matrices, max |E| / |checksum| over trials, +20 %).  Measured over
+    // n = 128 .. 8192, both layouts of B, 100 000 trials per size: the relative difference is 3.1 - 6.0 u for
+    // BF16 / FP16 / FP32 and 4.4 - 4.5 u for FP64, flat in n (every sum is a tree), which is above (a) at
+    // small n.  (b) lies at least 25 % above every +20 % value of that table, i.e. at least 50 % above every
+    // observed maximum; tests/test_library_cpu.py holds it to that against the committed table.
     const double n = (double)(K > N ? K : N);
     double paper, measured;
     // FP8: the 32x32x64 matrix instruction does not carry full FP32 precision through its 64-term dot
@@ -493,10 +509,10 @@ double vabft_default_emax(int32_t dtype, int32_t K, int32_t N) {
     if (is_fp8(dtype)) return 5.5e-6;
     if (dtype == VABFT_F64) {
         paper = 1.0e-17 * sqrt(n) + 2.5e-16;
-        measured = 8.0e-18 * sqrt(n) + 5.2e-16;
+        measured = 8.0e-18 * sqrt(n) + 6.6e-16;
     } else {
         paper = 5.0e-9 * sqrt(n) + 1.2e-7;
-        measured = 3.0e-9 * sqrt(n) + 3.9e-7;
+        measured = 3.0e-9 * sqrt(n) + 4.2e-7;
     }
     return paper > measured ? paper : measured;
 }
@@ -812,7 +828,7 @@ int vabft_gemm_verified_fused_static(const vabft_problem* p, const void* dA, con
     if (!aligned_to(d_Be, ab) || !aligned_to(d_S, 8) || !aligned_to(d_astat, ab)) return VABFT_EINVAL;
     // every call on this GPU shares the array, which keeps the last call's contents: the arrival counters
     // must start at zero (a fill kernel, not a memset, so that the call can be captured into a graph)
-    const size_t tb = tickets_bytes(p) - tickets_offset(p);
+    const size_t tb = tickets_used_bytes(p);
     fill_zero_kernel<<<1, 256, 0, (hipStream_t)stream>>>(
         reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(ws) + tickets_offset(p)), tb / 4);
     if (hipGetLastError() != hipSuccess) return VABFT_EDEVICE;

@@ -91,18 +91,17 @@ __device__ __forceinline__ void row_terms(acc_t sum, acc_t mx, acc_t mn, int N, 
 }
 
 // ---------------------------------------------------------------------------
-// B stored K x N: 16 wavefronts per block reduce RPB rows k, 16 / RPB wavefronts per row (each a
-// contiguous segment of the row, combined in segment order).  RPB is 16 when that gives enough
-// blocks to fill the chip, else 8, 4, 2 or 1.
+// B stored K x N: WAVES wavefronts per block reduce RPB rows k, WAVES / RPB wavefronts per row (each a
+// contiguous segment of the row, combined in segment order).  RPB is WAVES when that gives enough
+// blocks to fill the chip, else half of it, and so on down to 1.
+// WAVES is 16 when the kernel folds S1..S3 itself (the fold's tail is one atomic per block on one address,
+// about 11 ns each, so fewer and larger blocks are faster: 11.7 against 13.9 us at 4096 x 4096 BF16) and 8 when
+// the fold is deferred (smaller blocks retire and refill sooner: 25.3 against 28.3 us at 8192 x 8192 FP16).
 // ---------------------------------------------------------------------------
-#ifndef VABFT_ENC_ROWS_WAVES
-#define VABFT_ENC_ROWS_WAVES 16
-#endif
-constexpr int ENC_ROWS_WAVES = VABFT_ENC_ROWS_WAVES;
 
 // W: also the position-weighted checksum B*r2, r2 = [1..N] (section 2.2): Be2[k] = sum_n (n+1) B[k,n].
-template <typename T, bool W, int RPB>
-__global__ __launch_bounds__(64 * ENC_ROWS_WAVES) void encode_rows_kernel(const void* __restrict__ B, int K, int N, int64_t ldb,
+template <typename T, bool W, int RPB, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void encode_rows_kernel(const void* __restrict__ B, int K, int N, int64_t ldb,
                                                            typename Elem<T>::acc_t* __restrict__ Be,
                                                            typename Elem<T>::acc_t* __restrict__ Be2,
                                                            typename Elem<T>::acc_t* __restrict__ bstat, int vec_ok,
@@ -110,9 +109,9 @@ __global__ __launch_bounds__(64 * ENC_ROWS_WAVES) void encode_rows_kernel(const 
                                                            int32_t* __restrict__ ticket, double* __restrict__ S) {
     using acc_t = typename Elem<T>::acc_t;
     constexpr int V = Elem<T>::vec;
-    constexpr int WPR = ENC_ROWS_WAVES / RPB;  // wavefronts per row
+    constexpr int WPR = WAVES / RPB;  // wavefronts per row
     __shared__ double terms[RPB][3];
-    __shared__ acc_t seg[ENC_ROWS_WAVES][4];  // (sum, weighted sum, max, min) of each wavefront's segment
+    __shared__ acc_t seg[WAVES][4];  // (sum, weighted sum, max, min) of each wavefront's segment
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int k = blockIdx.x * RPB + wave / WPR, part = wave % WPR;
     acc_t sum = 0, sum2 = 0, mx = -type_max<acc_t>(), mn = type_max<acc_t>();
@@ -230,7 +229,7 @@ __global__ __launch_bounds__(64 * ENC_ROWS_WAVES) void encode_rows_kernel(const 
 // The weight of row n is n + 1 (the vector r2), or wvec[n] when a weight vector is given (then the
 // weighted sum is the dot product of every column with that vector).
 // ---------------------------------------------------------------------------
-template <typename T, bool W>
+template <typename T, bool W, int COLS_NL>
 __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict__ Bt, int K, int N, int64_t ldb,
                                                           int rows_per_block,
                                                           typename Elem<T>::acc_t* __restrict__ part, int vec_ok,
@@ -253,13 +252,14 @@ __global__ __launch_bounds__(256) void encode_cols_kernel(const void* __restrict
     const bool full = vec_ok && (k0 + V <= K);
     if (full) {
         int n = n_begin + wave;
-        for (; n + 12 < n_end; n += 16) {
-            raw16 r[4];
+        // COLS_NL rows in flight per wavefront (a wavefront reads 1 KiB of every fourth row of the slab)
+        for (; n + 4 * (COLS_NL - 1) < n_end; n += 4 * COLS_NL) {
+            raw16 r[COLS_NL];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < COLS_NL; ++u)
                 r[u] = ld16(reinterpret_cast<const char*>(Bt) + ((int64_t)(n + 4 * u) * ldb + k0) * Elem<T>::bytes);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < COLS_NL; ++u) {
                 acc_t v[V];
                 Unpack<T>::run(r[u], v);
                 const acc_t w = !W ? (acc_t)0 : (wvec ? wvec[n + 4 * u] : (acc_t)(n + 4 * u + 1));
@@ -426,11 +426,9 @@ __global__ __launch_bounds__(256) void encode_cols_combine_kernel(const acc_t* _
 // A side: one wavefront per row m: (max, min, mean), dot with Be, threshold
 // ---------------------------------------------------------------------------
 // W: also the expected weighted checksum C^{r2} = A (B r2) (section 2.2).
-#ifndef VABFT_THR_NL
-#define VABFT_THR_NL 4
-#endif
-constexpr int THR_NL = VABFT_THR_NL;
-template <typename T, bool W>
+// THR_NL: 16-byte pieces of the row in flight per lane.  Rows of 1024 pieces or more run 4 (30.0 against 31.8 us
+// at 8192 x 8192 FP16), shorter ones 2 (8.8 against 9.5 us at 4096 x 4096 BF16).
+template <typename T, bool W, int THR_NL>
 __global__ __launch_bounds__(256) void threshold_rows_kernel(const void* __restrict__ A, int M, int K, int N,
                                                              int64_t lda,
                                                              const typename Elem<T>::acc_t* __restrict__ Be,
@@ -583,26 +581,31 @@ __global__ __launch_bounds__(256) void check_offline_kernel(const void* __restri
 // host launchers
 // ---------------------------------------------------------------------------
 
-// Rows per block of the column reduction over a (rows x cols) row-major matrix: 128, or 64 when 128 would give
-// fewer than 512 blocks (the pass is bound by the loads in flight; every halving doubles the slab partials the
-// finishing kernel folds, and below 64 that costs more than it brings)
+// Rows per block of the column reduction over a (rows x cols) row-major matrix: 128 or 64.  Smaller slabs put more
+// loads in flight, and every halving doubles the slab partials the finishing kernel folds.  Measured (two launches,
+// N x K layouts): 8192 x 8192 FP16 42.2 us with 128-row slabs, 33.3 with 64-row slabs and eight rows in flight per
+// wavefront; 4096 x 4096 FP32 23.3 -> 17.2; 11008 x 4096 BF16 (172 slabs of 64 rows) 23.0 -> 28.2, hence the
+// limit on the row count; below 64 rows the fold costs more than the slabs bring.
 static int col_rows_per_block(int dtype, int64_t rows, int64_t cols) {
     const int64_t v = dtype == VABFT_F64 ? 2 : dtype == VABFT_F32 ? 4 : (dtype == VABFT_F8E4M3 || dtype == VABFT_F8E5M2) ? 16 : 8;
     const int64_t xblocks = (cols + 64 * v - 1) / (64 * v);
-    return xblocks * ((rows + 127) / 128) < 512 ? 64 : 128;
+    const int64_t blocks128 = xblocks * ((rows + 127) / 128);
+    return (blocks128 < 512 || (blocks128 < 2048 && rows <= 8192)) ? 64 : 128;
 }
 
 // Rows k per block of the finishing kernel: 16, or fewer (K x N layout) when 16 would leave most of the
 // chip's 256 compute units without a block
-static int encode_rows_per_block(const vabft_problem* p) {
+static int encode_rows_per_block(const vabft_problem* p, int waves) {
     if (p->transB) return 16;
-    int rpb = ENC_ROWS_WAVES;
+    int rpb = waves;
     while (rpb > 1 && (p->K + rpb - 1) / rpb < 256) rpb >>= 1;
     return rpb;
 }
-// per-block partials of (S1, S2, S3): [blocks][3] doubles
+constexpr int ENC_WAVES_OWN_FOLD = 16, ENC_WAVES_DEFERRED = 8;
+// Per-block partials of (S1, S2, S3), [blocks][3] doubles: the number an encode with the fold deferred leaves
+// (what the fused GEMM folds, and what the workspace reserves; an encode that folds them itself leaves no more)
 int s_partial_count(const vabft_problem* p) {
-    const int rpb = encode_rows_per_block(p);
+    const int rpb = encode_rows_per_block(p, ENC_WAVES_DEFERRED);
     return (p->K + rpb - 1) / rpb;
 }
 
@@ -622,19 +625,28 @@ static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, voi
                          double* s_partial, void* ws, int32_t* ticket, hipStream_t st) {
     using acc_t = typename Elem<T>::acc_t;
     const int vec_ok = aligned16(dB) && ((p->ldb * Elem<T>::bytes) % 16 == 0);
-    const int kblocks = s_partial_count(p);
     if (!p->transB) {
-#define VABFT_ENC_ROWS(R)                                                                                       \
-    if constexpr (R <= ENC_ROWS_WAVES)                                                                          \
-        encode_rows_kernel<T, W, R><<<dim3(kblocks), dim3(64 * ENC_ROWS_WAVES), 0, st>>>(                       \
+        const int waves = d_S ? ENC_WAVES_OWN_FOLD : ENC_WAVES_DEFERRED;
+        const int rpb = encode_rows_per_block(p, waves);
+        const int kblocks = (p->K + rpb - 1) / rpb;
+#define VABFT_ENC_ROWS(R, WV)                                                                                    \
+    if constexpr (R <= WV)                                                                                       \
+        encode_rows_kernel<T, W, R, WV><<<dim3(kblocks), dim3(64 * WV), 0, st>>>(                                \
             dB, p->K, p->N, p->ldb, (acc_t*)d_Be, (acc_t*)d_Be2, (acc_t*)d_bstat, vec_ok, s_partial, ticket, d_S)
-        switch (encode_rows_per_block(p)) {
-            case 16: VABFT_ENC_ROWS(16); break;
-            case 8: VABFT_ENC_ROWS(8); break;
-            case 4: VABFT_ENC_ROWS(4); break;
-            case 2: VABFT_ENC_ROWS(2); break;
-            default: VABFT_ENC_ROWS(1); break;
+#define VABFT_ENC_ROWS_SWITCH(WV)                 \
+    switch (rpb) {                                \
+        case 16: VABFT_ENC_ROWS(16, WV); break;   \
+        case 8: VABFT_ENC_ROWS(8, WV); break;     \
+        case 4: VABFT_ENC_ROWS(4, WV); break;     \
+        case 2: VABFT_ENC_ROWS(2, WV); break;     \
+        default: VABFT_ENC_ROWS(1, WV); break;    \
+    }
+        if (d_S) {
+            VABFT_ENC_ROWS_SWITCH(ENC_WAVES_OWN_FOLD)
+        } else {
+            VABFT_ENC_ROWS_SWITCH(ENC_WAVES_DEFERRED)
         }
+#undef VABFT_ENC_ROWS_SWITCH
 #undef VABFT_ENC_ROWS
     } else {
         constexpr int V = Elem<T>::vec;
@@ -642,7 +654,11 @@ static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, voi
         const int nsplit = (p->N + rpb - 1) / rpb;
         acc_t* part = reinterpret_cast<acc_t*>(ws);
         dim3 grid((p->K + 64 * V - 1) / (64 * V), nsplit);
-        encode_cols_kernel<T, W><<<grid, dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, rpb, part, vec_ok, nullptr);
+        if (rpb == 64)
+            encode_cols_kernel<T, W, 8><<<grid, dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, rpb, part, vec_ok, nullptr);
+        else
+            encode_cols_kernel<T, W, 4><<<grid, dim3(256), 0, st>>>(dB, p->K, p->N, p->ldb, rpb, part, vec_ok, nullptr);
+        const int kblocks = s_partial_count(p);
         encode_cols_combine_kernel<acc_t, W><<<dim3(kblocks), dim3(256), 0, st>>>(
             part, nsplit, p->K, p->N, (acc_t*)d_Be, (acc_t*)d_Be2, (acc_t*)d_bstat, s_partial, ticket, d_S);
     }
@@ -675,9 +691,14 @@ static int threshold_launch(const vabft_problem* p, const void* dA, const void* 
                             void* d_expected2, void* d_T, hipStream_t st) {
     using acc_t = typename Elem<T>::acc_t;
     const int vec_ok = aligned16(dA) && ((p->lda * Elem<T>::bytes) % 16 == 0);
-    threshold_rows_kernel<T, W><<<dim3((p->M + 3) / 4), dim3(256), 0, st>>>(
-        dA, p->M, p->K, p->N, p->lda, (const acc_t*)d_Be, (const acc_t*)d_Be2, d_S, e_max, c_sigma, (acc_t*)d_astat,
-        (acc_t*)d_expected, (acc_t*)d_expected2, (acc_t*)d_T, vec_ok);
+    if (p->K / Elem<T>::vec >= 1024)
+        threshold_rows_kernel<T, W, 4><<<dim3((p->M + 3) / 4), dim3(256), 0, st>>>(
+            dA, p->M, p->K, p->N, p->lda, (const acc_t*)d_Be, (const acc_t*)d_Be2, d_S, e_max, c_sigma,
+            (acc_t*)d_astat, (acc_t*)d_expected, (acc_t*)d_expected2, (acc_t*)d_T, vec_ok);
+    else
+        threshold_rows_kernel<T, W, 2><<<dim3((p->M + 3) / 4), dim3(256), 0, st>>>(
+            dA, p->M, p->K, p->N, p->lda, (const acc_t*)d_Be, (const acc_t*)d_Be2, d_S, e_max, c_sigma,
+            (acc_t*)d_astat, (acc_t*)d_expected, (acc_t*)d_expected2, (acc_t*)d_T, vec_ok);
     return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
 }
 
@@ -795,7 +816,7 @@ static int threshold_cols_launch(const vabft_problem* p, const void* dB, const v
     acc_t* part = reinterpret_cast<acc_t*>(ws);
     dim3 grid((p->N + 64 * V - 1) / (64 * V), nsplit);
     // rows of the reduction = k (K of them), columns = n (N of them), weight of row k = (c1 A)[k]
-    encode_cols_kernel<T, true><<<grid, dim3(256), 0, st>>>(dB, p->N, p->K, p->ldb, rpb, part, vec_ok,
+    encode_cols_kernel<T, true, 4><<<grid, dim3(256), 0, st>>>(dB, p->N, p->K, p->ldb, rpb, part, vec_ok,
                                                             (const acc_t*)d_eA);
     threshold_cols_finish_kernel<acc_t><<<dim3((p->N + 255) / 256), dim3(256), 0, st>>>(
         part, nsplit, p->N, p->K, p->M, d_SA, e_max, c_sigma, (acc_t*)d_bcolstat, (acc_t*)d_expected_col,

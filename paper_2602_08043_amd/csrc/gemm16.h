@@ -306,9 +306,49 @@ __device__ __forceinline__ void gemm16_epilogue(const GemmArgs& g, f32x16_t (&ac
     gemm16_store_c<T, EDGE>(g, acc, smem, row0, col0, lane, wm, wn, l32, lh);
 }
 
+// Eight FP8 elements of a row-major matrix, widened to FP16 (exact: every E4M3 and E5M2 value is an FP16 value),
+// zero-filled outside [nr) x [nc).  FMT 1: E4M3, 2: E5M2.
+template <int FMT>
+__device__ __forceinline__ raw16 guarded_chunk8to16(const uint8_t* base, int r, int nr, int c, int nc, int64_t ld,
+                                                    int vec_ok) {
+    uint32_t w0 = 0u, w1 = 0u;
+    if (r < nr && c < nc) {
+        const uint8_t* p = base + (int64_t)r * ld + c;
+        if (vec_ok && c + 8 <= nc) {  // rows are 16-byte aligned and c is a multiple of 8
+            const uint2 v = *reinterpret_cast<const uint2*>(p);
+            w0 = v.x;
+            w1 = v.y;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (c + e < nc) (e < 4 ? w0 : w1) |= ((uint32_t)p[e]) << ((e & 3) * 8);
+        }
+    }
+    auto widen = [](uint32_t w, int byte) -> uint32_t {
+        float x;
+        if constexpr (FMT == 1)
+            x = byte == 0 ? __builtin_amdgcn_cvt_f32_fp8((int)w, 0) : byte == 1 ? __builtin_amdgcn_cvt_f32_fp8((int)w, 1)
+              : byte == 2 ? __builtin_amdgcn_cvt_f32_fp8((int)w, 2) : __builtin_amdgcn_cvt_f32_fp8((int)w, 3);
+        else
+            x = byte == 0 ? __builtin_amdgcn_cvt_f32_bf8((int)w, 0) : byte == 1 ? __builtin_amdgcn_cvt_f32_bf8((int)w, 1)
+              : byte == 2 ? __builtin_amdgcn_cvt_f32_bf8((int)w, 2) : __builtin_amdgcn_cvt_f32_bf8((int)w, 3);
+        return (uint32_t)Elem<f16_t>::from_acc(x);
+    };
+    raw16 out;
+    out.w[0] = widen(w0, 0) | (widen(w0, 1) << 16);
+    out.w[1] = widen(w0, 2) | (widen(w0, 3) << 16);
+    out.w[2] = widen(w1, 0) | (widen(w1, 1) << 16);
+    out.w[3] = widen(w1, 2) | (widen(w1, 3) << 16);
+    return out;
+}
+
 // MODE 0: plain GEMM; 1: fused row-sum check; 2: check plus the fault injector.
-template <typename T, int TRANSB, int MODE, bool EDGE>
+// IN8 (guarded kernel with T = f16_t only): A and B hold FP8 elements (1: E4M3, 2: E5M2) that are widened to
+// FP16 on their way into LDS; the products and their FP32 accumulation are then exactly those of the FP8
+// problem (section 3.6: FP8 inputs, FP32 accumulation, FP16 output), for any shape and either layout of B.
+template <typename T, int TRANSB, int MODE, bool EDGE, int IN8 = 0>
 __global__ __launch_bounds__(256) void gemm16_kernel(const GemmArgs g) {
+    static_assert(IN8 == 0 || (EDGE && std::is_same<T, f16_t>::value), "FP8 inputs ride the guarded FP16 kernel");
     using namespace g16;
     constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -342,7 +382,10 @@ __global__ __launch_bounds__(256) void gemm16_kernel(const GemmArgs g) {
 #pragma unroll
             for (int p = 0; p < 8; ++p) {
                 const int gr = row0 + r + 32 * p, gk = kbase + c * 8;
-                if (!EDGE)
+                if constexpr (IN8 != 0)
+                    ra[p] = guarded_chunk8to16<IN8>(reinterpret_cast<const uint8_t*>(g.A), gr, g.M, gk, g.K, g.lda,
+                                                    g.a_vec_ok);
+                else if (!EDGE)
                     ra[p] = ld16(A + (int64_t)gr * g.lda + gk);
                 else
                     ra[p] = guarded_chunk2(A, gr, g.M, gk, g.K, g.lda, g.a_vec_ok);
@@ -353,7 +396,10 @@ __global__ __launch_bounds__(256) void gemm16_kernel(const GemmArgs g) {
 #pragma unroll
             for (int p = 0; p < 8; ++p) {
                 const int gn = col0 + r + 32 * p, gk = kbase + c * 8;
-                if (!EDGE)
+                if constexpr (IN8 != 0)
+                    rb[p] = guarded_chunk8to16<IN8>(reinterpret_cast<const uint8_t*>(g.B), gn, g.N, gk, g.K, g.ldb,
+                                                    g.b_vec_ok);
+                else if (!EDGE)
                     rb[p] = ld16(B + (int64_t)gn * g.ldb + gk);
                 else
                     rb[p] = guarded_chunk2(B, gn, g.N, gk, g.K, g.ldb, g.b_vec_ok);
@@ -363,7 +409,10 @@ __global__ __launch_bounds__(256) void gemm16_kernel(const GemmArgs g) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int gk = kbase + kb * 8 + e, gn = col0 + nc * 8;
-                if (!EDGE)
+                if constexpr (IN8 != 0)
+                    rb[e] = guarded_chunk8to16<IN8>(reinterpret_cast<const uint8_t*>(g.B), gk, g.K, gn, g.N, g.ldb,
+                                                    g.b_vec_ok);
+                else if (!EDGE)
                     rb[e] = ld16(B + (int64_t)gk * g.ldb + gn);
                 else
                     rb[e] = guarded_chunk2(B, gk, g.K, gn, g.N, g.ldb, g.b_vec_ok);
@@ -436,13 +485,13 @@ __global__ __launch_bounds__(256) void gemm16_kernel(const GemmArgs g) {
 }
 
 // Launcher of the guarded (ragged-size) kernel.
-template <typename T, int TRANSB>
+template <typename T, int TRANSB, int IN8 = 0>
 static int gemm16_edge_launch_tb(const GemmArgs& a, int mode, hipStream_t st) {
     const dim3 grid(a.tiles_m * a.tiles_n), block(256);
     const size_t lds = g16::LDS_BYTES;
 #define VABFT_G16_CASE(VF)                                                                                 \
     if (mode == VF) {                                                                                      \
-        auto kern = gemm16_kernel<T, TRANSB, VF, true>;                                                    \
+        auto kern = gemm16_kernel<T, TRANSB, VF, true, IN8>;                                               \
         static bool attr_set = false;                                                                      \
         if (!attr_set) {                                                                                   \
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \

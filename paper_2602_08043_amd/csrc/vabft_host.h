@@ -136,6 +136,8 @@ int gemm16_launch_f16_nn(const GemmArgs& a, int mode, bool edge, hipStream_t st)
 int gemm16_launch_f16_nt(const GemmArgs& a, int mode, bool edge, hipStream_t st);
 int gemm8_launch_f8_nt(const GemmArgs& a, int mode, hipStream_t st);   // E4M3, whole tiles only
 int gemm8_launch_bf8_nt(const GemmArgs& a, int mode, hipStream_t st);  // E5M2, whole tiles only
+// FP8 problems of any shape and either layout of B (guarded kernel, operands widened to FP16 on load)
+int gemm16_launch_f8_edge(const GemmArgs& a, int mode, int e5m2, int transB, hipStream_t st);
 // wave_tile: 64 (128 x 128 tiles per workgroup) or 32 (64 x 64 tiles); a.tiles_m / a.tiles_n must count tiles of that size
 int gemmw_launch_f32(const GemmArgs& a, int transB, int mode, bool edge, int wave_tile, hipStream_t st);
 int gemmw_launch_f64(const GemmArgs& a, int transB, int mode, bool edge, int wave_tile, hipStream_t st);
