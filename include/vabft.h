@@ -109,7 +109,7 @@ int vabft_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream
  * 5.0e-9*sqrt(n)+1.2e-7 for a float accumulator, 1.0e-17*sqrt(n)+2.5e-16 for double) and the
  * law measured on MI355X with this library's kernels by the paper's calibration protocol
  * (3.0e-9*sqrt(n)+4.2e-7, resp. 8.0e-18*sqrt(n)+6.6e-16: at least 25 % above every value that
- * protocol produced, its own 20 % margin included).  FP8 inputs: the constant 5.5e-6 measured
+ * protocol produced, its own 20 % margin included).  FP8 inputs: the constant 6.5e-6 measured
  * the same way (the FP8 matrix instruction accumulates its 64-term dot products with less than FP32
  * precision). */
 double vabft_default_emax(int32_t dtype, int32_t K, int32_t N);

@@ -504,9 +504,10 @@ double vabft_default_emax(int32_t dtype, int32_t K, int32_t N) {
     const double n = (double)(K > N ? K : N);
     double paper, measured;
     // FP8: the 32x32x64 matrix instruction does not carry full FP32 precision through its 64-term dot
-    // product; measured by the same protocol (n = 256 .. 8192, 7 000 - 48 000 trials per size) the relative
-    // difference is 31 - 72 u_FP32, largest at small n: a constant above every +20 % value.
-    if (is_fp8(dtype)) return 5.5e-6;
+    // product; measured by the same protocol (n = 256 .. 8192, B stored N x K, 25 000 - 100 000 trials per size) the
+    // relative difference is 31 - 72 u_FP32 for E4M3 and 18 - 48 u_FP32 for E5M2, largest at small n: a constant
+    // 25 % above the largest +20 % value (5.15e-6).
+    if (is_fp8(dtype)) return 6.5e-6;
     if (dtype == VABFT_F64) {
         paper = 1.0e-17 * sqrt(n) + 2.5e-16;
         measured = 8.0e-18 * sqrt(n) + 6.6e-16;
