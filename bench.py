@@ -30,9 +30,10 @@ PEAK_TFLOPS = {"bf16": 2516.6, "f16": 2516.6, "f8": 5033.2, "f8e5m2": 5033.2, "f
 HBM_PEAK_GBPS = 8000.0
 ELEM_BYTES = {"bf16": 2, "f16": 2, "f8": 1, "f8e5m2": 1, "f32": 4, "f64": 8}
 # Bytes per launch of the verified GEMM kernel that crossed the L2 boundary, from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE scaled by the same counters on 1 GiB device copies (profiles/*_hbm_traffic.md, one table per
-# workload).  A counter figure cannot be taken live inside this script; workloads without a profile report null.
-PROFILED_TRAFFIC_BYTES = {}
+# WRITE_SIZE scaled by the same counters on 1 GiB device copies (profiles/verified_gemm_c1_to_c5_hbm_traffic.md, one
+# table per workload; the bytes are served by the Infinity Cache or by HBM, the counter does not tell which).  A counter figure cannot be taken live inside this script; workloads without a profile report null.
+PROFILED_TRAFFIC_BYTES = {"c1_f32_256": 2062399, "c2_bf16_4096": 239404586, "c3_bf16_ffn": 688285063,
+                          "c4_f16_8192": 1762836180, "c5_f64_2048": 238568149}
 
 HEADLINE = "c2_bf16_4096"
 WORKLOAD_TEXT = {
@@ -310,9 +311,11 @@ def bench_config(mods, name, variant, steps, warmup, args, headline):
     # ---- HBM-bound passes on rotating buffers (> 512 MB in total, so the 256 MB Infinity Cache cannot serve them)
     eb = ELEM_BYTES[dt]
     if variant == 0:
-        nrot = max(3, int(np.ceil(600e6 / (K * N * eb))) + 1)
+        # (at most 64 buffers: a matrix of the smallest configuration is 256 KiB, its passes are bound by launch
+        # latency whatever serves them)
+        nrot = min(64, max(3, int(np.ceil(600e6 / (K * N * eb))) + 1))
         Bs = [B] + [B.clone() for _ in range(nrot - 1)]
-        nrotA = max(3, int(np.ceil(600e6 / (M * K * eb))) + 1)
+        nrotA = min(64, max(3, int(np.ceil(600e6 / (M * K * eb))) + 1))
         As = [A] + [A.clone() for _ in range(nrotA - 1)]
         ctr = [0]
 
