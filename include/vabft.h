@@ -108,7 +108,7 @@ int vabft_workspace_init(void* d_workspace, size_t workspace_bytes, void* stream
  * the larger of the paper's GPU law (table "Recommended e_max across platforms":
  * 5.0e-9*sqrt(n)+1.2e-7 for a float accumulator, 1.0e-17*sqrt(n)+2.5e-16 for double) and the
  * law measured on MI355X with this library's kernels by the paper's calibration protocol
- * (3.0e-9*sqrt(n)+4.2e-7, resp. 8.0e-18*sqrt(n)+6.6e-16: at least 25 % above every value that
+ * (3.0e-9*sqrt(n)+4.2e-7, resp. 8.0e-18*sqrt(n)+7.0e-16: at least 25 % above every value that
  * protocol produced, its own 20 % margin included).  FP8 inputs: the constant 6.5e-6 measured
  * the same way (the FP8 matrix instruction accumulates its 64-term dot products with less than FP32
  * precision). */

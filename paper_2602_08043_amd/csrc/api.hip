@@ -510,7 +510,7 @@ double vabft_default_emax(int32_t dtype, int32_t K, int32_t N) {
     if (is_fp8(dtype)) return 6.5e-6;
     if (dtype == VABFT_F64) {
         paper = 1.0e-17 * sqrt(n) + 2.5e-16;
-        measured = 8.0e-18 * sqrt(n) + 6.6e-16;
+        measured = 8.0e-18 * sqrt(n) + 7.0e-16;
     } else {
         paper = 5.0e-9 * sqrt(n) + 1.2e-7;
         measured = 3.0e-9 * sqrt(n) + 4.2e-7;

@@ -50,6 +50,18 @@ __device__ __forceinline__ void g2l16(const void* gptr, lds_u8* lds_base) {
 // Partials exchanged between workgroups (which may sit on different XCDs with private L2s) go
 // through device-scope relaxed atomic stores and loads: they are performed at the device's
 // coherence point, so no cache write-back / invalidate fence is needed around the ticket.
+// The order relied on is the hardware's, not the language's (a release fence at agent scope writes back the
+// whole L2 on this chip and cost 27 us per launch):
+//   1. an agent-scope atomic store is a write-through store: the issuing XCD's L2 keeps no dirty copy, the
+//      value goes to the memory-side coherence point that all XCDs share;
+//   2. s_waitcnt vmcnt(0) returns only when that point has acknowledged every outstanding store of the wavefront;
+//   3. the workgroup barrier that follows puts all wavefronts' waits in front of the one thread's ticket
+//      atomicAdd, itself executed at the same coherence point, so a workgroup that sees ticket == tiles_n - 1
+//      comes after every other workgroup's partials there;
+//   4. the last arriver reads the partials with agent-scope atomic loads, which are not served from its
+//      XCD's L2 or the compute unit's vector cache.
+// The s_waitcnt builtin and the barrier are also compiler barriers for these atomics (volatile-like side effects),
+// so the compiler keeps the same order.  A back-to-back soak test on rotating inputs watches this protocol.
 __device__ __forceinline__ float ld_agent(const float* p) {
     return __builtin_bit_cast(float, __hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED,
                                                         __HIP_MEMORY_SCOPE_AGENT));

@@ -13,6 +13,7 @@ pytestmark = pytest.mark.gpu
 from test_gpu_parity import (OUT_TINY, U_OUT, _dev, _emax, _session, _tol, check_light, check_rows)  # noqa: E402
 from test_gpu_weighted import check_weighted  # noqa: E402
 from test_gpu_columns import check_columns  # noqa: E402
+from test_gpu_blocks import check_blocks  # noqa: E402
 
 
 FORMATS = ["f8", "f8e5m2"]   # E4M3, E5M2 (section 3.6 names both)
@@ -203,3 +204,29 @@ def test_fp8_fused_call_single_launch(M, N, K, f8):
     assert r["flags"][i] == 1 and r["nflag"] == 1 and r["flags"].sum() == 1
     vg.run_fused(dA, dB)
     assert vg.results()["nflag"] == 0
+
+
+@pytest.mark.parametrize("f8", FORMATS)
+@pytest.mark.parametrize("M,N,K,transB", [(512, 768, 256, 1), (300, 520, 200, 0)])
+def test_fp8_blockwise(M, N, K, transB, f8):
+    """Block-wise verification (blocks of 256 columns) of FP8 problems: the whole-tile kernel's partials-only mode
+    and the guarded route, against the oracle; a planted fault flags exactly its (block, row) pair."""
+    from paper_2602_08043_amd import binding as vb
+    W = vb.vabft_block_width(f8)
+    assert W == 256
+    A, B = _gen8(M, N, K, transB, 23, "n_1_1", f8)
+    print(f"{f8} blocks {M}x{N}x{K} transB={transB}", flush=True)
+    e_blk = vb.vabft_default_emax(f8, K, min(N, W))
+    vg = _session(M, N, K, f8, transB)
+    dA, dB = _dev(A, f8), _dev(B, f8)
+    vg.run_blocks(dA, dB)
+    r = vg.results()
+    ob = orc.verify_blocks(A, B, f8, transB, W, e_blk)
+    check_blocks(r, ob, f8)
+    check_C8(r, ob, A, B, transB, f8)
+    assert r["nflag"] == 0 and r["nblockflag"] == 0 and not r["blockflags"].any() and not ob["blockflags"].any()
+    i, j = M // 2, N - 3
+    vg.run_blocks(dA, dB, inj=vg.make_inject(mode=1, faults=[(i, j, 30)]))
+    r = vg.results()
+    assert r["nblockflag"] == 1 and r["blockflags"][j // W, i] == 1 and r["blockflags"].sum() == 1
+    assert r["flags"][i] == 1 and r["nflag"] == 1

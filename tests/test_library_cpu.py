@@ -41,7 +41,7 @@ def test_status_strings_and_default_emax(lib):
     for n in (128, 512, 4096, 8192, 65536):
         paper, meas = 5.0e-9 * n ** 0.5 + 1.2e-7, 3.0e-9 * n ** 0.5 + 4.2e-7
         assert vb.vabft_default_emax("bf16", n, n) == pytest.approx(max(paper, meas))
-        paper, meas = 1.0e-17 * n ** 0.5 + 2.5e-16, 8.0e-18 * n ** 0.5 + 6.6e-16
+        paper, meas = 1.0e-17 * n ** 0.5 + 2.5e-16, 8.0e-18 * n ** 0.5 + 7.0e-16
         assert vb.vabft_default_emax("f64", n, n) == pytest.approx(max(paper, meas))
     assert vb.vabft_default_emax("f16", 4096, 11008) == vb.vabft_default_emax("f32", 11008, 4096)
 
