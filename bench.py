@@ -255,22 +255,44 @@ def bench_config(mods, name, variant, steps, warmup, args, headline):
     # ---- the timed region: W untimed warm-up steps, then exactly K whole-path steps between two synchronisations
     ms_step = timed(torch, step, steps, warmup)
     nflag_timed = int(vg.nflag.item())
-    ms_plain = timed(torch, lambda: vg.gemm(A, B, 0), steps, warmup)
+    # ... and K back-to-back launches of the fused call alone (the roofline's launch duration)
     ms_steady = timed(torch, lambda: vg.gemm_fused(A, B, e_max, deferred_S=True), steps, warmup)
-    vg.encode(B)  # the calls below read S1..S3 from their own buffer
+
+    # ---- the overhead figures.  The chip's clock under matrix load follows its power draw with a lag of many
+    # launches, so two loops timed one after the other sit in different states and their ratio drifts by several
+    # percent either way.  The routes are therefore timed in interleaved rounds (every route sees the same state)
+    # and compared by their medians.  Both forms of S1..S3 are in place at once: folded in vg.S for the calls that
+    # read it, as partials in the workspace for the fused call.
+    vg.encode(B)
     vg.threshold(A, e_max)
-    ms_check = timed(torch, lambda: vg.gemm(A, B, 1), steps, warmup)
+    vg.encode(B, defer_S=True)
 
     def three_call():
         vg.threshold(A, e_max)
         vg.gemm(A, B, 1)
 
-    ms_three_call = timed(torch, three_call, steps, warmup)
-    # a second pass over the three main figures, interleaved, keeps slow clock drifts out of the ratios
-    ms_plain = min(ms_plain, timed(torch, lambda: vg.gemm(A, B, 0), steps, warmup))
-    vg.encode(B, defer_S=True)
-    ms_steady = min(ms_steady, timed(torch, lambda: vg.gemm_fused(A, B, e_max, deferred_S=True), steps, warmup))
-    ms_step = min(ms_step, timed(torch, step, steps, warmup))
+    routes = {"step": step, "plain": lambda: vg.gemm(A, B, 0),
+              "fused": lambda: vg.gemm_fused(A, B, e_max, deferred_S=True), "check": lambda: vg.gemm(A, B, 1),
+              "three_call": three_call}
+    rounds = 9
+    per_round = max(5, steps // rounds)
+    samples = {k: [] for k in routes}
+    for _ in range(rounds):
+        for k, fn in routes.items():
+            samples[k].append(timed(torch, fn, per_round, 2))
+    med = {k: float(np.median(v)) for k, v in samples.items()}
+    ms_plain, ms_check, ms_three_call = med["plain"], med["check"], med["three_call"]
+    ms_fused_il, ms_step_il = med["fused"], med["step"]
+    # The other fair comparison: every route brought to its own sustained state first (a quarter of a second of
+    # nothing but that route), then timed; the plain GEMM at both ends.  A route whose launches contain waits
+    # draws less power and holds a higher clock in its matrix phases, so these ratios come out below the
+    # interleaved ones: this is what a job that runs one route all day sees.
+    own = {}
+    for k in ("plain", "check", "fused", "three_call", "step", "plain_again"):
+        fn = routes["plain" if k == "plain_again" else k]
+        spin_up(torch, fn, 0.25)
+        own[k] = timed(torch, fn, steps, warmup)
+    own_plain = 0.5 * (own["plain"] + own["plain_again"])
     vg.encode(B)
     vg.threshold(A, e_max)
 
@@ -297,14 +319,27 @@ def bench_config(mods, name, variant, steps, warmup, args, headline):
                      "avg_launch_ms": ms_dom,
                      "measured_mfma_loop_tflops": probe,
                      "frac_of_measured_mfma_loop": (achieved / probe) if probe else None},
-        "plain_gemm_tflops": flops / (ms_plain * 1e-3) / 1e12,
-        "plain_gemm_frac_of_peak": flops / (ms_plain * 1e-3) / 1e12 / peak,
-        "overhead_pct": {"cold_encode_included": 100.0 * (ms_step / ms_plain - 1.0),
-                         "steady_state_B_preencoded": 100.0 * (ms_steady / ms_plain - 1.0),
-                         "three_call_route_B_preencoded": 100.0 * (ms_three_call / ms_plain - 1.0),
-                         "check_with_given_threshold": 100.0 * (ms_check / ms_plain - 1.0)},
-        "ms": {"plain_gemm": ms_plain, "verified_gemm_given_threshold": ms_check, "fused_call": ms_steady,
-               "threshold_plus_gemm_calls": ms_three_call},
+        "plain_gemm_tflops": flops / (own_plain * 1e-3) / 1e12,
+        "plain_gemm_frac_of_peak": flops / (own_plain * 1e-3) / 1e12 / peak,
+        # every route in its own sustained state (see above), against the plain GEMM in its own
+        "overhead_pct": {"cold_encode_included": 100.0 * (own["step"] / own_plain - 1.0),
+                         "steady_state_B_preencoded": 100.0 * (own["fused"] / own_plain - 1.0),
+                         "three_call_route_B_preencoded": 100.0 * (own["three_call"] / own_plain - 1.0),
+                         "check_with_given_threshold": 100.0 * (own["check"] / own_plain - 1.0),
+                         "method": "each route timed after a quarter of a second of nothing but that route; the plain "
+                                   "GEMM at both ends"},
+        # ratios of medians over interleaved rounds of all routes: every route in the same (mixed) state, in which
+        # the plain GEMM runs faster than it does on its own
+        "overhead_pct_interleaved_rounds": {
+            "cold_encode_included": 100.0 * (ms_step_il / ms_plain - 1.0),
+            "steady_state_B_preencoded": 100.0 * (ms_fused_il / ms_plain - 1.0),
+            "three_call_route_B_preencoded": 100.0 * (ms_three_call / ms_plain - 1.0),
+            "check_with_given_threshold": 100.0 * (ms_check / ms_plain - 1.0),
+            "plain_gemm_ms": ms_plain,
+            "method": f"medians of {rounds} interleaved rounds of {per_round} launches per route"},
+        "ms": {"plain_gemm": own_plain, "verified_gemm_given_threshold": own["check"], "fused_call": own["fused"],
+               "whole_path_step": own["step"], "threshold_plus_gemm_calls": own["three_call"],
+               "fused_call_timed_region": ms_steady},
         "flags_in_timed_region": nflag_timed,
     }
 
@@ -361,25 +396,32 @@ def bench_config(mods, name, variant, steps, warmup, args, headline):
         }
 
     if headline:
-        # ---- the other routes, on the headline workload only
+        # ---- the other routes, on the headline workload only: prepared once (each keeps its vectors in buffers of
+        # its own), then each timed in its own sustained state against the plain GEMM, like the figures above
         vg.encode_weighted(B)
         vg.threshold_weighted(A, e_max)
-        ms_w = timed(torch, lambda: vg.gemm_weighted(A, B), steps, warmup)
-        ms_locate = timed(torch, lambda: vg.locate_correct(1), steps, warmup)
         vg.encode_blocks(B)
         vg.threshold_blocks(A)
-        ms_blocks = timed(torch, lambda: vg.gemm_blocks(A, B), steps, warmup)
-        vg.encode(B)
-        vg.threshold(A, e_max)
         vg.encode_a(A)
         vg.threshold_cols(B)
-        ms_rc = timed(torch, lambda: vg.gemm_rc(A, B), steps, warmup)
+        vg.encode(B)
+        vg.threshold(A, e_max)
+        routes2 = {"plain": lambda: vg.gemm(A, B, 0), "w": lambda: vg.gemm_weighted(A, B),
+                   "blocks": lambda: vg.gemm_blocks(A, B), "rc": lambda: vg.gemm_rc(A, B)}
+        own2 = {}
+        for k in ("plain", "w", "blocks", "rc", "plain_again"):
+            fn = routes2["plain" if k == "plain_again" else k]
+            spin_up(torch, fn, 0.25)
+            own2[k] = timed(torch, fn, steps, warmup)
+        ms_w, ms_blocks, ms_rc = own2["w"], own2["blocks"], own2["rc"]
+        ms_plain2 = 0.5 * (own2["plain"] + own2["plain_again"])
+        ms_locate = timed(torch, lambda: vg.locate_correct(1), steps, warmup)
         vg.encode(B)
         vg.threshold(A, e_max)
         out["other_routes_gemm_overhead_pct_vs_plain"] = {
-            "with_position_weighted_row_sums": 100.0 * (ms_w / ms_plain - 1.0),
-            "with_row_and_column_check": 100.0 * (ms_rc / ms_plain - 1.0),
-            "block_wise_check": 100.0 * (ms_blocks / ms_plain - 1.0),
+            "with_position_weighted_row_sums": 100.0 * (ms_w / ms_plain2 - 1.0),
+            "with_row_and_column_check": 100.0 * (ms_rc / ms_plain2 - 1.0),
+            "block_wise_check": 100.0 * (ms_blocks / ms_plain2 - 1.0),
             "ms_locate_correct": ms_locate}
 
     if not args.no_quality:
@@ -483,7 +525,8 @@ def main():
                    "step": "vabft_encode(B, d_S=NULL) + vabft_gemm_verified_fused(A, B, d_S=NULL) [B-side checksum and "
                            "statistics; A-side statistics, fold of S1..S3, threshold, GEMM, row sums, compare/flag]"},
     }
-    for k in ("roofline", "frac_of_peak_whole_path", "plain_gemm_tflops", "plain_gemm_frac_of_peak", "overhead_pct", "ms",
+    for k in ("roofline", "frac_of_peak_whole_path", "plain_gemm_tflops", "plain_gemm_frac_of_peak", "overhead_pct",
+              "overhead_pct_interleaved_rounds", "ms",
               "hbm_passes", "other_routes_gemm_overhead_pct_vs_plain", "flags_in_timed_region", "quality",
               "cpu_baseline"):
         if k in head:
