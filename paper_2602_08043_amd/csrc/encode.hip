@@ -602,10 +602,17 @@ static int encode_rows_per_block(const vabft_problem* p, int waves) {
     return rpb;
 }
 constexpr int ENC_WAVES_OWN_FOLD = 16, ENC_WAVES_DEFERRED = 8;
+// Wavefronts per workgroup of the row walk.  The smaller workgroup is only used when both sizes give one
+// wavefront per row (K >= 4096): with several wavefronts per row the split of a row into segments (and with it
+// the rounding of Be) would depend on the workgroup size, and both routes must produce the same bits.
+static int encode_rows_waves(const vabft_problem* p, bool deferred) {
+    if (deferred && encode_rows_per_block(p, ENC_WAVES_OWN_FOLD) == ENC_WAVES_OWN_FOLD) return ENC_WAVES_DEFERRED;
+    return ENC_WAVES_OWN_FOLD;
+}
 // Per-block partials of (S1, S2, S3), [blocks][3] doubles: the number an encode with the fold deferred leaves
 // (what the fused GEMM folds, and what the workspace reserves; an encode that folds them itself leaves no more)
 int s_partial_count(const vabft_problem* p) {
-    const int rpb = encode_rows_per_block(p, ENC_WAVES_DEFERRED);
+    const int rpb = encode_rows_per_block(p, encode_rows_waves(p, true));
     return (p->K + rpb - 1) / rpb;
 }
 
@@ -626,7 +633,7 @@ static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, voi
     using acc_t = typename Elem<T>::acc_t;
     const int vec_ok = aligned16(dB) && ((p->ldb * Elem<T>::bytes) % 16 == 0);
     if (!p->transB) {
-        const int waves = d_S ? ENC_WAVES_OWN_FOLD : ENC_WAVES_DEFERRED;
+        const int waves = encode_rows_waves(p, d_S == nullptr);
         const int rpb = encode_rows_per_block(p, waves);
         const int kblocks = (p->K + rpb - 1) / rpb;
 #define VABFT_ENC_ROWS(R, WV)                                                                                    \
@@ -641,7 +648,7 @@ static int encode_launch(const vabft_problem* p, const void* dB, void* d_Be, voi
         case 2: VABFT_ENC_ROWS(2, WV); break;     \
         default: VABFT_ENC_ROWS(1, WV); break;    \
     }
-        if (d_S) {
+        if (waves == ENC_WAVES_OWN_FOLD) {
             VABFT_ENC_ROWS_SWITCH(ENC_WAVES_OWN_FOLD)
         } else {
             VABFT_ENC_ROWS_SWITCH(ENC_WAVES_DEFERRED)

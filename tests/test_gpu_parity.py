@@ -480,6 +480,10 @@ DEFERRED = [
     ("bf16", 256, 512, 4352, 0),
     # the passes back to back (a small kernel folds the partials first)
     ("bf16", 300, 520, 200, 1), ("f16", 100, 99, 50, 0), ("f32", 200, 260, 70, 0), ("f64", 131, 67, 33, 1),
+    # row walks in which several wavefronts share a row of B (few rows, long rows), one with two wavefronts per row,
+    # and one where the encode with the fold deferred runs its smaller workgroups (K >= 4096): the split of a row
+    # into segments, and with it the bits of Be, must not depend on the route
+    ("f64", 1024, 2048, 128, 0), ("f64", 256, 2048, 2048, 0), ("f32", 128, 4096, 4096, 0), ("f16", 256, 8192, 256, 0),
 ]
 
 

@@ -24,7 +24,9 @@ def _differs(a, b):
 
 @pytest.mark.parametrize("dtype,M,N,K,transB,launches", [
     ("bf16", 2048, 2048, 512, 0, 2000), ("f16", 1024, 2048, 512, 1, 2000),
-    ("f32", 512, 512, 256, 0, 1500), ("f64", 512, 512, 256, 1, 1500),
+    ("bf16", 4096, 5120, 256, 1, 600),   # 320 tiles: more than one round per compute unit, arrivals spread over rounds
+    ("f32", 512, 512, 256, 0, 1500), ("f64", 512, 512, 256, 1, 1500),          # 64 x 64 tiles
+    ("f32", 2048, 1024, 128, 1, 1000), ("f64", 1024, 2048, 128, 0, 1000),      # 128 x 128 tiles
 ])
 def test_back_to_back_fused_launches_repeat_bit_for_bit(dtype, M, N, K, transB, launches):
     rot = 4
