@@ -557,6 +557,69 @@ def verify_blocks(A_st, B_st, dtype: str, transB: int, W: int, e_max: float, c_s
     return out
 
 
+def verify_blocks_k(A_st, B_st, dtype: str, transB: int, W: int, KB: int, e_max: float,
+                    c_sigma: float = C_SIGMA_DEFAULT, full_gemm: bool = True):
+    """Block-wise verification with K split as well (section 5.2: row statistics "for each block of A and B", the
+    threshold formula per block, block checksums; the section's tile is (M, K, N) = (128, 1024, 256), i.e. blocks
+    of K too).  K-block b holds k in [b KB, min(K, (b+1) KB)), column block t holds columns [t W, min(N, (t+1) W)).
+    Block (b, t) is the product of the K-block of A (all rows) with the (K-block, column-block) piece of B, verified
+    on its own: its checksum column Be_{b,t} = B_{b,t} r1, expected_{b,t} = A_b Be_{b,t}, the row sums of the partial
+    product A_b B_{b,t}, and Algorithm 1 with the statistics of A_b's rows and B_{b,t}'s rows and the block's width
+    in place of N.  The aggregate of a row is the sum of its block differences (again the full-row difference)
+    and the OR of its block flags.  Arrays are indexed [K-block][column block][...]."""
+    A = decode(A_st, dtype)
+    B = logical_B(B_st, dtype, transB)
+    M, K = A.shape
+    N = B.shape[1]
+    nkb, nb = (K + KB - 1) // KB, (N + W - 1) // W
+    out = {"W": W, "KB": KB, "nkblocks": nkb, "nblocks": nb}
+    for name, shape in (("S_blk", (nkb, nb, 3)), ("expected_blk", (nkb, nb, M)), ("T_blk", (nkb, nb, M)),
+                        ("scale_expected_blk", (nkb, nb, M)), ("scale_rowsum_blk", (nkb, nb, M)),
+                        ("astat", (nkb, M, 3))):
+        out[name] = np.zeros(shape)
+    out["Be_blk"] = [None] * nkb          # per K-block: [nb][length of the K-block]
+    out["scale_Be_blk"] = [None] * nkb
+    if full_gemm:
+        out["C"] = gemm(A, B)
+        out["rowsum_blk"] = np.zeros((nkb, nb, M))
+    for b in range(nkb):
+        ks = slice(b * KB, min(K, (b + 1) * KB))
+        Ab = A[:, ks]
+        mxa, mna, mua = row_stats(Ab)
+        out["astat"][b] = np.stack([mxa, mna, mua], axis=1)
+        be, sc = [], []
+        for t in range(nb):
+            Bbt = B[ks, t * W:min(N, (t + 1) * W)]
+            bet = encode_checksum(Bbt)
+            be.append(bet)
+            sc.append(np.abs(Bbt).sum(axis=1))
+            out["S_blk"][b, t] = b_aggregates(Bbt)
+            out["expected_blk"][b, t] = expected_checksum(Ab, bet)
+            out["T_blk"][b, t] = threshold(Ab, Bbt, e_max, c_sigma)
+            out["scale_expected_blk"][b, t] = np.abs(Ab) @ np.abs(bet)
+            out["scale_rowsum_blk"][b, t] = np.abs(Ab) @ sc[-1]
+            if full_gemm:
+                out["rowsum_blk"][b, t] = row_sums(gemm(Ab, Bbt))
+        out["Be_blk"][b] = np.stack(be)
+        out["scale_Be_blk"][b] = np.stack(sc)
+    if full_gemm:
+        out["E_blk"] = out["expected_blk"] - out["rowsum_blk"]
+        out["blockflags"] = fault_flags(out["E_blk"], out["T_blk"])
+        out["E"] = out["E_blk"].sum(axis=(0, 1))
+        out["flags"] = (out["blockflags"].sum(axis=(0, 1)) > 0).astype(np.int32)
+    return out
+
+
+def replay_faults_blocks_k(rowsum_blk: np.ndarray, records, W: int) -> np.ndarray:
+    """Block row sums [K-block][column block][row] after the logged faults.  A fault is injected on the finished
+    accumulator (section 6.1), after the last K-block has been added, so it lands in the last K-block's share:
+    rowsum_blk[-1][col // W][row] += (after - before)."""
+    out = np.array(rowsum_blk, dtype=np.float64, copy=True)
+    for (i, j, _bit, before, after) in records:
+        out[-1, j // W, i] = out[-1, j // W, i] + (after - before)
+    return out
+
+
 def replay_faults_blocks(rowsum_blk: np.ndarray, records, W: int) -> np.ndarray:
     """Block row sums after the logged faults: rowsum_blk[col // W][row] += (after - before)."""
     out = np.array(rowsum_blk, dtype=np.float64, copy=True)

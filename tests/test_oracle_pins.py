@@ -697,6 +697,58 @@ def test_row_check_tolerance_scales_match_brute_force():
         assert np.array_equal(o[key], ot[key]), key
 
 
+def test_k_blocked_blockwise_partitions_the_blockwise_check():
+    """Splitting K as well: the K-block shares of a column block add up to the column block's quantities, one
+    K-block as deep as K is the column-block check itself, and every (K-block, column-block) threshold is
+    Algorithm 1 on that piece alone (brute force)."""
+    g = np.random.default_rng(77)
+    M, K, N, W, KB = 9, 20, 23, 8, 6        # K-blocks of 6, 6, 6, 2; column blocks of 8, 8, 7
+    A = g.integers(-3, 4, size=(M, K)).astype(np.float64)
+    B = g.integers(-3, 4, size=(K, N)).astype(np.float64)
+    blk = orc.verify_blocks(A, B, "f64", 0, W, 1e-12)
+    kb = orc.verify_blocks_k(A, B, "f64", 0, W, KB, 1e-12)
+    assert kb["nkblocks"] == 4 and kb["nblocks"] == 3
+    assert np.array_equal(kb["rowsum_blk"].sum(axis=0), blk["rowsum_blk"])          # integers: exact
+    assert np.array_equal(kb["expected_blk"].sum(axis=0), blk["expected_blk"])
+    assert np.array_equal(np.concatenate(kb["Be_blk"], axis=1), blk["Be_blk"])
+    assert not kb["E_blk"].any() and not kb["flags"].any()
+    one = orc.verify_blocks_k(A, B, "f64", 0, W, 64, 1e-12)
+    assert one["nkblocks"] == 1
+    for key in ("expected_blk", "T_blk", "rowsum_blk", "S_blk"):
+        assert np.array_equal(one[key][0], blk[key]), key
+    # brute force of one interior piece and of the ragged corner piece
+    for (b, t) in ((1, 1), (3, 2)):
+        ks, ns = range(b * KB, min(K, (b + 1) * KB)), range(t * W, min(N, (t + 1) * W))
+        for i in (0, 4, M - 1):
+            a = [A[i, k] for k in ks]
+            mu_a = sum(a) / len(a)
+            var_a = max(0.0, (max(a) - mu_a) * (mu_a - min(a)))
+            s1 = s2 = s3 = 0.0
+            exp = rs = 0.0
+            for k in ks:
+                row = [B[k, n] for n in ns]
+                mu = sum(row) / len(row)
+                s1 += abs(mu)
+                s2 += max(0.0, (max(row) - mu) * (mu - min(row)))
+                s3 += mu * mu
+                exp += A[i, k] * sum(row)
+                rs += sum(A[i, k] * x for x in row)
+            n = len(ns)
+            T = 1e-12 * (n * abs(mu_a) * s1 + 2.5 * math.sqrt(n * mu_a ** 2 * s2 + n ** 2 * var_a * s3)
+                         + 2.5 * math.sqrt(n) * math.sqrt(var_a) * math.sqrt(s2))
+            assert kb["T_blk"][b, t, i] == pytest.approx(T, rel=1e-13)
+            assert kb["expected_blk"][b, t, i] == exp and kb["rowsum_blk"][b, t, i] == rs
+            assert kb["astat"][b, i].tolist() == [max(a), min(a), mu_a]
+    # a fault on the finished accumulator lands in the last K-block's share of its column block
+    rs = orc.replay_faults_blocks_k(kb["rowsum_blk"], [(4, 17, 0, kb["C"][4, 17], kb["C"][4, 17] + 5.0)], W)
+    E = kb["expected_blk"] - rs
+    want = np.zeros_like(E)
+    want[3, 2, 4] = -5.0
+    assert np.array_equal(E, want)
+    # tolerance scales: the pieces' scales add up to the column block's
+    assert np.array_equal(kb["scale_rowsum_blk"].sum(axis=0), blk["scale_rowsum_blk"])
+
+
 def test_column_and_block_tolerance_scales_match_brute_force():
     M, K, N, W = 6, 5, 8, 3
     A, B = _int_matrices(12, M, K, N)
