@@ -304,7 +304,8 @@ int vabft_gemm_verified_rc(const vabft_problem* p, const void* dA, const void* d
  * in blocks of W = vabft_block_width(dtype) columns (256; 64 for FP32 / FP64): block t holds columns
  * [tW, min(N, (t+1)W)), nblocks = ceil(N / W).  Per block: row statistics of the block of B, Algorithm 1 with
  * the block's width in place of N, block checksums compared on their own; a row's aggregate difference is
- * the sum of its block differences and its flag the OR of its block flags.  K is not split.
+ * the sum of its block differences and its flag the OR of its block flags.  K is not split here (the *_k entry
+ * points further down split it as well).
  * All block arrays are [nblocks][len] (block-major), in the accumulator type unless stated. */
 int32_t vabft_block_width(int32_t dtype);
 
@@ -330,6 +331,38 @@ int vabft_gemm_verified_blocks(const vabft_problem* p, const void* dA, const voi
                                int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog,
                                int32_t* d_ninj, void* d_workspace, size_t workspace_bytes,
                                void* stream);
+
+/* ---- Block-wise verification with K split as well (section 5.2: row statistics "for each block of A and B",
+ * the threshold formula per block, tile (M, K, N) = (128, 1024, 256)).  K-block b holds k in
+ * [b*kblock, min(K, (b+1)*kblock)), nkb = ceil(K / kblock) = vabft_kblock_count; kblock is a positive multiple of
+ * 128.  Piece (b, t) is the product of the K-block of A (all rows) with the (K-block, column block) piece of B,
+ * verified on its own: its checksum column, its expected row sums, the row sums of the partial product, and
+ * Algorithm 1 with the statistics of the K-block of A's rows and of the piece of B's rows.  A row's aggregate
+ * difference is the sum of its piece differences and its flag the OR of its piece flags.
+ * Arrays are [nkb][nblocks][len] unless stated.  The workspace for these calls is
+ * vabft_workspace_bytes_blocks_k bytes (it holds the workspace of the whole problem in front, so the other entry
+ * points can share it).
+ *   d_Be_blk_k: nkb pieces one after the other, piece b = [nblocks][len_b] acc at element offset b*nblocks*kblock
+ *   d_S_blk_k [nkb][nblocks][3] double;  d_astat_k [nkb][3M] acc
+ * vabft_encode_blocks_k and vabft_threshold_blocks_k take every type and shape (they run the column-block passes
+ * on the K-blocks).  vabft_gemm_verified_blocks_k takes BF16 / FP16 problems made of whole 256 x 256 x 64 tiles
+ * with 16-byte aligned rows (VABFT_EUNSUPPORTED otherwise): the kernel leaves the row sums of its accumulator tile
+ * at every K-block boundary, in double, and a piece's row sum is the difference of two consecutive ones.  The
+ * injector acts on the finished accumulator, i.e. on the last K-block's share. */
+int32_t vabft_kblock_count(const vabft_problem* p, int32_t kblock);
+size_t vabft_workspace_bytes_blocks_k(const vabft_problem* p, int32_t kblock);
+int vabft_encode_blocks_k(const vabft_problem* p, int32_t kblock, const void* dB, void* d_Be_blk_k,
+                          double* d_S_blk_k, void* d_workspace, size_t workspace_bytes, void* stream);
+int vabft_threshold_blocks_k(const vabft_problem* p, int32_t kblock, const void* dA, const void* d_Be_blk_k,
+                             const double* d_S_blk_k, double e_max, double c_sigma, void* d_astat_k,
+                             void* d_expected_blk_k, void* d_T_blk_k, void* stream);
+int vabft_gemm_verified_blocks_k(const vabft_problem* p, int32_t kblock, const void* dA, const void* dB, void* dC,
+                                 const void* d_expected_blk_k, const void* d_T_blk_k,
+                                 const vabft_inject* inj, void* d_rowsum_blk_k, void* d_E_blk_k,
+                                 int32_t* d_blockflags_k, int32_t* d_nblockflag, void* d_E,
+                                 int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog,
+                                 int32_t* d_ninj, void* d_workspace, size_t workspace_bytes,
+                                 void* stream);
 
 /* ---- Offline (post-hoc) verification (section 3.6 "Verification output precision: Offline vs.
  * Online ABFT"): the check is made on a product that already sits in memory in the output type,

@@ -24,7 +24,9 @@ EXPORTS = ("vabft_status_string", "vabft_workspace_bytes", "vabft_workspace_init
            "vabft_locate_correct", "vabft_default_emax_offline", "vabft_check_offline",
            "vabft_encode_a", "vabft_threshold_cols", "vabft_gemm_verified_rc",
            "vabft_block_width", "vabft_encode_blocks", "vabft_threshold_blocks", "vabft_gemm_verified_blocks",
-           "vabft_static_scratch_bytes", "vabft_gemm_verified_fused_static", "vabft_probe_mfma", "vabft_probe_read")
+           "vabft_static_scratch_bytes", "vabft_gemm_verified_fused_static", "vabft_probe_mfma", "vabft_probe_read",
+           "vabft_kblock_count", "vabft_workspace_bytes_blocks_k", "vabft_encode_blocks_k",
+           "vabft_threshold_blocks_k", "vabft_gemm_verified_blocks_k")
 
 
 class Problem(Structure):
@@ -133,6 +135,21 @@ def load(path: str | None = None):
     lib.vabft_threshold_blocks.restype = ctypes.c_int
     lib.vabft_threshold_blocks.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_double, c_double,
                                            c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.vabft_kblock_count.restype = c_int32
+    lib.vabft_kblock_count.argtypes = [POINTER(Problem), c_int32]
+    lib.vabft_workspace_bytes_blocks_k.restype = c_size_t
+    lib.vabft_workspace_bytes_blocks_k.argtypes = [POINTER(Problem), c_int32]
+    lib.vabft_encode_blocks_k.restype = ctypes.c_int
+    lib.vabft_encode_blocks_k.argtypes = [POINTER(Problem), c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
+                                          c_void_p]
+    lib.vabft_threshold_blocks_k.restype = ctypes.c_int
+    lib.vabft_threshold_blocks_k.argtypes = [POINTER(Problem), c_int32, c_void_p, c_void_p, c_void_p, c_double,
+                                             c_double, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.vabft_gemm_verified_blocks_k.restype = ctypes.c_int
+    lib.vabft_gemm_verified_blocks_k.argtypes = [POINTER(Problem), c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                                                 c_void_p, POINTER(Inject), c_void_p, c_void_p, c_void_p, c_void_p,
+                                                 c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
+                                                 c_void_p]
     lib.vabft_gemm_verified_blocks.restype = ctypes.c_int
     lib.vabft_gemm_verified_blocks.argtypes = [POINTER(Problem), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                                POINTER(Inject), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
@@ -306,6 +323,38 @@ def vabft_threshold_blocks(p: Problem, dA, d_Be_blk, d_S_blk, e_max, c_sigma, d_
     rc = load().vabft_threshold_blocks(byref(p), dA, d_Be_blk, d_S_blk, float(e_max), float(c_sigma), d_astat,
                                        d_expected_blk, d_T_blk, stream)
     return _check(rc, "vabft_threshold_blocks", check)
+
+
+def vabft_kblock_count(p: Problem, kblock: int) -> int:
+    return int(load().vabft_kblock_count(byref(p), int(kblock)))
+
+
+def vabft_workspace_bytes_blocks_k(p: Problem, kblock: int) -> int:
+    return int(load().vabft_workspace_bytes_blocks_k(byref(p), int(kblock)))
+
+
+def vabft_encode_blocks_k(p: Problem, kblock, dB, d_Be_blk_k, d_S_blk_k, d_workspace, workspace_bytes, stream=None,
+                          check=True) -> int:
+    rc = load().vabft_encode_blocks_k(byref(p), int(kblock), dB, d_Be_blk_k, d_S_blk_k, d_workspace, workspace_bytes,
+                                      stream)
+    return _check(rc, "vabft_encode_blocks_k", check)
+
+
+def vabft_threshold_blocks_k(p: Problem, kblock, dA, d_Be_blk_k, d_S_blk_k, e_max, c_sigma, d_astat_k,
+                             d_expected_blk_k, d_T_blk_k, stream=None, check=True) -> int:
+    rc = load().vabft_threshold_blocks_k(byref(p), int(kblock), dA, d_Be_blk_k, d_S_blk_k, float(e_max),
+                                         float(c_sigma), d_astat_k, d_expected_blk_k, d_T_blk_k, stream)
+    return _check(rc, "vabft_threshold_blocks_k", check)
+
+
+def vabft_gemm_verified_blocks_k(p: Problem, kblock, dA, dB, dC, d_expected_blk_k, d_T_blk_k, inj, d_rowsum_blk_k,
+                                 d_E_blk_k, d_blockflags_k, d_nblockflag, d_E, d_flags, d_nflag, d_injlog, d_ninj,
+                                 d_workspace, workspace_bytes, stream=None, check=True) -> int:
+    rc = load().vabft_gemm_verified_blocks_k(byref(p), int(kblock), dA, dB, dC, d_expected_blk_k, d_T_blk_k,
+                                             byref(inj) if inj is not None else None, d_rowsum_blk_k, d_E_blk_k,
+                                             d_blockflags_k, d_nblockflag, d_E, d_flags, d_nflag, d_injlog, d_ninj,
+                                             d_workspace, workspace_bytes, stream)
+    return _check(rc, "vabft_gemm_verified_blocks_k", check)
 
 
 def vabft_gemm_verified_blocks(p: Problem, dA, dB, dC, d_expected_blk, d_T_blk, inj, d_rowsum_blk, d_E_blk,

@@ -305,6 +305,8 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
     a.d_ncolflag = cols ? cols->d_ncolflag : nullptr;
     a.block_mode = blocks ? 1 : 0;
     a.d_nblockflag = blocks ? blocks->d_nblockflag : nullptr;
+    a.kprefix = nullptr;
+    a.kblock_tiles = 0;
     a.d_nflag = d_nflag;
     a.expected = d_expected;
     a.T = d_T;
@@ -384,6 +386,13 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
         if (cols || d_rowsum2) return VABFT_EUNSUPPORTED;
         if (mode == 1 && in_kernel_finalize && is16) mode = 5;  // partials only, no in-kernel compare (the wide
                                                                 // kernels read block_mode at run time)
+        if (blocks->kblock > 0) {
+            // K split as well: the 16-bit whole-tile kernel leaves a prefix of the row sums per K-block
+            if ((p->dtype != VABFT_BF16 && p->dtype != VABFT_F16) || edge) return VABFT_EUNSUPPORTED;
+            mode = a.inj.mode != 0 ? 7 : 6;
+            a.kprefix = blocks->kprefix;
+            a.kblock_tiles = blocks->kblock / 64;
+        }
     }
     switch (p->dtype) {
         case VABFT_F8E4M3:
@@ -404,6 +413,10 @@ int gemm_dispatch(const vabft_problem* p, const void* dA, const void* dB, void* 
         default: return VABFT_EINVAL;
     }
     if (rc != VABFT_OK || !verify) return rc;
+    if (blocks && blocks->kblock > 0)
+        return finalize_blocks_k_dispatch(p, (p->K + blocks->kblock - 1) / blocks->kblock, blocks->kprefix,
+                                          blocks->d_expected_blk, blocks->d_T_blk, blocks->d_rowsum_blk, blocks->d_E_blk,
+                                          blocks->d_blockflags, d_E, d_flags, d_nflag, blocks->d_nblockflag, st);
     if (blocks)
         return finalize_blocks_dispatch(p, a.rowpart, blocks->d_expected_blk, blocks->d_T_blk, blocks->d_rowsum_blk,
                                         blocks->d_E_blk, blocks->d_blockflags, d_E, d_flags, d_nflag,
@@ -749,6 +762,107 @@ int vabft_gemm_verified_blocks(const vabft_problem* p, const void* dA, const voi
     b.d_E_blk = d_E_blk;
     b.d_blockflags = d_blockflags;
     b.d_nblockflag = d_nblockflag;
+    return gemm_dispatch(p, dA, dB, dC, nullptr, nullptr, 1, nullptr, inj, nullptr, nullptr, d_E, d_flags, d_nflag,
+                         d_injlog, d_ninj, d_workspace, (hipStream_t)stream, nullptr, &b);
+}
+
+// ---- block-wise verification with K split as well -----------------------------------------------------------
+// The K-blocks of the encode and threshold passes are sub-problems of the column-block passes: K-block b is the
+// problem (M, N, len_b) on A + b*kblock columns and on the K-block's rows (K x N layout) or columns (N x K layout)
+// of B.  They run on a part of the workspace of their own, behind everything the whole problem uses, so that
+// their scratch never lands where the whole problem keeps counters that must stay zero.
+static bool kblock_ok(const vabft_problem* p, int32_t kblock) { return kblock > 0 && kblock % 128 == 0; }
+static int kblock_count(const vabft_problem* p, int32_t kblock) { return (p->K + kblock - 1) / kblock; }
+static vabft_problem kblock_problem(const vabft_problem* p, int32_t kblock, int b) {
+    vabft_problem q = *p;
+    q.K = (b + 1) * kblock <= p->K ? kblock : p->K - b * kblock;
+    return q;
+}
+static size_t kprefix_bytes(const vabft_problem* p, int32_t kblock) {
+    const size_t tiles_n = ((size_t)p->N + 255) / 256;
+    return round_up((size_t)kblock_count(p, kblock) * 2 * tiles_n * (size_t)p->M * sizeof(double), 256);
+}
+// [ workspace of the whole problem | K-block prefixes | workspace of one K-block sub-problem ]
+static size_t kblock_sub_offset(const vabft_problem* p, int32_t kblock) {
+    return round_up(vabft_workspace_bytes(p), 256) + kprefix_bytes(p, kblock);
+}
+
+int32_t vabft_kblock_count(const vabft_problem* p, int32_t kblock) {
+    return (problem_ok(p) && kblock_ok(p, kblock)) ? kblock_count(p, kblock) : 0;
+}
+
+size_t vabft_workspace_bytes_blocks_k(const vabft_problem* p, int32_t kblock) {
+    if (!problem_ok(p) || !kblock_ok(p, kblock)) return 0;
+    const vabft_problem q = kblock_problem(p, kblock, 0);  // the largest K-block
+    return kblock_sub_offset(p, kblock) + vabft_workspace_bytes(&q);
+}
+
+int vabft_encode_blocks_k(const vabft_problem* p, int32_t kblock, const void* dB, void* d_Be_blk_k, double* d_S_blk_k,
+                          void* d_workspace, size_t workspace_bytes, void* stream) {
+    if (!problem_ok(p) || !kblock_ok(p, kblock) || !dB || !d_Be_blk_k || !d_S_blk_k) return VABFT_EINVAL;
+    if (!d_workspace || workspace_bytes < vabft_workspace_bytes_blocks_k(p, kblock) || !aligned_to(d_workspace, 16))
+        return VABFT_EWORKSPACE;
+    const size_t eb = elem_bytes(p->dtype), ab = acc_bytes(p->dtype);
+    const int W = block_width(p->dtype), nblocks = (p->N + W - 1) / W, nkb = kblock_count(p, kblock);
+    unsigned char* sub = reinterpret_cast<unsigned char*>(d_workspace) + kblock_sub_offset(p, kblock);
+    for (int b = 0; b < nkb; ++b) {
+        const vabft_problem q = kblock_problem(p, kblock, b);
+        const size_t k0 = (size_t)b * kblock;
+        const unsigned char* Bb = reinterpret_cast<const unsigned char*>(dB) + (p->transB ? k0 : k0 * (size_t)p->ldb) * eb;
+        void* be = reinterpret_cast<unsigned char*>(d_Be_blk_k) + (size_t)nblocks * k0 * ab;
+        const int rc = vabft_encode_blocks(&q, Bb, be, d_S_blk_k + (size_t)b * nblocks * 3, sub,
+                                           workspace_bytes - kblock_sub_offset(p, kblock), stream);
+        if (rc != VABFT_OK) return rc;
+    }
+    return VABFT_OK;
+}
+
+int vabft_threshold_blocks_k(const vabft_problem* p, int32_t kblock, const void* dA, const void* d_Be_blk_k,
+                             const double* d_S_blk_k, double e_max, double c_sigma, void* d_astat_k,
+                             void* d_expected_blk_k, void* d_T_blk_k, void* stream) {
+    if (!problem_ok(p) || !kblock_ok(p, kblock) || !dA || !d_Be_blk_k || !d_S_blk_k || !d_astat_k || !d_expected_blk_k ||
+        !d_T_blk_k)
+        return VABFT_EINVAL;
+    const size_t eb = elem_bytes(p->dtype), ab = acc_bytes(p->dtype);
+    const int W = block_width(p->dtype), nblocks = (p->N + W - 1) / W, nkb = kblock_count(p, kblock);
+    for (int b = 0; b < nkb; ++b) {
+        const vabft_problem q = kblock_problem(p, kblock, b);
+        const size_t k0 = (size_t)b * kblock;
+        const unsigned char* Ab = reinterpret_cast<const unsigned char*>(dA) + k0 * eb;
+        const void* be = reinterpret_cast<const unsigned char*>(d_Be_blk_k) + (size_t)nblocks * k0 * ab;
+        const size_t piece = (size_t)b * nblocks * (size_t)p->M * ab;
+        const int rc = vabft_threshold_blocks(&q, Ab, be, d_S_blk_k + (size_t)b * nblocks * 3, e_max, c_sigma,
+                                              reinterpret_cast<unsigned char*>(d_astat_k) + (size_t)b * 3 * p->M * ab,
+                                              reinterpret_cast<unsigned char*>(d_expected_blk_k) + piece,
+                                              reinterpret_cast<unsigned char*>(d_T_blk_k) + piece, stream);
+        if (rc != VABFT_OK) return rc;
+    }
+    return VABFT_OK;
+}
+
+int vabft_gemm_verified_blocks_k(const vabft_problem* p, int32_t kblock, const void* dA, const void* dB, void* dC,
+                                 const void* d_expected_blk_k, const void* d_T_blk_k, const vabft_inject* inj,
+                                 void* d_rowsum_blk_k, void* d_E_blk_k, int32_t* d_blockflags_k, int32_t* d_nblockflag,
+                                 void* d_E, int32_t* d_flags, int32_t* d_nflag, vabft_inject_rec* d_injlog,
+                                 int32_t* d_ninj, void* d_workspace, size_t workspace_bytes, void* stream) {
+    if (!problem_ok(p) || !kblock_ok(p, kblock)) return VABFT_EINVAL;
+    const int rc = check_gemm_args(p, dA, dB, dC, 1, inj, d_expected_blk_k, d_T_blk_k, d_rowsum_blk_k, d_E, d_flags,
+                                   d_nflag, d_injlog, d_ninj, d_workspace, workspace_bytes);
+    if (rc != VABFT_OK) return rc;
+    if (workspace_bytes < vabft_workspace_bytes_blocks_k(p, kblock)) return VABFT_EWORKSPACE;
+    if (!d_E_blk_k || !d_blockflags_k || !d_nblockflag) return VABFT_EINVAL;
+    if (!aligned_to(d_E_blk_k, acc_bytes(p->dtype)) || !aligned_to(d_blockflags_k, 4) || !aligned_to(d_nblockflag, 4))
+        return VABFT_EINVAL;
+    BlockArgs b;
+    b.d_expected_blk = d_expected_blk_k;
+    b.d_T_blk = d_T_blk_k;
+    b.d_rowsum_blk = d_rowsum_blk_k;
+    b.d_E_blk = d_E_blk_k;
+    b.d_blockflags = d_blockflags_k;
+    b.d_nblockflag = d_nblockflag;
+    b.kblock = kblock;
+    b.kprefix = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(d_workspace) +
+                                          round_up(vabft_workspace_bytes(p), 256));
     return gemm_dispatch(p, dA, dB, dC, nullptr, nullptr, 1, nullptr, inj, nullptr, nullptr, d_E, d_flags, d_nflag,
                          d_injlog, d_ninj, d_workspace, (hipStream_t)stream, nullptr, &b);
 }

@@ -520,6 +520,58 @@ __global__ __launch_bounds__(64) void finalize_blocks_kernel(const acc_t* __rest
 }
 
 // ---------------------------------------------------------------------------
+// K split as well (section 5.2): kprefix[b][2 t + w][i] is the row sum, in double, of what wavefront column w of
+// tile-column t had accumulated when K-block b ended (b = last: the whole product).  The share of K-block b is
+// the difference of consecutive prefixes; it is compared with the piece's own expected value and threshold.
+// One thread per row, column blocks and K-blocks in order.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void finalize_blocks_k_kernel(const double* __restrict__ kprefix, int nkb,
+                                                               int nblocks, int M,
+                                                               const float* __restrict__ expected_blk,
+                                                               const float* __restrict__ T_blk,
+                                                               float* __restrict__ rowsum_blk,
+                                                               float* __restrict__ E_blk,
+                                                               int32_t* __restrict__ blockflags, float* __restrict__ E,
+                                                               int32_t* __restrict__ flags, int32_t* __restrict__ nflag,
+                                                               int32_t* __restrict__ nblockflag) {
+    const int i = blockIdx.x * 64 + threadIdx.x;
+    int any = 0, nb = 0;
+    if (i < M) {
+        double esum = 0;
+        for (int t = 0; t < nblocks; ++t) {
+            double prev = 0;
+            for (int b = 0; b < nkb; ++b) {
+                const double* q = kprefix + ((int64_t)b * (2 * nblocks) + 2 * t) * M + i;
+                const double cur = q[0] + q[M];
+                const int64_t idx = ((int64_t)b * nblocks + t) * M + i;
+                const double share = cur - prev;
+                prev = cur;
+                const double e = (double)expected_blk[idx] - share;
+                const int f = !(fabs(e) <= (double)T_blk[idx]);
+                rowsum_blk[idx] = (float)share;
+                E_blk[idx] = (float)e;
+                blockflags[idx] = f;
+                esum += e;
+                nb += f;
+            }
+        }
+        any = nb > 0;
+        E[i] = (float)esum;
+        flags[i] = any;
+    }
+    int cnt = any, w = nb;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        cnt += __shfl_xor(cnt, off, WAVE);
+        w += __shfl_xor(w, off, WAVE);
+    }
+    if (threadIdx.x == 0) {
+        if (cnt) atomicAdd(nflag, cnt);
+        if (w) atomicAdd(nblockflag, w);
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 int block_width(int dtype) { return (dtype == VABFT_F64 || dtype == VABFT_F32) ? 64 : 256; }
@@ -611,6 +663,18 @@ int finalize_blocks_dispatch(const vabft_problem* p, const void* rowpart, const 
         finalize_blocks_kernel<float><<<grid, block, 0, st>>>(
             (const float*)rowpart, nblocks, p->M, (const float*)d_expected_blk, (const float*)d_T_blk,
             (float*)d_rowsum_blk, (float*)d_E_blk, d_blockflags, (float*)d_E, d_flags, d_nflag, d_nblockflag);
+    return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
+}
+
+// FP32-accumulated 16-bit types only (the kernels that leave K-block prefixes)
+int finalize_blocks_k_dispatch(const vabft_problem* p, int nkb, const double* kprefix, const void* d_expected_blk,
+                               const void* d_T_blk, void* d_rowsum_blk, void* d_E_blk, int32_t* d_blockflags,
+                               void* d_E, int32_t* d_flags, int32_t* d_nflag, int32_t* d_nblockflag, hipStream_t st) {
+    const int W = block_width(p->dtype), nblocks = (p->N + W - 1) / W;
+    // d_nflag and d_nblockflag were zeroed by the GEMM kernel that produced the prefixes
+    finalize_blocks_k_kernel<<<dim3((p->M + 63) / 64), dim3(64), 0, st>>>(
+        kprefix, nkb, nblocks, p->M, (const float*)d_expected_blk, (const float*)d_T_blk, (float*)d_rowsum_blk,
+        (float*)d_E_blk, d_blockflags, (float*)d_E, d_flags, d_nflag, d_nblockflag);
     return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;
 }
 

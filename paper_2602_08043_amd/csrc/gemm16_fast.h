@@ -404,10 +404,26 @@ template <typename T> __device__ __forceinline__ uint16_t one16();
 template <> __device__ __forceinline__ uint16_t one16<bf16_t>() { return 0x3f80; }
 template <> __device__ __forceinline__ uint16_t one16<f16_t>() { return 0x3c00; }
 
+// The assembly MFMAs are opaque to the compiler's hazard handling: before vector code reads the accumulators, idle
+// slots let the last results land.  The empty statements behind them redefine every accumulator as far as the
+// compiler can tell, so no read of one can be scheduled in front of the idle slots (register reads are not
+// ordered against an assembly statement by its memory clobber).
+__device__ __forceinline__ void settle_accumulators(f32x4_t (&acc)[8][8]) {
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+#pragma unroll
+    for (int mi = 0; mi < 8; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 8; ++ni) asm volatile("" : "+a"(acc[mi][ni]));
+}
+
 template <typename T, int TRANSB, int MODE, bool FUSED>
 __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     using namespace g16x;
-    constexpr bool VERIFY = MODE >= 1, INJECT = MODE == 2, WSUM = MODE == 2 || MODE == 3;
+    // MODE 6 / 7: block-wise check with K split as well (7: with the injector).  The kernel leaves the row sums of
+    // the accumulator tile at every K-block boundary and at the end, in double; a kernel of its own forms the
+    // K-block shares as differences of consecutive prefixes and compares them.
+    constexpr bool KSNAP = MODE == 6 || MODE == 7;
+    constexpr bool VERIFY = MODE >= 1 && !KSNAP, INJECT = MODE == 2 || MODE == 7, WSUM = MODE == 2 || MODE == 3;
     constexpr bool CSUM = MODE == 2 || MODE == 4;
     static_assert(!FUSED || VERIFY, "fused statistics belong to the verified kernel");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -420,7 +436,7 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     int bm, bn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
     if (CSUM && blockIdx.x == 0 && tid == 0 && g.d_ncolflag) *g.d_ncolflag = 0;
-    if ((MODE == 5 || MODE == 2) && blockIdx.x == 0 && tid == 0 && g.block_mode) {
+    if ((MODE == 5 || MODE == 2 || KSNAP) && blockIdx.x == 0 && tid == 0 && (g.block_mode || KSNAP)) {
         *g.d_nflag = 0;
         *g.d_nblockflag = 0;
     }
@@ -650,6 +666,40 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     for (int i = 0; i < 8; ++i) af1[i] = bf1[i] = raw16{{0u, 0u, 0u, 0u}};
     asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");  // vector code wrote these operands: see Mfma16x
 
+    // KSNAP: prefix row sums of the accumulator tile (section 5.2, K split as well).  Lane l owns C row l % 16 of
+    // each of its 8 row fragments and 4 columns of each of the 8 column fragments: 32 values per row fragment,
+    // widened to double and added as a tree, then across the four lanes that share the row.  The two wavefronts of
+    // a tile-column (wn = 0, 1) leave one partial each.  The assembly MFMAs are opaque to the compiler's hazard
+    // handling, so idle slots let their results land first; outstanding LDS reads land before compiler-generated
+    // code runs between two k-steps.
+    int ksnap_idx = 0;
+    auto snapshot = [&](int idx) __attribute__((always_inline)) {
+        wait_lgkmcnt0();
+        settle_accumulators(acc);
+        // (opaque to the optimiser, so that none of the address arithmetic below is hoisted out of this block and
+        // kept in registers across the main loop)
+        idx = __builtin_amdgcn_readfirstlane(idx);
+        asm volatile("" : "+s"(idx));
+        double tot[8];
+#pragma unroll
+        for (int mi = 0; mi < 8; ++mi) {
+            double q[8];
+#pragma unroll
+            for (int ni = 0; ni < 8; ++ni)
+                q[ni] = ((double)acc[mi][ni][0] + (double)acc[mi][ni][1]) + ((double)acc[mi][ni][2] + (double)acc[mi][ni][3]);
+            double s = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
+            s += __shfl_xor(s, 16, 64);
+            s += __shfl_xor(s, 32, 64);
+            tot[mi] = s;
+            asm volatile("" : "+v"(tot[mi]));  // one row fragment at a time: keeps the live set small
+        }
+        if (lq == 0) {
+            double* dst = g.kprefix + ((int64_t)idx * (2 * g.tiles_n) + 2 * bn + wn) * g.M + row0 + wm * 128 + l16;
+#pragma unroll
+            for (int mi = 0; mi < 8; ++mi) dst[mi * 16] = tot[mi];
+        }
+    };
+
     // Body of k-tile kt (stage kt & 1), from barrier to barrier: step (kt-1, 1) multiplies register set 1 while
     // the fragments of (kt, 0) arrive in set 0, then step (kt, 0) multiplies set 0 while (kt, 1) arrives in set
     // 1.  The 16 loads of tile kt+1 (clamped at the last tile; the reload is harmless) go to the other stage,
@@ -693,6 +743,34 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         for (int mi = 0; mi < 8; ++mi)
 #pragma unroll
             for (int ni = 0; ni < 8; ++ni) Mfma16x<T>::acc_a(acc[mi][ni], bf1[ni], af1[mi]);
+    } else if constexpr (KSNAP) {
+        // One loop nest per K-block: the plain loop over the block's k-tiles, then the fragment pipeline is drained
+        // (the pending second step of the block's last tile is multiplied), the prefix is taken with no fragment
+        // live, and the pipeline restarts on zeros like at the kernel's start (one idle step per K-block).  The
+        // global -> LDS prefetch runs through: the next block's first tile is already on its way.
+        int kt = 0;
+        for (;;) {
+            const int kt_end = kt + g.kblock_tiles < nk ? kt + g.kblock_tiles : nk;  // kblock_tiles is even
+            for (; kt + 1 < kt_end; kt += 2) {
+                tile_body(I0{}, I0{}, kt, 0);
+                tile_body(I1{}, I0{}, kt + 1, 0);
+            }
+            if (kt < kt_end) {  // an odd tile count only in the last K-block
+                tile_body(I0{}, I0{}, kt, 0);
+                ++kt;
+            }
+            if (!TRANSB) wait_lgkmcnt0();
+#pragma unroll
+            for (int mi = 0; mi < 8; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 8; ++ni) Mfma16x<T>::acc_a(acc[mi][ni], bf1[ni], af1[mi]);
+            if (kt >= nk) break;  // the last prefix is taken in the epilogue, behind the injector
+            snapshot(ksnap_idx);
+            ++ksnap_idx;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) af1[i] = bf1[i] = raw16{{0u, 0u, 0u, 0u}};
+            asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");  // vector code wrote these operands: see Mfma16x
+        }
     } else {
         int kt = 0;
         for (; kt + 1 < nk; kt += 2) {
@@ -706,11 +784,11 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
 #pragma unroll
             for (int ni = 0; ni < 8; ++ni) Mfma16x<T>::acc_a(acc[mi][ni], bf1[ni], af1[mi]);
     }
-    // the MFMAs are opaque to the compiler's hazard handling: let the last results land before anything reads them
-    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+    settle_accumulators(acc);
 
     // ---- epilogue -------------------------------------------------------------------------------------------
     gemm16x_inject<INJECT>(g, acc, row0, col0, wm, wn, l16, lq);
+    if constexpr (KSNAP) snapshot(ksnap_idx);  // the last K-block's prefix is the whole row sum
     if (VERIFY) {
         float* red = reinterpret_cast<float*>(smem);                 // [2 wn][256 rows]
         float* sred = reinterpret_cast<float*>(smem + SRED_OFFSET);  // [4][256 rows]
@@ -792,6 +870,8 @@ static int gemm16_fast_launch_tb(const GemmArgs& a, int mode, hipStream_t st) {
     VABFT_G16F_CASE(3, 0)
     VABFT_G16F_CASE(4, 0)
     VABFT_G16F_CASE(5, 0)
+    VABFT_G16F_CASE(6, 0)
+    VABFT_G16F_CASE(7, 0)
     VABFT_G16F_CASE(1, 1)
     VABFT_G16F_CASE(2, 1)
 #undef VABFT_G16F_CASE

@@ -37,6 +37,9 @@ int threshold_blocks_dispatch(const vabft_problem* p, const void* dA, const void
 int finalize_blocks_dispatch(const vabft_problem* p, const void* rowpart, const void* d_expected_blk,
                              const void* d_T_blk, void* d_rowsum_blk, void* d_E_blk, int32_t* d_blockflags, void* d_E,
                              int32_t* d_flags, int32_t* d_nflag, int32_t* d_nblockflag, hipStream_t st);
+int finalize_blocks_k_dispatch(const vabft_problem* p, int nkb, const double* kprefix, const void* d_expected_blk,
+                               const void* d_T_blk, void* d_rowsum_blk, void* d_E_blk, int32_t* d_blockflags,
+                               void* d_E, int32_t* d_flags, int32_t* d_nflag, int32_t* d_nblockflag, hipStream_t st);
 int check_offline_dispatch(const vabft_problem* p, const void* dC, const void* d_expected, const void* d_T,
                            void* d_rowsum, void* d_E, int32_t* d_flags, int32_t* d_nflag, hipStream_t st);
 
@@ -91,6 +94,10 @@ struct GemmArgs {
     // block-wise check: the kernels only leave their partial row sums; a kernel of its own compares per block
     int32_t block_mode;
     int32_t* d_nblockflag;  // block mode: zeroed (with d_nflag) by the GEMM kernel for the compare that follows
+    // block-wise check with K split as well (kernel modes 6 and 7 of the 16-bit whole-tile kernel): the row sums of
+    // the accumulator tile taken every kblock_tiles k-tiles, in double
+    double* kprefix;        // [K-blocks][2 * tiles_n][M]: prefix row sums (one per wavefront column of a tile-column)
+    int32_t kblock_tiles;   // k-tiles (of 64) per K-block; even
 };
 
 size_t gemm_workspace_bytes(const vabft_problem* p);
@@ -109,6 +116,9 @@ struct BlockArgs {
     void* d_E_blk;               // [nblocks][M] acc
     int32_t* d_blockflags;       // [nblocks][M]
     int32_t* d_nblockflag;       // [1]
+    // K split as well: kblock > 0, every array above is [K-blocks][nblocks][M], kprefix as in GemmArgs
+    int32_t kblock = 0;
+    double* kprefix = nullptr;
 };
 struct ColArgs {
     const void* d_expected_col;  // [N] acc

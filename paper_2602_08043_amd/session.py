@@ -290,3 +290,78 @@ class VerifiedGemm:
         out["nflag"] = int(self.nflag.item())
         out["C"] = to_host(self.C, self.out_dtype)
         return out
+
+
+class KBlockedGemm:
+    """Buffers and thin wrappers of the block-wise route with K split as well (vabft_*_blocks_k): device memory and
+    the stream handle only, like VerifiedGemm."""
+
+    def __init__(self, M, N, K, dtype: str, transB=0, kblock=1024, device="cuda:0", log_capacity=256):
+        vb.load()
+        self.M, self.N, self.K, self.dtype, self.transB, self.kblock = M, N, K, dtype, int(transB), int(kblock)
+        self.device = dev = torch.device(device)
+        self.problem = vb.make_problem(M, N, K, dtype, transB)
+        acc = torch.float64 if dtype == "f64" else torch.float32
+        self.W = vb.vabft_block_width(dtype)
+        self.nblocks = nb = (N + self.W - 1) // self.W
+        self.nkb = nkb = vb.vabft_kblock_count(self.problem, kblock)
+        self.out_dtype = _OUT_DTYPE.get(dtype, dtype)
+        self.C = torch.empty((M, N), dtype=_TORCH_DTYPE[self.out_dtype], device=dev)
+        self.Be_blk_k = torch.empty(nb * K, dtype=acc, device=dev)  # piece b: [nb][len_b] at offset b * nb * kblock
+        self.S_blk_k = torch.empty((nkb, nb, 3), dtype=torch.float64, device=dev)
+        self.astat_k = torch.empty((nkb, M, 3), dtype=acc, device=dev)
+        self.expected_blk_k = torch.empty((nkb, nb, M), dtype=acc, device=dev)
+        self.T_blk_k = torch.empty((nkb, nb, M), dtype=acc, device=dev)
+        self.rowsum_blk_k = torch.empty((nkb, nb, M), dtype=acc, device=dev)
+        self.E_blk_k = torch.empty((nkb, nb, M), dtype=acc, device=dev)
+        self.blockflags_k = torch.empty((nkb, nb, M), dtype=torch.int32, device=dev)
+        self.nblockflag = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.E = torch.empty(M, dtype=acc, device=dev)
+        self.flags = torch.empty(M, dtype=torch.int32, device=dev)
+        self.nflag = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.ninj = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.log_capacity = int(log_capacity)
+        self.injlog = torch.zeros(max(1, self.log_capacity) * _REC_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+        self.ws_bytes = vb.vabft_workspace_bytes_blocks_k(self.problem, kblock)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
+        vb.vabft_workspace_init(self.ws.data_ptr(), self.ws_bytes, self._stream())
+        self._list = None
+
+    _stream = staticmethod(VerifiedGemm._stream)
+    make_inject = VerifiedGemm.make_inject
+    inject_records = VerifiedGemm.inject_records
+
+    def encode(self, B: torch.Tensor):
+        return vb.vabft_encode_blocks_k(self.problem, self.kblock, B.data_ptr(), self.Be_blk_k.data_ptr(),
+                                        self.S_blk_k.data_ptr(), self.ws.data_ptr(), self.ws_bytes, self._stream())
+
+    def threshold(self, A: torch.Tensor, e_max=None, c_sigma=2.5):
+        if e_max is None:
+            e_max = vb.vabft_default_emax(self.dtype, min(self.K, self.kblock), min(self.N, self.W))
+        return vb.vabft_threshold_blocks_k(self.problem, self.kblock, A.data_ptr(), self.Be_blk_k.data_ptr(),
+                                           self.S_blk_k.data_ptr(), e_max, c_sigma, self.astat_k.data_ptr(),
+                                           self.expected_blk_k.data_ptr(), self.T_blk_k.data_ptr(), self._stream())
+
+    def gemm(self, A: torch.Tensor, B: torch.Tensor, inj: vb.Inject | None = None):
+        return vb.vabft_gemm_verified_blocks_k(self.problem, self.kblock, A.data_ptr(), B.data_ptr(), self.C.data_ptr(),
+                                               self.expected_blk_k.data_ptr(), self.T_blk_k.data_ptr(), inj,
+                                               self.rowsum_blk_k.data_ptr(), self.E_blk_k.data_ptr(),
+                                               self.blockflags_k.data_ptr(), self.nblockflag.data_ptr(),
+                                               self.E.data_ptr(), self.flags.data_ptr(), self.nflag.data_ptr(),
+                                               self.injlog.data_ptr(), self.ninj.data_ptr(), self.ws.data_ptr(),
+                                               self.ws_bytes, self._stream())
+
+    def run(self, A, B, e_max=None, c_sigma=2.5, inj=None):
+        self.encode(B)
+        self.threshold(A, e_max, c_sigma)
+        self.gemm(A, B, inj)
+
+    def results(self):
+        torch.cuda.synchronize(self.device)
+        out = {k: getattr(self, k).cpu().numpy() for k in
+               ("Be_blk_k", "S_blk_k", "astat_k", "expected_blk_k", "T_blk_k", "rowsum_blk_k", "E_blk_k", "blockflags_k",
+                "E", "flags")}
+        out["C"] = to_host(self.C, self.out_dtype)
+        out["nflag"] = int(self.nflag.item())
+        out["nblockflag"] = int(self.nblockflag.item())
+        return out
