@@ -337,7 +337,9 @@ int vabft_gemm_verified_blocks(const vabft_problem* p, const void* dA, const voi
  * [b*kblock, min(K, (b+1)*kblock)), nkb = ceil(K / kblock) = vabft_kblock_count; kblock is a positive multiple of
  * 128.  Piece (b, t) is the product of the K-block of A (all rows) with the (K-block, column block) piece of B,
  * verified on its own: its checksum column, its expected row sums, the row sums of the partial product, and
- * Algorithm 1 with the statistics of the K-block of A's rows and of the piece of B's rows.  A row's aggregate
+ * Algorithm 1 with the statistics of the K-block of A's rows and of the piece of B's rows, with (b + 1) * e_max
+ * for K-block b (its share is gained on a running accumulator that already holds b blocks, so its rounding error
+ * goes with a sum (b + 1) blocks deep).  A row's aggregate
  * difference is the sum of its piece differences and its flag the OR of its piece flags.
  * Arrays are [nkb][nblocks][len] unless stated.  The workspace for these calls is
  * vabft_workspace_bytes_blocks_k bytes (it holds the workspace of the whole problem in front, so the other entry

@@ -566,7 +566,12 @@ def verify_blocks_k(A_st, B_st, dtype: str, transB: int, W: int, KB: int, e_max:
     on its own: its checksum column Be_{b,t} = B_{b,t} r1, expected_{b,t} = A_b Be_{b,t}, the row sums of the partial
     product A_b B_{b,t}, and Algorithm 1 with the statistics of A_b's rows and B_{b,t}'s rows and the block's width
     in place of N.  The aggregate of a row is the sum of its block differences (again the full-row difference)
-    and the OR of its block flags.  Arrays are indexed [K-block][column block][...]."""
+    and the OR of its block flags.  Arrays are indexed [K-block][column block][...].
+
+    Reading (the section does not say how a K-block's partial product is obtained): on hardware that keeps one
+    running accumulator over the whole K range, block b's share is what the accumulator gained while it already
+    held b blocks, so its rounding error goes with a sum (b + 1) blocks deep; e_max, which the paper calibrates
+    per accumulation depth, is taken (b + 1)-fold for K-block b."""
     A = decode(A_st, dtype)
     B = logical_B(B_st, dtype, transB)
     M, K = A.shape
@@ -595,7 +600,7 @@ def verify_blocks_k(A_st, B_st, dtype: str, transB: int, W: int, KB: int, e_max:
             sc.append(np.abs(Bbt).sum(axis=1))
             out["S_blk"][b, t] = b_aggregates(Bbt)
             out["expected_blk"][b, t] = expected_checksum(Ab, bet)
-            out["T_blk"][b, t] = threshold(Ab, Bbt, e_max, c_sigma)
+            out["T_blk"][b, t] = threshold(Ab, Bbt, e_max * (b + 1), c_sigma)
             out["scale_expected_blk"][b, t] = np.abs(Ab) @ np.abs(bet)
             out["scale_rowsum_blk"][b, t] = np.abs(Ab) @ sc[-1]
             if full_gemm:

@@ -831,7 +831,10 @@ int vabft_threshold_blocks_k(const vabft_problem* p, int32_t kblock, const void*
         const unsigned char* Ab = reinterpret_cast<const unsigned char*>(dA) + k0 * eb;
         const void* be = reinterpret_cast<const unsigned char*>(d_Be_blk_k) + (size_t)nblocks * k0 * ab;
         const size_t piece = (size_t)b * nblocks * (size_t)p->M * ab;
-        const int rc = vabft_threshold_blocks(&q, Ab, be, d_S_blk_k + (size_t)b * nblocks * 3, e_max, c_sigma,
+        // K-block b's share is what the running accumulator gained while it already held b blocks: the rounding of
+        // that accumulation goes with the running magnitude, (b + 1) blocks deep, not with the block's own terms.
+        // e_max, the relative rounding error per unit of checksum magnitude, is therefore taken (b + 1)-fold.
+        const int rc = vabft_threshold_blocks(&q, Ab, be, d_S_blk_k + (size_t)b * nblocks * 3, e_max * (b + 1), c_sigma,
                                               reinterpret_cast<unsigned char*>(d_astat_k) + (size_t)b * 3 * p->M * ab,
                                               reinterpret_cast<unsigned char*>(d_expected_blk_k) + piece,
                                               reinterpret_cast<unsigned char*>(d_T_blk_k) + piece, stream);

@@ -523,51 +523,91 @@ __global__ __launch_bounds__(64) void finalize_blocks_kernel(const acc_t* __rest
 // K split as well (section 5.2): kprefix[b][2 t + w][i] is the row sum, in double, of what wavefront column w of
 // tile-column t had accumulated when K-block b ended (b = last: the whole product).  The share of K-block b is
 // the difference of consecutive prefixes; it is compared with the piece's own expected value and threshold.
-// One thread per row, column blocks and K-blocks in order.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void finalize_blocks_k_kernel(const double* __restrict__ kprefix, int nkb,
-                                                               int nblocks, int M,
-                                                               const float* __restrict__ expected_blk,
-                                                               const float* __restrict__ T_blk,
-                                                               float* __restrict__ rowsum_blk,
-                                                               float* __restrict__ E_blk,
-                                                               int32_t* __restrict__ blockflags, float* __restrict__ E,
-                                                               int32_t* __restrict__ flags, int32_t* __restrict__ nflag,
-                                                               int32_t* __restrict__ nblockflag) {
-    const int i = blockIdx.x * 64 + threadIdx.x;
-    int any = 0, nb = 0;
+__global__ __launch_bounds__(256) void finalize_blocks_k_kernel(const double* __restrict__ kprefix, int nkb,
+                                                                int nblocks, int M,
+                                                                const float* __restrict__ expected_blk,
+                                                                const float* __restrict__ T_blk,
+                                                                float* __restrict__ rowsum_blk,
+                                                                float* __restrict__ E_blk,
+                                                                int32_t* __restrict__ blockflags, float* __restrict__ E,
+                                                                int32_t* __restrict__ flags, int32_t* __restrict__ nflag,
+                                                                int32_t* __restrict__ nblockflag) {
+    // 32 rows per workgroup, eight threads per row: thread (r, tl) takes the column blocks t = tl, tl + 8, ...; the
+    // eight partial aggregates of a row are added in the order of tl (a fixed order: results repeat bit for bit)
+    __shared__ double s_e[8][32];
+    __shared__ int s_n[8][32];
+    const int r = threadIdx.x & 31, tl = threadIdx.x >> 5;
+    const int i = blockIdx.x * 32 + r;
+    double esum = 0;
+    int nb = 0;
     if (i < M) {
-        double esum = 0;
-        for (int t = 0; t < nblocks; ++t) {
+        for (int t = tl; t < nblocks; t += 8) {
             double prev = 0;
-            for (int b = 0; b < nkb; ++b) {
-                const double* q = kprefix + ((int64_t)b * (2 * nblocks) + 2 * t) * M + i;
-                const double cur = q[0] + q[M];
-                const int64_t idx = ((int64_t)b * nblocks + t) * M + i;
-                const double share = cur - prev;
-                prev = cur;
-                const double e = (double)expected_blk[idx] - share;
-                const int f = !(fabs(e) <= (double)T_blk[idx]);
-                rowsum_blk[idx] = (float)share;
-                E_blk[idx] = (float)e;
-                blockflags[idx] = f;
-                esum += e;
-                nb += f;
+            // the loads of eight K-blocks in flight at once (the pass is a few dependent round trips long)
+            for (int b0 = 0; b0 < nkb; b0 += 8) {
+                double c0[8], c1[8];
+                float x[8], thr[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int b = b0 + u < nkb ? b0 + u : nkb - 1;
+                    const double* q = kprefix + ((int64_t)b * (2 * nblocks) + 2 * t) * M + i;
+                    const int64_t idx = ((int64_t)b * nblocks + t) * M + i;
+                    c0[u] = q[0];
+                    c1[u] = q[M];
+                    x[u] = expected_blk[idx];
+                    thr[u] = T_blk[idx];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (b0 + u < nkb) {
+                        const int64_t idx = ((int64_t)(b0 + u) * nblocks + t) * M + i;
+                        const double cur = c0[u] + c1[u];
+                        const double share = cur - prev;
+                        prev = cur;
+                        const double e = (double)x[u] - share;
+                        const int f = !(fabs(e) <= (double)thr[u]);
+                        rowsum_blk[idx] = (float)share;
+                        E_blk[idx] = (float)e;
+                        blockflags[idx] = f;
+                        esum += e;
+                        nb += f;
+                    }
+                }
             }
         }
-        any = nb > 0;
-        E[i] = (float)esum;
-        flags[i] = any;
     }
-    int cnt = any, w = nb;
+    s_e[tl][r] = esum;
+    s_n[tl][r] = nb;
+    __syncthreads();
+    int any = 0, w = 0;
+    if (tl == 0) {
+        double e = 0;
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        cnt += __shfl_xor(cnt, off, WAVE);
-        w += __shfl_xor(w, off, WAVE);
+        for (int q = 0; q < 8; ++q) {
+            e += s_e[q][r];
+            w += s_n[q][r];
+        }
+        if (i < M) {
+            any = w > 0;
+            E[i] = (float)e;
+            flags[i] = any;
+        } else {
+            w = 0;
+        }
     }
-    if (threadIdx.x == 0) {
-        if (cnt) atomicAdd(nflag, cnt);
-        if (w) atomicAdd(nblockflag, w);
+    // the counts sit in the threads with tl == 0, the first half of the first wavefront
+    if (threadIdx.x < 64) {
+        int cnt = any;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            cnt += __shfl_xor(cnt, off, WAVE);
+            w += __shfl_xor(w, off, WAVE);
+        }
+        if (threadIdx.x == 0) {
+            if (cnt) atomicAdd(nflag, cnt);
+            if (w) atomicAdd(nblockflag, w);
+        }
     }
 }
 
@@ -672,7 +712,7 @@ int finalize_blocks_k_dispatch(const vabft_problem* p, int nkb, const double* kp
                                void* d_E, int32_t* d_flags, int32_t* d_nflag, int32_t* d_nblockflag, hipStream_t st) {
     const int W = block_width(p->dtype), nblocks = (p->N + W - 1) / W;
     // d_nflag and d_nblockflag were zeroed by the GEMM kernel that produced the prefixes
-    finalize_blocks_k_kernel<<<dim3((p->M + 63) / 64), dim3(64), 0, st>>>(
+    finalize_blocks_k_kernel<<<dim3((p->M + 31) / 32), dim3(256), 0, st>>>(
         kprefix, nkb, nblocks, p->M, (const float*)d_expected_blk, (const float*)d_T_blk, (float*)d_rowsum_blk,
         (float*)d_E_blk, d_blockflags, (float*)d_E, d_flags, d_nflag, d_nblockflag);
     return hipGetLastError() == hipSuccess ? VABFT_OK : VABFT_EDEVICE;

@@ -668,7 +668,7 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
 
     // KSNAP: prefix row sums of the accumulator tile (section 5.2, K split as well).  Lane l owns C row l % 16 of
     // each of its 8 row fragments and 4 columns of each of the 8 column fragments: 32 values per row fragment,
-    // widened to double and added as a tree, then across the four lanes that share the row.  The two wavefronts of
+    // added as a tree, then across the four lanes that share the row.  The two wavefronts of
     // a tile-column (wn = 0, 1) leave one partial each.  The assembly MFMAs are opaque to the compiler's hazard
     // handling, so idle slots let their results land first; outstanding LDS reads land before compiler-generated
     // code runs between two k-steps.
@@ -683,11 +683,12 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         double tot[8];
 #pragma unroll
         for (int mi = 0; mi < 8; ++mi) {
-            double q[8];
+            // the lane's 32 values as a tree in FP32 (five roundings deep), then double across fragments' halves and
+            // lanes: the prefixes of consecutive K-blocks are subtracted, so what is kept between kernels is double
+            float q[8];
 #pragma unroll
-            for (int ni = 0; ni < 8; ++ni)
-                q[ni] = ((double)acc[mi][ni][0] + (double)acc[mi][ni][1]) + ((double)acc[mi][ni][2] + (double)acc[mi][ni][3]);
-            double s = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
+            for (int ni = 0; ni < 8; ++ni) q[ni] = (acc[mi][ni][0] + acc[mi][ni][1]) + (acc[mi][ni][2] + acc[mi][ni][3]);
+            double s = (double)((q[0] + q[1]) + (q[2] + q[3])) + (double)((q[4] + q[5]) + (q[6] + q[7]));
             s += __shfl_xor(s, 16, 64);
             s += __shfl_xor(s, 32, 64);
             tot[mi] = s;

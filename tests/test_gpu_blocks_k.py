@@ -122,8 +122,10 @@ def test_k_blocked_thresholds_are_tighter_than_the_column_block_ones():
     col = _plain_session(M, N, K, dtype, 0)
     col.run_blocks(dA, dB)
     rc = col.results()
-    ratio = rc["T_blk"][None, :, :] / r["T_blk_k"]
-    assert np.median(ratio) > 4.0                      # 8 K-blocks: each piece's threshold is well below the block's
+    ratio = rc["T_blk"][None, :, :] / r["T_blk_k"]      # [K-block][column block][row]
+    # 8 K-blocks: the first piece's threshold is an eighth of the block's or less; later pieces carry (b + 1) e_max
+    # (their share is gained on a running accumulator b blocks deep) and approach the block's threshold from below
+    assert np.median(ratio[0]) > 6.0 and np.median(ratio) > 1.5 and np.all(np.median(ratio, axis=(1, 2)) > 0.9)
     assert r["nflag"] == 0 and rc["nflag"] == 0
 
 

@@ -714,7 +714,7 @@ def test_k_blocked_blockwise_partitions_the_blockwise_check():
     assert not kb["E_blk"].any() and not kb["flags"].any()
     one = orc.verify_blocks_k(A, B, "f64", 0, W, 64, 1e-12)
     assert one["nkblocks"] == 1
-    for key in ("expected_blk", "T_blk", "rowsum_blk", "S_blk"):
+    for key in ("expected_blk", "T_blk", "rowsum_blk", "S_blk"):   # K-block 0 carries e_max itself
         assert np.array_equal(one[key][0], blk[key]), key
     # brute force of one interior piece and of the ragged corner piece
     for (b, t) in ((1, 1), (3, 2)):
@@ -734,7 +734,7 @@ def test_k_blocked_blockwise_partitions_the_blockwise_check():
                 exp += A[i, k] * sum(row)
                 rs += sum(A[i, k] * x for x in row)
             n = len(ns)
-            T = 1e-12 * (n * abs(mu_a) * s1 + 2.5 * math.sqrt(n * mu_a ** 2 * s2 + n ** 2 * var_a * s3)
+            T = 1e-12 * (b + 1) * (n * abs(mu_a) * s1 + 2.5 * math.sqrt(n * mu_a ** 2 * s2 + n ** 2 * var_a * s3)
                          + 2.5 * math.sqrt(n) * math.sqrt(var_a) * math.sqrt(s2))
             assert kb["T_blk"][b, t, i] == pytest.approx(T, rel=1e-13)
             assert kb["expected_blk"][b, t, i] == exp and kb["rowsum_blk"][b, t, i] == rs
