@@ -408,8 +408,14 @@ def bench_config(mods, name, variant, steps, warmup, args, headline):
         vg.threshold(A, e_max)
         routes2 = {"plain": lambda: vg.gemm(A, B, 0), "w": lambda: vg.gemm_weighted(A, B),
                    "blocks": lambda: vg.gemm_blocks(A, B), "rc": lambda: vg.gemm_rc(A, B)}
+        kb_ok = dt in ("bf16", "f16") and M % 256 == 0 and N % 256 == 0 and K % 128 == 0 and K > 1024
+        if kb_ok:  # block-wise with K split as well, K-blocks of 1024 (the section's tile depth)
+            from paper_2602_08043_amd.session import KBlockedGemm
+            kg = KBlockedGemm(M, N, K, dt, tb, 1024)
+            kg.run(A, B)
+            routes2["blocks_k1024"] = lambda: kg.gemm(A, B)
         own2 = {}
-        for k in ("plain", "w", "blocks", "rc", "plain_again"):
+        for k in ("plain", "w", "blocks", "rc") + (("blocks_k1024",) if kb_ok else ()) + ("plain_again",):
             fn = routes2["plain" if k == "plain_again" else k]
             spin_up(torch, fn, 0.25)
             own2[k] = timed(torch, fn, steps, warmup)
@@ -422,6 +428,8 @@ def bench_config(mods, name, variant, steps, warmup, args, headline):
             "with_position_weighted_row_sums": 100.0 * (ms_w / ms_plain2 - 1.0),
             "with_row_and_column_check": 100.0 * (ms_rc / ms_plain2 - 1.0),
             "block_wise_check": 100.0 * (ms_blocks / ms_plain2 - 1.0),
+            "block_wise_check_k_blocks_of_1024": (100.0 * (own2["blocks_k1024"] / ms_plain2 - 1.0)) if kb_ok else None,
+            "k_blocked_flagged_pieces_fault_free": int(kg.nblockflag.item()) if kb_ok else None,
             "ms_locate_correct": ms_locate}
 
     if not args.no_quality:
