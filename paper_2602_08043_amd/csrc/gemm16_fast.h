@@ -26,9 +26,13 @@
 //
 // The MFMAs are inline assembly with the accumulator tied to its register ("+a"): left to the register
 // allocator, a quarter of the 64 accumulator tiles changed registers every iteration and were copied
-// through the vector file.  The compiler's hazard handling does not see into them; the only hazards in
-// reach are at the ends of the loop and are padded by hand.
+// through the vector file.  The compiler's hazard handling does not see into them; the hazards in reach are at
+// the ends of the loop (operands written by vector code in front of an MFMA, accumulators read by vector code
+// behind one: settle_accumulators) and are padded by hand; asm_lint.py checks the generated assembly.
 //
+// Kernel modes: 0 plain; 1 row check; 2 injector (with every kind of sum); 3 + position-weighted row sums; 4 +
+// column sums; 5 partial row sums only (block-wise check by a kernel of its own); 6 / 7 prefix row sums at every
+// K-block boundary (block-wise check with K split as well; 7 with the injector).
 // Check-side work fused into this kernel (MODE >= 1): see gemm_tile32.h.  FUSED adds the A-side of Algorithm 1
 // on the matrix cores: tile-column bn folds the k-units (128 k) u = bn, bn + tiles_n, ... of its rows of A.
 // For those units a 16-column panel [1, Be_hi, Be_mid, Be_lo, 0 ...] (Be split into three pieces of the
