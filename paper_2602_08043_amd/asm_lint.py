@@ -69,8 +69,10 @@ def lint(asm_text: str, kernel_pattern: str = r"gemm16_fast_kernel") -> list[str
             continue
         ins = list(_instructions(m.group(0)))
         for i, (mn, ops, in_asm) in enumerate(ins):
-            if mn.startswith("global_load_lds") and in_asm:
-                sregs = _regs(ops[1], "s") if len(ops) > 1 else set()
+            if mn.startswith("global_load") and in_asm:
+                sregs = set()
+                for tok in ops[1:]:
+                    sregs |= _regs(tok, "s")
                 for d, (pm, pops) in _window(ins, i, 5):
                     if d == 1 and pm == "s_mov_b32" and pops and pops[0] == "m0":
                         problems.append(f"{name}: global_load_lds directly behind s_mov m0 (instruction {i})")

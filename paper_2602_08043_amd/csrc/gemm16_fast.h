@@ -97,6 +97,14 @@ template <> struct Mfma16x<f16_t> {
 namespace g16x {
 using namespace g16;
 using namespace g16f;
+// Schedule of the 16 global -> LDS loads of the next tile inside a tile body of 128 MFMA slots: load j goes out at
+// slot LOFF + j * LSTRIDE.  Measured on BF16 4096^3 (plain GEMM, same box, alternating): one load every 8 slots (the
+// last one 7 slots in front of the barrier, which then waits for it) 95.8 us; every 4 slots (all inside the first
+// step) 90.0 us, every 5 or 6 the same; every 2 slots 99.0 us (64 lanes x 16 B every 32 cycles from each of four
+// wavefronts is more than the compute unit's vector memory path takes, and the queue stalls the MFMA issue).
+constexpr int LSTRIDE = 4;
+constexpr int LOFF = 1;  // >= 1: the M0 of a group of four rides one slot ahead of its first load
+static_assert(LOFF >= 1 && LOFF + 15 * LSTRIDE < 128, "all 16 loads inside the tile body");
 constexpr int HALF = 32768;       // one operand stage
 constexpr int B_BASE = 2 * HALF;  // B stages behind the two A stages
 // FUSED: behind the operand stages, the panel [1, Be_hi, Be_mid, Be_lo] of every k32-step this tile-column
@@ -551,36 +559,39 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
     }
     const lds_u8* const panel_rd = lds + PANEL_OFFSET + (l16 & 3) * 64 + lq * 16;
     const lds_u8* const a_rd_st[2] = {a_rd[0] + wn * 8192, a_rd[1] + wn * 8192};
-    // The statistics of k32-step KS of the tile in stage S (step t of folded unit number hj): the wavefront's
-    // four fragments are read once more from LDS, so that the statistics do not lengthen the lives of the
-    // pipeline's fragment registers, and multiplied by the panel of that step.
-    auto stats_step = [&](auto s_c, auto ks_c, int hj) {
+    // The statistics of k32-step KS of the tile in stage S (step t = 2S + KS of folded unit number hj) ride in the
+    // slots of the k-step that runs while that tile is in LDS, instead of standing between
+    // two k-steps with the matrix cores idle: the wavefront's four fragments and the panel fragment are read once
+    // more from LDS in five early slots (the pipeline's own fragment registers are not touched), the panel rows
+    // 4..15 are zeroed well ahead of their use (a vector write of an MFMA operand must not sit within a few slots of
+    // the MFMA), the 16 fragment dwords fold into the max / min trackers one per slot in the last 16 slots, when every
+    // read of the step has been issued, and the four statistics MFMAs follow the step's last slot.
+    raw16 st_x;
+    raw16 st_a[4];
+    auto stats_slot = [&](auto s_c, auto ks_c, auto slot_c, int hj) __attribute__((always_inline)) {
+        constexpr int S = decltype(s_c)::value, KS = decltype(ks_c)::value, slot = decltype(slot_c)::value;
+        if constexpr (slot == 3) st_x = lds_read16(panel_rd + hj * 1024 + (2 * S + KS) * 256);
+        if constexpr (slot == 7 || slot == 11 || slot == 15 || slot == 19)
+            st_a[(slot - 7) / 4] = lds_read16(a_rd_st[KS] + S * HALF + ((slot - 7) / 4) * 2048);
+        if constexpr (slot >= 24 && slot < 28) st_x.w[slot - 24] = l16 < 4 ? st_x.w[slot - 24] : 0u;
+        if constexpr (slot >= 48) mm[(slot - 48) >> 2].fold(st_a[(slot - 48) >> 2].w[(slot - 48) & 3]);
+    };
+    auto stats_mfma = [&](auto s_c, auto ks_c) __attribute__((always_inline)) {
         constexpr int S = decltype(s_c)::value, KS = decltype(ks_c)::value;
-        asm volatile("s_nop 4");  // the step's last MFMA has read its operands before vector code reuses them
-        raw16 xf = lds_read16(panel_rd + hj * 1024 + (2 * S + KS) * 256);
-        raw16 a[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) a[j] = lds_read16(a_rd_st[KS] + S * HALF + j * 2048);
-#pragma unroll
-        for (int d = 0; d < 4; ++d) xf.w[d] = l16 < 4 ? xf.w[d] : 0u;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int d = 0; d < 4; ++d) mm[j].fold(a[j].w[d]);
         // vector code wrote the panel fragment (see Mfma16x): the idle slots are tied to its final value
-        u32x4_t xv = __builtin_bit_cast(u32x4_t, xf);
+        u32x4_t xv = __builtin_bit_cast(u32x4_t, st_x);
         asm volatile("s_nop 4" : "+v"(xv));
-        xf = __builtin_bit_cast(raw16, xv);
-        Mfma16x<T>::acc_v4(sacc[2 * S + KS], xf, a);
+        st_x = __builtin_bit_cast(raw16, xv);
+        Mfma16x<T>::acc_v4(sacc[2 * S + KS], st_x, st_a);
     };
 
     // One k32-step = 64 slots of one MFMA (16 cycles, four issue cycles).  Even slots issue fragment read
-    // slot/2 of the NEXT step (stage S, step KS, into the other register set).  With LBASE >= 0 the step
-    // carries loads LBASE .. LBASE+7 of the next tile into stage S^1: slot 8j + 1 issues load LBASE + j, and
-    // slots 0 and 32 move M0 to the group of four.
-    auto kstep = [&](auto s_c, auto ks_c, auto lbase_c, const raw16 (&af)[8], const raw16 (&bf)[8], raw16 (&naf)[8],
-                     raw16 (&nbf)[8], const unsigned char* ap, const unsigned char* bp) {
+    // slot/2 of the NEXT step (stage S, step KS, into the other register set).  LBASE is the step's first slot
+    // within the tile body (0 or 64; negative: no loads): the loads of the next tile go into stage S^1.
+    auto kstep = [&](auto s_c, auto ks_c, auto lbase_c, auto st_c, int hj, const raw16 (&af)[8], const raw16 (&bf)[8],
+                     raw16 (&naf)[8], raw16 (&nbf)[8], const unsigned char* ap, const unsigned char* bp) {
         constexpr int S = decltype(s_c)::value, LBASE = decltype(lbase_c)::value;
+        constexpr bool STATS = FUSED && decltype(st_c)::value != 0;
         if (!TRANSB) wait_lgkmcnt0();  // the assembly reads of (af, bf) issued during the previous step
         static_for<0, 64>([&](auto slot_c) {
             constexpr int slot = decltype(slot_c)::value;
@@ -589,16 +600,22 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
             __builtin_amdgcn_sched_barrier(0);  // MFMA first, the rest of the slot in its shadow
             if constexpr ((slot & 1) == 0 && slot / 2 < NRD)
                 frag_op(s_c, ks_c, std::integral_constant<int, slot / 2>{}, naf, nbf);
-            if constexpr (LBASE >= 0 && (slot & 31) == 0)
-                set_group(std::integral_constant<int, S ^ 1>{}, std::integral_constant<int, LBASE + slot / 8>{});
-            if constexpr (LBASE >= 0 && (slot & 7) == 1)
-                issue_load(std::integral_constant<int, LBASE + slot / 8>{}, ap, bp);
+            // G: slot within the tile body (two steps); load j goes out at G = LOFF + j * LSTRIDE, the M0 of its
+            // group of four one slot ahead of the group's first load
+            constexpr int G = LBASE + slot;
+            if constexpr (LBASE >= 0 && G + 1 >= LOFF && (G + 1 - LOFF) % (4 * LSTRIDE) == 0 &&
+                          (G + 1 - LOFF) / LSTRIDE < 16)
+                set_group(std::integral_constant<int, S ^ 1>{}, std::integral_constant<int, (G + 1 - LOFF) / LSTRIDE>{});
+            if constexpr (LBASE >= 0 && G >= LOFF && (G - LOFF) % LSTRIDE == 0 && (G - LOFF) / LSTRIDE < 16)
+                issue_load(std::integral_constant<int, (G - LOFF) / LSTRIDE>{}, ap, bp);
+            if constexpr (STATS) stats_slot(s_c, ks_c, slot_c, hj);
             __builtin_amdgcn_sched_barrier(0);
         });
+        if constexpr (STATS) stats_mfma(s_c, ks_c);
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
-    using I8 = std::integral_constant<int, 8>;
+    using I64 = std::integral_constant<int, 64>;
 
     const int nk = g.K / BK;
     raw16 af0[8], bf0[8], af1[8], bf1[8];
@@ -717,10 +734,8 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         const unsigned char* ap = uniform_ptr(a_base + (int64_t)ktn * (BK * 2));
         const unsigned char* bp = uniform_ptr(b_base + ktn * b_ktile);
         settle_bases(ap, bp);
-        kstep(s_c, I0{}, I0{}, af1, bf1, af0, bf0, ap, bp);  // step (kt-1, 1)
-        if constexpr (FUSED && STATS) stats_step(s_c, I0{}, hj);
-        kstep(s_c, I1{}, I8{}, af0, bf0, af1, bf1, ap, bp);  // step (kt, 0)
-        if constexpr (FUSED && STATS) stats_step(s_c, I1{}, hj);
+        kstep(s_c, I0{}, I0{}, st_c, hj, af1, bf1, af0, bf0, ap, bp);   // step (kt-1, 1)
+        kstep(s_c, I1{}, I64{}, st_c, hj, af0, bf0, af1, bf1, ap, bp);  // step (kt, 0)
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     };

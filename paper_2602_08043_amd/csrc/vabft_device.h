@@ -110,11 +110,25 @@ __device__ __forceinline__ void fold_s_partials_to_lds(const double* __restrict_
                                                        double* s_red) {
     if (t < 256) {
         double a1 = 0, a2 = 0, a3 = 0;
-        for (int b = t; b < count; b += 256) {
-            const double* q = partial + 3 * (int64_t)b;
-            a1 += q[0];
-            a2 += q[1];
-            a3 += q[2];
+        // four partials per round: their twelve loads are in flight together (one trip to memory per round, not per
+        // partial), the additions stay in increasing order of b
+        for (int b0 = t; b0 < count; b0 += 4 * 256) {
+            double q[4][3];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int b = b0 + u * 256;
+                const double* src = partial + 3 * (int64_t)(b < count ? b : t);
+                q[u][0] = src[0];
+                q[u][1] = src[1];
+                q[u][2] = src[2];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool ok = b0 + u * 256 < count;
+                a1 = ok ? a1 + q[u][0] : a1;
+                a2 = ok ? a2 + q[u][1] : a2;
+                a3 = ok ? a3 + q[u][2] : a3;
+            }
         }
         a1 = wave_sum(a1);
         a2 = wave_sum(a2);
