@@ -195,15 +195,28 @@ __device__ __forceinline__ void gemm16x_inject(const GemmArgs& g, f32x4_t (&acc)
 __device__ __forceinline__ void gemm16x_rowsum_to_lds(const f32x4_t (&acc)[8][8], float* red, int wm, int wn, int l16,
                                                       int lq) {
     using namespace g16;
+    // the eight row fragments side by side: their cross-lane exchanges are in flight together (one wait per
+    // exchange round instead of one per fragment); the order of the additions of a row is unchanged
+    float s[8];
 #pragma unroll
     for (int mi = 0; mi < 8; ++mi) {
         float t[8];
 #pragma unroll
         for (int ni = 0; ni < 8; ++ni) t[ni] = (acc[mi][ni][0] + acc[mi][ni][1]) + (acc[mi][ni][2] + acc[mi][ni][3]);
-        float s = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
-        s += __shfl_xor(s, 16, WAVE);
-        s += __shfl_xor(s, 32, WAVE);
-        if (lq == 0) red[wn * BM + wm * 128 + mi * 16 + l16] = s;
+        s[mi] = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+    }
+    float x[8];
+#pragma unroll
+    for (int mi = 0; mi < 8; ++mi) x[mi] = __shfl_xor(s[mi], 16, WAVE);
+#pragma unroll
+    for (int mi = 0; mi < 8; ++mi) s[mi] += x[mi];
+#pragma unroll
+    for (int mi = 0; mi < 8; ++mi) x[mi] = __shfl_xor(s[mi], 32, WAVE);
+#pragma unroll
+    for (int mi = 0; mi < 8; ++mi) s[mi] += x[mi];
+    if (lq == 0) {
+#pragma unroll
+        for (int mi = 0; mi < 8; ++mi) red[wn * BM + wm * 128 + mi * 16 + l16] = s[mi];
     }
 }
 
@@ -821,11 +834,13 @@ __global__ __launch_bounds__(256) void gemm16_fast_kernel(const GemmArgs g) {
         if (CSUM) gemm16x_colsum_to_lds(acc, cred, wm, wn, l16, lq);
         if (FUSED) {
             const float sigma = reinterpret_cast<const float*>(smem + SCALE_X)[4];
+            // the four k-chunk lanes of a row hold partial (max, min); lanes 0..15 hold the panel's result
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mm[j].merge_xor(16);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mm[j].merge_xor(32);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                // the four k-chunk lanes of a row hold partial (max, min); lanes 0..15 hold the panel's result
-                mm[j].merge_xor(16);
-                mm[j].merge_xor(32);
                 float mx, mn;
                 mm[j].result(mx, mn);
                 if (lq == 0) {
