@@ -127,3 +127,32 @@ def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(ImportError) as e:
         vb.load(missing)
     assert "has not been built" in str(e.value) and "no fallback" in str(e.value)
+
+
+def test_asm_lint_flags_the_hazards_it_is_built_for():
+    """The build-time hazard pass on the generated assembly of the inline-assembly kernels: each of its three
+    rules fires on a planted case and stays quiet on the padded form of the same sequence."""
+    from paper_2602_08043_amd import asm_lint
+
+    def kernel(body):
+        return "_ZN5vabft18gemm16_fast_kernelIxEEv:\n" + body + "\n\ts_endpgm\n"
+
+    asm = lambda text: "\t;;#ASMSTART\n\t" + text + "\n\t;;#ASMEND\n"
+    # a scalar base written by the vector ALU and read by a load from assembly within five wait states
+    bad = kernel("\tv_readfirstlane_b32 s4, v1\n" + asm("global_load_lds_dwordx4 v2, s[4:5] offset:0"))
+    good = kernel("\tv_readfirstlane_b32 s4, v1\n\ts_nop 4\n" + asm("global_load_lds_dwordx4 v2, s[4:5] offset:0"))
+    assert asm_lint.lint(bad) and not asm_lint.lint(good)
+    # ... the same for a plain global load issued from assembly
+    bad = kernel("\tv_readfirstlane_b32 s6, v1\n" + asm("global_load_dword v3, v2, s[6:7]"))
+    good = kernel("\tv_readfirstlane_b32 s6, v1\n\ts_nop 4\n" + asm("global_load_dword v3, v2, s[6:7]"))
+    assert asm_lint.lint(bad) and not asm_lint.lint(good)
+    # the load directly behind the move that sets M0
+    bad = kernel(asm("s_mov_b32 m0, s9") + asm("global_load_lds_dwordx4 v2, s[4:5] offset:0"))
+    good = kernel(asm("s_mov_b32 m0, s9") + asm("v_mfma_f32_16x16x32_bf16 a[0:3], v[4:7], v[8:11], a[0:3]") +
+                  asm("global_load_lds_dwordx4 v2, s[4:5] offset:0"))
+    assert asm_lint.lint(bad) and not asm_lint.lint(good)
+    # an operand of an MFMA from assembly written by the vector ALU within four wait states
+    bad = kernel("\tv_cndmask_b32_e32 v4, v20, v21, vcc\n" + asm("v_mfma_f32_16x16x32_bf16 a[0:3], v[4:7], v[8:11], a[0:3]"))
+    good = kernel("\tv_cndmask_b32_e32 v4, v20, v21, vcc\n\ts_nop 4\n" +
+                  asm("v_mfma_f32_16x16x32_bf16 a[0:3], v[4:7], v[8:11], a[0:3]"))
+    assert asm_lint.lint(bad) and not asm_lint.lint(good)
