@@ -165,6 +165,8 @@ FUSED = [
     # everything else: the two passes back to back behind the same entry point
     ("bf16", 512, 256, 256, 0), ("bf16", 512, 512, 192, 0), ("bf16", 300, 520, 200, 1), ("f16", 100, 99, 50, 0),
     ("f32", 256, 256, 256, 0), ("f64", 200, 260, 70, 1),
+    # a single k-tile (the whole-tile GEMM's loop runs one body, whose loads of a next tile re-read the only one)
+    ("bf16", 256, 256, 64, 0), ("f16", 256, 512, 64, 1),
     # whole-tile FP32 / FP64 problems: the same in-kernel path on the 128 x 128 tile kernels, with a k-tile count
     # that is not a multiple of the tile-columns, and with more tile-columns than k-tiles (some fold nothing)
     ("f32", 384, 512, 272, 1), ("f32", 128, 512, 32, 0), ("f32", 128, 128, 16, 0), ("f64", 256, 384, 128, 0),
