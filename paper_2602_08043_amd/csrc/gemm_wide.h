@@ -128,7 +128,11 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     constexpr int CPK = BN / V;                // chunks per k-row in a [k][n] tile
     constexpr int NCH_B = BK * CPK / 256;
     static_assert(NCH_A == NCH_B, "tile shape");
-    T ra[NCH_A][V], rb[NCH_B][V];
+    // PD k-tiles are in flight from global memory at a time, each in a register slot of its own.  The small tile
+    // serves problems of a few dozen workgroups, whose time is a chain of global-memory latencies, one per k-tile
+    // with a single slot (FP32 256^3: 16 k-tiles of 16); four slots take three of every four out of the chain.
+    constexpr int PD = WT == 32 ? 4 : 1;
+    T ra[PD][NCH_A][V], rb[PD][NCH_B][V];
 
     // one 16-byte chunk; whole-tile problems need no guards
     auto load_chunk = [&](const T* base, int r, int nr, int c, int nc, int64_t ld, int vec_ok, T (&out)[V]) {
@@ -139,50 +143,53 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
             guarded_chunk_wide<T, V>(base, r, nr, c, nc, ld, vec_ok, out);
         }
     };
-    auto load_tiles = [&](int kt) {
+    // (the register slot is a compile-time constant everywhere: a runtime index would put the slots in scratch)
+    auto load_tiles = [&](int kt, auto slot_c) {
+        constexpr int SL = decltype(slot_c)::value;
         const int kbase = kt * BK;
 #pragma unroll
         for (int p = 0; p < NCH_A; ++p) {
             const int id = tid + 256 * p, r = id / CPR, c = id % CPR;
-            load_chunk(A, row0 + r, g.M, kbase + c * V, g.K, g.lda, g.a_vec_ok, ra[p]);
+            load_chunk(A, row0 + r, g.M, kbase + c * V, g.K, g.lda, g.a_vec_ok, ra[SL][p]);
         }
         if (TRANSB) {
 #pragma unroll
             for (int p = 0; p < NCH_B; ++p) {
                 const int id = tid + 256 * p, r = id / CPR, c = id % CPR;
-                load_chunk(B, col0 + r, g.N, kbase + c * V, g.K, g.ldb, g.b_vec_ok, rb[p]);
+                load_chunk(B, col0 + r, g.N, kbase + c * V, g.K, g.ldb, g.b_vec_ok, rb[SL][p]);
             }
         } else {
 #pragma unroll
             for (int p = 0; p < NCH_B; ++p) {
                 const int id = tid + 256 * p, kr = id / CPK, c = id % CPK;
-                load_chunk(B, kbase + kr, g.K, col0 + c * V, g.N, g.ldb, g.b_vec_ok, rb[p]);
+                load_chunk(B, kbase + kr, g.K, col0 + c * V, g.N, g.ldb, g.b_vec_ok, rb[SL][p]);
             }
         }
     };
 
-    auto store_tiles = [&](int s) {
+    auto store_tiles = [&](int s, auto slot_c) {
+        constexpr int SL = decltype(slot_c)::value;
         T* As = smem + s * stage_elems<T, WT>();
         T* Bs = As + a_elems<T, WT>();
 #pragma unroll
         for (int p = 0; p < NCH_A; ++p) {
             const int id = tid + 256 * p, r = id / CPR, c = id % CPR;
 #pragma unroll
-            for (int e = 0; e < V; ++e) As[r * LDK + c * V + e] = ra[p][e];
+            for (int e = 0; e < V; ++e) As[r * LDK + c * V + e] = ra[SL][p][e];
         }
         if (TRANSB) {
 #pragma unroll
             for (int p = 0; p < NCH_B; ++p) {
                 const int id = tid + 256 * p, r = id / CPR, c = id % CPR;
 #pragma unroll
-                for (int e = 0; e < V; ++e) Bs[r * LDK + c * V + e] = rb[p][e];
+                for (int e = 0; e < V; ++e) Bs[r * LDK + c * V + e] = rb[SL][p][e];
             }
         } else {
 #pragma unroll
             for (int p = 0; p < NCH_B; ++p) {
                 const int id = tid + 256 * p, kr = id / CPK, c = id % CPK;
 #pragma unroll
-                for (int e = 0; e < V; ++e) Bs[kr * ldn<T, WT>() + c * V + e] = rb[p][e];
+                for (int e = 0; e < V; ++e) Bs[kr * ldn<T, WT>() + c * V + e] = rb[SL][p][e];
             }
         }
     };
@@ -192,7 +199,9 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
     // chunk's position in the k-tile, tid % CPR, is the same for every p, so one 16-byte
     // piece of Be serves all of them.  st[p] = (sum, dot with Be, max, min).
     T st[NCH_A][4];
-    raw16 be_raw = {{0u, 0u, 0u, 0u}};
+    raw16 be_raw[PD];
+#pragma unroll
+    for (int q = 0; q < PD; ++q) be_raw[q] = raw16{{0u, 0u, 0u, 0u}};
 #pragma unroll
     for (int p = 0; p < NCH_A; ++p) {
         st[p][0] = 0;
@@ -200,28 +209,31 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
         st[p][2] = lowest<T>();
         st[p][3] = -lowest<T>();
     }
-    auto load_be = [&](int kt) { be_raw = ld16(reinterpret_cast<const T*>(g.Be) + kt * BK + (tid % CPR) * V); };
-    auto fold_stats = [&]() {
+    auto load_be = [&](int kt, auto slot_c) {
+        be_raw[decltype(slot_c)::value] = ld16(reinterpret_cast<const T*>(g.Be) + kt * BK + (tid % CPR) * V);
+    };
+    auto fold_stats = [&](auto slot_c) {
+        constexpr int SL = decltype(slot_c)::value;
         T bev[V];
-        __builtin_memcpy(bev, &be_raw, 16);
+        __builtin_memcpy(bev, &be_raw[SL], 16);
         // the chunk's sum and dot product are formed pairwise and then added to the running values, so the
         // sequential rounding chain of a thread is one add per folded k-tile, not one per element
 #pragma unroll
         for (int p = 0; p < NCH_A; ++p) {
             T cs, cd;
             if constexpr (V == 2) {
-                cs = ra[p][0] + ra[p][1];
-                cd = fma(ra[p][1], bev[1], ra[p][0] * bev[0]);
+                cs = ra[SL][p][0] + ra[SL][p][1];
+                cd = fma(ra[SL][p][1], bev[1], ra[SL][p][0] * bev[0]);
             } else {
-                cs = (ra[p][0] + ra[p][1]) + (ra[p][2] + ra[p][3]);
-                cd = fma(ra[p][1], bev[1], ra[p][0] * bev[0]) + fma(ra[p][3], bev[3], ra[p][2] * bev[2]);
+                cs = (ra[SL][p][0] + ra[SL][p][1]) + (ra[SL][p][2] + ra[SL][p][3]);
+                cd = fma(ra[SL][p][1], bev[1], ra[SL][p][0] * bev[0]) + fma(ra[SL][p][3], bev[3], ra[SL][p][2] * bev[2]);
             }
             st[p][0] += cs;
             st[p][1] += cd;
 #pragma unroll
             for (int e = 0; e < V; ++e) {
-                st[p][2] = fmax(st[p][2], ra[p][e]);
-                st[p][3] = fmin(st[p][3], ra[p][e]);
+                st[p][2] = fmax(st[p][2], ra[SL][p][e]);
+                st[p][3] = fmin(st[p][3], ra[SL][p][e]);
             }
         }
     };
@@ -247,31 +259,48 @@ __global__ __launch_bounds__(256) void gemmw_kernel(const GemmArgs g) {
 
     const int nk = (g.K + BK - 1) / BK;
     int next_fold = bn;  // FUSED: the next k-tile this tile-column folds into the statistics
-    if (FUSED) load_be(0);
+    using SL0 = std::integral_constant<int, 0>;
+    // k-tile t travels in register slot t % PD: the first PD tiles go out at once
+    static_for<0, PD>([&](auto q_c) {
+        constexpr int q = decltype(q_c)::value;
+        if (q < nk) {
+            // the 16 bytes of Be are fetched for every k-tile, in front of the tile's own loads: loads
+            // return in order, so the waits of store_tiles cover them, and a conditional load here
+            // would make the compiler drain the whole load queue in front of it
+            if (FUSED) load_be(q, q_c);
+            load_tiles(q, q_c);
+        }
+    });
     if (FUSED && !g.S)
         fold_s_partials_to_lds(g.s_partial, g.s_nparts, tid, reinterpret_cast<double*>(smem_raw + flag_offset<T, WT>() + 16));
-    load_tiles(0);
-    store_tiles(0);
+    store_tiles(0, SL0{});
     if (FUSED && next_fold == 0) {
-        fold_stats();
+        fold_stats(SL0{});
         next_fold += g.tiles_n;
     }
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const bool more = kt + 1 < nk;
-        const bool fold = FUSED && more && kt + 1 == next_fold;  // workgroup-uniform
-        // the 16 bytes of Be are fetched for every k-tile, in front of the tile's own loads: loads
-        // return in order, so the waits of store_tiles cover them, and a conditional load here
-        // would make the compiler drain the whole load queue in front of it
-        if (FUSED && more) load_be(kt + 1);
-        if (more) load_tiles(kt + 1);
-        compute(kt & 1);
-        if (more) store_tiles((kt + 1) & 1);
-        if (fold) {
-            fold_stats();
-            next_fold += g.tiles_n;
-        }
-        __syncthreads();
+    for (int kt0 = 0; kt0 < nk; kt0 += PD) {
+        static_for<0, PD>([&](auto j_c) {
+            constexpr int j = decltype(j_c)::value;
+            using NEXT = std::integral_constant<int, (j + 1) % PD>;
+            const int kt = kt0 + j;
+            if (kt < nk) {  // workgroup-uniform
+                const bool more = kt + 1 < nk;
+                const bool fold = FUSED && more && kt + 1 == next_fold;  // workgroup-uniform
+                // slot j held k-tile kt, which is in LDS by now: it takes k-tile kt + PD
+                if (kt + PD < nk) {
+                    if (FUSED) load_be(kt + PD, j_c);
+                    load_tiles(kt + PD, j_c);
+                }
+                compute(kt & 1);
+                if (more) store_tiles((kt + 1) & 1, NEXT{});
+                if (fold) {
+                    fold_stats(NEXT{});
+                    next_fold += g.tiles_n;
+                }
+                __syncthreads();
+            }
+        });
     }
 
     if constexpr (FUSED) {
